@@ -1,0 +1,66 @@
+"""Dynamic-programming model partition (test infrastructure).
+
+Follows the paper's section "Dynamic Model Partition": the execution time of
+layer m on worker k is the central node's profiled time multiplied by the
+worker's computing capacity C_k (the per-layer estimate equation), A(j, 1) is
+the whole prefix on device 0 (base case), and A(j, n) minimises over the last
+cut the slowest of: the optimal (n-1)-device sub-pipeline, twice the transfer
+of the cut layer's output, and the last stage on device n-1 (the recurrence
+and the last-stage-time equation).
+
+Readings where the text is silent or garbled:
+  * capacity is a time multiplier (larger = slower), as the equations say;
+  * layers are 0-based, bounds are half-open, every stage holds >= 1 layer, so
+    for n stages over the first j layers the last cut l runs over n-1 .. j-1;
+  * stage k runs on device k (no permutation search);
+  * ties: cuts are scanned in ascending order and only a strictly smaller
+    value replaces the incumbent;
+  * float64: prefix sums accumulated in layer order, stage time
+    (P[j] - P[l]) * C[k], exact max and compare;
+  * the transfer term is used only when both output sizes and bandwidths are
+    given: 2 * D[l-1] / B[n-2] for the hop from device n-2 to device n-1.
+"""
+import math
+
+
+def solve_partition(costs, capacities, out_bytes=None, bandwidth=None):
+    """Returns (bounds[N+1], bottleneck).  Stage k = layers [bounds[k], bounds[k+1])."""
+    Lc, N = len(costs), len(capacities)
+    if N < 1 or Lc < N:
+        raise ValueError("need 1 <= N <= L")
+    for v in list(costs) + list(capacities):
+        if not (math.isfinite(v) and v > 0):
+            raise ValueError("costs and capacities must be finite and positive")
+    comm = out_bytes is not None and bandwidth is not None
+    P = [0.0]
+    for c in costs:
+        P.append(P[-1] + float(c))
+    INF = float('inf')
+    # A[n][j]: best bottleneck of the first j layers on devices 0..n-1
+    A = [[INF] * (Lc + 1) for _ in range(N + 1)]
+    cut = [[0] * (Lc + 1) for _ in range(N + 1)]
+    for j in range(1, Lc + 1):
+        A[1][j] = P[j] * float(capacities[0])
+    for n in range(2, N + 1):
+        for j in range(n, Lc + 1):
+            best, arg = INF, -1
+            for l in range(n - 1, j):
+                t = max(A[n - 1][l], (P[j] - P[l]) * float(capacities[n - 1]))
+                if comm:
+                    t = max(t, 2.0 * (float(out_bytes[l - 1]) / float(bandwidth[n - 2])))
+                if t < best:
+                    best, arg = t, l
+            A[n][j], cut[n][j] = best, arg
+    bounds = [0] * (N + 1)
+    bounds[N] = Lc
+    j = Lc
+    for n in range(N, 1, -1):
+        j = cut[n][j]
+        bounds[n - 1] = j
+    return bounds, A[N][Lc]
+
+
+def estimate_capacity(stage_time, layer_costs, start, end):
+    """Capacity equation: measured time of worker i's stage divided by the
+    central node's time for the same layers start..end (inclusive)."""
+    return stage_time / sum(layer_costs[start:end + 1])

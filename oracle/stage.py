@@ -1,0 +1,172 @@
+"""One pipeline stage's training step on the CPU (test infrastructure).
+
+A stage is the contiguous unit range [a, b) a worker builds from its partition
+points (paper, section "Initialization"); it forwards a batch, later backwards
+it with the weight version that forward used (weight stashing, section "Async
+Pipeline Training"), and applies SGD with momentum and weight decay (section
+"Experiment Setup").  Each in-flight batch occupies a slot holding whatever
+its backward needs.
+"""
+import numpy as np
+from . import layers as L
+from . import models as M
+
+
+def _conv_bn_act_fwd(x, w, gamma, beta, stride, ph, pw, groups, act):
+    z = L.conv2d_fwd(x, w, stride, ph, pw, groups)
+    y, mean, invstd, var = L.bn_fwd(z, gamma, beta)
+    a = L.act_fwd(y, act)
+    return a, dict(x=x, z=z, y=y, mean=mean, invstd=invstd, var=var)
+
+
+def _conv_bn_act_bwd(da, c, w, gamma, stride, ph, pw, groups, act):
+    dy = L.act_bwd(da, c['y'], act)
+    dz, dgamma, dbeta = L.bn_bwd(dy, c['z'], c['mean'], c['invstd'], gamma)
+    dx, dw = L.conv2d_bwd(c['x'], w, dz, stride, ph, pw, groups)
+    return dx, dw, dgamma, dbeta
+
+
+class Stage:
+    def __init__(self, units, in_shape, a, b, n_slots=1, dtype=np.float64):
+        """units: full unit list; in_shape: (H, W, C) of the model input."""
+        assert 0 <= a < b <= len(units)
+        self.units, self.a, self.b, self.dtype = units, a, b, dtype
+        shape = tuple(in_shape)
+        self.shapes = [shape]
+        for u in units:
+            shape = M.unit_out_shape(u, shape)
+            self.shapes.append(shape)
+        self.params = {i: [] for i in range(a, b)}
+        self.grads, self.mom, self.bn_run = {}, {}, {}
+        for i in range(a, b):
+            specs = M.param_specs(units[i])
+            self.params[i] = [np.zeros(s, dtype) for _, s, _, _ in specs]
+            self.grads[i] = [np.zeros(s, dtype) for _, s, _, _ in specs]
+            self.mom[i] = [np.zeros(s, dtype) for _, s, _, _ in specs]
+            self.bn_run[i] = [[np.zeros(c, dtype), np.ones(c, dtype)] for c in M.bn_channels(units[i])]
+        self.slots = [None] * n_slots
+
+    def set_params(self, i, arrays):
+        self.params[i] = [np.array(p, dtype=self.dtype) for p in arrays]
+
+    # ---------------------------------------------------------------- forward
+    def _bn_track(self, i, k, c):
+        cnt = c['z'].size // c['z'].shape[-1]
+        rm, rv = self.bn_run[i][k]
+        self.bn_run[i][k] = list(L.bn_running_update(rm, rv, c['mean'], c['var'], cnt))
+
+    def _unit_fwd(self, i, x, P):
+        u = self.units[i]
+        if u.kind == 'conv':
+            a, c = _conv_bn_act_fwd(x, P[0], P[1], P[2], u.stride, u.pad_h, u.pad_w, 1, u.act)
+            self._bn_track(i, 0, c)
+            return a, [c]
+        if u.kind == 'invres':
+            caches, h, k, nb = [], x, 0, 0
+            ce = u.cin * u.expand
+            if u.expand != 1:
+                h, c = _conv_bn_act_fwd(h, P[0], P[1], P[2], 1, 0, 0, 1, L.ACT_RELU6)
+                self._bn_track(i, nb, c); nb += 1
+                caches.append(c); k = 3
+            h, c = _conv_bn_act_fwd(h, P[k], P[k + 1], P[k + 2], u.stride, 1, 1, ce, L.ACT_RELU6)
+            self._bn_track(i, nb, c); nb += 1
+            caches.append(c)
+            h, c = _conv_bn_act_fwd(h, P[k + 3], P[k + 4], P[k + 5], 1, 0, 0, 1, L.ACT_NONE)
+            self._bn_track(i, nb, c)
+            caches.append(c)
+            if u.stride == 1 and u.cin == u.cout:
+                h = x + h
+            return h, caches
+        if u.kind == 'gap':
+            return L.gap_fwd(x)[:, None, None, :], [dict(hw=x.shape[1:3])]
+        if u.kind == 'fc':
+            x2 = x.reshape(x.shape[0], -1)
+            return L.fc_fwd(x2, P[0], P[1])[:, None, None, :], [dict(x=x2)]
+        return x, [dict()]                                   # loss unit: logits pass through
+
+    def forward(self, slot, x, stash_weights=True):
+        assert self.slots[slot] is None, "slot busy"
+        x = np.asarray(x, dtype=self.dtype)
+        # update() replaces parameter arrays instead of writing into them, so
+        # keeping the lists is a snapshot of this weight version
+        P = {i: list(self.params[i]) for i in range(self.a, self.b)}
+        caches, h = {}, x
+        for i in range(self.a, self.b):
+            h, caches[i] = self._unit_fwd(i, h, P[i])
+        self.slots[slot] = dict(caches=caches, params=P if stash_weights else None, out=h, dlogits=None)
+        return h
+
+    def loss(self, slot, labels):
+        assert self.units[self.b - 1].kind == 'loss'
+        s = self.slots[slot]
+        logits = s['out'].reshape(s['out'].shape[0], -1)
+        loss, d = L.softmax_ce(logits, np.asarray(labels))
+        s['dlogits'] = d[:, None, None, :]
+        return loss
+
+    # --------------------------------------------------------------- backward
+    def _acc(self, i, k, g):
+        self.grads[i][k] = self.grads[i][k] + g
+
+    def _unit_bwd(self, i, d, caches, P):
+        u = self.units[i]
+        if u.kind == 'conv':
+            dx, dw, dg, db = _conv_bn_act_bwd(d, caches[0], P[0], P[1], u.stride, u.pad_h, u.pad_w, 1, u.act)
+            self._acc(i, 0, dw); self._acc(i, 1, dg); self._acc(i, 2, db)
+            return dx
+        if u.kind == 'invres':
+            ce = u.cin * u.expand
+            k = 3 if u.expand != 1 else 0
+            dout = d
+            d, dw, dg, db = _conv_bn_act_bwd(d, caches[-1], P[k + 3], P[k + 4], 1, 0, 0, 1, L.ACT_NONE)
+            self._acc(i, k + 3, dw); self._acc(i, k + 4, dg); self._acc(i, k + 5, db)
+            d, dw, dg, db = _conv_bn_act_bwd(d, caches[-2], P[k], P[k + 1], u.stride, 1, 1, ce, L.ACT_RELU6)
+            self._acc(i, k, dw); self._acc(i, k + 1, dg); self._acc(i, k + 2, db)
+            if u.expand != 1:
+                d, dw, dg, db = _conv_bn_act_bwd(d, caches[0], P[0], P[1], 1, 0, 0, 1, L.ACT_RELU6)
+                self._acc(i, 0, dw); self._acc(i, 1, dg); self._acc(i, 2, db)
+            if u.stride == 1 and u.cin == u.cout:
+                d = d + dout
+            return d
+        if u.kind == 'gap':
+            H, W = caches[0]['hw']
+            return L.gap_bwd(d.reshape(d.shape[0], -1), H, W)
+        if u.kind == 'fc':
+            dx, dw, db = L.fc_bwd(caches[0]['x'], P[0], d.reshape(d.shape[0], -1))
+            self._acc(i, 0, dw); self._acc(i, 1, db)
+            return dx[:, None, None, :]
+        return d
+
+    def backward(self, slot, dy=None):
+        s = self.slots[slot]
+        assert s is not None, "slot empty"
+        d = s['dlogits'] if dy is None else np.asarray(dy, dtype=self.dtype)
+        assert d is not None
+        P = s['params'] if s['params'] is not None else self.params
+        for i in range(self.b - 1, self.a - 1, -1):
+            d = self._unit_bwd(i, d, s['caches'][i], P[i])
+        self.slots[slot] = None
+        return d
+
+    # ----------------------------------------------------------------- update
+    def update(self, lr, momentum, weight_decay):
+        for i in range(self.a, self.b):
+            for k in range(len(self.params[i])):
+                w, v = L.sgd_momentum(self.params[i][k], self.grads[i][k], self.mom[i][k], lr, momentum, weight_decay)
+                self.params[i][k], self.mom[i][k] = w, v
+                self.grads[i][k] = np.zeros_like(w)
+
+
+def one_f_one_b_order(stage_index, n_stages, n_batches):
+    """Call order of one stage under the one-forward-one-backward rule: stage i
+    of n keeps n-i batches in flight (section "Async Pipeline Training"), so it
+    forwards n-i batches, then alternates backward/forward, then drains.
+    Returns [('F', b) | ('B', b)]."""
+    depth = min(n_stages - stage_index, n_batches)
+    order = [('F', b) for b in range(depth)]
+    nf, nb = depth, 0
+    while nb < n_batches:
+        order.append(('B', nb)); nb += 1
+        if nf < n_batches:
+            order.append(('F', nf)); nf += 1
+    return order
