@@ -1,0 +1,184 @@
+/*
+ * ftp.h — C ABI of the MI355X stage-training library.
+ *
+ * One pipeline stage's training step of FTPipeHD: a worker builds the sub-model
+ * given by its partition points (paper, section "Initialization"), forwards and
+ * backwards batches under the one-forward-one-backward rule with weight
+ * stashing (section "Async Pipeline Training"), updates its weights with SGD,
+ * momentum and weight decay (section "Experiment Setup"), and the central node
+ * profiles per-layer execution time and output size (section "Initialization",
+ * model profiling phase) and solves the partition dynamic programme (section
+ * "Dynamic Model Partition").
+ *
+ * Conventions
+ *   - Every function returns 0 (FTP_OK) or a negative ftp_status; on error the
+ *     outputs are untouched and ftp_last_error() holds a thread-local message.
+ *     No C++ exception and no abort crosses this boundary.
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are host
+ *     addresses.  `stream` is a hipStream_t passed as void* (NULL = default
+ *     stream).  Compute calls are asynchronous on that stream; import / export /
+ *     profile / solve are synchronous.
+ *   - Activations are NHWC (channels fastest): [batch, H, W, C]; a 1-D window of
+ *     T steps is H = 1, W = T.  Their element type is the model's ftp_dtype
+ *     (float, or bfloat16 with fp32 accumulation, statistics, gradients of
+ *     weights, momentum and master weights).
+ *   - The caller owns x / y / dy / dx / labels / loss buffers.  The stage owns
+ *     everything that lives between calls (weights, momentum, gradients, BN
+ *     running statistics, per-slot stash, workspace) and frees it in
+ *     ftp_stage_destroy.
+ *   - A partition unit ("layer" in the paper) is the smallest piece a stage
+ *     boundary may fall between; a residual connection is never cut.
+ */
+#ifndef FTP_H
+#define FTP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FTP_OK = 0,
+  FTP_ERR_ARG = -1,         /* NULL pointer, bad range, bad size              */
+  FTP_ERR_SHAPE = -2,       /* unit list does not chain / count mismatch      */
+  FTP_ERR_UNSUPPORTED = -3, /* valid request the kernels do not cover         */
+  FTP_ERR_SLOT = -4,        /* slot busy on forward / empty on backward       */
+  FTP_ERR_VALUE = -5,       /* NaN, infinite or non-positive cost / capacity  */
+  FTP_ERR_HIP = -6,         /* HIP runtime failure (message has the detail)   */
+  FTP_ERR_NOMEM = -7
+} ftp_status;
+
+typedef enum { FTP_F32 = 0, FTP_BF16 = 1 } ftp_dtype;
+
+typedef enum {
+  FTP_UNIT_CONV = 0,   /* conv (kh x kw, stride, zero pad) + BatchNorm + act     */
+  FTP_UNIT_INVRES = 1, /* inverted residual: [1x1 expand+BN+ReLU6 if expand>1]
+                          -> depthwise 3x3 (stride)+BN+ReLU6 -> 1x1 project+BN;
+                          adds its input when stride == 1 and cin == cout        */
+  FTP_UNIT_GAP = 2,    /* mean over H and W                                      */
+  FTP_UNIT_FC = 3,     /* y = x W^T + b                                          */
+  FTP_UNIT_LOSS = 4    /* softmax cross-entropy, mean over the batch             */
+} ftp_unit_kind;
+
+typedef enum { FTP_ACT_NONE = 0, FTP_ACT_RELU = 1, FTP_ACT_RELU6 = 2 } ftp_act;
+
+typedef struct {
+  int32_t kind;          /* ftp_unit_kind                                        */
+  int32_t cin, cout;     /* channels in / out (LOSS: cin = cout = classes)       */
+  int32_t kh, kw;        /* CONV only                                            */
+  int32_t stride;        /* CONV, INVRES                                         */
+  int32_t pad_h, pad_w;  /* CONV only                                            */
+  int32_t expand;        /* INVRES only: expansion factor t                      */
+  int32_t act;           /* CONV only: ftp_act after the BatchNorm               */
+} ftp_unit_desc;
+
+/* SGD with momonentum and weight decay: g += wd*w; v = momentum*v + g; w -= lr*v. */
+typedef struct { float lr, momentum, weight_decay; } ftp_sgd;
+
+typedef struct ftp_model ftp_model; /* immutable unit list of the whole network  */
+typedef struct ftp_stage ftp_stage; /* units [a,b) at one batch size, on one GPU */
+
+const char* ftp_last_error(void);
+
+/* ---- model description ---------------------------------------------------- */
+
+/* Copies `units` (host, L entries).  in_h/in_w/in_c: shape of the network input.
+ * Channel counts that feed a BatchNorm must be multiples of 8. */
+int ftp_model_create(const ftp_unit_desc* units, int L, int in_h, int in_w, int in_c,
+                     ftp_dtype act_dtype, ftp_model** out);
+void ftp_model_destroy(ftp_model*);
+int ftp_model_num_units(const ftp_model*);
+/* Shape (H, W, C) of the tensor entering unit `u` (u == L: leaving the last). */
+int ftp_model_unit_in_shape(const ftp_model*, int u, int* h, int* w, int* c);
+/* Number of fp32 parameters of unit u.  Layout of a unit's parameter vector:
+ *   CONV   : w[cout][kh][kw][cin], gamma[cout], beta[cout]
+ *   INVRES : (expand > 1: w1[ce][cin], gamma1[ce], beta1[ce],)
+ *            wd[ce][3][3], gamma2[ce], beta2[ce], w3[cout][ce], gamma3[cout], beta3[cout]
+ *            with ce = cin * expand
+ *   FC     : w[cout][cin], b[cout]
+ *   GAP, LOSS : none */
+int ftp_model_unit_param_count(const ftp_model*, int u, size_t* n);
+/* Number of BatchNorm channels of unit u, summed over its BatchNorms in order. */
+int ftp_model_unit_bn_channels(const ftp_model*, int u, size_t* n);
+
+/* ---- stage ------------------------------------------------------------------ */
+
+/* Builds units [a,b) for `batch` samples with `n_slots` in-flight batches on the
+ * current HIP device; allocates all device memory it will ever need.  Weights
+ * start at zero (import them), momentum and gradients at zero, BN running mean
+ * 0 / variance 1. */
+int ftp_stage_create(const ftp_model*, int a, int b, int batch, int n_slots, ftp_stage** out);
+void ftp_stage_destroy(ftp_stage*);
+
+/* Host <-> device copies of one unit's parameter vector (layout above), its
+ * accumulated gradient, its momentum buffer, and its BN running statistics
+ * (running_mean then running_var of each BatchNorm in order; 2 * bn_channels). */
+int ftp_stage_import_weights(ftp_stage*, int unit, const float* host_w, size_t n);
+int ftp_stage_export_weights(const ftp_stage*, int unit, float* host_w, size_t n);
+int ftp_stage_export_grads(const ftp_stage*, int unit, float* host_g, size_t n);
+int ftp_stage_export_momentum(const ftp_stage*, int unit, float* host_v, size_t n);
+int ftp_stage_export_bn_stats(const ftp_stage*, int unit, float* host_s, size_t n);
+
+/* Forward of one batch through units [a,b) with the current weights.
+ * x_dev: [batch, H, W, C] of unit a's input, read only, copied into the slot
+ * (the stashed stage input).  y_dev: output of the last unit, or NULL; when the
+ * stage ends with the LOSS unit, y receives the logits [batch, classes].
+ * The slot must be free; it is busy until its backward. */
+int ftp_stage_forward(ftp_stage*, int slot, const void* x_dev, void* y_dev, void* stream);
+
+/* Stages that end with the LOSS unit: mean cross-entropy of the slot's logits
+ * against labels_dev (int32 [batch], 0 <= label < classes) into loss_dev (one
+ * float); also seeds the slot's backward so dy_dev may be NULL there. */
+int ftp_stage_loss(ftp_stage*, int slot, const int32_t* labels_dev, float* loss_dev, void* stream);
+
+/* Copies the current weights into the slot (weight stashing): the slot's
+ * backward then differentiates with respect to that version.  Call it between
+ * the slot's forward and the next update.  Without it, backward uses the
+ * weights current at that time. */
+int ftp_stage_snapshot_weights(ftp_stage*, int slot, void* stream);
+
+/* Backward of the slot's batch.  dy_dev: gradient of the stage output (same
+ * shape and type as y), or NULL after ftp_stage_loss.  dx_dev: receives the
+ * gradient of the stage input, or NULL (e.g. a == 0).  Weight gradients are
+ * ACCUMULATED into the stage's gradient buffers.  Frees the slot. */
+int ftp_stage_backward(ftp_stage*, int slot, const void* dy_dev, void* dx_dev, void* stream);
+
+/* One SGD-momentum step on all parameters of the stage from the accumulated
+ * gradients, which are then zeroed. */
+int ftp_stage_update(ftp_stage*, const ftp_sgd* opt, void* stream);
+
+/* ---- profiling and partition ------------------------------------------------ */
+
+/* Model profiling: runs forward and backward of every unit of the whole model
+ * on synthetic data `reps` times (the paper uses 10) after 2 discarded warm-up
+ * runs, and returns per unit the mean forward+backward time in nanoseconds
+ * rounded to an integer value (t_ns, host, [L]) and the output size in bytes
+ * (out_bytes, host, [L]).  Synchronous. */
+int ftp_profile_layers(const ftp_model*, int batch, int reps, double* t_ns, int64_t* out_bytes,
+                       void* stream);
+
+/* Partition dynamic programme.  layer_costs[L] > 0: execution time of each unit
+ * on the profiling device; device_capacities[N] > 0: TIME MULTIPLIERS (the
+ * paper's computing capacity C_k = worker time / central-node time, so larger =
+ * slower; stage k on device k costs C_k * sum of its costs).  Optional
+ * out_bytes[L] and bandwidth[N-1] (both non-NULL) add the transfer term
+ * 2 * out_bytes[l-1] / bandwidth[k-1] for the cut in front of stage k.
+ * bounds[N+1] receives bounds[0] = 0 < ... < bounds[N] = L, stage k = units
+ * [bounds[k], bounds[k+1]); *bottleneck (may be NULL) the minimised slowest
+ * time.  Every stage is non-empty (N <= L).  Ties: smallest last cut.
+ * All host pointers; float64 arithmetic, bit-reproducible. */
+int ftp_solve_partition(const double* layer_costs, int L, const double* device_capacities, int N,
+                        const double* out_bytes, const double* bandwidth, int32_t* bounds,
+                        double* bottleneck);
+
+/* Capacity estimate of a worker: its measured stage time divided by the
+ * profiling device's time for the same units [start, end] (inclusive). */
+int ftp_estimate_capacity(double stage_time, const double* layer_costs, int L, int start, int end,
+                          double* capacity);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FTP_H */

@@ -1,0 +1,234 @@
+"""ctypes binding of include/ftp.h.  Argument marshalling only: every function
+here has the name of the C entry point without the ftp_ prefix, converts
+arguments, calls it and raises FtpError on a negative status.  Device buffers
+are passed as integer addresses (e.g. torch_tensor.data_ptr()), streams as the
+raw hipStream_t (e.g. torch.cuda.current_stream().cuda_stream).
+
+There is no fallback: if libftp_hip.so has not been built, importing this module
+raises."""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libftp_hip.so")
+
+F32, BF16 = 0, 1
+UNIT_CONV, UNIT_INVRES, UNIT_GAP, UNIT_FC, UNIT_LOSS = range(5)
+ACT_NONE, ACT_RELU, ACT_RELU6 = range(3)
+
+
+class FtpError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__(f"ftp status {status}: {msg}")
+        self.status = status
+
+
+class UnitDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("kind", "cin", "cout", "kh", "kw", "stride", "pad_h", "pad_w", "expand", "act")]
+
+
+class Sgd(C.Structure):
+    _fields_ = [("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float)]
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: run `python -m paper_2110_02781_amd.build` "
+                          "(or __graft_entry__.build()) first; there is no CPU fallback")
+    return C.CDLL(_LIB_PATH)
+
+
+lib = _load()
+_vp, _i, _sz = C.c_void_p, C.c_int, C.c_size_t
+_fp = C.POINTER(C.c_float)
+_dp = C.POINTER(C.c_double)
+_SIGS = {
+    "ftp_last_error": (C.c_char_p, []),
+    "ftp_model_create": (_i, [C.POINTER(UnitDesc), _i, _i, _i, _i, _i, C.POINTER(_vp)]),
+    "ftp_model_destroy": (None, [_vp]),
+    "ftp_model_num_units": (_i, [_vp]),
+    "ftp_model_unit_in_shape": (_i, [_vp, _i, C.POINTER(_i), C.POINTER(_i), C.POINTER(_i)]),
+    "ftp_model_unit_param_count": (_i, [_vp, _i, C.POINTER(_sz)]),
+    "ftp_model_unit_bn_channels": (_i, [_vp, _i, C.POINTER(_sz)]),
+    "ftp_stage_create": (_i, [_vp, _i, _i, _i, _i, C.POINTER(_vp)]),
+    "ftp_stage_destroy": (None, [_vp]),
+    "ftp_stage_import_weights": (_i, [_vp, _i, _fp, _sz]),
+    "ftp_stage_export_weights": (_i, [_vp, _i, _fp, _sz]),
+    "ftp_stage_export_grads": (_i, [_vp, _i, _fp, _sz]),
+    "ftp_stage_export_momentum": (_i, [_vp, _i, _fp, _sz]),
+    "ftp_stage_export_bn_stats": (_i, [_vp, _i, _fp, _sz]),
+    "ftp_stage_forward": (_i, [_vp, _i, _vp, _vp, _vp]),
+    "ftp_stage_loss": (_i, [_vp, _i, _vp, _vp, _vp]),
+    "ftp_stage_snapshot_weights": (_i, [_vp, _i, _vp]),
+    "ftp_stage_backward": (_i, [_vp, _i, _vp, _vp, _vp]),
+    "ftp_stage_update": (_i, [_vp, C.POINTER(Sgd), _vp]),
+    "ftp_profile_layers": (_i, [_vp, _i, _i, _dp, C.POINTER(C.c_int64), _vp]),
+    "ftp_solve_partition": (_i, [_dp, _i, _dp, _i, _dp, _dp, C.POINTER(C.c_int32), _dp]),
+    "ftp_estimate_capacity": (_i, [C.c_double, _dp, _i, _i, _i, _dp]),
+}
+for _name, (_res, _args) in _SIGS.items():
+    _f = getattr(lib, _name)
+    _f.restype, _f.argtypes = _res, _args
+
+
+def last_error():
+    return lib.ftp_last_error().decode()
+
+
+def _chk(rc):
+    if rc < 0:
+        raise FtpError(rc, last_error())
+    return rc
+
+
+def _ptr(p):
+    """tensor / int / None -> void*"""
+    if p is None:
+        return None
+    if hasattr(p, "data_ptr"):
+        return C.c_void_p(p.data_ptr())
+    return C.c_void_p(int(p))
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, a.ctypes.data_as(_fp)
+
+
+def _f64(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a, a.ctypes.data_as(_dp)
+
+
+# ---- model ---------------------------------------------------------------------
+def model_create(units, in_h, in_w, in_c, act_dtype=F32):
+    """units: sequence of dicts / UnitDesc with the fields of ftp_unit_desc."""
+    arr = (UnitDesc * len(units))()
+    for i, u in enumerate(units):
+        if isinstance(u, UnitDesc):
+            arr[i] = u
+        else:
+            for f, _ in UnitDesc._fields_:
+                setattr(arr[i], f, int(u.get(f, 0)))
+    out = _vp()
+    _chk(lib.ftp_model_create(arr, len(units), in_h, in_w, in_c, act_dtype, C.byref(out)))
+    return out
+
+
+def model_destroy(model):
+    lib.ftp_model_destroy(model)
+
+
+def model_num_units(model):
+    return _chk(lib.ftp_model_num_units(model))
+
+
+def model_unit_in_shape(model, u):
+    h, w, c = _i(), _i(), _i()
+    _chk(lib.ftp_model_unit_in_shape(model, u, C.byref(h), C.byref(w), C.byref(c)))
+    return h.value, w.value, c.value
+
+
+def model_unit_param_count(model, u):
+    n = _sz()
+    _chk(lib.ftp_model_unit_param_count(model, u, C.byref(n)))
+    return n.value
+
+
+def model_unit_bn_channels(model, u):
+    n = _sz()
+    _chk(lib.ftp_model_unit_bn_channels(model, u, C.byref(n)))
+    return n.value
+
+
+# ---- stage ---------------------------------------------------------------------
+def stage_create(model, a, b, batch, n_slots=1):
+    out = _vp()
+    _chk(lib.ftp_stage_create(model, a, b, batch, n_slots, C.byref(out)))
+    return out
+
+
+def stage_destroy(stage):
+    lib.ftp_stage_destroy(stage)
+
+
+def stage_import_weights(stage, unit, host_w):
+    a, p = _f32(host_w)
+    _chk(lib.ftp_stage_import_weights(stage, unit, p, a.size))
+
+
+def _export(fn, stage, unit, n):
+    out = np.empty(n, dtype=np.float32)
+    _chk(fn(stage, unit, out.ctypes.data_as(_fp), n))
+    return out
+
+
+def stage_export_weights(stage, unit, n):
+    return _export(lib.ftp_stage_export_weights, stage, unit, n)
+
+
+def stage_export_grads(stage, unit, n):
+    return _export(lib.ftp_stage_export_grads, stage, unit, n)
+
+
+def stage_export_momentum(stage, unit, n):
+    return _export(lib.ftp_stage_export_momentum, stage, unit, n)
+
+
+def stage_export_bn_stats(stage, unit, n):
+    return _export(lib.ftp_stage_export_bn_stats, stage, unit, n)
+
+
+def stage_forward(stage, slot, x_dev, y_dev=None, stream=None):
+    _chk(lib.ftp_stage_forward(stage, slot, _ptr(x_dev), _ptr(y_dev), _ptr(stream)))
+
+
+def stage_loss(stage, slot, labels_dev, loss_dev, stream=None):
+    _chk(lib.ftp_stage_loss(stage, slot, _ptr(labels_dev), _ptr(loss_dev), _ptr(stream)))
+
+
+def stage_snapshot_weights(stage, slot, stream=None):
+    _chk(lib.ftp_stage_snapshot_weights(stage, slot, _ptr(stream)))
+
+
+def stage_backward(stage, slot, dy_dev=None, dx_dev=None, stream=None):
+    _chk(lib.ftp_stage_backward(stage, slot, _ptr(dy_dev), _ptr(dx_dev), _ptr(stream)))
+
+
+def stage_update(stage, lr, momentum, weight_decay, stream=None):
+    opt = Sgd(lr, momentum, weight_decay)
+    _chk(lib.ftp_stage_update(stage, C.byref(opt), _ptr(stream)))
+
+
+# ---- profiling and partition -----------------------------------------------------
+def profile_layers(model, batch, reps=10, stream=None):
+    L = model_num_units(model)
+    t = np.zeros(L, dtype=np.float64)
+    ob = np.zeros(L, dtype=np.int64)
+    _chk(lib.ftp_profile_layers(model, batch, reps, t.ctypes.data_as(_dp),
+                                ob.ctypes.data_as(C.POINTER(C.c_int64)), _ptr(stream)))
+    return t, ob
+
+
+def solve_partition(layer_costs, device_capacities, out_bytes=None, bandwidth=None):
+    c, cp = _f64(layer_costs)
+    k, kp = _f64(device_capacities)
+    dp = bp = None
+    if out_bytes is not None and bandwidth is not None:
+        d, dp = _f64(out_bytes)
+        b, bp = _f64(bandwidth)
+    bounds = np.zeros(k.size + 1, dtype=np.int32)
+    bott = C.c_double()
+    _chk(lib.ftp_solve_partition(cp, c.size, kp, k.size, dp, bp,
+                                 bounds.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(bott)))
+    return bounds, bott.value
+
+
+def estimate_capacity(stage_time, layer_costs, start, end):
+    c, cp = _f64(layer_costs)
+    out = C.c_double()
+    _chk(lib.ftp_estimate_capacity(stage_time, cp, c.size, start, end, C.byref(out)))
+    return out.value

@@ -1,0 +1,430 @@
+// BatchNorm statistics / apply / backward, pooling, softmax cross-entropy,
+// SGD-momentum and small utility kernels.  All are HBM-bound streaming kernels:
+// each thread moves 8 consecutive channels (16 or 32 bytes) per access, rows
+// are walked so that a block touches contiguous memory, and per-channel sums
+// are reduced in a fixed order (per thread -> LDS across the block -> float64
+// across blocks), so results are run-to-run deterministic.
+#include "dev_common.h"
+#include "kernels.h"
+
+namespace ftp {
+
+#define FTP_DISPATCH(dt, ...)                   \
+  do {                                          \
+    if ((dt) == 0) { typedef float T; __VA_ARGS__; } \
+    else { typedef bf16_t T; __VA_ARGS__; }     \
+  } while (0)
+
+RowTile make_rowtile(size_t M, int C, int max_partials) {
+  RowTile t;
+  int CG = C / 8;
+  t.nslab = (CG + 255) / 256;
+  t.W = (CG + t.nslab - 1) / t.nslab;
+  t.R = 256 / t.W;
+  if (t.R < 1) t.R = 1;
+  size_t want = (M + max_partials - 1) / max_partials;        // rows per block so that P <= max
+  size_t rpb = ((want + t.R - 1) / t.R) * t.R;
+  size_t min_rpb = (size_t)t.R * 4;                            // at least 4 iterations per block
+  if (rpb < min_rpb) rpb = min_rpb;
+  t.rows_per_block = rpb;
+  t.P = (int)((M + rpb - 1) / rpb);
+  if (t.P < 1) t.P = 1;
+  return t;
+}
+
+// Sum v[0..NV) over the threads of a block that share tx (same columns); the
+// result is valid in the threads with ty == 0.  smem needs NV*R*W floats.
+template <int NV>
+__device__ __forceinline__ void reduce_over_rows(float (&v)[NV], int tx, int ty, int W, int R, float* smem) {
+#pragma unroll
+  for (int e = 0; e < NV; ++e) smem[(e * R + ty) * W + tx] = v[e];
+  __syncthreads();
+  if (ty == 0) {
+#pragma unroll
+    for (int e = 0; e < NV; ++e) {
+      float s = 0.f;
+      for (int r = 0; r < R; ++r) s += smem[(e * R + r) * W + tx];
+      v[e] = s;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ bn_stats
+template <typename T>
+__global__ void bn_stats_k(const T* __restrict__ z, size_t M, int C, int W, int R, size_t rpb,
+                           float* __restrict__ partial) {
+  extern __shared__ float smem[];
+  int tx = threadIdx.x % W, ty = threadIdx.x / W;
+  int cg = blockIdx.y * W + tx;
+  float acc[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  if (cg < C / 8) {
+    size_t m0 = (size_t)blockIdx.x * rpb, m1 = m0 + rpb < M ? m0 + rpb : M;
+    for (size_t m = m0 + ty; m < m1; m += R) {
+      float v[8];
+      load8(z + m * C + cg * 8, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { acc[e] += v[e]; acc[8 + e] = fmaf(v[e], v[e], acc[8 + e]); }
+    }
+  }
+  reduce_over_rows<16>(acc, tx, ty, W, R, smem);
+  if (ty == 0 && cg < C / 8) {
+    float* p = partial + (size_t)blockIdx.x * 2 * C + cg * 8;
+    store8(p, acc);
+    store8(p + C, acc + 8);
+  }
+}
+
+void bn_stats(int dt, hipStream_t st, const void* z, size_t M, int C, float* partial, int* P_out) {
+  RowTile t = make_rowtile(M, C, kMaxPartials);
+  dim3 grid(t.P, t.nslab), block(t.W * t.R);
+  size_t sm = (size_t)16 * t.R * t.W * sizeof(float);
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_stats_k<T>, grid, block, sm, st, (const T*)z, M, C, t.W, t.R,
+                                      t.rows_per_block, partial));
+  *P_out = t.P;
+}
+
+// Sum partial[p][q][c] over p in float64; 16 channels per block, 16 lanes per channel.
+template <int Q>
+__device__ __forceinline__ void sum_partials(const float* __restrict__ partial, int P, int C, int c,
+                                             int lane, double (&out)[Q], double* smem) {
+  double s[Q];
+#pragma unroll
+  for (int q = 0; q < Q; ++q) s[q] = 0.0;
+  if (c < C)
+    for (int p = lane; p < P; p += 16)
+#pragma unroll
+      for (int q = 0; q < Q; ++q) s[q] += (double)partial[((size_t)p * Q + q) * C + c];
+  int cl = threadIdx.x % 16;
+#pragma unroll
+  for (int q = 0; q < Q; ++q) smem[(q * 16 + lane) * 16 + cl] = s[q];
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    double t = 0.0;
+    for (int l = 0; l < 16; ++l) t += smem[(q * 16 + l) * 16 + cl];
+    out[q] = t;
+  }
+}
+
+__global__ void bn_finalize_k(const float* __restrict__ partial, int P, size_t M, int C,
+                              const float* __restrict__ gamma, const float* __restrict__ beta,
+                              float* mean, float* invstd, float* scale, float* shift, float* run_mean,
+                              float* run_var, float eps, float momentum) {
+  __shared__ double smem[2 * 16 * 16];
+  int cl = threadIdx.x % 16, lane = threadIdx.x / 16;
+  int c = blockIdx.x * 16 + cl;
+  double s[2];
+  sum_partials<2>(partial, P, C, c, lane, s, smem);
+  if (lane == 0 && c < C) {
+    double mu = s[0] / (double)M;
+    double var = s[1] / (double)M - mu * mu;
+    if (var < 0.0) var = 0.0;
+    double is = 1.0 / sqrt(var + (double)eps);
+    float sc = (float)((double)gamma[c] * is);
+    mean[c] = (float)mu;
+    invstd[c] = (float)is;
+    scale[c] = sc;
+    shift[c] = (float)((double)beta[c] - mu * (double)sc);
+    double unb = M > 1 ? var * ((double)M / (double)(M - 1)) : var;
+    run_mean[c] = (float)((1.0 - momentum) * run_mean[c] + momentum * mu);
+    run_var[c] = (float)((1.0 - momentum) * run_var[c] + momentum * unb);
+  }
+}
+
+void bn_finalize(hipStream_t st, const float* partial, int P, size_t M, int C, const float* gamma,
+                 const float* beta, float* mean, float* invstd, float* scale, float* shift,
+                 float* run_mean, float* run_var, float eps, float momentum) {
+  hipLaunchKernelGGL(bn_finalize_k, dim3((C + 15) / 16), dim3(256), 0, st, partial, P, M, C, gamma, beta,
+                     mean, invstd, scale, shift, run_mean, run_var, eps, momentum);
+}
+
+// ------------------------------------------------------------- bn backward
+template <typename T>
+__global__ void bn_bwd_reduce_k(const T* __restrict__ dA, const T* __restrict__ z, size_t M, int C,
+                                const float* __restrict__ scale, const float* __restrict__ shift, int act,
+                                int W, int R, size_t rpb, float* __restrict__ partial) {
+  extern __shared__ float smem[];
+  int tx = threadIdx.x % W, ty = threadIdx.x / W;
+  int cg = blockIdx.y * W + tx;
+  float acc[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  if (cg < C / 8) {
+    float sc[8], sh[8];
+    load8(scale + cg * 8, sc);
+    load8(shift + cg * 8, sh);
+    size_t m0 = (size_t)blockIdx.x * rpb, m1 = m0 + rpb < M ? m0 + rpb : M;
+    for (size_t m = m0 + ty; m < m1; m += R) {
+      float d[8], v[8];
+      load8(dA + m * C + cg * 8, d);
+      load8(z + m * C + cg * 8, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float dy = d[e] * act_mask(fmaf(v[e], sc[e], sh[e]), act);
+        acc[e] += dy;
+        acc[8 + e] = fmaf(dy, v[e], acc[8 + e]);
+      }
+    }
+  }
+  reduce_over_rows<16>(acc, tx, ty, W, R, smem);
+  if (ty == 0 && cg < C / 8) {
+    float* p = partial + (size_t)blockIdx.x * 2 * C + cg * 8;
+    store8(p, acc);
+    store8(p + C, acc + 8);
+  }
+}
+
+void bn_bwd_reduce(int dt, hipStream_t st, const void* dA, const void* z, size_t M, int C,
+                   const float* scale, const float* shift, int act, float* partial, int* P_out) {
+  RowTile t = make_rowtile(M, C, kMaxPartials);
+  dim3 grid(t.P, t.nslab), block(t.W * t.R);
+  size_t sm = (size_t)16 * t.R * t.W * sizeof(float);
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_bwd_reduce_k<T>, grid, block, sm, st, (const T*)dA, (const T*)z, M,
+                                      C, scale, shift, act, t.W, t.R, t.rows_per_block, partial));
+  *P_out = t.P;
+}
+
+__global__ void bn_bwd_finalize_k(const float* __restrict__ partial, int P, size_t M, int C,
+                                  const float* __restrict__ gamma, const float* __restrict__ mean,
+                                  const float* __restrict__ invstd, float* g_gamma, float* g_beta,
+                                  float* coef) {
+  __shared__ double smem[2 * 16 * 16];
+  int cl = threadIdx.x % 16, lane = threadIdx.x / 16;
+  int c = blockIdx.x * 16 + cl;
+  double s[2];
+  sum_partials<2>(partial, P, C, c, lane, s, smem);
+  if (lane == 0 && c < C) {
+    double mu = mean[c], is = invstd[c], g = gamma[c];
+    double dbeta = s[0];
+    double dgamma = is * (s[1] - mu * s[0]);
+    g_gamma[c] += (float)dgamma;
+    g_beta[c] += (float)dbeta;
+    double k1 = g * is;
+    double k2 = -k1 * is * dgamma / (double)M;
+    double k3 = -k1 * dbeta / (double)M - k2 * mu;
+    coef[c] = (float)k1;
+    coef[C + c] = (float)k2;
+    coef[2 * C + c] = (float)k3;
+  }
+}
+
+void bn_bwd_finalize(hipStream_t st, const float* partial, int P, size_t M, int C, const float* gamma,
+                     const float* mean, const float* invstd, float* g_gamma, float* g_beta, float* coef) {
+  hipLaunchKernelGGL(bn_bwd_finalize_k, dim3((C + 15) / 16), dim3(256), 0, st, partial, P, M, C, gamma, mean,
+                     invstd, g_gamma, g_beta, coef);
+}
+
+template <typename T>
+__global__ void bn_bwd_apply_k(const T* __restrict__ dA, const T* __restrict__ z, size_t nvec, int CG,
+                               const float* __restrict__ scale, const float* __restrict__ shift, int act,
+                               const float* __restrict__ coef, T* __restrict__ dz) {
+  int C = CG * 8;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (size_t)gridDim.x * blockDim.x) {
+    int c = (int)(i % CG) * 8;
+    float d[8], v[8], sc[8], sh[8], k1[8], k2[8], k3[8], o[8];
+    load8(dA + i * 8, d);
+    load8(z + i * 8, v);
+    load8(scale + c, sc); load8(shift + c, sh);
+    load8(coef + c, k1); load8(coef + C + c, k2); load8(coef + 2 * C + c, k3);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float dy = d[e] * act_mask(fmaf(v[e], sc[e], sh[e]), act);
+      o[e] = fmaf(k1[e], dy, fmaf(k2[e], v[e], k3[e]));
+    }
+    store8(dz + i * 8, o);
+  }
+}
+
+static inline int flat_grid(size_t n, int block) {
+  size_t g = (n + block - 1) / block;
+  if (g > 65536) g = 65536;
+  if (g < 1) g = 1;
+  return (int)g;
+}
+
+void bn_bwd_apply(int dt, hipStream_t st, const void* dA, const void* z, size_t M, int C,
+                  const float* scale, const float* shift, int act, const float* coef, void* dz) {
+  size_t nvec = M * (size_t)(C / 8);
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_bwd_apply_k<T>, dim3(flat_grid(nvec, 256)), dim3(256), 0, st,
+                                      (const T*)dA, (const T*)z, nvec, C / 8, scale, shift, act, coef, (T*)dz));
+}
+
+template <typename T>
+__global__ void bn_apply_k(View in, size_t nvec, int CG, const T* __restrict__ res, T* __restrict__ out) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (size_t)gridDim.x * blockDim.x) {
+    int c = (int)(i % CG) * 8;
+    float v[8];
+    view_load8<T>(in, i * 8, c, v);
+    if (res) {
+      float r[8];
+      load8(res + i * 8, r);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += r[e];
+    }
+    store8(out + i * 8, v);
+  }
+}
+
+void bn_apply(int dt, hipStream_t st, HView in, size_t M, int C, const void* res, void* out) {
+  size_t nvec = M * (size_t)(C / 8);
+  View v{in.z, in.scale, in.shift, in.act};
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_apply_k<T>, dim3(flat_grid(nvec, 256)), dim3(256), 0, st, v, nvec,
+                                      C / 8, (const T*)res, (T*)out));
+}
+
+// ------------------------------------------------------------------ pooling
+template <typename T>
+__global__ void gap_fwd_k(View in, int N, int HW, int CG, T* __restrict__ out) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N * CG) return;
+  int n = i / CG, cg = i % CG;
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int p = 0; p < HW; ++p) {
+    float v[8];
+    view_load8<T>(in, ((size_t)n * HW + p) * CG * 8 + cg * 8, cg * 8, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += v[e];
+  }
+  float inv = 1.f / (float)HW;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] *= inv;
+  store8(out + (size_t)i * 8, acc);
+}
+
+void gap_fwd(int dt, hipStream_t st, HView in, int N, int HW, int C, void* out) {
+  View v{in.z, in.scale, in.shift, in.act};
+  int n = N * (C / 8);
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(gap_fwd_k<T>, dim3((n + 127) / 128), dim3(128), 0, st, v, N, HW, C / 8,
+                                      (T*)out));
+}
+
+template <typename T>
+__global__ void gap_bwd_k(const T* __restrict__ dOut, size_t nvec, int HW, int CG, T* __restrict__ dIn) {
+  float inv = 1.f / (float)HW;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (size_t)gridDim.x * blockDim.x) {
+    size_t n = i / ((size_t)HW * CG);
+    int cg = (int)(i % CG);
+    float v[8];
+    load8(dOut + (n * CG + cg) * 8, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] *= inv;
+    store8(dIn + i * 8, v);
+  }
+}
+
+void gap_bwd(int dt, hipStream_t st, const void* dOut, int N, int HW, int C, void* dIn) {
+  size_t nvec = (size_t)N * HW * (C / 8);
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(gap_bwd_k<T>, dim3(flat_grid(nvec, 256)), dim3(256), 0, st,
+                                      (const T*)dOut, nvec, HW, C / 8, (T*)dIn));
+}
+
+// ----------------------------------------------------- softmax cross-entropy
+__device__ __forceinline__ float block_reduce_256(float v, bool is_max, float* smem) {
+  int tid = threadIdx.x;
+  smem[tid] = v;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (tid < s) smem[tid] = is_max ? fmaxf(smem[tid], smem[tid + s]) : smem[tid] + smem[tid + s];
+    __syncthreads();
+  }
+  float r = smem[0];
+  __syncthreads();
+  return r;
+}
+
+template <typename T>
+__global__ void softmax_ce_k(const T* __restrict__ logits, const int32_t* __restrict__ labels, int B,
+                             int classes, float* __restrict__ row_loss, T* __restrict__ dlogits) {
+  __shared__ float smem[256];
+  int b = blockIdx.x;
+  const T* row = logits + (size_t)b * classes;
+  float mx = -INFINITY;
+  for (int j = threadIdx.x; j < classes; j += 256) mx = fmaxf(mx, to_f32(row[j]));
+  mx = block_reduce_256(mx, true, smem);
+  float s = 0.f;
+  for (int j = threadIdx.x; j < classes; j += 256) s += expf(to_f32(row[j]) - mx);
+  s = block_reduce_256(s, false, smem);
+  int lab = labels[b];
+  const bool lab_ok = lab >= 0 && lab < classes;   // an invalid label yields a NaN loss, never a stray read
+  float invB = 1.f / (float)B, invs = 1.f / s;
+  for (int j = threadIdx.x; j < classes; j += 256) {
+    float p = expf(to_f32(row[j]) - mx) * invs;
+    dlogits[(size_t)b * classes + j] = from_f32<T>((p - (j == lab ? 1.f : 0.f)) * invB);
+  }
+  if (threadIdx.x == 0) row_loss[b] = lab_ok ? -(to_f32(row[lab]) - mx - logf(s)) : NAN;
+}
+
+__global__ void mean_rows_k(const float* __restrict__ row_loss, int B, float* __restrict__ loss) {
+  __shared__ float smem[256];
+  float s = 0.f;
+  for (int i = threadIdx.x; i < B; i += 256) s += row_loss[i];
+  s = block_reduce_256(s, false, smem);
+  if (threadIdx.x == 0) *loss = s / (float)B;
+}
+
+void softmax_ce(int dt, hipStream_t st, const void* logits, const int32_t* labels, int B, int classes,
+                float* row_loss, void* dlogits, float* loss) {
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(softmax_ce_k<T>, dim3(B), dim3(256), 0, st, (const T*)logits, labels, B,
+                                      classes, row_loss, (T*)dlogits));
+  hipLaunchKernelGGL(mean_rows_k, dim3(1), dim3(256), 0, st, row_loss, B, loss);
+}
+
+template <typename T>
+__global__ void bias_grad_k(const T* __restrict__ d, int B, int Nout, float* __restrict__ g) {
+  int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= Nout) return;
+  float s = 0.f;
+  for (int b = 0; b < B; ++b) s += to_f32(d[(size_t)b * Nout + j]);
+  g[j] += s;
+}
+
+void bias_grad(int dt, hipStream_t st, const void* d, int B, int Nout, float* g_bias) {
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(bias_grad_k<T>, dim3((Nout + 127) / 128), dim3(128), 0, st,
+                                      (const T*)d, B, Nout, g_bias));
+}
+
+// -------------------------------------------------------------------- SGD
+__global__ void sgd_update_k(float* __restrict__ w, float* __restrict__ g, float* __restrict__ v,
+                             bf16_t* __restrict__ w_lp, size_t n, float lr, float mu, float wd) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+    float wi = w[i];
+    float gi = fmaf(wd, wi, g[i]);
+    float vi = fmaf(mu, v[i], gi);
+    wi = fmaf(-lr, vi, wi);
+    w[i] = wi;
+    v[i] = vi;
+    g[i] = 0.f;
+    if (w_lp) w_lp[i] = f32_to_bf16(wi);
+  }
+}
+
+void sgd_update(hipStream_t st, float* w, float* g, float* v, void* w_lp, size_t n, float lr, float mu,
+                float wd) {
+  hipLaunchKernelGGL(sgd_update_k, dim3(flat_grid(n, 256)), dim3(256), 0, st, w, g, v, (bf16_t*)w_lp, n, lr,
+                     mu, wd);
+}
+
+__global__ void fill_zero_k(uint32_t* p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = 0u;
+}
+
+void fill_zero(hipStream_t st, void* p, size_t bytes) {
+  size_t n = (bytes + 3) / 4;  // buffers are allocated in multiples of 256 bytes
+  hipLaunchKernelGGL(fill_zero_k, dim3(flat_grid(n, 256)), dim3(256), 0, st, (uint32_t*)p, n);
+}
+
+template <typename T>
+__global__ void f32_to_storage_k(const float* __restrict__ src, T* __restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = from_f32<T>(src[i]);
+}
+
+void f32_to_storage(int dt, hipStream_t st, const float* src, void* dst, size_t n) {
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(f32_to_storage_k<T>, dim3(flat_grid(n, 256)), dim3(256), 0, st, src,
+                                      (T*)dst, n));
+}
+
+}  // namespace ftp

@@ -1,0 +1,94 @@
+// Host-side launch interface of the HIP kernels.  All functions enqueue work on
+// `st` and return immediately; none allocates.  `dt` selects the storage type
+// of activations / activation gradients / working weights (0 = float,
+// 1 = bfloat16); statistics, weight gradients and accumulators are fp32.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ftp {
+
+struct HView {  // same layout as the device-side View
+  const void* z;
+  const float* scale;
+  const float* shift;
+  int act;
+};
+
+struct ConvGeom {
+  int N, Hin, Win, Cin, Hout, Wout, Cout, kh, kw, stride, ph, pw;
+};
+
+// Launch shape for kernels that walk a [M][C] tensor by rows, 8 channels per thread.
+struct RowTile {
+  int W;                  // column groups handled by one block
+  int R;                  // rows handled per block iteration
+  int nslab;              // grid.y
+  size_t rows_per_block;
+  int P;                  // grid.x = number of row chunks = number of partials
+};
+RowTile make_rowtile(size_t M, int C, int max_partials);
+enum { kMaxPartials = 512 };
+
+// ---- BatchNorm ---------------------------------------------------------------
+// partial[P][2][C] <- per-chunk sums of z and z*z
+void bn_stats(int dt, hipStream_t st, const void* z, size_t M, int C, float* partial, int* P_out);
+// mean/invstd/scale/shift (each [C]) from the partials; updates running stats
+void bn_finalize(hipStream_t st, const float* partial, int P, size_t M, int C, const float* gamma,
+                 const float* beta, float* mean, float* invstd, float* scale, float* shift,
+                 float* run_mean, float* run_var, float eps, float momentum);
+// partial[P][2][C] <- sums of dY and dY*z with dY = dA * act'(scale*z+shift)
+void bn_bwd_reduce(int dt, hipStream_t st, const void* dA, const void* z, size_t M, int C,
+                   const float* scale, const float* shift, int act, float* partial, int* P_out);
+// g_gamma += dgamma, g_beta += dbeta; coef[3][C] for dz = k1*dY + k2*z + k3
+void bn_bwd_finalize(hipStream_t st, const float* partial, int P, size_t M, int C, const float* gamma,
+                     const float* mean, const float* invstd, float* g_gamma, float* g_beta, float* coef);
+// dz (may alias dA) = k1*dA*act'(y) + k2*z + k3
+void bn_bwd_apply(int dt, hipStream_t st, const void* dA, const void* z, size_t M, int C,
+                  const float* scale, const float* shift, int act, const float* coef, void* dz);
+// out = act(scale*z+shift) (+ res)
+void bn_apply(int dt, hipStream_t st, HView in, size_t M, int C, const void* res, void* out);
+
+// ---- pooling, loss, optimiser ---------------------------------------------------
+void gap_fwd(int dt, hipStream_t st, HView in, int N, int HW, int C, void* out);
+void gap_bwd(int dt, hipStream_t st, const void* dOut, int N, int HW, int C, void* dIn);
+// per-row loss into row_loss[B], dlogits[B][classes] = (softmax - onehot)/B, then mean into *loss
+void softmax_ce(int dt, hipStream_t st, const void* logits, const int32_t* labels, int B, int classes,
+                float* row_loss, void* dlogits, float* loss);
+// g_bias[j] += sum_b d[b][j]
+void bias_grad(int dt, hipStream_t st, const void* d, int B, int Nout, float* g_bias);
+// g += wd*w; v = mu*v+g; w -= lr*v; g = 0; optional working copy w_lp (bfloat16)
+void sgd_update(hipStream_t st, float* w, float* g, float* v, void* w_lp, size_t n, float lr, float mu,
+                float wd);
+void fill_zero(hipStream_t st, void* p, size_t bytes);
+void f32_to_storage(int dt, hipStream_t st, const float* src, void* dst, size_t n);
+
+// ---- generic small dense convolution (stem 3x3, conv1d) ---------------------------
+int conv_direct_supported(const ConvGeom& g);
+void conv_direct_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z);
+void conv_direct_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvGeom& g, void* dIn);
+// partial then accumulate into g_w[Cout][kh][kw][Cin]
+size_t conv_direct_wgrad_ws(const ConvGeom& g);  // floats of workspace needed
+void conv_direct_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, float* ws,
+                       float* g_w);
+
+// ---- depthwise 3x3 ----------------------------------------------------------------
+void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z);
+void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvGeom& g, void* dIn);
+size_t dw_wgrad_ws(const ConvGeom& g);
+void dw_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, float* ws, float* g_w);
+
+// ---- pointwise / fully connected GEMMs (MFMA) ---------------------------------------
+// Z[M][N] = A'[M][K] * W[N][K]^T (+ bias[N])
+void pw_fwd(int dt, hipStream_t st, HView a, const void* w, const float* bias, size_t M, int K, int N,
+            void* z);
+// dA[M][K] = dZ[M][N] * W[N][K] (+ res[M][K])
+void pw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const void* res, size_t M, int K,
+              int N, void* dA);
+// g_w[N][K] += dZ[M][N]^T * A'[M][K]
+size_t pw_wgrad_ws(size_t M, int K, int N);
+void pw_wgrad(int dt, hipStream_t st, const void* dz, HView a, size_t M, int K, int N, float* ws,
+              float* g_w);
+
+}  // namespace ftp

@@ -1,0 +1,93 @@
+// Host-side partition solver and capacity estimate (paper, section "Dynamic
+// Model Partition": capacity equation, per-layer estimate, DP base case and
+// recurrence, transfer-time and last-stage-time equations).
+//
+// Capacity is a time multiplier (worker time / central-node time), so stage k
+// holding layers [l, j) costs (P[j] - P[l]) * C[k] with P the running sum of the
+// profiled layer costs.  best[n][j] is the optimum for the first j layers on
+// devices 0..n-1; the last cut l runs over n-1 .. j-1 so that no stage is empty.
+// Candidates are visited in ascending l and replace the incumbent only when
+// strictly smaller.  All arithmetic is float64 with one rounding per operation
+// (this file is compiled with floating-point contraction off).
+#include <cmath>
+#include <cstdio>
+#include <vector>
+
+#include "../../include/ftp.h"
+
+void ftp_set_error(const char* fmt, ...);
+
+extern "C" int ftp_solve_partition(const double* layer_costs, int L, const double* device_capacities, int N,
+                                   const double* out_bytes, const double* bandwidth, int32_t* bounds,
+                                   double* bottleneck) {
+  if (!layer_costs || !device_capacities || !bounds) { ftp_set_error("solve_partition: NULL argument"); return FTP_ERR_ARG; }
+  if (N < 1 || L < N) { ftp_set_error("solve_partition: need 1 <= N <= L (N=%d, L=%d)", N, L); return FTP_ERR_ARG; }
+  for (int i = 0; i < L; ++i)
+    if (!(std::isfinite(layer_costs[i]) && layer_costs[i] > 0.0)) {
+      ftp_set_error("solve_partition: layer_costs[%d] must be finite and > 0", i);
+      return FTP_ERR_VALUE;
+    }
+  for (int k = 0; k < N; ++k)
+    if (!(std::isfinite(device_capacities[k]) && device_capacities[k] > 0.0)) {
+      ftp_set_error("solve_partition: device_capacities[%d] must be finite and > 0", k);
+      return FTP_ERR_VALUE;
+    }
+  const bool comm = out_bytes && bandwidth;
+  if (comm) {
+    for (int i = 0; i < L; ++i)
+      if (!(std::isfinite(out_bytes[i]) && out_bytes[i] >= 0.0)) { ftp_set_error("solve_partition: bad out_bytes[%d]", i); return FTP_ERR_VALUE; }
+    for (int k = 0; k + 1 < N; ++k)
+      if (!(std::isfinite(bandwidth[k]) && bandwidth[k] > 0.0)) { ftp_set_error("solve_partition: bad bandwidth[%d]", k); return FTP_ERR_VALUE; }
+  }
+  std::vector<double> P(L + 1, 0.0);
+  for (int i = 0; i < L; ++i) P[i + 1] = P[i] + layer_costs[i];
+  const double INF = INFINITY;
+  const int S = L + 1;
+  std::vector<double> best((size_t)(N + 1) * S, INF);
+  std::vector<int> arg((size_t)(N + 1) * S, 0);
+  for (int j = 1; j <= L; ++j) best[(size_t)1 * S + j] = P[j] * device_capacities[0];
+  for (int n = 2; n <= N; ++n) {
+    const double cap = device_capacities[n - 1];
+    for (int j = n; j <= L; ++j) {
+      double b = INF;
+      int a = -1;
+      for (int l = n - 1; l < j; ++l) {
+        double t = best[(size_t)(n - 1) * S + l];
+        double last = (P[j] - P[l]) * cap;
+        if (last > t) t = last;
+        if (comm) {
+          double c = 2.0 * (out_bytes[l - 1] / bandwidth[n - 2]);
+          if (c > t) t = c;
+        }
+        if (t < b) { b = t; a = l; }
+      }
+      best[(size_t)n * S + j] = b;
+      arg[(size_t)n * S + j] = a;
+    }
+  }
+  std::vector<int32_t> out(N + 1);
+  out[N] = L;
+  int j = L;
+  for (int n = N; n >= 2; --n) {
+    j = arg[(size_t)n * S + j];
+    out[n - 1] = j;
+  }
+  out[0] = 0;
+  for (int k = 0; k <= N; ++k) bounds[k] = out[k];
+  if (bottleneck) *bottleneck = best[(size_t)N * S + L];
+  return FTP_OK;
+}
+
+extern "C" int ftp_estimate_capacity(double stage_time, const double* layer_costs, int L, int start, int end,
+                                     double* capacity) {
+  if (!layer_costs || !capacity || start < 0 || end < start || end >= L) {
+    ftp_set_error("estimate_capacity: bad argument");
+    return FTP_ERR_ARG;
+  }
+  if (!(std::isfinite(stage_time) && stage_time > 0.0)) { ftp_set_error("estimate_capacity: bad stage_time"); return FTP_ERR_VALUE; }
+  double s = 0.0;
+  for (int i = start; i <= end; ++i) s += layer_costs[i];
+  if (!(s > 0.0)) { ftp_set_error("estimate_capacity: non-positive cost sum"); return FTP_ERR_VALUE; }
+  *capacity = stage_time / s;
+  return FTP_OK;
+}

@@ -1,0 +1,758 @@
+// Model description, stage object and the C ABI entry points for
+// forward / loss / backward / update / weight stashing / profiling.
+//
+// A stage executes its units as a fixed sequence of kernel launches on the
+// caller's stream.  Every convolution writes its raw output z once; the
+// following BatchNorm is reduced to a per-channel scale/shift that the NEXT
+// kernel applies on load together with the activation ("view"), so activated
+// tensors are never written except at block outputs (where the residual is
+// added) and at the stage boundary.  Backward mirrors this: per convolution a
+// reduction for d(gamma), d(beta), one elementwise pass that forms dz, then
+// weight- and data-gradient kernels.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/ftp.h"
+#include "kernels.h"
+
+using namespace ftp;
+
+// ------------------------------------------------------------------ errors
+static thread_local char g_err[512] = "";
+void ftp_set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+extern "C" const char* ftp_last_error(void) { return g_err; }
+
+#define HIP_TRY(expr)                                                              \
+  do {                                                                             \
+    hipError_t e_ = (expr);                                                        \
+    if (e_ != hipSuccess) {                                                        \
+      ftp_set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+      return FTP_ERR_HIP;                                                          \
+    }                                                                              \
+  } while (0)
+
+static const float kBnEps = 1e-5f, kBnMomentum = 0.1f;
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline int conv_out(int n, int k, int s, int p) { return (n + 2 * p - k) / s + 1; }
+
+// ------------------------------------------------------------------- model
+enum SubType { SUB_DIRECT = 0, SUB_PW = 1, SUB_DW = 2 };
+
+struct Sub {           // convolution + BatchNorm + activation
+  int type;
+  ConvGeom g;          // N filled in per stage
+  int act;
+  size_t w_off, w_n;   // offsets relative to the unit's parameter vector
+  size_t gamma_off, beta_off;
+  size_t bn_off;       // channel offset relative to the unit's BatchNorm channels
+};
+
+struct UnitInfo {
+  ftp_unit_desc d;
+  int inH, inW, inC, outH, outW, outC;
+  std::vector<Sub> subs;
+  bool residual;
+  size_t n_param, n_bn;
+};
+
+struct ftp_model {
+  std::vector<UnitInfo> units;
+  int dtype;
+  int inH, inW, inC;
+};
+
+static int build_unit(const ftp_unit_desc& d, int H, int W, int C, int idx, UnitInfo* u) {
+  u->d = d;
+  u->inH = H; u->inW = W; u->inC = C;
+  u->residual = false;
+  u->n_param = 0; u->n_bn = 0;
+  auto add_sub = [&](int type, int Hin, int Win, int Cin, int Cout, int kh, int kw, int s, int ph, int pw, int act) {
+    Sub sb;
+    sb.type = type;
+    sb.g = ConvGeom{0, Hin, Win, Cin, conv_out(Hin, kh, s, ph), conv_out(Win, kw, s, pw), Cout, kh, kw, s, ph, pw};
+    sb.act = act;
+    sb.w_off = u->n_param;
+    sb.w_n = (size_t)Cout * kh * kw * (type == SUB_DW ? 1 : Cin);
+    sb.gamma_off = sb.w_off + sb.w_n;
+    sb.beta_off = sb.gamma_off + Cout;
+    sb.bn_off = u->n_bn;
+    u->n_param = sb.beta_off + Cout;
+    u->n_bn += Cout;
+    u->subs.push_back(sb);
+    return sb;
+  };
+  switch (d.kind) {
+    case FTP_UNIT_CONV: {
+      if (d.cin != C || d.cout < 8 || d.cout % 8 || d.kh < 1 || d.kw < 1 || d.stride < 1 || d.pad_h < 0 || d.pad_w < 0 ||
+          d.act < 0 || d.act > 2) {
+        ftp_set_error("unit %d (CONV): cin=%d must equal incoming channels %d, cout=%d a multiple of 8", idx, d.cin, C, d.cout);
+        return FTP_ERR_SHAPE;
+      }
+      if (H + 2 * d.pad_h < d.kh || W + 2 * d.pad_w < d.kw) { ftp_set_error("unit %d: kernel larger than padded input", idx); return FTP_ERR_SHAPE; }
+      bool pw = d.kh == 1 && d.kw == 1 && d.stride == 1 && d.pad_h == 0 && d.pad_w == 0 && C % 8 == 0;
+      Sub sb = add_sub(pw ? SUB_PW : SUB_DIRECT, H, W, C, d.cout, d.kh, d.kw, d.stride, d.pad_h, d.pad_w, d.act);
+      if (!pw && !conv_direct_supported(sb.g)) {
+        ftp_set_error("unit %d: dense %dx%d conv with cin*cout=%d > 8192 is not supported", idx, d.kh, d.kw, C * d.cout);
+        return FTP_ERR_UNSUPPORTED;
+      }
+      u->outH = sb.g.Hout; u->outW = sb.g.Wout; u->outC = d.cout;
+      break;
+    }
+    case FTP_UNIT_INVRES: {
+      if (d.cin != C || C % 8 || d.cout < 8 || d.cout % 8 || d.expand < 1 || (d.stride != 1 && d.stride != 2)) {
+        ftp_set_error("unit %d (INVRES): cin=%d must equal incoming channels %d; channels multiples of 8; stride 1 or 2", idx, d.cin, C);
+        return FTP_ERR_SHAPE;
+      }
+      int ce = C * d.expand;
+      if (d.expand != 1) add_sub(SUB_PW, H, W, C, ce, 1, 1, 1, 0, 0, FTP_ACT_RELU6);
+      Sub dw = add_sub(SUB_DW, H, W, ce, ce, 3, 3, d.stride, 1, 1, FTP_ACT_RELU6);
+      add_sub(SUB_PW, dw.g.Hout, dw.g.Wout, ce, d.cout, 1, 1, 1, 0, 0, FTP_ACT_NONE);
+      u->outH = dw.g.Hout; u->outW = dw.g.Wout; u->outC = d.cout;
+      u->residual = d.stride == 1 && d.cin == d.cout;
+      break;
+    }
+    case FTP_UNIT_GAP:
+      if (C % 8) { ftp_set_error("unit %d (GAP): channels must be a multiple of 8", idx); return FTP_ERR_SHAPE; }
+      u->outH = 1; u->outW = 1; u->outC = C;
+      break;
+    case FTP_UNIT_FC:
+      if (H != 1 || W != 1 || d.cin != C || d.cout < 1 || C % 8) {
+        ftp_set_error("unit %d (FC): needs a [batch,1,1,%d] input with cin %% 8 == 0 (got %dx%dx%d)", idx, d.cin, H, W, C);
+        return FTP_ERR_SHAPE;
+      }
+      u->n_param = (size_t)d.cout * C + d.cout;
+      u->outH = 1; u->outW = 1; u->outC = d.cout;
+      break;
+    case FTP_UNIT_LOSS:
+      if (H != 1 || W != 1 || d.cin != C) { ftp_set_error("unit %d (LOSS): needs [batch,1,1,classes] logits", idx); return FTP_ERR_SHAPE; }
+      u->outH = 1; u->outW = 1; u->outC = C;
+      break;
+    default:
+      ftp_set_error("unit %d: unknown kind %d", idx, d.kind);
+      return FTP_ERR_ARG;
+  }
+  if (u->outH < 1 || u->outW < 1) { ftp_set_error("unit %d: empty output", idx); return FTP_ERR_SHAPE; }
+  return FTP_OK;
+}
+
+extern "C" int ftp_model_create(const ftp_unit_desc* units, int L, int in_h, int in_w, int in_c, ftp_dtype act_dtype,
+                                ftp_model** out) {
+  if (!units || !out || L < 1 || in_h < 1 || in_w < 1 || in_c < 1 || (act_dtype != FTP_F32 && act_dtype != FTP_BF16)) {
+    ftp_set_error("model_create: bad argument");
+    return FTP_ERR_ARG;
+  }
+  ftp_model* m = new (std::nothrow) ftp_model();
+  if (!m) { ftp_set_error("model_create: out of host memory"); return FTP_ERR_NOMEM; }
+  m->dtype = (int)act_dtype;
+  m->inH = in_h; m->inW = in_w; m->inC = in_c;
+  int H = in_h, W = in_w, C = in_c;
+  for (int i = 0; i < L; ++i) {
+    UnitInfo u;
+    int rc = build_unit(units[i], H, W, C, i, &u);
+    if (rc != FTP_OK) { delete m; return rc; }
+    if (units[i].kind == FTP_UNIT_LOSS && i + 1 != L) { ftp_set_error("unit %d: LOSS must be the last unit", i); delete m; return FTP_ERR_SHAPE; }
+    if (units[i].kind == FTP_UNIT_LOSS && i > 0 && units[i - 1].kind == FTP_UNIT_CONV) {
+      ftp_set_error("unit %d: LOSS may not directly follow a CONV unit", i); delete m; return FTP_ERR_SHAPE;
+    }
+    H = u.outH; W = u.outW; C = u.outC;
+    m->units.push_back(u);
+  }
+  *out = m;
+  return FTP_OK;
+}
+
+extern "C" void ftp_model_destroy(ftp_model* m) { delete m; }
+extern "C" int ftp_model_num_units(const ftp_model* m) { return m ? (int)m->units.size() : FTP_ERR_ARG; }
+
+extern "C" int ftp_model_unit_in_shape(const ftp_model* m, int u, int* h, int* w, int* c) {
+  if (!m || u < 0 || u > (int)m->units.size() || !h || !w || !c) { ftp_set_error("unit_in_shape: bad argument"); return FTP_ERR_ARG; }
+  if (u == (int)m->units.size()) { const UnitInfo& x = m->units.back(); *h = x.outH; *w = x.outW; *c = x.outC; }
+  else { const UnitInfo& x = m->units[u]; *h = x.inH; *w = x.inW; *c = x.inC; }
+  return FTP_OK;
+}
+extern "C" int ftp_model_unit_param_count(const ftp_model* m, int u, size_t* n) {
+  if (!m || u < 0 || u >= (int)m->units.size() || !n) { ftp_set_error("unit_param_count: bad argument"); return FTP_ERR_ARG; }
+  *n = m->units[u].n_param;
+  return FTP_OK;
+}
+extern "C" int ftp_model_unit_bn_channels(const ftp_model* m, int u, size_t* n) {
+  if (!m || u < 0 || u >= (int)m->units.size() || !n) { ftp_set_error("unit_bn_channels: bad argument"); return FTP_ERR_ARG; }
+  *n = m->units[u].n_bn;
+  return FTP_OK;
+}
+
+// -------------------------------------------------------------------- stage
+struct UnitPlan {
+  const UnitInfo* info;
+  size_t p_off;                    // float offset of the unit's parameters in the flat buffers
+  size_t bn_off;                   // channel offset in the running-stat arrays
+  std::vector<size_t> z_off;       // per sub: byte offset of z in the slot stash
+  std::vector<size_t> st_off;      // per sub: float offset of mean|invstd|scale|shift in the slot stats
+  size_t out_off;                  // byte offset of the materialised unit output (if any)
+  bool out_virtual;                // CONV unit whose output stays a view
+  size_t in_mat_off;               // residual block fed by a view: materialised copy of its input
+  bool need_in_mat;
+};
+
+struct Slot {
+  char* stash = nullptr;
+  float* stats = nullptr;
+  float* snap_w = nullptr;   // fp32 parameter snapshot
+  void* snap_lp = nullptr;   // bfloat16 working-copy snapshot
+  void* dlogits = nullptr;
+  bool busy = false, has_snap = false, has_loss = false;
+};
+
+struct ProfEvents {          // optional per-unit timing (profile_layers)
+  std::vector<hipEvent_t> f0, f1, b0, b1;
+};
+
+struct ftp_stage {
+  const ftp_model* model;
+  int a, b, batch, dt, device;
+  size_t es;
+  std::vector<UnitPlan> plan;
+  size_t n_param = 0, n_bn = 0;
+  float *params = nullptr, *grads = nullptr, *mom = nullptr, *run_mean = nullptr, *run_var = nullptr;
+  void* w_lp = nullptr;
+  size_t stash_bytes = 0, stats_floats = 0, xin_bytes = 0, max_act_bytes = 0;
+  std::vector<Slot> slots;
+  char *gbuf[4] = {nullptr, nullptr, nullptr, nullptr};   // boundary A/B, dz, dA
+  float *bn_part = nullptr, *coef = nullptr, *ws = nullptr, *row_loss = nullptr;
+  size_t ws_floats = 0;
+  int max_c = 0;
+  bool has_loss = false;
+  int classes = 0;
+  ProfEvents* prof = nullptr;
+};
+
+static inline void dfree(void* p) { if (p) (void)hipFree(p); }
+
+static void stage_free(ftp_stage* s) {
+  if (!s) return;
+  dfree(s->params); dfree(s->grads); dfree(s->mom); dfree(s->run_mean); dfree(s->run_var); dfree(s->w_lp);
+  for (auto& sl : s->slots) { dfree(sl.stash); dfree(sl.stats); dfree(sl.snap_w); dfree(sl.snap_lp); dfree(sl.dlogits); }
+  for (int i = 0; i < 4; ++i) dfree(s->gbuf[i]);
+  dfree(s->bn_part); dfree(s->coef); dfree(s->ws); dfree(s->row_loss);
+  delete s;
+}
+
+extern "C" void ftp_stage_destroy(ftp_stage* s) { stage_free(s); }
+
+template <typename P>
+static int dev_alloc(P** p, size_t bytes) {
+  void* q = nullptr;
+  hipError_t e = hipMalloc(&q, align_up(bytes ? bytes : 1, 256));
+  if (e != hipSuccess) { ftp_set_error("hipMalloc(%zu bytes) failed: %s", bytes, hipGetErrorString(e)); return FTP_ERR_NOMEM; }
+  *p = (P*)q;
+  return FTP_OK;
+}
+
+extern "C" int ftp_stage_create(const ftp_model* m, int a, int b, int batch, int n_slots, ftp_stage** out) {
+  if (!m || !out) { ftp_set_error("stage_create: NULL argument"); return FTP_ERR_ARG; }
+  int L = (int)m->units.size();
+  if (a < 0 || a >= b || b > L) { ftp_set_error("stage_create: bad unit range [%d,%d) for %d units", a, b, L); return FTP_ERR_ARG; }
+  if (batch < 1 || n_slots < 1 || n_slots > 64) { ftp_set_error("stage_create: batch >= 1 and 1 <= n_slots <= 64 required"); return FTP_ERR_ARG; }
+  ftp_stage* s = new (std::nothrow) ftp_stage();
+  if (!s) { ftp_set_error("stage_create: out of host memory"); return FTP_ERR_NOMEM; }
+  s->model = m; s->a = a; s->b = b; s->batch = batch; s->dt = m->dtype;
+  s->es = m->dtype == FTP_F32 ? 4 : 2;
+  if (hipGetDevice(&s->device) != hipSuccess) { ftp_set_error("stage_create: no HIP device"); delete s; return FTP_ERR_HIP; }
+
+  size_t stash = 0, stats = 0, max_act = 0, ws_floats = 1024;
+  int max_c = 8;
+  auto act_bytes = [&](int H, int W, int C) { return align_up((size_t)batch * H * W * C * s->es, 256); };
+  const UnitInfo& first = m->units[a];
+  s->xin_bytes = act_bytes(first.inH, first.inW, first.inC);
+  stash += s->xin_bytes;
+  max_act = s->xin_bytes;
+  for (int i = a; i < b; ++i) {
+    const UnitInfo& u = m->units[i];
+    UnitPlan p;
+    p.info = &u;
+    p.p_off = s->n_param; s->n_param += align_up(u.n_param, 8);
+    p.bn_off = s->n_bn; s->n_bn += u.n_bn;
+    for (const Sub& sb : u.subs) {
+      size_t zb = act_bytes(sb.g.Hout, sb.g.Wout, sb.g.Cout);
+      p.z_off.push_back(stash); stash += zb;
+      p.st_off.push_back(stats); stats += (size_t)4 * sb.g.Cout;
+      if (zb > max_act) max_act = zb;
+      size_t ib = act_bytes(sb.g.Hin, sb.g.Win, sb.g.Cin);
+      if (ib > max_act) max_act = ib;
+      if (sb.g.Cout > max_c) max_c = sb.g.Cout;
+      ConvGeom g = sb.g; g.N = batch;
+      size_t M = (size_t)batch * g.Hout * g.Wout;
+      size_t need = sb.type == SUB_DIRECT ? conv_direct_wgrad_ws(g) : sb.type == SUB_DW ? dw_wgrad_ws(g) : pw_wgrad_ws(M, g.Cin, g.Cout);
+      if (need > ws_floats) ws_floats = need;
+    }
+    p.out_virtual = (u.d.kind == FTP_UNIT_CONV);
+    p.out_off = 0;
+    if (!p.out_virtual && u.d.kind != FTP_UNIT_LOSS) {
+      size_t ob = act_bytes(u.outH, u.outW, u.outC);
+      p.out_off = stash; stash += ob;
+      if (ob > max_act) max_act = ob;
+    }
+    p.need_in_mat = u.residual && i > a && m->units[i - 1].d.kind == FTP_UNIT_CONV;
+    p.in_mat_off = 0;
+    if (p.need_in_mat) { p.in_mat_off = stash; stash += act_bytes(u.inH, u.inW, u.inC); }
+    if (u.d.kind == FTP_UNIT_FC) {
+      size_t need = pw_wgrad_ws((size_t)batch, u.inC, u.outC);
+      if (need > ws_floats) ws_floats = need;
+    }
+    if (u.d.kind == FTP_UNIT_LOSS) { s->has_loss = true; s->classes = u.inC; }
+    s->plan.push_back(p);
+  }
+  s->stash_bytes = stash; s->stats_floats = stats; s->max_act_bytes = max_act; s->ws_floats = ws_floats; s->max_c = max_c;
+
+  int rc = FTP_OK;
+  size_t np = s->n_param ? s->n_param : 8;
+  size_t nb = s->n_bn ? s->n_bn : 8;
+  if ((rc = dev_alloc(&s->params, np * 4)) || (rc = dev_alloc(&s->grads, np * 4)) || (rc = dev_alloc(&s->mom, np * 4)) ||
+      (rc = dev_alloc(&s->run_mean, nb * 4)) || (rc = dev_alloc(&s->run_var, nb * 4))) { stage_free(s); return rc; }
+  if (s->dt == FTP_BF16 && (rc = dev_alloc(&s->w_lp, np * 2))) { stage_free(s); return rc; }
+  s->slots.resize(n_slots);
+  for (auto& sl : s->slots) {
+    if ((rc = dev_alloc(&sl.stash, stash)) || (rc = dev_alloc(&sl.stats, (stats ? stats : 8) * 4)) ||
+        (rc = dev_alloc(&sl.snap_w, np * 4))) { stage_free(s); return rc; }
+    if (s->dt == FTP_BF16 && (rc = dev_alloc(&sl.snap_lp, np * 2))) { stage_free(s); return rc; }
+    if (s->has_loss && (rc = dev_alloc(&sl.dlogits, (size_t)batch * s->classes * s->es))) { stage_free(s); return rc; }
+  }
+  for (int i = 0; i < 4; ++i)
+    if ((rc = dev_alloc(&s->gbuf[i], max_act))) { stage_free(s); return rc; }
+  if ((rc = dev_alloc(&s->bn_part, (size_t)kMaxPartials * 2 * max_c * 4)) || (rc = dev_alloc(&s->coef, (size_t)3 * max_c * 4)) ||
+      (rc = dev_alloc(&s->ws, ws_floats * 4)) || (rc = dev_alloc(&s->row_loss, (size_t)batch * 4))) { stage_free(s); return rc; }
+
+  // initial state: zero weights / momentum / gradients, running mean 0, running variance 1
+  std::vector<float> ones(nb, 1.0f);
+  hipError_t e = hipMemset(s->params, 0, np * 4);
+  if (e == hipSuccess) e = hipMemset(s->grads, 0, np * 4);
+  if (e == hipSuccess) e = hipMemset(s->mom, 0, np * 4);
+  if (e == hipSuccess) e = hipMemset(s->run_mean, 0, nb * 4);
+  if (e == hipSuccess) e = hipMemcpy(s->run_var, ones.data(), nb * 4, hipMemcpyHostToDevice);
+  if (e == hipSuccess && s->w_lp) e = hipMemset(s->w_lp, 0, np * 2);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) { ftp_set_error("stage_create: initialisation failed: %s", hipGetErrorString(e)); stage_free(s); return FTP_ERR_HIP; }
+  *out = s;
+  return FTP_OK;
+}
+
+// ---- parameter import / export ------------------------------------------------
+static int unit_check(const ftp_stage* s, int unit, size_t n, size_t expect, const void* p, const char* who) {
+  if (!s || !p) { ftp_set_error("%s: NULL argument", who); return FTP_ERR_ARG; }
+  if (unit < s->a || unit >= s->b) { ftp_set_error("%s: unit %d outside the stage [%d,%d)", who, unit, s->a, s->b); return FTP_ERR_ARG; }
+  if (n != expect) { ftp_set_error("%s: unit %d has %zu values, caller passed %zu", who, unit, expect, n); return FTP_ERR_SHAPE; }
+  return FTP_OK;
+}
+
+extern "C" int ftp_stage_import_weights(ftp_stage* s, int unit, const float* host_w, size_t n) {
+  int rc = unit_check(s, unit, n, s ? (unit >= s->a && unit < s->b ? s->plan[unit - s->a].info->n_param : 0) : 0, host_w, "import_weights");
+  if (rc) return rc;
+  if (n == 0) return FTP_OK;
+  const UnitPlan& p = s->plan[unit - s->a];
+  HIP_TRY(hipMemcpy(s->params + p.p_off, host_w, n * 4, hipMemcpyHostToDevice));
+  if (s->w_lp) {
+    f32_to_storage(FTP_BF16, nullptr, s->params + p.p_off, (char*)s->w_lp + p.p_off * 2, n);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipDeviceSynchronize());
+  }
+  return FTP_OK;
+}
+
+static int export_from(const ftp_stage* s, const float* base, int unit, float* host, size_t n, const char* who) {
+  int rc = unit_check(s, unit, n, s ? (unit >= s->a && unit < s->b ? s->plan[unit - s->a].info->n_param : 0) : 0, host, who);
+  if (rc) return rc;
+  if (n == 0) return FTP_OK;
+  HIP_TRY(hipDeviceSynchronize());
+  HIP_TRY(hipMemcpy(host, base + s->plan[unit - s->a].p_off, n * 4, hipMemcpyDeviceToHost));
+  return FTP_OK;
+}
+extern "C" int ftp_stage_export_weights(const ftp_stage* s, int unit, float* h, size_t n) { return export_from(s, s ? s->params : nullptr, unit, h, n, "export_weights"); }
+extern "C" int ftp_stage_export_grads(const ftp_stage* s, int unit, float* h, size_t n) { return export_from(s, s ? s->grads : nullptr, unit, h, n, "export_grads"); }
+extern "C" int ftp_stage_export_momentum(const ftp_stage* s, int unit, float* h, size_t n) { return export_from(s, s ? s->mom : nullptr, unit, h, n, "export_momentum"); }
+
+extern "C" int ftp_stage_export_bn_stats(const ftp_stage* s, int unit, float* host, size_t n) {
+  int rc = unit_check(s, unit, n, s ? (unit >= s->a && unit < s->b ? 2 * s->plan[unit - s->a].info->n_bn : 0) : 0, host, "export_bn_stats");
+  if (rc) return rc;
+  if (n == 0) return FTP_OK;
+  const UnitPlan& p = s->plan[unit - s->a];
+  HIP_TRY(hipDeviceSynchronize());
+  // per BatchNorm: running_mean then running_var
+  size_t o = 0;
+  for (const Sub& sb : p.info->subs) {
+    size_t C = sb.g.Cout;
+    HIP_TRY(hipMemcpy(host + o, s->run_mean + p.bn_off + sb.bn_off, C * 4, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(host + o + C, s->run_var + p.bn_off + sb.bn_off, C * 4, hipMemcpyDeviceToHost));
+    o += 2 * C;
+  }
+  return FTP_OK;
+}
+
+// ---- helpers for the compute calls ------------------------------------------------
+struct WeightSet { const float* w32; const char* lp; };
+
+static inline const void* conv_w(const ftp_stage* s, const WeightSet& ws, size_t off) {
+  return s->dt == FTP_F32 ? (const void*)(ws.w32 + off) : (const void*)(ws.lp + off * 2);
+}
+
+static int check_call(ftp_stage* s, int slot, const char* who) {
+  if (!s) { ftp_set_error("%s: NULL stage", who); return FTP_ERR_ARG; }
+  if (slot < 0 || slot >= (int)s->slots.size()) { ftp_set_error("%s: slot %d out of range (n_slots=%zu)", who, slot, s->slots.size()); return FTP_ERR_ARG; }
+  return FTP_OK;
+}
+
+static HView plain(const void* p) { return HView{p, nullptr, nullptr, 0}; }
+
+// Input view of every unit and of every convolution inside it, from the slot's buffers.
+struct Views {
+  std::vector<HView> unit_in;                 // per unit
+  std::vector<std::vector<HView>> sub_out;    // per unit, per sub
+};
+
+static void build_views(const ftp_stage* s, const Slot& sl, Views* v) {
+  HView cur = plain(sl.stash);                // stashed stage input at offset 0
+  size_t n = s->plan.size();
+  v->unit_in.resize(n);
+  v->sub_out.resize(n);
+  for (size_t i = 0; i < n; ++i) {
+    const UnitPlan& p = s->plan[i];
+    if (p.need_in_mat) cur = plain(sl.stash + p.in_mat_off);
+    v->unit_in[i] = cur;
+    for (size_t k = 0; k < p.info->subs.size(); ++k) {
+      const Sub& sb = p.info->subs[k];
+      float* st = sl.stats + p.st_off[k];
+      v->sub_out[i].push_back(HView{sl.stash + p.z_off[k], st + 2 * sb.g.Cout, st + 3 * sb.g.Cout, sb.act});
+    }
+    if (p.out_virtual) cur = v->sub_out[i].back();
+    else if (p.info->d.kind != FTP_UNIT_LOSS) cur = plain(sl.stash + p.out_off);
+  }
+}
+
+static void sub_forward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, HView in, const WeightSet& W, hipStream_t st) {
+  const Sub& sb = p.info->subs[k];
+  ConvGeom g = sb.g; g.N = s->batch;
+  void* z = sl.stash + p.z_off[k];
+  const void* w = conv_w(s, W, p.p_off + sb.w_off);
+  size_t M = (size_t)s->batch * g.Hout * g.Wout;
+  if (sb.type == SUB_DIRECT) conv_direct_fwd(s->dt, st, in, w, g, z);
+  else if (sb.type == SUB_PW) pw_fwd(s->dt, st, in, w, nullptr, M, g.Cin, g.Cout, z);
+  else dw_fwd(s->dt, st, in, w, g, z);
+  int P = 0;
+  bn_stats(s->dt, st, z, M, g.Cout, s->bn_part, &P);
+  float* stt = sl.stats + p.st_off[k];
+  int C = g.Cout;
+  bn_finalize(st, s->bn_part, P, M, C, W.w32 + p.p_off + sb.gamma_off, W.w32 + p.p_off + sb.beta_off, stt, stt + C,
+              stt + 2 * C, stt + 3 * C, s->run_mean + p.bn_off + sb.bn_off, s->run_var + p.bn_off + sb.bn_off, kBnEps, kBnMomentum);
+}
+
+extern "C" int ftp_stage_forward(ftp_stage* s, int slot, const void* x_dev, void* y_dev, void* stream) {
+  int rc = check_call(s, slot, "stage_forward");
+  if (rc) return rc;
+  if (!x_dev) { ftp_set_error("stage_forward: x_dev is NULL"); return FTP_ERR_ARG; }
+  Slot& sl = s->slots[slot];
+  if (sl.busy) { ftp_set_error("stage_forward: slot %d is busy (its backward has not run)", slot); return FTP_ERR_SLOT; }
+  hipStream_t st = (hipStream_t)stream;
+  const UnitInfo& first = *s->plan[0].info;
+  size_t xin = (size_t)s->batch * first.inH * first.inW * first.inC * s->es;
+  HIP_TRY(hipMemcpyAsync(sl.stash, x_dev, xin, hipMemcpyDeviceToDevice, st));
+  Views v;
+  build_views(s, sl, &v);
+  WeightSet W{s->params, (const char*)s->w_lp};
+  for (size_t i = 0; i < s->plan.size(); ++i) {
+    const UnitPlan& p = s->plan[i];
+    const UnitInfo& u = *p.info;
+    if (s->prof) HIP_TRY(hipEventRecord(s->prof->f0[i], st));
+    if (p.need_in_mat) {
+      // the previous CONV unit's output, materialised so the residual can read it
+      HView prev = v.sub_out[i - 1].back();
+      bn_apply(s->dt, st, prev, (size_t)s->batch * u.inH * u.inW, u.inC, nullptr, sl.stash + p.in_mat_off);
+    }
+    HView in = v.unit_in[i];
+    switch (u.d.kind) {
+      case FTP_UNIT_CONV:
+        sub_forward(s, sl, p, 0, in, W, st);
+        break;
+      case FTP_UNIT_INVRES: {
+        HView h = in;
+        for (size_t k = 0; k < u.subs.size(); ++k) { sub_forward(s, sl, p, k, h, W, st); h = v.sub_out[i][k]; }
+        bn_apply(s->dt, st, h, (size_t)s->batch * u.outH * u.outW, u.outC, u.residual ? in.z : nullptr, sl.stash + p.out_off);
+        break;
+      }
+      case FTP_UNIT_GAP:
+        gap_fwd(s->dt, st, in, s->batch, u.inH * u.inW, u.inC, sl.stash + p.out_off);
+        break;
+      case FTP_UNIT_FC:
+        pw_fwd(s->dt, st, in, conv_w(s, W, p.p_off), s->params + p.p_off + (size_t)u.outC * u.inC, (size_t)s->batch, u.inC,
+               u.outC, sl.stash + p.out_off);
+        break;
+      default:
+        break;  // LOSS: evaluated by ftp_stage_loss
+    }
+    if (s->prof) HIP_TRY(hipEventRecord(s->prof->f1[i], st));
+  }
+  if (y_dev) {
+    size_t li = s->plan.size() - 1;
+    const UnitPlan& p = s->plan[li];
+    const UnitInfo& u = *p.info;
+    size_t M = (size_t)s->batch * u.outH * u.outW;
+    if (p.out_virtual) {
+      bn_apply(s->dt, st, v.sub_out[li].back(), M, u.outC, nullptr, y_dev);
+    } else {
+      const void* src = u.d.kind == FTP_UNIT_LOSS ? v.unit_in[li].z : (const void*)(sl.stash + p.out_off);
+      HIP_TRY(hipMemcpyAsync(y_dev, src, M * u.outC * s->es, hipMemcpyDeviceToDevice, st));
+    }
+  }
+  HIP_TRY(hipGetLastError());
+  sl.busy = true; sl.has_snap = false; sl.has_loss = false;
+  return FTP_OK;
+}
+
+extern "C" int ftp_stage_loss(ftp_stage* s, int slot, const int32_t* labels_dev, float* loss_dev, void* stream) {
+  int rc = check_call(s, slot, "stage_loss");
+  if (rc) return rc;
+  if (!s->has_loss) { ftp_set_error("stage_loss: the stage does not end with the LOSS unit"); return FTP_ERR_ARG; }
+  if (!labels_dev || !loss_dev) { ftp_set_error("stage_loss: NULL argument"); return FTP_ERR_ARG; }
+  Slot& sl = s->slots[slot];
+  if (!sl.busy) { ftp_set_error("stage_loss: slot %d holds no forwarded batch", slot); return FTP_ERR_SLOT; }
+  hipStream_t st = (hipStream_t)stream;
+  Views v;
+  build_views(s, sl, &v);
+  size_t li = s->plan.size() - 1;
+  if (s->prof) HIP_TRY(hipEventRecord(s->prof->f0[li], st));
+  softmax_ce(s->dt, st, v.unit_in[li].z, labels_dev, s->batch, s->classes, s->row_loss, sl.dlogits, loss_dev);
+  if (s->prof) HIP_TRY(hipEventRecord(s->prof->f1[li], st));
+  HIP_TRY(hipGetLastError());
+  sl.has_loss = true;
+  return FTP_OK;
+}
+
+extern "C" int ftp_stage_snapshot_weights(ftp_stage* s, int slot, void* stream) {
+  int rc = check_call(s, slot, "stage_snapshot_weights");
+  if (rc) return rc;
+  Slot& sl = s->slots[slot];
+  if (!sl.busy) { ftp_set_error("stage_snapshot_weights: slot %d holds no forwarded batch", slot); return FTP_ERR_SLOT; }
+  hipStream_t st = (hipStream_t)stream;
+  if (s->n_param) {
+    HIP_TRY(hipMemcpyAsync(sl.snap_w, s->params, s->n_param * 4, hipMemcpyDeviceToDevice, st));
+    if (s->w_lp) HIP_TRY(hipMemcpyAsync(sl.snap_lp, s->w_lp, s->n_param * 2, hipMemcpyDeviceToDevice, st));
+  }
+  sl.has_snap = true;
+  return FTP_OK;
+}
+
+// Backward of one convolution+BN+act: dA is the gradient of the activated output.
+// Writes dz into s->gbuf[2]; accumulates weight / gamma / beta gradients; when dIn is
+// non-NULL writes the gradient of the (activated) input there (+ res for pointwise).
+static void sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, const void* dA, HView in, HView out,
+                         void* dIn, const void* res, const WeightSet& W, hipStream_t st) {
+  const Sub& sb = p.info->subs[k];
+  ConvGeom g = sb.g; g.N = s->batch;
+  int C = g.Cout;
+  size_t M = (size_t)s->batch * g.Hout * g.Wout;
+  float* stt = sl.stats + p.st_off[k];
+  void* dz = s->gbuf[2];
+  int P = 0;
+  bn_bwd_reduce(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->bn_part, &P);
+  bn_bwd_finalize(st, s->bn_part, P, M, C, W.w32 + p.p_off + sb.gamma_off, stt, stt + C, s->grads + p.p_off + sb.gamma_off,
+                  s->grads + p.p_off + sb.beta_off, s->coef);
+  bn_bwd_apply(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->coef, dz);
+  const void* w = conv_w(s, W, p.p_off + sb.w_off);
+  float* gw = s->grads + p.p_off + sb.w_off;
+  if (sb.type == SUB_DIRECT) {
+    conv_direct_wgrad(s->dt, st, dz, in, g, s->ws, gw);
+    if (dIn) conv_direct_dgrad(s->dt, st, dz, w, g, dIn);
+  } else if (sb.type == SUB_PW) {
+    pw_wgrad(s->dt, st, dz, in, M, g.Cin, g.Cout, s->ws, gw);
+    if (dIn) pw_dgrad(s->dt, st, dz, w, res, M, g.Cin, g.Cout, dIn);
+  } else {
+    dw_wgrad(s->dt, st, dz, in, g, s->ws, gw);
+    if (dIn) dw_dgrad(s->dt, st, dz, w, g, dIn);
+  }
+}
+
+extern "C" int ftp_stage_backward(ftp_stage* s, int slot, const void* dy_dev, void* dx_dev, void* stream) {
+  int rc = check_call(s, slot, "stage_backward");
+  if (rc) return rc;
+  Slot& sl = s->slots[slot];
+  if (!sl.busy) { ftp_set_error("stage_backward: slot %d holds no forwarded batch", slot); return FTP_ERR_SLOT; }
+  if (!dy_dev && !(s->has_loss && sl.has_loss)) {
+    ftp_set_error("stage_backward: dy_dev is NULL and ftp_stage_loss has not seeded slot %d", slot);
+    return FTP_ERR_ARG;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  Views v;
+  build_views(s, sl, &v);
+  WeightSet W{sl.has_snap ? sl.snap_w : s->params, (const char*)(sl.has_snap ? sl.snap_lp : s->w_lp)};
+  const void* d = dy_dev ? dy_dev : sl.dlogits;     // gradient of the current unit's output (read only)
+  int flip = 0;
+  for (int i = (int)s->plan.size() - 1; i >= 0; --i) {
+    const UnitPlan& p = s->plan[i];
+    const UnitInfo& u = *p.info;
+    if (s->prof) HIP_TRY(hipEventRecord(s->prof->b0[i], st));
+    // where the gradient of this unit's input goes: the boundary buffer that does not hold d
+    void* next = i > 0 ? (void*)s->gbuf[flip] : dx_dev;
+    bool produced = true;
+    HView in = v.unit_in[i];
+    switch (u.d.kind) {
+      case FTP_UNIT_LOSS:
+        produced = false;   // the logits gradient passes through unchanged
+        if (i == 0 && dx_dev) HIP_TRY(hipMemcpyAsync(dx_dev, d, (size_t)s->batch * u.inC * s->es, hipMemcpyDeviceToDevice, st));
+        break;
+      case FTP_UNIT_FC: {
+        size_t woff = p.p_off;
+        pw_wgrad(s->dt, st, d, in, (size_t)s->batch, u.inC, u.outC, s->ws, s->grads + woff);
+        bias_grad(s->dt, st, d, s->batch, u.outC, s->grads + woff + (size_t)u.outC * u.inC);
+        if (next) pw_dgrad(s->dt, st, d, conv_w(s, W, woff), nullptr, (size_t)s->batch, u.inC, u.outC, next);
+        break;
+      }
+      case FTP_UNIT_GAP:
+        if (next) gap_bwd(s->dt, st, d, s->batch, u.inH * u.inW, u.inC, next);
+        break;
+      case FTP_UNIT_CONV:
+        sub_backward(s, sl, p, 0, d, in, v.sub_out[i][0], next, nullptr, W, st);
+        break;
+      case FTP_UNIT_INVRES: {
+        size_t ns = u.subs.size();
+        void* tmp = s->gbuf[3];
+        // project: gradient of the activated depthwise output
+        sub_backward(s, sl, p, ns - 1, d, v.sub_out[i][ns - 2], v.sub_out[i][ns - 1], tmp, nullptr, W, st);
+        if (ns == 3) {
+          sub_backward(s, sl, p, 1, tmp, v.sub_out[i][0], v.sub_out[i][1], tmp, nullptr, W, st);
+          sub_backward(s, sl, p, 0, tmp, in, v.sub_out[i][0], next, u.residual ? d : nullptr, W, st);
+        } else {
+          if (next && u.residual) {
+            sub_backward(s, sl, p, 0, tmp, in, v.sub_out[i][0], tmp, nullptr, W, st);
+            bn_apply(s->dt, st, plain(tmp), (size_t)s->batch * u.inH * u.inW, u.inC, d, next);
+          } else {
+            sub_backward(s, sl, p, 0, tmp, in, v.sub_out[i][0], next, nullptr, W, st);
+          }
+        }
+        break;
+      }
+      default:
+        break;
+    }
+    if (s->prof) HIP_TRY(hipEventRecord(s->prof->b1[i], st));
+    if (produced && next) { d = next; if (i > 0) flip ^= 1; }
+  }
+  HIP_TRY(hipGetLastError());
+  sl.busy = false; sl.has_snap = false; sl.has_loss = false;
+  return FTP_OK;
+}
+
+extern "C" int ftp_stage_update(ftp_stage* s, const ftp_sgd* opt, void* stream) {
+  if (!s || !opt) { ftp_set_error("stage_update: NULL argument"); return FTP_ERR_ARG; }
+  if (!(std::isfinite(opt->lr) && std::isfinite(opt->momentum) && std::isfinite(opt->weight_decay))) {
+    ftp_set_error("stage_update: non-finite hyper-parameter");
+    return FTP_ERR_VALUE;
+  }
+  if (s->n_param) sgd_update((hipStream_t)stream, s->params, s->grads, s->mom, s->w_lp, s->n_param, opt->lr, opt->momentum, opt->weight_decay);
+  HIP_TRY(hipGetLastError());
+  return FTP_OK;
+}
+
+// ------------------------------------------------------------ profile_layers
+__global__ void synth_fill_k(float* p, size_t n, uint32_t salt, float amp) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+    uint32_t h = (uint32_t)i * 2654435761u + salt;
+    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13; h *= 3266489917u; h ^= h >> 16;
+    p[i] = ((float)(h >> 8) * (1.0f / 8388608.0f) - 1.0f) * amp;
+  }
+}
+
+extern "C" int ftp_profile_layers(const ftp_model* m, int batch, int reps, double* t_ns, int64_t* out_bytes, void* stream) {
+  if (!m || !t_ns || !out_bytes || batch < 1 || reps < 1) { ftp_set_error("profile_layers: bad argument"); return FTP_ERR_ARG; }
+  int L = (int)m->units.size();
+  ftp_stage* s = nullptr;
+  int rc = ftp_stage_create(m, 0, L, batch, 1, &s);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  ProfEvents ev;
+  float *x32 = nullptr, *loss = nullptr;
+  void *x = nullptr, *dy = nullptr;
+  int32_t* labels = nullptr;
+  const UnitInfo& last = m->units[L - 1];
+  size_t n_in = (size_t)batch * m->inH * m->inW * m->inC;
+  size_t n_out = (size_t)batch * last.outH * last.outW * last.outC;
+  size_t es = s->es;
+  auto cleanup = [&]() {
+    for (auto* vec : {&ev.f0, &ev.f1, &ev.b0, &ev.b1})
+      for (hipEvent_t e : *vec) (void)hipEventDestroy(e);
+    dfree(x32); dfree(x); dfree(dy); dfree(labels); dfree(loss);
+    s->prof = nullptr;
+    stage_free(s);
+  };
+#define PROF_TRY(expr)                                                                   \
+  do {                                                                                   \
+    hipError_t e_ = (expr);                                                              \
+    if (e_ != hipSuccess) {                                                              \
+      ftp_set_error("profile_layers: %s failed: %s", #expr, hipGetErrorString(e_));     \
+      cleanup();                                                                         \
+      return FTP_ERR_HIP;                                                                \
+    }                                                                                    \
+  } while (0)
+  size_t nmax = n_in > n_out ? n_in : n_out;
+  PROF_TRY(hipMalloc((void**)&x32, align_up(nmax * 4, 256)));
+  PROF_TRY(hipMalloc(&x, align_up(n_in * es, 256)));
+  PROF_TRY(hipMalloc(&dy, align_up(n_out * es, 256)));
+  PROF_TRY(hipMalloc((void**)&labels, align_up((size_t)batch * 4, 256)));
+  PROF_TRY(hipMalloc((void**)&loss, 256));
+  // synthetic weights (uniform, variance 2/fan_in-like scale is irrelevant for timing), input and output gradient
+  hipLaunchKernelGGL(synth_fill_k, dim3(1024), dim3(256), 0, st, s->params, s->n_param, 17u, 0.1f);
+  if (s->w_lp) f32_to_storage(FTP_BF16, st, s->params, s->w_lp, s->n_param);
+  hipLaunchKernelGGL(synth_fill_k, dim3(1024), dim3(256), 0, st, x32, n_in, 29u, 1.7f);
+  f32_to_storage(s->dt, st, x32, x, n_in);
+  hipLaunchKernelGGL(synth_fill_k, dim3(1024), dim3(256), 0, st, x32, n_out, 31u, 0.01f);
+  f32_to_storage(s->dt, st, x32, dy, n_out);
+  fill_zero(st, labels, align_up((size_t)batch * 4, 256));
+  // gamma = 1 so that activations keep a sane scale
+  for (const UnitPlan& p : s->plan)
+    for (const Sub& sb : p.info->subs) {
+      std::vector<float> ones(sb.g.Cout, 1.0f);
+      PROF_TRY(hipMemcpyAsync(s->params + p.p_off + sb.gamma_off, ones.data(), ones.size() * 4, hipMemcpyHostToDevice, st));
+      PROF_TRY(hipStreamSynchronize(st));
+    }
+  for (auto* vec : {&ev.f0, &ev.f1, &ev.b0, &ev.b1}) {
+    vec->resize(L);
+    for (int i = 0; i < L; ++i) PROF_TRY(hipEventCreate(&(*vec)[i]));
+  }
+  std::vector<double> acc(L, 0.0);
+  bool has_loss = s->has_loss;
+  for (int r = 0; r < reps + 2; ++r) {
+    s->prof = &ev;
+    rc = ftp_stage_forward(s, 0, x, nullptr, st);
+    if (!rc && has_loss) rc = ftp_stage_loss(s, 0, labels, loss, st);
+    if (!rc) rc = ftp_stage_backward(s, 0, has_loss ? nullptr : dy, nullptr, st);
+    s->prof = nullptr;
+    if (rc) { cleanup(); return rc; }
+    PROF_TRY(hipStreamSynchronize(st));
+    if (r < 2) continue;   // discarded warm-up runs
+    for (int i = 0; i < L; ++i) {
+      float f = 0.f, b = 0.f;
+      PROF_TRY(hipEventElapsedTime(&f, ev.f0[i], ev.f1[i]));
+      PROF_TRY(hipEventElapsedTime(&b, ev.b0[i], ev.b1[i]));
+      acc[i] += ((double)f + (double)b) * 1e6;
+    }
+  }
+  for (int i = 0; i < L; ++i) {
+    double t = std::floor(acc[i] / reps + 0.5);
+    t_ns[i] = t < 1.0 ? 1.0 : t;
+    const UnitInfo& u = m->units[i];
+    out_bytes[i] = (int64_t)((size_t)batch * u.outH * u.outW * u.outC * es);
+  }
+  cleanup();
+#undef PROF_TRY
+  return FTP_OK;
+}

@@ -1,0 +1,224 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, on
+the same seeded inputs, through the C ABI.  Tolerances: relative 1e-4 (fp32),
+2e-2 (bf16) on activations, gradients and updated weights, measured per tensor
+as max-abs error / max-abs reference AND relative L2 error."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import layers as L
+from oracle import models as OM
+from oracle.partition import solve_partition as oracle_solve
+from oracle.stage import one_f_one_b_order
+from harness import Pair, TOL, assert_close, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def hip_models():
+    import paper_2110_02781_amd as P
+    return P.models
+
+
+def conv_unit(cin, cout, kh, kw, stride, ph, pw, act):
+    import paper_2110_02781_amd.binding as B
+    return (OM.Unit('conv', cin, cout, kh, kw, stride, ph, pw, act=act),
+            dict(kind=B.UNIT_CONV, cin=cin, cout=cout, kh=kh, kw=kw, stride=stride, pad_h=ph, pad_w=pw, act=act))
+
+
+def invres_unit(cin, cout, stride, expand):
+    import paper_2110_02781_amd.binding as B
+    return (OM.Unit('invres', cin, cout, 3, 3, stride, 1, 1, expand=expand, act=L.ACT_RELU6),
+            dict(kind=B.UNIT_INVRES, cin=cin, cout=cout, stride=stride, expand=expand))
+
+
+def train_step_check(pair, seed, classes, tol, steps=2, lr=0.01, mu=0.9, wd=4e-5, want_dx=True):
+    """fwd + loss + bwd + update, `steps` times, everything compared."""
+    for step in range(steps):
+        x = synth.normal(seed, f"x{step}", (pair.batch,) + tuple(pair.in_shape))
+        labels = synth.labels(seed, f"labels{step}", pair.batch, classes)
+        y, yo = pair.forward(0, x)
+        assert_close(y, yo, tol, f"step {step} logits")
+        lh, lo = pair.loss(0, labels)
+        assert abs(lh - lo) <= tol * max(1.0, abs(lo)), (lh, lo)
+        dx, dxo = pair.backward(0, None, want_dx=want_dx)
+        if want_dx:
+            assert_close(dx, dxo, tol, f"step {step} dx")
+        pair.compare_unit_vectors("grads", tol, floor=1e-7)
+        pair.compare_unit_vectors("bn", tol)
+        pair.update(lr, mu, wd)
+        pair.compare_unit_vectors("weights", tol)
+        pair.compare_unit_vectors("momentum", tol, floor=1e-7)
+
+
+# ------------------------------------------------------------------ single units
+SINGLE = [
+    ("stem_s1", conv_unit(3, 32, 3, 3, 1, 1, 1, L.ACT_RELU6), (13, 11, 3), 5),
+    ("stem_s2", conv_unit(3, 48, 3, 3, 2, 1, 1, L.ACT_RELU6), (15, 18, 3), 3),
+    ("conv1d", conv_unit(16, 32, 1, 5, 1, 0, 2, L.ACT_RELU), (1, 37, 16), 4),
+    ("conv1d_cin9", conv_unit(9, 32, 1, 5, 1, 0, 2, L.ACT_RELU), (1, 50, 9), 4),
+    ("pw_head", conv_unit(40, 72, 1, 1, 1, 0, 0, L.ACT_RELU6), (5, 7, 40), 6),
+    ("invres_t6_s1_res", invres_unit(16, 16, 1, 6), (9, 7, 16), 5),
+    ("invres_t6_s2", invres_unit(16, 24, 2, 6), (9, 7, 16), 5),
+    ("invres_t1", invres_unit(32, 16, 1, 1), (6, 6, 32), 4),
+    ("invres_t1_res", invres_unit(16, 16, 1, 1), (6, 5, 16), 4),
+    ("invres_wide", invres_unit(88, 136, 2, 6), (7, 7, 88), 3),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("name,unit,in_shape,batch", SINGLE, ids=[s[0] for s in SINGLE])
+def test_single_unit_forward_backward(name, unit, in_shape, batch, dtype):
+    print(f"case {name} {dtype} in_shape={in_shape} batch={batch}", flush=True)
+    tol = TOL[dtype]
+    pair = Pair([unit[0]], [unit[1]], in_shape, batch, 0, 1, dtype, seed=3)
+    try:
+        x = synth.normal(11, "x", (batch,) + tuple(in_shape))
+        y, yo = pair.forward(0, x)
+        assert_close(y, yo, tol, "y")
+        dy = synth.normal(11, "dy", yo.shape)
+        dx, dxo = pair.backward(0, dy)
+        assert_close(dx, dxo, tol, "dx")
+        pair.compare_unit_vectors("grads", tol, floor=1e-6)
+        pair.compare_unit_vectors("bn", tol)
+        pair.update(0.05, 0.9, 4e-5)
+        pair.compare_unit_vectors("weights", tol)
+    finally:
+        pair.close()
+
+
+# ---------------------------------------------------------------------- config 1
+def test_config1_cnn1d_train_steps():
+    print("config 1: cnn1d batch 8 fp32", flush=True)
+    pair = Pair(OM.cnn1d(), hip_models().cnn1d_units(), (1, 128, 9), 8, 0, 6, "f32", seed=1)
+    try:
+        train_step_check(pair, 1, 6, TOL["f32"], steps=3, wd=0.0)
+    finally:
+        pair.close()
+
+
+def small_net():
+    us = [conv_unit(3, 8, 3, 3, 1, 1, 1, L.ACT_RELU6), invres_unit(8, 8, 1, 1), invres_unit(8, 16, 2, 6),
+          invres_unit(16, 16, 1, 6), invres_unit(16, 24, 1, 6), conv_unit(24, 32, 1, 1, 1, 0, 0, L.ACT_RELU6)]
+    import paper_2110_02781_amd.binding as B
+    o = [u[0] for u in us] + [OM.Unit('gap', 32, 32), OM.Unit('fc', 32, 10), OM.Unit('loss', 10, 10)]
+    h = [u[1] for u in us] + [dict(kind=B.UNIT_GAP, cin=32, cout=32), dict(kind=B.UNIT_FC, cin=32, cout=10),
+                              dict(kind=B.UNIT_LOSS, cin=10, cout=10)]
+    return o, h
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_small_net_ragged_shapes(dtype):
+    print(f"small net 9x11 batch 5 {dtype}", flush=True)
+    o, h = small_net()
+    pair = Pair(o, h, (9, 11, 3), 5, 0, len(o), dtype, seed=2)
+    try:
+        train_step_check(pair, 2, 10, TOL[dtype], steps=2)
+    finally:
+        pair.close()
+
+
+# ---------------------------------------------------------------------- config 2
+def test_config2_mobilenetv2_32_train_step():
+    print("config 2: MobileNetV2 w1.0 32x32 batch 32 fp32", flush=True)
+    pair = Pair(OM.mobilenet_v2(1.0, 10, 1), hip_models().mobilenet_v2_units(1.0, 10, 1), (32, 32, 3), 32, 0, 22,
+                "f32", seed=4)
+    try:
+        train_step_check(pair, 4, 10, TOL["f32"], steps=2, want_dx=False)
+    finally:
+        pair.close()
+
+
+# ---------------------------------------------------------------------- config 3
+def test_config3_heaviest_stage_one_f_one_b_with_stashing():
+    import paper_2110_02781_amd as P
+    print("config 3: 3-way split, heaviest stage, 4 micro-batches 1F1B", flush=True)
+    o_units, h_units = OM.mobilenet_v2(1.0, 10, 1), P.models.mobilenet_v2_units(1.0, 10, 1)
+    model = P.model_create(h_units, 32, 32, 3, P.F32)
+    costs, _ = P.profile_layers(model, 32, 10)
+    P.model_destroy(model)
+    caps = [1.0, 3.0, 10.0]
+    bounds, bott = P.solve_partition(costs, caps)
+    ob, obott = oracle_solve(list(costs), caps)
+    assert list(bounds) == ob and bott == obott
+    loads = [costs[bounds[k]:bounds[k + 1]].sum() for k in range(3)]
+    k = int(np.argmax(loads))
+    a, b = int(bounds[k]), int(bounds[k + 1])
+    print(f"bounds {list(bounds)} heaviest stage {k} = units [{a},{b})", flush=True)
+    tol = TOL["f32"]
+    pair = Pair(o_units, h_units, (32, 32, 3), 32, a, b, "f32", n_slots=3, seed=6)
+    try:
+        nb = 4
+        xs = [synth.normal(6, f"x{i}", (32,) + tuple(pair.in_shape)) for i in range(nb)]
+        dys = [synth.normal(6, f"dy{i}", (32,) + tuple(pair.out_shape), std=1.0 / 32) for i in range(nb)]
+        labels = [synth.labels(6, f"l{i}", 32, 10) for i in range(nb)]
+        last = (b == 22)
+        for op, i in one_f_one_b_order(k, 3, nb):
+            if op == 'F':
+                y, yo = pair.forward(i % 3, xs[i], snapshot=True)
+                assert_close(y, yo, tol, f"F{i} y")
+                if last:
+                    pair.loss(i % 3, labels[i])
+            else:
+                dx, dxo = pair.backward(i % 3, None if last else dys[i], want_dx=(a > 0))
+                if a > 0:
+                    assert_close(dx, dxo, tol, f"B{i} dx")
+                pair.compare_unit_vectors("grads", tol, floor=1e-7)
+                pair.update(0.01, 0.9, 4e-5)
+                pair.compare_unit_vectors("weights", tol)
+        pair.compare_unit_vectors("bn", tol)
+        pair.compare_unit_vectors("momentum", tol, floor=1e-7)
+    finally:
+        pair.close()
+
+
+def test_weight_stashing_matters_on_gpu():
+    """Without the snapshot the backward uses the newer weights: results must differ from the stashed run."""
+    o, h = small_net()
+    res = []
+    for snap in (True, False):
+        pair = Pair(o, h, (8, 8, 3), 4, 0, 5, "f32", n_slots=2, seed=8)
+        try:
+            x0, x1 = synth.normal(8, "x0", (4, 8, 8, 3)), synth.normal(8, "x1", (4, 8, 8, 3))
+            dy = synth.normal(8, "dy", (4,) + tuple(pair.out_shape))
+            pair.forward(0, x0, snapshot=snap)
+            pair.forward(1, x1, snapshot=snap)
+            pair.backward(0, dy, want_dx=False)
+            pair.update(0.1, 0.9, 0.0)
+            pair.backward(1, dy, want_dx=False)
+            e = pair.compare_unit_vectors("grads", TOL["f32"], floor=1e-7)
+            import paper_2110_02781_amd as P
+            res.append(P.stage_export_grads(pair.stage, 2, P.model_unit_param_count(pair.model, 2)))
+        finally:
+            pair.close()
+    assert np.abs(res[0] - res[1]).max() > 1e-6
+
+
+# ------------------------------------------------------------------------ solver
+def test_solver_bit_exact_on_1000_capacity_vectors():
+    import paper_2110_02781_amd as P
+    costs = synth.integers(5, "costs", (22,), 1000, 5000000)
+    for t in range(1000):
+        caps = synth.uniform(5, f"caps{t}", (4,), 1.0, 10.0)
+        b, bott = P.solve_partition(costs, caps)
+        ob, obott = oracle_solve(list(costs), list(caps))
+        assert list(b) == ob and bott == obott, t
+    D = synth.integers(5, "D", (22,), 1000, 9000000)
+    for t in range(200):
+        caps = synth.uniform(6, f"caps{t}", (3,), 1.0, 10.0)
+        bw = synth.uniform(6, f"bw{t}", (2,), 0.1, 20.0)
+        b, bott = P.solve_partition(costs, caps, D, bw)
+        ob, obott = oracle_solve(list(costs), list(caps), list(D), list(bw))
+        assert list(b) == ob and bott == obott, t
+
+
+def test_config1_solver_on_six_units():
+    import paper_2110_02781_amd as P
+    model = P.model_create(P.models.cnn1d_units(), 1, 128, 9, P.F32)
+    costs, out_bytes = P.profile_layers(model, 8, 10)
+    P.model_destroy(model)
+    assert costs.shape == (6,) and np.all(costs >= 1) and np.all(costs == np.floor(costs))
+    assert list(out_bytes) == [8 * 128 * 32 * 4, 8 * 128 * 64 * 4, 8 * 128 * 64 * 4, 8 * 64 * 4, 8 * 6 * 4, 8 * 6 * 4]
+    b, bott = P.solve_partition(costs, [1.0, 3.0, 10.0])
+    ob, obott = oracle_solve(list(costs), [1.0, 3.0, 10.0])
+    assert list(b) == ob and bott == obott
