@@ -12,24 +12,47 @@ from . import layers as L
 from . import models as M
 
 
-def _conv_bn_act_fwd(x, w, gamma, beta, stride, ph, pw, groups, act):
-    z = L.conv2d_fwd(x, w, stride, ph, pw, groups)
+def _identity(a):
+    return a
+
+
+def bf16_round(a):
+    """Round to the nearest bfloat16 (ties to even) and return in the input's dtype."""
+    a = np.asarray(a)
+    u = a.astype(np.float32).view(np.uint32).astype(np.uint64)
+    u = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+    return u.astype(np.uint32).view(np.float32).astype(a.dtype).reshape(a.shape)
+
+
+def _conv_bn_act_fwd(x, w, gamma, beta, stride, ph, pw, groups, act, q=_identity):
+    z = q(L.conv2d_fwd(x, q(w), stride, ph, pw, groups))
     y, mean, invstd, var = L.bn_fwd(z, gamma, beta)
     a = L.act_fwd(y, act)
     return a, dict(x=x, z=z, y=y, mean=mean, invstd=invstd, var=var)
 
 
-def _conv_bn_act_bwd(da, c, w, gamma, stride, ph, pw, groups, act):
+def _conv_bn_act_bwd(da, c, w, gamma, stride, ph, pw, groups, act, q=_identity):
+    """Returns the UNROUNDED input gradient (the caller rounds it once, after a
+    possible residual add) and the weight / gamma / beta gradients."""
     dy = L.act_bwd(da, c['y'], act)
     dz, dgamma, dbeta = L.bn_bwd(dy, c['z'], c['mean'], c['invstd'], gamma)
-    dx, dw = L.conv2d_bwd(c['x'], w, dz, stride, ph, pw, groups)
+    dx, dw = L.conv2d_bwd(c['x'], q(w), q(dz), stride, ph, pw, groups)
     return dx, dw, dgamma, dbeta
 
 
 class Stage:
-    def __init__(self, units, in_shape, a, b, n_slots=1, dtype=np.float64):
-        """units: full unit list; in_shape: (H, W, C) of the model input."""
+    def __init__(self, units, in_shape, a, b, n_slots=1, dtype=np.float64, storage=None):
+        """units: full unit list; in_shape: (H, W, C) of the model input.
+        storage='bf16' models mixed-precision training: every tensor that such a
+        run keeps in bfloat16 (convolution / FC outputs, block outputs, pooled
+        features, activation gradients, and the working copy of convolution / FC
+        weights) is rounded to bfloat16 at the point where it is stored, while
+        statistics, gamma/beta, weight gradients, momentum and master weights stay
+        exact.  The ReLU / ReLU6 on-off decisions are thereby taken on the same
+        rounded values a bfloat16 implementation sees."""
         assert 0 <= a < b <= len(units)
+        assert storage in (None, 'bf16')
+        self.q = bf16_round if storage == 'bf16' else _identity
         self.units, self.a, self.b, self.dtype = units, a, b, dtype
         shape = tuple(in_shape)
         self.shapes = [shape]
@@ -57,31 +80,32 @@ class Stage:
 
     def _unit_fwd(self, i, x, P):
         u = self.units[i]
+        q = self.q
         if u.kind == 'conv':
-            a, c = _conv_bn_act_fwd(x, P[0], P[1], P[2], u.stride, u.pad_h, u.pad_w, 1, u.act)
+            a, c = _conv_bn_act_fwd(x, P[0], P[1], P[2], u.stride, u.pad_h, u.pad_w, 1, u.act, q)
             self._bn_track(i, 0, c)
             return a, [c]
         if u.kind == 'invres':
             caches, h, k, nb = [], x, 0, 0
             ce = u.cin * u.expand
             if u.expand != 1:
-                h, c = _conv_bn_act_fwd(h, P[0], P[1], P[2], 1, 0, 0, 1, L.ACT_RELU6)
+                h, c = _conv_bn_act_fwd(h, P[0], P[1], P[2], 1, 0, 0, 1, L.ACT_RELU6, q)
                 self._bn_track(i, nb, c); nb += 1
                 caches.append(c); k = 3
-            h, c = _conv_bn_act_fwd(h, P[k], P[k + 1], P[k + 2], u.stride, 1, 1, ce, L.ACT_RELU6)
+            h, c = _conv_bn_act_fwd(h, P[k], P[k + 1], P[k + 2], u.stride, 1, 1, ce, L.ACT_RELU6, q)
             self._bn_track(i, nb, c); nb += 1
             caches.append(c)
-            h, c = _conv_bn_act_fwd(h, P[k + 3], P[k + 4], P[k + 5], 1, 0, 0, 1, L.ACT_NONE)
+            h, c = _conv_bn_act_fwd(h, P[k + 3], P[k + 4], P[k + 5], 1, 0, 0, 1, L.ACT_NONE, q)
             self._bn_track(i, nb, c)
             caches.append(c)
             if u.stride == 1 and u.cin == u.cout:
                 h = x + h
-            return h, caches
+            return q(h), caches
         if u.kind == 'gap':
-            return L.gap_fwd(x)[:, None, None, :], [dict(hw=x.shape[1:3])]
+            return q(L.gap_fwd(x))[:, None, None, :], [dict(hw=x.shape[1:3])]
         if u.kind == 'fc':
             x2 = x.reshape(x.shape[0], -1)
-            return L.fc_fwd(x2, P[0], P[1])[:, None, None, :], [dict(x=x2)]
+            return q(L.fc_fwd(x2, q(P[0]), P[1]))[:, None, None, :], [dict(x=x2)]
         return x, [dict()]                                   # loss unit: logits pass through
 
     def forward(self, slot, x, stash_weights=True):
@@ -93,6 +117,7 @@ class Stage:
         caches, h = {}, x
         for i in range(self.a, self.b):
             h, caches[i] = self._unit_fwd(i, h, P[i])
+        h = self.q(h)                                        # the stage output is a stored tensor
         self.slots[slot] = dict(caches=caches, params=P if stash_weights else None, out=h, dlogits=None)
         return h
 
@@ -101,7 +126,7 @@ class Stage:
         s = self.slots[slot]
         logits = s['out'].reshape(s['out'].shape[0], -1)
         loss, d = L.softmax_ce(logits, np.asarray(labels))
-        s['dlogits'] = d[:, None, None, :]
+        s['dlogits'] = self.q(d)[:, None, None, :]
         return loss
 
     # --------------------------------------------------------------- backward
@@ -110,31 +135,32 @@ class Stage:
 
     def _unit_bwd(self, i, d, caches, P):
         u = self.units[i]
+        q = self.q
         if u.kind == 'conv':
-            dx, dw, dg, db = _conv_bn_act_bwd(d, caches[0], P[0], P[1], u.stride, u.pad_h, u.pad_w, 1, u.act)
+            dx, dw, dg, db = _conv_bn_act_bwd(d, caches[0], P[0], P[1], u.stride, u.pad_h, u.pad_w, 1, u.act, q)
             self._acc(i, 0, dw); self._acc(i, 1, dg); self._acc(i, 2, db)
-            return dx
+            return q(dx)
         if u.kind == 'invres':
             ce = u.cin * u.expand
             k = 3 if u.expand != 1 else 0
             dout = d
-            d, dw, dg, db = _conv_bn_act_bwd(d, caches[-1], P[k + 3], P[k + 4], 1, 0, 0, 1, L.ACT_NONE)
+            d, dw, dg, db = _conv_bn_act_bwd(d, caches[-1], P[k + 3], P[k + 4], 1, 0, 0, 1, L.ACT_NONE, q)
             self._acc(i, k + 3, dw); self._acc(i, k + 4, dg); self._acc(i, k + 5, db)
-            d, dw, dg, db = _conv_bn_act_bwd(d, caches[-2], P[k], P[k + 1], u.stride, 1, 1, ce, L.ACT_RELU6)
+            d, dw, dg, db = _conv_bn_act_bwd(q(d), caches[-2], P[k], P[k + 1], u.stride, 1, 1, ce, L.ACT_RELU6, q)
             self._acc(i, k, dw); self._acc(i, k + 1, dg); self._acc(i, k + 2, db)
             if u.expand != 1:
-                d, dw, dg, db = _conv_bn_act_bwd(d, caches[0], P[0], P[1], 1, 0, 0, 1, L.ACT_RELU6)
+                d, dw, dg, db = _conv_bn_act_bwd(q(d), caches[0], P[0], P[1], 1, 0, 0, 1, L.ACT_RELU6, q)
                 self._acc(i, 0, dw); self._acc(i, 1, dg); self._acc(i, 2, db)
             if u.stride == 1 and u.cin == u.cout:
                 d = d + dout
-            return d
+            return q(d)
         if u.kind == 'gap':
             H, W = caches[0]['hw']
-            return L.gap_bwd(d.reshape(d.shape[0], -1), H, W)
+            return q(L.gap_bwd(d.reshape(d.shape[0], -1), H, W))
         if u.kind == 'fc':
-            dx, dw, db = L.fc_bwd(caches[0]['x'], P[0], d.reshape(d.shape[0], -1))
+            dx, dw, db = L.fc_bwd(caches[0]['x'], q(P[0]), d.reshape(d.shape[0], -1))
             self._acc(i, 0, dw); self._acc(i, 1, db)
-            return dx[:, None, None, :]
+            return q(dx)[:, None, None, :]
         return d
 
     def backward(self, slot, dy=None):

@@ -35,6 +35,14 @@ class Sgd(C.Structure):
 
 
 def _load():
+    # Callers hand us PyTorch device pointers and streams, so the library must bind to
+    # the HIP runtime PyTorch has loaded (its wheel bundles one whose soname our
+    # library's dependency resolves to once it is in the process).  Loading ours first
+    # would put a second, separate runtime into the process.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if not os.path.exists(_LIB_PATH):
         raise ImportError(f"{_LIB_PATH} is missing: run `python -m paper_2110_02781_amd.build` "
                           "(or __graft_entry__.build()) first; there is no CPU fallback")

@@ -63,14 +63,13 @@ class Pair:
         H, W, Cc = in_shape
         self.model = P.model_create(h_units, H, W, Cc, P.F32 if dtype == "f32" else P.BF16)
         self.stage = P.stage_create(self.model, a, b, batch, n_slots)
-        self.oracle = OracleStage(o_units, in_shape, a, b, n_slots)
+        self.oracle = OracleStage(o_units, in_shape, a, b, n_slots, storage='bf16' if dtype == 'bf16' else None)
         op = OM.init_params(o_units, seed)
         hp = P.models.init_unit_params(h_units, seed)
         for i in range(a, b):
             flat = flat_params(op[i])
             assert np.array_equal(flat.astype(np.float32), hp[i]), "both sides must draw identical weights"
-            # masters are fp32 on both sides; in bf16 mode the library also keeps a rounded working copy,
-            # the oracle stays exact
+            # masters are fp32 on both sides; in bf16 mode each side rounds its own working copy
             self.oracle.set_params(i, [p.astype(np.float32).astype(np.float64) for p in op[i]])
             P.stage_import_weights(self.stage, i, hp[i])
         self.in_shape = self.oracle.shapes[a]

@@ -225,3 +225,35 @@ def test_weight_stashing_differs_from_current_weights_and_lr0_equals_sync():
     a, _ = run(0.05, True, False)
     c, _ = run(0.05, False, False)
     assert np.abs(a.params[0][0] - c.params[0][0]).max() > 1e-6
+
+
+def test_bf16_rounding_matches_library_conversion():
+    from oracle.stage import bf16_round
+    v = np.concatenate([synth.normal(1, "r", (4096,)) * 10.0 ** synth.integers(1, "e", (4096,), -6, 6),
+                        np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.0e38, -2.5e-40])])
+    ref = torch.from_numpy(v.astype(np.float32)).to(torch.bfloat16).float().numpy().astype(np.float64)
+    np.testing.assert_array_equal(bf16_round(v), ref)
+    # ties go to the even mantissa: 1 + 2^-8 is half way between 1 and 1 + 2^-7
+    assert bf16_round(np.array([1.0 + 2.0 ** -8]))[0] == 1.0
+    assert bf16_round(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6
+
+
+def test_bf16_storage_mode_stays_close_to_exact_and_rounds_stored_tensors():
+    from oracle.stage import bf16_round
+    units, in_shape = small_mbv2(), (9, 9, 3)
+    x = bf16_round(synth.normal(2, "x", (4,) + in_shape))
+    labels = synth.labels(2, "labels", 4, 10)
+    P = M.init_params(units, 2)
+    out = []
+    for storage in (None, 'bf16'):
+        st = Stage(units, in_shape, 0, len(units), 1, storage=storage)
+        for i in range(len(units)):
+            st.set_params(i, P[i])
+        y = st.forward(0, x)
+        loss = st.loss(0, labels)
+        st.backward(0)
+        out.append((y, loss, st.grads[2][0]))
+        if storage == 'bf16':
+            np.testing.assert_array_equal(y, bf16_round(y))
+    assert abs(out[0][1] - out[1][1]) < 0.05 * abs(out[0][1])
+    assert np.abs(out[0][2] - out[1][2]).max() < 0.5 * np.abs(out[0][2]).max()
