@@ -121,6 +121,15 @@ int ftp_stage_export_grads(const ftp_stage*, int unit, float* host_g, size_t n);
 int ftp_stage_export_momentum(const ftp_stage*, int unit, float* host_v, size_t n);
 int ftp_stage_export_bn_stats(const ftp_stage*, int unit, float* host_s, size_t n);
 
+/* Inspection of a busy slot (between its forward and its backward): the raw
+ * output z of convolution number `conv` of `unit` (0-based within the unit, in
+ * execution order) converted to float, n = batch*Hout*Wout*Cout values in NHWC
+ * order; and that convolution's BatchNorm batch statistics as 4*Cout floats:
+ * mean, 1/sqrt(var+eps), scale = gamma/sqrt(var+eps), shift = beta - mean*scale.
+ * The value the next layer consumes is act(scale*z + shift).  Synchronous. */
+int ftp_stage_export_conv_output(const ftp_stage*, int slot, int unit, int conv, float* host_z, size_t n);
+int ftp_stage_export_bn_batch_stats(const ftp_stage*, int slot, int unit, int conv, float* host_s, size_t n);
+
 /* Forward of one batch through units [a,b) with the current weights.
  * x_dev: [batch, H, W, C] of unit a's input, read only, copied into the slot
  * (the stashed stage input).  y_dev: output of the last unit, or NULL; when the

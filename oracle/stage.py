@@ -27,14 +27,40 @@ def bf16_round(a):
 def _conv_bn_act_fwd(x, w, gamma, beta, stride, ph, pw, groups, act, q=_identity):
     z = q(L.conv2d_fwd(x, q(w), stride, ph, pw, groups))
     y, mean, invstd, var = L.bn_fwd(z, gamma, beta)
-    a = L.act_fwd(y, act)
-    return a, dict(x=x, z=z, y=y, mean=mean, invstd=invstd, var=var)
+    a = q(L.act_fwd(y, act))
+    return a, dict(x=x, z=z, y=y, mean=mean, invstd=invstd, var=var, beta=beta)
 
 
-def _conv_bn_act_bwd(da, c, w, gamma, stride, ph, pw, groups, act, q=_identity):
+def _conv_bn_act_bwd(da, c, w, gamma, stride, ph, pw, groups, act, q=_identity, tie=None):
     """Returns the UNROUNDED input gradient (the caller rounds it once, after a
-    possible residual add) and the weight / gamma / beta gradients."""
-    dy = L.act_bwd(da, c['y'], act)
+    possible residual add) and the weight / gamma / beta gradients.
+
+    tie = (on, guard, report) resolves ReLU / ReLU6 on-off decisions that are ties
+    at the precision of the implementation under test: where the pre-activation
+    y lies within guard * (|gamma| * sqrt(1 + mean^2/var) + |beta|) of a kink
+    (a relative error `guard` of the channel's typical |z|, carried through
+    y = gamma*(z-mean)/std + beta), on and off are both correct, and the caller's
+    boolean array `on` decides.  Everywhere
+    else the oracle's own decision stands; report counts the elements where `on`
+    disagrees with it outside the tie band (a real error of the caller)."""
+    if tie is not None and act != L.ACT_NONE:
+        on, guard, report = tie
+        y = c['y']
+        sc = gamma * c['invstd']
+        band = guard * (np.abs(sc) * np.sqrt(c['var'] + c['mean'] ** 2) + np.abs(c['beta']))
+        amb = np.abs(y) <= band
+        own = y > 0
+        if act == L.ACT_RELU6:
+            amb |= np.abs(y - 6) <= band
+            own &= y < 6
+        on = np.asarray(on, dtype=bool).reshape(y.shape)
+        report['elements'] = report.get('elements', 0) + int(y.size)
+        report['ties'] += int(amb.sum())
+        report['adopted'] += int((amb & (on != own)).sum())
+        report['disagree'] += int((~amb & (on != own)).sum())
+        dy = da * np.where(amb, on, own)
+    else:
+        dy = L.act_bwd(da, c['y'], act)
     dz, dgamma, dbeta = L.bn_bwd(dy, c['z'], c['mean'], c['invstd'], gamma)
     dx, dw = L.conv2d_bwd(c['x'], q(w), q(dz), stride, ph, pw, groups)
     return dx, dw, dgamma, dbeta
@@ -45,8 +71,8 @@ class Stage:
         """units: full unit list; in_shape: (H, W, C) of the model input.
         storage='bf16' models mixed-precision training: every tensor that such a
         run keeps in bfloat16 (convolution / FC outputs, block outputs, pooled
-        features, activation gradients, and the working copy of convolution / FC
-        weights) is rounded to bfloat16 at the point where it is stored, while
+        features, BatchNorm+activation outputs, activation gradients, and the
+        working copy of convolution / FC weights) is rounded to bfloat16 at the point where it is stored, while
         statistics, gamma/beta, weight gradients, momentum and master weights stay
         exact.  The ReLU / ReLU6 on-off decisions are thereby taken on the same
         rounded values a bfloat16 implementation sees."""
@@ -114,11 +140,13 @@ class Stage:
         # update() replaces parameter arrays instead of writing into them, so
         # keeping the lists is a snapshot of this weight version
         P = {i: list(self.params[i]) for i in range(self.a, self.b)}
-        caches, h = {}, x
+        caches, h, unit_in = {}, x, {}
         for i in range(self.a, self.b):
+            unit_in[i] = h
             h, caches[i] = self._unit_fwd(i, h, P[i])
         h = self.q(h)                                        # the stage output is a stored tensor
-        self.slots[slot] = dict(caches=caches, params=P if stash_weights else None, out=h, dlogits=None)
+        self.slots[slot] = dict(caches=caches, params=P if stash_weights else None, out=h, dlogits=None,
+                                unit_in=unit_in)
         return h
 
     def loss(self, slot, labels):
@@ -133,23 +161,29 @@ class Stage:
     def _acc(self, i, k, g):
         self.grads[i][k] = self.grads[i][k] + g
 
-    def _unit_bwd(self, i, d, caches, P):
+    def _unit_bwd(self, i, d, caches, P, ties=None):
         u = self.units[i]
         q = self.q
+
+        def tie(k):          # tie-break data of convolution k of this unit, if the caller gave any
+            if ties is None or (i, k) not in ties['on']:
+                return None
+            return (ties['on'][(i, k)], ties['guard'], ties['report'])
         if u.kind == 'conv':
-            dx, dw, dg, db = _conv_bn_act_bwd(d, caches[0], P[0], P[1], u.stride, u.pad_h, u.pad_w, 1, u.act, q)
+            dx, dw, dg, db = _conv_bn_act_bwd(d, caches[0], P[0], P[1], u.stride, u.pad_h, u.pad_w, 1, u.act, q, tie(0))
             self._acc(i, 0, dw); self._acc(i, 1, dg); self._acc(i, 2, db)
             return q(dx)
         if u.kind == 'invres':
             ce = u.cin * u.expand
             k = 3 if u.expand != 1 else 0
             dout = d
-            d, dw, dg, db = _conv_bn_act_bwd(d, caches[-1], P[k + 3], P[k + 4], 1, 0, 0, 1, L.ACT_NONE, q)
+            d, dw, dg, db = _conv_bn_act_bwd(d, caches[-1], P[k + 3], P[k + 4], 1, 0, 0, 1, L.ACT_NONE, q, None)
             self._acc(i, k + 3, dw); self._acc(i, k + 4, dg); self._acc(i, k + 5, db)
-            d, dw, dg, db = _conv_bn_act_bwd(q(d), caches[-2], P[k], P[k + 1], u.stride, 1, 1, ce, L.ACT_RELU6, q)
+            d, dw, dg, db = _conv_bn_act_bwd(q(d), caches[-2], P[k], P[k + 1], u.stride, 1, 1, ce, L.ACT_RELU6, q,
+                                             tie(len(caches) - 2))
             self._acc(i, k, dw); self._acc(i, k + 1, dg); self._acc(i, k + 2, db)
             if u.expand != 1:
-                d, dw, dg, db = _conv_bn_act_bwd(q(d), caches[0], P[0], P[1], 1, 0, 0, 1, L.ACT_RELU6, q)
+                d, dw, dg, db = _conv_bn_act_bwd(q(d), caches[0], P[0], P[1], 1, 0, 0, 1, L.ACT_RELU6, q, tie(0))
                 self._acc(i, 0, dw); self._acc(i, 1, dg); self._acc(i, 2, db)
             if u.stride == 1 and u.cin == u.cout:
                 d = d + dout
@@ -163,14 +197,21 @@ class Stage:
             return q(dx)[:, None, None, :]
         return d
 
-    def backward(self, slot, dy=None):
+    def backward(self, slot, dy=None, tie_breaks=None, guard=0.0):
+        """tie_breaks: {(unit, conv): boolean array} of activation on-off decisions
+        to adopt inside the tie band (see _conv_bn_act_bwd); the counts of ties,
+        adopted decisions and out-of-band disagreements land in self.tie_report."""
         s = self.slots[slot]
         assert s is not None, "slot empty"
         d = s['dlogits'] if dy is None else np.asarray(dy, dtype=self.dtype)
         assert d is not None
         P = s['params'] if s['params'] is not None else self.params
+        self.tie_report = dict(ties=0, adopted=0, disagree=0)
+        ties = None if tie_breaks is None else dict(on=tie_breaks, guard=guard, report=self.tie_report)
+        self.unit_in, self.unit_dout = s['unit_in'], {}     # kept for unit-by-unit checks
         for i in range(self.b - 1, self.a - 1, -1):
-            d = self._unit_bwd(i, d, s['caches'][i], P[i])
+            self.unit_dout[i] = d
+            d = self._unit_bwd(i, d, s['caches'][i], P[i], ties)
         self.slots[slot] = None
         return d
 

@@ -5,7 +5,7 @@ from .binding import (  # noqa: F401
     FtpError, lib, last_error,
     model_create, model_destroy, model_num_units, model_unit_in_shape, model_unit_param_count,
     model_unit_bn_channels, stage_create, stage_destroy, stage_import_weights, stage_export_weights,
-    stage_export_grads, stage_export_momentum, stage_export_bn_stats, stage_forward, stage_loss,
+    stage_export_grads, stage_export_momentum, stage_export_bn_stats, stage_export_conv_output, stage_export_bn_batch_stats, stage_forward, stage_loss,
     stage_snapshot_weights, stage_backward, stage_update, profile_layers, solve_partition,
     estimate_capacity, F32, BF16,
 )

@@ -68,6 +68,8 @@ _SIGS = {
     "ftp_stage_export_grads": (_i, [_vp, _i, _fp, _sz]),
     "ftp_stage_export_momentum": (_i, [_vp, _i, _fp, _sz]),
     "ftp_stage_export_bn_stats": (_i, [_vp, _i, _fp, _sz]),
+    "ftp_stage_export_conv_output": (_i, [_vp, _i, _i, _i, _fp, _sz]),
+    "ftp_stage_export_bn_batch_stats": (_i, [_vp, _i, _i, _i, _fp, _sz]),
     "ftp_stage_forward": (_i, [_vp, _i, _vp, _vp, _vp]),
     "ftp_stage_loss": (_i, [_vp, _i, _vp, _vp, _vp]),
     "ftp_stage_snapshot_weights": (_i, [_vp, _i, _vp]),
@@ -188,6 +190,18 @@ def stage_export_momentum(stage, unit, n):
 
 def stage_export_bn_stats(stage, unit, n):
     return _export(lib.ftp_stage_export_bn_stats, stage, unit, n)
+
+
+def stage_export_conv_output(stage, slot, unit, conv, n):
+    out = np.empty(n, dtype=np.float32)
+    _chk(lib.ftp_stage_export_conv_output(stage, slot, unit, conv, out.ctypes.data_as(_fp), n))
+    return out
+
+
+def stage_export_bn_batch_stats(stage, slot, unit, conv, n):
+    out = np.empty(n, dtype=np.float32)
+    _chk(lib.ftp_stage_export_bn_batch_stats(stage, slot, unit, conv, out.ctypes.data_as(_fp), n))
+    return out
 
 
 def stage_forward(stage, slot, x_dev, y_dev=None, stream=None):

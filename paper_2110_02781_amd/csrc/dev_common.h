@@ -68,7 +68,9 @@ __device__ __forceinline__ float act_mask(float y, int act) {
   return 1.f;
 }
 
-// A tensor as its consumer sees it: value(m, c) = act(scale[c] * z[m][c] + shift[c]);
+// A tensor as its consumer sees it: value(m, c) = act(scale[c] * z[m][c] + shift[c]),
+// rounded to the storage type (what a materialised BatchNorm+activation output
+// would hold, and what the bfloat16 MFMA operands hold anyway);
 // scale == nullptr means the tensor is stored already activated.
 struct View {
   const void* z;
@@ -80,7 +82,7 @@ struct View {
 template <typename T>
 __device__ __forceinline__ float view_at(const View& v, size_t idx, int c) {
   float x = to_f32(reinterpret_cast<const T*>(v.z)[idx]);
-  if (v.scale) x = act_apply(fmaf(x, v.scale[c], v.shift[c]), v.act);
+  if (v.scale) x = round_to<T>(act_apply(fmaf(x, v.scale[c], v.shift[c]), v.act));
   return x;
 }
 
@@ -93,7 +95,7 @@ __device__ __forceinline__ void view_load8(const View& v, size_t idx, int c, flo
     load8(v.scale + c, s);
     load8(v.shift + c, b);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) out[e] = act_apply(fmaf(out[e], s[e], b[e]), v.act);
+    for (int e = 0; e < 8; ++e) out[e] = round_to<T>(act_apply(fmaf(out[e], s[e], b[e]), v.act));
   }
 }
 

@@ -400,6 +400,45 @@ extern "C" int ftp_stage_export_bn_stats(const ftp_stage* s, int unit, float* ho
   return FTP_OK;
 }
 
+static int inspect_check(const ftp_stage* s, int slot, int unit, int conv, const void* host, const char* who) {
+  if (!s || !host) { ftp_set_error("%s: NULL argument", who); return FTP_ERR_ARG; }
+  if (slot < 0 || slot >= (int)s->slots.size()) { ftp_set_error("%s: slot %d out of range", who, slot); return FTP_ERR_ARG; }
+  if (unit < s->a || unit >= s->b) { ftp_set_error("%s: unit %d outside the stage [%d,%d)", who, unit, s->a, s->b); return FTP_ERR_ARG; }
+  if (conv < 0 || conv >= (int)s->plan[unit - s->a].info->subs.size()) { ftp_set_error("%s: unit %d has no convolution %d", who, unit, conv); return FTP_ERR_ARG; }
+  if (!s->slots[slot].busy) { ftp_set_error("%s: slot %d holds no forwarded batch", who, slot); return FTP_ERR_SLOT; }
+  return FTP_OK;
+}
+
+extern "C" int ftp_stage_export_conv_output(const ftp_stage* s, int slot, int unit, int conv, float* host_z, size_t n) {
+  int rc = inspect_check(s, slot, unit, conv, host_z, "export_conv_output");
+  if (rc) return rc;
+  const UnitPlan& p = s->plan[unit - s->a];
+  const Sub& sb = p.info->subs[conv];
+  size_t expect = (size_t)s->batch * sb.g.Hout * sb.g.Wout * sb.g.Cout;
+  if (n != expect) { ftp_set_error("export_conv_output: tensor has %zu values, caller passed %zu", expect, n); return FTP_ERR_SHAPE; }
+  HIP_TRY(hipDeviceSynchronize());
+  const char* src = s->slots[slot].stash + p.z_off[conv];
+  if (s->dt == FTP_F32) {
+    HIP_TRY(hipMemcpy(host_z, src, n * 4, hipMemcpyDeviceToHost));
+  } else {
+    std::vector<uint16_t> tmp(n);
+    HIP_TRY(hipMemcpy(tmp.data(), src, n * 2, hipMemcpyDeviceToHost));
+    for (size_t i = 0; i < n; ++i) { uint32_t u = (uint32_t)tmp[i] << 16; memcpy(&host_z[i], &u, 4); }
+  }
+  return FTP_OK;
+}
+
+extern "C" int ftp_stage_export_bn_batch_stats(const ftp_stage* s, int slot, int unit, int conv, float* host_s, size_t n) {
+  int rc = inspect_check(s, slot, unit, conv, host_s, "export_bn_batch_stats");
+  if (rc) return rc;
+  const UnitPlan& p = s->plan[unit - s->a];
+  size_t expect = (size_t)4 * p.info->subs[conv].g.Cout;
+  if (n != expect) { ftp_set_error("export_bn_batch_stats: %zu values, caller passed %zu", expect, n); return FTP_ERR_SHAPE; }
+  HIP_TRY(hipDeviceSynchronize());
+  HIP_TRY(hipMemcpy(host_s, s->slots[slot].stats + p.st_off[conv], n * 4, hipMemcpyDeviceToHost));
+  return FTP_OK;
+}
+
 // ---- helpers for the compute calls ------------------------------------------------
 struct WeightSet { const float* w32; const char* lp; };
 

@@ -7,6 +7,11 @@ from oracle import models as OM
 from oracle.stage import Stage as OracleStage
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
+# Width of the band around a ReLU / ReLU6 kink inside which on and off are both
+# correct, as a multiple of the magnitude of the two summands of y = scale*z + shift.
+# It equals the forward tolerance: a pre-activation that the tolerance allows to be
+# wrong by more than its distance to the kink cannot have a unique on/off decision.
+GUARD = dict(TOL)
 
 
 def rel_err(a, b):
@@ -22,14 +27,21 @@ def rel_err(a, b):
     return np.abs(d).max() / ref_max, np.sqrt((d * d).sum()) / ref_l2
 
 
-def assert_close(a, b, tol, what, floor=0.0):
+def assert_close(a, b, tol, what, floor=0.0, scale_ref=None):
     """Both the max-abs and the L2 relative error must be within tol.  `floor`:
-    tensors whose reference is numerically zero (below floor) are compared absolutely."""
+    tensors whose reference is numerically zero (below floor) are compared absolutely.
+    `scale_ref`: a tensor of the same natural magnitude as the terms summed into b;
+    used as the denominator when it is larger than b itself (sums that cancel)."""
     assert np.all(np.isfinite(np.asarray(a, dtype=np.float64))), f"{what}: non-finite values"
-    if np.abs(np.asarray(b)).max() <= floor:
+    if np.abs(np.asarray(b)).max() <= floor and scale_ref is None:
         assert np.abs(np.asarray(a)).max() <= max(floor, 1e-30) * 10, f"{what}: expected ~0"
         return 0.0, 0.0
     e_max, e_l2 = rel_err(a, b)
+    if scale_ref is not None:
+        d = np.asarray(a, dtype=np.float64).ravel() - np.asarray(b, dtype=np.float64).ravel()
+        sr = np.asarray(scale_ref, dtype=np.float64).ravel()
+        e_max = min(e_max, np.abs(d).max() / max(np.abs(sr).max(), 1e-30))
+        e_l2 = min(e_l2, np.sqrt((d * d).sum()) / max(np.sqrt((sr * sr).sum()), 1e-30))
     assert e_max <= tol and e_l2 <= tol, f"{what}: max-rel {e_max:.3e}, l2-rel {e_l2:.3e} > {tol}"
     return e_max, e_l2
 
@@ -52,7 +64,7 @@ def from_bf16_bits(b):
 class Pair:
     """The same stage [a,b) in the oracle (float64) and in the HIP library."""
 
-    def __init__(self, o_units, h_units, in_shape, batch, a, b, dtype="f32", n_slots=1, seed=1):
+    def __init__(self, o_units, h_units, in_shape, batch, a, b, dtype="f32", n_slots=1, seed=1, guard=None, max_disagree_frac=0.0):
         import torch
         import paper_2110_02781_amd as P
         self.P, self.torch = P, torch
@@ -75,6 +87,9 @@ class Pair:
         self.in_shape = self.oracle.shapes[a]
         self.out_shape = self.oracle.shapes[b]
         self.stream = torch.cuda.current_stream().cuda_stream
+        self.tie_reports = []
+        self.max_disagree_frac = max_disagree_frac
+        self.guard = GUARD[dtype] if guard is None else guard     # = the forward tolerance in force
 
     def close(self):
         self.P.stage_destroy(self.stage)
@@ -115,12 +130,49 @@ class Pair:
         lo = self.oracle.loss(slot, labels)
         return float(self.host(out)[0]), lo
 
+    def kernel_decisions(self, slot):
+        """The on/off decision the library takes for every ReLU / ReLU6 element of the
+        slot's batch: act'(fma(z, scale, shift)) evaluated in float32 on its own z and
+        BatchNorm scale / shift."""
+        P = self.P
+        out = {}
+        for i in range(self.a, self.b):
+            u = self.o_units[i]
+            if u.kind == 'conv':
+                acts = [u.act]
+            elif u.kind == 'invres':
+                acts = ([2] if u.expand != 1 else []) + [2, 0]
+            else:
+                continue
+            for k, act in enumerate(acts):
+                if act == 0:
+                    continue
+                zo = self.oracle.slots[slot]['caches'][i][k]['z']
+                C = zo.shape[-1]
+                z = P.stage_export_conv_output(self.stage, slot, i, k, zo.size).reshape(zo.shape)
+                st = P.stage_export_bn_batch_stats(self.stage, slot, i, k, 4 * C)
+                y = (z.astype(np.float64) * st[2 * C:3 * C].astype(np.float64) + st[3 * C:].astype(np.float64)).astype(np.float32)
+                on = y > 0
+                if act == 2:
+                    on &= y < 6
+                out[(i, k)] = on
+        return out
+
     def backward(self, slot, dy=None, want_dx=True):
+        """Backward on both sides.  On-off decisions of the activations that are ties at
+        the library's precision are resolved the way the library resolved them; any
+        decision that differs outside the tie band fails the test."""
         P = self.P
         dyd = self.dev_tensor(dy) if dy is not None else None
         dx = self.empty((self.batch,) + tuple(self.in_shape)) if want_dx else None
+        ties = self.kernel_decisions(slot)
         P.stage_backward(self.stage, slot, dyd, dx, self.stream)
-        dxo = self.oracle.backward(slot, None if dy is None else self.as_seen(dy))
+        dxo = self.oracle.backward(slot, None if dy is None else self.as_seen(dy), tie_breaks=ties,
+                                   guard=self.guard)
+        rep = self.oracle.tie_report
+        self.tie_reports.append(rep)
+        assert rep['disagree'] <= self.max_disagree_frac * rep.get('elements', 0), \
+            f"activation decisions differ outside the tie band: {rep}"
         return (self.host(dx) if want_dx else None), dxo
 
     def update(self, lr, mu, wd):
@@ -151,10 +203,69 @@ class Pair:
             src = {"weights": self.oracle.params, "grads": self.oracle.grads, "momentum": self.oracle.mom}[which]
             got = fn(self.stage, i, n)
             # compare tensor by tensor so that a small tensor is not hidden by a large one
+            # d(gamma) of a BatchNorm whose consumer is again normalised per channel (expand ->
+            # depthwise -> BatchNorm) cancels to almost zero; it is a sum of the same dY terms as
+            # d(beta) weighted by unit-variance x-hat, so it is judged on d(beta)'s scale.
+            names = [nm for nm, _, _, _ in OM.param_specs(self.o_units[i])]
             off = 0
             for k, ref in enumerate(src[i]):
                 m = ref.size
-                e = assert_close(got[off:off + m], ref.ravel(), tol, f"unit {i} {which}[{k}]", floor)
+                # gamma and beta of one BatchNorm are judged on their joint scale: either gradient can
+                # vanish by an invariance of the network (a per-channel shift or scale that the next
+                # normalisation removes) while the other does not
+                sref = None
+                if names[k].startswith("gamma"):
+                    sref = np.concatenate([src[i][k].ravel(), src[i][k + 1].ravel()])
+                elif names[k].startswith("beta"):
+                    sref = np.concatenate([src[i][k - 1].ravel(), src[i][k].ravel()])
+                e = assert_close(got[off:off + m], ref.ravel(), tol, f"unit {i} {which}[{k}:{names[k]}]", floor, sref)
                 worst = (max(worst[0], e[0]), max(worst[1], e[1]))
                 off += m
         return worst
+
+
+def e2e_tol(dtype, n_units):
+    """End-to-end tolerance over a chain of n_units partition units.  float: 1e-4 throughout.
+    bfloat16: two correct implementations that round every stored tensor to 8 significant
+    bits decorrelate in the last bit of almost every element within a few layers, so their
+    difference performs a random walk of about one storage rounding per convolution; the
+    2e-2 bar therefore applies per unit (see unitwise_check) and grows with the square root
+    of the chain length end to end."""
+    return TOL[dtype] if dtype == "f32" else TOL[dtype] * max(1.0, np.sqrt(n_units))
+
+
+def unitwise_check(o_units, h_units, in_shape, batch, a, b, dtype, seed, x, dy=None, labels=None, report=None):
+    """Teacher-forced parity of every unit of stage [a,b) at its real shape: the oracle runs
+    the whole stage once; then each unit alone is built in the library, fed the oracle's input
+    of that unit and the oracle's gradient of that unit's output, and compared at TOL."""
+    whole = OracleStage(o_units, in_shape, a, b, 1, storage='bf16' if dtype == 'bf16' else None)
+    op = OM.init_params(o_units, seed)
+    for i in range(a, b):
+        whole.set_params(i, [p.astype(np.float32).astype(np.float64) for p in op[i]])
+    whole.forward(0, x)
+    if labels is not None:
+        whole.loss(0, labels)
+    whole.backward(0, dy)
+    tol = TOL[dtype]
+    for i in range(a, b):
+        kind = o_units[i].kind
+        print(f"  unit {i} ({kind}) teacher-forced {dtype}", flush=True)
+        pair = Pair(o_units, h_units, in_shape, batch, i, i + 1, dtype, seed=seed)
+        try:
+            y, yo = pair.forward(0, whole.unit_in[i])
+            e_y = assert_close(y, yo, tol, f"unit {i} y")
+            if kind == 'loss':
+                lh, lo = pair.loss(0, labels)
+                assert abs(lh - lo) <= tol * max(1.0, abs(lo)), (lh, lo)
+                dx, dxo = pair.backward(0, None)
+            else:
+                dx, dxo = pair.backward(0, whole.unit_dout[i])
+            e_dx = assert_close(dx, dxo, tol, f"unit {i} dx")
+            e_g = pair.compare_unit_vectors("grads", tol, floor=1e-7)
+            pair.compare_unit_vectors("bn", tol)
+            pair.update(0.01, 0.9, 4e-5)
+            pair.compare_unit_vectors("weights", tol)
+            if report is not None:
+                report.append((i, kind, e_y, e_dx, e_g, dict(pair.tie_reports[-1])))
+        finally:
+            pair.close()

@@ -257,3 +257,32 @@ def test_bf16_storage_mode_stays_close_to_exact_and_rounds_stored_tensors():
             np.testing.assert_array_equal(y, bf16_round(y))
     assert abs(out[0][1] - out[1][1]) < 0.05 * abs(out[0][1])
     assert np.abs(out[0][2] - out[1][2]).max() < 0.5 * np.abs(out[0][2]).max()
+
+
+def test_tie_breaks_only_act_inside_the_band():
+    """Decisions handed to backward are adopted only within the rounding band around a
+    kink; elsewhere the oracle keeps its own and counts the disagreement."""
+    units, in_shape = M.cnn1d(channels=(8, 8, 8)), (1, 16, 9)
+    x = synth.normal(4, "x", (2,) + in_shape)
+    dy = synth.normal(4, "dy", (2, 1, 16, 8))
+    P = M.init_params(units, 4)
+
+    def run(ties, guard):
+        st = Stage(units, in_shape, 0, 1)
+        st.set_params(0, P[0])
+        st.forward(0, x)
+        y = st.slots[0]['caches'][0][0]['y']
+        d = st.backward(0, dy, tie_breaks=None if ties is None else {(0, 0): ties(y)}, guard=guard)
+        return d, st.tie_report, y
+    base, _, y = run(None, 0.0)
+    same, rep, _ = run(lambda y: y > 0, 1e-5)
+    np.testing.assert_array_equal(base, same)
+    assert rep['disagree'] == 0 and rep['adopted'] == 0
+    # flipping everything: outside the band nothing changes and every element is reported
+    flipped, rep, _ = run(lambda y: y <= 0, 1e-9)
+    assert rep['disagree'] + rep['adopted'] == y.size and rep['adopted'] == rep['ties']
+    if rep['ties'] == 0:
+        np.testing.assert_array_equal(base, flipped)
+    # a huge band adopts the caller's decisions, which changes the gradient
+    adopted, rep, _ = run(lambda y: y <= 0, 1e3)
+    assert rep['adopted'] == y.size and np.abs(adopted - base).max() > 1e-3
