@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Stage-training throughput on one MI355X: forward + loss + backward + SGD update of one
+pipeline stage on seeded synthetic data, through the C-ABI library.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config {1,2,5}] [--graph]
+
+Prints ONE JSON line: samples/s of the whole step (inputs resident in HBM), the roofline
+of the kernel family that takes the most time (measured with HIP events around every
+launch in a second pass of K steps) and the CPU oracle timed on this host as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+
+WORKLOADS = {
+    1: dict(name="config1: 1D-CNN 9x128 -> 32/64/64 -> 6 classes, batch 8, fp32, whole model",
+            net="cnn1d", batch=8, in_shape=(1, 128, 9), classes=6, dtype="f32", lr=0.01, mu=0.9, wd=0.0),
+    2: dict(name="config2: MobileNetV2 w1.0, 32x32x3, 10 classes, batch 32, fp32, whole model as one stage",
+            net="mbv2", width=1.0, stem_stride=1, batch=32, in_shape=(32, 32, 3), classes=10, dtype="f32",
+            lr=0.01, mu=0.9, wd=4e-5),
+    5: dict(name="config5: MobileNetV2 w1.4, 224x224x3, 1000 classes, batch 128, bf16 (fp32 masters), whole model",
+            net="mbv2", width=1.4, stem_stride=2, batch=128, in_shape=(224, 224, 3), classes=1000, dtype="bf16",
+            lr=0.01, mu=0.9, wd=4e-5),
+}
+
+
+def build_units(P, w):
+    if w["net"] == "cnn1d":
+        return P.models.cnn1d_units()
+    return P.models.mobilenet_v2_units(w["width"], w["classes"], w["stem_stride"])
+
+
+def oracle_baseline(w, seed, budget_s=30.0):
+    """One training step of the CPU oracle (float64, as it stands) on a bounded sample of the
+    same workload: the batch is cut so that the step should fit the time budget."""
+    import synth
+    from oracle import models as OM
+    from oracle.stage import Stage
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    units = OM.cnn1d() if w["net"] == "cnn1d" else OM.mobilenet_v2(w["width"], w["classes"], w["stem_stride"])
+    # rough cost model: config-2 batch 32 takes a few seconds; 224x224 images cost 49x more per sample
+    per_sample = (w["in_shape"][0] * w["in_shape"][1]) / 1024.0 * (w.get("width", 1.0) ** 2)
+    batch = int(max(2, min(w["batch"], 48.0 / max(per_sample, 1e-3))))
+    st = Stage(units, w["in_shape"], 0, len(units))
+    P = OM.init_params(units, seed)
+    for i in range(len(units)):
+        st.set_params(i, P[i])
+    x = synth.normal(seed, "x", (batch,) + tuple(w["in_shape"]))
+    labels = synth.labels(seed, "labels", batch, w["classes"])
+    t0 = time.perf_counter()
+    st.forward(0, x)
+    st.loss(0, labels)
+    st.backward(0)
+    st.update(w["lr"], w["mu"], w["wd"])
+    dt = time.perf_counter() - t0
+    return dict(value=batch / dt, unit="samples/s", cores=int(threads), kind="oracle",
+                sample=f"1 full training step (fwd+loss+bwd+update) of the same network at batch {batch} "
+                       f"of {w['batch']}, float64 numpy, {dt:.2f} s")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, choices=sorted(WORKLOADS))
+    ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ktrace", action="store_true")
+    ap.add_argument("--seed", type=int, default=2110)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs one pipeline stage on ONE GPU; --gpus must be 1 "
+              "(no multi-GPU path exists, see DESIGN.md 'More than one GPU')", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth
+    import paper_2110_02781_amd as P
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    w = WORKLOADS[args.config]
+    dev = torch.device("cuda:0")
+    tdt = torch.float32 if w["dtype"] == "f32" else torch.bfloat16
+    units = build_units(P, w)
+    H, W_, C = w["in_shape"]
+    model = P.model_create(units, H, W_, C, P.F32 if w["dtype"] == "f32" else P.BF16)
+    L = P.model_num_units(model)
+    stage = P.stage_create(model, 0, L, w["batch"], 1)
+    params = P.models.init_unit_params(units, args.seed)
+    for i in range(L):
+        P.stage_import_weights(stage, i, params[i])
+    x = torch.from_numpy(synth.normal(args.seed, "x", (w["batch"], H, W_, C)).astype(np.float32)).to(dev).to(tdt)
+    labels = torch.from_numpy(synth.labels(args.seed, "labels", w["batch"], w["classes"])).to(dev)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    stream = torch.cuda.Stream()
+    sp = stream.cuda_stream
+
+    def step():
+        P.stage_forward(stage, 0, x, None, sp)
+        P.stage_loss(stage, 0, labels, loss, sp)
+        P.stage_backward(stage, 0, None, None, sp)
+        P.stage_update(stage, w["lr"], w["mu"], w["wd"], sp)
+
+    run = step
+    graph = None
+    if args.graph:
+        # the library only enqueues kernels and device-to-device copies, so a step can be captured
+        step(); stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            step()
+        run = graph.replay
+
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    final_loss = float(loss.item())
+    ms_per_step = dt / args.steps * 1e3
+    value = w["batch"] * args.steps / dt
+
+    # second pass: HIP events around every launch -> the dominant kernel family and its roofline
+    roofline, kernels = None, []
+    if not args.no_ktrace:
+        P.ktrace_begin(1 << 16)
+        nsteps = max(1, min(args.steps, 20))
+        for _ in range(nsteps):
+            step()
+        rows = P.ktrace_end()
+        rows.sort(key=lambda r: -r["total_ms"])
+        tot = sum(r["total_ms"] for r in rows) or 1.0
+        for r in rows:
+            avg_us = r["total_ms"] / r["launches"] * 1e3
+            gbs = r["alg_bytes"] / (r["total_ms"] * 1e-3) / 1e9 if r["total_ms"] > 0 else 0.0
+            tfs = r["flops"] / (r["total_ms"] * 1e-3) / 1e12 if r["total_ms"] > 0 else 0.0
+            kernels.append(dict(name=r["name"], launches_per_step=r["launches"] / nsteps, avg_us=round(avg_us, 2),
+                                share=round(r["total_ms"] / tot, 4), alg_GBps=round(gbs, 1), TFLOPs=round(tfs, 2)))
+        d = rows[0]
+        ai = d["flops"] / max(d["alg_bytes"], 1.0)
+        balance = PEAK_TFLOPS[w["dtype"]] * 1e12 / (PEAK_HBM_GBS * 1e9)
+        is_gemm = d["name"].startswith("pw_")
+        if is_gemm and ai >= balance:
+            ach = d["flops"] / (d["total_ms"] * 1e-3) / 1e12
+            roofline = dict(bound="mfma", achieved=round(ach, 3), peak=PEAK_TFLOPS[w["dtype"]], unit="TFLOP/s",
+                            frac=round(ach / PEAK_TFLOPS[w["dtype"]], 4), traffic=None)
+        else:
+            ach = d["alg_bytes"] / (d["total_ms"] * 1e-3) / 1e9
+            roofline = dict(bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                            frac=round(ach / PEAK_HBM_GBS, 4), traffic=None)
+        roofline.update(kernel=d["name"], avg_launch_us=round(d["total_ms"] / d["launches"] * 1e3, 2),
+                        launches_per_step=d["launches"] / nsteps,
+                        alg_bytes_per_launch=round(d["alg_bytes"] / d["launches"]),
+                        note="algorithmic bytes = every operand of a launch once; durations from HIP events "
+                             "around each launch on its stream, in a separate traced pass")
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = oracle_baseline(w, args.seed)
+
+    out = {
+        "metric": "stage train samples/sec (fwd+bwd+update) at 1 MI355X; % HBM/MFMA roofline",
+        "value": round(value, 2), "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w["dtype"], "data": "synthetic (seeded N(0,1) inputs, uniform labels, He-normal weights)",
+        "config": {"workload": w["name"], "batch": w["batch"], "units": L, "hip_graph": bool(args.graph),
+                   "final_loss": round(final_loss, 4)},
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+    }
+    P.stage_destroy(stage)
+    P.model_destroy(model)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -187,6 +187,23 @@ int ftp_solve_partition(const double* layer_costs, int L, const double* device_c
 int ftp_estimate_capacity(double stage_time, const double* layer_costs, int L, int start, int end,
                           double* capacity);
 
+/* ---- diagnostics ---------------------------------------------------------------- */
+
+/* Per-kernel timing for benchmarks (not part of the paper's method).  Between
+ * begin and end every kernel launch of this library is bracketed by HIP events
+ * on its own stream; end synchronises the device and returns one row per kernel
+ * family: launches, summed duration, summed algorithmic bytes (every operand of
+ * a launch counted once) and floating-point operations.  max_launches bounds the
+ * event pool; exceeding it makes end return FTP_ERR_ARG with partial rows.
+ * Process-wide, not thread-safe, and the event records slow small steps down. */
+typedef struct {
+  char name[48];
+  int64_t launches;
+  double total_ms, alg_bytes, flops;
+} ftp_ktrace_row;
+int ftp_ktrace_begin(int max_launches);
+int ftp_ktrace_end(ftp_ktrace_row* rows, int max_rows, int* n_rows);
+
 #ifdef __cplusplus
 }
 #endif

@@ -30,6 +30,11 @@ class UnitDesc(C.Structure):
                 ("kind", "cin", "cout", "kh", "kw", "stride", "pad_h", "pad_w", "expand", "act")]
 
 
+class KtraceRow(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("launches", C.c_int64), ("total_ms", C.c_double),
+                ("alg_bytes", C.c_double), ("flops", C.c_double)]
+
+
 class Sgd(C.Structure):
     _fields_ = [("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float)]
 
@@ -78,6 +83,8 @@ _SIGS = {
     "ftp_profile_layers": (_i, [_vp, _i, _i, _dp, C.POINTER(C.c_int64), _vp]),
     "ftp_solve_partition": (_i, [_dp, _i, _dp, _i, _dp, _dp, C.POINTER(C.c_int32), _dp]),
     "ftp_estimate_capacity": (_i, [C.c_double, _dp, _i, _i, _i, _dp]),
+    "ftp_ktrace_begin": (_i, [_i]),
+    "ftp_ktrace_end": (_i, [C.POINTER(KtraceRow), _i, C.POINTER(_i)]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _f = getattr(lib, _name)
@@ -254,3 +261,17 @@ def estimate_capacity(stage_time, layer_costs, start, end):
     out = C.c_double()
     _chk(lib.ftp_estimate_capacity(stage_time, cp, c.size, start, end, C.byref(out)))
     return out.value
+
+
+# ---- diagnostics ---------------------------------------------------------------------
+def ktrace_begin(max_launches=65536):
+    _chk(lib.ftp_ktrace_begin(max_launches))
+
+
+def ktrace_end():
+    """-> list of dicts: name, launches, total_ms, alg_bytes, flops (one per kernel family)."""
+    rows = (KtraceRow * 64)()
+    n = _i()
+    _chk(lib.ftp_ktrace_end(rows, 64, C.byref(n)))
+    return [dict(name=rows[i].name.decode(), launches=rows[i].launches, total_ms=rows[i].total_ms,
+                 alg_bytes=rows[i].alg_bytes, flops=rows[i].flops) for i in range(n.value)]

@@ -16,6 +16,7 @@ SOURCES = [
     ("k_conv.hip", ["-x", "hip"]),
     ("k_gemm.hip", ["-x", "hip"]),
     ("stage.cpp", ["-x", "hip"]),
+    ("ktrace.cpp", ["-x", "hip"]),
     ("solver.cpp", ["-x", "c++", "-ffp-contract=off"]),
 ]
 
@@ -36,7 +37,7 @@ def _compile(item):
 
 def build(verbose=False):
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=5) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         for src, out in ex.map(_compile, SOURCES):
             if verbose and out.strip():
                 print(f"[{src}]\n{out}")

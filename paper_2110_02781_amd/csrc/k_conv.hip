@@ -26,6 +26,7 @@ __global__ void reduce_partials_k(const float* __restrict__ ws, int P, size_t QC
 
 void reduce_partials(hipStream_t st, const float* ws, int P, size_t QC, int C, size_t stride_q,
                      size_t stride_c, float* g) {
+  KScope ks(st, "reduce_partials", ((double)P + 2.0) * QC * 4, (double)P * QC);
   hipLaunchKernelGGL(reduce_partials_k, dim3((unsigned)((QC + 255) / 256)), dim3(256), 0, st, ws, P, QC, C,
                      stride_q, stride_c, g);
 }
@@ -93,6 +94,8 @@ void conv_direct_fwd(int dt, hipStream_t st, HView in, const void* w, const Conv
   size_t total = (size_t)g.N * g.Hout * g.Wout;
   size_t sm = (size_t)TC * g.Cin * g.Cout * sizeof(float);
   View v{in.z, in.scale, in.shift, in.act};
+  KScope ks(st, "conv_direct_fwd", ((double)g.N * g.Hin * g.Win * g.Cin + (double)total * g.Cout + (double)g.kh * g.kw * g.Cin * g.Cout) * (dt == 0 ? 4.0 : 2.0),
+            2.0 * total * g.Cout * g.kh * g.kw * g.Cin);
   FTP_DISPATCH(dt, hipLaunchKernelGGL(conv_direct_fwd_k<T>, dim3((unsigned)((total + PPB - 1) / PPB)),
                                       dim3(PPB * CGo), sm, st, v, (const T*)w, g, TC, PPB, (T*)z));
 }
@@ -132,6 +135,8 @@ __global__ void conv_direct_dgrad_k(const T* __restrict__ dz, const T* __restric
 
 void conv_direct_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvGeom& g, void* dIn) {
   size_t total = (size_t)g.N * g.Hin * g.Win * g.Cin;
+  KScope ks(st, "conv_direct_dgrad", ((double)total + (double)g.N * g.Hout * g.Wout * g.Cout) * (dt == 0 ? 4.0 : 2.0),
+            2.0 * g.N * g.Hout * g.Wout * g.Cout * g.kh * g.kw * g.Cin);
   FTP_DISPATCH(dt, hipLaunchKernelGGL(conv_direct_dgrad_k<T>, dim3((unsigned)((total + 255) / 256)), dim3(256),
                                       0, st, (const T*)dz, (const T*)w, g, (T*)dIn));
 }
@@ -185,8 +190,12 @@ void conv_direct_wgrad(int dt, hipStream_t st, const void* dz, HView in, const C
   int CGo = g.Cout / 8, KPB = 256 / CGo, K = g.kh * g.kw * g.Cin;
   if (KPB < 1) KPB = 1;
   View v{in.z, in.scale, in.shift, in.act};
-  FTP_DISPATCH(dt, hipLaunchKernelGGL(conv_direct_wgrad_k<T>, dim3(S, (K + KPB - 1) / KPB), dim3(KPB * CGo), 0,
-                                      st, (const T*)dz, v, g, KPB, ppc, ws));
+  {
+    KScope ks(st, "conv_direct_wgrad", ((double)g.N * g.Hin * g.Win * g.Cin + (double)g.N * g.Hout * g.Wout * g.Cout) * (dt == 0 ? 4.0 : 2.0) + (double)S * K * g.Cout * 4,
+              2.0 * g.N * g.Hout * g.Wout * g.Cout * K);
+    FTP_DISPATCH(dt, hipLaunchKernelGGL(conv_direct_wgrad_k<T>, dim3(S, (K + KPB - 1) / KPB), dim3(KPB * CGo), 0,
+                                        st, (const T*)dz, v, g, KPB, ppc, ws));
+  }
   reduce_partials(st, ws, S, (size_t)K * g.Cout, g.Cout, 1, (size_t)K, g_w);
 }
 
@@ -259,6 +268,7 @@ void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, 
   RowTile t = dw_tile(total, g.Cout);
   View v{in.z, in.scale, in.shift, in.act};
   size_t sm = (size_t)9 * t.W * 8 * sizeof(float);
+  KScope ks(st, "dw_fwd", ((double)g.N * g.Hin * g.Win * g.Cout + (double)total * g.Cout) * (dt == 0 ? 4.0 : 2.0), 18.0 * total * g.Cout);
   FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_fwd_k<T>, dim3(t.P, t.nslab), dim3(t.W * t.R), sm, st, v, (const T*)w, g,
                                       t.W, t.R, t.rows_per_block, (T*)z));
 }
@@ -308,6 +318,7 @@ void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvG
   size_t total = (size_t)g.N * g.Hin * g.Win;
   RowTile t = dw_tile(total, g.Cout);
   size_t sm = (size_t)9 * t.W * 8 * sizeof(float);
+  KScope ks(st, "dw_dgrad", ((double)total * g.Cout + (double)g.N * g.Hout * g.Wout * g.Cout) * (dt == 0 ? 4.0 : 2.0), 18.0 * g.N * g.Hout * g.Wout * g.Cout);
   FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_dgrad_k<T>, dim3(t.P, t.nslab), dim3(t.W * t.R), sm, st, (const T*)dz,
                                       (const T*)w, g, t.W, t.R, t.rows_per_block, (T*)dIn));
 }
@@ -393,8 +404,12 @@ void dw_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& 
   RowTile t = dw_wgrad_tile(g);
   View v{in.z, in.scale, in.shift, in.act};
   size_t sm = (size_t)24 * t.R * t.W * sizeof(float);
-  FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_wgrad_k<T>, dim3(t.P, t.nslab), dim3(t.W * t.R), sm, st, (const T*)dz, v,
-                                      g, t.W, t.R, t.rows_per_block, ws));
+  {
+    KScope ks(st, "dw_wgrad", ((double)g.N * g.Hin * g.Win * g.Cout + (double)g.N * g.Hout * g.Wout * g.Cout) * (dt == 0 ? 4.0 : 2.0) + (double)t.P * 9 * g.Cout * 4,
+              18.0 * g.N * g.Hout * g.Wout * g.Cout);
+    FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_wgrad_k<T>, dim3(t.P, t.nslab), dim3(t.W * t.R), sm, st, (const T*)dz, v,
+                                        g, t.W, t.R, t.rows_per_block, ws));
+  }
   reduce_partials(st, ws, t.P, (size_t)9 * g.Cout, g.Cout, 1, 9, g_w);
 }
 

@@ -78,6 +78,7 @@ __global__ void bn_stats_k(const T* __restrict__ z, size_t M, int C, int W, int 
 
 void bn_stats(int dt, hipStream_t st, const void* z, size_t M, int C, float* partial, int* P_out) {
   RowTile t = make_rowtile(M, C, kMaxPartials);
+  KScope ks(st, "bn_stats", (double)M * C * (dt == 0 ? 4.0 : 2.0), 3.0 * M * C);
   dim3 grid(t.P, t.nslab), block(t.W * t.R);
   size_t sm = (size_t)16 * t.R * t.W * sizeof(float);
   FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_stats_k<T>, grid, block, sm, st, (const T*)z, M, C, t.W, t.R,
@@ -136,6 +137,7 @@ __global__ void bn_finalize_k(const float* __restrict__ partial, int P, size_t M
 void bn_finalize(hipStream_t st, const float* partial, int P, size_t M, int C, const float* gamma,
                  const float* beta, float* mean, float* invstd, float* scale, float* shift,
                  float* run_mean, float* run_var, float eps, float momentum) {
+  KScope ks(st, "bn_finalize", (double)P * 2 * C * 4 + 8.0 * C * 4, 0);
   hipLaunchKernelGGL(bn_finalize_k, dim3((C + 15) / 16), dim3(256), 0, st, partial, P, M, C, gamma, beta,
                      mean, invstd, scale, shift, run_mean, run_var, eps, momentum);
 }
@@ -179,6 +181,7 @@ __global__ void bn_bwd_reduce_k(const T* __restrict__ dA, const T* __restrict__ 
 void bn_bwd_reduce(int dt, hipStream_t st, const void* dA, const void* z, size_t M, int C,
                    const float* scale, const float* shift, int act, float* partial, int* P_out) {
   RowTile t = make_rowtile(M, C, kMaxPartials);
+  KScope ks(st, "bn_bwd_reduce", 2.0 * M * C * (dt == 0 ? 4.0 : 2.0), 6.0 * M * C);
   dim3 grid(t.P, t.nslab), block(t.W * t.R);
   size_t sm = (size_t)16 * t.R * t.W * sizeof(float);
   FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_bwd_reduce_k<T>, grid, block, sm, st, (const T*)dA, (const T*)z, M,
@@ -212,6 +215,7 @@ __global__ void bn_bwd_finalize_k(const float* __restrict__ partial, int P, size
 
 void bn_bwd_finalize(hipStream_t st, const float* partial, int P, size_t M, int C, const float* gamma,
                      const float* mean, const float* invstd, float* g_gamma, float* g_beta, float* coef) {
+  KScope ks(st, "bn_bwd_finalize", (double)P * 2 * C * 4 + 10.0 * C * 4, 0);
   hipLaunchKernelGGL(bn_bwd_finalize_k, dim3((C + 15) / 16), dim3(256), 0, st, partial, P, M, C, gamma, mean,
                      invstd, g_gamma, g_beta, coef);
 }
@@ -247,6 +251,7 @@ static inline int flat_grid(size_t n, int block) {
 void bn_bwd_apply(int dt, hipStream_t st, const void* dA, const void* z, size_t M, int C,
                   const float* scale, const float* shift, int act, const float* coef, void* dz) {
   size_t nvec = M * (size_t)(C / 8);
+  KScope ks(st, "bn_bwd_apply", 3.0 * M * C * (dt == 0 ? 4.0 : 2.0), 6.0 * M * C);
   FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_bwd_apply_k<T>, dim3(flat_grid(nvec, 256)), dim3(256), 0, st,
                                       (const T*)dA, (const T*)z, nvec, C / 8, scale, shift, act, coef, (T*)dz));
 }
@@ -269,6 +274,7 @@ __global__ void bn_apply_k(View in, size_t nvec, int CG, const T* __restrict__ r
 
 void bn_apply(int dt, hipStream_t st, HView in, size_t M, int C, const void* res, void* out) {
   size_t nvec = M * (size_t)(C / 8);
+  KScope ks(st, "bn_apply", (res ? 3.0 : 2.0) * M * C * (dt == 0 ? 4.0 : 2.0), 3.0 * M * C);
   View v{in.z, in.scale, in.shift, in.act};
   FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_apply_k<T>, dim3(flat_grid(nvec, 256)), dim3(256), 0, st, v, nvec,
                                       C / 8, (const T*)res, (T*)out));
@@ -296,6 +302,7 @@ __global__ void gap_fwd_k(View in, int N, int HW, int CG, T* __restrict__ out) {
 void gap_fwd(int dt, hipStream_t st, HView in, int N, int HW, int C, void* out) {
   View v{in.z, in.scale, in.shift, in.act};
   int n = N * (C / 8);
+  KScope ks(st, "gap_fwd", ((double)N * HW * C + (double)N * C) * (dt == 0 ? 4.0 : 2.0), 3.0 * N * HW * C);
   FTP_DISPATCH(dt, hipLaunchKernelGGL(gap_fwd_k<T>, dim3((n + 127) / 128), dim3(128), 0, st, v, N, HW, C / 8,
                                       (T*)out));
 }
@@ -316,6 +323,7 @@ __global__ void gap_bwd_k(const T* __restrict__ dOut, size_t nvec, int HW, int C
 
 void gap_bwd(int dt, hipStream_t st, const void* dOut, int N, int HW, int C, void* dIn) {
   size_t nvec = (size_t)N * HW * (C / 8);
+  KScope ks(st, "gap_bwd", ((double)N * HW * C + (double)N * C) * (dt == 0 ? 4.0 : 2.0), 1.0 * N * HW * C);
   FTP_DISPATCH(dt, hipLaunchKernelGGL(gap_bwd_k<T>, dim3(flat_grid(nvec, 256)), dim3(256), 0, st,
                                       (const T*)dOut, nvec, HW, C / 8, (T*)dIn));
 }
@@ -366,6 +374,7 @@ __global__ void mean_rows_k(const float* __restrict__ row_loss, int B, float* __
 
 void softmax_ce(int dt, hipStream_t st, const void* logits, const int32_t* labels, int B, int classes,
                 float* row_loss, void* dlogits, float* loss) {
+  KScope ks(st, "softmax_ce", 2.0 * B * classes * (dt == 0 ? 4.0 : 2.0), 8.0 * B * classes);
   FTP_DISPATCH(dt, hipLaunchKernelGGL(softmax_ce_k<T>, dim3(B), dim3(256), 0, st, (const T*)logits, labels, B,
                                       classes, row_loss, (T*)dlogits));
   hipLaunchKernelGGL(mean_rows_k, dim3(1), dim3(256), 0, st, row_loss, B, loss);
@@ -381,6 +390,7 @@ __global__ void bias_grad_k(const T* __restrict__ d, int B, int Nout, float* __r
 }
 
 void bias_grad(int dt, hipStream_t st, const void* d, int B, int Nout, float* g_bias) {
+  KScope ks(st, "bias_grad", (double)B * Nout * (dt == 0 ? 4.0 : 2.0) + 8.0 * Nout, 1.0 * B * Nout);
   FTP_DISPATCH(dt, hipLaunchKernelGGL(bias_grad_k<T>, dim3((Nout + 127) / 128), dim3(128), 0, st,
                                       (const T*)d, B, Nout, g_bias));
 }
@@ -402,6 +412,7 @@ __global__ void sgd_update_k(float* __restrict__ w, float* __restrict__ g, float
 
 void sgd_update(hipStream_t st, float* w, float* g, float* v, void* w_lp, size_t n, float lr, float mu,
                 float wd) {
+  KScope ks(st, "sgd_update", (w_lp ? 26.0 : 24.0) * n, 6.0 * n);
   hipLaunchKernelGGL(sgd_update_k, dim3(flat_grid(n, 256)), dim3(256), 0, st, w, g, v, (bf16_t*)w_lp, n, lr,
                      mu, wd);
 }
@@ -412,6 +423,7 @@ __global__ void fill_zero_k(uint32_t* p, size_t n) {
 }
 
 void fill_zero(hipStream_t st, void* p, size_t bytes) {
+  KScope ks(st, "fill_zero", (double)bytes, 0);
   size_t n = (bytes + 3) / 4;  // buffers are allocated in multiples of 256 bytes
   hipLaunchKernelGGL(fill_zero_k, dim3(flat_grid(n, 256)), dim3(256), 0, st, (uint32_t*)p, n);
 }
@@ -423,6 +435,7 @@ __global__ void f32_to_storage_k(const float* __restrict__ src, T* __restrict__ 
 }
 
 void f32_to_storage(int dt, hipStream_t st, const float* src, void* dst, size_t n) {
+  KScope ks(st, "f32_to_storage", (4.0 + (dt == 0 ? 4.0 : 2.0)) * n, 0);
   FTP_DISPATCH(dt, hipLaunchKernelGGL(f32_to_storage_k<T>, dim3(flat_grid(n, 256)), dim3(256), 0, st, src,
                                       (T*)dst, n));
 }

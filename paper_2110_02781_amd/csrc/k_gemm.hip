@@ -227,6 +227,7 @@ void pw_fwd(int dt, hipStream_t st, HView av, const void* w, const float* bias, 
   a.x = av.z; a.y = w; a.view = View{av.z, av.scale, av.shift, av.act};
   a.bias = bias; a.out = z; a.M = M; a.K = K; a.N = N;
   a.itiles = (int)((M + BI - 1) / BI); a.jtiles = (N + BJ - 1) / BJ;
+  KScope ks(st, "pw_fwd", ((double)M * K + (double)M * N + (double)N * K) * (dt == 0 ? 4.0 : 2.0), 2.0 * M * K * N);
   launch<MODE_FWD>(dt, st, a, 1);
 }
 
@@ -235,6 +236,7 @@ void pw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const void*
   GemmArgs a{};
   a.x = dz; a.y = w; a.res = res; a.out = dA; a.M = M; a.K = K; a.N = N;
   a.itiles = (int)((M + BI - 1) / BI); a.jtiles = (K + BJ - 1) / BJ;
+  KScope ks(st, "pw_dgrad", ((double)M * K * (res ? 2.0 : 1.0) + (double)M * N + (double)N * K) * (dt == 0 ? 4.0 : 2.0), 2.0 * M * K * N);
   launch<MODE_DGRAD>(dt, st, a, 1);
 }
 
@@ -267,7 +269,10 @@ void pw_wgrad(int dt, hipStream_t st, const void* dz, HView av, size_t M, int K,
   a.x = dz; a.y = av.z; a.view = View{av.z, av.scale, av.shift, av.act};
   a.out = ws; a.M = M; a.K = K; a.N = N; a.mchunk = mc;
   a.itiles = (N + BI - 1) / BI; a.jtiles = (K + BJ - 1) / BJ;
-  launch<MODE_WGRAD>(dt, st, a, S);
+  {
+    KScope ks(st, "pw_wgrad", ((double)M * K + (double)M * N) * (dt == 0 ? 4.0 : 2.0) + (double)S * N * K * 4, 2.0 * M * K * N);
+    launch<MODE_WGRAD>(dt, st, a, S);
+  }
   reduce_partials(st, ws, S, (size_t)N * K, K, (size_t)K, 1, g_w);
 }
 

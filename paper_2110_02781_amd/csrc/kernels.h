@@ -9,6 +9,17 @@
 
 namespace ftp {
 
+// Optional per-launch timing (diagnostics for benchmarks): when tracing is on, a
+// KScope brackets one kernel launch with two HIP events on the launch stream and
+// records the kernel family, the bytes the launch must move at least (each operand
+// once) and its floating-point operations.
+struct KScope {
+  KScope(hipStream_t st, const char* name, double alg_bytes, double flops);
+  ~KScope();
+  int slot;
+  hipStream_t st;
+};
+
 struct HView {  // same layout as the device-side View
   const void* z;
   const float* scale;

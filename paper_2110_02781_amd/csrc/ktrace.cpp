@@ -1,0 +1,81 @@
+// Per-launch kernel timing behind ftp_ktrace_begin / ftp_ktrace_end.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "../../include/ftp.h"
+#include "kernels.h"
+
+void ftp_set_error(const char* fmt, ...);
+
+namespace {
+struct Rec { const char* name; double bytes, flops; hipEvent_t e0, e1; };
+struct Trace {
+  bool on = false;
+  std::vector<Rec> recs;
+  size_t used = 0;
+  bool overflow = false;
+} g_trace;
+}  // namespace
+
+namespace ftp {
+KScope::KScope(hipStream_t s, const char* name, double alg_bytes, double flops) : slot(-1), st(s) {
+  if (!g_trace.on) return;
+  if (g_trace.used >= g_trace.recs.size()) { g_trace.overflow = true; return; }
+  slot = (int)g_trace.used++;
+  Rec& r = g_trace.recs[slot];
+  r.name = name; r.bytes = alg_bytes; r.flops = flops;
+  (void)hipEventRecord(r.e0, st);
+}
+KScope::~KScope() {
+  if (slot >= 0) (void)hipEventRecord(g_trace.recs[slot].e1, st);
+}
+}  // namespace ftp
+
+static void trace_release() {
+  for (auto& r : g_trace.recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+  g_trace.recs.clear();
+  g_trace.used = 0;
+  g_trace.on = false;
+}
+
+extern "C" int ftp_ktrace_begin(int max_launches) {
+  if (max_launches < 1 || max_launches > (1 << 20)) { ftp_set_error("ktrace_begin: max_launches out of range"); return FTP_ERR_ARG; }
+  trace_release();
+  g_trace.recs.resize(max_launches);
+  for (auto& r : g_trace.recs) {
+    if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) {
+      ftp_set_error("ktrace_begin: hipEventCreate failed");
+      trace_release();
+      return FTP_ERR_HIP;
+    }
+  }
+  g_trace.overflow = false;
+  g_trace.on = true;
+  return FTP_OK;
+}
+
+extern "C" int ftp_ktrace_end(ftp_ktrace_row* rows, int max_rows, int* n_rows) {
+  if (!rows || !n_rows || max_rows < 1) { ftp_set_error("ktrace_end: bad argument"); return FTP_ERR_ARG; }
+  g_trace.on = false;
+  if (hipDeviceSynchronize() != hipSuccess) { ftp_set_error("ktrace_end: synchronize failed"); trace_release(); return FTP_ERR_HIP; }
+  std::map<std::string, ftp_ktrace_row> agg;
+  for (size_t i = 0; i < g_trace.used; ++i) {
+    Rec& r = g_trace.recs[i];
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, r.e0, r.e1) != hipSuccess) continue;
+    ftp_ktrace_row& row = agg[r.name];
+    if (row.launches == 0) { memset(&row, 0, sizeof(row)); strncpy(row.name, r.name, sizeof(row.name) - 1); }
+    row.launches += 1; row.total_ms += ms; row.alg_bytes += r.bytes; row.flops += r.flops;
+  }
+  int n = 0;
+  for (auto& kv : agg) { if (n < max_rows) rows[n++] = kv.second; }
+  *n_rows = n;
+  bool ovf = g_trace.overflow;
+  trace_release();
+  if (ovf) { ftp_set_error("ktrace_end: more launches than max_launches; rows are incomplete"); return FTP_ERR_ARG; }
+  return FTP_OK;
+}
