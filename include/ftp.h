@@ -194,7 +194,9 @@ int ftp_estimate_capacity(double stage_time, const double* layer_costs, int L, i
  * on its own stream; end synchronises the device and returns one row per kernel
  * family: launches, summed duration, summed algorithmic bytes (every operand of
  * a launch counted once) and floating-point operations.  max_launches bounds the
- * event pool; exceeding it makes end return FTP_ERR_ARG with partial rows.
+ * event pool; exceeding it makes end return FTP_ERR_ARG with partial rows.  A
+ * negative max_launches (pool size = its magnitude) splits the rows further by
+ * problem shape: the name then reads "family d0 d1 d2" (GEMMs: M K N).
  * Process-wide, not thread-safe, and the event records slow small steps down. */
 typedef struct {
   char name[48];

@@ -270,8 +270,8 @@ def ktrace_begin(max_launches=65536):
 
 def ktrace_end():
     """-> list of dicts: name, launches, total_ms, alg_bytes, flops (one per kernel family)."""
-    rows = (KtraceRow * 64)()
+    rows = (KtraceRow * 512)()
     n = _i()
-    _chk(lib.ftp_ktrace_end(rows, 64, C.byref(n)))
+    _chk(lib.ftp_ktrace_end(rows, 512, C.byref(n)))
     return [dict(name=rows[i].name.decode(), launches=rows[i].launches, total_ms=rows[i].total_ms,
                  alg_bytes=rows[i].alg_bytes, flops=rows[i].flops) for i in range(n.value)]

@@ -11,13 +11,14 @@ typedef uint16_t bf16_t;  // raw bfloat16 bits
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 
-// round to nearest even; NaN stays NaN
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+// round to nearest even in hardware (v_cvt_pk_bf16_f32 converts two floats per instruction)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
+  f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
 
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(bf16_t v) { return bf16_to_f32(v); }
@@ -47,26 +48,42 @@ __device__ __forceinline__ void store8(float* p, const float v[8]) {
 }
 __device__ __forceinline__ void store8(bf16_t* p, const float v[8]) {
   uint4 r;
-  r.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-  r.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
-  r.z = (uint32_t)f32_to_bf16(v[4]) | ((uint32_t)f32_to_bf16(v[5]) << 16);
-  r.w = (uint32_t)f32_to_bf16(v[6]) | ((uint32_t)f32_to_bf16(v[7]) << 16);
+  r.x = f32x2_to_bf16x2(v[0], v[1]);
+  r.y = f32x2_to_bf16x2(v[2], v[3]);
+  r.z = f32x2_to_bf16x2(v[4], v[5]);
+  r.w = f32x2_to_bf16x2(v[6], v[7]);
   *reinterpret_cast<uint4*>(p) = r;
+}
+
+// raw 8-element vector as loaded from global memory
+template <typename T> struct Raw;
+template <> struct Raw<float> { float4 a, b; };
+template <> struct Raw<bf16_t> { uint4 a; };
+
+__device__ __forceinline__ void raw_load(Raw<float>& r, const float* p) {
+  r.a = *reinterpret_cast<const float4*>(p);
+  r.b = *reinterpret_cast<const float4*>(p + 4);
+}
+__device__ __forceinline__ void raw_load(Raw<bf16_t>& r, const bf16_t* p) { r.a = *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ void raw_unpack(const Raw<float>& r, float v[8]) {
+  v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w; v[4] = r.b.x; v[5] = r.b.y; v[6] = r.b.z; v[7] = r.b.w;
+}
+__device__ __forceinline__ void raw_unpack(const Raw<bf16_t>& r, float v[8]) {
+  v[0] = __uint_as_float(r.a.x << 16); v[1] = __uint_as_float(r.a.x & 0xffff0000u);
+  v[2] = __uint_as_float(r.a.y << 16); v[3] = __uint_as_float(r.a.y & 0xffff0000u);
+  v[4] = __uint_as_float(r.a.z << 16); v[5] = __uint_as_float(r.a.z & 0xffff0000u);
+  v[6] = __uint_as_float(r.a.w << 16); v[7] = __uint_as_float(r.a.w & 0xffff0000u);
 }
 
 enum { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2 };
 
-__device__ __forceinline__ float act_apply(float y, int act) {
-  if (act == ACT_RELU) return fmaxf(y, 0.f);
-  if (act == ACT_RELU6) return fminf(fmaxf(y, 0.f), 6.f);
-  return y;
-}
-// derivative is 1 strictly inside the linear region
-__device__ __forceinline__ float act_mask(float y, int act) {
-  if (act == ACT_RELU) return y > 0.f ? 1.f : 0.f;
-  if (act == ACT_RELU6) return (y > 0.f && y < 6.f) ? 1.f : 0.f;
-  return 1.f;
-}
+// Every activation here is a clamp to [lo, hi]: none = (-inf, inf), ReLU = [0, inf), ReLU6 = [0, 6].
+// One v_med3_f32 applies it; the derivative is 1 strictly inside the interval.
+__device__ __forceinline__ float act_lo(int act) { return act == ACT_NONE ? -INFINITY : 0.f; }
+__device__ __forceinline__ float act_hi(int act) { return act == ACT_RELU6 ? 6.f : INFINITY; }
+__device__ __forceinline__ float clamp_act(float y, float lo, float hi) { return __builtin_amdgcn_fmed3f(y, lo, hi); }
+__device__ __forceinline__ float act_apply(float y, int act) { return clamp_act(y, act_lo(act), act_hi(act)); }
+__device__ __forceinline__ float act_mask(float y, int act) { return (y > act_lo(act) && y < act_hi(act)) ? 1.f : 0.f; }
 
 // A tensor as its consumer sees it: value(m, c) = act(scale[c] * z[m][c] + shift[c]),
 // rounded to the storage type (what a materialised BatchNorm+activation output
@@ -94,8 +111,9 @@ __device__ __forceinline__ void view_load8(const View& v, size_t idx, int c, flo
     float s[8], b[8];
     load8(v.scale + c, s);
     load8(v.shift + c, b);
+    const float lo = act_lo(v.act), hi = act_hi(v.act);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) out[e] = round_to<T>(act_apply(fmaf(out[e], s[e], b[e]), v.act));
+    for (int e = 0; e < 8; ++e) out[e] = round_to<T>(clamp_act(fmaf(out[e], s[e], b[e]), lo, hi));
   }
 }
 

@@ -157,6 +157,7 @@ __global__ void bn_bwd_reduce_k(const T* __restrict__ dA, const T* __restrict__ 
     float sc[8], sh[8];
     load8(scale + cg * 8, sc);
     load8(shift + cg * 8, sh);
+    const float lo = act_lo(act), hi = act_hi(act);
     size_t m0 = (size_t)blockIdx.x * rpb, m1 = m0 + rpb < M ? m0 + rpb : M;
     for (size_t m = m0 + ty; m < m1; m += R) {
       float d[8], v[8];
@@ -164,7 +165,8 @@ __global__ void bn_bwd_reduce_k(const T* __restrict__ dA, const T* __restrict__ 
       load8(z + m * C + cg * 8, v);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        float dy = d[e] * act_mask(fmaf(v[e], sc[e], sh[e]), act);
+        float y = fmaf(v[e], sc[e], sh[e]);
+        float dy = (y > lo && y < hi) ? d[e] : 0.f;
         acc[e] += dy;
         acc[8 + e] = fmaf(dy, v[e], acc[8 + e]);
       }
@@ -225,6 +227,7 @@ __global__ void bn_bwd_apply_k(const T* __restrict__ dA, const T* __restrict__ z
                                const float* __restrict__ scale, const float* __restrict__ shift, int act,
                                const float* __restrict__ coef, T* __restrict__ dz) {
   int C = CG * 8;
+  const float lo = act_lo(act), hi = act_hi(act);
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (size_t)gridDim.x * blockDim.x) {
     int c = (int)(i % CG) * 8;
     float d[8], v[8], sc[8], sh[8], k1[8], k2[8], k3[8], o[8];
@@ -234,7 +237,8 @@ __global__ void bn_bwd_apply_k(const T* __restrict__ dA, const T* __restrict__ z
     load8(coef + c, k1); load8(coef + C + c, k2); load8(coef + 2 * C + c, k3);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      float dy = d[e] * act_mask(fmaf(v[e], sc[e], sh[e]), act);
+      float y = fmaf(v[e], sc[e], sh[e]);
+      float dy = (y > lo && y < hi) ? d[e] : 0.f;
       o[e] = fmaf(k1[e], dy, fmaf(k2[e], v[e], k3[e]));
     }
     store8(dz + i * 8, o);

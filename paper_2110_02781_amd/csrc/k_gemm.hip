@@ -7,10 +7,20 @@
 //             the pixel range split over blocks into fp32 partials summed in a fixed order)
 // A' is read through a View (the producer's BatchNorm + activation applied on load).
 //
-// Block = 256 threads = 4 wavefronts, tile 128 (i) x 64 (j), reduction chunks of
-// 32 staged through LDS in "r contiguous" layout; each wavefront owns a 32 x 64
-// strip = two 32x32 MFMA accumulators.  bfloat16 uses v_mfma_f32_32x32x16_bf16
-// (8 consecutive r per lane), float uses v_mfma_f32_32x32x2_f32 (true fp32).
+// These GEMMs stream a tall activation matrix once against a small weight matrix,
+// so they are HBM-bound; the kernel is built around that:
+//   * a block owns one 64-wide column tile and walks a contiguous range of row
+//     tiles, so weights stay in L2 and per-column BatchNorm sums accumulate in
+//     registers over the whole range (one partial per block, fixed order);
+//   * the next reduction chunk is fetched from HBM into registers while the
+//     current one is multiplied out of LDS (software pipeline over a flat
+//     (row tile, chunk) sequence);
+//   * results leave through an LDS copy of the tile so that every global store is a
+//     16/32-byte vector of consecutive channels.
+// Two tile shapes: 128 x 64 with the four wavefronts splitting the rows (tall
+// problems), and 32 x 64 with the four wavefronts splitting a 128-long reduction
+// chunk (short problems: few rows, long reductions; keeps all CUs busy).
+// bfloat16 uses v_mfma_f32_32x32x16_bf16, float uses v_mfma_f32_32x32x2_f32.
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -19,12 +29,15 @@ namespace ftp {
 typedef float f16v __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-enum { BI = 128, BJ = 64, BR = 32 };
+enum { BJ = 64, CLD = BJ + 4 };
 enum { MODE_FWD = 0, MODE_DGRAD = 1, MODE_WGRAD = 2 };
 
-template <typename T> struct Lds;
-template <> struct Lds<float> { enum { LD = BR + 4 }; };
-template <> struct Lds<bf16_t> { enum { LD = BR + 8 }; };
+template <bool SMALL> struct Shape {
+  enum { TI = SMALL ? 32 : 128, CH = SMALL ? 128 : 32 };
+};
+template <typename T> struct Pad;
+template <> struct Pad<float> { enum { V = 4 }; };
+template <> struct Pad<bf16_t> { enum { V = 8 }; };
 
 struct GemmArgs {
   const void* x;     // dZ (dgrad, wgrad) or A (fwd; through view)
@@ -33,113 +46,136 @@ struct GemmArgs {
   const float* bias; // fwd
   const void* res;   // dgrad: added to the result
   void* out;         // T (fwd, dgrad) or float partials (wgrad)
+  float* stats;      // fwd: partial[nranges][2][N] column sums of the stored output, or nullptr
   size_t M;
   int K, N;
   int jtiles, itiles;
+  int nranges;       // fwd/dgrad: row-tile ranges; wgrad: splits of the pixel range
+  int tiles_per_range;
   size_t mchunk;     // wgrad: pixels per split
 };
 
-__device__ __forceinline__ void lds_put8(float* dst, const float v[8]) { store8(dst, v); }
-__device__ __forceinline__ void lds_put8(bf16_t* dst, const float v[8]) { store8(dst, v); }
+// One operand tile: ROWS (i or j) x CH (r).  RC = source is r-contiguous (element (i,r) at
+// src[i*ld + r]); otherwise i-contiguous (element (i,r) at src[r*ld + i]) and transposed on the
+// way into LDS.  The view prologue indexes scale/shift by the channel, which is r for RC
+// sources and i for the others.
+// PERM stores tile row n at LDS row (n & 1) * 32 + (n >> 1) (64-row tiles only), so that the two
+// MFMA column sub-tiles of a lane are the adjacent columns 2*lane and 2*lane+1.
+__device__ __forceinline__ int perm64(int n) { return ((n & 1) << 5) | (n >> 1); }
 
-// ---- tile loaders ---------------------------------------------------------------
-// "r contiguous" source: element (i, r) at src[i * ld + r]; rows valid < nrow, r valid < nr
-template <typename T, int ROWS, bool USE_VIEW>
-__device__ __forceinline__ void load_tile_rc(T* lds, const T* __restrict__ src, size_t ld, size_t row0,
-                                             size_t nrow, size_t r0, size_t nr, const View& vw) {
-  constexpr int LD = Lds<T>::LD;
-  constexpr int NVEC = ROWS * (BR / 8);
-  const bool vec_ok = (ld % 8) == 0;
-  for (int v = threadIdx.x; v < NVEC; v += 256) {
-    int i = v / (BR / 8), rv = v % (BR / 8);
-    size_t row = row0 + i, r = r0 + (size_t)rv * 8;
-    float val[8];
-    if (row < nrow && r + 8 <= nr && vec_ok) {
-      load8(src + row * ld + r, val);
-      if (USE_VIEW && vw.scale) {
-        float s[8], b[8];
-        load8(vw.scale + r, s);
-        load8(vw.shift + r, b);
+template <typename T, int ROWS, int CH, bool RC, bool USE_VIEW, bool PERM = false>
+struct TileLoader {
+  enum { NVEC = ROWS * CH / 8, PER = (NVEC + 255) / 256, LD = CH + Pad<T>::V };
+  Raw<T> raw[PER];
+  unsigned ok;      // bit q: raw[q] holds a full in-bounds vector
+
+  __device__ __forceinline__ void coords(int v, int& i, int& r) const {
+    if (RC) { i = v / (CH / 8); r = (v % (CH / 8)) * 8; }
+    else { r = v / (ROWS / 8); i = (v % (ROWS / 8)) * 8; }
+  }
+
+  __device__ __forceinline__ void fetch(const T* __restrict__ src, size_t ld, size_t i0, size_t ni, size_t r0,
+                                        size_t nr) {
+    ok = 0;
+    const bool vec_ok = (ld % 8) == 0;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) val[e] = act_apply(fmaf(val[e], s[e], b[e]), vw.act);
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float x = 0.f;
-        if (row < nrow && r + e < nr) {
-          x = to_f32(src[row * ld + r + e]);
-          if (USE_VIEW && vw.scale) x = act_apply(fmaf(x, vw.scale[r + e], vw.shift[r + e]), vw.act);
-        }
-        val[e] = x;
+    for (int q = 0; q < PER; ++q) {
+      int v = threadIdx.x + q * 256;
+      if (v >= NVEC) break;
+      int i, r;
+      coords(v, i, r);
+      size_t gi = i0 + i, gr = r0 + r;
+      bool full = vec_ok && (RC ? (gi < ni && gr + 8 <= nr) : (gr < nr && gi + 8 <= ni));
+      if (full) {
+        raw_load(raw[q], RC ? src + gi * ld + gr : src + gr * ld + gi);
+        ok |= 1u << q;
       }
     }
-    lds_put8(lds + i * LD + rv * 8, val);
   }
-}
 
-// "i contiguous" source: element (i, r) at src[r * ld + i]  (transposed on the way into LDS)
-template <typename T, int ROWS, bool USE_VIEW>
-__device__ __forceinline__ void load_tile_ic(T* lds, const T* __restrict__ src, size_t ld, size_t i0,
-                                             size_t ni, size_t r0, size_t nr, const View& vw) {
-  constexpr int LD = Lds<T>::LD;
-  constexpr int NVEC = (ROWS / 8) * BR;
-  const bool vec_ok = (ld % 8) == 0;
-  for (int v = threadIdx.x; v < NVEC; v += 256) {
-    int r = v / (ROWS / 8), iv = v % (ROWS / 8);
-    size_t rr = r0 + r, ii = i0 + (size_t)iv * 8;
-    float val[8];
-    if (rr < nr && ii + 8 <= ni && vec_ok) {
-      load8(src + rr * ld + ii, val);
-      if (USE_VIEW && vw.scale) {
-        float s[8], b[8];
-        load8(vw.scale + ii, s);
-        load8(vw.shift + ii, b);
+  __device__ __forceinline__ void commit(T* lds, const T* __restrict__ src, size_t ld, size_t i0, size_t ni,
+                                         size_t r0, size_t nr, const View& vw) const {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) val[e] = act_apply(fmaf(val[e], s[e], b[e]), vw.act);
-      }
-    } else {
+    for (int q = 0; q < PER; ++q) {
+      int v = threadIdx.x + q * 256;
+      if (v >= NVEC) break;
+      int i, r;
+      coords(v, i, r);
+      size_t gi = i0 + i, gr = r0 + r;
+      float val[8];
+      size_t ch = RC ? gr : gi;      // first channel of the vector
+      if (ok & (1u << q)) {
+        raw_unpack(raw[q], val);
+      } else {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float x = 0.f;
-        if (rr < nr && ii + e < ni) {
-          x = to_f32(src[rr * ld + ii + e]);
-          if (USE_VIEW && vw.scale) x = act_apply(fmaf(x, vw.scale[ii + e], vw.shift[ii + e]), vw.act);
+        for (int e = 0; e < 8; ++e) {
+          size_t ei = RC ? gi : gi + e, er = RC ? gr + e : gr;
+          val[e] = (ei < ni && er < nr) ? to_f32(RC ? src[ei * ld + er] : src[er * ld + ei]) : 0.f;
         }
-        val[e] = x;
+      }
+      if (USE_VIEW && vw.scale) {
+        if (ok & (1u << q)) {          // whole vector in range: channels ch .. ch+7 exist
+          float sc[8], sh[8];
+          load8(vw.scale + ch, sc);
+          load8(vw.shift + ch, sh);
+          const float lo = act_lo(vw.act), hi = act_hi(vw.act);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) val[e] = clamp_act(fmaf(val[e], sc[e], sh[e]), lo, hi);
+        } else {
+          size_t nch = RC ? nr : ni;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            // out-of-range elements must stay exactly zero
+            bool in = RC ? (gi < ni && gr + e < nr) : (gr < nr && gi + e < ni);
+            if (in && ch + e < nch) val[e] = act_apply(fmaf(val[e], vw.scale[ch + e], vw.shift[ch + e]), vw.act);
+          }
+        }
+      }
+      if (RC) {
+        store8(lds + (PERM ? perm64(i) : i) * LD + r, val);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) lds[(PERM ? perm64(i + e) : i + e) * LD + r] = from_f32<T>(val[e]);
       }
     }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) lds[(iv * 8 + e) * LD + r] = from_f32<T>(val[e]);
   }
+};
+
+// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Renumbering them so that
+// consecutive logical ids share an XCD keeps the column tiles of one row range (which re-read the
+// same activations) behind one L2.
+__device__ __forceinline__ int xcd_logical_block() {
+  const int nb = gridDim.x, b = blockIdx.x;
+  const int x = b & 7, idx = b >> 3, q = nb >> 3, rem = nb & 7;
+  return x * q + (x < rem ? x : rem) + idx;
 }
 
-// ---- MFMA over one staged chunk ----------------------------------------------------
-__device__ __forceinline__ void mma_chunk(const bf16_t* xs, const bf16_t* ys, int wave, int lane, f16v acc[2]) {
-  constexpr int LD = Lds<bf16_t>::LD;
-  const int i = wave * 32 + (lane & 31), h = lane >> 5;
+// ---- MFMA over one staged chunk of 32 reduction elements starting at column c0 -------
+__device__ __forceinline__ void mma32(const bf16_t* xs, const bf16_t* ys, int LD, int irow, int lane, int c0,
+                                      f16v acc[2]) {
+  const int h = lane >> 5, jl = lane & 31;
 #pragma unroll
-  for (int ks = 0; ks < BR / 16; ++ks) {
-    uint4 a = *reinterpret_cast<const uint4*>(xs + i * LD + ks * 16 + h * 8);
+  for (int ks = 0; ks < 2; ++ks) {
+    uint4 a = *reinterpret_cast<const uint4*>(xs + irow * LD + c0 + ks * 16 + h * 8);
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-      uint4 b = *reinterpret_cast<const uint4*>(ys + (t * 32 + (lane & 31)) * LD + ks * 16 + h * 8);
+      uint4 b = *reinterpret_cast<const uint4*>(ys + (t * 32 + jl) * LD + c0 + ks * 16 + h * 8);
       acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                        __builtin_bit_cast(bf16x8, b), acc[t], 0, 0, 0);
     }
   }
 }
 
-__device__ __forceinline__ void mma_chunk(const float* xs, const float* ys, int wave, int lane, f16v acc[2]) {
-  constexpr int LD = Lds<float>::LD;
-  const int i = wave * 32 + (lane & 31), h = lane >> 5;
+__device__ __forceinline__ void mma32(const float* xs, const float* ys, int LD, int irow, int lane, int c0,
+                                      f16v acc[2]) {
+  const int h = lane >> 5, jl = lane & 31;
 #pragma unroll
-  for (int q = 0; q < BR / 8; ++q) {
+  for (int q = 0; q < 4; ++q) {
     // lane half h holds r = 8q+4h .. +3; instruction t multiplies r = 8q+t and 8q+4+t
-    float4 a = *reinterpret_cast<const float4*>(xs + i * LD + q * 8 + h * 4);
+    float4 a = *reinterpret_cast<const float4*>(xs + irow * LD + c0 + q * 8 + h * 4);
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-      float4 b = *reinterpret_cast<const float4*>(ys + (t * 32 + (lane & 31)) * LD + q * 8 + h * 4);
+      float4 b = *reinterpret_cast<const float4*>(ys + (t * 32 + jl) * LD + c0 + q * 8 + h * 4);
       acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc[t], 0, 0, 0);
       acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc[t], 0, 0, 0);
       acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc[t], 0, 0, 0);
@@ -148,23 +184,54 @@ __device__ __forceinline__ void mma_chunk(const float* xs, const float* ys, int 
   }
 }
 
-template <typename T, int MODE>
+template <typename T, int MODE, bool SMALL>
 __global__ __launch_bounds__(256) void pw_gemm_k(GemmArgs p) {
-  constexpr int LD = Lds<T>::LD;
-  __shared__ __attribute__((aligned(16))) T xs[BI * LD];
-  __shared__ __attribute__((aligned(16))) T ys[BJ * LD];
+  constexpr int TI = Shape<SMALL>::TI, CH = Shape<SMALL>::CH;
+  constexpr int LD = CH + Pad<T>::V;
+  constexpr int STAGE_BYTES = (TI + BJ) * LD * (int)sizeof(T);
+  constexpr int CT_BYTES = (SMALL ? 4 : 1) * TI * CLD * 4;
+  constexpr int SMEM = STAGE_BYTES > CT_BYTES ? STAGE_BYTES : CT_BYTES;
+  __shared__ __attribute__((aligned(16))) char smem[SMEM];
+  T* xs = reinterpret_cast<T*>(smem);
+  T* ys = xs + TI * LD;
+  float* ct = reinterpret_cast<float*>(smem);   // aliases the staging buffers between tiles
+
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int tile = blockIdx.x % (p.jtiles * p.itiles);
-  const int split = blockIdx.x / (p.jtiles * p.itiles);
-  const int jt = tile % p.jtiles, it = tile / p.jtiles;
-  const size_t i0 = (size_t)it * BI, j0 = (size_t)jt * BJ;
+  const int lb = xcd_logical_block();
+  const int jt = lb % p.jtiles;
+  const int range = lb / p.jtiles;
+  const size_t j0 = (size_t)jt * BJ;
   const T* X = reinterpret_cast<const T*>(p.x);
   const T* Y = reinterpret_cast<const T*>(p.y);
 
+  // reduction extent and the row tiles this block walks
   size_t rbeg = 0, rend;
-  if (MODE == MODE_FWD) rend = p.K;
-  else if (MODE == MODE_DGRAD) rend = p.N;
-  else { rbeg = (size_t)split * p.mchunk; rend = rbeg + p.mchunk < p.M ? rbeg + p.mchunk : p.M; }
+  int it_beg, it_end;
+  if (MODE == MODE_WGRAD) {
+    // range = (row tile, split): all row tiles are walked by different blocks, the split picks the pixels
+    const int split = range / p.itiles;
+    it_beg = range % p.itiles; it_end = it_beg + 1;
+    rbeg = (size_t)split * p.mchunk;
+    rend = rbeg + p.mchunk < p.M ? rbeg + p.mchunk : p.M;
+  } else {
+    rend = MODE == MODE_FWD ? p.K : p.N;
+    it_beg = range * p.tiles_per_range;
+    it_end = it_beg + p.tiles_per_range < p.itiles ? it_beg + p.tiles_per_range : p.itiles;
+  }
+  const int nchunks = (int)((rend - rbeg + CH - 1) / CH);
+  const int nsteps = (it_end - it_beg) * nchunks;
+
+  // operand geometry: leading dimensions and extents
+  const size_t ldx = MODE == MODE_FWD ? p.K : p.N;
+  const size_t ldy = p.K;
+  const size_t ni = MODE == MODE_WGRAD ? (size_t)p.N : p.M;        // extent of i
+  const size_t nj = MODE == MODE_FWD ? (size_t)p.N : (size_t)p.K;  // extent of j
+
+  // forward: X = A' (r-contiguous, view), Y = W (r-contiguous)
+  // dgrad  : X = dZ (r-contiguous),       Y = W as (j=k, r=n)  (i-contiguous)
+  // wgrad  : X = dZ as (i=n, r=m),        Y = A' as (j=k, r=m) (both i-contiguous, view on Y)
+  TileLoader<T, TI, CH, MODE != MODE_WGRAD, MODE == MODE_FWD> lx;
+  TileLoader<T, BJ, CH, MODE == MODE_FWD, MODE == MODE_WGRAD> ly;
 
   f16v acc[2];
 #pragma unroll
@@ -172,90 +239,349 @@ __global__ __launch_bounds__(256) void pw_gemm_k(GemmArgs p) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
 
-  for (size_t r0 = rbeg; r0 < rend; r0 += BR) {
+  // output pass mapping: 8 column groups x 32 row lanes
+  const int ocg = threadIdx.x & 7, orl = threadIdx.x >> 3;
+  float ssum[8] = {0, 0, 0, 0, 0, 0, 0, 0}, ssq[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+
+  if (nsteps > 0) {
+    lx.fetch(X, ldx, (size_t)it_beg * TI, ni, rbeg, rend);
+    ly.fetch(Y, ldy, j0, nj, rbeg, rend);
+  }
+  for (int s = 0; s < nsteps; ++s) {
+    const int it = it_beg + s / nchunks, kc = s % nchunks;
+    const size_t i0 = (size_t)it * TI, r0 = rbeg + (size_t)kc * CH;
+    __syncthreads();                       // LDS free: previous multiply / output pass finished
+    lx.commit(xs, X, ldx, i0, ni, r0, rend, p.view);
+    ly.commit(ys, Y, ldy, j0, nj, r0, rend, p.view);
     __syncthreads();
-    if (MODE == MODE_FWD) {
-      load_tile_rc<T, BI, true>(xs, X, p.K, i0, p.M, r0, rend, p.view);     // A'[m][k]
-      load_tile_rc<T, BJ, false>(ys, Y, p.K, j0, p.N, r0, rend, p.view);    // W[n][k]
-    } else if (MODE == MODE_DGRAD) {
-      load_tile_rc<T, BI, false>(xs, X, p.N, i0, p.M, r0, rend, p.view);    // dZ[m][n]
-      load_tile_ic<T, BJ, false>(ys, Y, p.K, j0, p.K, r0, rend, p.view);    // W[n][k] as (j=k, r=n)
-    } else {
-      load_tile_ic<T, BI, false>(xs, X, p.N, i0, p.N, r0, rend, p.view);    // dZ[m][n] as (i=n, r=m)
-      load_tile_ic<T, BJ, true>(ys, Y, p.K, j0, p.K, r0, rend, p.view);     // A'[m][k] as (j=k, r=m)
+    if (s + 1 < nsteps) {                  // next chunk travels while this one is multiplied
+      const int it2 = it_beg + (s + 1) / nchunks, kc2 = (s + 1) % nchunks;
+      lx.fetch(X, ldx, (size_t)it2 * TI, ni, rbeg + (size_t)kc2 * CH, rend);
+      ly.fetch(Y, ldy, j0, nj, rbeg + (size_t)kc2 * CH, rend);
+    }
+    if (SMALL) mma32(xs, ys, LD, lane & 31, lane, wave * 32, acc);
+    else mma32(xs, ys, LD, wave * 32 + (lane & 31), lane, 0, acc);
+    if (kc + 1 < nchunks) continue;
+
+    // ---- tile finished: accumulators -> LDS tile -> vector stores ----
+    __syncthreads();                       // everyone is done reading the staging buffers
+    {
+      // register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32]
+      const int h = lane >> 5, jl = lane & 31;
+      float* base = SMALL ? ct + wave * TI * CLD : ct + wave * 32 * CLD;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          base[(8 * (r / 4) + 4 * h + (r % 4)) * CLD + t * 32 + jl] = acc[t][r];
+          acc[t][r] = 0.f;
+        }
     }
     __syncthreads();
-    mma_chunk(xs, ys, wave, lane, acc);
+    const size_t jg = j0 + ocg * 8;
+    const bool vec_out = (nj % 8) == 0;
+#pragma unroll
+    for (int q = 0; q < (SMALL ? 1 : 4); ++q) {
+      const int row = orl + q * 32;
+      const size_t ig = i0 + row;
+      if (ig >= ni || jg >= nj) continue;
+      float v[8];
+      {
+        const float* src = ct + row * CLD + ocg * 8;
+        float4 a = *reinterpret_cast<const float4*>(src), b = *reinterpret_cast<const float4*>(src + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+        if (SMALL) {
+#pragma unroll
+          for (int w = 1; w < 4; ++w) {
+            const float* s2 = src + w * TI * CLD;
+            float4 c = *reinterpret_cast<const float4*>(s2), d = *reinterpret_cast<const float4*>(s2 + 4);
+            v[0] += c.x; v[1] += c.y; v[2] += c.z; v[3] += c.w; v[4] += d.x; v[5] += d.y; v[6] += d.z; v[7] += d.w;
+          }
+        }
+      }
+      const bool full = vec_out && jg + 8 <= nj;
+      if (MODE == MODE_FWD) {
+        T* dst = reinterpret_cast<T*>(p.out) + ig * p.N + jg;
+        if (p.bias) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) if (jg + e < nj) v[e] += p.bias[jg + e];
+        }
+        if (full) store8(dst, v);
+        else for (int e = 0; e < 8 && jg + e < nj; ++e) dst[e] = from_f32<T>(v[e]);
+        if (p.stats) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            float sv = round_to<T>(v[e]);   // statistics of the values as stored
+            ssum[e] += sv;
+            ssq[e] = fmaf(sv, sv, ssq[e]);
+          }
+        }
+      } else if (MODE == MODE_DGRAD) {
+        T* dst = reinterpret_cast<T*>(p.out) + ig * p.K + jg;
+        if (p.res) {
+          const T* rs = reinterpret_cast<const T*>(p.res) + ig * p.K + jg;
+          if (full) {
+            float rv[8];
+            load8(rs, rv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += rv[e];
+          } else {
+            for (int e = 0; e < 8 && jg + e < nj; ++e) v[e] += to_f32(rs[e]);
+          }
+        }
+        if (full) store8(dst, v);
+        else for (int e = 0; e < 8 && jg + e < nj; ++e) dst[e] = from_f32<T>(v[e]);
+      } else {
+        const int split = range / p.itiles;
+        float* dst = reinterpret_cast<float*>(p.out) + ((size_t)split * p.N + ig) * p.K + jg;
+        if (full) store8(dst, v);
+        else for (int e = 0; e < 8 && jg + e < nj; ++e) dst[e] = v[e];
+      }
+    }
   }
 
-  // accumulator layout: register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32]
-  const int h = lane >> 5, jl = lane & 31;
-  const size_t ni = (MODE == MODE_WGRAD) ? (size_t)p.N : p.M;
-  const int nj = (MODE == MODE_FWD) ? p.N : p.K;
+  if (MODE == MODE_FWD && p.stats) {
+    // column sums over this block's rows: reduce the 32 row lanes through LDS, one partial per block
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(smem);      // [32][8 groups][16]
 #pragma unroll
-  for (int t = 0; t < 2; ++t) {
-    size_t j = j0 + t * 32 + jl;
-    if (j >= (size_t)nj) continue;
-    float bj = (MODE == MODE_FWD && p.bias) ? p.bias[j] : 0.f;
+    for (int e = 0; e < 8; ++e) {
+      red[(orl * 8 + ocg) * 16 + e] = ssum[e];
+      red[(orl * 8 + ocg) * 16 + 8 + e] = ssq[e];
+    }
+    __syncthreads();
+    if (threadIdx.x < 128) {
+      const int cg = threadIdx.x & 7, e = threadIdx.x >> 3;    // e in 0..15: 0-7 sums, 8-15 squares
+      float tot = 0.f;
+      for (int rl = 0; rl < 32; ++rl) tot += red[(rl * 8 + cg) * 16 + e];
+      const size_t j = j0 + cg * 8 + (e & 7);
+      if (j < (size_t)p.N) p.stats[((size_t)range * 2 + (e >> 3)) * p.N + j] = tot;
+    }
+  }
+}
+
+
+// ---- tall problems: 128 x 64 tiles, rows split over the four wavefronts ----------------
+// Double-buffered staging (one barrier per chunk); results go from the MFMA registers
+// straight to memory: with the permuted weight tile a lane owns columns 2l and 2l+1, so
+// each store instruction writes whole 128-byte (bfloat16) / 256-byte (float) row segments.
+__device__ __forceinline__ void store_pair(float* p, float a, float b) { *reinterpret_cast<float2*>(p) = make_float2(a, b); }
+__device__ __forceinline__ void store_pair(bf16_t* p, float a, float b) {
+  *reinterpret_cast<uint32_t*>(p) = f32x2_to_bf16x2(a, b);
+}
+__device__ __forceinline__ void load_pair(const float* p, float& a, float& b) { float2 v = *reinterpret_cast<const float2*>(p); a = v.x; b = v.y; }
+__device__ __forceinline__ void load_pair(const bf16_t* p, float& a, float& b) {
+  uint32_t v = *reinterpret_cast<const uint32_t*>(p);
+  a = __uint_as_float(v << 16); b = __uint_as_float(v & 0xffff0000u);
+}
+
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
+  constexpr int TI = 128, CH = 32;
+  constexpr int LD = CH + Pad<T>::V;
+  constexpr int BUF = (TI + BJ) * LD;
+  __shared__ __attribute__((aligned(16))) T smem[2 * BUF];
+  __shared__ float red[4][64][4];
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int lb = xcd_logical_block();
+  const int jt = lb % p.jtiles;
+  const int range = lb / p.jtiles;
+  const size_t j0 = (size_t)jt * BJ;
+  const T* X = reinterpret_cast<const T*>(p.x);
+  const T* Y = reinterpret_cast<const T*>(p.y);
+
+  size_t rbeg = 0, rend;
+  int it_beg, it_end, split = 0;
+  if (MODE == MODE_WGRAD) {
+    split = range / p.itiles;
+    it_beg = range % p.itiles; it_end = it_beg + 1;
+    rbeg = (size_t)split * p.mchunk;
+    rend = rbeg + p.mchunk < p.M ? rbeg + p.mchunk : p.M;
+  } else {
+    rend = MODE == MODE_FWD ? p.K : p.N;
+    it_beg = range * p.tiles_per_range;
+    it_end = it_beg + p.tiles_per_range < p.itiles ? it_beg + p.tiles_per_range : p.itiles;
+  }
+  const int nchunks = (int)((rend - rbeg + CH - 1) / CH);
+  const int nsteps = (it_end - it_beg) * nchunks;
+  const bool y_static = nchunks == 1;      // the weight tile never changes: stage it once per buffer
+
+  const size_t ldx = MODE == MODE_FWD ? p.K : p.N;
+  const size_t ldy = p.K;
+  const size_t ni = MODE == MODE_WGRAD ? (size_t)p.N : p.M;
+  const size_t nj = MODE == MODE_FWD ? (size_t)p.N : (size_t)p.K;
+  const size_t ldo = nj;                   // leading dimension of the output
+
+  TileLoader<T, TI, CH, MODE != MODE_WGRAD, MODE == MODE_FWD> lx;
+  TileLoader<T, BJ, CH, MODE == MODE_FWD, MODE == MODE_WGRAD, true> ly;
+
+  f16v acc[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+  float s0 = 0.f, s1 = 0.f, q0 = 0.f, q1 = 0.f;   // column sums / sums of squares of this lane's two columns
+
+  const int h = lane >> 5, jl = lane & 31;
+  const size_t jc = j0 + 2 * jl;                    // this lane's first column
+  const bool pair_ok = (ldo % 2) == 0 && jc + 1 < nj;
+  float b0 = 0.f, b1 = 0.f;
+  if (MODE == MODE_FWD && p.bias) {
+    if (jc < nj) b0 = p.bias[jc];
+    if (jc + 1 < nj) b1 = p.bias[jc + 1];
+  }
+
+  if (nsteps > 0) {
+    lx.fetch(X, ldx, (size_t)it_beg * TI, ni, rbeg, rend);
+    ly.fetch(Y, ldy, j0, nj, rbeg, rend);
+  }
+  for (int s = 0; s < nsteps; ++s) {
+    const int it = it_beg + s / nchunks, kc = s % nchunks;
+    const size_t i0 = (size_t)it * TI, r0 = rbeg + (size_t)kc * CH;
+    T* xs = smem + (s & 1) * BUF;
+    T* ys = xs + TI * LD;
+    lx.commit(xs, X, ldx, i0, ni, r0, rend, p.view);
+    if (!y_static || s < 2) ly.commit(ys, Y, ldy, j0, nj, r0, rend, p.view);
+    __syncthreads();
+    if (s + 1 < nsteps) {
+      const int it2 = it_beg + (s + 1) / nchunks, kc2 = (s + 1) % nchunks;
+      lx.fetch(X, ldx, (size_t)it2 * TI, ni, rbeg + (size_t)kc2 * CH, rend);
+      if (!y_static || s + 1 < 2) ly.fetch(Y, ldy, j0, nj, rbeg + (size_t)kc2 * CH, rend);
+    }
+    mma32(xs, ys, LD, wave * 32 + jl, lane, 0, acc);
+    if (kc + 1 < nchunks) continue;
+
+    // tile finished: register r of this lane is row 8*(r/4) + 4*h + r%4, columns jc (acc[0]) and jc+1 (acc[1])
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      size_t i = i0 + wave * 32 + 8 * (r / 4) + 4 * h + (r % 4);
-      if (i >= ni) continue;
-      float v = acc[t][r];
+      const size_t ig = i0 + wave * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+      float v0 = acc[0][r], v1 = acc[1][r];
+      acc[0][r] = 0.f; acc[1][r] = 0.f;
+      if (ig >= ni || jc >= nj) continue;
       if (MODE == MODE_FWD) {
-        reinterpret_cast<T*>(p.out)[i * p.N + j] = from_f32<T>(v + bj);
+        v0 += b0; v1 += b1;
+        T* dst = reinterpret_cast<T*>(p.out) + ig * ldo + jc;
+        if (pair_ok) store_pair(dst, v0, v1);
+        else { dst[0] = from_f32<T>(v0); if (jc + 1 < nj) dst[1] = from_f32<T>(v1); }
+        if (p.stats) {
+          float a = round_to<T>(v0), b = round_to<T>(v1);   // statistics of the values as stored
+          s0 += a; q0 = fmaf(a, a, q0); s1 += b; q1 = fmaf(b, b, q1);
+        }
       } else if (MODE == MODE_DGRAD) {
-        if (p.res) v += to_f32(reinterpret_cast<const T*>(p.res)[i * p.K + j]);
-        reinterpret_cast<T*>(p.out)[i * p.K + j] = from_f32<T>(v);
+        T* dst = reinterpret_cast<T*>(p.out) + ig * ldo + jc;
+        if (p.res) {
+          const T* rs = reinterpret_cast<const T*>(p.res) + ig * ldo + jc;
+          if (pair_ok) { float ra, rb; load_pair(rs, ra, rb); v0 += ra; v1 += rb; }
+          else { v0 += to_f32(rs[0]); if (jc + 1 < nj) v1 += to_f32(rs[1]); }
+        }
+        if (pair_ok) store_pair(dst, v0, v1);
+        else { dst[0] = from_f32<T>(v0); if (jc + 1 < nj) dst[1] = from_f32<T>(v1); }
       } else {
-        reinterpret_cast<float*>(p.out)[((size_t)split * p.N + i) * p.K + j] = v;
+        float* dst = reinterpret_cast<float*>(p.out) + ((size_t)split * p.N + ig) * ldo + jc;
+        if (pair_ok) store_pair(dst, v0, v1);
+        else { dst[0] = v0; if (jc + 1 < nj) dst[1] = v1; }
       }
+    }
+  }
+
+  if (MODE == MODE_FWD && p.stats) {
+    // one partial per block: sum the 8 (wave, half) contributions of every column in a fixed order
+    red[wave][lane][0] = s0; red[wave][lane][1] = s1; red[wave][lane][2] = q0; red[wave][lane][3] = q1;
+    __syncthreads();
+    if (threadIdx.x < 128) {
+      const int col = threadIdx.x & 63, sq = threadIdx.x >> 6;   // column within the tile; 0 = sum, 1 = squares
+      const int l = col >> 1, t = col & 1;
+      float tot = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) tot += red[w][l][2 * sq + t] + red[w][l + 32][2 * sq + t];
+      const size_t j = j0 + col;
+      if (j < (size_t)p.N) p.stats[((size_t)range * 2 + sq) * p.N + j] = tot;
     }
   }
 }
 
 template <int MODE>
-static void launch(int dt, hipStream_t st, const GemmArgs& a, int nsplit) {
-  unsigned grid = (unsigned)((size_t)a.jtiles * a.itiles * nsplit);
-  if (dt == 0) hipLaunchKernelGGL((pw_gemm_k<float, MODE>), dim3(grid), dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((pw_gemm_k<bf16_t, MODE>), dim3(grid), dim3(256), 0, st, a);
+static void launch(int dt, hipStream_t st, const GemmArgs& a, bool small) {
+  unsigned grid = (unsigned)((size_t)a.jtiles * a.nranges);
+  if (dt == 0) {
+    if (small) hipLaunchKernelGGL((pw_gemm_k<float, MODE, true>), dim3(grid), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((pw_gemm_rows_k<float, MODE>), dim3(grid), dim3(256), 0, st, a);
+  } else {
+    if (small) hipLaunchKernelGGL((pw_gemm_k<bf16_t, MODE, true>), dim3(grid), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((pw_gemm_rows_k<bf16_t, MODE>), dim3(grid), dim3(256), 0, st, a);
+  }
+}
+
+// Row-streaming passes (forward, dgrad): tile shape and the split of the row tiles into ranges.
+static void plan_rows(size_t M, int ncols, int R, GemmArgs* a, bool* small) {
+  a->jtiles = (ncols + BJ - 1) / BJ;
+  size_t big_tiles = (M + 127) / 128;
+  // short problems: too few 128-row tiles to fill 256 CUs and a reduction worth splitting
+  *small = big_tiles * a->jtiles < 96 && R >= 128;
+  int TI = *small ? 32 : 128;
+  a->itiles = (int)((M + TI - 1) / TI);
+  int want = (2048 + a->jtiles - 1) / a->jtiles;          // about 2048 blocks in flight
+  if (want > kMaxPartials) want = kMaxPartials;
+  if (want < 1) want = 1;
+  a->tiles_per_range = (a->itiles + want - 1) / want;
+  a->nranges = (a->itiles + a->tiles_per_range - 1) / a->tiles_per_range;
+}
+
+int pw_fwd_partials(size_t M, int K, int N) {
+  GemmArgs a{};
+  bool small;
+  plan_rows(M, N, K, &a, &small);
+  return a.nranges;
 }
 
 void pw_fwd(int dt, hipStream_t st, HView av, const void* w, const float* bias, size_t M, int K, int N,
-            void* z) {
+            void* z, float* stats, int* P_out) {
   GemmArgs a{};
   a.x = av.z; a.y = w; a.view = View{av.z, av.scale, av.shift, av.act};
-  a.bias = bias; a.out = z; a.M = M; a.K = K; a.N = N;
-  a.itiles = (int)((M + BI - 1) / BI); a.jtiles = (N + BJ - 1) / BJ;
-  KScope ks(st, "pw_fwd", ((double)M * K + (double)M * N + (double)N * K) * (dt == 0 ? 4.0 : 2.0), 2.0 * M * K * N);
-  launch<MODE_FWD>(dt, st, a, 1);
+  a.bias = bias; a.out = z; a.stats = stats; a.M = M; a.K = K; a.N = N;
+  bool small;
+  plan_rows(M, N, K, &a, &small);
+  if (P_out) *P_out = a.nranges;
+  KScope ks(st, "pw_fwd", ((double)M * K + (double)M * N + (double)N * K) * (dt == 0 ? 4.0 : 2.0), 2.0 * M * K * N, (long)M, K, N);
+  launch<MODE_FWD>(dt, st, a, small);
 }
 
 void pw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const void* res, size_t M, int K,
               int N, void* dA) {
   GemmArgs a{};
   a.x = dz; a.y = w; a.res = res; a.out = dA; a.M = M; a.K = K; a.N = N;
-  a.itiles = (int)((M + BI - 1) / BI); a.jtiles = (K + BJ - 1) / BJ;
-  KScope ks(st, "pw_dgrad", ((double)M * K * (res ? 2.0 : 1.0) + (double)M * N + (double)N * K) * (dt == 0 ? 4.0 : 2.0), 2.0 * M * K * N);
-  launch<MODE_DGRAD>(dt, st, a, 1);
+  bool small;
+  plan_rows(M, K, N, &a, &small);
+  KScope ks(st, "pw_dgrad", ((double)M * K * (res ? 2.0 : 1.0) + (double)M * N + (double)N * K) * (dt == 0 ? 4.0 : 2.0), 2.0 * M * K * N, (long)M, K, N);
+  launch<MODE_DGRAD>(dt, st, a, small);
 }
 
-static void wgrad_shape(size_t M, int K, int N, int* S, size_t* mchunk) {
-  size_t tiles = (size_t)((N + BI - 1) / BI) * ((K + BJ - 1) / BJ);
+// wgrad: output tiles (N x K) times splits of the pixel range
+static void plan_wgrad(size_t M, int K, int N, GemmArgs* a, bool* small) {
+  a->jtiles = (K + BJ - 1) / BJ;
+  *small = N <= 32;                         // few output rows: 32-row tiles waste less of the MFMA
+  int TI = *small ? 32 : 128;
+  int CH = *small ? 128 : 32;
+  a->itiles = (N + TI - 1) / TI;
+  size_t tiles = (size_t)a->itiles * a->jtiles;
   size_t s = (1024 + tiles - 1) / tiles;
-  size_t smax = (M + 255) / 256;
+  size_t smax = (M + 511) / 512;
   if (s > smax) s = smax;
+  if (s > (size_t)kMaxPartials) s = kMaxPartials;
   if (s < 1) s = 1;
   size_t mc = (M + s - 1) / s;
-  mc = ((mc + BR - 1) / BR) * BR;
-  *mchunk = mc;
-  *S = (int)((M + mc - 1) / mc);
+  mc = ((mc + CH - 1) / CH) * CH;
+  a->mchunk = mc;
+  a->nranges = (int)((M + mc - 1) / mc) * a->itiles;
+  a->tiles_per_range = 1;
 }
 
 size_t pw_wgrad_ws(size_t M, int K, int N) {
-  int S; size_t mc;
-  wgrad_shape(M, K, N, &S, &mc);
-  return (size_t)S * N * K;
+  GemmArgs a{};
+  bool small;
+  plan_wgrad(M, K, N, &a, &small);
+  return (size_t)(a.nranges / a.itiles) * N * K;
 }
 
 void reduce_partials(hipStream_t st, const float* ws, int P, size_t QC, int C, size_t stride_q,
@@ -263,15 +589,15 @@ void reduce_partials(hipStream_t st, const float* ws, int P, size_t QC, int C, s
 
 void pw_wgrad(int dt, hipStream_t st, const void* dz, HView av, size_t M, int K, int N, float* ws,
               float* g_w) {
-  int S; size_t mc;
-  wgrad_shape(M, K, N, &S, &mc);
   GemmArgs a{};
   a.x = dz; a.y = av.z; a.view = View{av.z, av.scale, av.shift, av.act};
-  a.out = ws; a.M = M; a.K = K; a.N = N; a.mchunk = mc;
-  a.itiles = (N + BI - 1) / BI; a.jtiles = (K + BJ - 1) / BJ;
+  a.out = ws; a.M = M; a.K = K; a.N = N;
+  bool small;
+  plan_wgrad(M, K, N, &a, &small);
+  int S = a.nranges / a.itiles;
   {
-    KScope ks(st, "pw_wgrad", ((double)M * K + (double)M * N) * (dt == 0 ? 4.0 : 2.0) + (double)S * N * K * 4, 2.0 * M * K * N);
-    launch<MODE_WGRAD>(dt, st, a, S);
+    KScope ks(st, "pw_wgrad", ((double)M * K + (double)M * N) * (dt == 0 ? 4.0 : 2.0) + (double)S * N * K * 4, 2.0 * M * K * N, (long)M, K, N);
+    launch<MODE_WGRAD>(dt, st, a, small);
   }
   reduce_partials(st, ws, S, (size_t)N * K, K, (size_t)K, 1, g_w);
 }

@@ -14,7 +14,7 @@ namespace ftp {
 // records the kernel family, the bytes the launch must move at least (each operand
 // once) and its floating-point operations.
 struct KScope {
-  KScope(hipStream_t st, const char* name, double alg_bytes, double flops);
+  KScope(hipStream_t st, const char* name, double alg_bytes, double flops, long d0 = -1, long d1 = -1, long d2 = -1);
   ~KScope();
   int slot;
   hipStream_t st;
@@ -91,9 +91,10 @@ size_t dw_wgrad_ws(const ConvGeom& g);
 void dw_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, float* ws, float* g_w);
 
 // ---- pointwise / fully connected GEMMs (MFMA) ---------------------------------------
-// Z[M][N] = A'[M][K] * W[N][K]^T (+ bias[N])
+// Z[M][N] = A'[M][K] * W[N][K]^T (+ bias[N]); when stats != nullptr also writes the per-column
+// partial sums stats[P][2][N] of the stored Z and Z*Z (same layout as bn_stats), P into *P_out
 void pw_fwd(int dt, hipStream_t st, HView a, const void* w, const float* bias, size_t M, int K, int N,
-            void* z);
+            void* z, float* stats, int* P_out);
 // dA[M][K] = dZ[M][N] * W[N][K] (+ res[M][K])
 void pw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const void* res, size_t M, int K,
               int N, void* dA);

@@ -1,6 +1,7 @@
 // Per-launch kernel timing behind ftp_ktrace_begin / ftp_ktrace_end.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
 #include <cstring>
 #include <map>
 #include <string>
@@ -12,22 +13,23 @@
 void ftp_set_error(const char* fmt, ...);
 
 namespace {
-struct Rec { const char* name; double bytes, flops; hipEvent_t e0, e1; };
+struct Rec { const char* name; double bytes, flops; long d[3]; hipEvent_t e0, e1; };
 struct Trace {
   bool on = false;
   std::vector<Rec> recs;
   size_t used = 0;
   bool overflow = false;
+  bool detail = false;   // one row per (kernel family, problem shape) instead of per family
 } g_trace;
 }  // namespace
 
 namespace ftp {
-KScope::KScope(hipStream_t s, const char* name, double alg_bytes, double flops) : slot(-1), st(s) {
+KScope::KScope(hipStream_t s, const char* name, double alg_bytes, double flops, long d0, long d1, long d2) : slot(-1), st(s) {
   if (!g_trace.on) return;
   if (g_trace.used >= g_trace.recs.size()) { g_trace.overflow = true; return; }
   slot = (int)g_trace.used++;
   Rec& r = g_trace.recs[slot];
-  r.name = name; r.bytes = alg_bytes; r.flops = flops;
+  r.name = name; r.bytes = alg_bytes; r.flops = flops; r.d[0] = d0; r.d[1] = d1; r.d[2] = d2;
   (void)hipEventRecord(r.e0, st);
 }
 KScope::~KScope() {
@@ -43,6 +45,8 @@ static void trace_release() {
 }
 
 extern "C" int ftp_ktrace_begin(int max_launches) {
+  g_trace.detail = max_launches < 0;      // negative: rows per problem shape ("name d0 d1 d2")
+  if (max_launches < 0) max_launches = -max_launches;
   if (max_launches < 1 || max_launches > (1 << 20)) { ftp_set_error("ktrace_begin: max_launches out of range"); return FTP_ERR_ARG; }
   trace_release();
   g_trace.recs.resize(max_launches);
@@ -67,8 +71,11 @@ extern "C" int ftp_ktrace_end(ftp_ktrace_row* rows, int max_rows, int* n_rows) {
     Rec& r = g_trace.recs[i];
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, r.e0, r.e1) != hipSuccess) continue;
-    ftp_ktrace_row& row = agg[r.name];
-    if (row.launches == 0) { memset(&row, 0, sizeof(row)); strncpy(row.name, r.name, sizeof(row.name) - 1); }
+    char key[48];
+    if (g_trace.detail && r.d[0] >= 0) snprintf(key, sizeof(key), "%s %ld %ld %ld", r.name, r.d[0], r.d[1], r.d[2]);
+    else snprintf(key, sizeof(key), "%s", r.name);
+    ftp_ktrace_row& row = agg[key];
+    if (row.launches == 0) { memset(&row, 0, sizeof(row)); strncpy(row.name, key, sizeof(row.name) - 1); }
     row.launches += 1; row.total_ms += ms; row.alg_bytes += r.bytes; row.flops += r.flops;
   }
   int n = 0;

@@ -485,11 +485,14 @@ static void sub_forward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, HVi
   void* z = sl.stash + p.z_off[k];
   const void* w = conv_w(s, W, p.p_off + sb.w_off);
   size_t M = (size_t)s->batch * g.Hout * g.Wout;
-  if (sb.type == SUB_DIRECT) conv_direct_fwd(s->dt, st, in, w, g, z);
-  else if (sb.type == SUB_PW) pw_fwd(s->dt, st, in, w, nullptr, M, g.Cin, g.Cout, z);
-  else dw_fwd(s->dt, st, in, w, g, z);
   int P = 0;
-  bn_stats(s->dt, st, z, M, g.Cout, s->bn_part, &P);
+  if (sb.type == SUB_PW) {
+    pw_fwd(s->dt, st, in, w, nullptr, M, g.Cin, g.Cout, z, s->bn_part, &P);   // statistics in the epilogue
+  } else {
+    if (sb.type == SUB_DW) dw_fwd(s->dt, st, in, w, g, z);
+    else conv_direct_fwd(s->dt, st, in, w, g, z);
+    bn_stats(s->dt, st, z, M, g.Cout, s->bn_part, &P);
+  }
   float* stt = sl.stats + p.st_off[k];
   int C = g.Cout;
   bn_finalize(st, s->bn_part, P, M, C, W.w32 + p.p_off + sb.gamma_off, W.w32 + p.p_off + sb.beta_off, stt, stt + C,
@@ -534,7 +537,7 @@ extern "C" int ftp_stage_forward(ftp_stage* s, int slot, const void* x_dev, void
         break;
       case FTP_UNIT_FC:
         pw_fwd(s->dt, st, in, conv_w(s, W, p.p_off), s->params + p.p_off + (size_t)u.outC * u.inC, (size_t)s->batch, u.inC,
-               u.outC, sl.stash + p.out_off);
+               u.outC, sl.stash + p.out_off, nullptr, nullptr);
         break;
       default:
         break;  // LOSS: evaluated by ftp_stage_loss
