@@ -15,9 +15,9 @@ namespace ftp {
 
 // g[(j % C) * stride_c + (j / C) * stride_q] += sum_p ws[p * QC + j]   (float64 sum, fixed order)
 __global__ void reduce_partials_flat_k(const float* __restrict__ ws, int P, size_t QC, int C, size_t stride_q,
-                                       size_t stride_c, float* __restrict__ g) {
+                                       size_t stride_c, int valid_c, float* __restrict__ g) {
   size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= QC) return;
+  if (j >= QC || (int)(j % C) >= valid_c) return;
   double s = 0.0;
   for (int p = 0; p < P; ++p) s += (double)ws[(size_t)p * QC + j];
   size_t o = (j % C) * stride_c + (j / C) * stride_q;
@@ -26,16 +26,23 @@ __global__ void reduce_partials_flat_k(const float* __restrict__ ws, int P, size
 
 // many partials: 16 outputs per block, 16 lanes share the partials of one output
 __global__ void reduce_partials_wide_k(const float* __restrict__ ws, int P, size_t QC, int C, size_t stride_q,
-                                       size_t stride_c, float* __restrict__ g) {
+                                       size_t stride_c, int valid_c, float* __restrict__ g) {
   __shared__ double sm[16][17];
   const int jl = threadIdx.x & 15, lane = threadIdx.x >> 4;
   const size_t j = (size_t)blockIdx.x * 16 + jl;
   double s = 0.0;
-  if (j < QC)
-    for (int p = lane; p < P; p += 16) s += (double)ws[(size_t)p * QC + j];
+  if (j < QC) {
+    int p = lane;
+    for (; p + 48 < P; p += 64) {        // four independent loads per round
+      float a = ws[(size_t)p * QC + j], b = ws[(size_t)(p + 16) * QC + j];
+      float c2 = ws[(size_t)(p + 32) * QC + j], d = ws[(size_t)(p + 48) * QC + j];
+      s += (double)a; s += (double)b; s += (double)c2; s += (double)d;
+    }
+    for (; p < P; p += 16) s += (double)ws[(size_t)p * QC + j];
+  }
   sm[lane][jl] = s;
   __syncthreads();
-  if (lane == 0 && j < QC) {
+  if (lane == 0 && j < QC && (int)(j % C) < valid_c) {
     double t = 0.0;
 #pragma unroll
     for (int l = 0; l < 16; ++l) t += sm[l][jl];
@@ -44,15 +51,17 @@ __global__ void reduce_partials_wide_k(const float* __restrict__ ws, int P, size
   }
 }
 
+// columns (j % C) >= valid_c are padding and are skipped
 void reduce_partials(hipStream_t st, const float* ws, int P, size_t QC, int C, size_t stride_q,
-                     size_t stride_c, float* g) {
+                     size_t stride_c, float* g, int valid_c) {
+  if (valid_c < 0) valid_c = C;
   KScope ks(st, "reduce_partials", ((double)P + 2.0) * QC * 4, (double)P * QC);
   if (P <= 8)
     hipLaunchKernelGGL(reduce_partials_flat_k, dim3((unsigned)((QC + 255) / 256)), dim3(256), 0, st, ws, P, QC, C,
-                       stride_q, stride_c, g);
+                       stride_q, stride_c, valid_c, g);
   else
     hipLaunchKernelGGL(reduce_partials_wide_k, dim3((unsigned)((QC + 15) / 16)), dim3(256), 0, st, ws, P, QC, C,
-                       stride_q, stride_c, g);
+                       stride_q, stride_c, valid_c, g);
 }
 
 // ======================================================== generic direct conv
@@ -165,62 +174,57 @@ void conv_direct_dgrad(int dt, hipStream_t st, const void* dz, const void* w, co
                                       0, st, (const T*)dz, (const T*)w, g, (T*)dIn));
 }
 
-// thread = (k = (tap, ci), 8 output channels); block = a chunk of output pixels
+// Weight gradient of a small dense convolution: the input patches are written out once as a
+// matrix A[pixel][Kpad] (k = (tap, ci), zero padded to a multiple of 8, producer BatchNorm +
+// activation applied), then dW = dZ^T * A runs on the MFMA weight-gradient kernel.
 template <typename T>
-__global__ void conv_direct_wgrad_k(const T* __restrict__ dz, View in, ConvGeom g, int KPB, size_t ppc,
-                                    float* __restrict__ ws) {
-  const int CGo = g.Cout / 8;
-  const int cg = threadIdx.x % CGo;
-  const int k = blockIdx.y * KPB + threadIdx.x / CGo;
-  const int K = g.kh * g.kw * g.Cin;
-  if (k >= K) return;
-  const int tap = k / g.Cin, ci = k % g.Cin, i = tap / g.kw, j = tap % g.kw;
-  const size_t total = (size_t)g.N * g.Hout * g.Wout;
-  size_t p0 = (size_t)blockIdx.x * ppc, p1 = p0 + ppc < total ? p0 + ppc : total;
-  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (size_t pix = p0; pix < p1; ++pix) {
-    int wo = (int)(pix % g.Wout);
-    size_t r = pix / g.Wout;
-    int ho = (int)(r % g.Hout), n = (int)(r / g.Hout);
-    int hi = ho * g.stride + i - g.ph, wi = wo * g.stride + j - g.pw;
-    if (hi < 0 || hi >= g.Hin || wi < 0 || wi >= g.Win) continue;
-    float xv = view_at<T>(in, (((size_t)n * g.Hin + hi) * g.Win + wi) * g.Cin + ci, ci);
-    float d[8];
-    load8(dz + pix * g.Cout + cg * 8, d);
+__global__ void im2col_k(View in, ConvGeom g, int Kpad, T* __restrict__ out) {
+  const int KG = Kpad / 8, K = g.kh * g.kw * g.Cin;
+  const size_t total = (size_t)g.N * g.Hout * g.Wout * KG;
+  for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+    const int kg = (int)(idx % KG);
+    const size_t pix = idx / KG;
+    const int wo = (int)(pix % g.Wout);
+    const size_t r = pix / g.Wout;
+    const int ho = (int)(r % g.Hout), n = (int)(r / g.Hout);
+    float v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = fmaf(xv, d[e], acc[e]);
+    for (int e = 0; e < 8; ++e) {
+      const int k = kg * 8 + e;
+      float x = 0.f;
+      if (k < K) {
+        const int tap = k / g.Cin, ci = k % g.Cin, i = tap / g.kw, j = tap % g.kw;
+        const int hi = ho * g.stride + i - g.ph, wi = wo * g.stride + j - g.pw;
+        if (hi >= 0 && hi < g.Hin && wi >= 0 && wi < g.Win)
+          x = view_at<T>(in, (((size_t)n * g.Hin + hi) * g.Win + wi) * g.Cin + ci, ci);
+      }
+      v[e] = x;
+    }
+    store8(out + idx * 8, v);
   }
-  store8(ws + ((size_t)blockIdx.x * K + k) * g.Cout + cg * 8, acc);
 }
 
-static void direct_wgrad_shape(const ConvGeom& g, int* S, size_t* ppc) {
-  size_t total = (size_t)g.N * g.Hout * g.Wout;
-  size_t c = (total + 511) / 512;
-  if (c < 64) c = 64;
-  *ppc = c;
-  *S = (int)((total + c - 1) / c);
-}
+static int direct_kpad(const ConvGeom& g) { return (g.kh * g.kw * g.Cin + 7) / 8 * 8; }
+
+size_t conv_direct_im2col_elems(const ConvGeom& g) { return (size_t)g.N * g.Hout * g.Wout * direct_kpad(g); }
 
 size_t conv_direct_wgrad_ws(const ConvGeom& g) {
-  int S; size_t ppc;
-  direct_wgrad_shape(g, &S, &ppc);
-  return (size_t)S * g.kh * g.kw * g.Cin * g.Cout;
+  return pw_wgrad_ws((size_t)g.N * g.Hout * g.Wout, direct_kpad(g), g.Cout);
 }
 
-void conv_direct_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, float* ws,
+void conv_direct_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, void* im2col, float* ws,
                        float* g_w) {
-  int S; size_t ppc;
-  direct_wgrad_shape(g, &S, &ppc);
-  int CGo = g.Cout / 8, KPB = 256 / CGo, K = g.kh * g.kw * g.Cin;
-  if (KPB < 1) KPB = 1;
+  const int Kpad = direct_kpad(g), K = g.kh * g.kw * g.Cin;
+  const size_t M = (size_t)g.N * g.Hout * g.Wout;
   View v{in.z, in.scale, in.shift, in.act};
   {
-    KScope ks(st, "conv_direct_wgrad", ((double)g.N * g.Hin * g.Win * g.Cin + (double)g.N * g.Hout * g.Wout * g.Cout) * (dt == 0 ? 4.0 : 2.0) + (double)S * K * g.Cout * 4,
-              2.0 * g.N * g.Hout * g.Wout * g.Cout * K);
-    FTP_DISPATCH(dt, hipLaunchKernelGGL(conv_direct_wgrad_k<T>, dim3(S, (K + KPB - 1) / KPB), dim3(KPB * CGo), 0,
-                                        st, (const T*)dz, v, g, KPB, ppc, ws));
+    const double es = dt == 0 ? 4.0 : 2.0;
+    KScope ks(st, "im2col", ((double)g.N * g.Hin * g.Win * g.Cin + (double)M * Kpad) * es, 0, (long)M, Kpad, g.Cout);
+    size_t nvec = M * (Kpad / 8);
+    unsigned grid = (unsigned)((nvec + 255) / 256 > 65536 ? 65536 : (nvec + 255) / 256);
+    FTP_DISPATCH(dt, hipLaunchKernelGGL(im2col_k<T>, dim3(grid), dim3(256), 0, st, v, g, Kpad, (T*)im2col));
   }
-  reduce_partials(st, ws, S, (size_t)K * g.Cout, g.Cout, 1, (size_t)K, g_w);
+  pw_wgrad(dt, st, dz, HView{im2col, nullptr, nullptr, 0}, M, Kpad, g.Cout, ws, g_w, K);
 }
 
 // ================================================================ depthwise 3x3
@@ -535,8 +539,6 @@ static DwPlan dw_wgrad_plan(const ConvGeom& g, int es, int* parts, size_t* lds) 
 
 size_t dw_wgrad_ws(const ConvGeom& g) { return (size_t)kMaxPartials * 9 * g.Cout; }
 
-void reduce_partials(hipStream_t st, const float* ws, int P, size_t QC, int C, size_t stride_q,
-                     size_t stride_c, float* g);
 
 void dw_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, float* ws, float* g_w) {
   const int es = dt == 0 ? 4 : 2;

@@ -78,11 +78,13 @@ __global__ void bn_stats_k(const T* __restrict__ z, size_t M, int C, int W, int 
 
 void bn_stats(int dt, hipStream_t st, const void* z, size_t M, int C, float* partial, int* P_out) {
   RowTile t = make_rowtile(M, C, kMaxPartials);
-  KScope ks(st, "bn_stats", (double)M * C * (dt == 0 ? 4.0 : 2.0), 3.0 * M * C);
-  dim3 grid(t.P, t.nslab), block(t.W * t.R);
-  size_t sm = (size_t)16 * t.R * t.W * sizeof(float);
-  FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_stats_k<T>, grid, block, sm, st, (const T*)z, M, C, t.W, t.R,
-                                      t.rows_per_block, partial));
+  {
+    KScope ks(st, "bn_stats", (double)M * C * (dt == 0 ? 4.0 : 2.0), 3.0 * M * C);
+    dim3 grid(t.P, t.nslab), block(t.W * t.R);
+    size_t sm = (size_t)16 * t.R * t.W * sizeof(float);
+    FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_stats_k<T>, grid, block, sm, st, (const T*)z, M, C, t.W, t.R,
+                                        t.rows_per_block, partial));
+  }
   *P_out = t.P;
 }
 
@@ -93,10 +95,24 @@ __device__ __forceinline__ void sum_partials(const float* __restrict__ partial, 
   double s[Q];
 #pragma unroll
   for (int q = 0; q < Q; ++q) s[q] = 0.0;
-  if (c < C)
-    for (int p = lane; p < P; p += 16)
+  if (c < C) {
+    // four partials per round: the loads are independent, the sums keep a fixed order
+    int p = lane;
+    for (; p + 48 < P; p += 64) {
+      float v[4][Q];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int q = 0; q < Q; ++q) v[u][q] = partial[((size_t)(p + 16 * u) * Q + q) * C + c];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int q = 0; q < Q; ++q) s[q] += (double)v[u][q];
+    }
+    for (; p < P; p += 16)
 #pragma unroll
       for (int q = 0; q < Q; ++q) s[q] += (double)partial[((size_t)p * Q + q) * C + c];
+  }
   int cl = threadIdx.x % 16;
 #pragma unroll
   for (int q = 0; q < Q; ++q) smem[(q * 16 + lane) * 16 + cl] = s[q];
@@ -183,11 +199,13 @@ __global__ void bn_bwd_reduce_k(const T* __restrict__ dA, const T* __restrict__ 
 void bn_bwd_reduce(int dt, hipStream_t st, const void* dA, const void* z, size_t M, int C,
                    const float* scale, const float* shift, int act, float* partial, int* P_out) {
   RowTile t = make_rowtile(M, C, kMaxPartials);
-  KScope ks(st, "bn_bwd_reduce", 2.0 * M * C * (dt == 0 ? 4.0 : 2.0), 6.0 * M * C);
-  dim3 grid(t.P, t.nslab), block(t.W * t.R);
-  size_t sm = (size_t)16 * t.R * t.W * sizeof(float);
-  FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_bwd_reduce_k<T>, grid, block, sm, st, (const T*)dA, (const T*)z, M,
-                                      C, scale, shift, act, t.W, t.R, t.rows_per_block, partial));
+  {
+    KScope ks(st, "bn_bwd_reduce", 2.0 * M * C * (dt == 0 ? 4.0 : 2.0), 6.0 * M * C);
+    dim3 grid(t.P, t.nslab), block(t.W * t.R);
+    size_t sm = (size_t)16 * t.R * t.W * sizeof(float);
+    FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_bwd_reduce_k<T>, grid, block, sm, st, (const T*)dA, (const T*)z, M,
+                                        C, scale, shift, act, t.W, t.R, t.rows_per_block, partial));
+  }
   *P_out = t.P;
 }
 

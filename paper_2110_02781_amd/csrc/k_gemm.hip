@@ -141,6 +141,108 @@ struct TileLoader {
   }
 };
 
+// Transposing loader for "i contiguous" sources (element (i, r) at src[r*ld + i]).  A thread takes
+// two consecutive reduction rows r, r+1 of the same 8 columns and writes LDS in (r, r+1) pairs:
+// one 32-bit (bfloat16) or 64-bit (float) store per column instead of two 16/32-bit ones, and for
+// plain bfloat16 data the pair is assembled from the raw bits without a float round trip.
+__device__ __forceinline__ void lds_put_pair(float* p, float a, float b) { *reinterpret_cast<float2*>(p) = make_float2(a, b); }
+__device__ __forceinline__ void lds_put_pair(bf16_t* p, float a, float b) { *reinterpret_cast<uint32_t*>(p) = f32x2_to_bf16x2(a, b); }
+
+template <typename T, int ROWS, int CH, bool USE_VIEW, bool PERM>
+struct TransLoader {
+  enum { NITEM = (ROWS / 8) * (CH / 2), PER = (NITEM + 255) / 256, LD = CH + Pad<T>::V };
+  Raw<T> raw[PER][2];
+  unsigned ok;      // bit 2q+u: raw[q][u] holds a full in-bounds vector
+
+  // consecutive lanes take consecutive row pairs of the same 8 columns, so their LDS stores fall into
+  // consecutive words of one LDS row (the other order would put 16 lanes on one bank)
+  __device__ __forceinline__ void coords(int item, int& i, int& r) const {
+    r = (item % (CH / 2)) * 2;
+    i = (item / (CH / 2)) * 8;
+  }
+
+  __device__ __forceinline__ void fetch(const T* __restrict__ src, size_t ld, size_t i0, size_t ni, size_t r0,
+                                        size_t nr) {
+    ok = 0;
+    const bool vec_ok = (ld % 8) == 0;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int item = threadIdx.x + q * 256;
+      if (item >= NITEM) break;
+      int i, r;
+      coords(item, i, r);
+      const size_t gi = i0 + i;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const size_t gr = r0 + r + u;
+        if (vec_ok && gr < nr && gi + 8 <= ni) {
+          raw_load(raw[q][u], src + gr * ld + gi);
+          ok |= 1u << (2 * q + u);
+        }
+      }
+    }
+  }
+
+  __device__ __forceinline__ void commit(T* lds, const T* __restrict__ src, size_t ld, size_t i0, size_t ni,
+                                         size_t r0, size_t nr, const View& vw) const {
+    const bool view = USE_VIEW && vw.scale != nullptr;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int item = threadIdx.x + q * 256;
+      if (item >= NITEM) break;
+      int i, r;
+      coords(item, i, r);
+      const size_t gi = i0 + i;
+      const unsigned both = (ok >> (2 * q)) & 3u;
+      if (sizeof(T) == 2 && !view && both == 3u) {
+        // raw bits straight into (r, r+1) pairs
+        const uint32_t* w0 = reinterpret_cast<const uint32_t*>(&raw[q][0]);
+        const uint32_t* w1 = reinterpret_cast<const uint32_t*>(&raw[q][1]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t a = w0[e >> 1], b = w1[e >> 1];
+          const uint32_t pr = (e & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+          *reinterpret_cast<uint32_t*>(lds + (PERM ? perm64(i + e) : i + e) * LD + r) = pr;
+        }
+        continue;
+      }
+      float val[2][8];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const size_t gr = r0 + r + u;
+        if (ok & (1u << (2 * q + u))) {
+          raw_unpack(raw[q][u], val[u]);
+          if (view) {
+            float sc[8], sh[8];
+            load8(vw.scale + gi, sc);
+            load8(vw.shift + gi, sh);
+            const float lo = act_lo(vw.act), hi = act_hi(vw.act);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) val[u][e] = clamp_act(fmaf(val[u][e], sc[e], sh[e]), lo, hi);
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            float x = 0.f;                      // out-of-range elements must stay exactly zero
+            if (gr < nr && gi + e < ni) {
+              x = to_f32(src[gr * ld + gi + e]);
+              if (view) x = act_apply(fmaf(x, vw.scale[gi + e], vw.shift[gi + e]), vw.act);
+            }
+            val[u][e] = x;
+          }
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) lds_put_pair(lds + (PERM ? perm64(i + e) : i + e) * LD + r, val[0][e], val[1][e]);
+    }
+  }
+};
+
+template <typename T, int ROWS, int CH, bool RC, bool USE_VIEW, bool PERM = false>
+struct LoaderSel { typedef TileLoader<T, ROWS, CH, true, USE_VIEW, PERM> type; };
+template <typename T, int ROWS, int CH, bool USE_VIEW, bool PERM>
+struct LoaderSel<T, ROWS, CH, false, USE_VIEW, PERM> { typedef TransLoader<T, ROWS, CH, USE_VIEW, PERM> type; };
+
 // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Renumbering them so that
 // consecutive logical ids share an XCD keeps the column tiles of one row range (which re-read the
 // same activations) behind one L2.
@@ -230,8 +332,8 @@ __global__ __launch_bounds__(256) void pw_gemm_k(GemmArgs p) {
   // forward: X = A' (r-contiguous, view), Y = W (r-contiguous)
   // dgrad  : X = dZ (r-contiguous),       Y = W as (j=k, r=n)  (i-contiguous)
   // wgrad  : X = dZ as (i=n, r=m),        Y = A' as (j=k, r=m) (both i-contiguous, view on Y)
-  TileLoader<T, TI, CH, MODE != MODE_WGRAD, MODE == MODE_FWD> lx;
-  TileLoader<T, BJ, CH, MODE == MODE_FWD, MODE == MODE_WGRAD> ly;
+  typename LoaderSel<T, TI, CH, MODE != MODE_WGRAD, MODE == MODE_FWD>::type lx;
+  typename LoaderSel<T, BJ, CH, MODE == MODE_FWD, MODE == MODE_WGRAD>::type ly;
 
   f16v acc[2];
 #pragma unroll
@@ -413,8 +515,8 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
   const size_t nj = MODE == MODE_FWD ? (size_t)p.N : (size_t)p.K;
   const size_t ldo = nj;                   // leading dimension of the output
 
-  TileLoader<T, TI, CH, MODE != MODE_WGRAD, MODE == MODE_FWD> lx;
-  TileLoader<T, BJ, CH, MODE == MODE_FWD, MODE == MODE_WGRAD, true> ly;
+  typename LoaderSel<T, TI, CH, MODE != MODE_WGRAD, MODE == MODE_FWD>::type lx;
+  typename LoaderSel<T, BJ, CH, MODE == MODE_FWD, MODE == MODE_WGRAD, true>::type ly;
 
   f16v acc[2];
 #pragma unroll
@@ -543,8 +645,10 @@ void pw_fwd(int dt, hipStream_t st, HView av, const void* w, const float* bias, 
   bool small;
   plan_rows(M, N, K, &a, &small);
   if (P_out) *P_out = a.nranges;
-  KScope ks(st, "pw_fwd", ((double)M * K + (double)M * N + (double)N * K) * (dt == 0 ? 4.0 : 2.0), 2.0 * M * K * N, (long)M, K, N);
-  launch<MODE_FWD>(dt, st, a, small);
+  {
+    KScope ks(st, "pw_fwd", ((double)M * K + (double)M * N + (double)N * K) * (dt == 0 ? 4.0 : 2.0), 2.0 * M * K * N, (long)M, K, N);
+    launch<MODE_FWD>(dt, st, a, small);
+  }
 }
 
 void pw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const void* res, size_t M, int K,
@@ -566,7 +670,7 @@ static void plan_wgrad(size_t M, int K, int N, GemmArgs* a, bool* small) {
   a->itiles = (N + TI - 1) / TI;
   size_t tiles = (size_t)a->itiles * a->jtiles;
   size_t s = (1024 + tiles - 1) / tiles;
-  size_t smax = (M + 511) / 512;
+  size_t smax = (M + 2 * CH - 1) / (2 * CH);      // at least two reduction chunks per split
   if (s > smax) s = smax;
   if (s > (size_t)kMaxPartials) s = kMaxPartials;
   if (s < 1) s = 1;
@@ -584,11 +688,8 @@ size_t pw_wgrad_ws(size_t M, int K, int N) {
   return (size_t)(a.nranges / a.itiles) * N * K;
 }
 
-void reduce_partials(hipStream_t st, const float* ws, int P, size_t QC, int C, size_t stride_q,
-                     size_t stride_c, float* g);
-
 void pw_wgrad(int dt, hipStream_t st, const void* dz, HView av, size_t M, int K, int N, float* ws,
-              float* g_w) {
+              float* g_w, int K_out) {
   GemmArgs a{};
   a.x = dz; a.y = av.z; a.view = View{av.z, av.scale, av.shift, av.act};
   a.out = ws; a.M = M; a.K = K; a.N = N;
@@ -599,7 +700,9 @@ void pw_wgrad(int dt, hipStream_t st, const void* dz, HView av, size_t M, int K,
     KScope ks(st, "pw_wgrad", ((double)M * K + (double)M * N) * (dt == 0 ? 4.0 : 2.0) + (double)S * N * K * 4, 2.0 * M * K * N, (long)M, K, N);
     launch<MODE_WGRAD>(dt, st, a, small);
   }
-  reduce_partials(st, ws, S, (size_t)N * K, K, (size_t)K, 1, g_w);
+  // K_out < K: the last K - K_out columns of A are padding and g_w is [N][K_out]
+  if (K_out < 0) K_out = K;
+  reduce_partials(st, ws, S, (size_t)N * K, K, (size_t)K_out, 1, g_w, K_out);
 }
 
 }  // namespace ftp

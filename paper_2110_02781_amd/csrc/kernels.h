@@ -79,10 +79,14 @@ void f32_to_storage(int dt, hipStream_t st, const float* src, void* dst, size_t 
 int conv_direct_supported(const ConvGeom& g);
 void conv_direct_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z);
 void conv_direct_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvGeom& g, void* dIn);
-// partial then accumulate into g_w[Cout][kh][kw][Cin]
+// g_w[Cout][kh][kw][Cin] += dW; im2col: scratch of conv_direct_im2col_elems(g) activation elements
 size_t conv_direct_wgrad_ws(const ConvGeom& g);  // floats of workspace needed
-void conv_direct_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, float* ws,
+size_t conv_direct_im2col_elems(const ConvGeom& g);
+void conv_direct_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, void* im2col, float* ws,
                        float* g_w);
+// g[(j % C) * stride_c + (j / C) * stride_q] += sum_p ws[p * QC + j]; columns j % C >= valid_c skipped (-1: none)
+void reduce_partials(hipStream_t st, const float* ws, int P, size_t QC, int C, size_t stride_q, size_t stride_c,
+                     float* g, int valid_c = -1);
 
 // ---- depthwise 3x3 ----------------------------------------------------------------
 void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z);
@@ -100,7 +104,8 @@ void pw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const void*
               int N, void* dA);
 // g_w[N][K] += dZ[M][N]^T * A'[M][K]
 size_t pw_wgrad_ws(size_t M, int K, int N);
+// K_out >= 0: g_w is [N][K_out] and the last K - K_out columns of A are zero padding
 void pw_wgrad(int dt, hipStream_t st, const void* dz, HView a, size_t M, int K, int N, float* ws,
-              float* g_w);
+              float* g_w, int K_out = -1);
 
 }  // namespace ftp

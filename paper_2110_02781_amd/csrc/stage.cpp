@@ -232,6 +232,8 @@ struct ftp_stage {
   std::vector<Slot> slots;
   char *gbuf[4] = {nullptr, nullptr, nullptr, nullptr};   // boundary A/B, dz, dA
   float *bn_part = nullptr, *coef = nullptr, *ws = nullptr, *row_loss = nullptr;
+  void* im2col = nullptr;     // patch matrix for the weight gradient of small dense convolutions
+  size_t im2col_elems = 0;
   size_t ws_floats = 0;
   int max_c = 0;
   bool has_loss = false;
@@ -246,7 +248,7 @@ static void stage_free(ftp_stage* s) {
   dfree(s->params); dfree(s->grads); dfree(s->mom); dfree(s->run_mean); dfree(s->run_var); dfree(s->w_lp);
   for (auto& sl : s->slots) { dfree(sl.stash); dfree(sl.stats); dfree(sl.snap_w); dfree(sl.snap_lp); dfree(sl.dlogits); }
   for (int i = 0; i < 4; ++i) dfree(s->gbuf[i]);
-  dfree(s->bn_part); dfree(s->coef); dfree(s->ws); dfree(s->row_loss);
+  dfree(s->bn_part); dfree(s->coef); dfree(s->ws); dfree(s->row_loss); dfree(s->im2col);
   delete s;
 }
 
@@ -297,6 +299,7 @@ extern "C" int ftp_stage_create(const ftp_model* m, int a, int b, int batch, int
       size_t M = (size_t)batch * g.Hout * g.Wout;
       size_t need = sb.type == SUB_DIRECT ? conv_direct_wgrad_ws(g) : sb.type == SUB_DW ? dw_wgrad_ws(g) : pw_wgrad_ws(M, g.Cin, g.Cout);
       if (need > ws_floats) ws_floats = need;
+      if (sb.type == SUB_DIRECT && conv_direct_im2col_elems(g) > s->im2col_elems) s->im2col_elems = conv_direct_im2col_elems(g);
     }
     p.out_virtual = (u.d.kind == FTP_UNIT_CONV);
     p.out_off = 0;
@@ -334,6 +337,7 @@ extern "C" int ftp_stage_create(const ftp_model* m, int a, int b, int batch, int
     if ((rc = dev_alloc(&s->gbuf[i], max_act))) { stage_free(s); return rc; }
   if ((rc = dev_alloc(&s->bn_part, (size_t)kMaxPartials * 2 * max_c * 4)) || (rc = dev_alloc(&s->coef, (size_t)3 * max_c * 4)) ||
       (rc = dev_alloc(&s->ws, ws_floats * 4)) || (rc = dev_alloc(&s->row_loss, (size_t)batch * 4))) { stage_free(s); return rc; }
+  if (s->im2col_elems && (rc = dev_alloc(&s->im2col, s->im2col_elems * s->es))) { stage_free(s); return rc; }
 
   // initial state: zero weights / momentum / gradients, running mean 0, running variance 1
   std::vector<float> ones(nb, 1.0f);
@@ -486,6 +490,8 @@ static void sub_forward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, HVi
   const void* w = conv_w(s, W, p.p_off + sb.w_off);
   size_t M = (size_t)s->batch * g.Hout * g.Wout;
   int P = 0;
+  float* stt = sl.stats + p.st_off[k];
+  int C = g.Cout;
   if (sb.type == SUB_PW) {
     pw_fwd(s->dt, st, in, w, nullptr, M, g.Cin, g.Cout, z, s->bn_part, &P);   // statistics in the epilogue
   } else {
@@ -493,8 +499,6 @@ static void sub_forward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, HVi
     else conv_direct_fwd(s->dt, st, in, w, g, z);
     bn_stats(s->dt, st, z, M, g.Cout, s->bn_part, &P);
   }
-  float* stt = sl.stats + p.st_off[k];
-  int C = g.Cout;
   bn_finalize(st, s->bn_part, P, M, C, W.w32 + p.p_off + sb.gamma_off, W.w32 + p.p_off + sb.beta_off, stt, stt + C,
               stt + 2 * C, stt + 3 * C, s->run_mean + p.bn_off + sb.bn_off, s->run_var + p.bn_off + sb.bn_off, kBnEps, kBnMomentum);
 }
@@ -613,7 +617,7 @@ static void sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, co
   const void* w = conv_w(s, W, p.p_off + sb.w_off);
   float* gw = s->grads + p.p_off + sb.w_off;
   if (sb.type == SUB_DIRECT) {
-    conv_direct_wgrad(s->dt, st, dz, in, g, s->ws, gw);
+    conv_direct_wgrad(s->dt, st, dz, in, g, s->im2col, s->ws, gw);
     if (dIn) conv_direct_dgrad(s->dt, st, dz, w, g, dIn);
   } else if (sb.type == SUB_PW) {
     pw_wgrad(s->dt, st, dz, in, M, g.Cin, g.Cout, s->ws, gw);
