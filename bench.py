@@ -2,11 +2,14 @@
 """Stage-training throughput on one MI355X: forward + loss + backward + SGD update of one
 pipeline stage on seeded synthetic data, through the C-ABI library.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config {1,2,5}] [--graph]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config {1,2,5}] [--also 5] [--graph]
 
 Prints ONE JSON line: samples/s of the whole step (inputs resident in HBM), the roofline
 of the kernel family that takes the most time (measured with HIP events around every
 launch in a second pass of K steps) and the CPU oracle timed on this host as a baseline.
+The headline workload is config 2 (MobileNetV2 at 32x32, batch 32, fp32); because its tensors
+are a few MB and its step is launch-latency bound, the large bf16 workload (config 5) is
+measured in the same run and reported under "also" with its own roofline.
 """
 import argparse
 import json
@@ -72,30 +75,28 @@ def oracle_baseline(w, seed, budget_s=30.0):
                        f"of {w['batch']}, float64 numpy, {dt:.2f} s")
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, choices=sorted(WORKLOADS))
-    ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-ktrace", action="store_true")
-    ap.add_argument("--seed", type=int, default=2110)
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs one pipeline stage on ONE GPU; --gpus must be 1 "
-              "(no multi-GPU path exists, see DESIGN.md 'More than one GPU')", file=sys.stderr)
-        sys.exit(2)
+def load_traffic(config):
+    """HBM bytes per launch per kernel family from the committed rocprofv3 --pmc summary
+    (profiles/config<N>_pmc_traffic.txt: family fetch_bytes write_bytes, already scaled by the copy yardstick)."""
+    path = os.path.join(ROOT, "profiles", f"config{config}_pmc_traffic.txt")
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 3 and not line.startswith("#"):
+                try:
+                    out[f[0]] = float(f[1]) + float(f[2])
+                except ValueError:
+                    pass
+    return out
 
+
+def run_workload(config, steps, warmup, use_graph, ktrace, calibrate, seed):
     import torch
     import synth
     import paper_2110_02781_amd as P
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    w = WORKLOADS[args.config]
+    w = WORKLOADS[config]
     dev = torch.device("cuda:0")
     tdt = torch.float32 if w["dtype"] == "f32" else torch.bfloat16
     units = build_units(P, w)
@@ -103,11 +104,11 @@ def main():
     model = P.model_create(units, H, W_, C, P.F32 if w["dtype"] == "f32" else P.BF16)
     L = P.model_num_units(model)
     stage = P.stage_create(model, 0, L, w["batch"], 1)
-    params = P.models.init_unit_params(units, args.seed)
+    params = P.models.init_unit_params(units, seed)
     for i in range(L):
         P.stage_import_weights(stage, i, params[i])
-    x = torch.from_numpy(synth.normal(args.seed, "x", (w["batch"], H, W_, C)).astype(np.float32)).to(dev).to(tdt)
-    labels = torch.from_numpy(synth.labels(args.seed, "labels", w["batch"], w["classes"])).to(dev)
+    x = torch.from_numpy(synth.normal(seed, "x", (w["batch"], H, W_, C)).astype(np.float32)).to(dev).to(tdt)
+    labels = torch.from_numpy(synth.labels(seed, "labels", w["batch"], w["classes"])).to(dev)
     loss = torch.zeros(1, dtype=torch.float32, device=dev)
     stream = torch.cuda.Stream()
     sp = stream.cuda_stream
@@ -119,32 +120,39 @@ def main():
         P.stage_update(stage, w["lr"], w["mu"], w["wd"], sp)
 
     run = step
-    graph = None
-    if args.graph:
+    if use_graph:
         # the library only enqueues kernels and device-to-device copies, so a step can be captured
-        step(); stream.synchronize()
+        step()
+        stream.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=stream):
             step()
         run = graph.replay
 
-    for _ in range(args.warmup):
+    if calibrate:
+        ca = torch.ones(1 << 26, dtype=torch.float32, device=dev)       # 256 MiB
+        cb = torch.empty_like(ca)
+        P.calibration_copy(cb, ca, ca.numel() * 4, sp)
+        stream.synchronize()
+        del ca, cb
+    for _ in range(warmup):
         run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         run()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     final_loss = float(loss.item())
-    ms_per_step = dt / args.steps * 1e3
-    value = w["batch"] * args.steps / dt
+    res = dict(workload=w["name"], batch=w["batch"], units=L, dtype=w["dtype"], hip_graph=bool(use_graph),
+               value=round(w["batch"] * steps / dt, 2), ms_per_step=round(dt / steps * 1e3, 4),
+               final_loss=round(final_loss, 4), roofline=None, kernels=[])
 
     # second pass: HIP events around every launch -> the dominant kernel family and its roofline
-    roofline, kernels = None, []
-    if not args.no_ktrace:
+    if ktrace:
+        traffic = load_traffic(config)
         P.ktrace_begin(1 << 16)
-        nsteps = max(1, min(args.steps, 20))
+        nsteps = max(1, min(steps, 20))
         for _ in range(nsteps):
             step()
         rows = P.ktrace_end()
@@ -154,41 +162,81 @@ def main():
             avg_us = r["total_ms"] / r["launches"] * 1e3
             gbs = r["alg_bytes"] / (r["total_ms"] * 1e-3) / 1e9 if r["total_ms"] > 0 else 0.0
             tfs = r["flops"] / (r["total_ms"] * 1e-3) / 1e12 if r["total_ms"] > 0 else 0.0
-            kernels.append(dict(name=r["name"], launches_per_step=r["launches"] / nsteps, avg_us=round(avg_us, 2),
-                                share=round(r["total_ms"] / tot, 4), alg_GBps=round(gbs, 1), TFLOPs=round(tfs, 2)))
+            res["kernels"].append(dict(name=r["name"], launches_per_step=r["launches"] / nsteps, avg_us=round(avg_us, 2),
+                                       share=round(r["total_ms"] / tot, 4), alg_GBps=round(gbs, 1), TFLOPs=round(tfs, 2)))
         d = rows[0]
         ai = d["flops"] / max(d["alg_bytes"], 1.0)
         balance = PEAK_TFLOPS[w["dtype"]] * 1e12 / (PEAK_HBM_GBS * 1e9)
-        is_gemm = d["name"].startswith("pw_")
-        if is_gemm and ai >= balance:
+        tr = traffic.get(d["name"])
+        if d["name"].startswith("pw_") and ai >= balance:
             ach = d["flops"] / (d["total_ms"] * 1e-3) / 1e12
-            roofline = dict(bound="mfma", achieved=round(ach, 3), peak=PEAK_TFLOPS[w["dtype"]], unit="TFLOP/s",
-                            frac=round(ach / PEAK_TFLOPS[w["dtype"]], 4), traffic=None)
+            roof = dict(bound="mfma", achieved=round(ach, 3), peak=PEAK_TFLOPS[w["dtype"]], unit="TFLOP/s",
+                        frac=round(ach / PEAK_TFLOPS[w["dtype"]], 4), traffic=tr)
         else:
             ach = d["alg_bytes"] / (d["total_ms"] * 1e-3) / 1e9
-            roofline = dict(bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                            frac=round(ach / PEAK_HBM_GBS, 4), traffic=None)
-        roofline.update(kernel=d["name"], avg_launch_us=round(d["total_ms"] / d["launches"] * 1e3, 2),
-                        launches_per_step=d["launches"] / nsteps,
-                        alg_bytes_per_launch=round(d["alg_bytes"] / d["launches"]),
-                        note="algorithmic bytes = every operand of a launch once; durations from HIP events "
-                             "around each launch on its stream, in a separate traced pass")
+            roof = dict(bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                        frac=round(ach / PEAK_HBM_GBS, 4), traffic=tr)
+        roof.update(kernel=d["name"], avg_launch_us=round(d["total_ms"] / d["launches"] * 1e3, 2),
+                    launches_per_step=d["launches"] / nsteps,
+                    alg_bytes_per_launch=round(d["alg_bytes"] / d["launches"]),
+                    note="algorithmic bytes = every operand of a launch once; durations from HIP events around each "
+                         "launch on its stream, in a separate traced pass; traffic = measured HBM bytes per launch "
+                         "(rocprofv3 FETCH_SIZE + WRITE_SIZE, see profiles/) or null")
+        res["roofline"] = roof
+    P.stage_destroy(stage)
+    P.model_destroy(model)
+    del x
+    torch.cuda.empty_cache()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, choices=sorted(WORKLOADS))
+    ap.add_argument("--also", type=int, nargs="*", default=None,
+                    help="further configs reported under 'also' (default: 5 when --config is 2)")
+    ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ktrace", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also launch one plain 256 MiB copy (a dispatch of known traffic for counter scaling)")
+    ap.add_argument("--seed", type=int, default=2110)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs one pipeline stage on ONE GPU; --gpus must be 1 "
+              "(no multi-GPU path exists, see DESIGN.md 'More than one GPU')", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    main_res = run_workload(args.config, args.steps, args.warmup, args.graph, not args.no_ktrace, args.calibrate, args.seed)
+    also_cfgs = args.also if args.also is not None else ([5] if args.config == 2 else [])
+    also = []
+    for c in also_cfgs:
+        if c == args.config or c not in WORKLOADS:
+            continue
+        r = run_workload(c, max(5, min(args.steps, 10)), 3, False, not args.no_ktrace, False, args.seed)
+        r["kernels"] = r["kernels"][:6]
+        also.append(r)
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = oracle_baseline(w, args.seed)
+        cpu = oracle_baseline(WORKLOADS[args.config], args.seed)
 
     out = {
         "metric": "stage train samples/sec (fwd+bwd+update) at 1 MI355X; % HBM/MFMA roofline",
-        "value": round(value, 2), "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w["dtype"], "data": "synthetic (seeded N(0,1) inputs, uniform labels, He-normal weights)",
-        "config": {"workload": w["name"], "batch": w["batch"], "units": L, "hip_graph": bool(args.graph),
-                   "final_loss": round(final_loss, 4)},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+        "value": main_res["value"], "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": main_res["dtype"], "data": "synthetic (seeded N(0,1) inputs, uniform labels, He-normal weights)",
+        "config": {"workload": main_res["workload"], "batch": main_res["batch"], "units": main_res["units"],
+                   "hip_graph": main_res["hip_graph"], "final_loss": main_res["final_loss"]},
+        "roofline": main_res["roofline"], "cpu_baseline": cpu, "kernels": main_res["kernels"], "also": also,
     }
-    P.stage_destroy(stage)
-    P.model_destroy(model)
     print(json.dumps(out))
 
 

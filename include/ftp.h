@@ -206,6 +206,11 @@ typedef struct {
 int ftp_ktrace_begin(int max_launches);
 int ftp_ktrace_end(ftp_ktrace_row* rows, int max_rows, int* n_rows);
 
+/* Copies `bytes` (a multiple of 16) from src_dev to dst_dev with a plain kernel: a launch of
+ * exactly known HBM traffic (bytes read + bytes written) against which hardware traffic counters
+ * (rocprofv3 FETCH_SIZE / WRITE_SIZE) are scaled.  Asynchronous on `stream`. */
+int ftp_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

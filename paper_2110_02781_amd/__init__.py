@@ -7,6 +7,6 @@ from .binding import (  # noqa: F401
     model_unit_bn_channels, stage_create, stage_destroy, stage_import_weights, stage_export_weights,
     stage_export_grads, stage_export_momentum, stage_export_bn_stats, stage_export_conv_output, stage_export_bn_batch_stats, stage_forward, stage_loss,
     stage_snapshot_weights, stage_backward, stage_update, profile_layers, solve_partition,
-    estimate_capacity, ktrace_begin, ktrace_end, F32, BF16,
+    estimate_capacity, ktrace_begin, ktrace_end, calibration_copy, F32, BF16,
 )
 from . import models  # noqa: F401

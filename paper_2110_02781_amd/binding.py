@@ -83,6 +83,7 @@ _SIGS = {
     "ftp_profile_layers": (_i, [_vp, _i, _i, _dp, C.POINTER(C.c_int64), _vp]),
     "ftp_solve_partition": (_i, [_dp, _i, _dp, _i, _dp, _dp, C.POINTER(C.c_int32), _dp]),
     "ftp_estimate_capacity": (_i, [C.c_double, _dp, _i, _i, _i, _dp]),
+    "ftp_calibration_copy": (_i, [_vp, _vp, _sz, _vp]),
     "ftp_ktrace_begin": (_i, [_i]),
     "ftp_ktrace_end": (_i, [C.POINTER(KtraceRow), _i, C.POINTER(_i)]),
 }
@@ -275,3 +276,7 @@ def ktrace_end():
     _chk(lib.ftp_ktrace_end(rows, 512, C.byref(n)))
     return [dict(name=rows[i].name.decode(), launches=rows[i].launches, total_ms=rows[i].total_ms,
                  alg_bytes=rows[i].alg_bytes, flops=rows[i].flops) for i in range(n.value)]
+
+
+def calibration_copy(dst_dev, src_dev, nbytes, stream=None):
+    _chk(lib.ftp_calibration_copy(_ptr(dst_dev), _ptr(src_dev), nbytes, _ptr(stream)))

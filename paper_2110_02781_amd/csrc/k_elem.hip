@@ -450,6 +450,18 @@ void fill_zero(hipStream_t st, void* p, size_t bytes) {
   hipLaunchKernelGGL(fill_zero_k, dim3(flat_grid(n, 256)), dim3(256), 0, st, (uint32_t*)p, n);
 }
 
+// plain 16-byte-per-thread copy of known size: the yardstick hardware traffic counters are scaled by
+__global__ void calibration_copy_k(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+void calibration_copy(hipStream_t st, const void* src, void* dst, size_t bytes) {
+  size_t n = bytes / 16;
+  KScope ks(st, "calibration_copy", 2.0 * n * 16, 0);
+  hipLaunchKernelGGL(calibration_copy_k, dim3(flat_grid(n, 256)), dim3(256), 0, st, (const uint4*)src, (uint4*)dst, n);
+}
+
 template <typename T>
 __global__ void f32_to_storage_k(const float* __restrict__ src, T* __restrict__ dst, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)

@@ -73,6 +73,7 @@ void bias_grad(int dt, hipStream_t st, const void* d, int B, int Nout, float* g_
 void sgd_update(hipStream_t st, float* w, float* g, float* v, void* w_lp, size_t n, float lr, float mu,
                 float wd);
 void fill_zero(hipStream_t st, void* p, size_t bytes);
+void calibration_copy(hipStream_t st, const void* src, void* dst, size_t bytes);
 void f32_to_storage(int dt, hipStream_t st, const float* src, void* dst, size_t n);
 
 // ---- generic small dense convolution (stem 3x3, conv1d) ---------------------------

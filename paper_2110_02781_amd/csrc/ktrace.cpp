@@ -86,3 +86,10 @@ extern "C" int ftp_ktrace_end(ftp_ktrace_row* rows, int max_rows, int* n_rows) {
   if (ovf) { ftp_set_error("ktrace_end: more launches than max_launches; rows are incomplete"); return FTP_ERR_ARG; }
   return FTP_OK;
 }
+
+extern "C" int ftp_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream) {
+  if (!dst_dev || !src_dev || bytes < 16 || (bytes % 16) != 0) { ftp_set_error("calibration_copy: need non-NULL buffers and a multiple of 16 bytes"); return FTP_ERR_ARG; }
+  ftp::calibration_copy((hipStream_t)stream, src_dev, dst_dev, bytes);
+  if (hipGetLastError() != hipSuccess) { ftp_set_error("calibration_copy: launch failed"); return FTP_ERR_HIP; }
+  return FTP_OK;
+}
