@@ -284,7 +284,7 @@ struct PatchLoader {
       }
     }
   }
-  __device__ __forceinline__ void commit(T* lds, const View& vw, int PH, int PW, int cg0, int CGB) const {
+  __device__ __forceinline__ void commit(float* lds, const View& vw, int PH, int PW, int cg0, int CGB) const {
     const int total = PH * PW * CGB;
 #pragma unroll
     for (int q = 0; q < NV; ++q) {
@@ -317,8 +317,8 @@ __global__ __launch_bounds__(256) void dw_fwd_k(View in, const T* __restrict__ w
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   const int C = g.Cout, cgs = C / 8, s = g.stride;
   const int PH = (d.TH - 1) * s + 3, PW = (d.TW - 1) * s + 3;
-  T* patch = reinterpret_cast<T*>(smem_raw);
-  float* wl = reinterpret_cast<float*>(patch + (size_t)PH * PW * d.CGB * 8);     // [9][CGB][8]
+  float* patch = reinterpret_cast<float*>(smem_raw);      // float in LDS: converted once, no unpacking per tap
+  float* wl = patch + (size_t)PH * PW * d.CGB * 8;        // [9][CGB][8]
   const int cg = threadIdx.x % d.CGB, pl = threadIdx.x / d.CGB;
   const int cg0 = blockIdx.y * d.CGB, gcg = cg0 + cg;
   const int tile = blockIdx.x;
@@ -375,7 +375,7 @@ void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, 
   KScope ks(st, "dw_fwd", ((double)g.N * g.Hin * g.Win * g.Cout + (double)total * g.Cout) * es, 18.0 * total * g.Cout,
             (long)total, g.Cout, g.stride);
   int PH = (d.TH - 1) * g.stride + 3, PW = (d.TW - 1) * g.stride + 3;
-  size_t lds = (size_t)PH * PW * d.CGB * 8 * es + (size_t)9 * d.CGB * 8 * 4;
+  size_t lds = (size_t)PH * PW * d.CGB * 8 * 4 + (size_t)9 * d.CGB * 8 * 4;
   FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_fwd_k<T>, dim3(d.ntiles, d.nslab), dim3(d.CGB * d.PPB), lds, st,
                                       v, (const T*)w, g, d, (T*)z));
 }
@@ -385,8 +385,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void dw_dgrad_k(const T* __restrict__ dz, const T* __restrict__ w, ConvGeom g, DwPlan d, T* __restrict__ dIn) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   const int C = g.Cout, cgs = C / 8, s = g.stride;
-  T* patch = reinterpret_cast<T*>(smem_raw);
-  float* wl = reinterpret_cast<float*>(patch + (size_t)d.PH * d.PW * d.CGB * 8);   // [9][CGB][8]
+  float* patch = reinterpret_cast<float*>(smem_raw);
+  float* wl = patch + (size_t)d.PH * d.PW * d.CGB * 8;    // [9][CGB][8]
   const int cg = threadIdx.x % d.CGB, pl = threadIdx.x / d.CGB;
   const int cg0 = blockIdx.y * d.CGB, gcg = cg0 + cg;
   const int tile = blockIdx.x;
@@ -456,7 +456,7 @@ void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvG
   size_t total = (size_t)g.N * g.Hin * g.Win;
   KScope ks(st, "dw_dgrad", ((double)total * g.Cout + (double)g.N * g.Hout * g.Wout * g.Cout) * es, 18.0 * g.N * g.Hout * g.Wout * g.Cout,
             (long)total, g.Cout, g.stride);
-  size_t lds = (size_t)d.PH * d.PW * d.CGB * 8 * es + (size_t)9 * d.CGB * 8 * 4;
+  size_t lds = (size_t)d.PH * d.PW * d.CGB * 8 * 4 + (size_t)9 * d.CGB * 8 * 4;
   FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_dgrad_k<T>, dim3(d.ntiles, d.nslab), dim3(d.CGB * d.PPB), lds, st, (const T*)dz,
                                       (const T*)w, g, d, (T*)dIn));
 }
@@ -487,8 +487,9 @@ __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View
     lt.fetch(dz, n, th * d.TH, tw * d.TW, d.TH, d.TW, g.Hout, g.Wout, C, cg0, d.CGB);
   }
   for (int tile = blockIdx.x; tile < d.ntiles; tile += gridDim.x, ++it) {
-    T* patch = reinterpret_cast<T*>(smem_raw) + (it & 1) * (psz + tsz);
-    T* dzt = patch + psz;
+    float* patch = reinterpret_cast<float*>(smem_raw);
+    float* dzt = patch + psz;
+    __syncthreads();                                       // the previous tile has been consumed
     lp.commit(patch, in, PH, PW, cg0, d.CGB);
     lt.commit(dzt, none, d.TH, d.TW, cg0, d.CGB);          // zero outside the image
     __syncthreads();
@@ -531,7 +532,7 @@ static DwPlan dw_wgrad_plan(const ConvGeom& g, int es, int* parts, size_t* lds) 
   DwPlan d = dw_plan(g, es, g.Hout, g.Wout, kMaxPartials);
   *parts = 256 / (d.CGB * 9);
   int PH = (d.TH - 1) * g.stride + 3, PW = (d.TW - 1) * g.stride + 3;
-  size_t a = (size_t)2 * ((size_t)PH * PW + (size_t)d.TH * d.TW) * d.CGB * 8 * es;
+  size_t a = ((size_t)PH * PW + (size_t)d.TH * d.TW) * d.CGB * 8 * 4;   // float tiles
   size_t b = (size_t)*parts * 9 * d.CGB * 8 * 4;
   *lds = a > b ? a : b;
   return d;

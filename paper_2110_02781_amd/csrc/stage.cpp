@@ -230,7 +230,13 @@ struct ftp_stage {
   void* w_lp = nullptr;
   size_t stash_bytes = 0, stats_floats = 0, xin_bytes = 0, max_act_bytes = 0;
   std::vector<Slot> slots;
-  char *gbuf[4] = {nullptr, nullptr, nullptr, nullptr};   // boundary A/B, dz, dA
+  char *gbuf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};   // boundary A/B, dz (even), dA, dz (odd)
+  // Weight gradients depend on nothing downstream, so in backward they run on a second stream next to the
+  // data-gradient chain: fork after dz is formed, join before that dz buffer is overwritten / at the end.
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork[2] = {nullptr, nullptr}, ev_join[2] = {nullptr, nullptr};
+  bool join_pending[2] = {false, false};
+  unsigned n_sub_bwd = 0;
   float *bn_part = nullptr, *coef = nullptr, *ws = nullptr, *row_loss = nullptr;
   void* im2col = nullptr;     // patch matrix for the weight gradient of small dense convolutions
   size_t im2col_elems = 0;
@@ -247,7 +253,12 @@ static void stage_free(ftp_stage* s) {
   if (!s) return;
   dfree(s->params); dfree(s->grads); dfree(s->mom); dfree(s->run_mean); dfree(s->run_var); dfree(s->w_lp);
   for (auto& sl : s->slots) { dfree(sl.stash); dfree(sl.stats); dfree(sl.snap_w); dfree(sl.snap_lp); dfree(sl.dlogits); }
-  for (int i = 0; i < 4; ++i) dfree(s->gbuf[i]);
+  for (int i = 0; i < 5; ++i) dfree(s->gbuf[i]);
+  if (s->side) (void)hipStreamDestroy(s->side);
+  for (int i = 0; i < 2; ++i) {
+    if (s->ev_fork[i]) (void)hipEventDestroy(s->ev_fork[i]);
+    if (s->ev_join[i]) (void)hipEventDestroy(s->ev_join[i]);
+  }
   dfree(s->bn_part); dfree(s->coef); dfree(s->ws); dfree(s->row_loss); dfree(s->im2col);
   delete s;
 }
@@ -333,8 +344,16 @@ extern "C" int ftp_stage_create(const ftp_model* m, int a, int b, int batch, int
     if (s->dt == FTP_BF16 && (rc = dev_alloc(&sl.snap_lp, np * 2))) { stage_free(s); return rc; }
     if (s->has_loss && (rc = dev_alloc(&sl.dlogits, (size_t)batch * s->classes * s->es))) { stage_free(s); return rc; }
   }
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 5; ++i)
     if ((rc = dev_alloc(&s->gbuf[i], max_act))) { stage_free(s); return rc; }
+  {
+    hipError_t e = hipStreamCreateWithFlags(&s->side, hipStreamNonBlocking);     // default priority
+    for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+      e = hipEventCreateWithFlags(&s->ev_fork[i], hipEventDisableTiming);
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_join[i], hipEventDisableTiming);
+    }
+    if (e != hipSuccess) { ftp_set_error("stage_create: stream/event creation failed: %s", hipGetErrorString(e)); stage_free(s); return FTP_ERR_HIP; }
+  }
   if ((rc = dev_alloc(&s->bn_part, (size_t)kMaxPartials * 2 * max_c * 4)) || (rc = dev_alloc(&s->coef, (size_t)3 * max_c * 4)) ||
       (rc = dev_alloc(&s->ws, ws_floats * 4)) || (rc = dev_alloc(&s->row_loss, (size_t)batch * 4))) { stage_free(s); return rc; }
   if (s->im2col_elems && (rc = dev_alloc(&s->im2col, s->im2col_elems * s->es))) { stage_free(s); return rc; }
@@ -599,33 +618,59 @@ extern "C" int ftp_stage_snapshot_weights(ftp_stage* s, int slot, void* stream) 
 }
 
 // Backward of one convolution+BN+act: dA is the gradient of the activated output.
-// Writes dz into s->gbuf[2]; accumulates weight / gamma / beta gradients; when dIn is
-// non-NULL writes the gradient of the (activated) input there (+ res for pointwise).
-static void sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, const void* dA, HView in, HView out,
-                         void* dIn, const void* res, const WeightSet& W, hipStream_t st) {
+// Forms dz in one of two alternating buffers; accumulates weight / gamma / beta gradients; when dIn is
+// non-NULL writes the gradient of the (activated) input there (+ res for pointwise).  The weight
+// gradient runs on the stage's side stream unless per-unit profiling is on.
+static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, const void* dA, HView in, HView out,
+                        void* dIn, const void* res, const WeightSet& W, hipStream_t st) {
   const Sub& sb = p.info->subs[k];
   ConvGeom g = sb.g; g.N = s->batch;
   int C = g.Cout;
   size_t M = (size_t)s->batch * g.Hout * g.Wout;
   float* stt = sl.stats + p.st_off[k];
-  void* dz = s->gbuf[2];
+  const int b = (int)(s->n_sub_bwd++ & 1u);
+  void* dz = s->gbuf[b ? 4 : 2];
+  const bool overlap = s->prof == nullptr;
   int P = 0;
   bn_bwd_reduce(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->bn_part, &P);
   bn_bwd_finalize(st, s->bn_part, P, M, C, W.w32 + p.p_off + sb.gamma_off, stt, stt + C, s->grads + p.p_off + sb.gamma_off,
                   s->grads + p.p_off + sb.beta_off, s->coef);
+  if (s->join_pending[b]) {             // the weight gradient that last read this dz buffer must be done
+    HIP_TRY(hipStreamWaitEvent(st, s->ev_join[b], 0));
+    s->join_pending[b] = false;
+  }
   bn_bwd_apply(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->coef, dz);
+  hipStream_t ws = st;
+  if (overlap) {
+    HIP_TRY(hipEventRecord(s->ev_fork[b], st));
+    HIP_TRY(hipStreamWaitEvent(s->side, s->ev_fork[b], 0));
+    ws = s->side;
+  }
   const void* w = conv_w(s, W, p.p_off + sb.w_off);
   float* gw = s->grads + p.p_off + sb.w_off;
-  if (sb.type == SUB_DIRECT) {
-    conv_direct_wgrad(s->dt, st, dz, in, g, s->im2col, s->ws, gw);
-    if (dIn) conv_direct_dgrad(s->dt, st, dz, w, g, dIn);
-  } else if (sb.type == SUB_PW) {
-    pw_wgrad(s->dt, st, dz, in, M, g.Cin, g.Cout, s->ws, gw);
-    if (dIn) pw_dgrad(s->dt, st, dz, w, res, M, g.Cin, g.Cout, dIn);
-  } else {
-    dw_wgrad(s->dt, st, dz, in, g, s->ws, gw);
-    if (dIn) dw_dgrad(s->dt, st, dz, w, g, dIn);
+  if (sb.type == SUB_DIRECT) conv_direct_wgrad(s->dt, ws, dz, in, g, s->im2col, s->ws, gw);
+  else if (sb.type == SUB_PW) pw_wgrad(s->dt, ws, dz, in, M, g.Cin, g.Cout, s->ws, gw);
+  else dw_wgrad(s->dt, ws, dz, in, g, s->ws, gw);
+  if (overlap) {
+    HIP_TRY(hipEventRecord(s->ev_join[b], s->side));
+    s->join_pending[b] = true;
   }
+  if (dIn) {
+    if (sb.type == SUB_DIRECT) conv_direct_dgrad(s->dt, st, dz, w, g, dIn);
+    else if (sb.type == SUB_PW) pw_dgrad(s->dt, st, dz, w, res, M, g.Cin, g.Cout, dIn);
+    else dw_dgrad(s->dt, st, dz, w, g, dIn);
+  }
+  return FTP_OK;
+}
+
+// all side-stream work of this backward is ordered before whatever the caller enqueues next
+static int join_side(ftp_stage* s, hipStream_t st) {
+  for (int b = 0; b < 2; ++b)
+    if (s->join_pending[b]) {
+      HIP_TRY(hipStreamWaitEvent(st, s->ev_join[b], 0));
+      s->join_pending[b] = false;
+    }
+  return FTP_OK;
 }
 
 extern "C" int ftp_stage_backward(ftp_stage* s, int slot, const void* dy_dev, void* dx_dev, void* stream) {
@@ -667,22 +712,22 @@ extern "C" int ftp_stage_backward(ftp_stage* s, int slot, const void* dy_dev, vo
         if (next) gap_bwd(s->dt, st, d, s->batch, u.inH * u.inW, u.inC, next);
         break;
       case FTP_UNIT_CONV:
-        sub_backward(s, sl, p, 0, d, in, v.sub_out[i][0], next, nullptr, W, st);
+        if ((rc = sub_backward(s, sl, p, 0, d, in, v.sub_out[i][0], next, nullptr, W, st))) return rc;
         break;
       case FTP_UNIT_INVRES: {
         size_t ns = u.subs.size();
         void* tmp = s->gbuf[3];
         // project: gradient of the activated depthwise output
-        sub_backward(s, sl, p, ns - 1, d, v.sub_out[i][ns - 2], v.sub_out[i][ns - 1], tmp, nullptr, W, st);
+        if ((rc = sub_backward(s, sl, p, ns - 1, d, v.sub_out[i][ns - 2], v.sub_out[i][ns - 1], tmp, nullptr, W, st))) return rc;
         if (ns == 3) {
-          sub_backward(s, sl, p, 1, tmp, v.sub_out[i][0], v.sub_out[i][1], tmp, nullptr, W, st);
-          sub_backward(s, sl, p, 0, tmp, in, v.sub_out[i][0], next, u.residual ? d : nullptr, W, st);
+          if ((rc = sub_backward(s, sl, p, 1, tmp, v.sub_out[i][0], v.sub_out[i][1], tmp, nullptr, W, st))) return rc;
+          if ((rc = sub_backward(s, sl, p, 0, tmp, in, v.sub_out[i][0], next, u.residual ? d : nullptr, W, st))) return rc;
         } else {
           if (next && u.residual) {
-            sub_backward(s, sl, p, 0, tmp, in, v.sub_out[i][0], tmp, nullptr, W, st);
+            if ((rc = sub_backward(s, sl, p, 0, tmp, in, v.sub_out[i][0], tmp, nullptr, W, st))) return rc;
             bn_apply(s->dt, st, plain(tmp), (size_t)s->batch * u.inH * u.inW, u.inC, d, next);
           } else {
-            sub_backward(s, sl, p, 0, tmp, in, v.sub_out[i][0], next, nullptr, W, st);
+            if ((rc = sub_backward(s, sl, p, 0, tmp, in, v.sub_out[i][0], next, nullptr, W, st))) return rc;
           }
         }
         break;
@@ -693,6 +738,7 @@ extern "C" int ftp_stage_backward(ftp_stage* s, int slot, const void* dy_dev, vo
     if (s->prof) HIP_TRY(hipEventRecord(s->prof->b1[i], st));
     if (produced && next) { d = next; if (i > 0) flip ^= 1; }
   }
+  if ((rc = join_side(s, st))) return rc;
   HIP_TRY(hipGetLastError());
   sl.busy = false; sl.has_snap = false; sl.has_loss = false;
   return FTP_OK;
