@@ -278,6 +278,89 @@ void bn_bwd_apply(int dt, hipStream_t st, const void* dA, const void* z, size_t 
                                       (const T*)dA, (const T*)z, nvec, C / 8, scale, shift, act, coef, (T*)dz));
 }
 
+// BatchNorm backward for short tensors in ONE launch: a block owns 8 channels over all M rows, so it
+// can reduce, finalize and apply without any other block (the three-kernel path needs two grid-wide
+// dependencies, i.e. two extra launches, which dominate when the tensor is a few hundred KB).
+// Second pass re-reads dA and z from L2.
+template <typename T>
+__global__ __launch_bounds__(1024) void bn_bwd_small_k(const T* __restrict__ dA, const T* __restrict__ z, size_t M, int C,
+                                                       const float* __restrict__ scale, const float* __restrict__ shift, int act,
+                                                       const float* __restrict__ gamma, const float* __restrict__ mean,
+                                                       const float* __restrict__ invstd, float* g_gamma, float* g_beta,
+                                                       T* __restrict__ dz) {
+  __shared__ float red[16][16];   // [wave][value]
+  __shared__ float coef[3][8];
+  const int c0 = blockIdx.x * 8, tid = threadIdx.x, nt = blockDim.x;
+  float sc[8], sh[8];
+  load8(scale + c0, sc);
+  load8(shift + c0, sh);
+  const float lo = act_lo(act), hi = act_hi(act);
+  float acc[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  for (size_t m = tid; m < M; m += nt) {
+    float d[8], v[8];
+    load8(dA + m * C + c0, d);
+    load8(z + m * C + c0, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float y = fmaf(v[e], sc[e], sh[e]);
+      float dy = (y > lo && y < hi) ? d[e] : 0.f;
+      acc[e] += dy;
+      acc[8 + e] = fmaf(dy, v[e], acc[8 + e]);
+    }
+  }
+  // fixed-shape reduction: butterfly inside each wave, then the waves in order
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) acc[e] += __shfl_xor(acc[e], s, 64);
+  }
+  const int wave = tid >> 6, nw = nt >> 6;
+  if ((tid & 63) == 0) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) red[wave][e] = acc[e];
+  }
+  __syncthreads();
+  if (tid < 8) {
+    const int c = c0 + tid;
+    double s0 = 0.0, s1 = 0.0;
+    for (int w = 0; w < nw; ++w) { s0 += red[w][tid]; s1 += red[w][8 + tid]; }
+    const double mu = mean[c], is = invstd[c], g = gamma[c], Md = (double)M;
+    const double dbeta = s0, dgamma = is * (s1 - mu * s0);
+    g_gamma[c] += (float)dgamma;
+    g_beta[c] += (float)dbeta;
+    const double k1 = g * is, k2 = -k1 * is * dgamma / Md, k3 = -k1 * dbeta / Md - k2 * mu;
+    coef[0][tid] = (float)k1; coef[1][tid] = (float)k2; coef[2][tid] = (float)k3;
+  }
+  __syncthreads();
+  float k1[8], k2[8], k3[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { k1[e] = coef[0][e]; k2[e] = coef[1][e]; k3[e] = coef[2][e]; }
+  for (size_t m = tid; m < M; m += nt) {
+    float d[8], v[8], o[8];
+    load8(dA + m * C + c0, d);
+    load8(z + m * C + c0, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float y = fmaf(v[e], sc[e], sh[e]);
+      float dy = (y > lo && y < hi) ? d[e] : 0.f;
+      o[e] = fmaf(k1[e], dy, fmaf(k2[e], v[e], k3[e]));
+    }
+    store8(dz + m * C + c0, o);
+  }
+}
+
+int bn_bwd_small_ok(size_t M, int C) { return M <= 2048 && C >= 32; }
+
+void bn_bwd_small(int dt, hipStream_t st, const void* dA, const void* z, size_t M, int C, const float* scale,
+                  const float* shift, int act, const float* gamma, const float* mean, const float* invstd,
+                  float* g_gamma, float* g_beta, void* dz) {
+  KScope ks(st, "bn_bwd_small", 3.0 * M * C * (dt == 0 ? 4.0 : 2.0), 12.0 * M * C);
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_bwd_small_k<T>, dim3(C / 8), dim3(M > 512 ? 1024 : (M > 256 ? 512 : 256)), 0, st, (const T*)dA, (const T*)z, M, C, scale,
+                                      shift, act, gamma, mean, invstd, g_gamma, g_beta, (T*)dz));
+}
+
 template <typename T>
 __global__ void bn_apply_k(View in, size_t nvec, int CG, const T* __restrict__ res, T* __restrict__ out) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (size_t)gridDim.x * blockDim.x) {

@@ -21,6 +21,7 @@
 // problems), and 32 x 64 with the four wavefronts splitting a 128-long reduction
 // chunk (short problems: few rows, long reductions; keeps all CUs busy).
 // bfloat16 uses v_mfma_f32_32x32x16_bf16, float uses v_mfma_f32_32x32x2_f32.
+#include <stdlib.h>
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -603,6 +604,152 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
   }
 }
 
+// ---- short problems: 16 x 16 output tiles, operands straight from global memory ----------------
+// When M x N is small the layer is pure latency: staged tiles would leave most CUs idle behind a long
+// serial reduction.  Here a block owns one 16 x 16 tile, its four wavefronts split the reduction,
+// every lane loads its MFMA fragments (G consecutive reduction elements) directly as vectors, and the
+// four partial tiles are summed through LDS in a fixed order.
+typedef float f4v __attribute__((ext_vector_type(4)));
+template <typename T> struct TinyStep;
+template <> struct TinyStep<float> { enum { G = 4, KS = 16 }; };
+template <> struct TinyStep<bf16_t> { enum { G = 8, KS = 32 }; };
+
+__device__ __forceinline__ void load_frag(const float* p, float* v) {
+  float4 a = *reinterpret_cast<const float4*>(p);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+}
+__device__ __forceinline__ void load_frag(const bf16_t* p, float* v) { load8(p, v); }
+
+__device__ __forceinline__ f4v tiny_mma(const float* a, const float* b, f4v acc, float) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e], b[e], acc, 0, 0, 0);
+  return acc;
+}
+__device__ __forceinline__ f4v tiny_mma(const float* a, const float* b, f4v acc, bf16_t) {
+  uint4 pa, pb;
+  pa.x = f32x2_to_bf16x2(a[0], a[1]); pa.y = f32x2_to_bf16x2(a[2], a[3]);
+  pa.z = f32x2_to_bf16x2(a[4], a[5]); pa.w = f32x2_to_bf16x2(a[6], a[7]);
+  pb.x = f32x2_to_bf16x2(b[0], b[1]); pb.y = f32x2_to_bf16x2(b[2], b[3]);
+  pb.z = f32x2_to_bf16x2(b[4], b[5]); pb.w = f32x2_to_bf16x2(b[6], b[7]);
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa), __builtin_bit_cast(bf16x8, pb), acc, 0, 0, 0);
+}
+
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void pw_gemm_tiny_k(GemmArgs p) {
+  constexpr int G = TinyStep<T>::G, KS = TinyStep<T>::KS, U = 4;
+  __shared__ float red[4][16][17];
+  __shared__ float sred[2][16][17];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int jt = blockIdx.x % p.jtiles, it = blockIdx.x / p.jtiles;
+  const size_t i0 = (size_t)it * 16;
+  const int j0 = jt * 16;
+  const int R = MODE == MODE_FWD ? p.K : p.N;       // reduction extent (a multiple of G)
+  const int nj = MODE == MODE_FWD ? p.N : p.K;      // output columns
+  const int nst = (R + KS - 1) / KS;
+  const int sb = wave * nst / 4, se = (wave + 1) * nst / 4;
+  const int l16 = lane & 15, kg = (lane >> 4) * G;
+  const size_t row = i0 + l16;
+  const int col = j0 + l16;
+  const bool row_ok = row < p.M, col_ok = col < nj;
+  const T* X = reinterpret_cast<const T*>(p.x) + row * (size_t)R;
+  const T* W = reinterpret_cast<const T*>(p.y);
+  const bool view = MODE == MODE_FWD && p.view.scale != nullptr;
+  const float lo = act_lo(p.view.act), hi = act_hi(p.view.act);
+
+  f4v acc = {0.f, 0.f, 0.f, 0.f};
+  for (int s = sb; s < se; s += U) {
+    float a[U][G], b[U][G], sc[U][G], sh[U][G];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int k = (s + u) * KS + kg;
+      const bool ok = s + u < se && k < R;
+#pragma unroll
+      for (int e = 0; e < G; ++e) { a[u][e] = 0.f; b[u][e] = 0.f; sc[u][e] = 1.f; sh[u][e] = 0.f; }
+      if (ok && row_ok) {
+        load_frag(X + k, a[u]);
+        if (view) {
+          load_frag(p.view.scale + k, sc[u]);
+          load_frag(p.view.shift + k, sh[u]);
+          if (G == 8) { load_frag(p.view.scale + k + 4, sc[u] + 4); load_frag(p.view.shift + k + 4, sh[u] + 4); }
+        }
+      }
+      if (ok && col_ok) {
+        if (MODE == MODE_FWD) {
+          load_frag(W + (size_t)col * p.K + k, b[u]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < G; ++e) b[u][e] = to_f32(W[(size_t)(k + e) * p.K + col]);
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (view) {
+        const bool live = s + u < se && (s + u) * KS + kg < R && row_ok;   // padding stays exactly zero
+#pragma unroll
+        for (int e = 0; e < G; ++e) {
+          float y = round_to<T>(clamp_act(fmaf(a[u][e], sc[u][e], sh[u][e]), lo, hi));
+          a[u][e] = live ? y : 0.f;
+        }
+      }
+      acc = tiny_mma(a[u], b[u], acc, T());
+    }
+  }
+
+  // register r of lane l is C[4*(l/16) + r][l%16]
+#pragma unroll
+  for (int r = 0; r < 4; ++r) red[wave][4 * (lane >> 4) + r][l16] = acc[r];
+  __syncthreads();
+  const int orow = threadIdx.x >> 4, ocol = threadIdx.x & 15;
+  const size_t ig = i0 + orow;
+  const int jg = j0 + ocol;
+  const bool in = ig < p.M && jg < nj;
+  float v = red[0][orow][ocol] + red[1][orow][ocol] + red[2][orow][ocol] + red[3][orow][ocol];
+  if (MODE == MODE_FWD) {
+    if (p.bias && jg < nj) v += p.bias[jg];
+    if (in) reinterpret_cast<T*>(p.out)[ig * p.N + jg] = from_f32<T>(v);
+    if (p.stats) {
+      const float sv = in ? round_to<T>(v) : 0.f;     // statistics of the values as stored
+      sred[0][orow][ocol] = sv;
+      sred[1][orow][ocol] = sv * sv;
+      __syncthreads();
+      if (threadIdx.x < 32) {
+        const int sq = threadIdx.x >> 4, c = threadIdx.x & 15;
+        float tot = 0.f;
+#pragma unroll
+        for (int rr = 0; rr < 16; ++rr) tot += sred[sq][rr][c];
+        if (j0 + c < p.N) p.stats[((size_t)it * 2 + sq) * p.N + j0 + c] = tot;
+      }
+    }
+  } else {
+    if (in) {
+      if (p.res) v += to_f32(reinterpret_cast<const T*>(p.res)[ig * p.K + jg]);
+      reinterpret_cast<T*>(p.out)[ig * p.K + jg] = from_f32<T>(v);
+    }
+  }
+}
+
+// the 16 x 16 kernel serves problems whose output is short (few rows) and whose reduction extent
+// allows aligned vector fragments
+static bool tiny_ok(int dt, size_t M, int R, bool stats) {
+  const int G = dt == 0 ? 4 : 8;
+  static const long max_m = getenv("FTP_TINY_M") ? atol(getenv("FTP_TINY_M")) : 2048;
+  if ((long)M > max_m || R % G != 0) return false;
+  if (stats && (M + 15) / 16 > (size_t)kMaxPartials) return false;
+  return true;
+}
+
+template <int MODE>
+static void launch_tiny(int dt, hipStream_t st, GemmArgs& a, int ncols) {
+  a.jtiles = (ncols + 15) / 16;
+  a.itiles = (int)((a.M + 15) / 16);
+  a.nranges = a.itiles;
+  a.tiles_per_range = 1;
+  unsigned grid = (unsigned)((size_t)a.jtiles * a.itiles);
+  if (dt == 0) hipLaunchKernelGGL((pw_gemm_tiny_k<float, MODE>), dim3(grid), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((pw_gemm_tiny_k<bf16_t, MODE>), dim3(grid), dim3(256), 0, st, a);
+}
+
 template <int MODE>
 static void launch(int dt, hipStream_t st, const GemmArgs& a, bool small) {
   unsigned grid = (unsigned)((size_t)a.jtiles * a.nranges);
@@ -630,34 +777,34 @@ static void plan_rows(size_t M, int ncols, int R, GemmArgs* a, bool* small) {
   a->nranges = (a->itiles + a->tiles_per_range - 1) / a->tiles_per_range;
 }
 
-int pw_fwd_partials(size_t M, int K, int N) {
-  GemmArgs a{};
-  bool small;
-  plan_rows(M, N, K, &a, &small);
-  return a.nranges;
-}
-
 void pw_fwd(int dt, hipStream_t st, HView av, const void* w, const float* bias, size_t M, int K, int N,
             void* z, float* stats, int* P_out) {
   GemmArgs a{};
   a.x = av.z; a.y = w; a.view = View{av.z, av.scale, av.shift, av.act};
   a.bias = bias; a.out = z; a.stats = stats; a.M = M; a.K = K; a.N = N;
+  KScope ks(st, "pw_fwd", ((double)M * K + (double)M * N + (double)N * K) * (dt == 0 ? 4.0 : 2.0), 2.0 * M * K * N, (long)M, K, N);
+  if (tiny_ok(dt, M, K, stats != nullptr)) {
+    launch_tiny<MODE_FWD>(dt, st, a, N);
+    if (P_out) *P_out = a.nranges;
+    return;
+  }
   bool small;
   plan_rows(M, N, K, &a, &small);
   if (P_out) *P_out = a.nranges;
-  {
-    KScope ks(st, "pw_fwd", ((double)M * K + (double)M * N + (double)N * K) * (dt == 0 ? 4.0 : 2.0), 2.0 * M * K * N, (long)M, K, N);
-    launch<MODE_FWD>(dt, st, a, small);
-  }
+  launch<MODE_FWD>(dt, st, a, small);
 }
 
 void pw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const void* res, size_t M, int K,
               int N, void* dA) {
   GemmArgs a{};
   a.x = dz; a.y = w; a.res = res; a.out = dA; a.M = M; a.K = K; a.N = N;
+  KScope ks(st, "pw_dgrad", ((double)M * K * (res ? 2.0 : 1.0) + (double)M * N + (double)N * K) * (dt == 0 ? 4.0 : 2.0), 2.0 * M * K * N, (long)M, K, N);
+  if (tiny_ok(dt, M, N, false)) {
+    launch_tiny<MODE_DGRAD>(dt, st, a, K);
+    return;
+  }
   bool small;
   plan_rows(M, K, N, &a, &small);
-  KScope ks(st, "pw_dgrad", ((double)M * K * (res ? 2.0 : 1.0) + (double)M * N + (double)N * K) * (dt == 0 ? 4.0 : 2.0), 2.0 * M * K * N, (long)M, K, N);
   launch<MODE_DGRAD>(dt, st, a, small);
 }
 

@@ -58,6 +58,11 @@ void bn_bwd_finalize(hipStream_t st, const float* partial, int P, size_t M, int 
 // dz (may alias dA) = k1*dA*act'(y) + k2*z + k3
 void bn_bwd_apply(int dt, hipStream_t st, const void* dA, const void* z, size_t M, int C,
                   const float* scale, const float* shift, int act, const float* coef, void* dz);
+// the three steps above in one launch for short tensors (bn_bwd_small_ok); dz must not alias dA
+int bn_bwd_small_ok(size_t M, int C);
+void bn_bwd_small(int dt, hipStream_t st, const void* dA, const void* z, size_t M, int C, const float* scale,
+                  const float* shift, int act, const float* gamma, const float* mean, const float* invstd,
+                  float* g_gamma, float* g_beta, void* dz);
 // out = act(scale*z+shift) (+ res)
 void bn_apply(int dt, hipStream_t st, HView in, size_t M, int C, const void* res, void* out);
 

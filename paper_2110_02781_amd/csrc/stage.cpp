@@ -631,15 +631,22 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
   const int b = (int)(s->n_sub_bwd++ & 1u);
   void* dz = s->gbuf[b ? 4 : 2];
   const bool overlap = s->prof == nullptr;
-  int P = 0;
-  bn_bwd_reduce(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->bn_part, &P);
-  bn_bwd_finalize(st, s->bn_part, P, M, C, W.w32 + p.p_off + sb.gamma_off, stt, stt + C, s->grads + p.p_off + sb.gamma_off,
-                  s->grads + p.p_off + sb.beta_off, s->coef);
+  const bool small = bn_bwd_small_ok(M, C) != 0;
+  if (!small) {
+    int P = 0;
+    bn_bwd_reduce(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->bn_part, &P);
+    bn_bwd_finalize(st, s->bn_part, P, M, C, W.w32 + p.p_off + sb.gamma_off, stt, stt + C, s->grads + p.p_off + sb.gamma_off,
+                    s->grads + p.p_off + sb.beta_off, s->coef);
+  }
   if (s->join_pending[b]) {             // the weight gradient that last read this dz buffer must be done
     HIP_TRY(hipStreamWaitEvent(st, s->ev_join[b], 0));
     s->join_pending[b] = false;
   }
-  bn_bwd_apply(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->coef, dz);
+  if (small)
+    bn_bwd_small(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, W.w32 + p.p_off + sb.gamma_off, stt, stt + C,
+                 s->grads + p.p_off + sb.gamma_off, s->grads + p.p_off + sb.beta_off, dz);
+  else
+    bn_bwd_apply(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->coef, dz);
   hipStream_t ws = st;
   if (overlap) {
     HIP_TRY(hipEventRecord(s->ev_fork[b], st));
