@@ -117,4 +117,24 @@ __device__ __forceinline__ void view_load8(const View& v, size_t idx, int c, flo
   }
 }
 
+// Sum over the 64 lanes of a wavefront without touching LDS: butterflies inside each row of 16 lanes
+// with data-parallel-primitive moves (VALU rate; cross-lane permutes through LDS cost ~20 cycles per
+// instruction), then the four row totals in lane order.  Every lane returns the same value.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float wave_sum(float x) {
+  x += dpp_move<0xB1>(x);    // quad_perm [1,0,3,2]
+  x += dpp_move<0x4E>(x);    // quad_perm [2,3,0,1]
+  x += dpp_move<0x141>(x);   // row_half_mirror
+  x += dpp_move<0x140>(x);   // row_mirror
+  const int xi = __builtin_bit_cast(int, x);
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 48));
+  return ((r0 + r1) + r2) + r3;
+}
+
 }  // namespace ftp

@@ -282,7 +282,7 @@ void bn_bwd_apply(int dt, hipStream_t st, const void* dA, const void* z, size_t 
 // can reduce, finalize and apply without any other block (the three-kernel path needs two grid-wide
 // dependencies, i.e. two extra launches, which dominate when the tensor is a few hundred KB).
 // Second pass re-reads dA and z from L2.
-template <typename T>
+template <typename T, int RPT>
 __global__ __launch_bounds__(1024) void bn_bwd_small_k(const T* __restrict__ dA, const T* __restrict__ z, size_t M, int C,
                                                        const float* __restrict__ scale, const float* __restrict__ shift, int act,
                                                        const float* __restrict__ gamma, const float* __restrict__ mean,
@@ -290,7 +290,20 @@ __global__ __launch_bounds__(1024) void bn_bwd_small_k(const T* __restrict__ dA,
                                                        T* __restrict__ dz) {
   __shared__ float red[16][16];   // [wave][value]
   __shared__ float coef[3][8];
-  const int c0 = blockIdx.x * 8, tid = threadIdx.x, nt = blockDim.x;
+  const int c0 = blockIdx.x * 8, tid = threadIdx.x, nt = blockDim.x;   // RPT * nt >= M
+  // every thread keeps its rows in registers: one trip to memory, then reduce, then apply
+  float d[RPT][8], v[RPT][8];
+#pragma unroll
+  for (int q = 0; q < RPT; ++q) {
+    const size_t m = tid + (size_t)q * nt;
+    if (m < M) {
+      load8(dA + m * C + c0, d[q]);
+      load8(z + m * C + c0, v[q]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { d[q][e] = 0.f; v[q][e] = 0.f; }
+    }
+  }
   float sc[8], sh[8];
   load8(scale + c0, sc);
   load8(shift + c0, sh);
@@ -298,24 +311,20 @@ __global__ __launch_bounds__(1024) void bn_bwd_small_k(const T* __restrict__ dA,
   float acc[16];
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-  for (size_t m = tid; m < M; m += nt) {
-    float d[8], v[8];
-    load8(dA + m * C + c0, d);
-    load8(z + m * C + c0, v);
+#pragma unroll
+  for (int q = 0; q < RPT; ++q) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      float y = fmaf(v[e], sc[e], sh[e]);
-      float dy = (y > lo && y < hi) ? d[e] : 0.f;
+      float y = fmaf(v[q][e], sc[e], sh[e]);
+      float dy = (y > lo && y < hi) ? d[q][e] : 0.f;   // rows past M hold zeros
+      d[q][e] = dy;
       acc[e] += dy;
-      acc[8 + e] = fmaf(dy, v[e], acc[8 + e]);
+      acc[8 + e] = fmaf(dy, v[q][e], acc[8 + e]);
     }
   }
-  // fixed-shape reduction: butterfly inside each wave, then the waves in order
+  // fixed-shape reduction: inside each wave, then the waves in order
 #pragma unroll
-  for (int e = 0; e < 16; ++e) {
-#pragma unroll
-    for (int s = 32; s > 0; s >>= 1) acc[e] += __shfl_xor(acc[e], s, 64);
-  }
+  for (int e = 0; e < 16; ++e) acc[e] = wave_sum(acc[e]);
   const int wave = tid >> 6, nw = nt >> 6;
   if ((tid & 63) == 0) {
 #pragma unroll
@@ -337,16 +346,13 @@ __global__ __launch_bounds__(1024) void bn_bwd_small_k(const T* __restrict__ dA,
   float k1[8], k2[8], k3[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) { k1[e] = coef[0][e]; k2[e] = coef[1][e]; k3[e] = coef[2][e]; }
-  for (size_t m = tid; m < M; m += nt) {
-    float d[8], v[8], o[8];
-    load8(dA + m * C + c0, d);
-    load8(z + m * C + c0, v);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float y = fmaf(v[e], sc[e], sh[e]);
-      float dy = (y > lo && y < hi) ? d[e] : 0.f;
-      o[e] = fmaf(k1[e], dy, fmaf(k2[e], v[e], k3[e]));
-    }
+  for (int q = 0; q < RPT; ++q) {
+    const size_t m = tid + (size_t)q * nt;
+    if (m >= M) continue;
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = fmaf(k1[e], d[q][e], fmaf(k2[e], v[q][e], k3[e]));
     store8(dz + m * C + c0, o);
   }
 }
@@ -356,9 +362,15 @@ int bn_bwd_small_ok(size_t M, int C) { return M <= 2048 && C >= 32; }
 void bn_bwd_small(int dt, hipStream_t st, const void* dA, const void* z, size_t M, int C, const float* scale,
                   const float* shift, int act, const float* gamma, const float* mean, const float* invstd,
                   float* g_gamma, float* g_beta, void* dz) {
-  KScope ks(st, "bn_bwd_small", 3.0 * M * C * (dt == 0 ? 4.0 : 2.0), 12.0 * M * C);
-  FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_bwd_small_k<T>, dim3(C / 8), dim3(M > 512 ? 1024 : (M > 256 ? 512 : 256)), 0, st, (const T*)dA, (const T*)z, M, C, scale,
-                                      shift, act, gamma, mean, invstd, g_gamma, g_beta, (T*)dz));
+  KScope ks(st, "bn_bwd_small", 3.0 * M * C * (dt == 0 ? 4.0 : 2.0), 12.0 * M * C, (long)M, C);
+  const int nt = M > 512 ? 1024 : (M > 256 ? 512 : 256);
+  if (M > 1024) {
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((bn_bwd_small_k<T, 2>), dim3(C / 8), dim3(nt), 0, st, (const T*)dA, (const T*)z, M, C, scale,
+                                        shift, act, gamma, mean, invstd, g_gamma, g_beta, (T*)dz));
+  } else {
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((bn_bwd_small_k<T, 1>), dim3(C / 8), dim3(nt), 0, st, (const T*)dA, (const T*)z, M, C, scale,
+                                        shift, act, gamma, mean, invstd, g_gamma, g_beta, (T*)dz));
+  }
 }
 
 template <typename T>

@@ -21,7 +21,6 @@
 // problems), and 32 x 64 with the four wavefronts splitting a 128-long reduction
 // chunk (short problems: few rows, long reductions; keeps all CUs busy).
 // bfloat16 uses v_mfma_f32_32x32x16_bf16, float uses v_mfma_f32_32x32x2_f32.
-#include <stdlib.h>
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -731,10 +730,10 @@ __global__ __launch_bounds__(256) void pw_gemm_tiny_k(GemmArgs p) {
 
 // the 16 x 16 kernel serves problems whose output is short (few rows) and whose reduction extent
 // allows aligned vector fragments
-static bool tiny_ok(int dt, size_t M, int R, bool stats) {
+static bool tiny_ok(int dt, size_t M, int R, int ncols, bool stats) {
   const int G = dt == 0 ? 4 : 8;
-  static const long max_m = getenv("FTP_TINY_M") ? atol(getenv("FTP_TINY_M")) : 2048;
-  if ((long)M > max_m || R % G != 0) return false;
+  if (M > 2048 || R % G != 0) return false;      // measured: taller problems run faster on the staged kernels
+  if ((double)M * R * ncols > 64.0 * 1024 * 1024) return false;   // every block re-reads its operand rows
   if (stats && (M + 15) / 16 > (size_t)kMaxPartials) return false;
   return true;
 }
@@ -783,7 +782,7 @@ void pw_fwd(int dt, hipStream_t st, HView av, const void* w, const float* bias, 
   a.x = av.z; a.y = w; a.view = View{av.z, av.scale, av.shift, av.act};
   a.bias = bias; a.out = z; a.stats = stats; a.M = M; a.K = K; a.N = N;
   KScope ks(st, "pw_fwd", ((double)M * K + (double)M * N + (double)N * K) * (dt == 0 ? 4.0 : 2.0), 2.0 * M * K * N, (long)M, K, N);
-  if (tiny_ok(dt, M, K, stats != nullptr)) {
+  if (tiny_ok(dt, M, K, N, stats != nullptr)) {
     launch_tiny<MODE_FWD>(dt, st, a, N);
     if (P_out) *P_out = a.nranges;
     return;
@@ -799,7 +798,7 @@ void pw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const void*
   GemmArgs a{};
   a.x = dz; a.y = w; a.res = res; a.out = dA; a.M = M; a.K = K; a.N = N;
   KScope ks(st, "pw_dgrad", ((double)M * K * (res ? 2.0 : 1.0) + (double)M * N + (double)N * K) * (dt == 0 ? 4.0 : 2.0), 2.0 * M * K * N, (long)M, K, N);
-  if (tiny_ok(dt, M, N, false)) {
+  if (tiny_ok(dt, M, N, K, false)) {
     launch_tiny<MODE_DGRAD>(dt, st, a, K);
     return;
   }
