@@ -238,10 +238,133 @@ struct TransLoader {
   }
 };
 
-template <typename T, int ROWS, int CH, bool RC, bool USE_VIEW, bool PERM = false>
+// Branch-free loaders for problems whose extents along the vectorised dimension are multiples of 8
+// (every layer of the networks here except the classifier output): a vector is then wholly inside or
+// wholly outside the tensor; outside ones are loaded from the base address, which is always valid,
+// and zeroed by a select.  The generic loaders above spend most of their instructions on
+// per-element bounds branches that never fire for such shapes.
+template <typename T, int ROWS, int CH, bool USE_VIEW, bool PERM>
+struct VecTileLoader {   // r-contiguous source
+  enum { NVEC = ROWS * CH / 8, PER = NVEC / 256, LD = CH + Pad<T>::V };
+  static_assert(NVEC % 256 == 0, "tile must divide over 256 threads");
+  Raw<T> raw[PER];
+  unsigned ok;
+
+  __device__ __forceinline__ void fetch(const T* __restrict__ src, size_t ld, size_t i0, size_t ni, size_t r0,
+                                        size_t nr) {
+    ok = 0;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int v = threadIdx.x + q * 256;
+      const int i = v / (CH / 8), r = (v % (CH / 8)) * 8;
+      const size_t gi = i0 + i, gr = r0 + r;
+      const bool in = gi < ni && gr < nr;
+      raw_load(raw[q], in ? src + gi * ld + gr : src);
+      ok |= (in ? 1u : 0u) << q;
+    }
+  }
+
+  __device__ __forceinline__ void commit(T* lds, const T* __restrict__, size_t, size_t, size_t, size_t r0, size_t,
+                                         const View& vw) const {
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int v = threadIdx.x + q * 256;
+      const int i = v / (CH / 8), r = (v % (CH / 8)) * 8;
+      const bool in = (ok >> q) & 1u;
+      float val[8];
+      raw_unpack(raw[q], val);
+      if (USE_VIEW && vw.scale) {
+        const size_t ch = in ? r0 + r : 0;
+        float sc[8], sh[8];
+        load8(vw.scale + ch, sc);
+        load8(vw.shift + ch, sh);
+        const float lo = act_lo(vw.act), hi = act_hi(vw.act);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) val[e] = clamp_act(fmaf(val[e], sc[e], sh[e]), lo, hi);
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) val[e] = in ? val[e] : 0.f;
+      store8(lds + (PERM ? perm64(i) : i) * LD + r, val);
+    }
+  }
+};
+
+template <typename T, int ROWS, int CH, bool USE_VIEW, bool PERM>
+struct VecTransLoader {  // i-contiguous source, transposed into (r, r+1) pairs like TransLoader
+  enum { NITEM = (ROWS / 8) * (CH / 2), PER = (NITEM + 255) / 256, LD = CH + Pad<T>::V };
+  Raw<T> raw[PER][2];
+  unsigned ok;
+
+  __device__ __forceinline__ void fetch(const T* __restrict__ src, size_t ld, size_t i0, size_t ni, size_t r0,
+                                        size_t nr) {
+    ok = 0;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int item = threadIdx.x + q * 256;
+      if (item >= NITEM) break;
+      const int r = (item % (CH / 2)) * 2, i = (item / (CH / 2)) * 8;
+      const size_t gi = i0 + i;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const size_t gr = r0 + r + u;
+        const bool in = gr < nr && gi < ni;
+        raw_load(raw[q][u], in ? src + gr * ld + gi : src);
+        ok |= (in ? 1u : 0u) << (2 * q + u);
+      }
+    }
+  }
+
+  __device__ __forceinline__ void commit(T* lds, const T* __restrict__, size_t, size_t i0, size_t, size_t, size_t,
+                                         const View& vw) const {
+    const bool view = USE_VIEW && vw.scale != nullptr;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int item = threadIdx.x + q * 256;
+      if (item >= NITEM) break;
+      const int r = (item % (CH / 2)) * 2, i = (item / (CH / 2)) * 8;
+      const bool in0 = (ok >> (2 * q)) & 1u, in1 = (ok >> (2 * q + 1)) & 1u;
+      if (sizeof(T) == 2 && !view) {
+        // raw bits straight into (r, r+1) pairs
+        const uint32_t* w0 = reinterpret_cast<const uint32_t*>(&raw[q][0]);
+        const uint32_t* w1 = reinterpret_cast<const uint32_t*>(&raw[q][1]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t a = in0 ? w0[e >> 1] : 0u, b = in1 ? w1[e >> 1] : 0u;
+          const uint32_t pr = (e & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+          *reinterpret_cast<uint32_t*>(lds + (PERM ? perm64(i + e) : i + e) * LD + r) = pr;
+        }
+        continue;
+      }
+      float val[2][8];
+      raw_unpack(raw[q][0], val[0]);
+      raw_unpack(raw[q][1], val[1]);
+      if (view) {
+        const size_t ch = (in0 || in1) ? i0 + i : 0;     // same channels for both rows
+        float sc[8], sh[8];
+        load8(vw.scale + ch, sc);
+        load8(vw.shift + ch, sh);
+        const float lo = act_lo(vw.act), hi = act_hi(vw.act);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          val[0][e] = clamp_act(fmaf(val[0][e], sc[e], sh[e]), lo, hi);
+          val[1][e] = clamp_act(fmaf(val[1][e], sc[e], sh[e]), lo, hi);
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        lds_put_pair(lds + (PERM ? perm64(i + e) : i + e) * LD + r, in0 ? val[0][e] : 0.f, in1 ? val[1][e] : 0.f);
+    }
+  }
+};
+
+template <typename T, int ROWS, int CH, bool RC, bool USE_VIEW, bool PERM, bool VEC>
 struct LoaderSel { typedef TileLoader<T, ROWS, CH, true, USE_VIEW, PERM> type; };
 template <typename T, int ROWS, int CH, bool USE_VIEW, bool PERM>
-struct LoaderSel<T, ROWS, CH, false, USE_VIEW, PERM> { typedef TransLoader<T, ROWS, CH, USE_VIEW, PERM> type; };
+struct LoaderSel<T, ROWS, CH, false, USE_VIEW, PERM, false> { typedef TransLoader<T, ROWS, CH, USE_VIEW, PERM> type; };
+template <typename T, int ROWS, int CH, bool USE_VIEW, bool PERM>
+struct LoaderSel<T, ROWS, CH, true, USE_VIEW, PERM, true> { typedef VecTileLoader<T, ROWS, CH, USE_VIEW, PERM> type; };
+template <typename T, int ROWS, int CH, bool USE_VIEW, bool PERM>
+struct LoaderSel<T, ROWS, CH, false, USE_VIEW, PERM, true> { typedef VecTransLoader<T, ROWS, CH, USE_VIEW, PERM> type; };
 
 // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Renumbering them so that
 // consecutive logical ids share an XCD keeps the column tiles of one row range (which re-read the
@@ -286,7 +409,7 @@ __device__ __forceinline__ void mma32(const float* xs, const float* ys, int LD, 
   }
 }
 
-template <typename T, int MODE, bool SMALL>
+template <typename T, int MODE, bool SMALL, bool VEC>
 __global__ __launch_bounds__(256) void pw_gemm_k(GemmArgs p) {
   constexpr int TI = Shape<SMALL>::TI, CH = Shape<SMALL>::CH;
   constexpr int LD = CH + Pad<T>::V;
@@ -332,8 +455,8 @@ __global__ __launch_bounds__(256) void pw_gemm_k(GemmArgs p) {
   // forward: X = A' (r-contiguous, view), Y = W (r-contiguous)
   // dgrad  : X = dZ (r-contiguous),       Y = W as (j=k, r=n)  (i-contiguous)
   // wgrad  : X = dZ as (i=n, r=m),        Y = A' as (j=k, r=m) (both i-contiguous, view on Y)
-  typename LoaderSel<T, TI, CH, MODE != MODE_WGRAD, MODE == MODE_FWD>::type lx;
-  typename LoaderSel<T, BJ, CH, MODE == MODE_FWD, MODE == MODE_WGRAD>::type ly;
+  typename LoaderSel<T, TI, CH, MODE != MODE_WGRAD, MODE == MODE_FWD, false, VEC>::type lx;
+  typename LoaderSel<T, BJ, CH, MODE == MODE_FWD, MODE == MODE_WGRAD, false, VEC>::type ly;
 
   f16v acc[2];
 #pragma unroll
@@ -477,7 +600,7 @@ __device__ __forceinline__ void load_pair(const bf16_t* p, float& a, float& b) {
   a = __uint_as_float(v << 16); b = __uint_as_float(v & 0xffff0000u);
 }
 
-template <typename T, int MODE>
+template <typename T, int MODE, bool VEC>
 __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
   constexpr int TI = 128, CH = 32;
   constexpr int LD = CH + Pad<T>::V;
@@ -515,8 +638,8 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
   const size_t nj = MODE == MODE_FWD ? (size_t)p.N : (size_t)p.K;
   const size_t ldo = nj;                   // leading dimension of the output
 
-  typename LoaderSel<T, TI, CH, MODE != MODE_WGRAD, MODE == MODE_FWD>::type lx;
-  typename LoaderSel<T, BJ, CH, MODE == MODE_FWD, MODE == MODE_WGRAD, true>::type ly;
+  typename LoaderSel<T, TI, CH, MODE != MODE_WGRAD, MODE == MODE_FWD, false, VEC>::type lx;
+  typename LoaderSel<T, BJ, CH, MODE == MODE_FWD, MODE == MODE_WGRAD, true, VEC>::type ly;
 
   f16v acc[2];
 #pragma unroll
@@ -555,9 +678,34 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
     if (kc + 1 < nchunks) continue;
 
     // tile finished: register r of this lane is row 8*(r/4) + 4*h + r%4, columns jc (acc[0]) and jc+1 (acc[1])
+    const size_t irow = i0 + wave * 32 + 4 * h;
+    if (VEC && i0 + TI <= ni && j0 + BJ <= nj) {
+      // interior tile of an even-width problem: no bounds tests, one address computation per lane
+      const size_t obase = (MODE == MODE_WGRAD ? (size_t)split * p.N + irow : irow) * ldo + jc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const size_t o = obase + (size_t)(8 * (r / 4) + (r % 4)) * ldo;
+        float v0 = acc[0][r], v1 = acc[1][r];
+        acc[0][r] = 0.f; acc[1][r] = 0.f;
+        if (MODE == MODE_FWD) {
+          v0 += b0; v1 += b1;
+          store_pair(reinterpret_cast<T*>(p.out) + o, v0, v1);
+          if (p.stats) {
+            float a = round_to<T>(v0), b = round_to<T>(v1);   // statistics of the values as stored
+            s0 += a; q0 = fmaf(a, a, q0); s1 += b; q1 = fmaf(b, b, q1);
+          }
+        } else if (MODE == MODE_DGRAD) {
+          if (p.res) { float ra, rb; load_pair(reinterpret_cast<const T*>(p.res) + o, ra, rb); v0 += ra; v1 += rb; }
+          store_pair(reinterpret_cast<T*>(p.out) + o, v0, v1);
+        } else {
+          store_pair(reinterpret_cast<float*>(p.out) + o, v0, v1);
+        }
+      }
+      continue;
+    }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const size_t ig = i0 + wave * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+      const size_t ig = irow + 8 * (r / 4) + (r % 4);
       float v0 = acc[0][r], v1 = acc[1][r];
       acc[0][r] = 0.f; acc[1][r] = 0.f;
       if (ig >= ni || jc >= nj) continue;
@@ -749,15 +897,22 @@ static void launch_tiny(int dt, hipStream_t st, GemmArgs& a, int ncols) {
   else hipLaunchKernelGGL((pw_gemm_tiny_k<bf16_t, MODE>), dim3(grid), dim3(256), 0, st, a);
 }
 
+template <typename T, int MODE, bool VEC>
+static void launch_t(hipStream_t st, const GemmArgs& a, bool small, unsigned grid) {
+  if (small) hipLaunchKernelGGL((pw_gemm_k<T, MODE, true, VEC>), dim3(grid), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC>), dim3(grid), dim3(256), 0, st, a);
+}
+
 template <int MODE>
 static void launch(int dt, hipStream_t st, const GemmArgs& a, bool small) {
   unsigned grid = (unsigned)((size_t)a.jtiles * a.nranges);
+  const bool vec = a.K % 8 == 0 && a.N % 8 == 0;   // whole vectors along both weight dimensions
   if (dt == 0) {
-    if (small) hipLaunchKernelGGL((pw_gemm_k<float, MODE, true>), dim3(grid), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((pw_gemm_rows_k<float, MODE>), dim3(grid), dim3(256), 0, st, a);
+    if (vec) launch_t<float, MODE, true>(st, a, small, grid);
+    else launch_t<float, MODE, false>(st, a, small, grid);
   } else {
-    if (small) hipLaunchKernelGGL((pw_gemm_k<bf16_t, MODE, true>), dim3(grid), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((pw_gemm_rows_k<bf16_t, MODE>), dim3(grid), dim3(256), 0, st, a);
+    if (vec) launch_t<bf16_t, MODE, true>(st, a, small, grid);
+    else launch_t<bf16_t, MODE, false>(st, a, small, grid);
   }
 }
 
