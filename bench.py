@@ -227,7 +227,7 @@ def main():
         if c == args.config or c not in WORKLOADS:
             continue
         r = run_workload(c, max(5, min(args.steps, 10)), 3, False, not args.no_ktrace, False, args.seed)
-        r["kernels"] = r["kernels"][:6]
+        r["kernels"] = r["kernels"][:12]
         also.append(r)
 
     cpu = None

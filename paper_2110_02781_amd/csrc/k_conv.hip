@@ -228,328 +228,403 @@ void conv_direct_wgrad(int dt, hipStream_t st, const void* dz, HView in, const C
 }
 
 // ================================================================ depthwise 3x3
-// A block owns a slab of CGB*8 channels and walks spatial output tiles (TH x TW).  For every
-// tile the input patch with its one-pixel halo is staged in LDS once, already passed through the
+// A block owns a slab of CGB*8 channels (128 bytes of every pixel) of one spatial tile.  The input
+// patch with its one-pixel halo is staged in LDS once as floats, already passed through the
 // producer's BatchNorm + activation and with zeros outside the image, so HBM sees every input
-// element once per tile and the nine taps are served from LDS.  Threads keep the slab's weights
-// in registers; per-channel BatchNorm sums (forward) and weight-gradient sums (wgrad) accumulate
-// over all tiles of the block and leave as one partial per block.
+// element once per tile.  A thread then owns 4 channels of a horizontal run of 4 pixels: per kernel
+// row it reads the 6 (stride 1) or 9 (stride 2) patch vectors under the run once and uses each for
+// up to three taps, which cuts the LDS traffic of a pixel-per-thread mapping to a quarter, and it
+// keeps the nine weight vectors in registers.  Tiles are numbered so that neighbours, which share
+// halo pixels, run on the same XCD and meet in its L2.
 struct DwPlan {
-  int TH, TW, PH, PW;       // output tile, staged patch (input resolution)
-  int CGB, nslab, PPB;      // column groups per slab, slabs, pixels per pass (blockDim = CGB*PPB)
+  int TH, TW, PH, PW;       // tile of the produced / walked tensor, staged patch
+  int CGB, nslab, PPB;      // column groups per slab, slabs, patch pixels staged per pass
+  int segw, nseg, spp;      // 4-pixel runs per tile row, per tile, and runs the block covers per pass
   int tiles_h, tiles_w, ntiles, nblocks;
-  size_t lds_bytes;
 };
+enum { kDwFillNV = 5 };     // passes the patch staging is unrolled for
 
-static DwPlan dw_plan(const ConvGeom& g, int es, int out_h, int out_w, int max_blocks) {
+static DwPlan dw_plan(int C, int es, bool half_rows, int out_h, int out_w, int max_blocks) {
   DwPlan d;
-  const int cgs = g.Cout / 8, cap = es == 2 ? 8 : 4;       // 128 bytes of channels per pixel
+  const int cgs = C / 8, cap = es == 2 ? 8 : 4;            // 128 bytes of channels per pixel
   d.nslab = (cgs + cap - 1) / cap;
   d.CGB = (cgs + d.nslab - 1) / d.nslab;
   d.PPB = 256 / d.CGB;
-  d.TH = g.stride == 1 ? 8 : 4;
-  d.TW = 8;
+  d.spp = 256 / (2 * d.CGB);
+  d.TH = half_rows ? 4 : 8;
+  d.TW = (es == 4 && !half_rows) ? 16 : 8;                 // float slabs are half as wide: longer tiles
   if (d.TH > out_h) d.TH = out_h;
   if (d.TW > out_w) d.TW = out_w;
+  d.segw = (d.TW + 3) / 4;
+  d.nseg = d.TH * d.segw;
   d.tiles_h = (out_h + d.TH - 1) / d.TH;
   d.tiles_w = (out_w + d.TW - 1) / d.TW;
-  d.ntiles = g.N * d.tiles_h * d.tiles_w;
-  d.nblocks = d.ntiles < max_blocks ? d.ntiles : max_blocks;
-  d.PH = d.PW = 0;
-  d.lds_bytes = 0;
+  d.ntiles = 0; d.nblocks = 0; d.PH = d.PW = 0;
+  (void)max_blocks;
   return d;
 }
 
-// Rows h0..h0+PH-1, cols w0..w0+PW-1 of image n (H x W x C), channel groups cg0..cg0+CGB-1, as
-// LDS array [PH][PW][CGB][8].  fetch() issues the global loads into registers, commit() applies the
-// view and writes LDS, so the loads of the next tile are in flight while the current one is used.
-template <typename T, bool VIEW, int NV>
-struct PatchLoader {
-  Raw<T> raw[NV];
+__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ float4 load4(const bf16_t* p) {
+  const uint2 u = *reinterpret_cast<const uint2*>(p);
+  return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u), __uint_as_float(u.y << 16),
+                     __uint_as_float(u.y & 0xffff0000u));
+}
+__device__ __forceinline__ void store4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ void store4(bf16_t* p, float4 v) {
+  uint2 u;
+  u.x = f32x2_to_bf16x2(v.x, v.y);
+  u.y = f32x2_to_bf16x2(v.z, v.w);
+  *reinterpret_cast<uint2*>(p) = u;
+}
+__device__ __forceinline__ float4 fma4(float4 a, float4 b, float4 c) {
+  return make_float4(fmaf(a.x, b.x, c.x), fmaf(a.y, b.y, c.y), fmaf(a.z, b.z, c.z), fmaf(a.w, b.w, c.w));
+}
+
+// Patch rows h0 .. h0+PH-1, cols w0 .. w0+PW-1 of image n (H x W x C), column groups cg0 .. cg0+CGB-1,
+// into LDS as float [PH][PW][CGB][8].  Thread = (pixel lane, column group); fetch() issues all global
+// loads, commit() applies the view and writes LDS, so a caller can keep the loads of the next tile
+// in flight while it works on the current one.
+template <typename T>
+struct DwPatch {
+  Raw<T> raw[kDwFillNV];
   unsigned ok;
-  __device__ __forceinline__ void fetch(const T* __restrict__ src, int n, int h0, int w0, int PH, int PW, int H, int W,
-                                        int C, int cg0, int CGB) {
+  __device__ __forceinline__ void fetch(const T* __restrict__ src, int n, int h0, int w0, const DwPlan& d, int H, int W,
+                                        int C, int cg0) {
     ok = 0;
-    const int total = PH * PW * CGB, cgs = C / 8;
-#pragma unroll
-    for (int q = 0; q < NV; ++q) {
-      const int v = threadIdx.x + q * blockDim.x;
-      if (v < total) {
-        const int cg = v % CGB, pix = v / CGB, pw = pix % PW, ph = pix / PW;
-        const int h = h0 + ph, w = w0 + pw, gcg = cg0 + cg;
-        if (h >= 0 && h < H && w >= 0 && w < W && gcg < cgs) {
-          raw_load(raw[q], src + (((size_t)n * H + h) * W + w) * C + gcg * 8);
-          ok |= 1u << q;
-        }
-      }
-    }
-  }
-  __device__ __forceinline__ void commit(float* lds, const View& vw, int PH, int PW, int cg0, int CGB) const {
-    const int total = PH * PW * CGB;
-#pragma unroll
-    for (int q = 0; q < NV; ++q) {
-      const int v = threadIdx.x + q * blockDim.x;
-      if (v < total) {
-        float val[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (ok & (1u << q)) {
-          raw_unpack(raw[q], val);
-          if (VIEW && vw.scale) {
-            const int c = (cg0 + v % CGB) * 8;
-            float sc[8], sh[8];
-            load8(vw.scale + c, sc);
-            load8(vw.shift + c, sh);
-            const float lo = act_lo(vw.act), hi = act_hi(vw.act);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) val[e] = round_to<T>(clamp_act(fmaf(val[e], sc[e], sh[e]), lo, hi));
-          }
-        }
-        store8(lds + (size_t)v * 8, val);
-      }
-    }
-  }
-};
-enum { kDwPatchNV = 5, kDwTileNV = 2 };
-
-// Forward: one block = one spatial tile x one channel slab.  Many small blocks per CU hide the
-// HBM latency; weights of the slab sit in LDS next to the patch.
-template <typename T>
-__global__ __launch_bounds__(256) void dw_fwd_k(View in, const T* __restrict__ w, ConvGeom g, DwPlan d, T* __restrict__ z) {
-  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  const int C = g.Cout, cgs = C / 8, s = g.stride;
-  const int PH = (d.TH - 1) * s + 3, PW = (d.TW - 1) * s + 3;
-  float* patch = reinterpret_cast<float*>(smem_raw);      // float in LDS: converted once, no unpacking per tap
-  float* wl = patch + (size_t)PH * PW * d.CGB * 8;        // [9][CGB][8]
-  const int cg = threadIdx.x % d.CGB, pl = threadIdx.x / d.CGB;
-  const int cg0 = blockIdx.y * d.CGB, gcg = cg0 + cg;
-  const int tile = blockIdx.x;
-  const int tw = tile % d.tiles_w, th = (tile / d.tiles_w) % d.tiles_h, n = tile / (d.tiles_w * d.tiles_h);
-  const int ho0 = th * d.TH, wo0 = tw * d.TW;
-  for (int i = threadIdx.x; i < 9 * d.CGB * 8; i += blockDim.x) {
-    const int e = i % 8, c8 = (i / 8) % d.CGB, t = i / (8 * d.CGB);
-    const int c = (cg0 + c8) * 8 + e;
-    wl[i] = c < C ? to_f32(w[(size_t)c * 9 + t]) : 0.f;
-  }
-  {
-    // thread = (pixel lane pl, column group cg); pixel index advances by PPB per pass
-    const int npix = PH * PW, h0 = ho0 * s - 1, w0 = wo0 * s - 1;
-    const int dph = d.PPB / PW, dpw = d.PPB % PW;
-    int ph = pl / PW, pw = pl % PW;
-    for (int pix = pl; pix < npix; pix += d.PPB) {
-      const int h = h0 + ph, ww = w0 + pw;
-      float val[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (h >= 0 && h < g.Hin && ww >= 0 && ww < g.Win && gcg < cgs)
-        view_load8<T>(in, (((size_t)n * g.Hin + h) * g.Win + ww) * C + gcg * 8, gcg * 8, val);
-      store8(patch + ((size_t)pix * d.CGB + cg) * 8, val);
-      ph += dph; pw += dpw;
-      if (pw >= PW) { pw -= PW; ++ph; }
-    }
-  }
-  __syncthreads();
-  if (gcg >= cgs) return;
-  const int dhl = d.PPB / d.TW, dwl = d.PPB % d.TW;
-  int hl = pl / d.TW, wl_ = pl % d.TW;
-  for (int p = pl; p < d.TH * d.TW; p += d.PPB, hl += dhl, wl_ += dwl) {
-    if (wl_ >= d.TW) { wl_ -= d.TW; ++hl; }
-    const int ho = ho0 + hl, wo = wo0 + wl_;
-    if (ho >= g.Hout || wo >= g.Wout) continue;
-    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-    for (int i = 0; i < 3; ++i)
-#pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        float v[8], wr[8];
-        load8(patch + ((size_t)((hl * s + i) * PW + wl_ * s + j) * d.CGB + cg) * 8, v);
-        load8(wl + ((i * 3 + j) * d.CGB + cg) * 8, wr);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] = fmaf(v[e], wr[e], acc[e]);
-      }
-    store8(z + (((size_t)n * g.Hout + ho) * g.Wout + wo) * C + gcg * 8, acc);
-  }
-}
-
-void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z) {
-  const int es = dt == 0 ? 4 : 2;
-  DwPlan d = dw_plan(g, es, g.Hout, g.Wout, 1 << 30);
-  View v{in.z, in.scale, in.shift, in.act};
-  size_t total = (size_t)g.N * g.Hout * g.Wout;
-  KScope ks(st, "dw_fwd", ((double)g.N * g.Hin * g.Win * g.Cout + (double)total * g.Cout) * es, 18.0 * total * g.Cout,
-            (long)total, g.Cout, g.stride);
-  int PH = (d.TH - 1) * g.stride + 3, PW = (d.TW - 1) * g.stride + 3;
-  size_t lds = (size_t)PH * PW * d.CGB * 8 * 4 + (size_t)9 * d.CGB * 8 * 4;
-  FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_fwd_k<T>, dim3(d.ntiles, d.nslab), dim3(d.CGB * d.PPB), lds, st,
-                                      v, (const T*)w, g, d, (T*)z));
-}
-
-// dIn tile (input resolution) from a staged dz patch: dIn[h][w] = sum_{i,j} dz[(h+1-i)/s][(w+1-j)/s] * w[i][j]
-template <typename T>
-__global__ __launch_bounds__(256) void dw_dgrad_k(const T* __restrict__ dz, const T* __restrict__ w, ConvGeom g, DwPlan d, T* __restrict__ dIn) {
-  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  const int C = g.Cout, cgs = C / 8, s = g.stride;
-  float* patch = reinterpret_cast<float*>(smem_raw);
-  float* wl = patch + (size_t)d.PH * d.PW * d.CGB * 8;    // [9][CGB][8]
-  const int cg = threadIdx.x % d.CGB, pl = threadIdx.x / d.CGB;
-  const int cg0 = blockIdx.y * d.CGB, gcg = cg0 + cg;
-  const int tile = blockIdx.x;
-  const int tw = tile % d.tiles_w, th = (tile / d.tiles_w) % d.tiles_h, n = tile / (d.tiles_w * d.tiles_h);
-  const int h0 = th * d.TH, w0 = tw * d.TW;                 // input-resolution tile origin (even)
-  // dz rows that can reach input rows h0 .. h0+TH-1: ho = (h+1-i)/s, i in 0..2
-  const int ho_lo = s == 1 ? h0 - 1 : h0 / 2, wo_lo = s == 1 ? w0 - 1 : w0 / 2;
-  for (int i = threadIdx.x; i < 9 * d.CGB * 8; i += blockDim.x) {
-    const int e = i % 8, c8 = (i / 8) % d.CGB, t = i / (8 * d.CGB);
-    const int c = (cg0 + c8) * 8 + e;
-    wl[i] = c < C ? to_f32(w[(size_t)c * 9 + t]) : 0.f;
-  }
-  {
-    const int npix = d.PH * d.PW;
-    const int dph = d.PPB / d.PW, dpw = d.PPB % d.PW;
+    const int cg = threadIdx.x % d.CGB, pl = threadIdx.x / d.CGB, gcg = cg0 + cg;
+    if (pl >= d.PPB || gcg >= C / 8) return;
+    const int npix = d.PH * d.PW, dph = d.PPB / d.PW, dpw = d.PPB % d.PW;
     int ph = pl / d.PW, pw = pl % d.PW;
-    for (int pix = pl; pix < npix; pix += d.PPB) {
-      const int ho = ho_lo + ph, wo = wo_lo + pw;
-      float val[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (ho >= 0 && ho < g.Hout && wo >= 0 && wo < g.Wout && gcg < cgs)
-        load8(dz + (((size_t)n * g.Hout + ho) * g.Wout + wo) * C + gcg * 8, val);
-      store8(patch + ((size_t)pix * d.CGB + cg) * 8, val);
+#pragma unroll
+    for (int q = 0; q < kDwFillNV; ++q) {
+      const int h = h0 + ph, w = w0 + pw;
+      if (pl + q * d.PPB < npix && h >= 0 && h < H && w >= 0 && w < W) {
+        raw_load(raw[q], src + (((size_t)n * H + h) * W + w) * C + gcg * 8);
+        ok |= 1u << q;
+      }
       ph += dph; pw += dpw;
       if (pw >= d.PW) { pw -= d.PW; ++ph; }
     }
   }
+  __device__ __forceinline__ void commit(float* patch, const View& vw, const DwPlan& d, int cg0) const {
+    const int cg = threadIdx.x % d.CGB, pl = threadIdx.x / d.CGB;
+    if (pl >= d.PPB) return;
+    const int npix = d.PH * d.PW;
+    float sc[8], sh[8];
+    const bool view = vw.scale != nullptr && ok != 0;
+    if (view) {
+      load8(vw.scale + (cg0 + cg) * 8, sc);
+      load8(vw.shift + (cg0 + cg) * 8, sh);
+    }
+    const float lo = act_lo(vw.act), hi = act_hi(vw.act);
+#pragma unroll
+    for (int q = 0; q < kDwFillNV; ++q) {
+      const int pix = pl + q * d.PPB;
+      if (pix >= npix) break;
+      float val[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (ok & (1u << q)) {
+        raw_unpack(raw[q], val);
+        if (view) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) val[e] = round_to<T>(clamp_act(fmaf(val[e], sc[e], sh[e]), lo, hi));
+        }
+      }
+      store8(patch + ((size_t)pix * d.CGB + cg) * 8, val);
+    }
+  }
+};
+
+// the slab's weights as float [9][CGB][8]
+template <typename T>
+__device__ __forceinline__ void dw_stage_weights(float* wl, const T* __restrict__ w, int C, int cg0, int CGB) {
+  for (int i = threadIdx.x; i < 9 * CGB * 8; i += blockDim.x) {
+    const int e = i % 8, c8 = (i / 8) % CGB, t = i / (8 * CGB);
+    const int c = (cg0 + c8) * 8 + e;
+    wl[i] = c < C ? to_f32(w[(size_t)c * 9 + t]) : 0.f;
+  }
+}
+
+__device__ __forceinline__ int dw_logical_block() {   // neighbours in the numbering share an XCD (see k_gemm)
+  const int nb = gridDim.x, b = blockIdx.x;
+  const int x = b & 7, idx = b >> 3, q = nb >> 3, rem = nb & 7;
+  return x * q + (x < rem ? x : rem) + idx;
+}
+
+// out[ho][wo] = sum_{ky,kx} src[ho*S-1+ky][wo*S-1+kx] * w[ky][kx]   (FLIP: w[2-ky][2-kx], which for
+// S = 1 is the data gradient with src = dz)
+template <typename T, int S, bool FLIP>
+__global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ w, DwPlan d, int Hin, int Win, int Hout,
+                                                 int Wout, int C, T* __restrict__ out) {
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  float* patch = reinterpret_cast<float*>(smem_raw);
+  float* wl = patch + (size_t)d.PH * d.PW * d.CGB * 8;
+  const int lb = dw_logical_block();
+  const int tile = lb % d.ntiles, slab = lb / d.ntiles;
+  const int tw = tile % d.tiles_w, th = (tile / d.tiles_w) % d.tiles_h, n = tile / (d.tiles_w * d.tiles_h);
+  const int ho0 = th * d.TH, wo0 = tw * d.TW, cg0 = slab * d.CGB;
+  DwPatch<T> lp;
+  lp.fetch(reinterpret_cast<const T*>(in.z), n, ho0 * S - 1, wo0 * S - 1, d, Hin, Win, C, cg0);
+  dw_stage_weights(wl, w, C, cg0, d.CGB);
+  lp.commit(patch, in, d, cg0);
   __syncthreads();
-  if (gcg >= cgs) return;
-  const int dhl = d.PPB / d.TW, dwl = d.PPB % d.TW;
-  int hl = pl / d.TW, wl_ = pl % d.TW;
-  for (int p = pl; p < d.TH * d.TW; p += d.PPB, hl += dhl, wl_ += dwl) {
-    if (wl_ >= d.TW) { wl_ -= d.TW; ++hl; }
-    const int h = h0 + hl, ww = w0 + wl_;
-    if (h >= g.Hin || ww >= g.Win) continue;
-    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  const int QB = 2 * d.CGB, cq = threadIdx.x % QB, seg0 = threadIdx.x / QB;
+  const int c4 = cq * 4, gc = cg0 * 8 + c4;
+  if (seg0 >= d.spp || gc >= C) return;
+  float4 wr[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) wr[t] = ld4(wl + (size_t)(FLIP ? 8 - t : t) * d.CGB * 8 + c4);
+  const int vs = d.CGB * 8;                       // floats per patch pixel
+  for (int sg = seg0; sg < d.nseg; sg += d.spp) {
+    const int hl = sg / d.segw, wl0 = (sg % d.segw) * 4;
+    const int ho = ho0 + hl;
+    if (ho >= Hout) continue;
+    float4 acc[4];
+#pragma unroll
+    for (int o = 0; o < 4; ++o) acc[o] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int ky = 0; ky < 3; ++ky) {
+      const float* row = patch + (size_t)((hl * S + ky) * d.PW + wl0 * S) * vs + c4;
+      float4 iv[3 * S + 3];
+#pragma unroll
+      for (int x = 0; x < 3 * S + 3; ++x) iv[x] = ld4(row + (size_t)x * vs);
+#pragma unroll
+      for (int kx = 0; kx < 3; ++kx)
+#pragma unroll
+        for (int o = 0; o < 4; ++o) acc[o] = fma4(iv[o * S + kx], wr[ky * 3 + kx], acc[o]);
+    }
+    T* dst = out + (((size_t)n * Hout + ho) * Wout + wo0 + wl0) * C + gc;
+#pragma unroll
+    for (int o = 0; o < 4; ++o)
+      if (wo0 + wl0 + o < Wout) store4(dst + (size_t)o * C, acc[o]);
+  }
+}
+
+static size_t dw_lds_bytes(const DwPlan& d) { return ((size_t)d.PH * d.PW + 9) * d.CGB * 8 * 4; }
+
+static void dw_check_plan(const DwPlan& d) {
+  // staging is unrolled for kDwFillNV passes
+  if (d.PH * d.PW > kDwFillNV * d.PPB) abort();
+}
+
+void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z) {
+  const int es = dt == 0 ? 4 : 2, s = g.stride;
+  DwPlan d = dw_plan(g.Cout, es, s == 2, g.Hout, g.Wout, 0);
+  d.PH = (d.TH - 1) * s + 3;
+  d.PW = (d.segw * 4 - 1) * s + 3;               // runs are whole: the patch covers the rounded-up tile width
+  d.ntiles = g.N * d.tiles_h * d.tiles_w;
+  dw_check_plan(d);
+  View v{in.z, in.scale, in.shift, in.act};
+  size_t total = (size_t)g.N * g.Hout * g.Wout;
+  KScope ks(st, "dw_fwd", ((double)g.N * g.Hin * g.Win * g.Cout + (double)total * g.Cout) * es, 18.0 * total * g.Cout,
+            (long)total, g.Cout, g.stride);
+  const unsigned grid = (unsigned)d.ntiles * d.nslab;
+  if (s == 1) {
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 1, false>), dim3(grid), dim3(256), dw_lds_bytes(d), st, v, (const T*)w, d,
+                                        g.Hin, g.Win, g.Hout, g.Wout, g.Cout, (T*)z));
+  } else {
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 2, false>), dim3(grid), dim3(256), dw_lds_bytes(d), st, v, (const T*)w, d,
+                                        g.Hin, g.Win, g.Hout, g.Wout, g.Cout, (T*)z));
+  }
+}
+
+// Stride-2 data gradient over 8 x 8 input tiles: dIn[h][w] = sum over taps (i, j) with h+1-i and w+1-j
+// even of dz[(h+1-i)/2][(w+1-j)/2] * w[i][j].  A run of 4 input pixels starting at an even column
+// touches three dz columns per dz row.
+template <typename T>
+__global__ __launch_bounds__(256) void dw_dgrad_s2_k(const T* __restrict__ dz, const T* __restrict__ w, DwPlan d, int Hin,
+                                                     int Win, int Hout, int Wout, int C, T* __restrict__ dIn) {
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  float* patch = reinterpret_cast<float*>(smem_raw);
+  float* wl = patch + (size_t)d.PH * d.PW * d.CGB * 8;
+  const int lb = dw_logical_block();
+  const int tile = lb % d.ntiles, slab = lb / d.ntiles;
+  const int tw = tile % d.tiles_w, th = (tile / d.tiles_w) % d.tiles_h, n = tile / (d.tiles_w * d.tiles_h);
+  const int h0 = th * d.TH, w0 = tw * d.TW, cg0 = slab * d.CGB;       // tile origin, even
+  const int ho_lo = h0 / 2, wo_lo = w0 / 2;
+  DwPatch<T> lp;
+  View none{nullptr, nullptr, nullptr, 0};
+  lp.fetch(dz, n, ho_lo, wo_lo, d, Hout, Wout, C, cg0);
+  dw_stage_weights(wl, w, C, cg0, d.CGB);
+  lp.commit(patch, none, d, cg0);
+  __syncthreads();
+  const int QB = 2 * d.CGB, cq = threadIdx.x % QB, seg0 = threadIdx.x / QB;
+  const int c4 = cq * 4, gc = cg0 * 8 + c4;
+  if (seg0 >= d.spp || gc >= C) return;
+  float4 wr[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) wr[t] = ld4(wl + (size_t)t * d.CGB * 8 + c4);
+  const int vs = d.CGB * 8;
+  for (int sg = seg0; sg < d.nseg; sg += d.spp) {
+    const int hl = sg / d.segw, wl0 = (sg % d.segw) * 4;
+    const int h = h0 + hl;
+    if (h >= Hin) continue;
+    float4 acc[4];
+#pragma unroll
+    for (int o = 0; o < 4; ++o) acc[o] = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
     for (int i = 0; i < 3; ++i) {
       const int hn = h + 1 - i;
-      if (hn < 0 || (s == 2 && (hn & 1))) continue;
-      const int ho = hn / s;
-      if (ho >= g.Hout) continue;
-#pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        const int wn = ww + 1 - j;
-        if (wn < 0 || (s == 2 && (wn & 1))) continue;
-        const int wo = wn / s;
-        if (wo >= g.Wout) continue;
-        float v[8], wr[8];
-        load8(patch + ((size_t)((ho - ho_lo) * d.PW + (wo - wo_lo)) * d.CGB + cg) * 8, v);
-        load8(wl + ((i * 3 + j) * d.CGB + cg) * 8, wr);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] = fmaf(v[e], wr[e], acc[e]);
-      }
+      if (hn & 1) continue;                        // also skips hn = -1
+      const float* row = patch + (size_t)((hn / 2 - ho_lo) * d.PW + wl0 / 2) * vs + c4;
+      const float4 d0 = ld4(row), d1 = ld4(row + vs), d2 = ld4(row + 2 * (size_t)vs);
+      // pixel 0, 2 (even columns): tap j = 1; pixel 1, 3 (odd): taps j = 0 (next dz column) and j = 2
+      acc[0] = fma4(d0, wr[i * 3 + 1], acc[0]);
+      acc[1] = fma4(d1, wr[i * 3 + 0], acc[1]);
+      acc[1] = fma4(d0, wr[i * 3 + 2], acc[1]);
+      acc[2] = fma4(d1, wr[i * 3 + 1], acc[2]);
+      acc[3] = fma4(d2, wr[i * 3 + 0], acc[3]);
+      acc[3] = fma4(d1, wr[i * 3 + 2], acc[3]);
     }
-    store8(dIn + (((size_t)n * g.Hin + h) * g.Win + ww) * C + gcg * 8, acc);
+    T* dst = dIn + (((size_t)n * Hin + h) * Win + w0 + wl0) * C + gc;
+#pragma unroll
+    for (int o = 0; o < 4; ++o)
+      if (w0 + wl0 + o < Win) store4(dst + (size_t)o * C, acc[o]);
   }
 }
 
 void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvGeom& g, void* dIn) {
   const int es = dt == 0 ? 4 : 2;
-  // tiles are in input resolution; for stride 2 an 8x8 input tile needs a 5x5 dz patch
-  ConvGeom gi = g;
-  gi.stride = 1;
-  DwPlan d = dw_plan(gi, es, g.Hin, g.Win, 1 << 30);
-  if (g.stride == 1) { d.PH = d.TH + 2; d.PW = d.TW + 2; }
-  else { d.PH = d.TH / 2 + 2; d.PW = d.TW / 2 + 2; }
   size_t total = (size_t)g.N * g.Hin * g.Win;
   KScope ks(st, "dw_dgrad", ((double)total * g.Cout + (double)g.N * g.Hout * g.Wout * g.Cout) * es, 18.0 * g.N * g.Hout * g.Wout * g.Cout,
             (long)total, g.Cout, g.stride);
-  size_t lds = (size_t)d.PH * d.PW * d.CGB * 8 * 4 + (size_t)9 * d.CGB * 8 * 4;
-  FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_dgrad_k<T>, dim3(d.ntiles, d.nslab), dim3(d.CGB * d.PPB), lds, st, (const T*)dz,
-                                      (const T*)w, g, d, (T*)dIn));
+  // tiles are in input resolution
+  DwPlan d = dw_plan(g.Cout, es, false, g.Hin, g.Win, 0);
+  d.ntiles = g.N * d.tiles_h * d.tiles_w;
+  const unsigned grid = (unsigned)d.ntiles * d.nslab;
+  if (g.stride == 1) {
+    // the forward kernel on dz with the weights flipped
+    d.PH = d.TH + 2;
+    d.PW = d.segw * 4 + 2;
+    dw_check_plan(d);
+    View v{dz, nullptr, nullptr, 0};
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 1, true>), dim3(grid), dim3(256), dw_lds_bytes(d), st, v, (const T*)w, d,
+                                        g.Hout, g.Wout, g.Hin, g.Win, g.Cout, (T*)dIn));
+  } else {
+    d.PH = d.TH / 2 + 2;
+    d.PW = d.segw * 2 + 2;
+    dw_check_plan(d);
+    FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_dgrad_s2_k<T>, dim3(grid), dim3(256), dw_lds_bytes(d), st, (const T*)dz, (const T*)w,
+                                        d, g.Hin, g.Win, g.Hout, g.Wout, g.Cout, (T*)dIn));
+  }
 }
 
-// dW[c][tap] += sum over pixels dz[p][c] * in[p*s + tap][c]: input patch and dz tile in LDS, thread =
-// (column group, tap, pixel part); the block's sums over all its tiles leave as one partial ws[block][9][C]
-template <typename T>
-__global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View in, ConvGeom g, DwPlan d, int parts, float* __restrict__ ws) {
+// dW[c][ky][kx] += sum over output pixels dz[p][c] * in[p*S-1+(ky,kx)][c].  Blocks are persistent over
+// tiles; a thread reads the dz of its run straight from global memory (nobody else needs it), keeps
+// 9 x 4 sums over all its runs, and the block leaves one partial ws[block][9][C].
+template <typename T, int S>
+__global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View in, DwPlan d, int Hin, int Win, int Hout,
+                                                  int Wout, int C, float* __restrict__ ws) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  const int C = g.Cout, cgs = C / 8, s = g.stride;
-  const int PH = (d.TH - 1) * s + 3, PW = (d.TW - 1) * s + 3;
-  const size_t psz = (size_t)PH * PW * d.CGB * 8, tsz = (size_t)d.TH * d.TW * d.CGB * 8;
-  const int cg0 = blockIdx.y * d.CGB;
-  // accumulate role: cg fastest, then tap, then part
-  const int acg = threadIdx.x % d.CGB, atap = (threadIdx.x / d.CGB) % 9, apart = threadIdx.x / (d.CGB * 9);
-  const bool worker = apart < parts && cg0 + acg < cgs;
-  const int ti = atap / 3, tj = atap % 3;
-  View none{nullptr, nullptr, nullptr, 0};
-  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  PatchLoader<T, true, kDwPatchNV> lp;
-  PatchLoader<T, false, kDwTileNV> lt;
+  float* patch = reinterpret_cast<float*>(smem_raw);
+  const int lb = dw_logical_block();
+  const int b = lb % d.nblocks, slab = lb / d.nblocks, cg0 = slab * d.CGB;
+  const int QB = 2 * d.CGB, cq = threadIdx.x % QB, seg0 = threadIdx.x / QB;
+  const int c4 = cq * 4, gc = cg0 * 8 + c4;
+  const bool worker = seg0 < d.spp && gc < C;
+  const int vs = d.CGB * 8;
   const T* src = reinterpret_cast<const T*>(in.z);
-  int it = 0;
-  if ((int)blockIdx.x < d.ntiles) {
-    const int tile = blockIdx.x;
-    const int tw = tile % d.tiles_w, th = (tile / d.tiles_w) % d.tiles_h, n = tile / (d.tiles_w * d.tiles_h);
-    lp.fetch(src, n, th * d.TH * s - 1, tw * d.TW * s - 1, PH, PW, g.Hin, g.Win, C, cg0, d.CGB);
-    lt.fetch(dz, n, th * d.TH, tw * d.TW, d.TH, d.TW, g.Hout, g.Wout, C, cg0, d.CGB);
+  float4 acc[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) acc[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+  DwPatch<T> lp;
+  if (b < d.ntiles) {
+    const int tw = b % d.tiles_w, th = (b / d.tiles_w) % d.tiles_h, n = b / (d.tiles_w * d.tiles_h);
+    lp.fetch(src, n, th * d.TH * S - 1, tw * d.TW * S - 1, d, Hin, Win, C, cg0);
   }
-  for (int tile = blockIdx.x; tile < d.ntiles; tile += gridDim.x, ++it) {
-    float* patch = reinterpret_cast<float*>(smem_raw);
-    float* dzt = patch + psz;
+  for (int tile = b; tile < d.ntiles; tile += d.nblocks) {
+    const int tw = tile % d.tiles_w, th = (tile / d.tiles_w) % d.tiles_h, n = tile / (d.tiles_w * d.tiles_h);
+    const int ho0 = th * d.TH, wo0 = tw * d.TW;
     __syncthreads();                                       // the previous tile has been consumed
-    lp.commit(patch, in, PH, PW, cg0, d.CGB);
-    lt.commit(dzt, none, d.TH, d.TW, cg0, d.CGB);          // zero outside the image
+    lp.commit(patch, in, d, cg0);
     __syncthreads();
-    const int nt = tile + gridDim.x;
+    const int nt = tile + d.nblocks;
     if (nt < d.ntiles) {
       const int tw2 = nt % d.tiles_w, th2 = (nt / d.tiles_w) % d.tiles_h, n2 = nt / (d.tiles_w * d.tiles_h);
-      lp.fetch(src, n2, th2 * d.TH * s - 1, tw2 * d.TW * s - 1, PH, PW, g.Hin, g.Win, C, cg0, d.CGB);
-      lt.fetch(dz, n2, th2 * d.TH, tw2 * d.TW, d.TH, d.TW, g.Hout, g.Wout, C, cg0, d.CGB);
+      lp.fetch(src, n2, th2 * d.TH * S - 1, tw2 * d.TW * S - 1, d, Hin, Win, C, cg0);
     }
     if (!worker) continue;
-    for (int p = apart; p < d.TH * d.TW; p += parts) {
-      const int hl = p / d.TW, wl = p % d.TW;
-      float dv[8], v[8];
-      load8(dzt + ((size_t)p * d.CGB + acg) * 8, dv);
-      load8(patch + ((size_t)((hl * s + ti) * PW + wl * s + tj) * d.CGB + acg) * 8, v);
+    for (int sg = seg0; sg < d.nseg; sg += d.spp) {
+      const int hl = sg / d.segw, wl0 = (sg % d.segw) * 4;
+      const int ho = ho0 + hl;
+      if (ho >= Hout) continue;
+      float4 dv[4];
+      const T* dp = dz + (((size_t)n * Hout + ho) * Wout + wo0 + wl0) * C + gc;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] = fmaf(dv[e], v[e], acc[e]);
+      for (int o = 0; o < 4; ++o)
+        dv[o] = wo0 + wl0 + o < Wout ? load4(dp + (size_t)o * C) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int ky = 0; ky < 3; ++ky) {
+        const float* row = patch + (size_t)((hl * S + ky) * d.PW + wl0 * S) * vs + c4;
+        float4 iv[3 * S + 3];
+#pragma unroll
+        for (int x = 0; x < 3 * S + 3; ++x) iv[x] = ld4(row + (size_t)x * vs);
+#pragma unroll
+        for (int kx = 0; kx < 3; ++kx)
+#pragma unroll
+          for (int o = 0; o < 4; ++o) acc[ky * 3 + kx] = fma4(dv[o], iv[o * S + kx], acc[ky * 3 + kx]);
+      }
     }
   }
+  // sum the runs of every channel quad in a fixed order: red[spp][9][QB] float4
   __syncthreads();
-  float* red = reinterpret_cast<float*>(smem_raw);          // [parts][9][CGB][8]
-  if (apart < parts) {
+  float4* red = reinterpret_cast<float4*>(smem_raw);
+  if (seg0 < d.spp) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) red[((apart * 9 + atap) * d.CGB + acg) * 8 + e] = worker ? acc[e] : 0.f;
+    for (int t = 0; t < 9; ++t) red[(seg0 * 9 + t) * QB + cq] = worker ? acc[t] : make_float4(0.f, 0.f, 0.f, 0.f);
   }
   __syncthreads();
-  if (apart == 0 && cg0 + acg < cgs) {
-    float o[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float t = 0.f;
-      for (int r = 0; r < parts; ++r) t += red[((r * 9 + atap) * d.CGB + acg) * 8 + e];
-      o[e] = t;
+  for (int i = threadIdx.x; i < 9 * QB; i += blockDim.x) {
+    const int q = i % QB, t = i / QB;
+    if (cg0 * 8 + q * 4 >= C) continue;
+    float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int r = 0; r < d.spp; ++r) {
+      const float4 v = red[(r * 9 + t) * QB + q];
+      tot.x += v.x; tot.y += v.y; tot.z += v.z; tot.w += v.w;
     }
-    store8(ws + ((size_t)blockIdx.x * 9 + atap) * C + (cg0 + acg) * 8, o);
+    store4(ws + ((size_t)b * 9 + t) * C + cg0 * 8 + q * 4, tot);
   }
 }
 
-static DwPlan dw_wgrad_plan(const ConvGeom& g, int es, int* parts, size_t* lds) {
-  DwPlan d = dw_plan(g, es, g.Hout, g.Wout, kMaxPartials);
-  *parts = 256 / (d.CGB * 9);
-  int PH = (d.TH - 1) * g.stride + 3, PW = (d.TW - 1) * g.stride + 3;
-  size_t a = ((size_t)PH * PW + (size_t)d.TH * d.TW) * d.CGB * 8 * 4;   // float tiles
-  size_t b = (size_t)*parts * 9 * d.CGB * 8 * 4;
+static DwPlan dw_wgrad_plan(const ConvGeom& g, int es, size_t* lds) {
+  const int s = g.stride;
+  DwPlan d = dw_plan(g.Cout, es, s == 2, g.Hout, g.Wout, 0);
+  d.PH = (d.TH - 1) * s + 3;
+  d.PW = (d.segw * 4 - 1) * s + 3;
+  d.ntiles = g.N * d.tiles_h * d.tiles_w;
+  const int cap = 2048 / d.nslab > 1 ? 2048 / d.nslab : 1;   // about 2048 persistent blocks over all slabs
+  d.nblocks = d.ntiles < cap ? d.ntiles : cap;
+  size_t a = (size_t)d.PH * d.PW * d.CGB * 8 * 4;
+  size_t b = (size_t)d.spp * 9 * 2 * d.CGB * 16;
   *lds = a > b ? a : b;
   return d;
 }
 
-size_t dw_wgrad_ws(const ConvGeom& g) { return (size_t)kMaxPartials * 9 * g.Cout; }
-
+size_t dw_wgrad_ws(const ConvGeom& g) {
+  size_t lds;
+  DwPlan d = dw_wgrad_plan(g, 4, &lds);          // the float plan has at least as many slabs, the bound holds for both
+  DwPlan e = dw_wgrad_plan(g, 2, &lds);
+  return (size_t)(d.nblocks > e.nblocks ? d.nblocks : e.nblocks) * 9 * g.Cout;
+}
 
 void dw_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, float* ws, float* g_w) {
   const int es = dt == 0 ? 4 : 2;
-  int parts; size_t lds;
-  DwPlan d = dw_wgrad_plan(g, es, &parts, &lds);
+  size_t lds;
+  DwPlan d = dw_wgrad_plan(g, es, &lds);
+  dw_check_plan(d);
   View v{in.z, in.scale, in.shift, in.act};
   {
     KScope ks(st, "dw_wgrad", ((double)g.N * g.Hin * g.Win * g.Cout + (double)g.N * g.Hout * g.Wout * g.Cout) * es + (double)d.nblocks * 9 * g.Cout * 4,
               18.0 * g.N * g.Hout * g.Wout * g.Cout, (long)g.N * g.Hout * g.Wout, g.Cout, g.stride);
-    FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_wgrad_k<T>, dim3(d.nblocks, d.nslab), dim3(256), lds, st, (const T*)dz, v, g, d, parts, ws));
+    const unsigned grid = (unsigned)d.nblocks * d.nslab;
+    if (g.stride == 1) {
+      FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_wgrad_k<T, 1>), dim3(grid), dim3(256), lds, st, (const T*)dz, v, d, g.Hin, g.Win,
+                                          g.Hout, g.Wout, g.Cout, ws));
+    } else {
+      FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_wgrad_k<T, 2>), dim3(grid), dim3(256), lds, st, (const T*)dz, v, d, g.Hin, g.Win,
+                                          g.Hout, g.Wout, g.Cout, ws));
+    }
   }
   reduce_partials(st, ws, d.nblocks, (size_t)9 * g.Cout, g.Cout, 1, 9, g_w);
 }
