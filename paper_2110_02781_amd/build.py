@@ -10,7 +10,9 @@ LIB = os.path.join(HERE, "libftp_hip.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
 COMMON = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
-          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          # MFMA accumulators in ordinary VGPRs: the epilogues read them without accvgpr moves
+          "-mllvm", "-amdgpu-mfma-vgpr-form"]
 SOURCES = [
     ("k_elem.hip", ["-x", "hip"]),
     ("k_conv.hip", ["-x", "hip"]),

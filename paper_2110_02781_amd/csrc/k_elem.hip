@@ -61,11 +61,20 @@ __global__ void bn_stats_k(const T* __restrict__ z, size_t M, int C, int W, int 
   for (int e = 0; e < 16; ++e) acc[e] = 0.f;
   if (cg < C / 8) {
     size_t m0 = (size_t)blockIdx.x * rpb, m1 = m0 + rpb < M ? m0 + rpb : M;
-    for (size_t m = m0 + ty; m < m1; m += R) {
-      float v[8];
-      load8(z + m * C + cg * 8, v);
+    // four rows per round: the loads are issued together, the sums keep a fixed order
+    for (size_t m = m0 + ty; m < m1; m += 4 * (size_t)R) {
+      Raw<T> rv[4];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) { acc[e] += v[e]; acc[8 + e] = fmaf(v[e], v[e], acc[8 + e]); }
+      for (int u = 0; u < 4; ++u)
+        if (m + (size_t)u * R < m1) raw_load(rv[u], z + (m + (size_t)u * R) * C + cg * 8);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (m + (size_t)u * R >= m1) break;
+        float v[8];
+        raw_unpack(rv[u], v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { acc[e] += v[e]; acc[8 + e] = fmaf(v[e], v[e], acc[8 + e]); }
+      }
     }
   }
   reduce_over_rows<16>(acc, tx, ty, W, R, smem);
@@ -159,9 +168,25 @@ void bn_finalize(hipStream_t st, const float* partial, int P, size_t M, int C, c
 }
 
 // ------------------------------------------------------------- bn backward
-template <typename T>
+// dY = dA where the activation (compile-time ACT) passes, else 0
+template <int ACT>
+__device__ __forceinline__ float act_gate(float d, float z, float sc, float sh) {
+  if (ACT == ACT_NONE) return d;
+  const float y = fmaf(z, sc, sh);
+  if (ACT == ACT_RELU) return y > 0.f ? d : 0.f;
+  return (y > 0.f && y < 6.f) ? d : 0.f;
+}
+
+#define FTP_DISPATCH_ACT(dt, act, ...)                                        \
+  do {                                                                        \
+    if ((act) == ACT_NONE) { constexpr int ACT = ACT_NONE; FTP_DISPATCH(dt, __VA_ARGS__); }        \
+    else if ((act) == ACT_RELU) { constexpr int ACT = ACT_RELU; FTP_DISPATCH(dt, __VA_ARGS__); }   \
+    else { constexpr int ACT = ACT_RELU6; FTP_DISPATCH(dt, __VA_ARGS__); }    \
+  } while (0)
+
+template <typename T, int ACT>
 __global__ void bn_bwd_reduce_k(const T* __restrict__ dA, const T* __restrict__ z, size_t M, int C,
-                                const float* __restrict__ scale, const float* __restrict__ shift, int act,
+                                const float* __restrict__ scale, const float* __restrict__ shift,
                                 int W, int R, size_t rpb, float* __restrict__ partial) {
   extern __shared__ float smem[];
   int tx = threadIdx.x % W, ty = threadIdx.x / W;
@@ -173,18 +198,28 @@ __global__ void bn_bwd_reduce_k(const T* __restrict__ dA, const T* __restrict__ 
     float sc[8], sh[8];
     load8(scale + cg * 8, sc);
     load8(shift + cg * 8, sh);
-    const float lo = act_lo(act), hi = act_hi(act);
     size_t m0 = (size_t)blockIdx.x * rpb, m1 = m0 + rpb < M ? m0 + rpb : M;
-    for (size_t m = m0 + ty; m < m1; m += R) {
-      float d[8], v[8];
-      load8(dA + m * C + cg * 8, d);
-      load8(z + m * C + cg * 8, v);
+    // two rows per round: the loads are issued together, the sums keep a fixed order
+    for (size_t m = m0 + ty; m < m1; m += 2 * (size_t)R) {
+      Raw<T> rd[2], rv[2];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float y = fmaf(v[e], sc[e], sh[e]);
-        float dy = (y > lo && y < hi) ? d[e] : 0.f;
-        acc[e] += dy;
-        acc[8 + e] = fmaf(dy, v[e], acc[8 + e]);
+      for (int u = 0; u < 2; ++u)
+        if (m + (size_t)u * R < m1) {
+          raw_load(rd[u], dA + (m + (size_t)u * R) * C + cg * 8);
+          raw_load(rv[u], z + (m + (size_t)u * R) * C + cg * 8);
+        }
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        if (m + (size_t)u * R >= m1) break;
+        float d[8], v[8];
+        raw_unpack(rd[u], d);
+        raw_unpack(rv[u], v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float dy = act_gate<ACT>(d[e], v[e], sc[e], sh[e]);
+          acc[e] += dy;
+          acc[8 + e] = fmaf(dy, v[e], acc[8 + e]);
+        }
       }
     }
   }
@@ -203,8 +238,8 @@ void bn_bwd_reduce(int dt, hipStream_t st, const void* dA, const void* z, size_t
     KScope ks(st, "bn_bwd_reduce", 2.0 * M * C * (dt == 0 ? 4.0 : 2.0), 6.0 * M * C);
     dim3 grid(t.P, t.nslab), block(t.W * t.R);
     size_t sm = (size_t)16 * t.R * t.W * sizeof(float);
-    FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_bwd_reduce_k<T>, grid, block, sm, st, (const T*)dA, (const T*)z, M,
-                                        C, scale, shift, act, t.W, t.R, t.rows_per_block, partial));
+    FTP_DISPATCH_ACT(dt, act, hipLaunchKernelGGL((bn_bwd_reduce_k<T, ACT>), grid, block, sm, st, (const T*)dA, (const T*)z, M,
+                                                 C, scale, shift, t.W, t.R, t.rows_per_block, partial));
   }
   *P_out = t.P;
 }
@@ -240,26 +275,40 @@ void bn_bwd_finalize(hipStream_t st, const float* partial, int P, size_t M, int 
                      invstd, g_gamma, g_beta, coef);
 }
 
-template <typename T>
-__global__ void bn_bwd_apply_k(const T* __restrict__ dA, const T* __restrict__ z, size_t nvec, int CG,
-                               const float* __restrict__ scale, const float* __restrict__ shift, int act,
-                               const float* __restrict__ coef, T* __restrict__ dz) {
-  int C = CG * 8;
-  const float lo = act_lo(act), hi = act_hi(act);
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (size_t)gridDim.x * blockDim.x) {
-    int c = (int)(i % CG) * 8;
-    float d[8], v[8], sc[8], sh[8], k1[8], k2[8], k3[8], o[8];
-    load8(dA + i * 8, d);
-    load8(z + i * 8, v);
-    load8(scale + c, sc); load8(shift + c, sh);
-    load8(coef + c, k1); load8(coef + C + c, k2); load8(coef + 2 * C + c, k3);
+// thread = (column group, row lane): coefficients stay in registers, rows advance by R
+template <typename T, int ACT>
+__global__ void bn_bwd_apply_k(const T* __restrict__ dA, const T* __restrict__ z, size_t M, int C,
+                               const float* __restrict__ scale, const float* __restrict__ shift,
+                               const float* __restrict__ coef, int W, int R, size_t rpb, T* __restrict__ dz) {
+  const int tx = threadIdx.x % W, ty = threadIdx.x / W;
+  const int cg = blockIdx.y * W + tx;
+  if (cg >= C / 8) return;
+  const int c = cg * 8;
+  float sc[8], sh[8], k1[8], k2[8], k3[8];
+  if (ACT != ACT_NONE) { load8(scale + c, sc); load8(shift + c, sh); }
+  load8(coef + c, k1); load8(coef + C + c, k2); load8(coef + 2 * C + c, k3);
+  const size_t m0 = (size_t)blockIdx.x * rpb, m1 = m0 + rpb < M ? m0 + rpb : M;
+  for (size_t m = m0 + ty; m < m1; m += 2 * (size_t)R) {
+    Raw<T> rd[2], rv[2];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float y = fmaf(v[e], sc[e], sh[e]);
-      float dy = (y > lo && y < hi) ? d[e] : 0.f;
-      o[e] = fmaf(k1[e], dy, fmaf(k2[e], v[e], k3[e]));
+    for (int u = 0; u < 2; ++u)
+      if (m + (size_t)u * R < m1) {
+        raw_load(rd[u], dA + (m + (size_t)u * R) * C + c);
+        raw_load(rv[u], z + (m + (size_t)u * R) * C + c);
+      }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      if (m + (size_t)u * R >= m1) break;
+      float d[8], v[8], o[8];
+      raw_unpack(rd[u], d);
+      raw_unpack(rv[u], v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float dy = act_gate<ACT>(d[e], v[e], sc[e], sh[e]);
+        o[e] = fmaf(k1[e], dy, fmaf(k2[e], v[e], k3[e]));
+      }
+      store8(dz + (m + (size_t)u * R) * C + c, o);
     }
-    store8(dz + i * 8, o);
   }
 }
 
@@ -272,10 +321,11 @@ static inline int flat_grid(size_t n, int block) {
 
 void bn_bwd_apply(int dt, hipStream_t st, const void* dA, const void* z, size_t M, int C,
                   const float* scale, const float* shift, int act, const float* coef, void* dz) {
-  size_t nvec = M * (size_t)(C / 8);
   KScope ks(st, "bn_bwd_apply", 3.0 * M * C * (dt == 0 ? 4.0 : 2.0), 6.0 * M * C);
-  FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_bwd_apply_k<T>, dim3(flat_grid(nvec, 256)), dim3(256), 0, st,
-                                      (const T*)dA, (const T*)z, nvec, C / 8, scale, shift, act, coef, (T*)dz));
+  RowTile t = make_rowtile(M, C, 1 << 14);       // no partials here: many short blocks
+  dim3 grid(t.P, t.nslab), block(t.W * t.R);
+  FTP_DISPATCH_ACT(dt, act, hipLaunchKernelGGL((bn_bwd_apply_k<T, ACT>), grid, block, 0, st, (const T*)dA, (const T*)z, M, C,
+                                               scale, shift, coef, t.W, t.R, t.rows_per_block, (T*)dz));
 }
 
 // BatchNorm backward for short tensors in ONE launch: a block owns 8 channels over all M rows, so it

@@ -594,6 +594,14 @@ __device__ __forceinline__ void store_pair(float* p, float a, float b) { *reinte
 __device__ __forceinline__ void store_pair(bf16_t* p, float a, float b) {
   *reinterpret_cast<uint32_t*>(p) = f32x2_to_bf16x2(a, b);
 }
+__device__ __forceinline__ void store_pair_rounded(float* p, float a, float b, float& ra, float& rb) {
+  *reinterpret_cast<float2*>(p) = make_float2(a, b); ra = a; rb = b;
+}
+__device__ __forceinline__ void store_pair_rounded(bf16_t* p, float a, float b, float& ra, float& rb) {
+  const uint32_t v = f32x2_to_bf16x2(a, b);
+  *reinterpret_cast<uint32_t*>(p) = v;
+  ra = __uint_as_float(v << 16); rb = __uint_as_float(v & 0xffff0000u);
+}
 __device__ __forceinline__ void load_pair(const float* p, float& a, float& b) { float2 v = *reinterpret_cast<const float2*>(p); a = v.x; b = v.y; }
 __device__ __forceinline__ void load_pair(const bf16_t* p, float& a, float& b) {
   uint32_t v = *reinterpret_cast<const uint32_t*>(p);
@@ -689,11 +697,9 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
         acc[0][r] = 0.f; acc[1][r] = 0.f;
         if (MODE == MODE_FWD) {
           v0 += b0; v1 += b1;
-          store_pair(reinterpret_cast<T*>(p.out) + o, v0, v1);
-          if (p.stats) {
-            float a = round_to<T>(v0), b = round_to<T>(v1);   // statistics of the values as stored
-            s0 += a; q0 = fmaf(a, a, q0); s1 += b; q1 = fmaf(b, b, q1);
-          }
+          float a, b;                                         // the values as stored: the statistics use those
+          store_pair_rounded(reinterpret_cast<T*>(p.out) + o, v0, v1, a, b);
+          if (p.stats) { s0 += a; q0 = fmaf(a, a, q0); s1 += b; q1 = fmaf(b, b, q1); }
         } else if (MODE == MODE_DGRAD) {
           if (p.res) { float ra, rb; load_pair(reinterpret_cast<const T*>(p.res) + o, ra, rb); v0 += ra; v1 += rb; }
           store_pair(reinterpret_cast<T*>(p.out) + o, v0, v1);
