@@ -97,7 +97,9 @@ void bn_stats(int dt, hipStream_t st, const void* z, size_t M, int C, float* par
   *P_out = t.P;
 }
 
-// Sum partial[p][q][c] over p in float64; 16 channels per block, 16 lanes per channel.
+// Sum partial[p][q][c] over p in float64; kFinCh channels per block, kFinLanes lanes per channel
+// (few channels per block: a layer has only C / kFinCh blocks and the partial walk is pure latency).
+enum { kFinCh = 8, kFinLanes = 256 / kFinCh };
 template <int Q>
 __device__ __forceinline__ void sum_partials(const float* __restrict__ partial, int P, int C, int c,
                                              int lane, double (&out)[Q], double* smem) {
@@ -107,29 +109,29 @@ __device__ __forceinline__ void sum_partials(const float* __restrict__ partial, 
   if (c < C) {
     // four partials per round: the loads are independent, the sums keep a fixed order
     int p = lane;
-    for (; p + 48 < P; p += 64) {
+    for (; p + 3 * kFinLanes < P; p += 4 * kFinLanes) {
       float v[4][Q];
 #pragma unroll
       for (int u = 0; u < 4; ++u)
 #pragma unroll
-        for (int q = 0; q < Q; ++q) v[u][q] = partial[((size_t)(p + 16 * u) * Q + q) * C + c];
+        for (int q = 0; q < Q; ++q) v[u][q] = partial[((size_t)(p + kFinLanes * u) * Q + q) * C + c];
 #pragma unroll
       for (int u = 0; u < 4; ++u)
 #pragma unroll
         for (int q = 0; q < Q; ++q) s[q] += (double)v[u][q];
     }
-    for (; p < P; p += 16)
+    for (; p < P; p += kFinLanes)
 #pragma unroll
       for (int q = 0; q < Q; ++q) s[q] += (double)partial[((size_t)p * Q + q) * C + c];
   }
-  int cl = threadIdx.x % 16;
+  int cl = threadIdx.x % kFinCh;
 #pragma unroll
-  for (int q = 0; q < Q; ++q) smem[(q * 16 + lane) * 16 + cl] = s[q];
+  for (int q = 0; q < Q; ++q) smem[(q * kFinLanes + lane) * kFinCh + cl] = s[q];
   __syncthreads();
 #pragma unroll
   for (int q = 0; q < Q; ++q) {
     double t = 0.0;
-    for (int l = 0; l < 16; ++l) t += smem[(q * 16 + l) * 16 + cl];
+    for (int l = 0; l < kFinLanes; ++l) t += smem[(q * kFinLanes + l) * kFinCh + cl];
     out[q] = t;
   }
 }
@@ -138,9 +140,9 @@ __global__ void bn_finalize_k(const float* __restrict__ partial, int P, size_t M
                               const float* __restrict__ gamma, const float* __restrict__ beta,
                               float* mean, float* invstd, float* scale, float* shift, float* run_mean,
                               float* run_var, float eps, float momentum) {
-  __shared__ double smem[2 * 16 * 16];
-  int cl = threadIdx.x % 16, lane = threadIdx.x / 16;
-  int c = blockIdx.x * 16 + cl;
+  __shared__ double smem[2 * kFinLanes * kFinCh];
+  int cl = threadIdx.x % kFinCh, lane = threadIdx.x / kFinCh;
+  int c = blockIdx.x * kFinCh + cl;
   double s[2];
   sum_partials<2>(partial, P, C, c, lane, s, smem);
   if (lane == 0 && c < C) {
@@ -163,7 +165,7 @@ void bn_finalize(hipStream_t st, const float* partial, int P, size_t M, int C, c
                  const float* beta, float* mean, float* invstd, float* scale, float* shift,
                  float* run_mean, float* run_var, float eps, float momentum) {
   KScope ks(st, "bn_finalize", (double)P * 2 * C * 4 + 8.0 * C * 4, 0);
-  hipLaunchKernelGGL(bn_finalize_k, dim3((C + 15) / 16), dim3(256), 0, st, partial, P, M, C, gamma, beta,
+  hipLaunchKernelGGL(bn_finalize_k, dim3((C + kFinCh - 1) / kFinCh), dim3(256), 0, st, partial, P, M, C, gamma, beta,
                      mean, invstd, scale, shift, run_mean, run_var, eps, momentum);
 }
 
@@ -199,17 +201,17 @@ __global__ void bn_bwd_reduce_k(const T* __restrict__ dA, const T* __restrict__ 
     load8(scale + cg * 8, sc);
     load8(shift + cg * 8, sh);
     size_t m0 = (size_t)blockIdx.x * rpb, m1 = m0 + rpb < M ? m0 + rpb : M;
-    // two rows per round: the loads are issued together, the sums keep a fixed order
-    for (size_t m = m0 + ty; m < m1; m += 2 * (size_t)R) {
-      Raw<T> rd[2], rv[2];
+    // four rows per round: the loads are issued together, the sums keep a fixed order
+    for (size_t m = m0 + ty; m < m1; m += 4 * (size_t)R) {
+      Raw<T> rd[4], rv[4];
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
+      for (int u = 0; u < 4; ++u)
         if (m + (size_t)u * R < m1) {
           raw_load(rd[u], dA + (m + (size_t)u * R) * C + cg * 8);
           raw_load(rv[u], z + (m + (size_t)u * R) * C + cg * 8);
         }
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
+      for (int u = 0; u < 4; ++u) {
         if (m + (size_t)u * R >= m1) break;
         float d[8], v[8];
         raw_unpack(rd[u], d);
@@ -248,9 +250,9 @@ __global__ void bn_bwd_finalize_k(const float* __restrict__ partial, int P, size
                                   const float* __restrict__ gamma, const float* __restrict__ mean,
                                   const float* __restrict__ invstd, float* g_gamma, float* g_beta,
                                   float* coef) {
-  __shared__ double smem[2 * 16 * 16];
-  int cl = threadIdx.x % 16, lane = threadIdx.x / 16;
-  int c = blockIdx.x * 16 + cl;
+  __shared__ double smem[2 * kFinLanes * kFinCh];
+  int cl = threadIdx.x % kFinCh, lane = threadIdx.x / kFinCh;
+  int c = blockIdx.x * kFinCh + cl;
   double s[2];
   sum_partials<2>(partial, P, C, c, lane, s, smem);
   if (lane == 0 && c < C) {
@@ -271,7 +273,7 @@ __global__ void bn_bwd_finalize_k(const float* __restrict__ partial, int P, size
 void bn_bwd_finalize(hipStream_t st, const float* partial, int P, size_t M, int C, const float* gamma,
                      const float* mean, const float* invstd, float* g_gamma, float* g_beta, float* coef) {
   KScope ks(st, "bn_bwd_finalize", (double)P * 2 * C * 4 + 10.0 * C * 4, 0);
-  hipLaunchKernelGGL(bn_bwd_finalize_k, dim3((C + 15) / 16), dim3(256), 0, st, partial, P, M, C, gamma, mean,
+  hipLaunchKernelGGL(bn_bwd_finalize_k, dim3((C + kFinCh - 1) / kFinCh), dim3(256), 0, st, partial, P, M, C, gamma, mean,
                      invstd, g_gamma, g_beta, coef);
 }
 

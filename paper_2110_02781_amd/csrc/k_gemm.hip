@@ -687,26 +687,30 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
 
     // tile finished: register r of this lane is row 8*(r/4) + 4*h + r%4, columns jc (acc[0]) and jc+1 (acc[1])
     const size_t irow = i0 + wave * 32 + 4 * h;
-    if (VEC && i0 + TI <= ni && j0 + BJ <= nj) {
-      // interior tile of an even-width problem: no bounds tests, one address computation per lane
-      const size_t obase = (MODE == MODE_WGRAD ? (size_t)split * p.N + irow : irow) * ldo + jc;
+    if (VEC && i0 + TI <= ni) {
+      // all rows inside and an even width: a lane's column pair is wholly in or out, no other bounds
+      // tests, one address computation per lane
+      if (jc < nj) {
+        const size_t obase = (MODE == MODE_WGRAD ? (size_t)split * p.N + irow : irow) * ldo + jc;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const size_t o = obase + (size_t)(8 * (r / 4) + (r % 4)) * ldo;
-        float v0 = acc[0][r], v1 = acc[1][r];
-        acc[0][r] = 0.f; acc[1][r] = 0.f;
-        if (MODE == MODE_FWD) {
-          v0 += b0; v1 += b1;
-          float a, b;                                         // the values as stored: the statistics use those
-          store_pair_rounded(reinterpret_cast<T*>(p.out) + o, v0, v1, a, b);
-          if (p.stats) { s0 += a; q0 = fmaf(a, a, q0); s1 += b; q1 = fmaf(b, b, q1); }
-        } else if (MODE == MODE_DGRAD) {
-          if (p.res) { float ra, rb; load_pair(reinterpret_cast<const T*>(p.res) + o, ra, rb); v0 += ra; v1 += rb; }
-          store_pair(reinterpret_cast<T*>(p.out) + o, v0, v1);
-        } else {
-          store_pair(reinterpret_cast<float*>(p.out) + o, v0, v1);
+        for (int r = 0; r < 16; ++r) {
+          const size_t o = obase + (size_t)(8 * (r / 4) + (r % 4)) * ldo;
+          float v0 = acc[0][r], v1 = acc[1][r];
+          if (MODE == MODE_FWD) {
+            v0 += b0; v1 += b1;
+            float a, b;                                         // the values as stored: the statistics use those
+            store_pair_rounded(reinterpret_cast<T*>(p.out) + o, v0, v1, a, b);
+            if (p.stats) { s0 += a; q0 = fmaf(a, a, q0); s1 += b; q1 = fmaf(b, b, q1); }
+          } else if (MODE == MODE_DGRAD) {
+            if (p.res) { float ra, rb; load_pair(reinterpret_cast<const T*>(p.res) + o, ra, rb); v0 += ra; v1 += rb; }
+            store_pair(reinterpret_cast<T*>(p.out) + o, v0, v1);
+          } else {
+            store_pair(reinterpret_cast<float*>(p.out) + o, v0, v1);
+          }
         }
       }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { acc[0][r] = 0.f; acc[1][r] = 0.f; }
       continue;
     }
 #pragma unroll
