@@ -199,8 +199,8 @@ def run_workload(config, steps, warmup, use_graph, ktrace, calibrate, seed):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, choices=sorted(WORKLOADS))
     ap.add_argument("--also", type=int, nargs="*", default=None,
                     help="further configs reported under 'also' (default: 5 when --config is 2)")

@@ -429,6 +429,101 @@ void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, 
   }
 }
 
+// Depthwise convolution, BatchNorm statistics and their finalisation in ONE launch for short tensors
+// (a few hundred KB, where the three separate kernels are all launch latency): a block owns 8 channels
+// over every output pixel, so the per-channel sums never leave the block.
+template <typename T>
+__global__ __launch_bounds__(1024) void dw_fwd_bn_small_k(View in, const T* __restrict__ w, ConvGeom g, size_t M,
+                                                          const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                          float* mean, float* invstd, float* scale, float* shift,
+                                                          float* run_mean, float* run_var, float eps, float momentum,
+                                                          T* __restrict__ z) {
+  __shared__ float wl[9][8];
+  __shared__ float red[16][16];
+  const int C = g.Cout, c0 = blockIdx.x * 8, tid = threadIdx.x, nt = blockDim.x, s = g.stride;
+  if (tid < 72) wl[tid / 8][tid % 8] = to_f32(w[(size_t)(c0 + tid % 8) * 9 + tid / 8]);
+  float sc[8], sh[8];
+  const bool view = in.scale != nullptr;
+  if (view) { load8(in.scale + c0, sc); load8(in.shift + c0, sh); }
+  const float lo = act_lo(in.act), hi = act_hi(in.act);
+  const T* src = reinterpret_cast<const T*>(in.z);
+  float acc[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  __syncthreads();
+  for (size_t m = tid; m < M; m += nt) {
+    const int wo = (int)(m % g.Wout), ho = (int)((m / g.Wout) % g.Hout), n = (int)(m / ((size_t)g.Wout * g.Hout));
+    float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      const int h = ho * s - 1 + i;
+      if (h < 0 || h >= g.Hin) continue;
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const int ww = wo * s - 1 + j;
+        if (ww < 0 || ww >= g.Win) continue;
+        float v[8];
+        load8(src + (((size_t)n * g.Hin + h) * g.Win + ww) * C + c0, v);
+        if (view) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = round_to<T>(clamp_act(fmaf(v[e], sc[e], sh[e]), lo, hi));
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = fmaf(v[e], wl[i * 3 + j][e], o[e]);
+      }
+    }
+    store8(z + m * C + c0, o);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float sv = round_to<T>(o[e]);       // statistics of the values as stored
+      acc[e] += sv;
+      acc[8 + e] = fmaf(sv, sv, acc[8 + e]);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = wave_sum(acc[e]);
+  const int wave = tid >> 6, nw = nt >> 6;
+  if ((tid & 63) == 0) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) red[wave][e] = acc[e];
+  }
+  __syncthreads();
+  if (tid < 8) {
+    const int c = c0 + tid;
+    double s0 = 0.0, s1 = 0.0;
+    for (int q = 0; q < nw; ++q) { s0 += red[q][tid]; s1 += red[q][8 + tid]; }
+    const double Md = (double)M, mu = s0 / Md;
+    double var = s1 / Md - mu * mu;
+    if (var < 0.0) var = 0.0;
+    const double is = 1.0 / sqrt(var + (double)eps);
+    const float scv = (float)((double)gamma[c] * is);
+    mean[c] = (float)mu;
+    invstd[c] = (float)is;
+    scale[c] = scv;
+    shift[c] = (float)((double)beta[c] - mu * (double)scv);
+    const double unb = M > 1 ? var * (Md / (Md - 1.0)) : var;
+    run_mean[c] = (float)((1.0 - momentum) * run_mean[c] + momentum * mu);
+    run_var[c] = (float)((1.0 - momentum) * run_var[c] + momentum * unb);
+  }
+}
+
+int dw_fwd_bn_small_ok(const ConvGeom& g) {
+  return (size_t)g.N * g.Hout * g.Wout <= 2048 && g.Cout >= 32 && g.Cout % 8 == 0;
+}
+
+void dw_fwd_bn_small(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, const float* gamma,
+                     const float* beta, float* mean, float* invstd, float* scale, float* shift, float* run_mean,
+                     float* run_var, float eps, float momentum, void* z) {
+  const size_t M = (size_t)g.N * g.Hout * g.Wout;
+  const int es = dt == 0 ? 4 : 2;
+  View v{in.z, in.scale, in.shift, in.act};
+  KScope ks(st, "dw_fwd_bn_small", ((double)g.N * g.Hin * g.Win * g.Cout + (double)M * g.Cout) * es, 21.0 * M * g.Cout,
+            (long)M, g.Cout, g.stride);
+  const int nt = M > 512 ? 1024 : (M > 256 ? 512 : 256);
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_fwd_bn_small_k<T>, dim3(g.Cout / 8), dim3(nt), 0, st, v, (const T*)w, g, M, gamma, beta,
+                                      mean, invstd, scale, shift, run_mean, run_var, eps, momentum, (T*)z));
+}
+
 // Stride-2 data gradient over 8 x 8 input tiles: dIn[h][w] = sum over taps (i, j) with h+1-i and w+1-j
 // even of dz[(h+1-i)/2][(w+1-j)/2] * w[i][j].  A run of 4 input pixels starting at an even column
 // touches three dz columns per dz row.

@@ -96,6 +96,11 @@ void reduce_partials(hipStream_t st, const float* ws, int P, size_t QC, int C, s
 
 // ---- depthwise 3x3 ----------------------------------------------------------------
 void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z);
+// convolution + BatchNorm statistics + finalize in one launch for short tensors (dw_fwd_bn_small_ok)
+int dw_fwd_bn_small_ok(const ConvGeom& g);
+void dw_fwd_bn_small(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, const float* gamma,
+                     const float* beta, float* mean, float* invstd, float* scale, float* shift, float* run_mean,
+                     float* run_var, float eps, float momentum, void* z);
 void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvGeom& g, void* dIn);
 size_t dw_wgrad_ws(const ConvGeom& g);
 void dw_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, float* ws, float* g_w);

@@ -511,6 +511,11 @@ static void sub_forward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, HVi
   int P = 0;
   float* stt = sl.stats + p.st_off[k];
   int C = g.Cout;
+  if (sb.type == SUB_DW && dw_fwd_bn_small_ok(g)) {
+    dw_fwd_bn_small(s->dt, st, in, w, g, W.w32 + p.p_off + sb.gamma_off, W.w32 + p.p_off + sb.beta_off, stt, stt + C, stt + 2 * C,
+                    stt + 3 * C, s->run_mean + p.bn_off + sb.bn_off, s->run_var + p.bn_off + sb.bn_off, kBnEps, kBnMomentum, z);
+    return;
+  }
   if (sb.type == SUB_PW) {
     pw_fwd(s->dt, st, in, w, nullptr, M, g.Cin, g.Cout, z, s->bn_part, &P);   // statistics in the epilogue
   } else {
