@@ -241,8 +241,14 @@ struct DwPlan {
   int CGB, nslab, PPB;      // column groups per slab, slabs, patch pixels staged per pass
   int segw, nseg, spp;      // 4-pixel runs per tile row, per tile, and runs the block covers per pass
   int tiles_h, tiles_w, ntiles, nblocks;
+  unsigned m_cgb, m_qb, m_pw, m_segw;   // reciprocals for dw_div (divisors < 64, dividends < 1024)
 };
-enum { kDwFillNV = 5 };     // passes the patch staging is unrolled for
+enum { kDwFillNV = 6 };
+
+// x / d for x < 1024, d < 64 with m = 65536 / d + 1: two full-rate instructions instead of the
+// ~25-instruction integer division sequence (thread-index decoding was a third of the kernel's VALU work)
+static unsigned dw_magic(int d) { return 65536u / (unsigned)d + 1u; }
+__device__ __forceinline__ int dw_div(int x, unsigned m) { return (int)(__umul24((unsigned)x, m) >> 16); }     // passes the patch staging is unrolled for
 
 static DwPlan dw_plan(int C, int es, bool half_rows, int out_h, int out_w, int max_blocks) {
   DwPlan d;
@@ -252,7 +258,7 @@ static DwPlan dw_plan(int C, int es, bool half_rows, int out_h, int out_w, int m
   d.PPB = 256 / d.CGB;
   d.spp = 256 / (2 * d.CGB);
   d.TH = half_rows ? 4 : 8;
-  d.TW = (es == 4 && !half_rows) ? 16 : 8;                 // float slabs are half as wide: longer tiles
+  d.TW = half_rows ? 8 : 16;     // measured: 8x16 tiles beat 8x8 by 10-25 % (less halo, fewer blocks), 4x8 is best for stride 2
   if (d.TH > out_h) d.TH = out_h;
   if (d.TW > out_w) d.TW = out_w;
   d.segw = (d.TW + 3) / 4;
@@ -260,6 +266,7 @@ static DwPlan dw_plan(int C, int es, bool half_rows, int out_h, int out_w, int m
   d.tiles_h = (out_h + d.TH - 1) / d.TH;
   d.tiles_w = (out_w + d.TW - 1) / d.TW;
   d.ntiles = 0; d.nblocks = 0; d.PH = d.PW = 0;
+  d.m_cgb = dw_magic(d.CGB); d.m_qb = dw_magic(2 * d.CGB); d.m_segw = dw_magic(d.segw); d.m_pw = 0;
   (void)max_blocks;
   return d;
 }
@@ -290,18 +297,20 @@ template <typename T>
 struct DwPatch {
   Raw<T> raw[kDwFillNV];
   unsigned ok;
+  // image n is at most 2^31 elements: offsets inside it are 32-bit, products of 24-bit factors
   __device__ __forceinline__ void fetch(const T* __restrict__ src, int n, int h0, int w0, const DwPlan& d, int H, int W,
                                         int C, int cg0) {
     ok = 0;
-    const int cg = threadIdx.x % d.CGB, pl = threadIdx.x / d.CGB, gcg = cg0 + cg;
+    const int pl = dw_div(threadIdx.x, d.m_cgb), cg = threadIdx.x - pl * d.CGB, gcg = cg0 + cg;
     if (pl >= d.PPB || gcg >= C / 8) return;
-    const int npix = d.PH * d.PW, dph = d.PPB / d.PW, dpw = d.PPB % d.PW;
-    int ph = pl / d.PW, pw = pl % d.PW;
+    const T* img = src + (size_t)n * H * W * C + gcg * 8;
+    const int npix = d.PH * d.PW, dph = dw_div(d.PPB, d.m_pw), dpw = d.PPB - dph * d.PW;
+    int ph = dw_div(pl, d.m_pw), pw = pl - ph * d.PW;
 #pragma unroll
     for (int q = 0; q < kDwFillNV; ++q) {
       const int h = h0 + ph, w = w0 + pw;
       if (pl + q * d.PPB < npix && h >= 0 && h < H && w >= 0 && w < W) {
-        raw_load(raw[q], src + (((size_t)n * H + h) * W + w) * C + gcg * 8);
+        raw_load(raw[q], img + __umul24(__umul24(h, W) + w, C));
         ok |= 1u << q;
       }
       ph += dph; pw += dpw;
@@ -309,7 +318,7 @@ struct DwPatch {
     }
   }
   __device__ __forceinline__ void commit(float* patch, const View& vw, const DwPlan& d, int cg0) const {
-    const int cg = threadIdx.x % d.CGB, pl = threadIdx.x / d.CGB;
+    const int pl = dw_div(threadIdx.x, d.m_cgb), cg = threadIdx.x - pl * d.CGB;
     if (pl >= d.PPB) return;
     const int npix = d.PH * d.PW;
     float sc[8], sh[8];
@@ -319,10 +328,11 @@ struct DwPatch {
       load8(vw.shift + (cg0 + cg) * 8, sh);
     }
     const float lo = act_lo(vw.act), hi = act_hi(vw.act);
+    float* dst = patch + (pl * d.CGB + cg) * 8;
+    const int step = d.PPB * d.CGB * 8;
 #pragma unroll
     for (int q = 0; q < kDwFillNV; ++q) {
-      const int pix = pl + q * d.PPB;
-      if (pix >= npix) break;
+      if (pl + q * d.PPB >= npix) break;
       float val[8] = {0, 0, 0, 0, 0, 0, 0, 0};
       if (ok & (1u << q)) {
         raw_unpack(raw[q], val);
@@ -331,7 +341,7 @@ struct DwPatch {
           for (int e = 0; e < 8; ++e) val[e] = round_to<T>(clamp_act(fmaf(val[e], sc[e], sh[e]), lo, hi));
         }
       }
-      store8(patch + ((size_t)pix * d.CGB + cg) * 8, val);
+      store8(dst + q * step, val);
     }
   }
 };
@@ -369,7 +379,7 @@ __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ 
   dw_stage_weights(wl, w, C, cg0, d.CGB);
   lp.commit(patch, in, d, cg0);
   __syncthreads();
-  const int QB = 2 * d.CGB, cq = threadIdx.x % QB, seg0 = threadIdx.x / QB;
+  const int QB = 2 * d.CGB, seg0 = dw_div(threadIdx.x, d.m_qb), cq = threadIdx.x - seg0 * QB;
   const int c4 = cq * 4, gc = cg0 * 8 + c4;
   if (seg0 >= d.spp || gc >= C) return;
   float4 wr[9];
@@ -377,7 +387,7 @@ __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ 
   for (int t = 0; t < 9; ++t) wr[t] = ld4(wl + (size_t)(FLIP ? 8 - t : t) * d.CGB * 8 + c4);
   const int vs = d.CGB * 8;                       // floats per patch pixel
   for (int sg = seg0; sg < d.nseg; sg += d.spp) {
-    const int hl = sg / d.segw, wl0 = (sg % d.segw) * 4;
+    const int hl = dw_div(sg, d.m_segw), wl0 = (sg - hl * d.segw) * 4;
     const int ho = ho0 + hl;
     if (ho >= Hout) continue;
     float4 acc[4];
@@ -403,9 +413,10 @@ __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ 
 
 static size_t dw_lds_bytes(const DwPlan& d) { return ((size_t)d.PH * d.PW + 9) * d.CGB * 8 * 4; }
 
-static void dw_check_plan(const DwPlan& d) {
-  // staging is unrolled for kDwFillNV passes
-  if (d.PH * d.PW > kDwFillNV * d.PPB) abort();
+static void dw_check_plan(DwPlan& d) {
+  // staging is unrolled for kDwFillNV passes; dw_div needs small divisors
+  if (d.PH * d.PW > kDwFillNV * d.PPB || d.PW > 63 || d.CGB > 16 || d.segw > 32) abort();
+  d.m_pw = dw_magic(d.PW);
 }
 
 void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z) {
@@ -544,7 +555,7 @@ __global__ __launch_bounds__(256) void dw_dgrad_s2_k(const T* __restrict__ dz, c
   dw_stage_weights(wl, w, C, cg0, d.CGB);
   lp.commit(patch, none, d, cg0);
   __syncthreads();
-  const int QB = 2 * d.CGB, cq = threadIdx.x % QB, seg0 = threadIdx.x / QB;
+  const int QB = 2 * d.CGB, seg0 = dw_div(threadIdx.x, d.m_qb), cq = threadIdx.x - seg0 * QB;
   const int c4 = cq * 4, gc = cg0 * 8 + c4;
   if (seg0 >= d.spp || gc >= C) return;
   float4 wr[9];
@@ -552,7 +563,7 @@ __global__ __launch_bounds__(256) void dw_dgrad_s2_k(const T* __restrict__ dz, c
   for (int t = 0; t < 9; ++t) wr[t] = ld4(wl + (size_t)t * d.CGB * 8 + c4);
   const int vs = d.CGB * 8;
   for (int sg = seg0; sg < d.nseg; sg += d.spp) {
-    const int hl = sg / d.segw, wl0 = (sg % d.segw) * 4;
+    const int hl = dw_div(sg, d.m_segw), wl0 = (sg - hl * d.segw) * 4;
     const int h = h0 + hl;
     if (h >= Hin) continue;
     float4 acc[4];
@@ -615,7 +626,7 @@ __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View
   float* patch = reinterpret_cast<float*>(smem_raw);
   const int lb = dw_logical_block();
   const int b = lb % d.nblocks, slab = lb / d.nblocks, cg0 = slab * d.CGB;
-  const int QB = 2 * d.CGB, cq = threadIdx.x % QB, seg0 = threadIdx.x / QB;
+  const int QB = 2 * d.CGB, seg0 = dw_div(threadIdx.x, d.m_qb), cq = threadIdx.x - seg0 * QB;
   const int c4 = cq * 4, gc = cg0 * 8 + c4;
   const bool worker = seg0 < d.spp && gc < C;
   const int vs = d.CGB * 8;
@@ -641,7 +652,7 @@ __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View
     }
     if (!worker) continue;
     for (int sg = seg0; sg < d.nseg; sg += d.spp) {
-      const int hl = sg / d.segw, wl0 = (sg % d.segw) * 4;
+      const int hl = dw_div(sg, d.m_segw), wl0 = (sg - hl * d.segw) * 4;
       const int ho = ho0 + hl;
       if (ho >= Hout) continue;
       float4 dv[4];
