@@ -25,6 +25,7 @@ RowTile make_rowtile(size_t M, int C, int max_partials) {
   size_t want = (M + max_partials - 1) / max_partials;        // rows per block so that P <= max
   size_t rpb = ((want + t.R - 1) / t.R) * t.R;
   size_t min_rpb = (size_t)t.R * 4;                            // at least 4 iterations per block
+  if (min_rpb < (size_t)kBnMinRows) min_rpb = ((kBnMinRows + t.R - 1) / t.R) * t.R;
   if (rpb < min_rpb) rpb = min_rpb;
   t.rows_per_block = rpb;
   t.P = (int)((M + rpb - 1) / rpb);
@@ -32,20 +33,21 @@ RowTile make_rowtile(size_t M, int C, int max_partials) {
   return t;
 }
 
-// Sum v[0..NV) over the threads of a block that share tx (same columns); the
-// result is valid in the threads with ty == 0.  smem needs NV*R*W floats.
-template <int NV>
-__device__ __forceinline__ void reduce_over_rows(float (&v)[NV], int tx, int ty, int W, int R, float* smem) {
+// Column sums of a block: v[0..16) of thread (tx = column group, ty = row lane) are 8 sums and 8 second
+// sums for channels cg*8..+7.  They go through LDS; then every (value, column group) pair gets its own
+// thread, which adds the R row lanes in order and stores straight into partial[2][C] (the serial tail of
+// one thread per column group doing all 16 values cost more than the streaming loop for short blocks).
+__device__ __forceinline__ void reduce_rows_to_partial(const float (&v)[16], int tx, int ty, int W, int R, int cg0, int C,
+                                                       float* smem, float* __restrict__ partial) {
 #pragma unroll
-  for (int e = 0; e < NV; ++e) smem[(e * R + ty) * W + tx] = v[e];
+  for (int e = 0; e < 16; ++e) smem[(e * R + ty) * W + tx] = v[e];
   __syncthreads();
-  if (ty == 0) {
-#pragma unroll
-    for (int e = 0; e < NV; ++e) {
-      float s = 0.f;
-      for (int r = 0; r < R; ++r) s += smem[(e * R + r) * W + tx];
-      v[e] = s;
-    }
+  for (int i = threadIdx.x; i < 16 * W; i += blockDim.x) {
+    const int e = i / W, x = i - e * W;
+    if ((cg0 + x) * 8 >= C) continue;
+    float s = 0.f;
+    for (int r = 0; r < R; ++r) s += smem[(e * R + r) * W + x];
+    partial[(size_t)(e >> 3) * C + (cg0 + x) * 8 + (e & 7)] = s;
   }
 }
 
@@ -77,16 +79,11 @@ __global__ void bn_stats_k(const T* __restrict__ z, size_t M, int C, int W, int 
       }
     }
   }
-  reduce_over_rows<16>(acc, tx, ty, W, R, smem);
-  if (ty == 0 && cg < C / 8) {
-    float* p = partial + (size_t)blockIdx.x * 2 * C + cg * 8;
-    store8(p, acc);
-    store8(p + C, acc + 8);
-  }
+  reduce_rows_to_partial(acc, tx, ty, W, R, blockIdx.y * W, C, smem, partial + (size_t)blockIdx.x * 2 * C);
 }
 
 void bn_stats(int dt, hipStream_t st, const void* z, size_t M, int C, float* partial, int* P_out) {
-  RowTile t = make_rowtile(M, C, kMaxPartials);
+  RowTile t = make_rowtile(M, C, kBnPartials);
   {
     KScope ks(st, "bn_stats", (double)M * C * (dt == 0 ? 4.0 : 2.0), 3.0 * M * C);
     dim3 grid(t.P, t.nslab), block(t.W * t.R);
@@ -225,17 +222,12 @@ __global__ void bn_bwd_reduce_k(const T* __restrict__ dA, const T* __restrict__ 
       }
     }
   }
-  reduce_over_rows<16>(acc, tx, ty, W, R, smem);
-  if (ty == 0 && cg < C / 8) {
-    float* p = partial + (size_t)blockIdx.x * 2 * C + cg * 8;
-    store8(p, acc);
-    store8(p + C, acc + 8);
-  }
+  reduce_rows_to_partial(acc, tx, ty, W, R, blockIdx.y * W, C, smem, partial + (size_t)blockIdx.x * 2 * C);
 }
 
 void bn_bwd_reduce(int dt, hipStream_t st, const void* dA, const void* z, size_t M, int C,
                    const float* scale, const float* shift, int act, float* partial, int* P_out) {
-  RowTile t = make_rowtile(M, C, kMaxPartials);
+  RowTile t = make_rowtile(M, C, kBnPartials);
   {
     KScope ks(st, "bn_bwd_reduce", 2.0 * M * C * (dt == 0 ? 4.0 : 2.0), 6.0 * M * C);
     dim3 grid(t.P, t.nslab), block(t.W * t.R);

@@ -354,7 +354,7 @@ extern "C" int ftp_stage_create(const ftp_model* m, int a, int b, int batch, int
     }
     if (e != hipSuccess) { ftp_set_error("stage_create: stream/event creation failed: %s", hipGetErrorString(e)); stage_free(s); return FTP_ERR_HIP; }
   }
-  if ((rc = dev_alloc(&s->bn_part, (size_t)kMaxPartials * 2 * max_c * 4)) || (rc = dev_alloc(&s->coef, (size_t)3 * max_c * 4)) ||
+  if ((rc = dev_alloc(&s->bn_part, (size_t)kBnPartials * 2 * max_c * 4)) || (rc = dev_alloc(&s->coef, (size_t)3 * max_c * 4)) ||
       (rc = dev_alloc(&s->ws, ws_floats * 4)) || (rc = dev_alloc(&s->row_loss, (size_t)batch * 4))) { stage_free(s); return rc; }
   if (s->im2col_elems && (rc = dev_alloc(&s->im2col, s->im2col_elems * s->es))) { stage_free(s); return rc; }
 
