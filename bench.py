@@ -219,7 +219,10 @@ def main():
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch one plain 256 MiB copy (a dispatch of known traffic for counter scaling)")
     ap.add_argument("--seed", type=int, default=2110)
+    ap.add_argument("--spinup", type=float, default=1.0, help="seconds of untimed steps before the warm-up (0 for profiler runs)")
     args = ap.parse_args()
+    global SPINUP_S
+    SPINUP_S = args.spinup
     if args.gpus != 1:
         print("bench.py: this build runs one pipeline stage on ONE GPU; --gpus must be 1 "
               "(no multi-GPU path exists, see DESIGN.md 'More than one GPU')", file=sys.stderr)

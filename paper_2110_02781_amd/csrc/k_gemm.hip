@@ -886,6 +886,61 @@ __global__ __launch_bounds__(256) void pw_gemm_tiny_k(GemmArgs p) {
   }
 }
 
+// Weight gradient of a short problem, g_w[n][k] += sum_m dZ[m][n] * A'[m][k], in one launch: a block owns a
+// 16 x 16 tile of g_w, its four wavefronts split the pixels and meet in LDS, so there are no partial
+// buffers and no second kernel.  A lane's two MFMA operands are single elements of consecutive columns
+// (64-byte runs), the per-column scale/shift of the view sit in two registers.  Both storage types use
+// the fp32 16x16x4 MFMA: products of bfloat16 values are exact in fp32.
+template <typename T>
+__global__ __launch_bounds__(256) void pw_wgrad_tiny_k(GemmArgs p, int K_out) {
+  constexpr int U = 8;
+  __shared__ float red[4][16][17];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int jt = blockIdx.x % p.jtiles, it = blockIdx.x / p.jtiles;
+  const int l16 = lane & 15, mg = lane >> 4;
+  const int n = it * 16 + l16, k = jt * 16 + l16;
+  const bool n_ok = n < p.N, k_ok = k < p.K;
+  const T* X = reinterpret_cast<const T*>(p.x) + (n_ok ? n : 0);
+  const T* Y = reinterpret_cast<const T*>(p.y) + (k_ok ? k : 0);
+  const bool view = p.view.scale != nullptr;
+  const float sc = view && k_ok ? p.view.scale[k] : 1.f, sh = view && k_ok ? p.view.shift[k] : 0.f;
+  const float lo = act_lo(p.view.act), hi = act_hi(p.view.act);
+  const size_t M = p.M;
+  const size_t per = ((M + 15) / 16) * 4;                  // pixels per wavefront, a multiple of 4
+  const size_t mb = (size_t)wave * per, me = mb + per < M ? mb + per : M;
+  f4v acc = {0.f, 0.f, 0.f, 0.f};
+  for (size_t m0 = mb; m0 < me; m0 += 4 * U) {
+    float x[U], y[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t m = m0 + 4 * u + mg;
+      const bool ok = m < me;
+      x[u] = ok && n_ok ? to_f32(X[m * p.N]) : 0.f;
+      y[u] = ok && k_ok ? to_f32(Y[m * p.K]) : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float a = y[u];
+      if (view) {
+        const bool ok = m0 + 4 * u + mg < me && k_ok;       // padding stays exactly zero
+        a = ok ? round_to<T>(clamp_act(fmaf(a, sc, sh), lo, hi)) : 0.f;
+      }
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(x[u], a, acc, 0, 0, 0);
+    }
+  }
+  // register r of lane l is tile element (row 4*(l/16) + r = n, column l%16 = k)
+#pragma unroll
+  for (int r = 0; r < 4; ++r) red[wave][4 * mg + r][l16] = acc[r];
+  __syncthreads();
+  const int orow = threadIdx.x >> 4, ocol = threadIdx.x & 15;
+  const int on = it * 16 + orow, ok_ = jt * 16 + ocol;
+  if (on < p.N && ok_ < K_out) {
+    const float v = red[0][orow][ocol] + red[1][orow][ocol] + red[2][orow][ocol] + red[3][orow][ocol];
+    float* dst = reinterpret_cast<float*>(p.out) + (size_t)on * K_out + ok_;
+    *dst += v;
+  }
+}
+
 // the 16 x 16 kernel serves problems whose output is short (few rows) and whose reduction extent
 // allows aligned vector fragments
 static bool tiny_ok(int dt, size_t M, int R, int ncols, bool stats) {
@@ -1004,6 +1059,17 @@ void pw_wgrad(int dt, hipStream_t st, const void* dz, HView av, size_t M, int K,
   GemmArgs a{};
   a.x = dz; a.y = av.z; a.view = View{av.z, av.scale, av.shift, av.act};
   a.out = ws; a.M = M; a.K = K; a.N = N;
+  if (M <= 2048) {
+    // short problem: straight into g_w, no partials
+    KScope ks(st, "pw_wgrad", ((double)M * K + (double)M * N) * (dt == 0 ? 4.0 : 2.0) + (double)N * K * 8, 2.0 * M * K * N, (long)M, K, N);
+    a.out = g_w;
+    a.jtiles = (K + 15) / 16;
+    a.itiles = (N + 15) / 16;
+    const unsigned grid = (unsigned)a.jtiles * a.itiles;
+    if (dt == 0) hipLaunchKernelGGL(pw_wgrad_tiny_k<float>, dim3(grid), dim3(256), 0, st, a, K_out < 0 ? K : K_out);
+    else hipLaunchKernelGGL(pw_wgrad_tiny_k<bf16_t>, dim3(grid), dim3(256), 0, st, a, K_out < 0 ? K : K_out);
+    return;
+  }
   bool small;
   plan_wgrad(M, K, N, &a, &small);
   int S = a.nranges / a.itiles;
