@@ -535,6 +535,148 @@ void dw_fwd_bn_small(int dt, hipStream_t st, HView in, const void* w, const Conv
                                       mean, invstd, scale, shift, run_mean, run_var, eps, momentum, (T*)z));
 }
 
+// Backward of a depthwise layer and of the BatchNorm in front of it, for short tensors, in ONE launch.  A block
+// owns 8 channels over every input pixel; a thread gathers the dz values that reach its pixel once and uses each
+// twice: times the tap weight for the data gradient, times the pixel's own activation for the weight gradient
+// (dW[tap] = sum_p dz[p] * a[p*s-1+tap] is the same sum walked from the input side).  The data gradient never
+// leaves the registers: it is gated by the activation, reduced into the BatchNorm sums, and after the block-wide
+// reduction turned into the gradient of the raw convolution output in front (dz_prev).  Replaces depthwise
+// dgrad + wgrad + partial reduction + BatchNorm backward, which for tensors of a few hundred KB are all launch
+// latency.
+template <typename T, int RPT>
+__global__ __launch_bounds__(512) void dw_bwd_small_k(const T* __restrict__ dz, const T* __restrict__ w, View in, ConvGeom g,
+                                                      size_t M, const float* __restrict__ gamma, const float* __restrict__ mean,
+                                                      const float* __restrict__ invstd, float* g_w, float* g_gamma, float* g_beta,
+                                                      T* __restrict__ dz_prev) {
+  __shared__ float wl[9][8];
+  __shared__ float red[8][88];    // [wave][value]
+  __shared__ float coef[3][8];
+  const int C = g.Cout, c0 = blockIdx.x * 8, tid = threadIdx.x, nt = blockDim.x, s = g.stride;
+  if (tid < 72) wl[tid / 8][tid % 8] = to_f32(w[(size_t)(c0 + tid % 8) * 9 + tid / 8]);
+  float sc[8], sh[8];
+  load8(in.scale + c0, sc);
+  load8(in.shift + c0, sh);
+  const float lo = act_lo(in.act), hi = act_hi(in.act);
+  const T* zin = reinterpret_cast<const T*>(in.z);
+  float accw[9][8], bsum[16], dy[RPT][8], zv[RPT][8];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) accw[t][e] = 0.f;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) bsum[e] = 0.f;
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < RPT; ++q) {
+    const size_t m = tid + (size_t)q * nt;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { dy[q][e] = 0.f; zv[q][e] = 0.f; }
+    if (m >= M) continue;
+    const int ww = (int)(m % g.Win), h = (int)((m / g.Win) % g.Hin), n = (int)(m / ((size_t)g.Win * g.Hin));
+    load8(zin + m * C + c0, zv[q]);
+    float a[8], dA[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    bool pass[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float y = fmaf(zv[q][e], sc[e], sh[e]);
+      pass[e] = y > lo && y < hi;
+      a[e] = round_to<T>(clamp_act(y, lo, hi));
+    }
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      const int hn = h + 1 - i;
+      if (hn < 0 || (s == 2 && (hn & 1))) continue;
+      const int ho = s == 2 ? hn >> 1 : hn;
+      if (ho >= g.Hout) continue;
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const int wn = ww + 1 - j;
+        if (wn < 0 || (s == 2 && (wn & 1))) continue;
+        const int wo = s == 2 ? wn >> 1 : wn;
+        if (wo >= g.Wout) continue;
+        float d[8];
+        load8(dz + (((size_t)n * g.Hout + ho) * g.Wout + wo) * C + c0, d);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          dA[e] = fmaf(d[e], wl[i * 3 + j][e], dA[e]);
+          accw[i * 3 + j][e] = fmaf(d[e], a[e], accw[i * 3 + j][e]);
+        }
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float v = pass[e] ? round_to<T>(dA[e]) : 0.f;    // the data gradient as the separate kernels would store it
+      dy[q][e] = v;
+      bsum[e] += v;
+      bsum[8 + e] = fmaf(v, zv[q][e], bsum[8 + e]);
+    }
+  }
+  // block-wide sums in a fixed order: inside each wave, then the waves in order
+  const int wave = tid >> 6, nw = nt >> 6;
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float r = wave_sum(accw[t][e]);
+      if ((tid & 63) == 0) red[wave][t * 8 + e] = r;
+    }
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    const float r = wave_sum(bsum[e]);
+    if ((tid & 63) == 0) red[wave][72 + e] = r;
+  }
+  __syncthreads();
+  if (tid < 72) {
+    float tot = 0.f;
+    for (int q = 0; q < nw; ++q) tot += red[q][tid];
+    g_w[(size_t)(c0 + tid % 8) * 9 + tid / 8] += tot;
+  } else if (tid < 80) {
+    const int e = tid - 72, c = c0 + e;
+    double s0 = 0.0, s1 = 0.0;
+    for (int q = 0; q < nw; ++q) { s0 += red[q][72 + e]; s1 += red[q][80 + e]; }
+    const double mu = mean[c], is = invstd[c], gm = gamma[c], Md = (double)M;
+    const double dbeta = s0, dgamma = is * (s1 - mu * s0);
+    g_gamma[c] += (float)dgamma;
+    g_beta[c] += (float)dbeta;
+    const double k1 = gm * is, k2 = -k1 * is * dgamma / Md, k3 = -k1 * dbeta / Md - k2 * mu;
+    coef[0][e] = (float)k1; coef[1][e] = (float)k2; coef[2][e] = (float)k3;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < RPT; ++q) {
+    const size_t m = tid + (size_t)q * nt;
+    if (m >= M) continue;
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = fmaf(coef[0][e], dy[q][e], fmaf(coef[1][e], zv[q][e], coef[2][e]));
+    store8(dz_prev + m * C + c0, o);
+  }
+}
+
+int dw_bwd_small_ok(const ConvGeom& g) {
+  return (size_t)g.N * g.Hin * g.Win <= 2048 && g.Cout >= 32 && g.Cout % 8 == 0 && (g.stride == 1 || g.stride == 2);
+}
+
+void dw_bwd_small(int dt, hipStream_t st, const void* dz, const void* w, HView in, const ConvGeom& g, const float* gamma,
+                  const float* mean, const float* invstd, float* g_w, float* g_gamma, float* g_beta, void* dz_prev) {
+  const size_t M = (size_t)g.N * g.Hin * g.Win;
+  const int es = dt == 0 ? 4 : 2;
+  View v{in.z, in.scale, in.shift, in.act};
+  KScope ks(st, "dw_bwd_small", ((double)M * g.Cout * 2 + (double)g.N * g.Hout * g.Wout * g.Cout) * es, 42.0 * M * g.Cout,
+            (long)M, g.Cout, g.stride);
+  const dim3 grid(g.Cout / 8);
+  if (M > 1024) {
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_bwd_small_k<T, 4>), grid, dim3(512), 0, st, (const T*)dz, (const T*)w, v, g, M, gamma,
+                                        mean, invstd, g_w, g_gamma, g_beta, (T*)dz_prev));
+  } else if (M > 256) {
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_bwd_small_k<T, 2>), grid, dim3(M > 512 ? 512 : 256), 0, st, (const T*)dz, (const T*)w, v,
+                                        g, M, gamma, mean, invstd, g_w, g_gamma, g_beta, (T*)dz_prev));
+  } else {
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_bwd_small_k<T, 1>), grid, dim3(256), 0, st, (const T*)dz, (const T*)w, v, g, M, gamma,
+                                        mean, invstd, g_w, g_gamma, g_beta, (T*)dz_prev));
+  }
+}
+
 // Stride-2 data gradient over 8 x 8 input tiles: dIn[h][w] = sum over taps (i, j) with h+1-i and w+1-j
 // even of dz[(h+1-i)/2][(w+1-j)/2] * w[i][j].  A run of 4 input pixels starting at an even column
 // touches three dz columns per dz row.

@@ -104,6 +104,11 @@ int dw_fwd_bn_small_ok(const ConvGeom& g);
 void dw_fwd_bn_small(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, const float* gamma,
                      const float* beta, float* mean, float* invstd, float* scale, float* shift, float* run_mean,
                      float* run_var, float eps, float momentum, void* z);
+// depthwise dgrad + wgrad + the BatchNorm backward of the layer in front, one launch, short tensors
+// (dw_bwd_small_ok): dz_prev = gradient of the raw output of the convolution that feeds `in`
+int dw_bwd_small_ok(const ConvGeom& g);
+void dw_bwd_small(int dt, hipStream_t st, const void* dz, const void* w, HView in, const ConvGeom& g, const float* gamma,
+                  const float* mean, const float* invstd, float* g_w, float* g_gamma, float* g_beta, void* dz_prev);
 void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvGeom& g, void* dIn);
 size_t dw_wgrad_ws(const ConvGeom& g);
 void dw_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, float* ws, float* g_w);

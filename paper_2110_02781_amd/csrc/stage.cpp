@@ -626,35 +626,45 @@ extern "C" int ftp_stage_snapshot_weights(ftp_stage* s, int slot, void* stream) 
 // Forms dz in one of two alternating buffers; accumulates weight / gamma / beta gradients; when dIn is
 // non-NULL writes the gradient of the (activated) input there (+ res for pointwise).  The weight
 // gradient runs on the stage's side stream unless per-unit profiling is on.
+// mode: the whole layer; only up to dz (returned in *dz_out); or from a dz that the caller formed (passed as dA)
+enum { BWD_FULL = 0, BWD_DZ_ONLY = 1, BWD_FROM_DZ = 2 };
+static bool stage_overlaps(const ftp_stage* s) { return s->prof == nullptr && s->max_act_bytes >= ((size_t)32 << 20); }
+
 static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, const void* dA, HView in, HView out,
-                        void* dIn, const void* res, const WeightSet& W, hipStream_t st) {
+                        void* dIn, const void* res, const WeightSet& W, hipStream_t st, int mode = BWD_FULL,
+                        void** dz_out = nullptr) {
   const Sub& sb = p.info->subs[k];
   ConvGeom g = sb.g; g.N = s->batch;
   int C = g.Cout;
   size_t M = (size_t)s->batch * g.Hout * g.Wout;
   float* stt = sl.stats + p.st_off[k];
-  const int b = (int)(s->n_sub_bwd++ & 1u);
-  void* dz = s->gbuf[b ? 4 : 2];
   // The fork/join costs four event calls per layer on the host and a cross-stream dependency on the device:
   // it pays only when the kernels are long.  Measured: a 32x32-input stage (largest activation 12 MB) is
   // 10 % faster on one stream, a 224x224 one 15 % slower.
-  const bool overlap = s->prof == nullptr && s->max_act_bytes >= ((size_t)32 << 20) && M * (size_t)C >= ((size_t)1 << 20);
-  const bool small = bn_bwd_small_ok(M, C) != 0;
-  if (!small) {
-    int P = 0;
-    bn_bwd_reduce(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->bn_part, &P);
-    bn_bwd_finalize(st, s->bn_part, P, M, C, W.w32 + p.p_off + sb.gamma_off, stt, stt + C, s->grads + p.p_off + sb.gamma_off,
-                    s->grads + p.p_off + sb.beta_off, s->coef);
+  const bool overlap = mode == BWD_FULL && stage_overlaps(s) && M * (size_t)C >= ((size_t)1 << 20);
+  int b = 0;
+  void* dz = const_cast<void*>(dA);
+  if (mode != BWD_FROM_DZ) {
+    b = (int)(s->n_sub_bwd++ & 1u);
+    dz = s->gbuf[b ? 4 : 2];
+    const bool small = bn_bwd_small_ok(M, C) != 0;
+    if (!small) {
+      int P = 0;
+      bn_bwd_reduce(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->bn_part, &P);
+      bn_bwd_finalize(st, s->bn_part, P, M, C, W.w32 + p.p_off + sb.gamma_off, stt, stt + C, s->grads + p.p_off + sb.gamma_off,
+                      s->grads + p.p_off + sb.beta_off, s->coef);
+    }
+    if (s->join_pending[b]) {             // the weight gradient that last read this dz buffer must be done
+      HIP_TRY(hipStreamWaitEvent(st, s->ev_join[b], 0));
+      s->join_pending[b] = false;
+    }
+    if (small)
+      bn_bwd_small(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, W.w32 + p.p_off + sb.gamma_off, stt, stt + C,
+                   s->grads + p.p_off + sb.gamma_off, s->grads + p.p_off + sb.beta_off, dz);
+    else
+      bn_bwd_apply(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->coef, dz);
+    if (mode == BWD_DZ_ONLY) { *dz_out = dz; return FTP_OK; }
   }
-  if (s->join_pending[b]) {             // the weight gradient that last read this dz buffer must be done
-    HIP_TRY(hipStreamWaitEvent(st, s->ev_join[b], 0));
-    s->join_pending[b] = false;
-  }
-  if (small)
-    bn_bwd_small(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, W.w32 + p.p_off + sb.gamma_off, stt, stt + C,
-                 s->grads + p.p_off + sb.gamma_off, s->grads + p.p_off + sb.beta_off, dz);
-  else
-    bn_bwd_apply(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->coef, dz);
   hipStream_t ws = st;
   if (overlap) {
     HIP_TRY(hipEventRecord(s->ev_fork[b], st));
@@ -734,7 +744,21 @@ extern "C" int ftp_stage_backward(ftp_stage* s, int slot, const void* dy_dev, vo
         void* tmp = s->gbuf[3];
         // project: gradient of the activated depthwise output
         if ((rc = sub_backward(s, sl, p, ns - 1, d, v.sub_out[i][ns - 2], v.sub_out[i][ns - 1], tmp, nullptr, W, st))) return rc;
-        if (ns == 3) {
+        ConvGeom gd = ns == 3 ? u.subs[1].g : ConvGeom{};
+        gd.N = s->batch;
+        if (ns == 3 && !stage_overlaps(s) && !s->prof && dw_bwd_small_ok(gd)) {
+          // short tensors: depthwise dgrad + wgrad and the expand layer's BatchNorm backward in one launch
+          const Sub& s0 = u.subs[0];
+          const Sub& s1 = u.subs[1];
+          void* dz2 = nullptr;
+          if ((rc = sub_backward(s, sl, p, 1, tmp, v.sub_out[i][0], v.sub_out[i][1], nullptr, nullptr, W, st, BWD_DZ_ONLY, &dz2))) return rc;
+          void* dz1 = s->gbuf[(s->n_sub_bwd++ & 1u) ? 4 : 2];
+          float* st0 = sl.stats + p.st_off[0];
+          dw_bwd_small(s->dt, st, dz2, conv_w(s, W, p.p_off + s1.w_off), v.sub_out[i][0], gd, W.w32 + p.p_off + s0.gamma_off, st0,
+                       st0 + s0.g.Cout, s->grads + p.p_off + s1.w_off, s->grads + p.p_off + s0.gamma_off,
+                       s->grads + p.p_off + s0.beta_off, dz1);
+          if ((rc = sub_backward(s, sl, p, 0, dz1, in, v.sub_out[i][0], next, u.residual ? d : nullptr, W, st, BWD_FROM_DZ))) return rc;
+        } else if (ns == 3) {
           if ((rc = sub_backward(s, sl, p, 1, tmp, v.sub_out[i][0], v.sub_out[i][1], tmp, nullptr, W, st))) return rc;
           if ((rc = sub_backward(s, sl, p, 0, tmp, in, v.sub_out[i][0], next, u.residual ? d : nullptr, W, st))) return rc;
         } else {
