@@ -444,18 +444,55 @@ void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, 
 // (a few hundred KB, where the three separate kernels are all launch latency): a block owns 8 channels
 // over every output pixel, so the per-channel sums never leave the block.
 template <typename T>
-__global__ __launch_bounds__(1024) void dw_fwd_bn_small_k(View in, const T* __restrict__ w, ConvGeom g, size_t M,
+__global__ __launch_bounds__(1024) void dw_fwd_bn_small_k(View in, BnPending pend, const T* __restrict__ w, ConvGeom g, size_t M,
                                                           const float* __restrict__ gamma, const float* __restrict__ beta,
                                                           float* mean, float* invstd, float* scale, float* shift,
                                                           float* run_mean, float* run_var, float eps, float momentum,
                                                           T* __restrict__ z) {
   __shared__ float wl[9][8];
   __shared__ float red[16][16];
+  __shared__ double pre[16][16];
+  __shared__ float insc[2][8];
   const int C = g.Cout, c0 = blockIdx.x * 8, tid = threadIdx.x, nt = blockDim.x, s = g.stride;
   if (tid < 72) wl[tid / 8][tid % 8] = to_f32(w[(size_t)(c0 + tid % 8) * 9 + tid / 8]);
+  if (pend.partial) {
+    // the producer left its BatchNorm statistics as partial sums: finish them for this block's 8 channels
+    // (the depthwise channel owns the same channel of its input) and publish scale / shift for everyone else
+    if (tid < 256) {
+      const int v = tid & 15, lane = tid >> 4;
+      double t = 0.0;
+      for (int q = lane; q < pend.P; q += 16) t += (double)pend.partial[((size_t)q * 2 + (v >> 3)) * C + c0 + (v & 7)];
+      pre[lane][v] = t;
+    }
+    __syncthreads();
+    if (tid < 8) {
+      const int c = c0 + tid;
+      double s0 = 0.0, s1 = 0.0;
+      for (int l = 0; l < 16; ++l) { s0 += pre[l][tid]; s1 += pre[l][8 + tid]; }
+      const double Md = (double)pend.M, mu = s0 / Md;
+      double var = s1 / Md - mu * mu;
+      if (var < 0.0) var = 0.0;
+      const double is = 1.0 / sqrt(var + (double)eps);
+      const float scv = (float)((double)pend.gamma[c] * is);
+      const float shv = (float)((double)pend.beta[c] - mu * (double)scv);
+      pend.mean[c] = (float)mu;
+      pend.invstd[c] = (float)is;
+      pend.scale[c] = scv;
+      pend.shift[c] = shv;
+      const double unb = pend.M > 1 ? var * (Md / (Md - 1.0)) : var;
+      pend.run_mean[c] = (float)((1.0 - momentum) * pend.run_mean[c] + momentum * mu);
+      pend.run_var[c] = (float)((1.0 - momentum) * pend.run_var[c] + momentum * unb);
+      insc[0][tid] = scv;
+      insc[1][tid] = shv;
+    }
+    __syncthreads();
+  }
   float sc[8], sh[8];
   const bool view = in.scale != nullptr;
-  if (view) { load8(in.scale + c0, sc); load8(in.shift + c0, sh); }
+  if (pend.partial) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { sc[e] = insc[0][e]; sh[e] = insc[1][e]; }
+  } else if (view) { load8(in.scale + c0, sc); load8(in.shift + c0, sh); }
   const float lo = act_lo(in.act), hi = act_hi(in.act);
   const T* src = reinterpret_cast<const T*>(in.z);
   float acc[16];
@@ -522,7 +559,7 @@ int dw_fwd_bn_small_ok(const ConvGeom& g) {
   return (size_t)g.N * g.Hout * g.Wout <= 2048 && g.Cout >= 32 && g.Cout % 8 == 0;
 }
 
-void dw_fwd_bn_small(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, const float* gamma,
+void dw_fwd_bn_small(int dt, hipStream_t st, HView in, const BnPending& pend, const void* w, const ConvGeom& g, const float* gamma,
                      const float* beta, float* mean, float* invstd, float* scale, float* shift, float* run_mean,
                      float* run_var, float eps, float momentum, void* z) {
   const size_t M = (size_t)g.N * g.Hout * g.Wout;
@@ -531,7 +568,7 @@ void dw_fwd_bn_small(int dt, hipStream_t st, HView in, const void* w, const Conv
   KScope ks(st, "dw_fwd_bn_small", ((double)g.N * g.Hin * g.Win * g.Cout + (double)M * g.Cout) * es, 21.0 * M * g.Cout,
             (long)M, g.Cout, g.stride);
   const int nt = M > 512 ? 1024 : (M > 256 ? 512 : 256);
-  FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_fwd_bn_small_k<T>, dim3(g.Cout / 8), dim3(nt), 0, st, v, (const T*)w, g, M, gamma, beta,
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_fwd_bn_small_k<T>, dim3(g.Cout / 8), dim3(nt), 0, st, v, pend, (const T*)w, g, M, gamma, beta,
                                       mean, invstd, scale, shift, run_mean, run_var, eps, momentum, (T*)z));
 }
 

@@ -441,6 +441,72 @@ void bn_apply(int dt, hipStream_t st, HView in, size_t M, int C, const void* res
                                       C / 8, (const T*)res, (T*)out));
 }
 
+// Finish a BatchNorm whose statistics are still partial sums and materialise its output (+ residual) in ONE
+// launch, for short tensors: a block owns 8 channels over all rows.
+template <typename T>
+__global__ __launch_bounds__(1024) void bn_finalize_apply_small_k(BnPending pend, const T* __restrict__ z, size_t M, int C, int act,
+                                                                  float eps, float momentum, const T* __restrict__ res,
+                                                                  T* __restrict__ out) {
+  __shared__ double pre[16][16];
+  __shared__ float insc[2][8];
+  const int c0 = blockIdx.x * 8, tid = threadIdx.x, nt = blockDim.x;
+  if (tid < 256) {
+    const int v = tid & 15, lane = tid >> 4;
+    double t = 0.0;
+    for (int q = lane; q < pend.P; q += 16) t += (double)pend.partial[((size_t)q * 2 + (v >> 3)) * C + c0 + (v & 7)];
+    pre[lane][v] = t;
+  }
+  __syncthreads();
+  if (tid < 8) {
+    const int c = c0 + tid;
+    double s0 = 0.0, s1 = 0.0;
+    for (int l = 0; l < 16; ++l) { s0 += pre[l][tid]; s1 += pre[l][8 + tid]; }
+    const double Md = (double)pend.M, mu = s0 / Md;
+    double var = s1 / Md - mu * mu;
+    if (var < 0.0) var = 0.0;
+    const double is = 1.0 / sqrt(var + (double)eps);
+    const float scv = (float)((double)pend.gamma[c] * is);
+    const float shv = (float)((double)pend.beta[c] - mu * (double)scv);
+    pend.mean[c] = (float)mu;
+    pend.invstd[c] = (float)is;
+    pend.scale[c] = scv;
+    pend.shift[c] = shv;
+    const double unb = pend.M > 1 ? var * (Md / (Md - 1.0)) : var;
+    pend.run_mean[c] = (float)((1.0 - momentum) * pend.run_mean[c] + momentum * mu);
+    pend.run_var[c] = (float)((1.0 - momentum) * pend.run_var[c] + momentum * unb);
+    insc[0][tid] = scv;
+    insc[1][tid] = shv;
+  }
+  __syncthreads();
+  float sc[8], sh[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { sc[e] = insc[0][e]; sh[e] = insc[1][e]; }
+  const float lo = act_lo(act), hi = act_hi(act);
+  for (size_t m = tid; m < M; m += nt) {
+    float v[8];
+    load8(z + m * C + c0, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = round_to<T>(clamp_act(fmaf(v[e], sc[e], sh[e]), lo, hi));
+    if (res) {
+      float r[8];
+      load8(res + m * C + c0, r);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += r[e];
+    }
+    store8(out + m * C + c0, v);
+  }
+}
+
+int bn_finalize_apply_small_ok(size_t M, int C) { return M <= 2048 && C % 8 == 0; }
+
+void bn_finalize_apply_small(int dt, hipStream_t st, const BnPending& pend, const void* z, size_t M, int C, int act, float eps,
+                             float momentum, const void* res, void* out) {
+  KScope ks(st, "bn_fin_apply_small", (res ? 3.0 : 2.0) * M * C * (dt == 0 ? 4.0 : 2.0) + (double)pend.P * 2 * C * 4, 3.0 * M * C);
+  const int nt = M > 512 ? 1024 : (M > 256 ? 512 : 256);
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_finalize_apply_small_k<T>, dim3(C / 8), dim3(nt), 0, st, pend, (const T*)z, M, C, act, eps,
+                                      momentum, (const T*)res, (T*)out));
+}
+
 // ------------------------------------------------------------------ pooling
 template <typename T>
 __global__ void gap_fwd_k(View in, int N, int HW, int CG, T* __restrict__ out) {

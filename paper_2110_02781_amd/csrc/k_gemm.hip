@@ -792,12 +792,12 @@ __device__ __forceinline__ f4v tiny_mma(const float* a, const float* b, f4v acc,
 }
 
 template <typename T, int MODE>
-__global__ __launch_bounds__(256) void pw_gemm_tiny_k(GemmArgs p) {
+__device__ __forceinline__ void pw_gemm_tiny_body(const GemmArgs& p, const int bid) {
   constexpr int G = TinyStep<T>::G, KS = TinyStep<T>::KS, U = 4;
   __shared__ float red[4][16][17];
   __shared__ float sred[2][16][17];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int jt = blockIdx.x % p.jtiles, it = blockIdx.x / p.jtiles;
+  const int jt = bid % p.jtiles, it = bid / p.jtiles;
   const size_t i0 = (size_t)it * 16;
   const int j0 = jt * 16;
   const int R = MODE == MODE_FWD ? p.K : p.N;       // reduction extent (a multiple of G)
@@ -892,11 +892,11 @@ __global__ __launch_bounds__(256) void pw_gemm_tiny_k(GemmArgs p) {
 // (64-byte runs), the per-column scale/shift of the view sit in two registers.  Both storage types use
 // the fp32 16x16x4 MFMA: products of bfloat16 values are exact in fp32.
 template <typename T>
-__global__ __launch_bounds__(256) void pw_wgrad_tiny_k(GemmArgs p, int K_out) {
+__device__ __forceinline__ void pw_wgrad_tiny_body(const GemmArgs& p, const int K_out, const int bid) {
   constexpr int U = 8;
   __shared__ float red[4][16][17];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int jt = blockIdx.x % p.jtiles, it = blockIdx.x / p.jtiles;
+  const int jt = bid % p.jtiles, it = bid / p.jtiles;
   const int l16 = lane & 15, mg = lane >> 4;
   const int n = it * 16 + l16, k = jt * 16 + l16;
   const bool n_ok = n < p.N, k_ok = k < p.K;
@@ -939,6 +939,18 @@ __global__ __launch_bounds__(256) void pw_wgrad_tiny_k(GemmArgs p, int K_out) {
     float* dst = reinterpret_cast<float*>(p.out) + (size_t)on * K_out + ok_;
     *dst += v;
   }
+}
+
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void pw_gemm_tiny_k(GemmArgs p) { pw_gemm_tiny_body<T, MODE>(p, blockIdx.x); }
+template <typename T>
+__global__ __launch_bounds__(256) void pw_wgrad_tiny_k(GemmArgs p, int K_out) { pw_wgrad_tiny_body<T>(p, K_out, blockIdx.x); }
+// data gradient and weight gradient of one short layer in one launch: both read the same dZ, their tiles are
+// independent, and for these sizes a launch costs more than either of them
+template <typename T>
+__global__ __launch_bounds__(256) void pw_bwd_tiny_k(GemmArgs pd, GemmArgs pw, int K_out, int n_dgrad) {
+  if ((int)blockIdx.x < n_dgrad) pw_gemm_tiny_body<T, MODE_DGRAD>(pd, blockIdx.x);
+  else pw_wgrad_tiny_body<T>(pw, K_out, blockIdx.x - n_dgrad);
 }
 
 // the 16 x 16 kernel serves problems whose output is short (few rows) and whose reduction extent
@@ -1080,6 +1092,27 @@ void pw_wgrad(int dt, hipStream_t st, const void* dz, HView av, size_t M, int K,
   // K_out < K: the last K - K_out columns of A are padding and g_w is [N][K_out]
   if (K_out < 0) K_out = K;
   reduce_partials(st, ws, S, (size_t)N * K, K, (size_t)K_out, 1, g_w, K_out);
+}
+
+// wgrad then dgrad of one pointwise layer; short problems take one launch for both
+void pw_bwd(int dt, hipStream_t st, const void* dz, const void* w, const void* res, HView av, size_t M, int K, int N,
+            float* ws, float* g_w, void* dA) {
+  if (M <= 2048 && tiny_ok(dt, M, N, K, false)) {
+    GemmArgs d{}, g{};
+    d.x = dz; d.y = w; d.res = res; d.out = dA; d.M = M; d.K = K; d.N = N;
+    d.jtiles = (K + 15) / 16; d.itiles = (int)((M + 15) / 16); d.nranges = d.itiles; d.tiles_per_range = 1;
+    g.x = dz; g.y = av.z; g.view = View{av.z, av.scale, av.shift, av.act}; g.out = g_w; g.M = M; g.K = K; g.N = N;
+    g.jtiles = (K + 15) / 16; g.itiles = (N + 15) / 16;
+    const int nd = d.jtiles * d.itiles, nw = g.jtiles * g.itiles;
+    const double es = dt == 0 ? 4.0 : 2.0;
+    KScope ks(st, "pw_bwd", ((double)M * K * (res ? 3.0 : 2.0) + (double)M * N + (double)N * K) * es + (double)N * K * 8,
+              4.0 * M * K * N, (long)M, K, N);
+    if (dt == 0) hipLaunchKernelGGL(pw_bwd_tiny_k<float>, dim3(nd + nw), dim3(256), 0, st, d, g, K, nd);
+    else hipLaunchKernelGGL(pw_bwd_tiny_k<bf16_t>, dim3(nd + nw), dim3(256), 0, st, d, g, K, nd);
+    return;
+  }
+  pw_wgrad(dt, st, dz, av, M, K, N, ws, g_w);
+  pw_dgrad(dt, st, dz, w, res, M, K, N, dA);
 }
 
 }  // namespace ftp

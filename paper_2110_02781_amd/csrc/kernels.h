@@ -27,6 +27,16 @@ struct HView {  // same layout as the device-side View
   int act;
 };
 
+// BatchNorm statistics that have been reduced to partial[P][2][C] but not finalised yet
+struct BnPending {
+  const float* partial;
+  int P;
+  size_t M;
+  const float* gamma;
+  const float* beta;
+  float *mean, *invstd, *scale, *shift, *run_mean, *run_var;
+};
+
 struct ConvGeom {
   int N, Hin, Win, Cin, Hout, Wout, Cout, kh, kw, stride, ph, pw;
 };
@@ -69,6 +79,11 @@ void bn_bwd_small(int dt, hipStream_t st, const void* dA, const void* z, size_t 
 // out = act(scale*z+shift) (+ res)
 void bn_apply(int dt, hipStream_t st, HView in, size_t M, int C, const void* res, void* out);
 
+// finalize the pending statistics of z and write act(scale*z+shift) (+ res), one launch, short tensors
+int bn_finalize_apply_small_ok(size_t M, int C);
+void bn_finalize_apply_small(int dt, hipStream_t st, const BnPending& pend, const void* z, size_t M, int C, int act, float eps,
+                             float momentum, const void* res, void* out);
+
 // ---- pooling, loss, optimiser ---------------------------------------------------
 void gap_fwd(int dt, hipStream_t st, HView in, int N, int HW, int C, void* out);
 void gap_bwd(int dt, hipStream_t st, const void* dOut, int N, int HW, int C, void* dIn);
@@ -101,7 +116,9 @@ void reduce_partials(hipStream_t st, const float* ws, int P, size_t QC, int C, s
 void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z);
 // convolution + BatchNorm statistics + finalize in one launch for short tensors (dw_fwd_bn_small_ok)
 int dw_fwd_bn_small_ok(const ConvGeom& g);
-void dw_fwd_bn_small(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, const float* gamma,
+// pend.partial != nullptr: the BatchNorm of the input is still partial sums (pw_fwd's epilogue); the kernel
+// finishes it for the channels it owns (writes the per-channel vectors and the running statistics)
+void dw_fwd_bn_small(int dt, hipStream_t st, HView in, const BnPending& pend, const void* w, const ConvGeom& g, const float* gamma,
                      const float* beta, float* mean, float* invstd, float* scale, float* shift, float* run_mean,
                      float* run_var, float eps, float momentum, void* z);
 // depthwise dgrad + wgrad + the BatchNorm backward of the layer in front, one launch, short tensors
@@ -126,5 +143,9 @@ size_t pw_wgrad_ws(size_t M, int K, int N);
 // K_out >= 0: g_w is [N][K_out] and the last K - K_out columns of A are zero padding
 void pw_wgrad(int dt, hipStream_t st, const void* dz, HView a, size_t M, int K, int N, float* ws,
               float* g_w, int K_out = -1);
+
+// wgrad (g_w +=) then dgrad (dA =) of one layer on one stream; one launch for short problems
+void pw_bwd(int dt, hipStream_t st, const void* dz, const void* w, const void* res, HView a, size_t M, int K, int N,
+            float* ws, float* g_w, void* dA);
 
 }  // namespace ftp

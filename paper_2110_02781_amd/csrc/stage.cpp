@@ -502,7 +502,10 @@ static void build_views(const ftp_stage* s, const Slot& sl, Views* v) {
   }
 }
 
-static void sub_forward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, HView in, const WeightSet& W, hipStream_t st) {
+// pend (in/out): on entry the unfinished BatchNorm of `in` (partial == nullptr: none); on exit, when
+// defer is set and the statistics of this layer were left as partial sums, their description
+static void sub_forward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, HView in, const WeightSet& W, hipStream_t st,
+                        BnPending* pend = nullptr, bool defer = false) {
   const Sub& sb = p.info->subs[k];
   ConvGeom g = sb.g; g.N = s->batch;
   void* z = sl.stash + p.z_off[k];
@@ -511,20 +514,29 @@ static void sub_forward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, HVi
   int P = 0;
   float* stt = sl.stats + p.st_off[k];
   int C = g.Cout;
+  const float* gamma = W.w32 + p.p_off + sb.gamma_off;
+  const float* beta = W.w32 + p.p_off + sb.beta_off;
+  float* rm = s->run_mean + p.bn_off + sb.bn_off;
+  float* rv = s->run_var + p.bn_off + sb.bn_off;
   if (sb.type == SUB_DW && dw_fwd_bn_small_ok(g)) {
-    dw_fwd_bn_small(s->dt, st, in, w, g, W.w32 + p.p_off + sb.gamma_off, W.w32 + p.p_off + sb.beta_off, stt, stt + C, stt + 2 * C,
-                    stt + 3 * C, s->run_mean + p.bn_off + sb.bn_off, s->run_var + p.bn_off + sb.bn_off, kBnEps, kBnMomentum, z);
+    BnPending none{};
+    dw_fwd_bn_small(s->dt, st, in, pend ? *pend : none, w, g, gamma, beta, stt, stt + C, stt + 2 * C, stt + 3 * C, rm, rv, kBnEps,
+                    kBnMomentum, z);
+    if (pend) pend->partial = nullptr;
     return;
   }
   if (sb.type == SUB_PW) {
     pw_fwd(s->dt, st, in, w, nullptr, M, g.Cin, g.Cout, z, s->bn_part, &P);   // statistics in the epilogue
+    if (defer && pend) {
+      *pend = BnPending{s->bn_part, P, M, gamma, beta, stt, stt + C, stt + 2 * C, stt + 3 * C, rm, rv};
+      return;
+    }
   } else {
     if (sb.type == SUB_DW) dw_fwd(s->dt, st, in, w, g, z);
     else conv_direct_fwd(s->dt, st, in, w, g, z);
     bn_stats(s->dt, st, z, M, g.Cout, s->bn_part, &P);
   }
-  bn_finalize(st, s->bn_part, P, M, C, W.w32 + p.p_off + sb.gamma_off, W.w32 + p.p_off + sb.beta_off, stt, stt + C,
-              stt + 2 * C, stt + 3 * C, s->run_mean + p.bn_off + sb.bn_off, s->run_var + p.bn_off + sb.bn_off, kBnEps, kBnMomentum);
+  bn_finalize(st, s->bn_part, P, M, C, gamma, beta, stt, stt + C, stt + 2 * C, stt + 3 * C, rm, rv, kBnEps, kBnMomentum);
 }
 
 extern "C" int ftp_stage_forward(ftp_stage* s, int slot, const void* x_dev, void* y_dev, void* stream) {
@@ -556,8 +568,27 @@ extern "C" int ftp_stage_forward(ftp_stage* s, int slot, const void* x_dev, void
         break;
       case FTP_UNIT_INVRES: {
         HView h = in;
-        for (size_t k = 0; k < u.subs.size(); ++k) { sub_forward(s, sl, p, k, h, W, st); h = v.sub_out[i][k]; }
-        bn_apply(s->dt, st, h, (size_t)s->batch * u.outH * u.outW, u.outC, u.residual ? in.z : nullptr, sl.stash + p.out_off);
+        BnPending pend{};
+        for (size_t k = 0; k < u.subs.size(); ++k) {
+          // an expand layer in front of a short depthwise layer leaves its statistics to that layer's kernel
+          bool defer = false;
+          if (k + 1 < u.subs.size() && u.subs[k].type == SUB_PW && u.subs[k + 1].type == SUB_DW) {
+            ConvGeom gn = u.subs[k + 1].g; gn.N = s->batch;
+            defer = dw_fwd_bn_small_ok(gn) && (size_t)s->batch * u.subs[k].g.Hout * u.subs[k].g.Wout <= 16 * 128;
+          }
+          // ... and the project layer leaves them to the kernel that writes the block output
+          const size_t Mo = (size_t)s->batch * u.outH * u.outW;
+          if (k + 1 == u.subs.size() && u.subs[k].type == SUB_PW) defer = bn_finalize_apply_small_ok(Mo, u.outC) != 0;
+          sub_forward(s, sl, p, k, h, W, st, &pend, defer);
+          h = v.sub_out[i][k];
+        }
+        if (pend.partial) {
+          bn_finalize_apply_small(s->dt, st, pend, h.z, (size_t)s->batch * u.outH * u.outW, u.outC, h.act, kBnEps, kBnMomentum,
+                                  u.residual ? in.z : nullptr, sl.stash + p.out_off);
+          pend.partial = nullptr;
+        } else {
+          bn_apply(s->dt, st, h, (size_t)s->batch * u.outH * u.outW, u.outC, u.residual ? in.z : nullptr, sl.stash + p.out_off);
+        }
         break;
       }
       case FTP_UNIT_GAP:
@@ -673,6 +704,10 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
   }
   const void* w = conv_w(s, W, p.p_off + sb.w_off);
   float* gw = s->grads + p.p_off + sb.w_off;
+  if (sb.type == SUB_PW && !overlap && dIn) {
+    pw_bwd(s->dt, st, dz, w, res, in, M, g.Cin, g.Cout, s->ws, gw, dIn);
+    return FTP_OK;
+  }
   if (sb.type == SUB_DIRECT) conv_direct_wgrad(s->dt, ws, dz, in, g, s->im2col, s->ws, gw);
   else if (sb.type == SUB_PW) pw_wgrad(s->dt, ws, dz, in, M, g.Cin, g.Cout, s->ws, gw);
   else dw_wgrad(s->dt, ws, dz, in, g, s->ws, gw);
