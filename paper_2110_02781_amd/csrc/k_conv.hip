@@ -440,68 +440,93 @@ void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, 
   }
 }
 
-// Depthwise convolution, BatchNorm statistics and their finalisation in ONE launch for short tensors
-// (a few hundred KB, where the three separate kernels are all launch latency): a block owns 8 channels
-// over every output pixel, so the per-channel sums never leave the block.
+// ---- short tensors: whole depthwise layers in one launch ------------------------------------------------
+// For tensors of a few hundred KB the separate kernels are all launch latency.  Here a block owns 4 channels
+// over every pixel: the tensor that is gathered from (input in forward, dz in backward) is staged once in LDS
+// as one float4 per pixel (the view applied once per element), so the nine taps are LDS reads and the
+// per-channel sums never leave the block.
+__device__ __forceinline__ float4 view4(float4 v, const float* sc, const float* sh, float lo, float hi) {
+  return make_float4(clamp_act(fmaf(v.x, sc[0], sh[0]), lo, hi), clamp_act(fmaf(v.y, sc[1], sh[1]), lo, hi),
+                     clamp_act(fmaf(v.z, sc[2], sh[2]), lo, hi), clamp_act(fmaf(v.w, sc[3], sh[3]), lo, hi));
+}
+template <typename T> __device__ __forceinline__ float4 round4(float4 v) {
+  return make_float4(round_to<T>(v.x), round_to<T>(v.y), round_to<T>(v.z), round_to<T>(v.w));
+}
+
+// finish pending BatchNorm statistics for channels c0..c0+3 (first 256 threads), result in insc[2][4]
+__device__ __forceinline__ void finish_pending4(const BnPending& pend, int C, int c0, float eps, float momentum, double (*pre)[8],
+                                                float (*insc)[4]) {
+  const int tid = threadIdx.x;
+  if (tid < 256) {
+    const int v = tid & 7, lane = tid >> 3;           // 4 sums, 4 second sums; 32 lanes each
+    double t = 0.0;
+    for (int q = lane; q < pend.P; q += 32) t += (double)pend.partial[((size_t)q * 2 + (v >> 2)) * C + c0 + (v & 3)];
+    pre[lane][v] = t;
+  }
+  __syncthreads();
+  if (tid < 4) {
+    const int c = c0 + tid;
+    double s0 = 0.0, s1 = 0.0;
+    for (int l = 0; l < 32; ++l) { s0 += pre[l][tid]; s1 += pre[l][4 + tid]; }
+    const double Md = (double)pend.M, mu = s0 / Md;
+    double var = s1 / Md - mu * mu;
+    if (var < 0.0) var = 0.0;
+    const double is = 1.0 / sqrt(var + (double)eps);
+    const float scv = (float)((double)pend.gamma[c] * is);
+    const float shv = (float)((double)pend.beta[c] - mu * (double)scv);
+    pend.mean[c] = (float)mu;
+    pend.invstd[c] = (float)is;
+    pend.scale[c] = scv;
+    pend.shift[c] = shv;
+    const double unb = pend.M > 1 ? var * (Md / (Md - 1.0)) : var;
+    pend.run_mean[c] = (float)((1.0 - momentum) * pend.run_mean[c] + momentum * mu);
+    pend.run_var[c] = (float)((1.0 - momentum) * pend.run_var[c] + momentum * unb);
+    insc[0][tid] = scv;
+    insc[1][tid] = shv;
+  }
+  __syncthreads();
+}
+
+// Depthwise convolution + BatchNorm statistics + their finalisation (and, when the producer left them pending,
+// the finalisation of the input's BatchNorm too).
 template <typename T>
 __global__ __launch_bounds__(1024) void dw_fwd_bn_small_k(View in, BnPending pend, const T* __restrict__ w, ConvGeom g, size_t M,
-                                                          const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                          size_t Min, const float* __restrict__ gamma, const float* __restrict__ beta,
                                                           float* mean, float* invstd, float* scale, float* shift,
                                                           float* run_mean, float* run_var, float eps, float momentum,
                                                           T* __restrict__ z) {
-  __shared__ float wl[9][8];
-  __shared__ float red[16][16];
-  __shared__ double pre[16][16];
-  __shared__ float insc[2][8];
-  const int C = g.Cout, c0 = blockIdx.x * 8, tid = threadIdx.x, nt = blockDim.x, s = g.stride;
-  if (tid < 72) wl[tid / 8][tid % 8] = to_f32(w[(size_t)(c0 + tid % 8) * 9 + tid / 8]);
-  if (pend.partial) {
-    // the producer left its BatchNorm statistics as partial sums: finish them for this block's 8 channels
-    // (the depthwise channel owns the same channel of its input) and publish scale / shift for everyone else
-    if (tid < 256) {
-      const int v = tid & 15, lane = tid >> 4;
-      double t = 0.0;
-      for (int q = lane; q < pend.P; q += 16) t += (double)pend.partial[((size_t)q * 2 + (v >> 3)) * C + c0 + (v & 7)];
-      pre[lane][v] = t;
-    }
-    __syncthreads();
-    if (tid < 8) {
-      const int c = c0 + tid;
-      double s0 = 0.0, s1 = 0.0;
-      for (int l = 0; l < 16; ++l) { s0 += pre[l][tid]; s1 += pre[l][8 + tid]; }
-      const double Md = (double)pend.M, mu = s0 / Md;
-      double var = s1 / Md - mu * mu;
-      if (var < 0.0) var = 0.0;
-      const double is = 1.0 / sqrt(var + (double)eps);
-      const float scv = (float)((double)pend.gamma[c] * is);
-      const float shv = (float)((double)pend.beta[c] - mu * (double)scv);
-      pend.mean[c] = (float)mu;
-      pend.invstd[c] = (float)is;
-      pend.scale[c] = scv;
-      pend.shift[c] = shv;
-      const double unb = pend.M > 1 ? var * (Md / (Md - 1.0)) : var;
-      pend.run_mean[c] = (float)((1.0 - momentum) * pend.run_mean[c] + momentum * mu);
-      pend.run_var[c] = (float)((1.0 - momentum) * pend.run_var[c] + momentum * unb);
-      insc[0][tid] = scv;
-      insc[1][tid] = shv;
-    }
-    __syncthreads();
-  }
-  float sc[8], sh[8];
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  float4* tile = reinterpret_cast<float4*>(smem_raw);           // [Min]
+  __shared__ float wl[9][4];
+  __shared__ float red[16][8];
+  __shared__ double pre[32][8];
+  __shared__ float insc[2][4];
+  const int C = g.Cout, c0 = blockIdx.x * 4, tid = threadIdx.x, nt = blockDim.x, s = g.stride;
+  if (tid < 36) wl[tid / 4][tid % 4] = to_f32(w[(size_t)(c0 + tid % 4) * 9 + tid / 4]);
   const bool view = in.scale != nullptr;
-  if (pend.partial) {
+  if (pend.partial) finish_pending4(pend, C, c0, eps, momentum, pre, insc);
+  else if (tid < 4 && view) { insc[0][tid] = in.scale[c0 + tid]; insc[1][tid] = in.shift[c0 + tid]; }
+  if (!pend.partial) __syncthreads();
+  float sc[4] = {1.f, 1.f, 1.f, 1.f}, sh[4] = {0.f, 0.f, 0.f, 0.f};
+  if (view) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { sc[e] = insc[0][e]; sh[e] = insc[1][e]; }
-  } else if (view) { load8(in.scale + c0, sc); load8(in.shift + c0, sh); }
-  const float lo = act_lo(in.act), hi = act_hi(in.act);
+    for (int e = 0; e < 4; ++e) { sc[e] = insc[0][e]; sh[e] = insc[1][e]; }
+  }
+  const float lo = view ? act_lo(in.act) : -INFINITY, hi = view ? act_hi(in.act) : INFINITY;
   const T* src = reinterpret_cast<const T*>(in.z);
-  float acc[16];
-#pragma unroll
-  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  for (size_t m = tid; m < Min; m += nt) {
+    float4 v = load4(src + m * C + c0);
+    if (view) v = round4<T>(view4(v, sc, sh, lo, hi));
+    tile[m] = v;
+  }
   __syncthreads();
+  float4 wr[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) wr[t] = make_float4(wl[t][0], wl[t][1], wl[t][2], wl[t][3]);
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (size_t m = tid; m < M; m += nt) {
     const int wo = (int)(m % g.Wout), ho = (int)((m / g.Wout) % g.Hout), n = (int)(m / ((size_t)g.Wout * g.Hout));
-    float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
     for (int i = 0; i < 3; ++i) {
       const int h = ho * s - 1 + i;
@@ -510,36 +535,27 @@ __global__ __launch_bounds__(1024) void dw_fwd_bn_small_k(View in, BnPending pen
       for (int j = 0; j < 3; ++j) {
         const int ww = wo * s - 1 + j;
         if (ww < 0 || ww >= g.Win) continue;
-        float v[8];
-        load8(src + (((size_t)n * g.Hin + h) * g.Win + ww) * C + c0, v);
-        if (view) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] = round_to<T>(clamp_act(fmaf(v[e], sc[e], sh[e]), lo, hi));
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = fmaf(v[e], wl[i * 3 + j][e], o[e]);
+        o = fma4(tile[((size_t)n * g.Hin + h) * g.Win + ww], wr[i * 3 + j], o);
       }
     }
-    store8(z + m * C + c0, o);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float sv = round_to<T>(o[e]);       // statistics of the values as stored
-      acc[e] += sv;
-      acc[8 + e] = fmaf(sv, sv, acc[8 + e]);
-    }
+    store4(z + m * C + c0, o);
+    const float4 sv = round4<T>(o);               // statistics of the values as stored
+    acc[0] += sv.x; acc[1] += sv.y; acc[2] += sv.z; acc[3] += sv.w;
+    acc[4] = fmaf(sv.x, sv.x, acc[4]); acc[5] = fmaf(sv.y, sv.y, acc[5]);
+    acc[6] = fmaf(sv.z, sv.z, acc[6]); acc[7] = fmaf(sv.w, sv.w, acc[7]);
   }
 #pragma unroll
-  for (int e = 0; e < 16; ++e) acc[e] = wave_sum(acc[e]);
+  for (int e = 0; e < 8; ++e) acc[e] = wave_sum(acc[e]);
   const int wave = tid >> 6, nw = nt >> 6;
   if ((tid & 63) == 0) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) red[wave][e] = acc[e];
+    for (int e = 0; e < 8; ++e) red[wave][e] = acc[e];
   }
   __syncthreads();
-  if (tid < 8) {
+  if (tid < 4) {
     const int c = c0 + tid;
     double s0 = 0.0, s1 = 0.0;
-    for (int q = 0; q < nw; ++q) { s0 += red[q][tid]; s1 += red[q][8 + tid]; }
+    for (int q = 0; q < nw; ++q) { s0 += red[q][tid]; s1 += red[q][4 + tid]; }
     const double Md = (double)M, mu = s0 / Md;
     double var = s1 / Md - mu * mu;
     if (var < 0.0) var = 0.0;
@@ -556,69 +572,67 @@ __global__ __launch_bounds__(1024) void dw_fwd_bn_small_k(View in, BnPending pen
 }
 
 int dw_fwd_bn_small_ok(const ConvGeom& g) {
-  return (size_t)g.N * g.Hout * g.Wout <= 2048 && g.Cout >= 32 && g.Cout % 8 == 0;
+  return (size_t)g.N * g.Hout * g.Wout <= 2048 && (size_t)g.N * g.Hin * g.Win <= 3072 && g.Cout >= 32 && g.Cout % 8 == 0;
 }
 
 void dw_fwd_bn_small(int dt, hipStream_t st, HView in, const BnPending& pend, const void* w, const ConvGeom& g, const float* gamma,
                      const float* beta, float* mean, float* invstd, float* scale, float* shift, float* run_mean,
                      float* run_var, float eps, float momentum, void* z) {
-  const size_t M = (size_t)g.N * g.Hout * g.Wout;
+  const size_t M = (size_t)g.N * g.Hout * g.Wout, Min = (size_t)g.N * g.Hin * g.Win;
   const int es = dt == 0 ? 4 : 2;
   View v{in.z, in.scale, in.shift, in.act};
-  KScope ks(st, "dw_fwd_bn_small", ((double)g.N * g.Hin * g.Win * g.Cout + (double)M * g.Cout) * es, 21.0 * M * g.Cout,
-            (long)M, g.Cout, g.stride);
-  const int nt = M > 512 ? 1024 : (M > 256 ? 512 : 256);
-  FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_fwd_bn_small_k<T>, dim3(g.Cout / 8), dim3(nt), 0, st, v, pend, (const T*)w, g, M, gamma, beta,
-                                      mean, invstd, scale, shift, run_mean, run_var, eps, momentum, (T*)z));
+  KScope ks(st, "dw_fwd_bn_small", ((double)Min * g.Cout + (double)M * g.Cout) * es, 21.0 * M * g.Cout, (long)M, g.Cout, g.stride);
+  const int nt = Min > 512 ? 1024 : (Min > 256 ? 512 : 256);
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_fwd_bn_small_k<T>, dim3(g.Cout / 4), dim3(nt), Min * 16, st, v, pend, (const T*)w, g, M, Min,
+                                      gamma, beta, mean, invstd, scale, shift, run_mean, run_var, eps, momentum, (T*)z));
 }
 
-// Backward of a depthwise layer and of the BatchNorm in front of it, for short tensors, in ONE launch.  A block
-// owns 8 channels over every input pixel; a thread gathers the dz values that reach its pixel once and uses each
-// twice: times the tap weight for the data gradient, times the pixel's own activation for the weight gradient
-// (dW[tap] = sum_p dz[p] * a[p*s-1+tap] is the same sum walked from the input side).  The data gradient never
-// leaves the registers: it is gated by the activation, reduced into the BatchNorm sums, and after the block-wide
-// reduction turned into the gradient of the raw convolution output in front (dz_prev).  Replaces depthwise
-// dgrad + wgrad + partial reduction + BatchNorm backward, which for tensors of a few hundred KB are all launch
-// latency.
+// Backward of a depthwise layer and of the BatchNorm in front of it.  A thread owns input pixels; it gathers the
+// dz values that reach a pixel once (from the LDS copy) and uses each twice: times the tap weight for the data
+// gradient, times the pixel's own activation for the weight gradient (dW[tap] = sum_p dz[p] * a[p*s-1+tap] is
+// the same sum walked from the input side).  The data gradient never leaves the registers: it is gated by the
+// activation, reduced into the BatchNorm sums, and after the block-wide reduction turned into the gradient of
+// the raw convolution output in front (dz_prev).  Replaces depthwise dgrad + wgrad + partial reduction +
+// BatchNorm backward.
 template <typename T, int RPT>
 __global__ __launch_bounds__(512) void dw_bwd_small_k(const T* __restrict__ dz, const T* __restrict__ w, View in, ConvGeom g,
-                                                      size_t M, const float* __restrict__ gamma, const float* __restrict__ mean,
-                                                      const float* __restrict__ invstd, float* g_w, float* g_gamma, float* g_beta,
-                                                      T* __restrict__ dz_prev) {
-  __shared__ float wl[9][8];
-  __shared__ float red[8][88];    // [wave][value]
-  __shared__ float coef[3][8];
-  const int C = g.Cout, c0 = blockIdx.x * 8, tid = threadIdx.x, nt = blockDim.x, s = g.stride;
-  if (tid < 72) wl[tid / 8][tid % 8] = to_f32(w[(size_t)(c0 + tid % 8) * 9 + tid / 8]);
-  float sc[8], sh[8];
-  load8(in.scale + c0, sc);
-  load8(in.shift + c0, sh);
+                                                      size_t M, size_t Mout, const float* __restrict__ gamma,
+                                                      const float* __restrict__ mean, const float* __restrict__ invstd, float* g_w,
+                                                      float* g_gamma, float* g_beta, T* __restrict__ dz_prev) {
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  float4* tile = reinterpret_cast<float4*>(smem_raw);           // dz, [Mout]
+  __shared__ float wl[9][4];
+  __shared__ float red[8][44];    // [wave][value]
+  __shared__ float coef[3][4];
+  const int C = g.Cout, c0 = blockIdx.x * 4, tid = threadIdx.x, nt = blockDim.x, s = g.stride;
+  if (tid < 36) wl[tid / 4][tid % 4] = to_f32(w[(size_t)(c0 + tid % 4) * 9 + tid / 4]);
+  float sc[4], sh[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { sc[e] = in.scale[c0 + e]; sh[e] = in.shift[c0 + e]; }
   const float lo = act_lo(in.act), hi = act_hi(in.act);
   const T* zin = reinterpret_cast<const T*>(in.z);
-  float accw[9][8], bsum[16], dy[RPT][8], zv[RPT][8];
-#pragma unroll
-  for (int t = 0; t < 9; ++t)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) accw[t][e] = 0.f;
-#pragma unroll
-  for (int e = 0; e < 16; ++e) bsum[e] = 0.f;
+  for (size_t m = tid; m < Mout; m += nt) tile[m] = load4(dz + m * C + c0);
   __syncthreads();
+  float4 wr[9], accw[9], dy[RPT], zv[RPT];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) {
+    wr[t] = make_float4(wl[t][0], wl[t][1], wl[t][2], wl[t][3]);
+    accw[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  float bsum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
   for (int q = 0; q < RPT; ++q) {
     const size_t m = tid + (size_t)q * nt;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { dy[q][e] = 0.f; zv[q][e] = 0.f; }
+    dy[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    zv[q] = dy[q];
     if (m >= M) continue;
     const int ww = (int)(m % g.Win), h = (int)((m / g.Win) % g.Hin), n = (int)(m / ((size_t)g.Win * g.Hin));
-    load8(zin + m * C + c0, zv[q]);
-    float a[8], dA[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    bool pass[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float y = fmaf(zv[q][e], sc[e], sh[e]);
-      pass[e] = y > lo && y < hi;
-      a[e] = round_to<T>(clamp_act(y, lo, hi));
-    }
+    zv[q] = load4(zin + m * C + c0);
+    const float4 y = make_float4(fmaf(zv[q].x, sc[0], sh[0]), fmaf(zv[q].y, sc[1], sh[1]), fmaf(zv[q].z, sc[2], sh[2]),
+                                 fmaf(zv[q].w, sc[3], sh[3]));
+    const float4 a = round4<T>(make_float4(clamp_act(y.x, lo, hi), clamp_act(y.y, lo, hi), clamp_act(y.z, lo, hi),
+                                           clamp_act(y.w, lo, hi)));
+    float4 dA = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
     for (int i = 0; i < 3; ++i) {
       const int hn = h + 1 - i;
@@ -631,46 +645,44 @@ __global__ __launch_bounds__(512) void dw_bwd_small_k(const T* __restrict__ dz, 
         if (wn < 0 || (s == 2 && (wn & 1))) continue;
         const int wo = s == 2 ? wn >> 1 : wn;
         if (wo >= g.Wout) continue;
-        float d[8];
-        load8(dz + (((size_t)n * g.Hout + ho) * g.Wout + wo) * C + c0, d);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          dA[e] = fmaf(d[e], wl[i * 3 + j][e], dA[e]);
-          accw[i * 3 + j][e] = fmaf(d[e], a[e], accw[i * 3 + j][e]);
-        }
+        const float4 d = tile[((size_t)n * g.Hout + ho) * g.Wout + wo];
+        dA = fma4(d, wr[i * 3 + j], dA);
+        accw[i * 3 + j] = fma4(d, a, accw[i * 3 + j]);
       }
     }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float v = pass[e] ? round_to<T>(dA[e]) : 0.f;    // the data gradient as the separate kernels would store it
-      dy[q][e] = v;
-      bsum[e] += v;
-      bsum[8 + e] = fmaf(v, zv[q][e], bsum[8 + e]);
-    }
+    dA = round4<T>(dA);                    // the data gradient as the separate kernels would store it
+    float4 v;
+    v.x = (y.x > lo && y.x < hi) ? dA.x : 0.f;
+    v.y = (y.y > lo && y.y < hi) ? dA.y : 0.f;
+    v.z = (y.z > lo && y.z < hi) ? dA.z : 0.f;
+    v.w = (y.w > lo && y.w < hi) ? dA.w : 0.f;
+    dy[q] = v;
+    bsum[0] += v.x; bsum[1] += v.y; bsum[2] += v.z; bsum[3] += v.w;
+    bsum[4] = fmaf(v.x, zv[q].x, bsum[4]); bsum[5] = fmaf(v.y, zv[q].y, bsum[5]);
+    bsum[6] = fmaf(v.z, zv[q].z, bsum[6]); bsum[7] = fmaf(v.w, zv[q].w, bsum[7]);
   }
   // block-wide sums in a fixed order: inside each wave, then the waves in order
   const int wave = tid >> 6, nw = nt >> 6;
+  const bool lead = (tid & 63) == 0;
 #pragma unroll
-  for (int t = 0; t < 9; ++t)
+  for (int t = 0; t < 9; ++t) {
+    const float r0 = wave_sum(accw[t].x), r1 = wave_sum(accw[t].y), r2 = wave_sum(accw[t].z), r3 = wave_sum(accw[t].w);
+    if (lead) { red[wave][t * 4 + 0] = r0; red[wave][t * 4 + 1] = r1; red[wave][t * 4 + 2] = r2; red[wave][t * 4 + 3] = r3; }
+  }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float r = wave_sum(accw[t][e]);
-      if ((tid & 63) == 0) red[wave][t * 8 + e] = r;
-    }
-#pragma unroll
-  for (int e = 0; e < 16; ++e) {
+  for (int e = 0; e < 8; ++e) {
     const float r = wave_sum(bsum[e]);
-    if ((tid & 63) == 0) red[wave][72 + e] = r;
+    if (lead) red[wave][36 + e] = r;
   }
   __syncthreads();
-  if (tid < 72) {
+  if (tid < 36) {
     float tot = 0.f;
     for (int q = 0; q < nw; ++q) tot += red[q][tid];
-    g_w[(size_t)(c0 + tid % 8) * 9 + tid / 8] += tot;
-  } else if (tid < 80) {
-    const int e = tid - 72, c = c0 + e;
+    g_w[(size_t)(c0 + tid % 4) * 9 + tid / 4] += tot;
+  } else if (tid >= 64 && tid < 68) {
+    const int e = tid - 64, c = c0 + e;
     double s0 = 0.0, s1 = 0.0;
-    for (int q = 0; q < nw; ++q) { s0 += red[q][72 + e]; s1 += red[q][80 + e]; }
+    for (int q = 0; q < nw; ++q) { s0 += red[q][36 + e]; s1 += red[q][40 + e]; }
     const double mu = mean[c], is = invstd[c], gm = gamma[c], Md = (double)M;
     const double dbeta = s0, dgamma = is * (s1 - mu * s0);
     g_gamma[c] += (float)dgamma;
@@ -679,14 +691,14 @@ __global__ __launch_bounds__(512) void dw_bwd_small_k(const T* __restrict__ dz, 
     coef[0][e] = (float)k1; coef[1][e] = (float)k2; coef[2][e] = (float)k3;
   }
   __syncthreads();
+  const float4 k1 = make_float4(coef[0][0], coef[0][1], coef[0][2], coef[0][3]);
+  const float4 k2 = make_float4(coef[1][0], coef[1][1], coef[1][2], coef[1][3]);
+  const float4 k3 = make_float4(coef[2][0], coef[2][1], coef[2][2], coef[2][3]);
 #pragma unroll
   for (int q = 0; q < RPT; ++q) {
     const size_t m = tid + (size_t)q * nt;
     if (m >= M) continue;
-    float o[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = fmaf(coef[0][e], dy[q][e], fmaf(coef[1][e], zv[q][e], coef[2][e]));
-    store8(dz_prev + m * C + c0, o);
+    store4(dz_prev + m * C + c0, fma4(k1, dy[q], fma4(k2, zv[q], k3)));
   }
 }
 
@@ -696,21 +708,21 @@ int dw_bwd_small_ok(const ConvGeom& g) {
 
 void dw_bwd_small(int dt, hipStream_t st, const void* dz, const void* w, HView in, const ConvGeom& g, const float* gamma,
                   const float* mean, const float* invstd, float* g_w, float* g_gamma, float* g_beta, void* dz_prev) {
-  const size_t M = (size_t)g.N * g.Hin * g.Win;
+  const size_t M = (size_t)g.N * g.Hin * g.Win, Mout = (size_t)g.N * g.Hout * g.Wout;
   const int es = dt == 0 ? 4 : 2;
   View v{in.z, in.scale, in.shift, in.act};
-  KScope ks(st, "dw_bwd_small", ((double)M * g.Cout * 2 + (double)g.N * g.Hout * g.Wout * g.Cout) * es, 42.0 * M * g.Cout,
-            (long)M, g.Cout, g.stride);
-  const dim3 grid(g.Cout / 8);
+  KScope ks(st, "dw_bwd_small", ((double)M * g.Cout * 2 + (double)Mout * g.Cout) * es, 42.0 * M * g.Cout, (long)M, g.Cout, g.stride);
+  const dim3 grid(g.Cout / 4);
+  const size_t lds = Mout * 16;
   if (M > 1024) {
-    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_bwd_small_k<T, 4>), grid, dim3(512), 0, st, (const T*)dz, (const T*)w, v, g, M, gamma,
-                                        mean, invstd, g_w, g_gamma, g_beta, (T*)dz_prev));
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_bwd_small_k<T, 4>), grid, dim3(512), lds, st, (const T*)dz, (const T*)w, v, g, M, Mout,
+                                        gamma, mean, invstd, g_w, g_gamma, g_beta, (T*)dz_prev));
   } else if (M > 256) {
-    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_bwd_small_k<T, 2>), grid, dim3(M > 512 ? 512 : 256), 0, st, (const T*)dz, (const T*)w, v,
-                                        g, M, gamma, mean, invstd, g_w, g_gamma, g_beta, (T*)dz_prev));
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_bwd_small_k<T, 2>), grid, dim3(M > 512 ? 512 : 256), lds, st, (const T*)dz, (const T*)w,
+                                        v, g, M, Mout, gamma, mean, invstd, g_w, g_gamma, g_beta, (T*)dz_prev));
   } else {
-    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_bwd_small_k<T, 1>), grid, dim3(256), 0, st, (const T*)dz, (const T*)w, v, g, M, gamma,
-                                        mean, invstd, g_w, g_gamma, g_beta, (T*)dz_prev));
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_bwd_small_k<T, 1>), grid, dim3(256), lds, st, (const T*)dz, (const T*)w, v, g, M, Mout,
+                                        gamma, mean, invstd, g_w, g_gamma, g_beta, (T*)dz_prev));
   }
 }
 
