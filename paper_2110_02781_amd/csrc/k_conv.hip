@@ -595,8 +595,8 @@ void dw_fwd_bn_small(int dt, hipStream_t st, HView in, const BnPending& pend, co
 // the raw convolution output in front (dz_prev).  Replaces depthwise dgrad + wgrad + partial reduction +
 // BatchNorm backward.
 template <typename T, int RPT>
-__global__ __launch_bounds__(512) void dw_bwd_small_k(const T* __restrict__ dz, const T* __restrict__ w, View in, ConvGeom g,
-                                                      size_t M, size_t Mout, const float* __restrict__ gamma,
+__global__ __launch_bounds__(512) void dw_bwd_small_k(const T* __restrict__ dz, BnBwdIn bo, const T* __restrict__ w, View in,
+                                                      ConvGeom g, size_t M, size_t Mout, const float* __restrict__ gamma,
                                                       const float* __restrict__ mean, const float* __restrict__ invstd, float* g_w,
                                                       float* g_gamma, float* g_beta, T* __restrict__ dz_prev) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
@@ -611,7 +611,67 @@ __global__ __launch_bounds__(512) void dw_bwd_small_k(const T* __restrict__ dz, 
   for (int e = 0; e < 4; ++e) { sc[e] = in.scale[c0 + e]; sh[e] = in.shift[c0 + e]; }
   const float lo = act_lo(in.act), hi = act_hi(in.act);
   const T* zin = reinterpret_cast<const T*>(in.z);
-  for (size_t m = tid; m < Mout; m += nt) tile[m] = load4(dz + m * C + c0);
+  if (bo.dA) {
+    // dz is not formed yet: this layer's own BatchNorm backward first (same channels, all pixels: block-local),
+    // its result goes straight into the LDS tile and never to memory
+    __shared__ float red2[8][8];
+    __shared__ float coef2[3][4];
+    const T* dA2 = reinterpret_cast<const T*>(bo.dA);
+    const T* z2 = reinterpret_cast<const T*>(bo.out.z);
+    float sc2[4], sh2[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { sc2[e] = bo.out.scale[c0 + e]; sh2[e] = bo.out.shift[c0 + e]; }
+    const float lo2 = act_lo(bo.out.act), hi2 = act_hi(bo.out.act);
+    float4 dy2[RPT], z2v[RPT];
+    float b2[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int q = 0; q < RPT; ++q) {
+      const size_t m = tid + (size_t)q * nt;
+      dy2[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      z2v[q] = dy2[q];
+      if (m >= Mout) continue;
+      const float4 d = load4(dA2 + m * C + c0);
+      const float4 zz = load4(z2 + m * C + c0);
+      const float y0 = fmaf(zz.x, sc2[0], sh2[0]), y1 = fmaf(zz.y, sc2[1], sh2[1]), y2 = fmaf(zz.z, sc2[2], sh2[2]),
+                  y3 = fmaf(zz.w, sc2[3], sh2[3]);
+      float4 v;
+      v.x = (y0 > lo2 && y0 < hi2) ? d.x : 0.f;
+      v.y = (y1 > lo2 && y1 < hi2) ? d.y : 0.f;
+      v.z = (y2 > lo2 && y2 < hi2) ? d.z : 0.f;
+      v.w = (y3 > lo2 && y3 < hi2) ? d.w : 0.f;
+      dy2[q] = v; z2v[q] = zz;
+      b2[0] += v.x; b2[1] += v.y; b2[2] += v.z; b2[3] += v.w;
+      b2[4] = fmaf(v.x, zz.x, b2[4]); b2[5] = fmaf(v.y, zz.y, b2[5]); b2[6] = fmaf(v.z, zz.z, b2[6]); b2[7] = fmaf(v.w, zz.w, b2[7]);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float r = wave_sum(b2[e]);
+      if ((tid & 63) == 0) red2[tid >> 6][e] = r;
+    }
+    __syncthreads();
+    if (tid < 4) {
+      const int c = c0 + tid;
+      double s0 = 0.0, s1 = 0.0;
+      for (int q = 0; q < (nt >> 6); ++q) { s0 += red2[q][tid]; s1 += red2[q][4 + tid]; }
+      const double mu = bo.mean[c], is = bo.invstd[c], gm = bo.gamma[c], Md = (double)Mout;
+      const double dbeta = s0, dgamma = is * (s1 - mu * s0);
+      bo.g_gamma[c] += (float)dgamma;
+      bo.g_beta[c] += (float)dbeta;
+      const double k1 = gm * is, k2 = -k1 * is * dgamma / Md, k3 = -k1 * dbeta / Md - k2 * mu;
+      coef2[0][tid] = (float)k1; coef2[1][tid] = (float)k2; coef2[2][tid] = (float)k3;
+    }
+    __syncthreads();
+    const float4 k1 = make_float4(coef2[0][0], coef2[0][1], coef2[0][2], coef2[0][3]);
+    const float4 k2 = make_float4(coef2[1][0], coef2[1][1], coef2[1][2], coef2[1][3]);
+    const float4 k3 = make_float4(coef2[2][0], coef2[2][1], coef2[2][2], coef2[2][3]);
+#pragma unroll
+    for (int q = 0; q < RPT; ++q) {
+      const size_t m = tid + (size_t)q * nt;
+      if (m < Mout) tile[m] = round4<T>(fma4(k1, dy2[q], fma4(k2, z2v[q], k3)));   // as a stored dz would read back
+    }
+  } else {
+    for (size_t m = tid; m < Mout; m += nt) tile[m] = load4(dz + m * C + c0);
+  }
   __syncthreads();
   float4 wr[9], accw[9], dy[RPT], zv[RPT];
 #pragma unroll
@@ -706,8 +766,9 @@ int dw_bwd_small_ok(const ConvGeom& g) {
   return (size_t)g.N * g.Hin * g.Win <= 2048 && g.Cout >= 32 && g.Cout % 8 == 0 && (g.stride == 1 || g.stride == 2);
 }
 
-void dw_bwd_small(int dt, hipStream_t st, const void* dz, const void* w, HView in, const ConvGeom& g, const float* gamma,
-                  const float* mean, const float* invstd, float* g_w, float* g_gamma, float* g_beta, void* dz_prev) {
+void dw_bwd_small(int dt, hipStream_t st, const void* dz, const BnBwdIn& bo, const void* w, HView in, const ConvGeom& g,
+                  const float* gamma, const float* mean, const float* invstd, float* g_w, float* g_gamma, float* g_beta,
+                  void* dz_prev) {
   const size_t M = (size_t)g.N * g.Hin * g.Win, Mout = (size_t)g.N * g.Hout * g.Wout;
   const int es = dt == 0 ? 4 : 2;
   View v{in.z, in.scale, in.shift, in.act};
@@ -715,13 +776,13 @@ void dw_bwd_small(int dt, hipStream_t st, const void* dz, const void* w, HView i
   const dim3 grid(g.Cout / 4);
   const size_t lds = Mout * 16;
   if (M > 1024) {
-    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_bwd_small_k<T, 4>), grid, dim3(512), lds, st, (const T*)dz, (const T*)w, v, g, M, Mout,
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_bwd_small_k<T, 4>), grid, dim3(512), lds, st, (const T*)dz, bo, (const T*)w, v, g, M, Mout,
                                         gamma, mean, invstd, g_w, g_gamma, g_beta, (T*)dz_prev));
   } else if (M > 256) {
-    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_bwd_small_k<T, 2>), grid, dim3(M > 512 ? 512 : 256), lds, st, (const T*)dz, (const T*)w,
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_bwd_small_k<T, 2>), grid, dim3(M > 512 ? 512 : 256), lds, st, (const T*)dz, bo, (const T*)w,
                                         v, g, M, Mout, gamma, mean, invstd, g_w, g_gamma, g_beta, (T*)dz_prev));
   } else {
-    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_bwd_small_k<T, 1>), grid, dim3(256), lds, st, (const T*)dz, (const T*)w, v, g, M, Mout,
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_bwd_small_k<T, 1>), grid, dim3(256), lds, st, (const T*)dz, bo, (const T*)w, v, g, M, Mout,
                                         gamma, mean, invstd, g_w, g_gamma, g_beta, (T*)dz_prev));
   }
 }

@@ -37,6 +37,14 @@ struct BnPending {
   float *mean, *invstd, *scale, *shift, *run_mean, *run_var;
 };
 
+// a BatchNorm backward still to be done: gradient dA of the activated output `out`
+struct BnBwdIn {
+  const void* dA;
+  HView out;
+  const float *gamma, *mean, *invstd;
+  float *g_gamma, *g_beta;
+};
+
 struct ConvGeom {
   int N, Hin, Win, Cin, Hout, Wout, Cout, kh, kw, stride, ph, pw;
 };
@@ -124,8 +132,11 @@ void dw_fwd_bn_small(int dt, hipStream_t st, HView in, const BnPending& pend, co
 // depthwise dgrad + wgrad + the BatchNorm backward of the layer in front, one launch, short tensors
 // (dw_bwd_small_ok): dz_prev = gradient of the raw output of the convolution that feeds `in`
 int dw_bwd_small_ok(const ConvGeom& g);
-void dw_bwd_small(int dt, hipStream_t st, const void* dz, const void* w, HView in, const ConvGeom& g, const float* gamma,
-                  const float* mean, const float* invstd, float* g_w, float* g_gamma, float* g_beta, void* dz_prev);
+// bo.dA != nullptr: dz is not formed yet; the kernel first runs the BatchNorm backward of the depthwise layer's own
+// output (bo: gradient of the activated output, the output view, its BatchNorm vectors and gradient slots)
+void dw_bwd_small(int dt, hipStream_t st, const void* dz, const BnBwdIn& bo, const void* w, HView in, const ConvGeom& g,
+                  const float* gamma, const float* mean, const float* invstd, float* g_w, float* g_gamma, float* g_beta,
+                  void* dz_prev);
 void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvGeom& g, void* dIn);
 size_t dw_wgrad_ws(const ConvGeom& g);
 void dw_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, float* ws, float* g_w);

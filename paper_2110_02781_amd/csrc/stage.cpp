@@ -785,11 +785,13 @@ extern "C" int ftp_stage_backward(ftp_stage* s, int slot, const void* dy_dev, vo
           // short tensors: depthwise dgrad + wgrad and the expand layer's BatchNorm backward in one launch
           const Sub& s0 = u.subs[0];
           const Sub& s1 = u.subs[1];
-          void* dz2 = nullptr;
-          if ((rc = sub_backward(s, sl, p, 1, tmp, v.sub_out[i][0], v.sub_out[i][1], nullptr, nullptr, W, st, BWD_DZ_ONLY, &dz2))) return rc;
+          // the depthwise layer's own BatchNorm backward happens inside too: its dz never reaches memory
           void* dz1 = s->gbuf[(s->n_sub_bwd++ & 1u) ? 4 : 2];
           float* st0 = sl.stats + p.st_off[0];
-          dw_bwd_small(s->dt, st, dz2, conv_w(s, W, p.p_off + s1.w_off), v.sub_out[i][0], gd, W.w32 + p.p_off + s0.gamma_off, st0,
+          float* st1 = sl.stats + p.st_off[1];
+          BnBwdIn bo{tmp, v.sub_out[i][1], W.w32 + p.p_off + s1.gamma_off, st1, st1 + s1.g.Cout,
+                     s->grads + p.p_off + s1.gamma_off, s->grads + p.p_off + s1.beta_off};
+          dw_bwd_small(s->dt, st, nullptr, bo, conv_w(s, W, p.p_off + s1.w_off), v.sub_out[i][0], gd, W.w32 + p.p_off + s0.gamma_off, st0,
                        st0 + s0.g.Cout, s->grads + p.p_off + s1.w_off, s->grads + p.p_off + s0.gamma_off,
                        s->grads + p.p_off + s0.beta_off, dz1);
           if ((rc = sub_backward(s, sl, p, 0, dz1, in, v.sub_out[i][0], next, u.residual ? d : nullptr, W, st, BWD_FROM_DZ))) return rc;
