@@ -791,13 +791,17 @@ __device__ __forceinline__ f4v tiny_mma(const float* a, const float* b, f4v acc,
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa), __builtin_bit_cast(bf16x8, pb), acc, 0, 0, 0);
 }
 
-template <typename T, int MODE>
+template <typename T, int MODE, int NW>
 __device__ __forceinline__ void pw_gemm_tiny_body(const GemmArgs& p, const int bid) {
   constexpr int G = TinyStep<T>::G, KS = TinyStep<T>::KS, U = 4;
-  __shared__ float red[4][16][17];
-  __shared__ float sred[2][16][17];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int jt = bid % p.jtiles, it = bid / p.jtiles;
+  // a block of NW wavefronts works on NW / 4 tiles, four wavefronts each
+  constexpr int GROUPS = NW / 4;
+  __shared__ float red[GROUPS][4][16][17];
+  __shared__ float sred[GROUPS][2][16][17];
+  const int grp = (threadIdx.x >> 8), wave = (threadIdx.x >> 6) & 3, lane = threadIdx.x & 63;
+  const int tile = bid * GROUPS + grp;
+  const bool tile_ok = tile < p.jtiles * p.itiles;
+  const int jt = tile % p.jtiles, it = tile / p.jtiles;
   const size_t i0 = (size_t)it * 16;
   const int j0 = jt * 16;
   const int R = MODE == MODE_FWD ? p.K : p.N;       // reduction extent (a multiple of G)
@@ -807,7 +811,7 @@ __device__ __forceinline__ void pw_gemm_tiny_body(const GemmArgs& p, const int b
   const int l16 = lane & 15, kg = (lane >> 4) * G;
   const size_t row = i0 + l16;
   const int col = j0 + l16;
-  const bool row_ok = row < p.M, col_ok = col < nj;
+  const bool row_ok = tile_ok && row < p.M, col_ok = tile_ok && col < nj;
   const T* X = reinterpret_cast<const T*>(p.x) + row * (size_t)R;
   const T* W = reinterpret_cast<const T*>(p.y);
   const bool view = MODE == MODE_FWD && p.view.scale != nullptr;
@@ -855,26 +859,27 @@ __device__ __forceinline__ void pw_gemm_tiny_body(const GemmArgs& p, const int b
 
   // register r of lane l is C[4*(l/16) + r][l%16]
 #pragma unroll
-  for (int r = 0; r < 4; ++r) red[wave][4 * (lane >> 4) + r][l16] = acc[r];
+  for (int r = 0; r < 4; ++r) red[grp][wave][4 * (lane >> 4) + r][l16] = acc[r];
   __syncthreads();
-  const int orow = threadIdx.x >> 4, ocol = threadIdx.x & 15;
+  const int orow = (threadIdx.x >> 4) & 15, ocol = threadIdx.x & 15;
   const size_t ig = i0 + orow;
   const int jg = j0 + ocol;
-  const bool in = ig < p.M && jg < nj;
-  float v = red[0][orow][ocol] + red[1][orow][ocol] + red[2][orow][ocol] + red[3][orow][ocol];
+  const bool in = tile_ok && ig < p.M && jg < nj;
+  const float v0 = red[grp][0][orow][ocol] + red[grp][1][orow][ocol] + red[grp][2][orow][ocol] + red[grp][3][orow][ocol];
+  float v = v0;
   if (MODE == MODE_FWD) {
     if (p.bias && jg < nj) v += p.bias[jg];
     if (in) reinterpret_cast<T*>(p.out)[ig * p.N + jg] = from_f32<T>(v);
     if (p.stats) {
       const float sv = in ? round_to<T>(v) : 0.f;     // statistics of the values as stored
-      sred[0][orow][ocol] = sv;
-      sred[1][orow][ocol] = sv * sv;
+      sred[grp][0][orow][ocol] = sv;
+      sred[grp][1][orow][ocol] = sv * sv;
       __syncthreads();
-      if (threadIdx.x < 32) {
-        const int sq = threadIdx.x >> 4, c = threadIdx.x & 15;
+      if ((threadIdx.x & 255) < 32 && tile_ok) {
+        const int sq = (threadIdx.x >> 4) & 1, c = threadIdx.x & 15;
         float tot = 0.f;
 #pragma unroll
-        for (int rr = 0; rr < 16; ++rr) tot += sred[sq][rr][c];
+        for (int rr = 0; rr < 16; ++rr) tot += sred[grp][sq][rr][c];
         if (j0 + c < p.N) p.stats[((size_t)it * 2 + sq) * p.N + j0 + c] = tot;
       }
     }
@@ -891,10 +896,10 @@ __device__ __forceinline__ void pw_gemm_tiny_body(const GemmArgs& p, const int b
 // buffers and no second kernel.  A lane's two MFMA operands are single elements of consecutive columns
 // (64-byte runs), the per-column scale/shift of the view sit in two registers.  Both storage types use
 // the fp32 16x16x4 MFMA: products of bfloat16 values are exact in fp32.
-template <typename T>
+template <typename T, int NW>
 __device__ __forceinline__ void pw_wgrad_tiny_body(const GemmArgs& p, const int K_out, const int bid) {
   constexpr int U = 8;
-  __shared__ float red[4][16][17];
+  __shared__ float red[NW][16][17];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int jt = bid % p.jtiles, it = bid / p.jtiles;
   const int l16 = lane & 15, mg = lane >> 4;
@@ -906,7 +911,7 @@ __device__ __forceinline__ void pw_wgrad_tiny_body(const GemmArgs& p, const int 
   const float sc = view && k_ok ? p.view.scale[k] : 1.f, sh = view && k_ok ? p.view.shift[k] : 0.f;
   const float lo = act_lo(p.view.act), hi = act_hi(p.view.act);
   const size_t M = p.M;
-  const size_t per = ((M + 15) / 16) * 4;                  // pixels per wavefront, a multiple of 4
+  const size_t per = ((M + 4 * NW - 1) / (4 * NW)) * 4;    // pixels per wavefront, a multiple of 4
   const size_t mb = (size_t)wave * per, me = mb + per < M ? mb + per : M;
   f4v acc = {0.f, 0.f, 0.f, 0.f};
   for (size_t m0 = mb; m0 < me; m0 += 4 * U) {
@@ -932,25 +937,28 @@ __device__ __forceinline__ void pw_wgrad_tiny_body(const GemmArgs& p, const int 
 #pragma unroll
   for (int r = 0; r < 4; ++r) red[wave][4 * mg + r][l16] = acc[r];
   __syncthreads();
-  const int orow = threadIdx.x >> 4, ocol = threadIdx.x & 15;
+  const int orow = (threadIdx.x >> 4) & 15, ocol = threadIdx.x & 15;
   const int on = it * 16 + orow, ok_ = jt * 16 + ocol;
-  if (on < p.N && ok_ < K_out) {
-    const float v = red[0][orow][ocol] + red[1][orow][ocol] + red[2][orow][ocol] + red[3][orow][ocol];
+  if (threadIdx.x < 256 && on < p.N && ok_ < K_out) {
+    float v = 0.f;
+#pragma unroll
+    for (int q = 0; q < NW; ++q) v += red[q][orow][ocol];
     float* dst = reinterpret_cast<float*>(p.out) + (size_t)on * K_out + ok_;
     *dst += v;
   }
 }
 
 template <typename T, int MODE>
-__global__ __launch_bounds__(256) void pw_gemm_tiny_k(GemmArgs p) { pw_gemm_tiny_body<T, MODE>(p, blockIdx.x); }
+__global__ __launch_bounds__(256) void pw_gemm_tiny_k(GemmArgs p) { pw_gemm_tiny_body<T, MODE, 4>(p, blockIdx.x); }
 template <typename T>
-__global__ __launch_bounds__(256) void pw_wgrad_tiny_k(GemmArgs p, int K_out) { pw_wgrad_tiny_body<T>(p, K_out, blockIdx.x); }
+__global__ __launch_bounds__(256) void pw_wgrad_tiny_k(GemmArgs p, int K_out) { pw_wgrad_tiny_body<T, 4>(p, K_out, blockIdx.x); }
 // data gradient and weight gradient of one short layer in one launch: both read the same dZ, their tiles are
-// independent, and for these sizes a launch costs more than either of them
-template <typename T>
-__global__ __launch_bounds__(256) void pw_bwd_tiny_k(GemmArgs pd, GemmArgs pw, int K_out, int n_dgrad) {
-  if ((int)blockIdx.x < n_dgrad) pw_gemm_tiny_body<T, MODE_DGRAD>(pd, blockIdx.x);
-  else pw_wgrad_tiny_body<T>(pw, K_out, blockIdx.x - n_dgrad);
+// independent, and for these sizes a launch costs more than either of them.  NW wavefronts per block: with many
+// pixels the weight-gradient tiles are few and each walks all pixels, so 16 wavefronts share that walk.
+template <typename T, int NW>
+__global__ __launch_bounds__(64 * NW) void pw_bwd_tiny_k(GemmArgs pd, GemmArgs pw, int K_out, int n_dgrad) {
+  if ((int)blockIdx.x < n_dgrad) pw_gemm_tiny_body<T, MODE_DGRAD, NW>(pd, blockIdx.x);
+  else pw_wgrad_tiny_body<T, NW>(pw, K_out, blockIdx.x - n_dgrad);
 }
 
 // the 16 x 16 kernel serves problems whose output is short (few rows) and whose reduction extent
@@ -1107,8 +1115,14 @@ void pw_bwd(int dt, hipStream_t st, const void* dz, const void* w, const void* r
     const double es = dt == 0 ? 4.0 : 2.0;
     KScope ks(st, "pw_bwd", ((double)M * K * (res ? 3.0 : 2.0) + (double)M * N + (double)N * K) * es + (double)N * K * 8,
               4.0 * M * K * N, (long)M, K, N);
-    if (dt == 0) hipLaunchKernelGGL(pw_bwd_tiny_k<float>, dim3(nd + nw), dim3(256), 0, st, d, g, K, nd);
-    else hipLaunchKernelGGL(pw_bwd_tiny_k<bf16_t>, dim3(nd + nw), dim3(256), 0, st, d, g, K, nd);
+    if (M > 512) {
+      const int nd4 = (nd + 3) / 4;             // four data-gradient tiles per 16-wavefront block
+      if (dt == 0) hipLaunchKernelGGL((pw_bwd_tiny_k<float, 16>), dim3(nd4 + nw), dim3(1024), 0, st, d, g, K, nd4);
+      else hipLaunchKernelGGL((pw_bwd_tiny_k<bf16_t, 16>), dim3(nd4 + nw), dim3(1024), 0, st, d, g, K, nd4);
+    } else {
+      if (dt == 0) hipLaunchKernelGGL((pw_bwd_tiny_k<float, 4>), dim3(nd + nw), dim3(256), 0, st, d, g, K, nd);
+      else hipLaunchKernelGGL((pw_bwd_tiny_k<bf16_t, 4>), dim3(nd + nw), dim3(256), 0, st, d, g, K, nd);
+    }
     return;
   }
   pw_wgrad(dt, st, dz, av, M, K, N, ws, g_w);
