@@ -229,7 +229,7 @@ void bn_bwd_reduce(int dt, hipStream_t st, const void* dA, const void* z, size_t
                    const float* scale, const float* shift, int act, float* partial, int* P_out) {
   RowTile t = make_rowtile(M, C, kBnPartials);
   {
-    KScope ks(st, "bn_bwd_reduce", 2.0 * M * C * (dt == 0 ? 4.0 : 2.0), 6.0 * M * C);
+    KScope ks(st, "bn_bwd_reduce", 2.0 * M * C * (dt == 0 ? 4.0 : 2.0), 6.0 * M * C, (long)M, C, act);
     dim3 grid(t.P, t.nslab), block(t.W * t.R);
     size_t sm = (size_t)16 * t.R * t.W * sizeof(float);
     FTP_DISPATCH_ACT(dt, act, hipLaunchKernelGGL((bn_bwd_reduce_k<T, ACT>), grid, block, sm, st, (const T*)dA, (const T*)z, M,
@@ -315,7 +315,7 @@ static inline int flat_grid(size_t n, int block) {
 
 void bn_bwd_apply(int dt, hipStream_t st, const void* dA, const void* z, size_t M, int C,
                   const float* scale, const float* shift, int act, const float* coef, void* dz) {
-  KScope ks(st, "bn_bwd_apply", 3.0 * M * C * (dt == 0 ? 4.0 : 2.0), 6.0 * M * C);
+  KScope ks(st, "bn_bwd_apply", 3.0 * M * C * (dt == 0 ? 4.0 : 2.0), 6.0 * M * C, (long)M, C, act);
   RowTile t = make_rowtile(M, C, 1 << 14);       // no partials here: many short blocks
   dim3 grid(t.P, t.nslab), block(t.W * t.R);
   FTP_DISPATCH_ACT(dt, act, hipLaunchKernelGGL((bn_bwd_apply_k<T, ACT>), grid, block, 0, st, (const T*)dA, (const T*)z, M, C,

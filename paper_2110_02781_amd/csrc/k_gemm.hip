@@ -1009,7 +1009,7 @@ static void plan_rows(size_t M, int ncols, int R, GemmArgs* a, bool* small) {
   *small = big_tiles * a->jtiles < 96 && R >= 128;
   int TI = *small ? 32 : 128;
   a->itiles = (int)((M + TI - 1) / TI);
-  int want = (2048 + a->jtiles - 1) / a->jtiles;          // about 2048 blocks in flight
+  int want = (4096 + a->jtiles - 1) / a->jtiles;          // about 4096 blocks in flight
   if (want > kMaxPartials) want = kMaxPartials;
   if (want < 1) want = 1;
   a->tiles_per_range = (a->itiles + want - 1) / want;
@@ -1055,7 +1055,7 @@ static void plan_wgrad(size_t M, int K, int N, GemmArgs* a, bool* small) {
   int CH = *small ? 128 : 32;
   a->itiles = (N + TI - 1) / TI;
   size_t tiles = (size_t)a->itiles * a->jtiles;
-  size_t s = (1024 + tiles - 1) / tiles;
+  size_t s = (512 + tiles - 1) / tiles;
   size_t smax = (M + 2 * CH - 1) / (2 * CH);      // at least two reduction chunks per split
   if (s > smax) s = smax;
   if (s > (size_t)kMaxPartials) s = kMaxPartials;

@@ -61,7 +61,7 @@ RowTile make_rowtile(size_t M, int C, int max_partials);
 enum { kMaxPartials = 512 };
 // row-streaming BatchNorm reductions: more, shorter blocks (occupancy); each block covers >= kBnMinRows rows so
 // the partials stay small next to the tensor
-enum { kBnPartials = 2048, kBnMinRows = 32 };
+enum { kBnPartials = 512, kBnMinRows = 32 };
 
 // ---- BatchNorm ---------------------------------------------------------------
 // partial[P][2][C] <- per-chunk sums of z and z*z
