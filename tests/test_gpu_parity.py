@@ -126,6 +126,47 @@ def test_small_net_ragged_shapes(dtype):
     unitwise_check(o, h, (9, 11, 3), 5, 0, len(o), dtype, 2, x, labels=synth.labels(2, "labels0", 5, 10))
 
 
+def test_degenerate_tail_only_stage():
+    """A stage that holds no convolution at all: [GAP, FC, loss] on a 2x2x32 boundary tensor."""
+    print("tail-only stage: gap + fc + loss, batch 7", flush=True)
+    o, h = small_net()
+    a, b = len(o) - 3, len(o)
+    pair = Pair(o, h, (9, 11, 3), 7, a, b, "f32", seed=13)
+    try:
+        x = synth.normal(13, "x", (7,) + tuple(pair.in_shape))
+        labels = synth.labels(13, "labels", 7, 10)
+        y, yo = pair.forward(0, x)
+        assert_close(y, yo, TOL["f32"], "logits")
+        lh, lo = pair.loss(0, labels)
+        assert abs(lh - lo) <= TOL["f32"] * max(1.0, abs(lo))
+        dx, dxo = pair.backward(0, None, want_dx=True)
+        assert_close(dx, dxo, TOL["f32"], "dx")
+        pair.compare_unit_vectors("grads", TOL["f32"], floor=1e-7)
+        pair.update(0.01, 0.9, 0.0)
+        pair.compare_unit_vectors("weights", TOL["f32"])
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_degenerate_tiny_feature_maps(dtype):
+    """Batch 3 on a 12x10 input: the last blocks see 3x3 and 2x2 feature maps, BatchNorm over 27 and 12 values.
+    (Over 2-3 values the input gradient of BatchNorm cancels to rounding noise: fp32 against the float64 oracle
+    then differs by more than 1e-4 relative without either being wrong, so that case is not compared.)"""
+    print(f"small net 12x10 batch 3 {dtype}", flush=True)
+    us = [conv_unit(3, 8, 3, 3, 2, 1, 1, L.ACT_RELU6), invres_unit(8, 16, 2, 6), invres_unit(16, 16, 1, 6),
+          invres_unit(16, 24, 2, 6)]
+    import paper_2110_02781_amd.binding as B
+    o = [u[0] for u in us] + [OM.Unit('gap', 24, 24), OM.Unit('fc', 24, 10), OM.Unit('loss', 10, 10)]
+    h = [u[1] for u in us] + [dict(kind=B.UNIT_GAP, cin=24, cout=24), dict(kind=B.UNIT_FC, cin=24, cout=10),
+                              dict(kind=B.UNIT_LOSS, cin=10, cout=10)]
+    x = synth.normal(14, "x0", (3, 12, 10, 3))
+    if dtype == "bf16":
+        from oracle.stage import bf16_round
+        x = bf16_round(x)
+    unitwise_check(o, h, (12, 10, 3), 3, 0, len(o), dtype, 14, x, labels=synth.labels(14, "labels0", 3, 10))
+
+
 # ---------------------------------------------------------------------- config 2
 def test_config2_mobilenetv2_32_train_step():
     print("config 2: MobileNetV2 w1.0 32x32 batch 32 fp32", flush=True)
