@@ -227,6 +227,39 @@ void conv_direct_wgrad(int dt, hipStream_t st, const void* dz, HView in, const C
   pw_wgrad(dt, st, dz, HView{im2col, nullptr, nullptr, 0}, M, Kpad, g.Cout, ws, g_w, K);
 }
 
+// Forward of a small dense convolution over many pixels (the 224x224 stem) as im2col + MFMA GEMM: the patch
+// matrix costs one extra write and read of M x Kpad elements but the GEMM streams at several TB/s and leaves the
+// BatchNorm statistics in its epilogue, where the direct kernel issues Cin*kh*kw scalar loads per output vector.
+template <typename T>
+__global__ void pad_rows_k(const T* __restrict__ w, int rows, int K, int Kpad, T* __restrict__ out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows * Kpad) return;
+  const int r = i / Kpad, k = i - r * Kpad;
+  out[i] = k < K ? w[(size_t)r * K + k] : from_f32<T>(0.f);
+}
+
+int conv_direct_gemm_ok(const ConvGeom& g) {
+  return (size_t)g.N * g.Hout * g.Wout >= ((size_t)1 << 18) && direct_kpad(g) <= 64 && g.Cout % 8 == 0;
+}
+size_t conv_direct_gemm_wpad_elems(const ConvGeom& g) { return (size_t)g.Cout * direct_kpad(g); }
+
+void conv_direct_fwd_gemm(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* im2col, void* wpad, void* z,
+                          float* stats, int* P_out) {
+  const int Kpad = direct_kpad(g), K = g.kh * g.kw * g.Cin;
+  const size_t M = (size_t)g.N * g.Hout * g.Wout;
+  View v{in.z, in.scale, in.shift, in.act};
+  {
+    const double es = dt == 0 ? 4.0 : 2.0;
+    KScope ks(st, "im2col", ((double)g.N * g.Hin * g.Win * g.Cin + (double)M * Kpad) * es, 0, (long)M, Kpad, g.Cout);
+    size_t nvec = M * (Kpad / 8);
+    unsigned grid = (unsigned)((nvec + 255) / 256 > 65536 ? 65536 : (nvec + 255) / 256);
+    FTP_DISPATCH(dt, hipLaunchKernelGGL(im2col_k<T>, dim3(grid), dim3(256), 0, st, v, g, Kpad, (T*)im2col));
+    FTP_DISPATCH(dt, hipLaunchKernelGGL(pad_rows_k<T>, dim3((g.Cout * Kpad + 255) / 256), dim3(256), 0, st, (const T*)w, g.Cout, K,
+                                        Kpad, (T*)wpad));
+  }
+  pw_fwd(dt, st, HView{im2col, nullptr, nullptr, 0}, wpad, nullptr, M, Kpad, g.Cout, z, stats, P_out);
+}
+
 // ================================================================ depthwise 3x3
 // A block owns a slab of CGB*8 channels (128 bytes of every pixel) of one spatial tile.  The input
 // patch with its one-pixel halo is staged in LDS once as floats, already passed through the
@@ -243,12 +276,12 @@ struct DwPlan {
   int tiles_h, tiles_w, ntiles, nblocks;
   unsigned m_cgb, m_qb, m_pw, m_segw;   // reciprocals for dw_div (divisors < 64, dividends < 1024)
 };
-enum { kDwFillNV = 6 };
+enum { kDwFillNV = 6 };     // passes the patch staging is unrolled for
 
 // x / d for x < 1024, d < 64 with m = 65536 / d + 1: two full-rate instructions instead of the
 // ~25-instruction integer division sequence (thread-index decoding was a third of the kernel's VALU work)
 static unsigned dw_magic(int d) { return 65536u / (unsigned)d + 1u; }
-__device__ __forceinline__ int dw_div(int x, unsigned m) { return (int)(__umul24((unsigned)x, m) >> 16); }     // passes the patch staging is unrolled for
+__device__ __forceinline__ int dw_div(int x, unsigned m) { return (int)(__umul24((unsigned)x, m) >> 16); }
 
 static DwPlan dw_plan(int C, int es, bool half_rows, int out_h, int out_w, int max_blocks) {
   DwPlan d;

@@ -110,6 +110,12 @@ void f32_to_storage(int dt, hipStream_t st, const float* src, void* dst, size_t 
 // ---- generic small dense convolution (stem 3x3, conv1d) ---------------------------
 int conv_direct_supported(const ConvGeom& g);
 void conv_direct_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z);
+// many pixels, few taps: im2col + GEMM with the BatchNorm statistics in its epilogue (conv_direct_gemm_ok);
+// im2col: conv_direct_im2col_elems(g) elements, wpad: conv_direct_gemm_wpad_elems(g) elements of scratch
+int conv_direct_gemm_ok(const ConvGeom& g);
+size_t conv_direct_gemm_wpad_elems(const ConvGeom& g);
+void conv_direct_fwd_gemm(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* im2col, void* wpad, void* z,
+                          float* stats, int* P_out);
 void conv_direct_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvGeom& g, void* dIn);
 // g_w[Cout][kh][kw][Cin] += dW; im2col: scratch of conv_direct_im2col_elems(g) activation elements
 size_t conv_direct_wgrad_ws(const ConvGeom& g);  // floats of workspace needed

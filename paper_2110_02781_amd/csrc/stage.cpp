@@ -531,6 +531,10 @@ static void sub_forward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, HVi
       *pend = BnPending{s->bn_part, P, M, gamma, beta, stt, stt + C, stt + 2 * C, stt + 3 * C, rm, rv};
       return;
     }
+  } else if (sb.type == SUB_DIRECT && conv_direct_gemm_ok(g) && s->im2col &&
+             conv_direct_gemm_wpad_elems(g) * s->es <= s->ws_floats * sizeof(float)) {
+    // the float workspace is free during a forward: the padded weight copy lives there
+    conv_direct_fwd_gemm(s->dt, st, in, w, g, s->im2col, s->ws, z, s->bn_part, &P);
   } else {
     if (sb.type == SUB_DW) dw_fwd(s->dt, st, in, w, g, z);
     else conv_direct_fwd(s->dt, st, in, w, g, z);
