@@ -117,6 +117,25 @@ __device__ __forceinline__ void view_load8(const View& v, size_t idx, int c, flo
   }
 }
 
+// four consecutive channels as a float4
+__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ float4 load4(const bf16_t* p) {
+  const uint2 u = *reinterpret_cast<const uint2*>(p);
+  return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u), __uint_as_float(u.y << 16),
+                     __uint_as_float(u.y & 0xffff0000u));
+}
+__device__ __forceinline__ void store4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ void store4(bf16_t* p, float4 v) {
+  uint2 u;
+  u.x = f32x2_to_bf16x2(v.x, v.y);
+  u.y = f32x2_to_bf16x2(v.z, v.w);
+  *reinterpret_cast<uint2*>(p) = u;
+}
+__device__ __forceinline__ float4 fma4(float4 a, float4 b, float4 c) {
+  return make_float4(fmaf(a.x, b.x, c.x), fmaf(a.y, b.y, c.y), fmaf(a.z, b.z, c.z), fmaf(a.w, b.w, c.w));
+}
+
 // Sum over the 64 lanes of a wavefront without touching LDS: butterflies inside each row of 16 lanes
 // with data-parallel-primitive moves (VALU rate; cross-lane permutes through LDS cost ~20 cycles per
 // instruction), then the four row totals in lane order.  Every lane returns the same value.

@@ -4,6 +4,7 @@
 // act(bn(0))).
 #include "dev_common.h"
 #include "kernels.h"
+#include "bn_pending.h"
 
 namespace ftp {
 
@@ -304,24 +305,6 @@ static DwPlan dw_plan(int C, int es, bool half_rows, int out_h, int out_w, int m
   return d;
 }
 
-__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
-__device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
-__device__ __forceinline__ float4 load4(const bf16_t* p) {
-  const uint2 u = *reinterpret_cast<const uint2*>(p);
-  return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u), __uint_as_float(u.y << 16),
-                     __uint_as_float(u.y & 0xffff0000u));
-}
-__device__ __forceinline__ void store4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
-__device__ __forceinline__ void store4(bf16_t* p, float4 v) {
-  uint2 u;
-  u.x = f32x2_to_bf16x2(v.x, v.y);
-  u.y = f32x2_to_bf16x2(v.z, v.w);
-  *reinterpret_cast<uint2*>(p) = u;
-}
-__device__ __forceinline__ float4 fma4(float4 a, float4 b, float4 c) {
-  return make_float4(fmaf(a.x, b.x, c.x), fmaf(a.y, b.y, c.y), fmaf(a.z, b.z, c.z), fmaf(a.w, b.w, c.w));
-}
-
 // Patch rows h0 .. h0+PH-1, cols w0 .. w0+PW-1 of image n (H x W x C), column groups cg0 .. cg0+CGB-1,
 // into LDS as float [PH][PW][CGB][8].  Thread = (pixel lane, column group); fetch() issues all global
 // loads, commit() applies the view and writes LDS, so a caller can keep the loads of the next tile
@@ -484,40 +467,6 @@ __device__ __forceinline__ float4 view4(float4 v, const float* sc, const float* 
 }
 template <typename T> __device__ __forceinline__ float4 round4(float4 v) {
   return make_float4(round_to<T>(v.x), round_to<T>(v.y), round_to<T>(v.z), round_to<T>(v.w));
-}
-
-// finish pending BatchNorm statistics for channels c0..c0+3 (first 256 threads), result in insc[2][4]
-__device__ __forceinline__ void finish_pending4(const BnPending& pend, int C, int c0, float eps, float momentum, double (*pre)[8],
-                                                float (*insc)[4]) {
-  const int tid = threadIdx.x;
-  if (tid < 256) {
-    const int v = tid & 7, lane = tid >> 3;           // 4 sums, 4 second sums; 32 lanes each
-    double t = 0.0;
-    for (int q = lane; q < pend.P; q += 32) t += (double)pend.partial[((size_t)q * 2 + (v >> 2)) * C + c0 + (v & 3)];
-    pre[lane][v] = t;
-  }
-  __syncthreads();
-  if (tid < 4) {
-    const int c = c0 + tid;
-    double s0 = 0.0, s1 = 0.0;
-    for (int l = 0; l < 32; ++l) { s0 += pre[l][tid]; s1 += pre[l][4 + tid]; }
-    const double Md = (double)pend.M, mu = s0 / Md;
-    double var = s1 / Md - mu * mu;
-    if (var < 0.0) var = 0.0;
-    const double is = 1.0 / sqrt(var + (double)eps);
-    const float scv = (float)((double)pend.gamma[c] * is);
-    const float shv = (float)((double)pend.beta[c] - mu * (double)scv);
-    pend.mean[c] = (float)mu;
-    pend.invstd[c] = (float)is;
-    pend.scale[c] = scv;
-    pend.shift[c] = shv;
-    const double unb = pend.M > 1 ? var * (Md / (Md - 1.0)) : var;
-    pend.run_mean[c] = (float)((1.0 - momentum) * pend.run_mean[c] + momentum * mu);
-    pend.run_var[c] = (float)((1.0 - momentum) * pend.run_var[c] + momentum * unb);
-    insc[0][tid] = scv;
-    insc[1][tid] = shv;
-  }
-  __syncthreads();
 }
 
 // Depthwise convolution + BatchNorm statistics + their finalisation (and, when the producer left them pending,

@@ -6,6 +6,7 @@
 // across blocks), so results are run-to-run deterministic.
 #include "dev_common.h"
 #include "kernels.h"
+#include "bn_pending.h"
 
 namespace ftp {
 
@@ -322,63 +323,63 @@ void bn_bwd_apply(int dt, hipStream_t st, const void* dA, const void* z, size_t 
                                                scale, shift, coef, t.W, t.R, t.rows_per_block, (T*)dz));
 }
 
-// BatchNorm backward for short tensors in ONE launch: a block owns 8 channels over all M rows, so it
+// BatchNorm backward for short tensors in ONE launch: a block owns 4 channels over all M rows, so it
 // can reduce, finalize and apply without any other block (the three-kernel path needs two grid-wide
 // dependencies, i.e. two extra launches, which dominate when the tensor is a few hundred KB).
-// Second pass re-reads dA and z from L2.
+// Every thread keeps its rows in registers: one trip to memory, then reduce, then apply.
 template <typename T, int RPT>
 __global__ __launch_bounds__(1024) void bn_bwd_small_k(const T* __restrict__ dA, const T* __restrict__ z, size_t M, int C,
                                                        const float* __restrict__ scale, const float* __restrict__ shift, int act,
                                                        const float* __restrict__ gamma, const float* __restrict__ mean,
                                                        const float* __restrict__ invstd, float* g_gamma, float* g_beta,
                                                        T* __restrict__ dz) {
-  __shared__ float red[16][16];   // [wave][value]
-  __shared__ float coef[3][8];
-  const int c0 = blockIdx.x * 8, tid = threadIdx.x, nt = blockDim.x;   // RPT * nt >= M
-  // every thread keeps its rows in registers: one trip to memory, then reduce, then apply
-  float d[RPT][8], v[RPT][8];
+  __shared__ float red[16][8];    // [wave][value]
+  __shared__ float coef[3][4];
+  const int c0 = blockIdx.x * 4, tid = threadIdx.x, nt = blockDim.x;   // RPT * nt >= M
+  float4 d[RPT], v[RPT];
 #pragma unroll
   for (int q = 0; q < RPT; ++q) {
     const size_t m = tid + (size_t)q * nt;
     if (m < M) {
-      load8(dA + m * C + c0, d[q]);
-      load8(z + m * C + c0, v[q]);
+      d[q] = load4(dA + m * C + c0);
+      v[q] = load4(z + m * C + c0);
     } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { d[q][e] = 0.f; v[q][e] = 0.f; }
+      d[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      v[q] = d[q];
     }
   }
-  float sc[8], sh[8];
-  load8(scale + c0, sc);
-  load8(shift + c0, sh);
-  const float lo = act_lo(act), hi = act_hi(act);
-  float acc[16];
+  float sc[4], sh[4];
 #pragma unroll
-  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  for (int e = 0; e < 4; ++e) { sc[e] = scale[c0 + e]; sh[e] = shift[c0 + e]; }
+  const float lo = act_lo(act), hi = act_hi(act);
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
   for (int q = 0; q < RPT; ++q) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float y = fmaf(v[q][e], sc[e], sh[e]);
-      float dy = (y > lo && y < hi) ? d[q][e] : 0.f;   // rows past M hold zeros
-      d[q][e] = dy;
-      acc[e] += dy;
-      acc[8 + e] = fmaf(dy, v[q][e], acc[8 + e]);
-    }
+    const float y0 = fmaf(v[q].x, sc[0], sh[0]), y1 = fmaf(v[q].y, sc[1], sh[1]), y2 = fmaf(v[q].z, sc[2], sh[2]),
+                y3 = fmaf(v[q].w, sc[3], sh[3]);
+    float4 dy;                              // rows past M hold zeros
+    dy.x = (y0 > lo && y0 < hi) ? d[q].x : 0.f;
+    dy.y = (y1 > lo && y1 < hi) ? d[q].y : 0.f;
+    dy.z = (y2 > lo && y2 < hi) ? d[q].z : 0.f;
+    dy.w = (y3 > lo && y3 < hi) ? d[q].w : 0.f;
+    d[q] = dy;
+    acc[0] += dy.x; acc[1] += dy.y; acc[2] += dy.z; acc[3] += dy.w;
+    acc[4] = fmaf(dy.x, v[q].x, acc[4]); acc[5] = fmaf(dy.y, v[q].y, acc[5]);
+    acc[6] = fmaf(dy.z, v[q].z, acc[6]); acc[7] = fmaf(dy.w, v[q].w, acc[7]);
   }
   // fixed-shape reduction: inside each wave, then the waves in order
 #pragma unroll
-  for (int e = 0; e < 16; ++e) acc[e] = wave_sum(acc[e]);
+  for (int e = 0; e < 8; ++e) acc[e] = wave_sum(acc[e]);
   const int wave = tid >> 6, nw = nt >> 6;
   if ((tid & 63) == 0) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) red[wave][e] = acc[e];
+    for (int e = 0; e < 8; ++e) red[wave][e] = acc[e];
   }
   __syncthreads();
-  if (tid < 8) {
+  if (tid < 4) {
     const int c = c0 + tid;
     double s0 = 0.0, s1 = 0.0;
-    for (int w = 0; w < nw; ++w) { s0 += red[w][tid]; s1 += red[w][8 + tid]; }
+    for (int w = 0; w < nw; ++w) { s0 += red[w][tid]; s1 += red[w][4 + tid]; }
     const double mu = mean[c], is = invstd[c], g = gamma[c], Md = (double)M;
     const double dbeta = s0, dgamma = is * (s1 - mu * s0);
     g_gamma[c] += (float)dgamma;
@@ -387,21 +388,18 @@ __global__ __launch_bounds__(1024) void bn_bwd_small_k(const T* __restrict__ dA,
     coef[0][tid] = (float)k1; coef[1][tid] = (float)k2; coef[2][tid] = (float)k3;
   }
   __syncthreads();
-  float k1[8], k2[8], k3[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) { k1[e] = coef[0][e]; k2[e] = coef[1][e]; k3[e] = coef[2][e]; }
+  const float4 k1 = make_float4(coef[0][0], coef[0][1], coef[0][2], coef[0][3]);
+  const float4 k2 = make_float4(coef[1][0], coef[1][1], coef[1][2], coef[1][3]);
+  const float4 k3 = make_float4(coef[2][0], coef[2][1], coef[2][2], coef[2][3]);
 #pragma unroll
   for (int q = 0; q < RPT; ++q) {
     const size_t m = tid + (size_t)q * nt;
     if (m >= M) continue;
-    float o[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = fmaf(k1[e], d[q][e], fmaf(k2[e], v[q][e], k3[e]));
-    store8(dz + m * C + c0, o);
+    store4(dz + m * C + c0, fma4(k1, d[q], fma4(k2, v[q], k3)));
   }
 }
 
-int bn_bwd_small_ok(size_t M, int C) { return M <= 2048 && C >= 32; }
+int bn_bwd_small_ok(size_t M, int C) { return M <= 2048 && C >= 16 && C % 4 == 0; }
 
 void bn_bwd_small(int dt, hipStream_t st, const void* dA, const void* z, size_t M, int C, const float* scale,
                   const float* shift, int act, const float* gamma, const float* mean, const float* invstd,
@@ -409,10 +407,10 @@ void bn_bwd_small(int dt, hipStream_t st, const void* dA, const void* z, size_t 
   KScope ks(st, "bn_bwd_small", 3.0 * M * C * (dt == 0 ? 4.0 : 2.0), 12.0 * M * C, (long)M, C);
   const int nt = M > 512 ? 1024 : (M > 256 ? 512 : 256);
   if (M > 1024) {
-    FTP_DISPATCH(dt, hipLaunchKernelGGL((bn_bwd_small_k<T, 2>), dim3(C / 8), dim3(nt), 0, st, (const T*)dA, (const T*)z, M, C, scale,
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((bn_bwd_small_k<T, 2>), dim3(C / 4), dim3(nt), 0, st, (const T*)dA, (const T*)z, M, C, scale,
                                         shift, act, gamma, mean, invstd, g_gamma, g_beta, (T*)dz));
   } else {
-    FTP_DISPATCH(dt, hipLaunchKernelGGL((bn_bwd_small_k<T, 1>), dim3(C / 8), dim3(nt), 0, st, (const T*)dA, (const T*)z, M, C, scale,
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((bn_bwd_small_k<T, 1>), dim3(C / 4), dim3(nt), 0, st, (const T*)dA, (const T*)z, M, C, scale,
                                         shift, act, gamma, mean, invstd, g_gamma, g_beta, (T*)dz));
   }
 }
@@ -442,68 +440,40 @@ void bn_apply(int dt, hipStream_t st, HView in, size_t M, int C, const void* res
 }
 
 // Finish a BatchNorm whose statistics are still partial sums and materialise its output (+ residual) in ONE
-// launch, for short tensors: a block owns 8 channels over all rows.
+// launch, for short tensors: a block owns 4 channels over all rows.
 template <typename T>
 __global__ __launch_bounds__(1024) void bn_finalize_apply_small_k(BnPending pend, const T* __restrict__ z, size_t M, int C, int act,
                                                                   float eps, float momentum, const T* __restrict__ res,
                                                                   T* __restrict__ out) {
-  __shared__ double pre[16][16];
-  __shared__ float insc[2][8];
-  const int c0 = blockIdx.x * 8, tid = threadIdx.x, nt = blockDim.x;
-  if (tid < 256) {
-    const int v = tid & 15, lane = tid >> 4;
-    double t = 0.0;
-    for (int q = lane; q < pend.P; q += 16) t += (double)pend.partial[((size_t)q * 2 + (v >> 3)) * C + c0 + (v & 7)];
-    pre[lane][v] = t;
-  }
-  __syncthreads();
-  if (tid < 8) {
-    const int c = c0 + tid;
-    double s0 = 0.0, s1 = 0.0;
-    for (int l = 0; l < 16; ++l) { s0 += pre[l][tid]; s1 += pre[l][8 + tid]; }
-    const double Md = (double)pend.M, mu = s0 / Md;
-    double var = s1 / Md - mu * mu;
-    if (var < 0.0) var = 0.0;
-    const double is = 1.0 / sqrt(var + (double)eps);
-    const float scv = (float)((double)pend.gamma[c] * is);
-    const float shv = (float)((double)pend.beta[c] - mu * (double)scv);
-    pend.mean[c] = (float)mu;
-    pend.invstd[c] = (float)is;
-    pend.scale[c] = scv;
-    pend.shift[c] = shv;
-    const double unb = pend.M > 1 ? var * (Md / (Md - 1.0)) : var;
-    pend.run_mean[c] = (float)((1.0 - momentum) * pend.run_mean[c] + momentum * mu);
-    pend.run_var[c] = (float)((1.0 - momentum) * pend.run_var[c] + momentum * unb);
-    insc[0][tid] = scv;
-    insc[1][tid] = shv;
-  }
-  __syncthreads();
-  float sc[8], sh[8];
+  __shared__ double pre[32][8];
+  __shared__ float insc[2][4];
+  const int c0 = blockIdx.x * 4, tid = threadIdx.x, nt = blockDim.x;
+  finish_pending4(pend, C, c0, eps, momentum, pre, insc);
+  float sc[4], sh[4];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) { sc[e] = insc[0][e]; sh[e] = insc[1][e]; }
+  for (int e = 0; e < 4; ++e) { sc[e] = insc[0][e]; sh[e] = insc[1][e]; }
   const float lo = act_lo(act), hi = act_hi(act);
   for (size_t m = tid; m < M; m += nt) {
-    float v[8];
-    load8(z + m * C + c0, v);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = round_to<T>(clamp_act(fmaf(v[e], sc[e], sh[e]), lo, hi));
+    float4 v = load4(z + m * C + c0);
+    v.x = round_to<T>(clamp_act(fmaf(v.x, sc[0], sh[0]), lo, hi));
+    v.y = round_to<T>(clamp_act(fmaf(v.y, sc[1], sh[1]), lo, hi));
+    v.z = round_to<T>(clamp_act(fmaf(v.z, sc[2], sh[2]), lo, hi));
+    v.w = round_to<T>(clamp_act(fmaf(v.w, sc[3], sh[3]), lo, hi));
     if (res) {
-      float r[8];
-      load8(res + m * C + c0, r);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] += r[e];
+      const float4 r = load4(res + m * C + c0);
+      v.x += r.x; v.y += r.y; v.z += r.z; v.w += r.w;
     }
-    store8(out + m * C + c0, v);
+    store4(out + m * C + c0, v);
   }
 }
 
-int bn_finalize_apply_small_ok(size_t M, int C) { return M <= 2048 && C % 8 == 0; }
+int bn_finalize_apply_small_ok(size_t M, int C) { return M <= 2048 && C % 4 == 0; }
 
 void bn_finalize_apply_small(int dt, hipStream_t st, const BnPending& pend, const void* z, size_t M, int C, int act, float eps,
                              float momentum, const void* res, void* out) {
   KScope ks(st, "bn_fin_apply_small", (res ? 3.0 : 2.0) * M * C * (dt == 0 ? 4.0 : 2.0) + (double)pend.P * 2 * C * 4, 3.0 * M * C);
   const int nt = M > 512 ? 1024 : (M > 256 ? 512 : 256);
-  FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_finalize_apply_small_k<T>, dim3(C / 8), dim3(nt), 0, st, pend, (const T*)z, M, C, act, eps,
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(bn_finalize_apply_small_k<T>, dim3(C / 4), dim3(nt), 0, st, pend, (const T*)z, M, C, act, eps,
                                       momentum, (const T*)res, (T*)out));
 }
 
