@@ -216,12 +216,54 @@ class Stage:
         return d
 
     # ----------------------------------------------------------------- update
+    def aggregate(self, slots):
+        """Weight aggregation (section "Async Pipeline Training"): the live
+        weights become the arithmetic mean of the weight versions stashed in
+        `slots`; momentum and gradients stay as they are."""
+        snaps = [self.slots[s]['params'] for s in slots]
+        assert all(sn is not None for sn in snaps)
+        for i in range(self.a, self.b):
+            for k in range(len(self.params[i])):
+                acc = np.zeros(self.params[i][k].shape, dtype=np.float64)
+                for sn in snaps:
+                    acc = acc + sn[i][k].astype(np.float64)
+                self.params[i][k] = (acc / len(snaps)).astype(self.params[i][k].dtype)
+
     def update(self, lr, momentum, weight_decay):
         for i in range(self.a, self.b):
             for k in range(len(self.params[i])):
                 w, v = L.sgd_momentum(self.params[i][k], self.grads[i][k], self.mom[i][k], lr, momentum, weight_decay)
                 self.params[i][k], self.mom[i][k] = w, v
                 self.grads[i][k] = np.zeros_like(w)
+
+
+def version_trace(stage_index, n_stages, n_batches, aggregate=False):
+    """Weight versions along the one-forward-one-backward order of one stage
+    (section "Async Pipeline Training"): every backward produces the next
+    version, a forward uses the newest one, a backward uses the version its
+    forward used (weight stashing).  With aggregate=True the stage also
+    aggregates: stage i of n has n-i versions in use at once, and after every
+    n-i backwards, right behind the forward that picks up the newest of them,
+    those n-i versions are merged into one new version.
+    Returns [('F'|'B', batch, version_used) | ('A', (versions...), new_version)]."""
+    depth = n_stages - stage_index
+    out, fwd_version, version, n_bwd, pending = [], {}, 0, 0, False
+    for op, b in one_f_one_b_order(stage_index, n_stages, n_batches):
+        if op == 'F':
+            fwd_version[b] = version
+            out.append(('F', b, version))
+            if aggregate and pending:
+                live = sorted(fwd_version[x] for x in fwd_version if x > b - depth)   # versions of the batches in flight
+                version += 1
+                out.append(('A', tuple(live), version))
+                pending = False
+        else:
+            out.append(('B', b, fwd_version[b]))
+            version += 1
+            n_bwd += 1
+            if n_bwd % depth == 0:
+                pending = True
+    return out
 
 
 def one_f_one_b_order(stage_index, n_stages, n_batches):

@@ -286,3 +286,50 @@ def test_tie_breaks_only_act_inside_the_band():
     # a huge band adopts the caller's decisions, which changes the gradient
     adopted, rep, _ = run(lambda y: y <= 0, 1e3)
     assert rep['adopted'] == y.size and np.abs(adopted - base).max() > 1e-3
+
+
+def test_version_trace_with_aggregation_matches_paper_example():
+    """Pin: the version numbers the paper prints for its three-device example, aggregation included."""
+    from oracle.stage import version_trace
+    want = []
+    for line in open(os.path.join(GOLDEN, "onef1b_aggregation.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        f = line.split()
+        if f[0] == 'A':
+            want.append(('A', tuple(int(x) for x in f[1].split(',')), int(f[2])))
+        else:
+            want.append((f[0], int(f[1]), int(f[2])))
+    got = version_trace(0, 3, 9, aggregate=True)
+    assert got[:len(want)] == want
+    # without aggregation the trace is the plain stashing example
+    plain = version_trace(0, 3, 6)
+    assert plain[:10] == [('F', 0, 0), ('F', 1, 0), ('F', 2, 0), ('B', 0, 0), ('F', 3, 1), ('B', 1, 0), ('F', 4, 2),
+                          ('B', 2, 0), ('F', 5, 3), ('B', 3, 1)]
+    # the last stage holds one version at a time: aggregating one version changes nothing but the counter
+    last = version_trace(2, 3, 3, aggregate=True)
+    assert [e for e in last if e[0] == 'A'] == [('A', (1,), 2), ('A', (3,), 4)]
+
+
+def test_aggregate_is_the_mean_of_the_stashed_versions():
+    """Pins: mean of identical versions is that version; mean of two versions is their midpoint; momentum and
+    gradients untouched; a stage whose slots all hold the live weights is unchanged."""
+    units = M.cnn1d()
+    st = Stage(units, (1, 16, 9), 0, len(units), n_slots=3)
+    st.params = M.init_params(units, 7)
+    x = synth.normal(7, "x", (4, 1, 16, 9))
+    labels = synth.labels(7, "l", 4, 6)
+    w0 = [[p.copy() for p in st.params[i]] for i in range(len(units))]
+    st.forward(0, x); st.loss(0, labels)
+    st.forward(1, x)
+    st.aggregate([0, 1])                      # both slots stashed the same version
+    assert all(np.array_equal(p, q) for i in range(len(units)) for p, q in zip(st.params[i], w0[i]))
+    st.backward(0); st.update(0.05, 0.9, 0.0)       # version 1
+    w1 = [[p.copy() for p in st.params[i]] for i in range(len(units))]
+    mom = [[m.copy() for m in st.mom[i]] for i in range(len(units))]
+    st.forward(0, x)                           # slot 0 stashes version 1, slot 1 still version 0
+    st.aggregate([0, 1])
+    for i in range(len(units)):
+        for p, a, b in zip(st.params[i], w0[i], w1[i]):
+            np.testing.assert_allclose(p, (a.astype(np.float64) + b.astype(np.float64)) / 2, rtol=0, atol=1e-7)
+    assert all(np.array_equal(m, n) for i in range(len(units)) for m, n in zip(st.mom[i], mom[i]))
