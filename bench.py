@@ -205,6 +205,52 @@ def run_workload(config, steps, warmup, use_graph, ktrace, calibrate, seed):
     return res
 
 
+def bench_aggregate(config, versions=3, reps=50, seed=2110):
+    """Weight aggregation (mean of `versions` stashed weight versions into the live weights) timed on its own:
+    an HBM-bound pass over (versions + 1) fp32 copies of the parameters (+ the bfloat16 copy)."""
+    import torch
+    import synth
+    import paper_2110_02781_amd as P
+
+    w = WORKLOADS[config]
+    dev = torch.device("cuda:0")
+    tdt = torch.float32 if w["dtype"] == "f32" else torch.bfloat16
+    units = build_units(P, w)
+    H, W_, C = w["in_shape"]
+    batch = min(w["batch"], 8)                      # the pass does not depend on the batch
+    model = P.model_create(units, H, W_, C, P.F32 if w["dtype"] == "f32" else P.BF16)
+    L = P.model_num_units(model)
+    stage = P.stage_create(model, 0, L, batch, versions)
+    params = P.models.init_unit_params(units, seed)
+    n_param = 0
+    for i in range(L):
+        P.stage_import_weights(stage, i, params[i])
+        n_param += len(params[i])
+    x = torch.from_numpy(synth.normal(seed, "x", (batch, H, W_, C)).astype(np.float32)).to(dev).to(tdt)
+    stream = torch.cuda.Stream()
+    sp = stream.cuda_stream
+    for sl in range(versions):
+        P.stage_forward(stage, sl, x, None, sp)
+        P.stage_snapshot_weights(stage, sl, sp)
+    slots = list(range(versions))
+    for _ in range(5):
+        P.stage_aggregate_weights(stage, slots, sp)
+    stream.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(stream):
+        e0.record(stream)
+        for _ in range(reps):
+            P.stage_aggregate_weights(stage, slots, sp)
+        e1.record(stream)
+    stream.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / reps
+    nbytes = n_param * (4.0 * (versions + 1) + (2.0 if w["dtype"] == "bf16" else 0.0))
+    P.stage_destroy(stage)
+    P.model_destroy(model)
+    return dict(workload=w["name"], params=n_param, versions=versions, us_per_call=round(us, 2),
+                alg_GBps=round(nbytes / (us * 1e-6) / 1e9, 1), frac_of_hbm_peak=round(nbytes / (us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -242,6 +288,11 @@ def main():
         r["kernels"] = r["kernels"][:12]
         also.append(r)
 
+    # the widened row: weight aggregation over three stashed versions, on the larger parameter set
+    agg = None
+    if also and not args.no_ktrace:
+        agg = bench_aggregate(also_cfgs[0] if also_cfgs[0] in WORKLOADS else args.config, 3, 50, args.seed)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = oracle_baseline(WORKLOADS[args.config], args.seed)
@@ -254,6 +305,7 @@ def main():
         "config": {"workload": main_res["workload"], "batch": main_res["batch"], "units": main_res["units"],
                    "hip_graph": main_res["hip_graph"], "final_loss": main_res["final_loss"]},
         "roofline": main_res["roofline"], "cpu_baseline": cpu, "kernels": main_res["kernels"], "also": also,
+        "aggregate": agg,
     }
     print(json.dumps(out))
 

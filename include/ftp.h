@@ -148,6 +148,19 @@ int ftp_stage_loss(ftp_stage*, int slot, const int32_t* labels_dev, float* loss_
  * weights current at that time. */
 int ftp_stage_snapshot_weights(ftp_stage*, int slot, void* stream);
 
+/* Weight aggregation (section "Async Pipeline Training": stage i of n has n-i weight
+ * versions in use at once and merges them at an interval that is a multiple of
+ * n-i).  The live weights become the arithmetic mean, element by element in fp32
+ * (summed in the order given, then divided by n), of the versions stashed by
+ * ftp_stage_snapshot_weights() in slots[0..n); the bfloat16 working copy is
+ * re-derived; momentum, gradients and the snapshots themselves are not touched.
+ * `slots` is a host array, 1 <= n <= 8, every listed slot must hold a snapshot
+ * (FTP_ERR_SLOT otherwise), a slot may not be listed twice.  Asynchronous on
+ * `stream`.  When to call it is the caller's schedule: the paper's example merges
+ * the versions of the n-i batches in flight right after the forward that follows
+ * every (n-i)-th backward. */
+int ftp_stage_aggregate_weights(ftp_stage*, const int* slots, int n, void* stream);
+
 /* Backward of the slot's batch.  dy_dev: gradient of the stage output (same
  * shape and type as y), or NULL after ftp_stage_loss.  dx_dev: receives the
  * gradient of the stage input, or NULL (e.g. a == 0).  Weight gradients are

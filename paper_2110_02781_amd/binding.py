@@ -78,6 +78,7 @@ _SIGS = {
     "ftp_stage_forward": (_i, [_vp, _i, _vp, _vp, _vp]),
     "ftp_stage_loss": (_i, [_vp, _i, _vp, _vp, _vp]),
     "ftp_stage_snapshot_weights": (_i, [_vp, _i, _vp]),
+    "ftp_stage_aggregate_weights": (_i, [_vp, C.POINTER(C.c_int), _i, _vp]),
     "ftp_stage_backward": (_i, [_vp, _i, _vp, _vp, _vp]),
     "ftp_stage_update": (_i, [_vp, C.POINTER(Sgd), _vp]),
     "ftp_profile_layers": (_i, [_vp, _i, _i, _dp, C.POINTER(C.c_int64), _vp]),
@@ -222,6 +223,11 @@ def stage_loss(stage, slot, labels_dev, loss_dev, stream=None):
 
 def stage_snapshot_weights(stage, slot, stream=None):
     _chk(lib.ftp_stage_snapshot_weights(stage, slot, _ptr(stream)))
+
+
+def stage_aggregate_weights(stage, slots, stream=None):
+    arr = (C.c_int * len(slots))(*[int(s) for s in slots])
+    _chk(lib.ftp_stage_aggregate_weights(stage, arr, len(slots), _ptr(stream)))
 
 
 def stage_backward(stage, slot, dy_dev=None, dx_dev=None, stream=None):

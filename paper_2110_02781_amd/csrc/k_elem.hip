@@ -614,6 +614,22 @@ void sgd_update(hipStream_t st, float* w, float* g, float* v, void* w_lp, size_t
                      mu, wd);
 }
 
+// w[i] = (src[0][i] + src[1][i] + ... ) / n, summed in the order given; optional bfloat16 copy
+__global__ void aggregate_k(float* __restrict__ w, bf16_t* __restrict__ w_lp, AggSources src, int n, size_t count) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) {
+    float acc = src.p[0][i];
+    for (int j = 1; j < n; ++j) acc += src.p[j][i];
+    acc = acc / (float)n;
+    w[i] = acc;
+    if (w_lp) w_lp[i] = from_f32<bf16_t>(acc);
+  }
+}
+
+void aggregate_weights(hipStream_t st, float* w, void* w_lp, const AggSources& src, int n, size_t count) {
+  KScope ks(st, "aggregate", (double)count * (4.0 * (n + 1) + (w_lp ? 2.0 : 0.0)), (double)count * n);
+  hipLaunchKernelGGL(aggregate_k, dim3(flat_grid(count, 256)), dim3(256), 0, st, w, (bf16_t*)w_lp, src, n, count);
+}
+
 __global__ void fill_zero_k(uint32_t* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
     p[i] = 0u;

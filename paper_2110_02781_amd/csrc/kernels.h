@@ -103,6 +103,9 @@ void bias_grad(int dt, hipStream_t st, const void* d, int B, int Nout, float* g_
 // g += wd*w; v = mu*v+g; w -= lr*v; g = 0; optional working copy w_lp (bfloat16)
 void sgd_update(hipStream_t st, float* w, float* g, float* v, void* w_lp, size_t n, float lr, float mu,
                 float wd);
+// weight aggregation: w = mean of up to 8 stashed versions (fp32, summed in order), optional bfloat16 copy
+struct AggSources { const float* p[8]; };
+void aggregate_weights(hipStream_t st, float* w, void* w_lp, const AggSources& src, int n, size_t count);
 void fill_zero(hipStream_t st, void* p, size_t bytes);
 void calibration_copy(hipStream_t st, const void* src, void* dst, size_t bytes);
 void f32_to_storage(int dt, hipStream_t st, const float* src, void* dst, size_t n);

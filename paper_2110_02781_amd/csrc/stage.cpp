@@ -657,6 +657,29 @@ extern "C" int ftp_stage_snapshot_weights(ftp_stage* s, int slot, void* stream) 
   return FTP_OK;
 }
 
+extern "C" int ftp_stage_aggregate_weights(ftp_stage* s, const int* slots, int n, void* stream) {
+  if (!s || !slots) { ftp_set_error("stage_aggregate_weights: NULL argument"); return FTP_ERR_ARG; }
+  if (n < 1 || n > 8) { ftp_set_error("stage_aggregate_weights: 1 <= n <= 8 required, got %d", n); return FTP_ERR_ARG; }
+  AggSources src{};
+  for (int j = 0; j < n; ++j) {
+    const int slot = slots[j];
+    if (slot < 0 || slot >= (int)s->slots.size()) {
+      ftp_set_error("stage_aggregate_weights: slot %d out of range (n_slots=%zu)", slot, s->slots.size());
+      return FTP_ERR_ARG;
+    }
+    for (int q = 0; q < j; ++q)
+      if (slots[q] == slot) { ftp_set_error("stage_aggregate_weights: slot %d listed twice", slot); return FTP_ERR_ARG; }
+    if (!s->slots[slot].has_snap) {
+      ftp_set_error("stage_aggregate_weights: slot %d holds no weight snapshot", slot);
+      return FTP_ERR_SLOT;
+    }
+    src.p[j] = s->slots[slot].snap_w;
+  }
+  if (s->n_param) aggregate_weights((hipStream_t)stream, s->params, s->w_lp, src, n, s->n_param);
+  HIP_TRY(hipGetLastError());
+  return FTP_OK;
+}
+
 // Backward of one convolution+BN+act: dA is the gradient of the activated output.
 // Forms dz in one of two alternating buffers; accumulates weight / gamma / beta gradients; when dIn is
 // non-NULL writes the gradient of the (activated) input there (+ res for pointwise).  The weight

@@ -122,6 +122,10 @@ class Pair:
         yo = self.oracle.forward(slot, self.as_seen(x), stash_weights=snapshot)
         return self.host(y), yo
 
+    def aggregate(self, slots):
+        self.P.stage_aggregate_weights(self.stage, slots, self.stream)
+        self.oracle.aggregate(slots)
+
     def loss(self, slot, labels):
         P, torch = self.P, self.torch
         ld = torch.from_numpy(np.asarray(labels, dtype=np.int32)).to(self.dev)
@@ -180,6 +184,17 @@ class Pair:
         self.oracle.update(lr, mu, wd)
 
     # -- comparisons ------------------------------------------------------------------
+    def export_unit_vectors(self, which):
+        """The library's per-unit parameter / gradient / momentum vectors as a list of float32 arrays."""
+        P = self.P
+        self.torch.cuda.synchronize()
+        fn = {"weights": P.stage_export_weights, "grads": P.stage_export_grads, "momentum": P.stage_export_momentum}[which]
+        return [np.array(fn(self.stage, i, P.model_unit_param_count(self.model, i)), copy=True)
+                for i in range(self.a, self.b) if P.model_unit_param_count(self.model, i)]
+
+    def oracle_busy_slots(self):
+        return [i for i, sl in enumerate(self.oracle.slots) if sl is not None]
+
     def compare_unit_vectors(self, which, tol, floor=0.0):
         """which: 'weights' | 'grads' | 'momentum' | 'bn'.  Returns the worst (max, l2) errors."""
         P = self.P

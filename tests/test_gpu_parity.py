@@ -221,6 +221,76 @@ def test_config3_heaviest_stage_one_f_one_b_with_stashing():
         pair.close()
 
 
+def test_weight_aggregation_along_the_one_f_one_b_schedule():
+    """Stage 0 of 3 with weight stashing and aggregation (section "Async Pipeline Training"): the schedule and
+    the aggregation points come from the oracle's version trace (pinned to the paper's example); weights,
+    momentum and gradients are compared after every update and after every aggregation."""
+    from oracle.stage import version_trace
+    print("weight aggregation: small net, stage 0 of 3, 9 micro-batches", flush=True)
+    o, h = small_net()
+    nb, depth = 9, 3
+    pair = Pair(o, h, (9, 11, 3), 4, 0, len(o), "f32", seed=21, n_slots=depth)
+    try:
+        xs = [synth.normal(21, f"x{i}", (4, 9, 11, 3)) for i in range(nb)]
+        ls = [synth.labels(21, f"l{i}", 4, 10) for i in range(nb)]
+        tol, n_agg = TOL["f32"], 0
+        for ev in version_trace(0, 3, nb, aggregate=True):
+            if ev[0] == 'F':
+                b = ev[1]
+                pair.forward(b % depth, xs[b], snapshot=True)
+                pair.loss(b % depth, ls[b])
+            elif ev[0] == 'B':
+                pair.backward(ev[1] % depth, None, want_dx=False)
+                pair.update(0.01, 0.9, 4e-5)
+                pair.compare_unit_vectors("weights", tol)
+                tol = max(tol, 3e-4)       # later versions start from weights that already differ by the tolerance
+            else:
+                in_flight = sorted(pair.oracle_busy_slots())
+                assert len(in_flight) == len(ev[1]) == depth
+                before = pair.export_unit_vectors("weights")
+                pair.aggregate(in_flight)
+                pair.compare_unit_vectors("weights", tol)
+                pair.compare_unit_vectors("momentum", tol, floor=1e-7)
+                after = pair.export_unit_vectors("weights")
+                assert any(not np.array_equal(a, b) for a, b in zip(before, after)), "aggregation changed nothing"
+                n_agg += 1
+        assert n_agg == 2
+    finally:
+        pair.close()
+
+
+def test_weight_aggregation_is_exact_and_rejects_bad_slots():
+    """The mean is computed in fp32 in the order given, so two versions give exactly (a + b) / 2 in fp32; slots
+    without a snapshot, duplicates and n outside 1..8 are refused."""
+    import paper_2110_02781_amd as P
+    o, h = small_net()
+    pair = Pair(o, h, (9, 11, 3), 4, 0, len(o), "f32", seed=22, n_slots=3)
+    try:
+        x = synth.normal(22, "x", (4, 9, 11, 3))
+        labels = synth.labels(22, "l", 4, 10)
+        pair.forward(0, x, snapshot=True); pair.loss(0, labels)
+        w0 = pair.export_unit_vectors("weights")
+        pair.backward(0, None, want_dx=False); pair.update(0.05, 0.9, 0.0)
+        pair.forward(1, x, snapshot=True)                     # slot 1: version 1
+        pair.forward(0, x, snapshot=False)                    # slot 0 busy again, but without a snapshot
+        with pytest.raises(RuntimeError):
+            P.stage_aggregate_weights(pair.stage, [0, 1], pair.stream)
+        with pytest.raises(RuntimeError):
+            P.stage_aggregate_weights(pair.stage, [1, 1], pair.stream)
+        with pytest.raises(RuntimeError):
+            P.stage_aggregate_weights(pair.stage, [], pair.stream)
+        with pytest.raises(RuntimeError):
+            P.stage_aggregate_weights(pair.stage, [7], pair.stream)
+        w1 = pair.export_unit_vectors("weights")
+        P.stage_snapshot_weights(pair.stage, 0, pair.stream)  # now slot 0 stashes version 1 as well
+        P.stage_aggregate_weights(pair.stage, [0, 1], pair.stream)
+        same = pair.export_unit_vectors("weights")
+        assert all(np.array_equal(a, b) for a, b in zip(w1, same)), "mean of two equal versions must be that version"
+        assert any(not np.array_equal(a, b) for a, b in zip(w0, w1))
+    finally:
+        pair.close()
+
+
 def test_weight_stashing_matters_on_gpu():
     """Without the snapshot the backward uses the newer weights: results must differ from the stashed run."""
     o, h = small_net()
