@@ -1006,7 +1006,7 @@ static void plan_rows(size_t M, int ncols, int R, GemmArgs* a, bool* small) {
   a->jtiles = (ncols + BJ - 1) / BJ;
   size_t big_tiles = (M + 127) / 128;
   // short problems: too few 128-row tiles to fill 256 CUs and a reduction worth splitting
-  *small = big_tiles * a->jtiles < 96 && R >= 128;
+  *small = (big_tiles * a->jtiles < 96 && R >= 128) || (big_tiles * a->jtiles < 512 && R >= 512);
   int TI = *small ? 32 : 128;
   a->itiles = (int)((M + TI - 1) / TI);
   int want = (4096 + a->jtiles - 1) / a->jtiles;          // about 4096 blocks in flight
