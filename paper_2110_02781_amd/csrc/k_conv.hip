@@ -372,12 +372,6 @@ __device__ __forceinline__ void dw_stage_weights(float* wl, const T* __restrict_
   }
 }
 
-__device__ __forceinline__ int dw_logical_block() {   // neighbours in the numbering share an XCD (see k_gemm)
-  const int nb = gridDim.x, b = blockIdx.x;
-  const int x = b & 7, idx = b >> 3, q = nb >> 3, rem = nb & 7;
-  return x * q + (x < rem ? x : rem) + idx;
-}
-
 // out[ho][wo] = sum_{ky,kx} src[ho*S-1+ky][wo*S-1+kx] * w[ky][kx]   (FLIP: w[2-ky][2-kx], which for
 // S = 1 is the data gradient with src = dz)
 template <typename T, int S, bool FLIP>
@@ -386,7 +380,7 @@ __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ 
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   float* patch = reinterpret_cast<float*>(smem_raw);
   float* wl = patch + (size_t)d.PH * d.PW * d.CGB * 8;
-  const int lb = dw_logical_block();
+  const int lb = xcd_logical_block();
   const int tile = lb % d.ntiles, slab = lb / d.ntiles;
   const int tw = tile % d.tiles_w, th = (tile / d.tiles_w) % d.tiles_h, n = tile / (d.tiles_w * d.tiles_h);
   const int ho0 = th * d.TH, wo0 = tw * d.TW, cg0 = slab * d.CGB;
@@ -483,7 +477,8 @@ __global__ __launch_bounds__(1024) void dw_fwd_bn_small_k(View in, BnPending pen
   __shared__ float red[16][8];
   __shared__ double pre[32][8];
   __shared__ float insc[2][4];
-  const int C = g.Cout, c0 = blockIdx.x * 4, tid = threadIdx.x, nt = blockDim.x, s = g.stride;
+  // adjacent channel groups share cache lines: keep them on one XCD
+  const int C = g.Cout, c0 = xcd_logical_block() * 4, tid = threadIdx.x, nt = blockDim.x, s = g.stride;
   if (tid < 36) wl[tid / 4][tid % 4] = to_f32(w[(size_t)(c0 + tid % 4) * 9 + tid / 4]);
   const bool view = in.scale != nullptr;
   if (pend.partial) finish_pending4(pend, C, c0, eps, momentum, pre, insc);
@@ -586,7 +581,8 @@ __global__ __launch_bounds__(512) void dw_bwd_small_k(const T* __restrict__ dz, 
   __shared__ float wl[9][4];
   __shared__ float red[8][44];    // [wave][value]
   __shared__ float coef[3][4];
-  const int C = g.Cout, c0 = blockIdx.x * 4, tid = threadIdx.x, nt = blockDim.x, s = g.stride;
+  // adjacent channel groups share cache lines: keep them on one XCD
+  const int C = g.Cout, c0 = xcd_logical_block() * 4, tid = threadIdx.x, nt = blockDim.x, s = g.stride;
   if (tid < 36) wl[tid / 4][tid % 4] = to_f32(w[(size_t)(c0 + tid % 4) * 9 + tid / 4]);
   float sc[4], sh[4];
 #pragma unroll
@@ -778,7 +774,7 @@ __global__ __launch_bounds__(256) void dw_dgrad_s2_k(const T* __restrict__ dz, c
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   float* patch = reinterpret_cast<float*>(smem_raw);
   float* wl = patch + (size_t)d.PH * d.PW * d.CGB * 8;
-  const int lb = dw_logical_block();
+  const int lb = xcd_logical_block();
   const int tile = lb % d.ntiles, slab = lb / d.ntiles;
   const int tw = tile % d.tiles_w, th = (tile / d.tiles_w) % d.tiles_h, n = tile / (d.tiles_w * d.tiles_h);
   const int h0 = th * d.TH, w0 = tw * d.TW, cg0 = slab * d.CGB;       // tile origin, even
@@ -858,7 +854,7 @@ __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View
                                                   int Wout, int C, float* __restrict__ ws) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   float* patch = reinterpret_cast<float*>(smem_raw);
-  const int lb = dw_logical_block();
+  const int lb = xcd_logical_block();
   const int b = lb % d.nblocks, slab = lb / d.nblocks, cg0 = slab * d.CGB;
   const int QB = 2 * d.CGB, seg0 = dw_div(threadIdx.x, d.m_qb), cq = threadIdx.x - seg0 * QB;
   const int c4 = cq * 4, gc = cg0 * 8 + c4;

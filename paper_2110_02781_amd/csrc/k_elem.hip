@@ -335,7 +335,7 @@ __global__ __launch_bounds__(1024) void bn_bwd_small_k(const T* __restrict__ dA,
                                                        T* __restrict__ dz) {
   __shared__ float red[16][8];    // [wave][value]
   __shared__ float coef[3][4];
-  const int c0 = blockIdx.x * 4, tid = threadIdx.x, nt = blockDim.x;   // RPT * nt >= M
+  const int c0 = xcd_logical_block() * 4, tid = threadIdx.x, nt = blockDim.x;   // RPT * nt >= M; neighbours share an XCD
   float4 d[RPT], v[RPT];
 #pragma unroll
   for (int q = 0; q < RPT; ++q) {
@@ -447,7 +447,7 @@ __global__ __launch_bounds__(1024) void bn_finalize_apply_small_k(BnPending pend
                                                                   T* __restrict__ out) {
   __shared__ double pre[32][8];
   __shared__ float insc[2][4];
-  const int c0 = blockIdx.x * 4, tid = threadIdx.x, nt = blockDim.x;
+  const int c0 = xcd_logical_block() * 4, tid = threadIdx.x, nt = blockDim.x;
   finish_pending4(pend, C, c0, eps, momentum, pre, insc);
   float sc[4], sh[4];
 #pragma unroll

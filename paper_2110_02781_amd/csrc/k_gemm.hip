@@ -366,15 +366,6 @@ struct LoaderSel<T, ROWS, CH, true, USE_VIEW, PERM, true> { typedef VecTileLoade
 template <typename T, int ROWS, int CH, bool USE_VIEW, bool PERM>
 struct LoaderSel<T, ROWS, CH, false, USE_VIEW, PERM, true> { typedef VecTransLoader<T, ROWS, CH, USE_VIEW, PERM> type; };
 
-// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Renumbering them so that
-// consecutive logical ids share an XCD keeps the column tiles of one row range (which re-read the
-// same activations) behind one L2.
-__device__ __forceinline__ int xcd_logical_block() {
-  const int nb = gridDim.x, b = blockIdx.x;
-  const int x = b & 7, idx = b >> 3, q = nb >> 3, rem = nb & 7;
-  return x * q + (x < rem ? x : rem) + idx;
-}
-
 // ---- MFMA over one staged chunk of 32 reduction elements starting at column c0 -------
 __device__ __forceinline__ void mma32(const bf16_t* xs, const bf16_t* ys, int LD, int irow, int lane, int c0,
                                       f16v acc[2]) {
