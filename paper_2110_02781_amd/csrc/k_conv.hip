@@ -1,7 +1,8 @@
 // Small dense convolutions (3x3 stem, conv1d) and depthwise 3x3, NHWC.
 // Inputs are read through a View, so the producer's BatchNorm + activation is
 // applied on load and zero padding is inserted after it (a halo cell is 0, not
-// act(bn(0))).
+// act(bn(0))).  Depthwise layers over short tensors (at most 2048 pixels) run whole
+// forward / backward sub-chains in one launch (dw_fwd_bn_small_k, dw_bwd_small_k).
 #include "dev_common.h"
 #include "kernels.h"
 #include "bn_pending.h"
@@ -284,7 +285,7 @@ enum { kDwFillNV = 6 };     // passes the patch staging is unrolled for
 static unsigned dw_magic(int d) { return 65536u / (unsigned)d + 1u; }
 __device__ __forceinline__ int dw_div(int x, unsigned m) { return (int)(__umul24((unsigned)x, m) >> 16); }
 
-static DwPlan dw_plan(int C, int es, bool half_rows, int out_h, int out_w, int max_blocks) {
+static DwPlan dw_plan(int C, int es, bool half_rows, int out_h, int out_w) {
   DwPlan d;
   const int cgs = C / 8, cap = es == 2 ? 8 : 4;            // 128 bytes of channels per pixel
   d.nslab = (cgs + cap - 1) / cap;
@@ -301,7 +302,6 @@ static DwPlan dw_plan(int C, int es, bool half_rows, int out_h, int out_w, int m
   d.tiles_w = (out_w + d.TW - 1) / d.TW;
   d.ntiles = 0; d.nblocks = 0; d.PH = d.PW = 0;
   d.m_cgb = dw_magic(d.CGB); d.m_qb = dw_magic(2 * d.CGB); d.m_segw = dw_magic(d.segw); d.m_pw = 0;
-  (void)max_blocks;
   return d;
 }
 
@@ -431,7 +431,7 @@ static void dw_check_plan(DwPlan& d) {
 
 void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z) {
   const int es = dt == 0 ? 4 : 2, s = g.stride;
-  DwPlan d = dw_plan(g.Cout, es, s == 2, g.Hout, g.Wout, 0);
+  DwPlan d = dw_plan(g.Cout, es, s == 2, g.Hout, g.Wout);
   d.PH = (d.TH - 1) * s + 3;
   d.PW = (d.segw * 4 - 1) * s + 3;               // runs are whole: the patch covers the rounded-up tile width
   d.ntiles = g.N * d.tiles_h * d.tiles_w;
@@ -826,7 +826,7 @@ void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvG
   KScope ks(st, "dw_dgrad", ((double)total * g.Cout + (double)g.N * g.Hout * g.Wout * g.Cout) * es, 18.0 * g.N * g.Hout * g.Wout * g.Cout,
             (long)total, g.Cout, g.stride);
   // tiles are in input resolution
-  DwPlan d = dw_plan(g.Cout, es, false, g.Hin, g.Win, 0);
+  DwPlan d = dw_plan(g.Cout, es, false, g.Hin, g.Win);
   d.ntiles = g.N * d.tiles_h * d.tiles_w;
   const unsigned grid = (unsigned)d.ntiles * d.nslab;
   if (g.stride == 1) {
@@ -925,7 +925,7 @@ __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View
 
 static DwPlan dw_wgrad_plan(const ConvGeom& g, int es, size_t* lds) {
   const int s = g.stride;
-  DwPlan d = dw_plan(g.Cout, es, s == 2, g.Hout, g.Wout, 0);
+  DwPlan d = dw_plan(g.Cout, es, s == 2, g.Hout, g.Wout);
   d.PH = (d.TH - 1) * s + 3;
   d.PW = (d.segw * 4 - 1) * s + 3;
   d.ntiles = g.N * d.tiles_h * d.tiles_w;

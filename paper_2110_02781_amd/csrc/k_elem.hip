@@ -3,7 +3,8 @@
 // each thread moves 8 consecutive channels (16 or 32 bytes) per access, rows
 // are walked so that a block touches contiguous memory, and per-channel sums
 // are reduced in a fixed order (per thread -> LDS across the block -> float64
-// across blocks), so results are run-to-run deterministic.
+// across blocks), so results are run-to-run deterministic.  Short tensors (at most
+// 2048 rows) use one-launch variants in which a block owns 4 channels over all rows.
 #include "dev_common.h"
 #include "kernels.h"
 #include "bn_pending.h"

@@ -15,12 +15,16 @@
 //   * the next reduction chunk is fetched from HBM into registers while the
 //     current one is multiplied out of LDS (software pipeline over a flat
 //     (row tile, chunk) sequence);
-//   * results leave through an LDS copy of the tile so that every global store is a
-//     16/32-byte vector of consecutive channels.
-// Two tile shapes: 128 x 64 with the four wavefronts splitting the rows (tall
-// problems), and 32 x 64 with the four wavefronts splitting a 128-long reduction
-// chunk (short problems: few rows, long reductions; keeps all CUs busy).
-// bfloat16 uses v_mfma_f32_32x32x16_bf16, float uses v_mfma_f32_32x32x2_f32.
+//   * the weight tile is stored row-permuted so that a lane's two accumulators are adjacent
+//     columns: results leave straight from the MFMA registers and every store instruction
+//     writes whole 128/256-byte row segments.
+// Three tile shapes: 128 x 64 with the four wavefronts splitting the rows (tall problems);
+// 32 x 64 with the four wavefronts splitting a 128-long reduction chunk (few row tiles, long
+// reductions); and 16 x 16 with fragments loaded straight from global memory (at most 2048
+// rows: pure latency, see pw_gemm_tiny_body), where data gradient and weight gradient of a
+// layer share one launch and the weight gradient needs no partial buffers.
+// bfloat16 uses v_mfma_f32_32x32x16_bf16 (16x16x32 in the short kernels), float uses
+// v_mfma_f32_32x32x2_f32 (16x16x4).
 #include "dev_common.h"
 #include "kernels.h"
 

@@ -684,13 +684,12 @@ extern "C" int ftp_stage_aggregate_weights(ftp_stage* s, const int* slots, int n
 // Forms dz in one of two alternating buffers; accumulates weight / gamma / beta gradients; when dIn is
 // non-NULL writes the gradient of the (activated) input there (+ res for pointwise).  The weight
 // gradient runs on the stage's side stream unless per-unit profiling is on.
-// mode: the whole layer; only up to dz (returned in *dz_out); or from a dz that the caller formed (passed as dA)
-enum { BWD_FULL = 0, BWD_DZ_ONLY = 1, BWD_FROM_DZ = 2 };
+// mode: the whole layer, or from a dz that the caller formed (passed as dA)
+enum { BWD_FULL = 0, BWD_FROM_DZ = 1 };
 static bool stage_overlaps(const ftp_stage* s) { return s->prof == nullptr && s->max_act_bytes >= ((size_t)32 << 20); }
 
 static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, const void* dA, HView in, HView out,
-                        void* dIn, const void* res, const WeightSet& W, hipStream_t st, int mode = BWD_FULL,
-                        void** dz_out = nullptr) {
+                        void* dIn, const void* res, const WeightSet& W, hipStream_t st, int mode = BWD_FULL) {
   const Sub& sb = p.info->subs[k];
   ConvGeom g = sb.g; g.N = s->batch;
   int C = g.Cout;
@@ -721,7 +720,6 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
                    s->grads + p.p_off + sb.gamma_off, s->grads + p.p_off + sb.beta_off, dz);
     else
       bn_bwd_apply(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->coef, dz);
-    if (mode == BWD_DZ_ONLY) { *dz_out = dz; return FTP_OK; }
   }
   hipStream_t ws = st;
   if (overlap) {
