@@ -64,3 +64,41 @@ def estimate_capacity(stage_time, layer_costs, start, end):
     """Capacity equation: measured time of worker i's stage divided by the
     central node's time for the same layers start..end (inclusive)."""
     return stage_time / sum(layer_costs[start:end + 1])
+
+
+def renumber_workers(worker_list, failed):
+    """Worker list after failures (section "Fault Tolerance Mechanism"): with one
+    failure every index above the failed one drops by one; with several, each failed
+    entry is replaced by the alive workers behind it one by one.  Both are the
+    stable removal of the failed entries.  Returns the new list."""
+    dead = set(failed)
+    return [w for i, w in enumerate(worker_list) if i not in dead]
+
+
+def redistribution_plan(bounds_new, bounds_cur, i_fail, i_cur, i_new):
+    """Weight redistribution (the paper's Algorithm "Weight Redistribution"), for the
+    worker that held stage i_cur of bounds_cur and will hold stage i_new of
+    bounds_new.  i_fail: index (in the current numbering) of the one failed
+    worker, or None for a plain re-partition.  Bounds are half-open layer indices.
+
+    Returns (M_need, L_local): M_need maps a worker index in the NEW numbering to
+    the layers to fetch from it; L_local lists the layers of the new stage that the
+    worker already holds.  A layer of the failed stage is fetched from the worker
+    that follows it in the chain (chain replication puts its backup there: that
+    worker's new index equals the failed index), or from worker 0 (the central
+    node) when the failed stage was the last one."""
+    start_cur, end_cur = bounds_cur[i_cur], bounds_cur[i_cur + 1] - 1
+    start_new, end_new = bounds_new[i_new], bounds_new[i_new + 1] - 1
+    needed = [l for l in range(start_new, end_new + 1) if not (start_cur <= l <= end_cur)]
+    local = [l for l in range(start_new, end_new + 1) if l not in needed]
+    last_stage = len(bounds_cur) - 2
+    m_need = {}
+    for l in needed:
+        target = next(k for k in range(len(bounds_cur) - 1) if bounds_cur[k] <= l < bounds_cur[k + 1])
+        if i_fail is not None:
+            if target > i_fail:
+                target -= 1
+            elif target == i_fail and i_fail == last_stage:
+                target = 0
+        m_need.setdefault(target, []).append(l)
+    return m_need, local

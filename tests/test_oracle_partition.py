@@ -114,3 +114,77 @@ def test_capacity_estimate():
     costs = [2.0, 3.0, 5.0, 7.0]
     assert estimate_capacity(30.0, costs, 1, 2) == 30.0 / 8.0
     assert estimate_capacity(17.0, costs, 0, 3) == 1.0
+
+
+# ---- weight redistribution (the paper's Algorithm "Weight Redistribution") ----------------------
+# Table written from the rules of section "Fault Tolerance Mechanism": a needed layer that the worker does
+# not hold is fetched from the stage that holds it now; indices above the failed one drop by one; a layer of
+# the failed stage comes from the worker behind it in the chain (whose new index is the failed index); if the
+# failed stage was the last one its backup is on the central node, index 0; a plain re-partition corrects
+# nothing.   (bounds_cur, bounds_new, i_fail, i_cur, i_new) -> (M_need, L_local)
+REDISTRIBUTION_TABLE = [
+    # plain re-partition of 12 layers over 3 workers
+    (([0, 4, 8, 12], [0, 6, 9, 12], None, 0, 0), ({1: [4, 5]}, [0, 1, 2, 3])),
+    (([0, 4, 8, 12], [0, 6, 9, 12], None, 1, 1), ({2: [8]}, [6, 7])),
+    (([0, 4, 8, 12], [0, 6, 9, 12], None, 2, 2), ({}, [9, 10, 11])),
+    # shrink: worker 2 takes layers from both neighbours' old ranges
+    (([0, 4, 8, 12], [0, 2, 4, 12], None, 2, 2), ({1: [4, 5, 6, 7]}, [8, 9, 10, 11])),
+    # worker 1 of 4 fails; survivors are renumbered 0, 1 (was 2), 2 (was 3)
+    (([0, 3, 6, 9, 12], [0, 4, 8, 12], 1, 0, 0), ({1: [3]}, [0, 1, 2])),
+    (([0, 3, 6, 9, 12], [0, 4, 8, 12], 1, 2, 1), ({1: [4, 5]}, [6, 7])),
+    (([0, 3, 6, 9, 12], [0, 4, 8, 12], 1, 3, 2), ({1: [8]}, [9, 10, 11])),
+    # the last stage fails: its backup is on the central node
+    (([0, 4, 8, 12], [0, 6, 12], 2, 1, 1), ({0: [8, 9, 10, 11]}, [6, 7])),
+    (([0, 4, 8, 12], [0, 6, 12], 2, 0, 0), ({1: [4, 5]}, [0, 1, 2, 3])),
+    # worker 0 (the central node's own stage is never the failed one) with a failure behind it
+    (([0, 4, 8, 12], [0, 5, 12], 1, 0, 0), ({1: [4]}, [0, 1, 2, 3])),
+    (([0, 4, 8, 12], [0, 5, 12], 1, 2, 1), ({1: [5, 6, 7]}, [8, 9, 10, 11])),
+]
+
+
+def test_redistribution_plan_table():
+    from oracle.partition import redistribution_plan
+    for (cur, new, i_fail, i_cur, i_new), (m_need, local) in REDISTRIBUTION_TABLE:
+        got = redistribution_plan(new, cur, i_fail, i_cur, i_new)
+        assert got == (m_need, local), ((cur, new, i_fail, i_cur, i_new), got)
+
+
+def test_redistribution_plan_invariants():
+    """Brute-force properties on random partitions: needed and local layers partition the new stage exactly;
+    every needed layer is asked from a worker that exists in the new numbering; without a failure the source is
+    the current holder; nothing is needed when the partition does not change."""
+    from oracle.partition import redistribution_plan
+    for t in range(300):
+        L = 6 + t % 17
+        n = 2 + t % 4
+        cuts_c = sorted(set(int(x) for x in synth.integers(t, "c", (n - 1,), 1, L - 1)))
+        cur = [0] + cuts_c + [L]
+        n_cur = len(cur) - 1
+        fail = None if t % 3 == 0 or n_cur < 3 else 1 + t % (n_cur - 1)
+        n_new = n_cur - (fail is not None)
+        cuts_n = sorted(set(int(x) for x in synth.integers(t, "n", (n_new - 1,), 1, L - 1)))[:n_new - 1] if n_new > 1 else []
+        new = [0] + cuts_n + [L]
+        n_new = len(new) - 1
+        for i_cur in range(n_cur):
+            if i_cur == fail:
+                continue
+            i_new = i_cur - 1 if fail is not None and i_cur > fail else i_cur
+            if i_new >= n_new:
+                continue
+            m_need, local = redistribution_plan(new, cur, fail, i_cur, i_new)
+            asked = sorted(l for ls in m_need.values() for l in ls)
+            assert sorted(asked + local) == list(range(new[i_new], new[i_new + 1]))
+            assert all(cur[i_cur] <= l < cur[i_cur + 1] for l in local)
+            assert all(0 <= k < max(n_cur - (fail is not None), 1) for k in m_need)
+            if fail is None:
+                for k, ls in m_need.items():
+                    assert all(cur[k] <= l < cur[k + 1] for l in ls)
+        same, _ = redistribution_plan(cur, cur, None, 0, 0)
+        assert same == {}
+
+
+def test_renumber_workers():
+    from oracle.partition import renumber_workers
+    assert renumber_workers(["c", "w1", "w2", "w3"], [2]) == ["c", "w1", "w3"]
+    assert renumber_workers(["c", "w1", "w2", "w3", "w4"], [1, 3]) == ["c", "w2", "w4"]
+    assert renumber_workers(["c", "w1"], []) == ["c", "w1"]
