@@ -200,6 +200,29 @@ int ftp_solve_partition(const double* layer_costs, int L, const double* device_c
 int ftp_estimate_capacity(double stage_time, const double* layer_costs, int L, int start, int end,
                           double* capacity);
 
+/* Weight redistribution after a re-partition or a single worker failure (the
+ * paper's Algorithm "Weight Redistribution", sections "Dynamic Model Partition"
+ * and "Fault Tolerance Mechanism"), for the worker that holds stage i_cur of
+ * bounds_cur[n_cur+1] and will hold stage i_new of bounds_new[n_new+1] (half-open
+ * unit bounds as returned by ftp_solve_partition, same total).  i_fail: index in
+ * the CURRENT numbering of the failed worker, or -1 for a plain re-partition.
+ * source[j], j = 0 .. bounds_new[i_new+1]-bounds_new[i_new]-1, receives for unit
+ * bounds_new[i_new]+j either -1 (the worker holds it already) or the index, in
+ * the NEW numbering, of the worker to fetch it from: the current holder, moved
+ * up by one if it sat behind the failed worker; the failed worker's chain
+ * successor (which now carries the failed index) for a unit of the failed stage;
+ * worker 0 (the central node) if the failed stage was the last one.  Host
+ * pointers only; no device work. */
+int ftp_redistribution_plan(const int32_t* bounds_new, int n_new, const int32_t* bounds_cur, int n_cur, int i_fail,
+                            int i_cur, int i_new, int32_t* source);
+
+/* Device-side half of the redistribution: copies weights, momentum and BatchNorm
+ * running statistics of units [unit_lo, unit_hi) from `src` to `dst` (both
+ * stages must contain the range and be built from the same model and type),
+ * device to device on `stream`, and refreshes dst's bfloat16 working copy of
+ * them.  Pending gradients are not copied. */
+int ftp_stage_copy_units(ftp_stage* dst, const ftp_stage* src, int unit_lo, int unit_hi, void* stream);
+
 /* ---- diagnostics ---------------------------------------------------------------- */
 
 /* Per-kernel timing for benchmarks (not part of the paper's method).  Between

@@ -216,6 +216,16 @@ class Stage:
         return d
 
     # ----------------------------------------------------------------- update
+    def adopt_units(self, other, lo, hi):
+        """Weight redistribution, receiving side: take weights, momentum and BatchNorm
+        running statistics of units [lo, hi) from another stage (section "Dynamic Model
+        Partition": a worker fetches the layers it is missing from their current owner)."""
+        for i in range(lo, hi):
+            self.params[i] = [p.copy() for p in other.params[i]]
+            self.mom[i] = [m.copy() for m in other.mom[i]]
+            if i in other.bn_run:
+                self.bn_run[i] = [[a.copy() for a in pair] for pair in other.bn_run[i]]
+
     def aggregate(self, slots):
         """Weight aggregation (section "Async Pipeline Training"): the live
         weights become the arithmetic mean of the weight versions stashed in

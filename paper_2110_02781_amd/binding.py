@@ -84,6 +84,8 @@ _SIGS = {
     "ftp_profile_layers": (_i, [_vp, _i, _i, _dp, C.POINTER(C.c_int64), _vp]),
     "ftp_solve_partition": (_i, [_dp, _i, _dp, _i, _dp, _dp, C.POINTER(C.c_int32), _dp]),
     "ftp_estimate_capacity": (_i, [C.c_double, _dp, _i, _i, _i, _dp]),
+    "ftp_redistribution_plan": (_i, [C.POINTER(C.c_int32), _i, C.POINTER(C.c_int32), _i, _i, _i, _i, C.POINTER(C.c_int32)]),
+    "ftp_stage_copy_units": (_i, [_vp, _vp, _i, _i, _vp]),
     "ftp_calibration_copy": (_i, [_vp, _vp, _sz, _vp]),
     "ftp_ktrace_begin": (_i, [_i]),
     "ftp_ktrace_end": (_i, [C.POINTER(KtraceRow), _i, C.POINTER(_i)]),
@@ -286,3 +288,25 @@ def ktrace_end():
 
 def calibration_copy(dst_dev, src_dev, nbytes, stream=None):
     _chk(lib.ftp_calibration_copy(_ptr(dst_dev), _ptr(src_dev), nbytes, _ptr(stream)))
+
+
+def redistribution_plan(bounds_new, bounds_cur, i_fail, i_cur, i_new):
+    """Returns (M_need, L_local) like the paper's algorithm: {worker index in the new numbering: [units]}, [units held]."""
+    bn = (C.c_int32 * len(bounds_new))(*[int(v) for v in bounds_new])
+    bc = (C.c_int32 * len(bounds_cur))(*[int(v) for v in bounds_cur])
+    n = int(bounds_new[i_new + 1]) - int(bounds_new[i_new]) if 0 <= i_new < len(bounds_new) - 1 else 1
+    src = (C.c_int32 * max(n, 1))()
+    _chk(lib.ftp_redistribution_plan(bn, len(bounds_new) - 1, bc, len(bounds_cur) - 1, -1 if i_fail is None else int(i_fail),
+                                     int(i_cur), int(i_new), src))
+    m_need, local = {}, []
+    for j in range(n):
+        unit = int(bounds_new[i_new]) + j
+        if src[j] < 0:
+            local.append(unit)
+        else:
+            m_need.setdefault(int(src[j]), []).append(unit)
+    return m_need, local
+
+
+def stage_copy_units(dst, src, unit_lo, unit_hi, stream=None):
+    _chk(lib.ftp_stage_copy_units(dst, src, unit_lo, unit_hi, _ptr(stream)))

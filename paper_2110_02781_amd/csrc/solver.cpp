@@ -91,3 +91,47 @@ extern "C" int ftp_estimate_capacity(double stage_time, const double* layer_cost
   *capacity = stage_time / s;
   return FTP_OK;
 }
+
+// Which stage of `bounds` (n stages, half-open) holds layer l; -1 if none.
+static int stage_of(const int32_t* bounds, int n, int l) {
+  for (int k = 0; k < n; ++k)
+    if (bounds[k] <= l && l < bounds[k + 1]) return k;
+  return -1;
+}
+
+static bool bounds_ok(const int32_t* b, int n) {
+  if (!b || n < 1 || b[0] != 0) return false;
+  for (int k = 0; k < n; ++k)
+    if (b[k + 1] <= b[k]) return false;
+  return true;
+}
+
+extern "C" int ftp_redistribution_plan(const int32_t* bounds_new, int n_new, const int32_t* bounds_cur, int n_cur, int i_fail,
+                                       int i_cur, int i_new, int32_t* source) {
+  if (!bounds_ok(bounds_new, n_new) || !bounds_ok(bounds_cur, n_cur) || !source) {
+    ftp_set_error("redistribution_plan: bounds must start at 0 and increase strictly; source must not be NULL");
+    return FTP_ERR_ARG;
+  }
+  if (bounds_new[n_new] != bounds_cur[n_cur]) {
+    ftp_set_error("redistribution_plan: both partitions must cover the same %d layers", (int)bounds_cur[n_cur]);
+    return FTP_ERR_ARG;
+  }
+  if (i_cur < 0 || i_cur >= n_cur || i_new < 0 || i_new >= n_new || i_fail < -1 || i_fail >= n_cur || i_fail == i_cur) {
+    ftp_set_error("redistribution_plan: worker index out of range (i_cur=%d of %d, i_new=%d of %d, i_fail=%d)", i_cur, n_cur,
+                  i_new, n_new, i_fail);
+    return FTP_ERR_ARG;
+  }
+  const int lo = bounds_new[i_new], hi = bounds_new[i_new + 1];
+  const int have_lo = bounds_cur[i_cur], have_hi = bounds_cur[i_cur + 1];
+  for (int l = lo; l < hi; ++l) {
+    if (have_lo <= l && l < have_hi) { source[l - lo] = -1; continue; }     // held already
+    int t = stage_of(bounds_cur, n_cur, l);
+    if (i_fail >= 0) {
+      if (t > i_fail) t -= 1;                                  // the numbering behind the failed worker moved up
+      else if (t == i_fail && i_fail == n_cur - 1) t = 0;      // backup of the last stage lives on the central node
+      // t == i_fail otherwise: the chain successor holds the backup and now carries this index
+    }
+    source[l - lo] = t;
+  }
+  return FTP_OK;
+}

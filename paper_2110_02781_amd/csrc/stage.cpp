@@ -657,6 +657,36 @@ extern "C" int ftp_stage_snapshot_weights(ftp_stage* s, int slot, void* stream) 
   return FTP_OK;
 }
 
+extern "C" int ftp_stage_copy_units(ftp_stage* dst, const ftp_stage* src, int unit_lo, int unit_hi, void* stream) {
+  if (!dst || !src) { ftp_set_error("stage_copy_units: NULL stage"); return FTP_ERR_ARG; }
+  if (dst->model != src->model || dst->dt != src->dt) {
+    ftp_set_error("stage_copy_units: the two stages must come from the same model and storage type");
+    return FTP_ERR_ARG;
+  }
+  if (unit_lo < 0 || unit_hi < unit_lo || unit_lo < dst->a || unit_hi > dst->b || unit_lo < src->a || unit_hi > src->b) {
+    ftp_set_error("stage_copy_units: units [%d,%d) must lie inside both stages (dst [%d,%d), src [%d,%d))", unit_lo, unit_hi,
+                  dst->a, dst->b, src->a, src->b);
+    return FTP_ERR_ARG;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  for (int u = unit_lo; u < unit_hi; ++u) {
+    const UnitPlan& pd = dst->plan[u - dst->a];
+    const UnitPlan& ps = src->plan[u - src->a];
+    const size_t n = pd.info->n_param, nb = pd.info->n_bn;
+    if (n) {
+      HIP_TRY(hipMemcpyAsync(dst->params + pd.p_off, src->params + ps.p_off, n * 4, hipMemcpyDeviceToDevice, st));
+      HIP_TRY(hipMemcpyAsync(dst->mom + pd.p_off, src->mom + ps.p_off, n * 4, hipMemcpyDeviceToDevice, st));
+      if (dst->w_lp) f32_to_storage(FTP_BF16, st, dst->params + pd.p_off, (char*)dst->w_lp + pd.p_off * 2, n);
+    }
+    if (nb) {
+      HIP_TRY(hipMemcpyAsync(dst->run_mean + pd.bn_off, src->run_mean + ps.bn_off, nb * 4, hipMemcpyDeviceToDevice, st));
+      HIP_TRY(hipMemcpyAsync(dst->run_var + pd.bn_off, src->run_var + ps.bn_off, nb * 4, hipMemcpyDeviceToDevice, st));
+    }
+  }
+  HIP_TRY(hipGetLastError());
+  return FTP_OK;
+}
+
 extern "C" int ftp_stage_aggregate_weights(ftp_stage* s, const int* slots, int n, void* stream) {
   if (!s || !slots) { ftp_set_error("stage_aggregate_weights: NULL argument"); return FTP_ERR_ARG; }
   if (n < 1 || n > 8) { ftp_set_error("stage_aggregate_weights: 1 <= n <= 8 required, got %d", n); return FTP_ERR_ARG; }

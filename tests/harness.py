@@ -64,7 +64,8 @@ def from_bf16_bits(b):
 class Pair:
     """The same stage [a,b) in the oracle (float64) and in the HIP library."""
 
-    def __init__(self, o_units, h_units, in_shape, batch, a, b, dtype="f32", n_slots=1, seed=1, guard=None, max_disagree_frac=0.0):
+    def __init__(self, o_units, h_units, in_shape, batch, a, b, dtype="f32", n_slots=1, seed=1, guard=None, max_disagree_frac=0.0,
+                 model_of=None):
         import torch
         import paper_2110_02781_amd as P
         self.P, self.torch = P, torch
@@ -73,7 +74,9 @@ class Pair:
         self.dev = torch.device("cuda:0")
         self.tdt = torch.float32 if dtype == "f32" else torch.bfloat16
         H, W, Cc = in_shape
-        self.model = P.model_create(h_units, H, W, Cc, P.F32 if dtype == "f32" else P.BF16)
+        # stages that exchange units (re-partition) are built from one model object
+        self.owns_model = model_of is None
+        self.model = P.model_create(h_units, H, W, Cc, P.F32 if dtype == "f32" else P.BF16) if model_of is None else model_of.model
         self.stage = P.stage_create(self.model, a, b, batch, n_slots)
         self.oracle = OracleStage(o_units, in_shape, a, b, n_slots, storage='bf16' if dtype == 'bf16' else None)
         op = OM.init_params(o_units, seed)
@@ -93,7 +96,13 @@ class Pair:
 
     def close(self):
         self.P.stage_destroy(self.stage)
-        self.P.model_destroy(self.model)
+        if self.owns_model:
+            self.P.model_destroy(self.model)
+
+    def copy_units_from(self, other, lo, hi):
+        """Weights, momentum and BatchNorm running statistics of units [lo, hi) from another pair, on both sides."""
+        self.P.stage_copy_units(self.stage, other.stage, lo, hi, self.stream)
+        self.oracle.adopt_units(other.oracle, lo, hi)
 
     # -- tensors ------------------------------------------------------------------
     def dev_tensor(self, arr):

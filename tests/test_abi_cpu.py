@@ -94,3 +94,38 @@ def test_model_description_matches_oracle_and_rejects_bad_chains(P):
         P.model_create(bad, 1, 128, 9, P.F32)
     with pytest.raises(P.FtpError):
         P.model_create(P.models.cnn1d_units()[:-1] + [dict(kind=99)], 1, 128, 9, P.F32)
+
+
+def test_redistribution_plan_matches_oracle(P):
+    """The library's host function against the oracle: the paper-derived table and 300 random partitions."""
+    from oracle.partition import redistribution_plan as oracle_plan
+    from test_oracle_partition import REDISTRIBUTION_TABLE
+    for (cur, new, i_fail, i_cur, i_new), want in REDISTRIBUTION_TABLE:
+        assert P.redistribution_plan(new, cur, i_fail, i_cur, i_new) == want
+    for t in range(300):
+        L = 6 + t % 17
+        n = 2 + t % 4
+        cur = [0] + sorted(set(int(x) for x in synth.integers(t, "c", (n - 1,), 1, L - 1))) + [L]
+        n_cur = len(cur) - 1
+        fail = None if t % 3 == 0 or n_cur < 3 else 1 + t % (n_cur - 1)
+        n_new = n_cur - (fail is not None)
+        new = [0] + (sorted(set(int(x) for x in synth.integers(t, "n", (n_new - 1,), 1, L - 1)))[:n_new - 1] if n_new > 1 else []) + [L]
+        n_new = len(new) - 1
+        for i_cur in range(n_cur):
+            if i_cur == fail:
+                continue
+            i_new = i_cur - 1 if fail is not None and i_cur > fail else i_cur
+            if i_new >= n_new:
+                continue
+            assert P.redistribution_plan(new, cur, fail, i_cur, i_new) == oracle_plan(new, cur, fail, i_cur, i_new)
+
+
+def test_redistribution_plan_rejects_bad_arguments(P):
+    with pytest.raises(RuntimeError):
+        P.redistribution_plan([0, 4, 8], [0, 4, 9], None, 0, 0)          # different totals
+    with pytest.raises(RuntimeError):
+        P.redistribution_plan([0, 4, 4, 8], [0, 4, 8], None, 0, 0)       # empty stage
+    with pytest.raises(RuntimeError):
+        P.redistribution_plan([0, 4, 8], [0, 4, 8], 1, 1, 0)             # the failed worker asks
+    with pytest.raises(RuntimeError):
+        P.redistribution_plan([0, 4, 8], [0, 4, 8], None, 2, 0)          # index out of range

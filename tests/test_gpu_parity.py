@@ -291,6 +291,73 @@ def test_weight_aggregation_is_exact_and_rejects_bad_slots():
         pair.close()
 
 
+def _two_stage_step(pa, pb, x, labels, tol, lr=0.01):
+    """One synchronous step of a two-stage pipeline: each side's boundary tensors feed its own next stage."""
+    ya, yao = pa.forward(0, x)
+    assert_close(ya, yao, tol, "boundary activation")
+    yb, ybo = pb.forward(0, ya)             # teacher-forced with the library's boundary tensor on both sides
+    assert_close(yb, ybo, tol, "logits")
+    pb.loss(0, labels)
+    dxb, dxbo = pb.backward(0, None, want_dx=True)
+    assert_close(dxb, dxbo, tol, "boundary gradient")
+    pa.backward(0, dxb, want_dx=False)
+    for p in (pa, pb):
+        p.compare_unit_vectors("grads", tol, floor=1e-7)
+        p.update(lr, 0.9, 4e-5)
+        p.compare_unit_vectors("weights", tol)
+        p.compare_unit_vectors("momentum", tol, floor=1e-7)
+    return yb
+
+
+def test_repartition_moves_units_between_stages_on_the_device():
+    """Dynamic re-partition (section "Dynamic Model Partition"): two stages train, the cut moves, every worker
+    works out what it is missing with the redistribution plan and takes it from its owner device-to-device,
+    then training goes on.  Each step is compared with the oracle; after the move, so are the moved weights,
+    momentum and BatchNorm running statistics."""
+    import paper_2110_02781_amd as P
+    print("re-partition: small net, cut 4 -> 6, two stages", flush=True)
+    o, h = small_net()
+    L = len(o)
+    cur, new = [0, 4, L], [0, 6, L]
+    tol = TOL["f32"]
+    A = Pair(o, h, (9, 11, 3), 4, cur[0], cur[1], "f32", seed=31)
+    B = Pair(o, h, (9, 11, 3), 4, cur[1], cur[2], "f32", seed=31, model_of=A)
+    A2 = B2 = None
+    try:
+        xs = [synth.normal(31, f"x{i}", (4, 9, 11, 3)) for i in range(3)]
+        ls = [synth.labels(31, f"l{i}", 4, 10) for i in range(3)]
+        _two_stage_step(A, B, xs[0], ls[0], tol)
+        _two_stage_step(A, B, xs[1], ls[1], 3 * tol)
+        # new stages; every worker fetches what the plan says, from the stage that holds it now
+        A2 = Pair(o, h, (9, 11, 3), 4, new[0], new[1], "f32", seed=99, model_of=A)      # other seed: nothing may survive
+        B2 = Pair(o, h, (9, 11, 3), 4, new[1], new[2], "f32", seed=99, model_of=A)
+        old = [A, B]
+        for i_w, dst in enumerate([A2, B2]):
+            m_need, local = P.redistribution_plan(new, cur, None, i_w, i_w)
+            for u in local:
+                dst.copy_units_from(old[i_w], u, u + 1)
+            for src_w, units in m_need.items():
+                for u in units:
+                    dst.copy_units_from(old[src_w], u, u + 1)
+        assert P.redistribution_plan(new, cur, None, 0, 0) == ({1: [4, 5]}, [0, 1, 2, 3])
+        for p in (A2, B2):
+            p.compare_unit_vectors("weights", 3 * tol)
+            p.compare_unit_vectors("momentum", 3 * tol, floor=1e-7)
+            p.compare_unit_vectors("bn", 3 * tol)
+        # the moved state is the old state, bit for bit
+        wa = {u: v for u, v in zip(range(cur[1], cur[2]), B.export_unit_vectors("weights"))}
+        w2 = A2.export_unit_vectors("weights")
+        assert np.array_equal(w2[4], wa[4]) and np.array_equal(w2[5], wa[5])
+        _two_stage_step(A2, B2, xs[2], ls[2], 6 * tol)
+        with pytest.raises(RuntimeError):
+            P.stage_copy_units(A2.stage, B.stage, 0, 2, A2.stream)       # B never held units 0-1
+    finally:
+        for p in (B2, A2, B):
+            if p is not None:
+                p.close()
+        A.close()
+
+
 def test_weight_stashing_matters_on_gpu():
     """Without the snapshot the backward uses the newer weights: results must differ from the stashed run."""
     o, h = small_net()
