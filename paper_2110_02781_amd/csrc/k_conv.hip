@@ -240,8 +240,10 @@ __global__ void pad_rows_k(const T* __restrict__ w, int rows, int K, int Kpad, T
   out[i] = k < K ? w[(size_t)r * K + k] : from_f32<T>(0.f);
 }
 
+// many pixels (the 224x224 stem) or many taps x channels per output (conv1d): the direct kernel's scalar loads lose
 int conv_direct_gemm_ok(const ConvGeom& g) {
-  return (size_t)g.N * g.Hout * g.Wout >= ((size_t)1 << 18) && direct_kpad(g) <= 64 && g.Cout % 8 == 0;
+  const int Kpad = direct_kpad(g);
+  return g.Cout % 8 == 0 && (((size_t)g.N * g.Hout * g.Wout >= ((size_t)1 << 18) && Kpad <= 64) || (Kpad >= 40 && Kpad <= 2048));
 }
 size_t conv_direct_gemm_wpad_elems(const ConvGeom& g) { return (size_t)g.Cout * direct_kpad(g); }
 
@@ -260,6 +262,58 @@ void conv_direct_fwd_gemm(int dt, hipStream_t st, HView in, const void* w, const
                                         Kpad, (T*)wpad));
   }
   pw_fwd(dt, st, HView{im2col, nullptr, nullptr, 0}, wpad, nullptr, M, Kpad, g.Cout, z, stats, P_out);
+}
+
+// Data gradient of a stride-1 dense convolution as a forward convolution of dz with the taps flipped and the
+// channel roles swapped: dIn[hi][ci] = sum_{i',j',co} dz[hi - (kh-1-ph) + i'][co] * w[co][kh-1-i'][kw-1-j'][ci],
+// run as im2col(dz) x rearranged weights on the MFMA GEMM.
+template <typename T>
+__global__ void dgrad_weights_k(const T* __restrict__ w, int Cout, int kh, int kw, int Cin, int Kpad, T* __restrict__ out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= Cin * Kpad) return;
+  const int ci = i / Kpad, k = i - ci * Kpad;
+  T v = from_f32<T>(0.f);
+  if (k < kh * kw * Cout) {
+    const int tap = k / Cout, co = k - tap * Cout, ti = tap / kw, tj = tap - ti * kw;
+    v = w[(((size_t)co * kh + (kh - 1 - ti)) * kw + (kw - 1 - tj)) * Cin + ci];
+  }
+  out[i] = v;
+}
+
+static ConvGeom dgrad_as_forward(const ConvGeom& g) {
+  ConvGeom d = g;
+  d.Hin = g.Hout; d.Win = g.Wout; d.Cin = g.Cout;
+  d.Hout = g.Hin; d.Wout = g.Win; d.Cout = g.Cin;
+  d.stride = 1; d.ph = g.kh - 1 - g.ph; d.pw = g.kw - 1 - g.pw;
+  return d;
+}
+
+int conv_direct_dgrad_gemm_ok(const ConvGeom& g) {
+  if (g.stride != 1 || g.kh - 1 - g.ph < 0 || g.kw - 1 - g.pw < 0) return 0;
+  const int Kpad = direct_kpad(dgrad_as_forward(g));
+  return Kpad >= 40 && Kpad <= 4096;
+}
+size_t conv_direct_dgrad_gemm_im2col_elems(const ConvGeom& g) {
+  return (size_t)g.N * g.Hin * g.Win * direct_kpad(dgrad_as_forward(g));
+}
+size_t conv_direct_dgrad_gemm_w_elems(const ConvGeom& g) { return (size_t)g.Cin * direct_kpad(dgrad_as_forward(g)); }
+
+void conv_direct_dgrad_gemm(int dt, hipStream_t st, const void* dz, const void* w, const ConvGeom& g, void* im2col, void* wscratch,
+                            void* dIn) {
+  const ConvGeom d = dgrad_as_forward(g);
+  const int Kpad = direct_kpad(d);
+  const size_t M = (size_t)g.N * g.Hin * g.Win;
+  View v{dz, nullptr, nullptr, 0};
+  {
+    const double es = dt == 0 ? 4.0 : 2.0;
+    KScope ks(st, "im2col", ((double)g.N * g.Hout * g.Wout * g.Cout + (double)M * Kpad) * es, 0, (long)M, Kpad, g.Cin);
+    size_t nvec = M * (Kpad / 8);
+    unsigned grid = (unsigned)((nvec + 255) / 256 > 65536 ? 65536 : (nvec + 255) / 256);
+    FTP_DISPATCH(dt, hipLaunchKernelGGL(im2col_k<T>, dim3(grid), dim3(256), 0, st, v, d, Kpad, (T*)im2col));
+    FTP_DISPATCH(dt, hipLaunchKernelGGL(dgrad_weights_k<T>, dim3((g.Cin * Kpad + 255) / 256), dim3(256), 0, st, (const T*)w, g.Cout,
+                                        g.kh, g.kw, g.Cin, Kpad, (T*)wscratch));
+  }
+  pw_fwd(dt, st, HView{im2col, nullptr, nullptr, 0}, wscratch, nullptr, M, Kpad, g.Cin, dIn, nullptr, nullptr);
 }
 
 // ================================================================ depthwise 3x3

@@ -479,30 +479,34 @@ void bn_finalize_apply_small(int dt, hipStream_t st, const BnPending& pend, cons
 }
 
 // ------------------------------------------------------------------ pooling
+// block = (image n, group of 8 channels); 64 lanes walk the positions, fixed-order sum through LDS
 template <typename T>
-__global__ void gap_fwd_k(View in, int N, int HW, int CG, T* __restrict__ out) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= N * CG) return;
-  int n = i / CG, cg = i % CG;
+__global__ __launch_bounds__(64) void gap_fwd_k(View in, int N, int HW, int CG, T* __restrict__ out) {
+  __shared__ float red[64][8];
+  const int i = blockIdx.x, n = i / CG, cg = i % CG, lane = threadIdx.x;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int p = 0; p < HW; ++p) {
+  for (int p = lane; p < HW; p += 64) {
     float v[8];
     view_load8<T>(in, ((size_t)n * HW + p) * CG * 8 + cg * 8, cg * 8, v);
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] += v[e];
   }
-  float inv = 1.f / (float)HW;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) acc[e] *= inv;
-  store8(out + (size_t)i * 8, acc);
+  for (int e = 0; e < 8; ++e) red[lane][e] = acc[e];
+  __syncthreads();
+  if (lane < 8) {
+    float s = 0.f;
+    for (int l = 0; l < 64; ++l) s += red[l][lane];
+    float o = s * (1.f / (float)HW);
+    out[(size_t)i * 8 + lane] = from_f32<T>(o);
+  }
 }
 
 void gap_fwd(int dt, hipStream_t st, HView in, int N, int HW, int C, void* out) {
   View v{in.z, in.scale, in.shift, in.act};
   int n = N * (C / 8);
   KScope ks(st, "gap_fwd", ((double)N * HW * C + (double)N * C) * (dt == 0 ? 4.0 : 2.0), 3.0 * N * HW * C);
-  FTP_DISPATCH(dt, hipLaunchKernelGGL(gap_fwd_k<T>, dim3((n + 127) / 128), dim3(128), 0, st, v, N, HW, C / 8,
-                                      (T*)out));
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(gap_fwd_k<T>, dim3(n), dim3(64), 0, st, v, N, HW, C / 8, (T*)out));
 }
 
 template <typename T>

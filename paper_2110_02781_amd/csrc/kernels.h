@@ -120,6 +120,12 @@ size_t conv_direct_gemm_wpad_elems(const ConvGeom& g);
 void conv_direct_fwd_gemm(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* im2col, void* wpad, void* z,
                           float* stats, int* P_out);
 void conv_direct_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvGeom& g, void* dIn);
+// stride-1 data gradient as im2col(dz) x flipped weights on the GEMM (conv_direct_dgrad_gemm_ok); scratch sizes in elements
+int conv_direct_dgrad_gemm_ok(const ConvGeom& g);
+size_t conv_direct_dgrad_gemm_im2col_elems(const ConvGeom& g);
+size_t conv_direct_dgrad_gemm_w_elems(const ConvGeom& g);
+void conv_direct_dgrad_gemm(int dt, hipStream_t st, const void* dz, const void* w, const ConvGeom& g, void* im2col, void* wscratch,
+                            void* dIn);
 // g_w[Cout][kh][kw][Cin] += dW; im2col: scratch of conv_direct_im2col_elems(g) activation elements
 size_t conv_direct_wgrad_ws(const ConvGeom& g);  // floats of workspace needed
 size_t conv_direct_im2col_elems(const ConvGeom& g);

@@ -310,7 +310,13 @@ extern "C" int ftp_stage_create(const ftp_model* m, int a, int b, int batch, int
       size_t M = (size_t)batch * g.Hout * g.Wout;
       size_t need = sb.type == SUB_DIRECT ? conv_direct_wgrad_ws(g) : sb.type == SUB_DW ? dw_wgrad_ws(g) : pw_wgrad_ws(M, g.Cin, g.Cout);
       if (need > ws_floats) ws_floats = need;
+      if (sb.type == SUB_DIRECT && conv_direct_gemm_ok(g) && conv_direct_gemm_wpad_elems(g) > ws_floats)
+        ws_floats = conv_direct_gemm_wpad_elems(g);      // padded weight copy of the GEMM forward (at most 4 bytes each)
       if (sb.type == SUB_DIRECT && conv_direct_im2col_elems(g) > s->im2col_elems) s->im2col_elems = conv_direct_im2col_elems(g);
+      if (sb.type == SUB_DIRECT && conv_direct_dgrad_gemm_ok(g)) {
+        if (conv_direct_dgrad_gemm_im2col_elems(g) > s->im2col_elems) s->im2col_elems = conv_direct_dgrad_gemm_im2col_elems(g);
+        if (conv_direct_dgrad_gemm_w_elems(g) > ws_floats) ws_floats = conv_direct_dgrad_gemm_w_elems(g);
+      }
     }
     p.out_virtual = (u.d.kind == FTP_UNIT_CONV);
     p.out_off = 0;
@@ -771,7 +777,12 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
     s->join_pending[b] = true;
   }
   if (dIn) {
-    if (sb.type == SUB_DIRECT) conv_direct_dgrad(s->dt, st, dz, w, g, dIn);
+    if (sb.type == SUB_DIRECT) {
+      // the scratch buffers are shared with the weight gradients: fine on one stream, but a stage that runs them on
+      // the side stream keeps the direct kernel
+      if (conv_direct_dgrad_gemm_ok(g) && !stage_overlaps(s) && s->im2col) conv_direct_dgrad_gemm(s->dt, st, dz, w, g, s->im2col, s->ws, dIn);
+      else conv_direct_dgrad(s->dt, st, dz, w, g, dIn);
+    }
     else if (sb.type == SUB_PW) pw_dgrad(s->dt, st, dz, w, res, M, g.Cin, g.Cout, dIn);
     else dw_dgrad(s->dt, st, dz, w, g, dIn);
   }
