@@ -31,6 +31,8 @@ WORKLOADS = {
     2: dict(name="config2: MobileNetV2 w1.0, 32x32x3, 10 classes, batch 32, fp32, whole model as one stage",
             net="mbv2", width=1.0, stem_stride=1, batch=32, in_shape=(32, 32, 3), classes=10, dtype="f32",
             lr=0.01, mu=0.9, wd=4e-5),
+    6: dict(name="1D-CNN 9x128 -> 32/64/64 -> 6 classes at batch 256 (sensor-window workload at a realistic batch), fp32, whole model",
+            net="cnn1d", batch=256, in_shape=(1, 128, 9), classes=6, dtype="f32", lr=0.01, mu=0.9, wd=0.0),
     5: dict(name="config5: MobileNetV2 w1.4, 224x224x3, 1000 classes, batch 128, bf16 (fp32 masters), whole model",
             net="mbv2", width=1.4, stem_stride=2, batch=128, in_shape=(224, 224, 3), classes=1000, dtype="bf16",
             lr=0.01, mu=0.9, wd=4e-5),

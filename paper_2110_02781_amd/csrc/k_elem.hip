@@ -582,19 +582,28 @@ void softmax_ce(int dt, hipStream_t st, const void* logits, const int32_t* label
   hipLaunchKernelGGL(mean_rows_k, dim3(1), dim3(256), 0, st, row_loss, B, loss);
 }
 
+// block = 16 output columns x 16 row lanes; the row lanes' sums meet in LDS in a fixed order
 template <typename T>
-__global__ void bias_grad_k(const T* __restrict__ d, int B, int Nout, float* __restrict__ g) {
-  int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= Nout) return;
+__global__ __launch_bounds__(256) void bias_grad_k(const T* __restrict__ d, int B, int Nout, float* __restrict__ g) {
+  __shared__ float red[16][17];
+  const int jl = threadIdx.x & 15, lane = threadIdx.x >> 4;
+  const int j = blockIdx.x * 16 + jl;
   float s = 0.f;
-  for (int b = 0; b < B; ++b) s += to_f32(d[(size_t)b * Nout + j]);
-  g[j] += s;
+  if (j < Nout)
+    for (int b = lane; b < B; b += 16) s += to_f32(d[(size_t)b * Nout + j]);
+  red[lane][jl] = s;
+  __syncthreads();
+  if (lane == 0 && j < Nout) {
+    float t = 0.f;
+#pragma unroll
+    for (int l = 0; l < 16; ++l) t += red[l][jl];
+    g[j] += t;
+  }
 }
 
 void bias_grad(int dt, hipStream_t st, const void* d, int B, int Nout, float* g_bias) {
   KScope ks(st, "bias_grad", (double)B * Nout * (dt == 0 ? 4.0 : 2.0) + 8.0 * Nout, 1.0 * B * Nout);
-  FTP_DISPATCH(dt, hipLaunchKernelGGL(bias_grad_k<T>, dim3((Nout + 127) / 128), dim3(128), 0, st,
-                                      (const T*)d, B, Nout, g_bias));
+  FTP_DISPATCH(dt, hipLaunchKernelGGL(bias_grad_k<T>, dim3((Nout + 15) / 16), dim3(256), 0, st, (const T*)d, B, Nout, g_bias));
 }
 
 // -------------------------------------------------------------------- SGD

@@ -100,6 +100,24 @@ def test_config1_cnn1d_train_steps():
         pair.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_cnn1d_at_a_larger_batch(dtype):
+    """The 1-D CNN at batch 40 (5120 positions per layer): the convolutions leave the short-problem kernels and
+    run as patch matrix + row-streaming MFMA GEMM (forward, data gradient, weight gradient)."""
+    print(f"cnn1d batch 40 {dtype}", flush=True)
+    o, h = OM.cnn1d(), hip_models().cnn1d_units()
+    if dtype == "f32":
+        pair = Pair(o, h, (1, 128, 9), 40, 0, 6, "f32", seed=17)
+        try:
+            train_step_check(pair, 17, 6, TOL["f32"], steps=2, wd=0.0)
+        finally:
+            pair.close()
+    else:
+        from oracle.stage import bf16_round
+        x = bf16_round(synth.normal(17, "x0", (40, 1, 128, 9)))
+        unitwise_check(o, h, (1, 128, 9), 40, 0, 6, "bf16", 17, x, labels=synth.labels(17, "labels0", 40, 6))
+
+
 def small_net():
     us = [conv_unit(3, 8, 3, 3, 1, 1, 1, L.ACT_RELU6), invres_unit(8, 8, 1, 1), invres_unit(8, 16, 2, 6),
           invres_unit(16, 16, 1, 6), invres_unit(16, 24, 1, 6), conv_unit(24, 32, 1, 1, 1, 0, 0, L.ACT_RELU6)]
