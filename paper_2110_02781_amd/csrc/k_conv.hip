@@ -983,7 +983,7 @@ static DwPlan dw_wgrad_plan(const ConvGeom& g, int es, size_t* lds) {
   d.PH = (d.TH - 1) * s + 3;
   d.PW = (d.segw * 4 - 1) * s + 3;
   d.ntiles = g.N * d.tiles_h * d.tiles_w;
-  const int cap = 1024 / d.nslab > 1 ? 1024 / d.nslab : 1;   // about 1024 persistent blocks over all slabs
+  const int cap = 512 / d.nslab > 1 ? 512 / d.nslab : 1;   // about 512 persistent blocks over all slabs
   d.nblocks = d.ntiles < cap ? d.ntiles : cap;
   size_t a = (size_t)d.PH * d.PW * d.CGB * 8 * 4;
   size_t b = (size_t)d.spp * 9 * 2 * d.CGB * 16;
