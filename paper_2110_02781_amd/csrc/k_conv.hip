@@ -432,6 +432,7 @@ template <typename T, int S, bool FLIP>
 __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ w, DwPlan d, int Hin, int Win, int Hout,
                                                  int Wout, int C, T* __restrict__ out) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  if (FLIP) __builtin_amdgcn_s_setprio(3);   // data-gradient chain: ahead of the weight-gradient stream's waves
   float* patch = reinterpret_cast<float*>(smem_raw);
   float* wl = patch + (size_t)d.PH * d.PW * d.CGB * 8;
   const int lb = xcd_logical_block();
@@ -832,6 +833,7 @@ __global__ __launch_bounds__(256) void dw_dgrad_s2_k(const T* __restrict__ dz, c
   const int tile = lb % d.ntiles, slab = lb / d.ntiles;
   const int tw = tile % d.tiles_w, th = (tile / d.tiles_w) % d.tiles_h, n = tile / (d.tiles_w * d.tiles_h);
   const int h0 = th * d.TH, w0 = tw * d.TW, cg0 = slab * d.CGB;       // tile origin, even
+  __builtin_amdgcn_s_setprio(3);             // data-gradient chain: ahead of the weight-gradient stream's waves
   const int ho_lo = h0 / 2, wo_lo = w0 / 2;
   DwPatch<T> lp;
   View none{nullptr, nullptr, nullptr, 0};

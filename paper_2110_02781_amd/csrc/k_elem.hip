@@ -190,6 +190,7 @@ __global__ void bn_bwd_reduce_k(const T* __restrict__ dA, const T* __restrict__ 
                                 const float* __restrict__ scale, const float* __restrict__ shift,
                                 int W, int R, size_t rpb, float* __restrict__ partial) {
   extern __shared__ float smem[];
+  __builtin_amdgcn_s_setprio(3);     // data-gradient chain: ahead of the weight-gradient stream's waves on a shared SIMD
   int tx = threadIdx.x % W, ty = threadIdx.x / W;
   int cg = blockIdx.y * W + tx;
   float acc[16];
@@ -276,6 +277,7 @@ template <typename T, int ACT>
 __global__ void bn_bwd_apply_k(const T* __restrict__ dA, const T* __restrict__ z, size_t M, int C,
                                const float* __restrict__ scale, const float* __restrict__ shift,
                                const float* __restrict__ coef, int W, int R, size_t rpb, T* __restrict__ dz) {
+  __builtin_amdgcn_s_setprio(3);     // data-gradient chain: ahead of the weight-gradient stream's waves on a shared SIMD
   const int tx = threadIdx.x % W, ty = threadIdx.x / W;
   const int cg = blockIdx.y * W + tx;
   if (cg >= C / 8) return;

@@ -610,6 +610,7 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
   constexpr int BUF = (TI + BJ) * LD;
   __shared__ __attribute__((aligned(16))) T smem[2 * BUF];
   __shared__ float red[4][64][4];
+  if (MODE == MODE_DGRAD) __builtin_amdgcn_s_setprio(3);   // data-gradient chain: ahead of the weight-gradient stream's waves
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int lb = xcd_logical_block();
