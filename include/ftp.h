@@ -200,6 +200,21 @@ int ftp_solve_partition(const double* layer_costs, int L, const double* device_c
 int ftp_estimate_capacity(double stage_time, const double* layer_costs, int L, int start, int end,
                           double* capacity);
 
+/* Online execution profiling (section "Dynamic Model Partition", execution
+ * profiling phase: every worker records the execution time of every batch and
+ * reports the average, which becomes the numerator of its capacity).
+ * ftp_stage_timing(stage, 1) starts recording, per forwarded batch, the time of
+ * its forward plus its backward on the streams they were enqueued on (HIP
+ * events; up to 256 batches between reads, later ones are not recorded);
+ * ftp_stage_timing(stage, 0) stops and discards.  Switch only while no batch is
+ * in flight.  ftp_stage_timing_read waits for the recorded batches, returns their
+ * number and the mean forward+backward time in nanoseconds (0 if none), and
+ * starts a new window; batches in flight at that moment are left out.  Feed the
+ * mean to ftp_estimate_capacity together with the profiled costs of the stage's
+ * units.  Off by default: a step then records no events at all. */
+int ftp_stage_timing(ftp_stage*, int enable);
+int ftp_stage_timing_read(ftp_stage*, double* mean_ns, int* n_batches);
+
 /* Weight redistribution after a re-partition or a single worker failure (the
  * paper's Algorithm "Weight Redistribution", sections "Dynamic Model Partition"
  * and "Fault Tolerance Mechanism"), for the worker that holds stage i_cur of

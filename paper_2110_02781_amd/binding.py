@@ -86,6 +86,8 @@ _SIGS = {
     "ftp_estimate_capacity": (_i, [C.c_double, _dp, _i, _i, _i, _dp]),
     "ftp_redistribution_plan": (_i, [C.POINTER(C.c_int32), _i, C.POINTER(C.c_int32), _i, _i, _i, _i, C.POINTER(C.c_int32)]),
     "ftp_stage_copy_units": (_i, [_vp, _vp, _i, _i, _vp]),
+    "ftp_stage_timing": (_i, [_vp, _i]),
+    "ftp_stage_timing_read": (_i, [_vp, _dp, C.POINTER(C.c_int)]),
     "ftp_calibration_copy": (_i, [_vp, _vp, _sz, _vp]),
     "ftp_ktrace_begin": (_i, [_i]),
     "ftp_ktrace_end": (_i, [C.POINTER(KtraceRow), _i, C.POINTER(_i)]),
@@ -310,3 +312,14 @@ def redistribution_plan(bounds_new, bounds_cur, i_fail, i_cur, i_new):
 
 def stage_copy_units(dst, src, unit_lo, unit_hi, stream=None):
     _chk(lib.ftp_stage_copy_units(dst, src, unit_lo, unit_hi, _ptr(stream)))
+
+
+def stage_timing(stage, enable):
+    _chk(lib.ftp_stage_timing(stage, 1 if enable else 0))
+
+
+def stage_timing_read(stage):
+    """Returns (mean forward+backward nanoseconds per batch, number of batches) since the last read."""
+    mean, n = C.c_double(0.0), C.c_int(0)
+    _chk(lib.ftp_stage_timing_read(stage, C.byref(mean), C.byref(n)))
+    return mean.value, n.value

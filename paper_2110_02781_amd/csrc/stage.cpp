@@ -211,6 +211,7 @@ struct Slot {
   char* stash = nullptr;
   float* stats = nullptr;
   float* snap_w = nullptr;   // fp32 parameter snapshot
+  int timer_idx = -1;        // ring entry of the batch in this slot when execution timing is on
   void* snap_lp = nullptr;   // bfloat16 working-copy snapshot
   void* dlogits = nullptr;
   bool busy = false, has_snap = false, has_loss = false;
@@ -218,6 +219,16 @@ struct Slot {
 
 struct ProfEvents {          // optional per-unit timing (profile_layers)
   std::vector<hipEvent_t> f0, f1, b0, b1;
+};
+
+// Optional per-batch execution time of the stage (the online profiling that feeds the capacity estimate):
+// a ring of event quadruples, one per forwarded batch, harvested by ftp_stage_timing_read.
+struct ExecTimer {
+  enum { kRing = 256 };
+  hipEvent_t ev[kRing][4];       // forward begin/end, backward begin/end
+  bool bwd_done[kRing];
+  int used = 0;                  // entries handed out since the last read
+  bool created = false;
 };
 
 struct ftp_stage {
@@ -245,6 +256,7 @@ struct ftp_stage {
   bool has_loss = false;
   int classes = 0;
   ProfEvents* prof = nullptr;
+  ExecTimer* timer = nullptr;   // non-null while execution timing is enabled
 };
 
 static inline void dfree(void* p) { if (p) (void)hipFree(p); }
@@ -260,6 +272,12 @@ static void stage_free(ftp_stage* s) {
     if (s->ev_join[i]) (void)hipEventDestroy(s->ev_join[i]);
   }
   dfree(s->bn_part); dfree(s->coef); dfree(s->ws); dfree(s->row_loss); dfree(s->im2col);
+  if (s->timer) {
+    if (s->timer->created)
+      for (auto& q : s->timer->ev)
+        for (auto& e : q) (void)hipEventDestroy(e);
+    delete s->timer;
+  }
   delete s;
 }
 
@@ -558,6 +576,12 @@ extern "C" int ftp_stage_forward(ftp_stage* s, int slot, const void* x_dev, void
   hipStream_t st = (hipStream_t)stream;
   const UnitInfo& first = *s->plan[0].info;
   size_t xin = (size_t)s->batch * first.inH * first.inW * first.inC * s->es;
+  sl.timer_idx = -1;
+  if (s->timer && s->timer->used < ExecTimer::kRing) {
+    sl.timer_idx = s->timer->used++;
+    s->timer->bwd_done[sl.timer_idx] = false;
+    HIP_TRY(hipEventRecord(s->timer->ev[sl.timer_idx][0], st));
+  }
   HIP_TRY(hipMemcpyAsync(sl.stash, x_dev, xin, hipMemcpyDeviceToDevice, st));
   Views v;
   build_views(s, sl, &v);
@@ -625,6 +649,7 @@ extern "C" int ftp_stage_forward(ftp_stage* s, int slot, const void* x_dev, void
       HIP_TRY(hipMemcpyAsync(y_dev, src, M * u.outC * s->es, hipMemcpyDeviceToDevice, st));
     }
   }
+  if (s->timer && sl.timer_idx >= 0) HIP_TRY(hipEventRecord(s->timer->ev[sl.timer_idx][1], st));
   HIP_TRY(hipGetLastError());
   sl.busy = true; sl.has_snap = false; sl.has_loss = false;
   return FTP_OK;
@@ -809,6 +834,7 @@ extern "C" int ftp_stage_backward(ftp_stage* s, int slot, const void* dy_dev, vo
     return FTP_ERR_ARG;
   }
   hipStream_t st = (hipStream_t)stream;
+  if (s->timer && sl.timer_idx >= 0) HIP_TRY(hipEventRecord(s->timer->ev[sl.timer_idx][2], st));
   Views v;
   build_views(s, sl, &v);
   WeightSet W{sl.has_snap ? sl.snap_w : s->params, (const char*)(sl.has_snap ? sl.snap_lp : s->w_lp)};
@@ -881,8 +907,58 @@ extern "C" int ftp_stage_backward(ftp_stage* s, int slot, const void* dy_dev, vo
     if (produced && next) { d = next; if (i > 0) flip ^= 1; }
   }
   if ((rc = join_side(s, st))) return rc;
+  if (s->timer && sl.timer_idx >= 0) {
+    HIP_TRY(hipEventRecord(s->timer->ev[sl.timer_idx][3], st));
+    s->timer->bwd_done[sl.timer_idx] = true;
+    sl.timer_idx = -1;
+  }
   HIP_TRY(hipGetLastError());
   sl.busy = false; sl.has_snap = false; sl.has_loss = false;
+  return FTP_OK;
+}
+
+extern "C" int ftp_stage_timing(ftp_stage* s, int enable) {
+  if (!s) { ftp_set_error("stage_timing: NULL stage"); return FTP_ERR_ARG; }
+  for (auto& sl : s->slots)
+    if (sl.busy) { ftp_set_error("stage_timing: switch it while no batch is in flight"); return FTP_ERR_SLOT; }
+  if (!enable) {
+    if (s->timer) {
+      if (s->timer->created)
+        for (auto& q : s->timer->ev)
+          for (auto& e : q) (void)hipEventDestroy(e);
+      delete s->timer;
+      s->timer = nullptr;
+    }
+    return FTP_OK;
+  }
+  if (!s->timer) {
+    s->timer = new ExecTimer();
+    for (auto& q : s->timer->ev)
+      for (auto& e : q) HIP_TRY(hipEventCreate(&e));
+    s->timer->created = true;
+  }
+  s->timer->used = 0;
+  return FTP_OK;
+}
+
+extern "C" int ftp_stage_timing_read(ftp_stage* s, double* mean_ns, int* n_batches) {
+  if (!s || !mean_ns || !n_batches) { ftp_set_error("stage_timing_read: NULL argument"); return FTP_ERR_ARG; }
+  if (!s->timer) { ftp_set_error("stage_timing_read: execution timing is not enabled"); return FTP_ERR_ARG; }
+  double sum = 0.0;
+  int n = 0;
+  for (int i = 0; i < s->timer->used; ++i) {
+    if (!s->timer->bwd_done[i]) continue;              // forwarded, not yet backwarded: not a whole batch
+    float f = 0.f, b = 0.f;
+    HIP_TRY(hipEventSynchronize(s->timer->ev[i][3]));
+    HIP_TRY(hipEventElapsedTime(&f, s->timer->ev[i][0], s->timer->ev[i][1]));
+    HIP_TRY(hipEventElapsedTime(&b, s->timer->ev[i][2], s->timer->ev[i][3]));
+    sum += ((double)f + (double)b) * 1e6;
+    ++n;
+  }
+  for (auto& sl : s->slots) sl.timer_idx = -1;         // batches in flight are dropped from the measurement
+  s->timer->used = 0;
+  *n_batches = n;
+  *mean_ns = n ? sum / n : 0.0;
   return FTP_OK;
 }
 

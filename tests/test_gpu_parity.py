@@ -376,6 +376,45 @@ def test_repartition_moves_units_between_stages_on_the_device():
         A.close()
 
 
+def test_online_execution_timing_feeds_the_capacity_estimate():
+    """Execution profiling phase of the dynamic partition: the stage records forward+backward time per batch,
+    the mean over the window and the profiled unit costs give the worker's capacity (about 1 on the device that
+    did the profiling), and the solver accepts it.  Batches in flight at the read are left out."""
+    import paper_2110_02781_amd as P
+    print("online execution timing -> capacity -> partition", flush=True)
+    o, h = small_net()
+    L = len(o)
+    pair = Pair(o, h, (9, 11, 3), 4, 0, L, "f32", seed=41, n_slots=2)
+    try:
+        costs, out_bytes = P.profile_layers(pair.model, 4, 3)
+        assert len(costs) == L and all(c > 0 for c in costs)
+        with pytest.raises(RuntimeError):
+            P.stage_timing_read(pair.stage)                   # not enabled
+        P.stage_timing(pair.stage, True)
+        x = synth.normal(41, "x", (4, 9, 11, 3))
+        labels = synth.labels(41, "l", 4, 10)
+        for _ in range(5):
+            pair.forward(0, x); pair.loss(0, labels)
+            pair.backward(0, None, want_dx=False)
+            pair.update(0.01, 0.9, 0.0)
+        pair.forward(1, x)                                    # in flight: not a whole batch yet
+        mean_ns, n = P.stage_timing_read(pair.stage)
+        assert n == 5 and mean_ns > 0
+        cap = P.estimate_capacity(mean_ns, costs, 0, L - 1)
+        assert 0.05 < cap < 20.0, cap                         # same device as the profile: order one
+        bounds, bottleneck = P.solve_partition(costs, [cap, 3.0 * cap])
+        assert bounds[0] == 0 and bounds[-1] == L and bounds[1] > L // 2 - 1      # the faster device takes more
+        mean2, n2 = P.stage_timing_read(pair.stage)
+        assert n2 == 0 and mean2 == 0.0                       # new window, the in-flight batch was dropped
+        pair.loss(1, labels); pair.backward(1, None, want_dx=False)
+        with pytest.raises(RuntimeError):
+            pair.forward(0, x); P.stage_timing(pair.stage, False)     # a batch is in flight
+        pair.loss(0, labels); pair.backward(0, None, want_dx=False)
+        P.stage_timing(pair.stage, False)
+    finally:
+        pair.close()
+
+
 def test_weight_stashing_matters_on_gpu():
     """Without the snapshot the backward uses the newer weights: results must differ from the stashed run."""
     o, h = small_net()
