@@ -67,8 +67,13 @@ def _conv_bn_act_bwd(da, c, w, gamma, stride, ph, pw, groups, act, q=_identity, 
 
 
 class Stage:
-    def __init__(self, units, in_shape, a, b, n_slots=1, dtype=np.float64, storage=None):
+    def __init__(self, units, in_shape, a, b, n_slots=1, dtype=np.float64, storage=None, recompute=False):
         """units: full unit list; in_shape: (H, W, C) of the model input.
+        recompute=True: a slot keeps only the stage input of its batch (and the weight
+        version); the backward first runs the forward again to get the intermediates
+        back (section "Synchronous Pipeline Parallelism Training": intermediates are
+        thrown away and re-computed when the gradient arrives).  The second forward
+        is not a training forward: the BatchNorm running statistics do not move.
         storage='bf16' models mixed-precision training: every tensor that such a
         run keeps in bfloat16 (convolution / FC outputs, block outputs, pooled
         features, BatchNorm+activation outputs, activation gradients, and the
@@ -94,12 +99,16 @@ class Stage:
             self.mom[i] = [np.zeros(s, dtype) for _, s, _, _ in specs]
             self.bn_run[i] = [[np.zeros(c, dtype), np.ones(c, dtype)] for c in M.bn_channels(units[i])]
         self.slots = [None] * n_slots
+        self.recompute = recompute
+        self._tracking = True
 
     def set_params(self, i, arrays):
         self.params[i] = [np.array(p, dtype=self.dtype) for p in arrays]
 
     # ---------------------------------------------------------------- forward
     def _bn_track(self, i, k, c):
+        if not self._tracking:
+            return
         cnt = c['z'].size // c['z'].shape[-1]
         rm, rv = self.bn_run[i][k]
         self.bn_run[i][k] = list(L.bn_running_update(rm, rv, c['mean'], c['var'], cnt))
@@ -147,7 +156,21 @@ class Stage:
         h = self.q(h)                                        # the stage output is a stored tensor
         self.slots[slot] = dict(caches=caches, params=P if stash_weights else None, out=h, dlogits=None,
                                 unit_in=unit_in)
+        if self.recompute:
+            self.slots[slot].update(caches=None, unit_in=None, x=x)
         return h
+
+    def _recompute(self, s, P):
+        """The intermediates of a slot that kept only its input, from the weights P."""
+        self._tracking = False
+        try:
+            caches, h, unit_in = {}, s['x'], {}
+            for i in range(self.a, self.b):
+                unit_in[i] = h
+                h, caches[i] = self._unit_fwd(i, h, P[i])
+        finally:
+            self._tracking = True
+        s['caches'], s['unit_in'] = caches, unit_in
 
     def loss(self, slot, labels):
         assert self.units[self.b - 1].kind == 'loss'
@@ -206,6 +229,8 @@ class Stage:
         d = s['dlogits'] if dy is None else np.asarray(dy, dtype=self.dtype)
         assert d is not None
         P = s['params'] if s['params'] is not None else self.params
+        if s['caches'] is None:
+            self._recompute(s, P)
         self.tie_report = dict(ties=0, adopted=0, disagree=0)
         ties = None if tie_breaks is None else dict(on=tie_breaks, guard=guard, report=self.tie_report)
         self.unit_in, self.unit_dout = s['unit_in'], {}     # kept for unit-by-unit checks

@@ -333,3 +333,61 @@ def test_aggregate_is_the_mean_of_the_stashed_versions():
         for p, a, b in zip(st.params[i], w0[i], w1[i]):
             np.testing.assert_allclose(p, (a.astype(np.float64) + b.astype(np.float64)) / 2, rtol=0, atol=1e-7)
     assert all(np.array_equal(m, n) for i in range(len(units)) for m, n in zip(st.mom[i], mom[i]))
+
+
+# ------------------------------------------------------------ recomputation
+def _run_1f1b(recompute, storage=None, n_batches=5):
+    units, in_shape, seed = small_mbv2(), (8, 8, 3), 23
+    st = Stage(units, in_shape, 0, len(units), n_slots=3, storage=storage, recompute=recompute)
+    P = M.init_params(units, seed)
+    for i in range(len(units)):
+        st.set_params(i, P[i])
+    xs = [synth.normal(seed, f"x{b}", (4,) + in_shape) for b in range(n_batches)]
+    ls = [synth.labels(seed, f"l{b}", 4, 10) for b in range(n_batches)]
+    losses, held = [], []
+    for op, b in one_f_one_b_order(0, 3, n_batches):
+        if op == 'F':
+            st.forward(b % 3, xs[b])
+            losses.append(st.loss(b % 3, ls[b]))
+            held.append(st.slots[b % 3]['caches'] is None)
+        else:
+            st.backward(b % 3)
+            st.update(0.05, 0.9, 4e-5)
+    return st, losses, held
+
+
+@pytest.mark.parametrize("storage", [None, "bf16"])
+def test_recomputation_gives_the_same_training_run(storage):
+    """Throwing the intermediates away and running the forward again from the stashed
+    input and the stashed weight version changes nothing: weights, momentum, running
+    statistics and losses along a one-forward-one-backward run are identical."""
+    a, la, held_a = _run_1f1b(False, storage)
+    b, lb, held_b = _run_1f1b(True, storage)
+    assert not any(held_a) and all(held_b)          # the recomputing slots really hold no intermediates
+    assert la == lb
+    for i in range(len(a.units)):
+        for p, q in zip(a.params[i], b.params[i]):
+            assert np.array_equal(p, q)
+        for p, q in zip(a.mom[i], b.mom[i]):
+            assert np.array_equal(p, q)
+        for (m0, v0), (m1, v1) in zip(a.bn_run[i], b.bn_run[i]):
+            assert np.array_equal(m0, m1) and np.array_equal(v0, v1)
+
+
+def test_recomputation_moves_running_statistics_once_per_batch():
+    """Closed form: K training forwards of the same batch with fixed weights leave the
+    running mean at (1 - 0.9^K) * mean and the running variance at 0.9^K + (1 - 0.9^K) * var
+    (unbiased); a recomputation that counted as a training forward would give 0.9^(2K)."""
+    units, in_shape, seed, K = small_mbv2(), (8, 8, 3), 29, 3
+    st = Stage(units, in_shape, 0, 1, recompute=True)
+    st.set_params(0, M.init_params(units, seed)[0])
+    x = synth.normal(seed, "x", (4,) + in_shape)
+    dy = synth.normal(seed, "dy", (4, 8, 8, 8))
+    z = L.conv2d_fwd(x, st.params[0][0], 1, 1, 1, 1).reshape(-1, 8)
+    for _ in range(K):
+        st.forward(0, x)
+        st.backward(0, dy)
+    rm, rv = st.bn_run[0][0]
+    f = 0.9 ** K
+    np.testing.assert_allclose(rm, (1 - f) * z.mean(0), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(rv, f + (1 - f) * z.var(0, ddof=1), rtol=1e-12, atol=1e-14)
