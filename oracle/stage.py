@@ -160,6 +160,12 @@ class Stage:
             self.slots[slot].update(caches=None, unit_in=None, x=x)
         return h
 
+    def materialize(self, slot):
+        """Run the second forward of a recomputing slot now (backward does it on demand)."""
+        s = self.slots[slot]
+        if s['caches'] is None:
+            self._recompute(s, s['params'] if s['params'] is not None else self.params)
+
     def _recompute(self, s, P):
         """The intermediates of a slot that kept only its input, from the weights P."""
         self._tracking = False
