@@ -253,6 +253,59 @@ def bench_aggregate(config, versions=3, reps=50, seed=2110):
                 alg_GBps=round(nbytes / (us * 1e-6) / 1e9, 1), frac_of_hbm_peak=round(nbytes / (us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4))
 
 
+def bench_recompute(config, micro=4, reps=3, seed=2110):
+    """Recomputation as a memory / time trade: `micro` micro-batches forwarded, then backwarded, then one update
+    (the synchronous pipeline order), once with stages that keep every intermediate per micro-batch and once with
+    slots that keep only their input and run the forward again in the backward."""
+    import torch
+    import synth
+    import paper_2110_02781_amd as P
+
+    w = WORKLOADS[config]
+    dev = torch.device("cuda:0")
+    tdt = torch.float32 if w["dtype"] == "f32" else torch.bfloat16
+    units = build_units(P, w)
+    H, W_, C = w["in_shape"]
+    batch = w["batch"]
+    model = P.model_create(units, H, W_, C, P.F32 if w["dtype"] == "f32" else P.BF16)
+    L = P.model_num_units(model)
+    params = P.models.init_unit_params(units, seed)
+    x = torch.from_numpy(synth.normal(seed, "x", (batch, H, W_, C)).astype(np.float32)).to(dev).to(tdt)
+    labels = torch.from_numpy(synth.labels(seed, "labels", batch, w["classes"]).astype(np.int32)).to(dev)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    stream = torch.cuda.Stream()
+    sp = stream.cuda_stream
+    res = {}
+    for name, flags in (("keep", 0), ("recompute", P.STAGE_RECOMPUTE)):
+        stage = P.stage_create(model, 0, L, batch, micro, flags)
+        for i in range(L):
+            P.stage_import_weights(stage, i, params[i])
+
+        def mini_batch():
+            for sl in range(micro):
+                P.stage_forward(stage, sl, x, None, sp)
+                P.stage_loss(stage, sl, labels, loss, sp)
+            for sl in range(micro):
+                P.stage_backward(stage, sl, None, None, sp)
+            P.stage_update(stage, 0.01 / micro, 0.9, 4e-5, sp)
+        mini_batch()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(stream):
+            e0.record(stream)
+            for _ in range(reps):
+                mini_batch()
+            e1.record(stream)
+        stream.synchronize()
+        res[name] = dict(ms_per_mini_batch=round(e0.elapsed_time(e1) / reps, 3), device_GiB=round(P.stage_device_bytes(stage) / 2**30, 2))
+        P.stage_destroy(stage)
+        torch.cuda.synchronize()
+    P.model_destroy(model)
+    return dict(workload=w["name"], micro_batches=micro, **res,
+                time_ratio=round(res["recompute"]["ms_per_mini_batch"] / res["keep"]["ms_per_mini_batch"], 3),
+                memory_ratio=round(res["recompute"]["device_GiB"] / res["keep"]["device_GiB"], 3))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -291,9 +344,10 @@ def main():
         also.append(r)
 
     # the widened row: weight aggregation over three stashed versions, on the larger parameter set
-    agg = None
+    agg = rec = None
     if also and not args.no_ktrace:
         agg = bench_aggregate(also_cfgs[0] if also_cfgs[0] in WORKLOADS else args.config, 3, 50, args.seed)
+        rec = bench_recompute(also_cfgs[0] if also_cfgs[0] in WORKLOADS else args.config, 4, 3, args.seed)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -307,7 +361,7 @@ def main():
         "config": {"workload": main_res["workload"], "batch": main_res["batch"], "units": main_res["units"],
                    "hip_graph": main_res["hip_graph"], "final_loss": main_res["final_loss"]},
         "roofline": main_res["roofline"], "cpu_baseline": cpu, "kernels": main_res["kernels"], "also": also,
-        "aggregate": agg,
+        "aggregate": agg, "recompute": rec,
     }
     print(json.dumps(out))
 

@@ -110,7 +110,21 @@ int ftp_model_unit_bn_channels(const ftp_model*, int u, size_t* n);
  * start at zero (import them), momentum and gradients at zero, BN running mean
  * 0 / variance 1. */
 int ftp_stage_create(const ftp_model*, int a, int b, int batch, int n_slots, ftp_stage** out);
+/* The same with options.  FTP_STAGE_RECOMPUTE: a slot keeps only the stage input of its batch (and, after
+ * ftp_stage_snapshot_weights, its weight version); the intermediates of the batch forwarded last live in one
+ * stash that all slots share, and the backward of any other slot first runs the forward again from the kept
+ * input with that slot's weights (paper, section "Synchronous Pipeline Parallelism Training": intermediates
+ * are thrown away and re-computed when the gradient arrives).  The second forward leaves the BatchNorm running
+ * statistics alone, and the kernels being deterministic, a run gives bit for bit the weights of a stage
+ * that keeps everything.  Memory: one stash + n_slots inputs instead of n_slots stashes.  With this option
+ * ftp_stage_loss(slot) must follow ftp_stage_forward(slot) before any other forward (the logits are not kept),
+ * and ftp_stage_export_conv_output sees only the slot forwarded or recomputed last.
+ * Unknown flag bits: FTP_ERR_ARG. */
+enum { FTP_STAGE_RECOMPUTE = 1 };
+int ftp_stage_create_ex(const ftp_model*, int a, int b, int batch, int n_slots, unsigned flags, ftp_stage** out);
 void ftp_stage_destroy(ftp_stage*);
+/* Device memory, in bytes, that the stage allocated at creation (host pointer out). */
+int ftp_stage_device_bytes(const ftp_stage*, size_t* bytes);
 
 /* Host <-> device copies of one unit's parameter vector (layout above), its
  * accumulated gradient, its momentum buffer, and its BN running statistics

@@ -67,6 +67,8 @@ _SIGS = {
     "ftp_model_unit_param_count": (_i, [_vp, _i, C.POINTER(_sz)]),
     "ftp_model_unit_bn_channels": (_i, [_vp, _i, C.POINTER(_sz)]),
     "ftp_stage_create": (_i, [_vp, _i, _i, _i, _i, C.POINTER(_vp)]),
+    "ftp_stage_create_ex": (_i, [_vp, _i, _i, _i, _i, C.c_uint, C.POINTER(_vp)]),
+    "ftp_stage_device_bytes": (_i, [_vp, C.POINTER(_sz)]),
     "ftp_stage_destroy": (None, [_vp]),
     "ftp_stage_import_weights": (_i, [_vp, _i, _fp, _sz]),
     "ftp_stage_export_weights": (_i, [_vp, _i, _fp, _sz]),
@@ -168,10 +170,22 @@ def model_unit_bn_channels(model, u):
 
 
 # ---- stage ---------------------------------------------------------------------
-def stage_create(model, a, b, batch, n_slots=1):
+STAGE_RECOMPUTE = 1
+
+
+def stage_create(model, a, b, batch, n_slots=1, flags=0):
     out = _vp()
-    _chk(lib.ftp_stage_create(model, a, b, batch, n_slots, C.byref(out)))
+    if flags:
+        _chk(lib.ftp_stage_create_ex(model, a, b, batch, n_slots, flags, C.byref(out)))
+    else:
+        _chk(lib.ftp_stage_create(model, a, b, batch, n_slots, C.byref(out)))
     return out
+
+
+def stage_device_bytes(stage):
+    n = _sz(0)
+    _chk(lib.ftp_stage_device_bytes(stage, C.byref(n)))
+    return int(n.value)
 
 
 def stage_destroy(stage):

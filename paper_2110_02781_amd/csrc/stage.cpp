@@ -208,7 +208,8 @@ struct UnitPlan {
 };
 
 struct Slot {
-  char* stash = nullptr;
+  char* stash = nullptr;     // intermediates; with recomputation all slots point at the stage's one shared stash
+  char* xin_keep = nullptr;  // recomputation: the slot's own copy of its stage input
   float* stats = nullptr;
   float* snap_w = nullptr;   // fp32 parameter snapshot
   int timer_idx = -1;        // ring entry of the batch in this slot when execution timing is on
@@ -257,6 +258,13 @@ struct ftp_stage {
   int classes = 0;
   ProfEvents* prof = nullptr;
   ExecTimer* timer = nullptr;   // non-null while execution timing is enabled
+  // Recomputation: slots keep only their stage input; the intermediates of the batch whose forward ran last
+  // live in one shared stash, and a backward of any other slot first runs the forward again.
+  bool recompute = false;
+  char* shared_stash = nullptr;
+  int stash_owner = -1;         // slot whose intermediates the shared stash holds
+  float bn_mom = kBnMomentum;   // 0 while a forward is being recomputed: running statistics stay put
+  size_t dev_bytes = 0;         // device memory the stage allocated
 };
 
 static inline void dfree(void* p) { if (p) (void)hipFree(p); }
@@ -264,7 +272,8 @@ static inline void dfree(void* p) { if (p) (void)hipFree(p); }
 static void stage_free(ftp_stage* s) {
   if (!s) return;
   dfree(s->params); dfree(s->grads); dfree(s->mom); dfree(s->run_mean); dfree(s->run_var); dfree(s->w_lp);
-  for (auto& sl : s->slots) { dfree(sl.stash); dfree(sl.stats); dfree(sl.snap_w); dfree(sl.snap_lp); dfree(sl.dlogits); }
+  for (auto& sl : s->slots) { if (!s->recompute) dfree(sl.stash); dfree(sl.xin_keep); dfree(sl.stats); dfree(sl.snap_w); dfree(sl.snap_lp); dfree(sl.dlogits); }
+  dfree(s->shared_stash);
   for (int i = 0; i < 5; ++i) dfree(s->gbuf[i]);
   if (s->side) (void)hipStreamDestroy(s->side);
   for (int i = 0; i < 2; ++i) {
@@ -283,23 +292,29 @@ static void stage_free(ftp_stage* s) {
 
 extern "C" void ftp_stage_destroy(ftp_stage* s) { stage_free(s); }
 
+static thread_local size_t g_alloc_total = 0;
+
 template <typename P>
 static int dev_alloc(P** p, size_t bytes) {
   void* q = nullptr;
   hipError_t e = hipMalloc(&q, align_up(bytes ? bytes : 1, 256));
   if (e != hipSuccess) { ftp_set_error("hipMalloc(%zu bytes) failed: %s", bytes, hipGetErrorString(e)); return FTP_ERR_NOMEM; }
   *p = (P*)q;
+  g_alloc_total += align_up(bytes ? bytes : 1, 256);
   return FTP_OK;
 }
 
-extern "C" int ftp_stage_create(const ftp_model* m, int a, int b, int batch, int n_slots, ftp_stage** out) {
+extern "C" int ftp_stage_create_ex(const ftp_model* m, int a, int b, int batch, int n_slots, unsigned flags, ftp_stage** out) {
   if (!m || !out) { ftp_set_error("stage_create: NULL argument"); return FTP_ERR_ARG; }
+  if (flags & ~(unsigned)FTP_STAGE_RECOMPUTE) { ftp_set_error("stage_create: unknown flags 0x%x", flags); return FTP_ERR_ARG; }
   int L = (int)m->units.size();
   if (a < 0 || a >= b || b > L) { ftp_set_error("stage_create: bad unit range [%d,%d) for %d units", a, b, L); return FTP_ERR_ARG; }
   if (batch < 1 || n_slots < 1 || n_slots > 64) { ftp_set_error("stage_create: batch >= 1 and 1 <= n_slots <= 64 required"); return FTP_ERR_ARG; }
   ftp_stage* s = new (std::nothrow) ftp_stage();
   if (!s) { ftp_set_error("stage_create: out of host memory"); return FTP_ERR_NOMEM; }
   s->model = m; s->a = a; s->b = b; s->batch = batch; s->dt = m->dtype;
+  s->recompute = (flags & FTP_STAGE_RECOMPUTE) != 0;
+  g_alloc_total = 0;
   s->es = m->dtype == FTP_F32 ? 4 : 2;
   if (hipGetDevice(&s->device) != hipSuccess) { ftp_set_error("stage_create: no HIP device"); delete s; return FTP_ERR_HIP; }
 
@@ -362,8 +377,13 @@ extern "C" int ftp_stage_create(const ftp_model* m, int a, int b, int batch, int
       (rc = dev_alloc(&s->run_mean, nb * 4)) || (rc = dev_alloc(&s->run_var, nb * 4))) { stage_free(s); return rc; }
   if (s->dt == FTP_BF16 && (rc = dev_alloc(&s->w_lp, np * 2))) { stage_free(s); return rc; }
   s->slots.resize(n_slots);
+  if (s->recompute && (rc = dev_alloc(&s->shared_stash, stash))) { stage_free(s); return rc; }
   for (auto& sl : s->slots) {
-    if ((rc = dev_alloc(&sl.stash, stash)) || (rc = dev_alloc(&sl.stats, (stats ? stats : 8) * 4)) ||
+    if (s->recompute) {
+      sl.stash = s->shared_stash;
+      if ((rc = dev_alloc(&sl.xin_keep, s->xin_bytes))) { stage_free(s); return rc; }
+    } else if ((rc = dev_alloc(&sl.stash, stash))) { stage_free(s); return rc; }
+    if ((rc = dev_alloc(&sl.stats, (stats ? stats : 8) * 4)) ||
         (rc = dev_alloc(&sl.snap_w, np * 4))) { stage_free(s); return rc; }
     if (s->dt == FTP_BF16 && (rc = dev_alloc(&sl.snap_lp, np * 2))) { stage_free(s); return rc; }
     if (s->has_loss && (rc = dev_alloc(&sl.dlogits, (size_t)batch * s->classes * s->es))) { stage_free(s); return rc; }
@@ -392,7 +412,18 @@ extern "C" int ftp_stage_create(const ftp_model* m, int a, int b, int batch, int
   if (e == hipSuccess && s->w_lp) e = hipMemset(s->w_lp, 0, np * 2);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) { ftp_set_error("stage_create: initialisation failed: %s", hipGetErrorString(e)); stage_free(s); return FTP_ERR_HIP; }
+  s->dev_bytes = g_alloc_total;
   *out = s;
+  return FTP_OK;
+}
+
+extern "C" int ftp_stage_create(const ftp_model* m, int a, int b, int batch, int n_slots, ftp_stage** out) {
+  return ftp_stage_create_ex(m, a, b, batch, n_slots, 0u, out);
+}
+
+extern "C" int ftp_stage_device_bytes(const ftp_stage* s, size_t* bytes) {
+  if (!s || !bytes) { ftp_set_error("stage_device_bytes: NULL argument"); return FTP_ERR_ARG; }
+  *bytes = s->dev_bytes;
   return FTP_OK;
 }
 
@@ -447,6 +478,13 @@ extern "C" int ftp_stage_export_bn_stats(const ftp_stage* s, int unit, float* ho
   return FTP_OK;
 }
 
+static int inspect_check_owner(const ftp_stage* s, int slot, const char* who) {
+  if (s->recompute && s->stash_owner != slot) {
+    ftp_set_error("%s: with recomputation only the slot forwarded (or recomputed) last has intermediates, not slot %d", who, slot);
+    return FTP_ERR_SLOT;
+  }
+  return FTP_OK;
+}
 static int inspect_check(const ftp_stage* s, int slot, int unit, int conv, const void* host, const char* who) {
   if (!s || !host) { ftp_set_error("%s: NULL argument", who); return FTP_ERR_ARG; }
   if (slot < 0 || slot >= (int)s->slots.size()) { ftp_set_error("%s: slot %d out of range", who, slot); return FTP_ERR_ARG; }
@@ -458,6 +496,7 @@ static int inspect_check(const ftp_stage* s, int slot, int unit, int conv, const
 
 extern "C" int ftp_stage_export_conv_output(const ftp_stage* s, int slot, int unit, int conv, float* host_z, size_t n) {
   int rc = inspect_check(s, slot, unit, conv, host_z, "export_conv_output");
+  if (!rc) rc = inspect_check_owner(s, slot, "export_conv_output");
   if (rc) return rc;
   const UnitPlan& p = s->plan[unit - s->a];
   const Sub& sb = p.info->subs[conv];
@@ -545,7 +584,7 @@ static void sub_forward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, HVi
   if (sb.type == SUB_DW && dw_fwd_bn_small_ok(g)) {
     BnPending none{};
     dw_fwd_bn_small(s->dt, st, in, pend ? *pend : none, w, g, gamma, beta, stt, stt + C, stt + 2 * C, stt + 3 * C, rm, rv, kBnEps,
-                    kBnMomentum, z);
+                    s->bn_mom, z);
     if (pend) pend->partial = nullptr;
     return;
   }
@@ -564,28 +603,11 @@ static void sub_forward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, HVi
     else conv_direct_fwd(s->dt, st, in, w, g, z);
     bn_stats(s->dt, st, z, M, g.Cout, s->bn_part, &P);
   }
-  bn_finalize(st, s->bn_part, P, M, C, gamma, beta, stt, stt + C, stt + 2 * C, stt + 3 * C, rm, rv, kBnEps, kBnMomentum);
+  bn_finalize(st, s->bn_part, P, M, C, gamma, beta, stt, stt + C, stt + 2 * C, stt + 3 * C, rm, rv, kBnEps, s->bn_mom);
 }
 
-extern "C" int ftp_stage_forward(ftp_stage* s, int slot, const void* x_dev, void* y_dev, void* stream) {
-  int rc = check_call(s, slot, "stage_forward");
-  if (rc) return rc;
-  if (!x_dev) { ftp_set_error("stage_forward: x_dev is NULL"); return FTP_ERR_ARG; }
-  Slot& sl = s->slots[slot];
-  if (sl.busy) { ftp_set_error("stage_forward: slot %d is busy (its backward has not run)", slot); return FTP_ERR_SLOT; }
-  hipStream_t st = (hipStream_t)stream;
-  const UnitInfo& first = *s->plan[0].info;
-  size_t xin = (size_t)s->batch * first.inH * first.inW * first.inC * s->es;
-  sl.timer_idx = -1;
-  if (s->timer && s->timer->used < ExecTimer::kRing) {
-    sl.timer_idx = s->timer->used++;
-    s->timer->bwd_done[sl.timer_idx] = false;
-    HIP_TRY(hipEventRecord(s->timer->ev[sl.timer_idx][0], st));
-  }
-  HIP_TRY(hipMemcpyAsync(sl.stash, x_dev, xin, hipMemcpyDeviceToDevice, st));
-  Views v;
-  build_views(s, sl, &v);
-  WeightSet W{s->params, (const char*)s->w_lp};
+// every unit of the stage over the input at offset 0 of the slot's stash, with the weights W
+static int forward_units(ftp_stage* s, Slot& sl, const Views& v, const WeightSet& W, hipStream_t st) {
   for (size_t i = 0; i < s->plan.size(); ++i) {
     const UnitPlan& p = s->plan[i];
     const UnitInfo& u = *p.info;
@@ -617,7 +639,7 @@ extern "C" int ftp_stage_forward(ftp_stage* s, int slot, const void* x_dev, void
           h = v.sub_out[i][k];
         }
         if (pend.partial) {
-          bn_finalize_apply_small(s->dt, st, pend, h.z, (size_t)s->batch * u.outH * u.outW, u.outC, h.act, kBnEps, kBnMomentum,
+          bn_finalize_apply_small(s->dt, st, pend, h.z, (size_t)s->batch * u.outH * u.outW, u.outC, h.act, kBnEps, s->bn_mom,
                                   u.residual ? in.z : nullptr, sl.stash + p.out_off);
           pend.partial = nullptr;
         } else {
@@ -629,7 +651,7 @@ extern "C" int ftp_stage_forward(ftp_stage* s, int slot, const void* x_dev, void
         gap_fwd(s->dt, st, in, s->batch, u.inH * u.inW, u.inC, sl.stash + p.out_off);
         break;
       case FTP_UNIT_FC:
-        pw_fwd(s->dt, st, in, conv_w(s, W, p.p_off), s->params + p.p_off + (size_t)u.outC * u.inC, (size_t)s->batch, u.inC,
+        pw_fwd(s->dt, st, in, conv_w(s, W, p.p_off), W.w32 + p.p_off + (size_t)u.outC * u.inC, (size_t)s->batch, u.inC,
                u.outC, sl.stash + p.out_off, nullptr, nullptr);
         break;
       default:
@@ -637,6 +659,33 @@ extern "C" int ftp_stage_forward(ftp_stage* s, int slot, const void* x_dev, void
     }
     if (s->prof) HIP_TRY(hipEventRecord(s->prof->f1[i], st));
   }
+  return FTP_OK;
+}
+
+extern "C" int ftp_stage_forward(ftp_stage* s, int slot, const void* x_dev, void* y_dev, void* stream) {
+  int rc = check_call(s, slot, "stage_forward");
+  if (rc) return rc;
+  if (!x_dev) { ftp_set_error("stage_forward: x_dev is NULL"); return FTP_ERR_ARG; }
+  Slot& sl = s->slots[slot];
+  if (sl.busy) { ftp_set_error("stage_forward: slot %d is busy (its backward has not run)", slot); return FTP_ERR_SLOT; }
+  hipStream_t st = (hipStream_t)stream;
+  const UnitInfo& first = *s->plan[0].info;
+  size_t xin = (size_t)s->batch * first.inH * first.inW * first.inC * s->es;
+  sl.timer_idx = -1;
+  if (s->timer && s->timer->used < ExecTimer::kRing) {
+    sl.timer_idx = s->timer->used++;
+    s->timer->bwd_done[sl.timer_idx] = false;
+    HIP_TRY(hipEventRecord(s->timer->ev[sl.timer_idx][0], st));
+  }
+  HIP_TRY(hipMemcpyAsync(sl.stash, x_dev, xin, hipMemcpyDeviceToDevice, st));
+  if (s->recompute) {
+    HIP_TRY(hipMemcpyAsync(sl.xin_keep, x_dev, xin, hipMemcpyDeviceToDevice, st));
+    s->stash_owner = slot;
+  }
+  Views v;
+  build_views(s, sl, &v);
+  WeightSet W{s->params, (const char*)s->w_lp};
+  if ((rc = forward_units(s, sl, v, W, st))) return rc;
   if (y_dev) {
     size_t li = s->plan.size() - 1;
     const UnitPlan& p = s->plan[li];
@@ -662,6 +711,10 @@ extern "C" int ftp_stage_loss(ftp_stage* s, int slot, const int32_t* labels_dev,
   if (!labels_dev || !loss_dev) { ftp_set_error("stage_loss: NULL argument"); return FTP_ERR_ARG; }
   Slot& sl = s->slots[slot];
   if (!sl.busy) { ftp_set_error("stage_loss: slot %d holds no forwarded batch", slot); return FTP_ERR_SLOT; }
+  if (s->recompute && s->stash_owner != slot) {
+    ftp_set_error("stage_loss: with recomputation the loss of slot %d has to follow its forward directly (the logits are gone)", slot);
+    return FTP_ERR_SLOT;
+  }
   hipStream_t st = (hipStream_t)stream;
   Views v;
   build_views(s, sl, &v);
@@ -838,6 +891,18 @@ extern "C" int ftp_stage_backward(ftp_stage* s, int slot, const void* dy_dev, vo
   Views v;
   build_views(s, sl, &v);
   WeightSet W{sl.has_snap ? sl.snap_w : s->params, (const char*)(sl.has_snap ? sl.snap_lp : s->w_lp)};
+  if (s->recompute && s->stash_owner != slot) {
+    // the intermediates of this batch are gone: forward again from the kept input with the weights of its
+    // forward; not a training forward, so the running statistics stay as they are
+    const UnitInfo& first = *s->plan[0].info;
+    HIP_TRY(hipMemcpyAsync(sl.stash, sl.xin_keep, (size_t)s->batch * first.inH * first.inW * first.inC * s->es,
+                           hipMemcpyDeviceToDevice, st));
+    s->bn_mom = 0.f;
+    rc = forward_units(s, sl, v, W, st);
+    s->bn_mom = kBnMomentum;
+    if (rc) return rc;
+    s->stash_owner = slot;
+  }
   const void* d = dy_dev ? dy_dev : sl.dlogits;     // gradient of the current unit's output (read only)
   int flip = 0;
   for (int i = (int)s->plan.size() - 1; i >= 0; --i) {

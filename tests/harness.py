@@ -65,7 +65,7 @@ class Pair:
     """The same stage [a,b) in the oracle (float64) and in the HIP library."""
 
     def __init__(self, o_units, h_units, in_shape, batch, a, b, dtype="f32", n_slots=1, seed=1, guard=None, max_disagree_frac=0.0,
-                 model_of=None):
+                 model_of=None, recompute=False):
         import torch
         import paper_2110_02781_amd as P
         self.P, self.torch = P, torch
@@ -77,8 +77,12 @@ class Pair:
         # stages that exchange units (re-partition) are built from one model object
         self.owns_model = model_of is None
         self.model = P.model_create(h_units, H, W, Cc, P.F32 if dtype == "f32" else P.BF16) if model_of is None else model_of.model
-        self.stage = P.stage_create(self.model, a, b, batch, n_slots)
-        self.oracle = OracleStage(o_units, in_shape, a, b, n_slots, storage='bf16' if dtype == 'bf16' else None)
+        self.stage = P.stage_create(self.model, a, b, batch, n_slots, P.STAGE_RECOMPUTE if recompute else 0)
+        # A recomputing stage has no intermediates to show between forward and backward: a twin that keeps
+        # everything runs the same calls; it supplies the activation decisions, and the two must agree bit for bit.
+        self.twin = P.stage_create(self.model, a, b, batch, n_slots) if recompute else None
+        self.oracle = OracleStage(o_units, in_shape, a, b, n_slots, storage='bf16' if dtype == 'bf16' else None,
+                                  recompute=recompute)
         op = OM.init_params(o_units, seed)
         hp = P.models.init_unit_params(h_units, seed)
         for i in range(a, b):
@@ -87,6 +91,8 @@ class Pair:
             # masters are fp32 on both sides; in bf16 mode each side rounds its own working copy
             self.oracle.set_params(i, [p.astype(np.float32).astype(np.float64) for p in op[i]])
             P.stage_import_weights(self.stage, i, hp[i])
+            if self.twin:
+                P.stage_import_weights(self.twin, i, hp[i])
         self.in_shape = self.oracle.shapes[a]
         self.out_shape = self.oracle.shapes[b]
         self.stream = torch.cuda.current_stream().cuda_stream
@@ -96,6 +102,8 @@ class Pair:
 
     def close(self):
         self.P.stage_destroy(self.stage)
+        if self.twin:
+            self.P.stage_destroy(self.twin)
         if self.owns_model:
             self.P.model_destroy(self.model)
 
@@ -128,6 +136,12 @@ class Pair:
         P.stage_forward(self.stage, slot, xd, y, self.stream)
         if snapshot:
             P.stage_snapshot_weights(self.stage, slot, self.stream)
+        if self.twin:
+            y2 = self.empty((self.batch,) + tuple(self.out_shape))
+            P.stage_forward(self.twin, slot, xd, y2, self.stream)
+            if snapshot:
+                P.stage_snapshot_weights(self.twin, slot, self.stream)
+            assert self.torch.equal(y, y2), "recomputing stage and its twin disagree on the forward output"
         yo = self.oracle.forward(slot, self.as_seen(x), stash_weights=snapshot)
         return self.host(y), yo
 
@@ -140,6 +154,10 @@ class Pair:
         ld = torch.from_numpy(np.asarray(labels, dtype=np.int32)).to(self.dev)
         out = torch.zeros(1, dtype=torch.float32, device=self.dev)
         P.stage_loss(self.stage, slot, ld, out, self.stream)
+        if self.twin:
+            out2 = torch.zeros(1, dtype=torch.float32, device=self.dev)
+            P.stage_loss(self.twin, slot, ld, out2, self.stream)
+            assert torch.equal(out, out2)
         lo = self.oracle.loss(slot, labels)
         return float(self.host(out)[0]), lo
 
@@ -149,6 +167,9 @@ class Pair:
         BatchNorm scale / shift."""
         P = self.P
         out = {}
+        src = self.twin if self.twin else self.stage
+        if self.twin:
+            self.oracle.materialize(slot)
         for i in range(self.a, self.b):
             u = self.o_units[i]
             if u.kind == 'conv':
@@ -162,8 +183,8 @@ class Pair:
                     continue
                 zo = self.oracle.slots[slot]['caches'][i][k]['z']
                 C = zo.shape[-1]
-                z = P.stage_export_conv_output(self.stage, slot, i, k, zo.size).reshape(zo.shape)
-                st = P.stage_export_bn_batch_stats(self.stage, slot, i, k, 4 * C)
+                z = P.stage_export_conv_output(src, slot, i, k, zo.size).reshape(zo.shape)
+                st = P.stage_export_bn_batch_stats(src, slot, i, k, 4 * C)
                 y = (z.astype(np.float64) * st[2 * C:3 * C].astype(np.float64) + st[3 * C:].astype(np.float64)).astype(np.float32)
                 on = y > 0
                 if act == 2:
@@ -180,6 +201,10 @@ class Pair:
         dx = self.empty((self.batch,) + tuple(self.in_shape)) if want_dx else None
         ties = self.kernel_decisions(slot)
         P.stage_backward(self.stage, slot, dyd, dx, self.stream)
+        if self.twin:
+            dx2 = self.empty((self.batch,) + tuple(self.in_shape)) if want_dx else None
+            P.stage_backward(self.twin, slot, dyd, dx2, self.stream)
+            assert dx is None or self.torch.equal(dx, dx2), "recomputing stage and its twin disagree on dx"
         dxo = self.oracle.backward(slot, None if dy is None else self.as_seen(dy), tie_breaks=ties,
                                    guard=self.guard)
         rep = self.oracle.tie_report
@@ -190,6 +215,8 @@ class Pair:
 
     def update(self, lr, mu, wd):
         self.P.stage_update(self.stage, lr, mu, wd, self.stream)
+        if self.twin:
+            self.P.stage_update(self.twin, lr, mu, wd, self.stream)
         self.oracle.update(lr, mu, wd)
 
     # -- comparisons ------------------------------------------------------------------
@@ -200,6 +227,20 @@ class Pair:
         fn = {"weights": P.stage_export_weights, "grads": P.stage_export_grads, "momentum": P.stage_export_momentum}[which]
         return [np.array(fn(self.stage, i, P.model_unit_param_count(self.model, i)), copy=True)
                 for i in range(self.a, self.b) if P.model_unit_param_count(self.model, i)]
+
+    def assert_twin_identical(self):
+        """Weights, gradients, momentum and running statistics of the recomputing stage and of its twin, bit for bit."""
+        P = self.P
+        self.torch.cuda.synchronize()
+        for i in range(self.a, self.b):
+            n = P.model_unit_param_count(self.model, i)
+            for fn in (P.stage_export_weights, P.stage_export_grads, P.stage_export_momentum):
+                if n:
+                    assert np.array_equal(fn(self.stage, i, n), fn(self.twin, i, n)), f"unit {i}: {fn.__name__} differ"
+            nb = P.model_unit_bn_channels(self.model, i)
+            if nb:
+                assert np.array_equal(P.stage_export_bn_stats(self.stage, i, 2 * nb), P.stage_export_bn_stats(self.twin, i, 2 * nb)), \
+                    f"unit {i}: running statistics differ"
 
     def oracle_busy_slots(self):
         return [i for i, sl in enumerate(self.oracle.slots) if sl is not None]

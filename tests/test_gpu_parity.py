@@ -376,6 +376,67 @@ def test_repartition_moves_units_between_stages_on_the_device():
         A.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_recomputation_along_the_one_f_one_b_schedule(dtype):
+    """Slots that keep only their stage input and run the forward again in the backward (section "Synchronous
+    Pipeline Parallelism Training"), under one-forward-one-backward with weight stashing: against the oracle to the
+    usual tolerance, against a twin stage that keeps every intermediate bit for bit, and with less device memory."""
+    import paper_2110_02781_amd as P
+    print(f"recomputation: small net, stage 0 of 3, 6 micro-batches, {dtype}", flush=True)
+    o, h = small_net()
+    nb, depth = 6, 3
+    pair = Pair(o, h, (9, 11, 3), 4, 0, len(o), dtype, seed=51, n_slots=depth, recompute=True, guard=e2e_tol(dtype, 6),
+                max_disagree_frac=0.0 if dtype == "f32" else 2e-3)
+    try:
+        assert P.stage_device_bytes(pair.stage) < P.stage_device_bytes(pair.twin)
+        xs = [synth.normal(51, f"x{i}", (4, 9, 11, 3)) for i in range(nb)]
+        ls = [synth.labels(51, f"l{i}", 4, 10) for i in range(nb)]
+        tol = e2e_tol(dtype, len(o))
+        for op, b in one_f_one_b_order(0, 3, nb):
+            if op == 'F':
+                y, yo = pair.forward(b % depth, xs[b], snapshot=True)
+                l, lo = pair.loss(b % depth, ls[b])
+                assert abs(l - lo) <= tol * max(1.0, abs(lo))
+            else:
+                pair.backward(b % depth, None, want_dx=False)
+                if dtype == "f32":
+                    pair.compare_unit_vectors("grads", tol, floor=1e-7)
+                pair.update(0.01, 0.9, 4e-5)
+                pair.assert_twin_identical()
+                if dtype == "f32":
+                    pair.compare_unit_vectors("weights", tol)
+                    tol = max(tol, 3e-4)   # later versions start from weights that already differ by the tolerance
+        pair.compare_unit_vectors("bn", tol)        # the second forwards did not move the running statistics
+    finally:
+        pair.close()
+
+
+def test_recomputation_call_order_errors():
+    """With recomputation the logits of a slot are gone once another slot has been forwarded."""
+    import paper_2110_02781_amd as P
+    o, h = small_net()
+    pair = Pair(o, h, (9, 11, 3), 4, 0, len(o), "f32", seed=52, n_slots=2, recompute=True)
+    try:
+        x = synth.normal(52, "x", (4, 9, 11, 3))
+        labels = synth.labels(52, "l", 4, 10)
+        pair.forward(0, x); pair.forward(1, x)
+        ld = pair.torch.from_numpy(np.asarray(labels, dtype=np.int32)).to(pair.dev)
+        out = pair.torch.zeros(1, dtype=pair.torch.float32, device=pair.dev)
+        with pytest.raises(RuntimeError):
+            P.stage_loss(pair.stage, 0, ld, out, pair.stream)             # slot 1 owns the stash now
+        with pytest.raises(RuntimeError):
+            P.stage_export_conv_output(pair.stage, 0, 0, 0, 4 * 9 * 11 * 8)
+        with pytest.raises(RuntimeError):
+            P.stage_create(pair.model, 0, len(o), 4, 1, 0x80)             # unknown flag
+        pair.loss(1, labels)
+        pair.backward(1, None, want_dx=False)
+        dy = synth.normal(52, "dy", (4,) + tuple(pair.out_shape))
+        pair.backward(0, dy, want_dx=False)                               # recomputes slot 0; needs an explicit gradient
+        pair.assert_twin_identical()
+    finally:
+        pair.close()
+
+
 def test_online_execution_timing_feeds_the_capacity_estimate():
     """Execution profiling phase of the dynamic partition: the stage records forward+backward time per batch,
     the mean over the window and the profiled unit costs give the worker's capacity (about 1 on the device that
