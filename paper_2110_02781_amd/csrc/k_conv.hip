@@ -905,6 +905,49 @@ void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvG
 // dW[c][ky][kx] += sum over output pixels dz[p][c] * in[p*S-1+(ky,kx)][c].  Blocks are persistent over
 // tiles; a thread reads the dz of its run straight from global memory (nobody else needs it), keeps
 // 9 x 4 sums over all its runs, and the block leaves one partial ws[block][9][C].
+// four channels of one pixel as loaded, converted at the point of use (so the load can stay in flight)
+template <typename T> struct Raw4;
+template <> struct Raw4<float> { float4 v; };
+template <> struct Raw4<bf16_t> { uint2 v; };
+__device__ __forceinline__ void raw4_load(Raw4<float>& r, const float* p) { r.v = *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ void raw4_load(Raw4<bf16_t>& r, const bf16_t* p) { r.v = *reinterpret_cast<const uint2*>(p); }
+__device__ __forceinline__ float4 raw4_unpack(const Raw4<float>& r) { return r.v; }
+__device__ __forceinline__ float4 raw4_unpack(const Raw4<bf16_t>& r) {
+  return make_float4(__uint_as_float(r.v.x << 16), __uint_as_float(r.v.x & 0xffff0000u), __uint_as_float(r.v.y << 16),
+                     __uint_as_float(r.v.y & 0xffff0000u));
+}
+
+// The dz values of a thread's (at most kDwSegs) 4-pixel runs of one tile, requested a whole tile ahead like the
+// input patch: a persistent block has few neighbours on its CU to hide a load behind.
+enum { kDwSegs = 2 };
+template <typename T>
+struct DwDzRuns {
+  Raw4<T> r[kDwSegs][4];
+  unsigned ok;
+  __device__ __forceinline__ void fetch(const T* __restrict__ dz, int tile, const DwPlan& d, int Hout, int Wout, int C,
+                                        int seg0, int gc, bool worker) {
+    ok = 0;
+    if (!worker) return;
+    const int tw = tile % d.tiles_w, th = (tile / d.tiles_w) % d.tiles_h, n = tile / (d.tiles_w * d.tiles_h);
+    const int ho0 = th * d.TH, wo0 = tw * d.TW;
+#pragma unroll
+    for (int k = 0; k < kDwSegs; ++k) {
+      const int sg = seg0 + k * d.spp;
+      if (sg >= d.nseg) break;
+      const int hl = dw_div(sg, d.m_segw), wl0 = (sg - hl * d.segw) * 4;
+      const int ho = ho0 + hl;
+      if (ho >= Hout) continue;
+      const T* dp = dz + (((size_t)n * Hout + ho) * Wout + wo0 + wl0) * C + gc;
+#pragma unroll
+      for (int o = 0; o < 4; ++o)
+        if (wo0 + wl0 + o < Wout) {
+          raw4_load(r[k][o], dp + (size_t)o * C);
+          ok |= 1u << (4 * k + o);
+        }
+    }
+  }
+};
+
 template <typename T, int S>
 __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View in, DwPlan d, int Hin, int Win, int Hout,
                                                   int Wout, int C, float* __restrict__ ws) {
@@ -921,41 +964,50 @@ __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View
 #pragma unroll
   for (int t = 0; t < 9; ++t) acc[t] = make_float4(0.f, 0.f, 0.f, 0.f);
   DwPatch<T> lp;
+  DwDzRuns<T> dq[2];
   if (b < d.ntiles) {
     const int tw = b % d.tiles_w, th = (b / d.tiles_w) % d.tiles_h, n = b / (d.tiles_w * d.tiles_h);
     lp.fetch(src, n, th * d.TH * S - 1, tw * d.TW * S - 1, d, Hin, Win, C, cg0);
+    dq[0].fetch(dz, b, d, Hout, Wout, C, seg0, gc, worker);
   }
-  for (int tile = b; tile < d.ntiles; tile += d.nblocks) {
-    const int tw = tile % d.tiles_w, th = (tile / d.tiles_w) % d.tiles_h, n = tile / (d.tiles_w * d.tiles_h);
-    const int ho0 = th * d.TH, wo0 = tw * d.TW;
-    __syncthreads();                                       // the previous tile has been consumed
-    lp.commit(patch, in, d, cg0);
-    __syncthreads();
-    const int nt = tile + d.nblocks;
-    if (nt < d.ntiles) {
-      const int tw2 = nt % d.tiles_w, th2 = (nt / d.tiles_w) % d.tiles_h, n2 = nt / (d.tiles_w * d.tiles_h);
-      lp.fetch(src, n2, th2 * d.TH * S - 1, tw2 * d.TW * S - 1, d, Hin, Win, C, cg0);
-    }
-    if (!worker) continue;
-    for (int sg = seg0; sg < d.nseg; sg += d.spp) {
-      const int hl = dw_div(sg, d.m_segw), wl0 = (sg - hl * d.segw) * 4;
-      const int ho = ho0 + hl;
-      if (ho >= Hout) continue;
-      float4 dv[4];
-      const T* dp = dz + (((size_t)n * Hout + ho) * Wout + wo0 + wl0) * C + gc;
+  // two tiles per round so that the two sets of dz registers are addressed statically
+  for (int tile0 = b; tile0 < d.ntiles; tile0 += 2 * d.nblocks) {
 #pragma unroll
-      for (int o = 0; o < 4; ++o)
-        dv[o] = wo0 + wl0 + o < Wout ? load4(dp + (size_t)o * C) : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int par = 0; par < 2; ++par) {
+      const int tile = tile0 + par * d.nblocks;
+      if (tile >= d.ntiles) break;
+      __syncthreads();                                       // the previous tile has been consumed
+      lp.commit(patch, in, d, cg0);
+      __syncthreads();
+      const int nt = tile + d.nblocks;
+      if (nt < d.ntiles) {
+        const int tw2 = nt % d.tiles_w, th2 = (nt / d.tiles_w) % d.tiles_h, n2 = nt / (d.tiles_w * d.tiles_h);
+        lp.fetch(src, n2, th2 * d.TH * S - 1, tw2 * d.TW * S - 1, d, Hin, Win, C, cg0);
+        dq[par ^ 1].fetch(dz, nt, d, Hout, Wout, C, seg0, gc, worker);
+      }
+      if (!worker) continue;
+      const DwDzRuns<T>& cur = dq[par];
 #pragma unroll
-      for (int ky = 0; ky < 3; ++ky) {
-        const float* row = patch + (size_t)((hl * S + ky) * d.PW + wl0 * S) * vs + c4;
-        float4 iv[3 * S + 3];
+      for (int k = 0; k < kDwSegs; ++k) {
+        const int sg = seg0 + k * d.spp;
+        if (sg >= d.nseg) break;
+        if (((cur.ok >> (4 * k)) & 15u) == 0u) continue;     // the run lies outside the image
+        const int hl = dw_div(sg, d.m_segw), wl0 = (sg - hl * d.segw) * 4;
+        float4 dv[4];
 #pragma unroll
-        for (int x = 0; x < 3 * S + 3; ++x) iv[x] = ld4(row + (size_t)x * vs);
+        for (int o = 0; o < 4; ++o)
+          dv[o] = (cur.ok >> (4 * k + o)) & 1u ? raw4_unpack(cur.r[k][o]) : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int kx = 0; kx < 3; ++kx)
+        for (int ky = 0; ky < 3; ++ky) {
+          const float* row = patch + (size_t)((hl * S + ky) * d.PW + wl0 * S) * vs + c4;
+          float4 iv[3 * S + 3];
 #pragma unroll
-          for (int o = 0; o < 4; ++o) acc[ky * 3 + kx] = fma4(dv[o], iv[o * S + kx], acc[ky * 3 + kx]);
+          for (int x = 0; x < 3 * S + 3; ++x) iv[x] = ld4(row + (size_t)x * vs);
+#pragma unroll
+          for (int kx = 0; kx < 3; ++kx)
+#pragma unroll
+            for (int o = 0; o < 4; ++o) acc[ky * 3 + kx] = fma4(dv[o], iv[o * S + kx], acc[ky * 3 + kx]);
+        }
       }
     }
   }
@@ -987,6 +1039,7 @@ static DwPlan dw_wgrad_plan(const ConvGeom& g, int es, size_t* lds) {
   d.ntiles = g.N * d.tiles_h * d.tiles_w;
   const int cap = 512 / d.nslab > 1 ? 512 / d.nslab : 1;   // about 512 persistent blocks over all slabs
   d.nblocks = d.ntiles < cap ? d.ntiles : cap;
+  if (d.nseg > kDwSegs * d.spp) abort();                   // a thread holds the dz of at most kDwSegs runs per tile
   size_t a = (size_t)d.PH * d.PW * d.CGB * 8 * 4;
   size_t b = (size_t)d.spp * 9 * 2 * d.CGB * 16;
   *lds = a > b ? a : b;

@@ -603,9 +603,11 @@ __device__ __forceinline__ void load_pair(const bf16_t* p, float& a, float& b) {
   a = __uint_as_float(v << 16); b = __uint_as_float(v & 0xffff0000u);
 }
 
-template <typename T, int MODE, bool VEC>
+// CH = reduction elements staged per step: the bfloat16 weight gradient runs with 64, which halves the steps and
+// their barriers.
+template <typename T, int MODE, bool VEC, int CH>
 __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
-  constexpr int TI = 128, CH = 32;
+  constexpr int TI = 128;
   constexpr int LD = CH + Pad<T>::V;
   constexpr int BUF = (TI + BJ) * LD;
   __shared__ __attribute__((aligned(16))) T smem[2 * BUF];
@@ -678,7 +680,8 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
       lx.fetch(X, ldx, (size_t)it2 * TI, ni, rbeg + (size_t)kc2 * CH, rend);
       if (!y_static || s + 1 < 2) ly.fetch(Y, ldy, j0, nj, rbeg + (size_t)kc2 * CH, rend);
     }
-    mma32(xs, ys, LD, wave * 32 + jl, lane, 0, acc);
+#pragma unroll
+    for (int c0 = 0; c0 < CH; c0 += 32) mma32(xs, ys, LD, wave * 32 + jl, lane, c0, acc);
     if (kc + 1 < nchunks) continue;
 
     // tile finished: register r of this lane is row 8*(r/4) + 4*h + r%4, columns jc (acc[0]) and jc+1 (acc[1])
@@ -978,10 +981,16 @@ static void launch_tiny(int dt, hipStream_t st, GemmArgs& a, int ncols) {
   else hipLaunchKernelGGL((pw_gemm_tiny_k<bf16_t, MODE>), dim3(grid), dim3(256), 0, st, a);
 }
 
+enum { kDeepReduction = 256 };   // bfloat16 reductions at least this long are staged 64 elements per step
 template <typename T, int MODE, bool VEC>
 static void launch_t(hipStream_t st, const GemmArgs& a, bool small, unsigned grid) {
-  if (small) hipLaunchKernelGGL((pw_gemm_k<T, MODE, true, VEC>), dim3(grid), dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC>), dim3(grid), dim3(256), 0, st, a);
+  if (small) { hipLaunchKernelGGL((pw_gemm_k<T, MODE, true, VEC>), dim3(grid), dim3(256), 0, st, a); return; }
+  const size_t red = MODE == MODE_FWD ? (size_t)a.K : MODE == MODE_DGRAD ? (size_t)a.N : a.mchunk;   // reduction extent of a block
+  // measured: the weight gradient (both operands transposed on the way into LDS) gains 10-30 %, forward and data
+  // gradient lose a little (fewer blocks fit a CU)
+  if (MODE == MODE_WGRAD && sizeof(T) == 2 && red >= (size_t)kDeepReduction)
+    hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, sizeof(T) == 2 ? 64 : 32>), dim3(grid), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, 32>), dim3(grid), dim3(256), 0, st, a);
 }
 
 template <int MODE>

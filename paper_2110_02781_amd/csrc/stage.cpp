@@ -836,6 +836,11 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
       bn_bwd_apply(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->coef, dz);
   }
   hipStream_t ws = st;
+  // The depthwise data gradient and weight gradient want the same units (LDS tiles, vector ALU): side by side each
+  // takes nearly twice as long.  The data gradient goes first, alone; the weight gradient then shares the GPU with
+  // the memory-bound BatchNorm backward of the layer in front.
+  const bool dgrad_first = overlap && sb.type == SUB_DW && dIn != nullptr;
+  if (dgrad_first) dw_dgrad(s->dt, st, dz, conv_w(s, W, p.p_off + sb.w_off), g, dIn);
   if (overlap) {
     HIP_TRY(hipEventRecord(s->ev_fork[b], st));
     HIP_TRY(hipStreamWaitEvent(s->side, s->ev_fork[b], 0));
@@ -862,7 +867,7 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
       else conv_direct_dgrad(s->dt, st, dz, w, g, dIn);
     }
     else if (sb.type == SUB_PW) pw_dgrad(s->dt, st, dz, w, res, M, g.Cin, g.Cout, dIn);
-    else dw_dgrad(s->dt, st, dz, w, g, dIn);
+    else if (!dgrad_first) dw_dgrad(s->dt, st, dz, w, g, dIn);
   }
   return FTP_OK;
 }
