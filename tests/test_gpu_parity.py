@@ -437,6 +437,72 @@ def test_recomputation_call_order_errors():
         pair.close()
 
 
+@pytest.mark.parametrize("case", ["one_stream_f32", "two_streams_bf16"])
+def test_training_step_replays_from_a_hip_graph(case):
+    """The compute calls only enqueue kernels and device-to-device copies (no allocation, no memset, no host
+    synchronisation), so a whole step can be captured into a HIP graph, including the fork and join of the
+    weight-gradient stream of a large stage.  Every replay, with eager work and synchronisations in between, must
+    leave exactly the weights that the same step gives when it is launched eagerly on a second stage."""
+    import torch
+    import paper_2110_02781_amd as P
+    print(f"graph replay {case}", flush=True)
+    if case == "one_stream_f32":
+        _, units = small_net()
+        shape, batch, dt, tdt, classes = (9, 11, 3), 4, P.F32, torch.float32, 10
+    else:
+        units = P.models.mobilenet_v2_units(1.4, 1000, 2)          # largest activation 58 MB: the side stream is on
+        shape, batch, dt, tdt, classes = (224, 224, 3), 16, P.BF16, torch.bfloat16, 1000
+    dev = torch.device("cuda:0")
+    model = P.model_create(units, *shape, dt)
+    L = P.model_num_units(model)
+    params = P.models.init_unit_params(units, 61)
+    stages = [P.stage_create(model, 0, L, batch, 1) for _ in range(2)]
+    try:
+        for st in stages:
+            for i in range(L):
+                P.stage_import_weights(st, i, params[i])
+        x = torch.from_numpy(synth.normal(61, "x", (batch,) + shape).astype(np.float32)).to(dev).to(tdt)
+        labels = torch.from_numpy(synth.labels(61, "l", batch, classes).astype(np.int32)).to(dev)
+        loss = [torch.zeros(1, dtype=torch.float32, device=dev) for _ in range(2)]
+        stream = torch.cuda.Stream()
+        sp = stream.cuda_stream
+
+        def step(k):
+            P.stage_forward(stages[k], 0, x, None, sp)
+            P.stage_loss(stages[k], 0, labels, loss[k], sp)
+            P.stage_backward(stages[k], 0, None, None, sp)
+            P.stage_update(stages[k], 0.01, 0.9, 4e-5, sp)
+
+        def weights(k):
+            torch.cuda.synchronize()
+            return [np.array(P.stage_export_weights(stages[k], i, P.model_unit_param_count(model, i)), copy=True)
+                    for i in range(L) if P.model_unit_param_count(model, i)]
+
+        step(0); step(1)                                  # first launches (code objects load) stay outside the capture
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            step(1)
+        step(0)                                           # the capture itself runs nothing: stage 1 is one step behind
+        graph.replay()
+        for a, b in zip(weights(0), weights(1)):
+            assert np.array_equal(a, b), "first replay differs from the eager step"
+        for rep in range(3):
+            step(0)
+            junk = torch.randn(1 << 16, device=dev).sum()           # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            assert np.isfinite(float(junk))
+            for a, b in zip(weights(0), weights(1)):
+                assert np.array_equal(a, b), f"replay {rep + 2} differs from the eager step"
+            assert float(loss[0].item()) == float(loss[1].item())
+        del graph
+    finally:
+        for st in stages:
+            P.stage_destroy(st)
+        P.model_destroy(model)
+
+
 def test_online_execution_timing_feeds_the_capacity_estimate():
     """Execution profiling phase of the dynamic partition: the stage records forward+backward time per batch,
     the mean over the window and the profiled unit costs give the worker's capacity (about 1 on the device that
