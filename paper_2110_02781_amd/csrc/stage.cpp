@@ -802,6 +802,8 @@ extern "C" int ftp_stage_aggregate_weights(ftp_stage* s, const int* slots, int n
 enum { BWD_FULL = 0, BWD_FROM_DZ = 1 };
 static bool stage_overlaps(const ftp_stage* s) { return s->prof == nullptr && s->max_act_bytes >= ((size_t)32 << 20); }
 
+static int join_side(ftp_stage* s, hipStream_t st);
+
 static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, const void* dA, HView in, HView out,
                         void* dIn, const void* res, const WeightSet& W, hipStream_t st, int mode = BWD_FULL) {
   const Sub& sb = p.info->subs[k];
@@ -813,7 +815,7 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
   // it pays only when the kernels are long.  Measured: a 32x32-input stage (largest activation 12 MB) is
   // 10 % faster on one stream, a 224x224 one 15 % slower.
   const bool overlap = mode == BWD_FULL && stage_overlaps(s) && M * (size_t)C >= ((size_t)1 << 20);
-  int b = 0;
+  int b = 0, rc_join = 0;
   void* dz = const_cast<void*>(dA);
   if (mode != BWD_FROM_DZ) {
     b = (int)(s->n_sub_bwd++ & 1u);
@@ -848,6 +850,9 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
   }
   const void* w = conv_w(s, W, p.p_off + sb.w_off);
   float* gw = s->grads + p.p_off + sb.w_off;
+  // a layer too short to fork still takes the partial-sum workspace: in a stage that forks its longer layers the
+  // side stream may be in the middle of using it, so that work is waited for first
+  if (!overlap && stage_overlaps(s) && (rc_join = join_side(s, st))) return rc_join;
   if (sb.type == SUB_PW && !overlap && dIn) {
     pw_bwd(s->dt, st, dz, w, res, in, M, g.Cin, g.Cout, s->ws, gw, dIn);
     return FTP_OK;
