@@ -66,6 +66,28 @@ def estimate_capacity(stage_time, layer_costs, start, end):
     return stage_time / sum(layer_costs[start:end + 1])
 
 
+def repartition_due(batches_done):
+    """Re-partition schedule (section "Dynamic Model Partition"): the first one after
+    10 trained batches, then one every 100 batches (10, 110, 210, ...)."""
+    return batches_done == 10 or (batches_done > 10 and (batches_done - 10) % 100 == 0)
+
+
+def repartition_capacities(mean_times, layer_costs, bounds_cur):
+    """Capacities for the next re-partition.  mean_times[i]: average execution time
+    worker i reported for its current stage [bounds_cur[i], bounds_cur[i+1]), None if
+    it reported none.  The central node (worker 0) keeps capacity 1.0 (capacity
+    equations); if any other worker has reported nothing, all workers are taken to be
+    equal (section "Fault Tolerance Mechanism": the scheduler then uses the central
+    node's times alone)."""
+    n = len(bounds_cur) - 1
+    if any(mean_times[i] is None for i in range(1, n)):
+        return [1.0] * n
+    caps = [1.0]
+    for i in range(1, n):
+        caps.append(estimate_capacity(mean_times[i], layer_costs, bounds_cur[i], bounds_cur[i + 1] - 1))
+    return caps
+
+
 def renumber_workers(worker_list, failed):
     """Worker list after failures (section "Fault Tolerance Mechanism"): with one
     failure every index above the failed one drops by one; with several, each failed

@@ -188,3 +188,29 @@ def test_renumber_workers():
     assert renumber_workers(["c", "w1", "w2", "w3"], [2]) == ["c", "w1", "w3"]
     assert renumber_workers(["c", "w1", "w2", "w3", "w4"], [1, 3]) == ["c", "w2", "w4"]
     assert renumber_workers(["c", "w1"], []) == ["c", "w1"]
+
+
+# ------------------------------------------------------------ re-partition schedule and capacities
+def test_repartition_schedule_first_after_10_then_every_100():
+    """Section "Dynamic Model Partition": first after 10 batches, then every 100."""
+    from oracle.partition import repartition_due
+    due = [b for b in range(0, 450) if repartition_due(b)]
+    assert due == [10, 110, 210, 310, 410]
+
+
+def test_repartition_capacities_closed_form_and_fallback():
+    """A worker that takes exactly k times the central node's profiled time for its layers has capacity k (capacity
+    equations), whatever the cut; the central node stays at 1.0; one missing report makes everybody equal."""
+    from oracle.partition import repartition_capacities, solve_partition
+    costs = [3.0, 1.0, 4.0, 1.0, 5.0, 9.0, 2.0, 6.0]
+    bounds = [0, 3, 5, 8]
+    slow = [1.0, 2.5, 7.0]
+    means = [123.0] + [slow[i] * sum(costs[bounds[i]:bounds[i + 1]]) for i in (1, 2)]     # worker 0's report is not used
+    caps = repartition_capacities(means, costs, bounds)
+    assert caps == [1.0, 2.5, 7.0]
+    assert repartition_capacities([None, means[1], means[2]], costs, bounds) == caps           # central node: no report needed
+    assert repartition_capacities([means[0], None, means[2]], costs, bounds) == [1.0, 1.0, 1.0]
+    # the slower the later workers, the more layers the central node keeps
+    b_equal, _ = solve_partition(costs, [1.0, 1.0, 1.0])
+    b_meas, _ = solve_partition(costs, caps)
+    assert b_meas[1] >= b_equal[1] and b_meas[1] > 3
