@@ -214,6 +214,19 @@ int ftp_solve_partition(const double* layer_costs, int L, const double* device_c
 int ftp_estimate_capacity(double stage_time, const double* layer_costs, int L, int start, int end,
                           double* capacity);
 
+/* Re-partition schedule (section "Dynamic Model Partition"): *due = 1 when a re-partition follows the
+ * batches_done-th trained batch: the first after 10 batches, then every 100 (10, 110, 210, ...). */
+int ftp_repartition_due(int64_t batches_done, int* due);
+
+/* Capacities for the next re-partition (capacity equations of the same section).  mean_times[n]: the mean
+ * execution time each worker reported for its current stage [bounds_cur[i], bounds_cur[i+1]) in the unit of
+ * layer_costs[L]; a value that is not finite and positive means "no report".  capacities[0] = 1.0 (the central
+ * node, whose report is not used); capacities[i] = mean_times[i] / sum of layer_costs over worker i's stage; if
+ * any worker i >= 1 has no report every capacity is 1.0 (the re-partition then uses the central node's times
+ * alone).  All host pointers. */
+int ftp_repartition_capacities(const double* mean_times, const double* layer_costs, int L, const int32_t* bounds_cur,
+                               int n, double* capacities);
+
 /* Online execution profiling (section "Dynamic Model Partition", execution
  * profiling phase: every worker records the execution time of every batch and
  * reports the average, which becomes the numerator of its capacity).

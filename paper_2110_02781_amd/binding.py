@@ -86,6 +86,8 @@ _SIGS = {
     "ftp_profile_layers": (_i, [_vp, _i, _i, _dp, C.POINTER(C.c_int64), _vp]),
     "ftp_solve_partition": (_i, [_dp, _i, _dp, _i, _dp, _dp, C.POINTER(C.c_int32), _dp]),
     "ftp_estimate_capacity": (_i, [C.c_double, _dp, _i, _i, _i, _dp]),
+    "ftp_repartition_due": (_i, [C.c_int64, C.POINTER(_i)]),
+    "ftp_repartition_capacities": (_i, [_dp, _dp, _i, C.POINTER(C.c_int32), _i, _dp]),
     "ftp_redistribution_plan": (_i, [C.POINTER(C.c_int32), _i, C.POINTER(C.c_int32), _i, _i, _i, _i, C.POINTER(C.c_int32)]),
     "ftp_stage_copy_units": (_i, [_vp, _vp, _i, _i, _vp]),
     "ftp_stage_timing": (_i, [_vp, _i]),
@@ -304,6 +306,23 @@ def ktrace_end():
 
 def calibration_copy(dst_dev, src_dev, nbytes, stream=None):
     _chk(lib.ftp_calibration_copy(_ptr(dst_dev), _ptr(src_dev), nbytes, _ptr(stream)))
+
+
+def repartition_due(batches_done):
+    due = _i(0)
+    _chk(lib.ftp_repartition_due(int(batches_done), C.byref(due)))
+    return bool(due.value)
+
+
+def repartition_capacities(mean_times, layer_costs, bounds_cur):
+    """mean_times: per worker, None (or nan) where nothing was reported."""
+    m, mp = _f64([float("nan") if v is None else float(v) for v in mean_times])
+    c, cp = _f64(layer_costs)
+    b = (C.c_int32 * len(bounds_cur))(*[int(v) for v in bounds_cur])
+    n = len(bounds_cur) - 1
+    out = np.zeros(n, dtype=np.float64)
+    _chk(lib.ftp_repartition_capacities(mp, cp, len(c), b, n, out.ctypes.data_as(_dp)))
+    return [float(v) for v in out]
 
 
 def redistribution_plan(bounds_new, bounds_cur, i_fail, i_cur, i_new):

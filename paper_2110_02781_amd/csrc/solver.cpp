@@ -135,3 +135,30 @@ extern "C" int ftp_redistribution_plan(const int32_t* bounds_new, int n_new, con
   }
   return FTP_OK;
 }
+
+// Re-partition schedule (section "Dynamic Model Partition"): first after 10 trained batches, then every 100.
+extern "C" int ftp_repartition_due(int64_t batches_done, int* due) {
+  if (!due || batches_done < 0) { ftp_set_error("repartition_due: batches_done >= 0 and a non-NULL result required"); return FTP_ERR_ARG; }
+  *due = batches_done == 10 || (batches_done > 10 && (batches_done - 10) % 100 == 0);
+  return FTP_OK;
+}
+
+// Capacities for the next re-partition from the workers' reported mean execution times (capacity equations): the
+// central node keeps 1.0; with a report missing from any other worker all are taken equal.
+extern "C" int ftp_repartition_capacities(const double* mean_times, const double* layer_costs, int L, const int32_t* bounds_cur,
+                                          int n, double* capacities) {
+  if (!mean_times || !layer_costs || !capacities || !bounds_ok(bounds_cur, n) || bounds_cur[n] != L) {
+    ftp_set_error("repartition_capacities: NULL argument or bounds that do not cover the %d layers", L);
+    return FTP_ERR_ARG;
+  }
+  bool all = true;
+  for (int i = 1; i < n; ++i) all = all && std::isfinite(mean_times[i]) && mean_times[i] > 0.0;
+  capacities[0] = 1.0;
+  for (int i = 1; i < n; ++i) {
+    capacities[i] = 1.0;
+    if (!all) continue;
+    int rc = ftp_estimate_capacity(mean_times[i], layer_costs, L, bounds_cur[i], bounds_cur[i + 1] - 1, &capacities[i]);
+    if (rc) return rc;
+  }
+  return FTP_OK;
+}

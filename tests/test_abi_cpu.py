@@ -129,3 +129,22 @@ def test_redistribution_plan_rejects_bad_arguments(P):
         P.redistribution_plan([0, 4, 8], [0, 4, 8], 1, 1, 0)             # the failed worker asks
     with pytest.raises(RuntimeError):
         P.redistribution_plan([0, 4, 8], [0, 4, 8], None, 2, 0)          # index out of range
+
+
+def test_repartition_schedule_and_capacities_match_oracle(P):
+    from oracle.partition import repartition_due, repartition_capacities
+    assert [b for b in range(0, 450) if P.repartition_due(b)] == [b for b in range(0, 450) if repartition_due(b)] == [10, 110, 210, 310, 410]
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        L = int(rng.integers(3, 14)); n = int(rng.integers(1, min(L, 5) + 1))
+        costs = rng.uniform(0.5, 9.0, L)
+        cuts = sorted(rng.choice(np.arange(1, L), size=n - 1, replace=False).tolist()) if n > 1 else []
+        bounds = [0] + cuts + [L]
+        means = [None if rng.random() < 0.15 else float(rng.uniform(1.0, 50.0)) for _ in range(n)]
+        got = P.repartition_capacities(means, costs, bounds)
+        ref = repartition_capacities(means, list(costs), bounds)
+        assert got == ref                                    # same float64 operations in the same order
+    with pytest.raises(RuntimeError):
+        P.repartition_capacities([1.0, 2.0], [1.0, 1.0, 1.0], [0, 1, 2])      # bounds do not cover the layers
+    with pytest.raises(RuntimeError):
+        P.repartition_due(-1)
