@@ -117,6 +117,12 @@ static int build_unit(const ftp_unit_desc& d, int H, int W, int C, int idx, Unit
         return FTP_ERR_SHAPE;
       }
       int ce = C * d.expand;
+      // the depthwise kernels address inside one image with 32-bit offsets formed from 24-bit factors
+      if ((size_t)H * W >= ((size_t)1 << 24) || (size_t)H * W * ce >= ((size_t)1 << 31) || ce >= (1 << 24)) {
+        ftp_set_error("unit %d (INVRES): a %dx%dx%d expanded feature map is beyond the depthwise kernels' in-image offsets "
+                      "(H*W < 2^24 and H*W*C < 2^31)", idx, H, W, ce);
+        return FTP_ERR_UNSUPPORTED;
+      }
       if (d.expand != 1) add_sub(SUB_PW, H, W, C, ce, 1, 1, 1, 0, 0, FTP_ACT_RELU6);
       Sub dw = add_sub(SUB_DW, H, W, ce, ce, 3, 3, d.stride, 1, 1, FTP_ACT_RELU6);
       add_sub(SUB_PW, dw.g.Hout, dw.g.Wout, ce, d.cout, 1, 1, 1, 0, 0, FTP_ACT_NONE);

@@ -148,3 +148,15 @@ def test_repartition_schedule_and_capacities_match_oracle(P):
         P.repartition_capacities([1.0, 2.0], [1.0, 1.0, 1.0], [0, 1, 2])      # bounds do not cover the layers
     with pytest.raises(RuntimeError):
         P.repartition_due(-1)
+
+
+def test_model_create_rejects_feature_maps_beyond_the_depthwise_offsets(P):
+    """Host check, no GPU: the depthwise kernels form in-image offsets in 32 bits."""
+    import paper_2110_02781_amd.binding as B
+    unit = [dict(kind=B.UNIT_INVRES, cin=8, cout=8, stride=1, expand=6)]
+    with pytest.raises(RuntimeError):
+        P.model_create(unit, 8192, 4096, 8, P.BF16)          # H*W = 2^25
+    with pytest.raises(RuntimeError):
+        P.model_create(unit, 4096, 4000, 8 * 20, P.BF16)     # H*W*C*expand >= 2^31
+    m = P.model_create(unit, 1024, 1024, 8, P.BF16)
+    P.model_destroy(m)
