@@ -416,13 +416,25 @@ struct DwPatch {
   }
 };
 
-// the slab's weights as float [9][CGB][8]
+// the slab's weights as float [9][CGB][8].  All global loads are issued before the first LDS store (at most five
+// per thread: 9 * 16 * 8 values over 256 threads): loaded and stored one by one, every round cost a memory round trip
+// that nothing else in the block could hide.
 template <typename T>
-__device__ __forceinline__ void dw_stage_weights(float* wl, const T* __restrict__ w, int C, int cg0, int CGB) {
-  for (int i = threadIdx.x; i < 9 * CGB * 8; i += blockDim.x) {
-    const int e = i % 8, c8 = (i / 8) % CGB, t = i / (8 * CGB);
+__device__ __forceinline__ void dw_stage_weights(float* wl, const T* __restrict__ w, int C, int cg0, int CGB, unsigned m_cgb) {
+  constexpr int NV = 5;
+  const int n = 9 * CGB * 8;
+  float v[NV];
+#pragma unroll
+  for (int q = 0; q < NV; ++q) {
+    const int i = threadIdx.x + q * 256;
+    const int e = i & 7, t = dw_div(i >> 3, m_cgb), c8 = (i >> 3) - t * CGB;      // i >> 3 < 160
     const int c = (cg0 + c8) * 8 + e;
-    wl[i] = c < C ? to_f32(w[(size_t)c * 9 + t]) : 0.f;
+    v[q] = (i < n && c < C) ? to_f32(w[(size_t)c * 9 + t]) : 0.f;
+  }
+#pragma unroll
+  for (int q = 0; q < NV; ++q) {
+    const int i = threadIdx.x + q * 256;
+    if (i < n) wl[i] = v[q];
   }
 }
 
@@ -441,7 +453,7 @@ __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ 
   const int ho0 = th * d.TH, wo0 = tw * d.TW, cg0 = slab * d.CGB;
   DwPatch<T> lp;
   lp.fetch(reinterpret_cast<const T*>(in.z), n, ho0 * S - 1, wo0 * S - 1, d, Hin, Win, C, cg0);
-  dw_stage_weights(wl, w, C, cg0, d.CGB);
+  dw_stage_weights(wl, w, C, cg0, d.CGB, d.m_cgb);
   lp.commit(patch, in, d, cg0);
   __syncthreads();
   const int QB = 2 * d.CGB, seg0 = dw_div(threadIdx.x, d.m_qb), cq = threadIdx.x - seg0 * QB;
@@ -838,7 +850,7 @@ __global__ __launch_bounds__(256) void dw_dgrad_s2_k(const T* __restrict__ dz, c
   DwPatch<T> lp;
   View none{nullptr, nullptr, nullptr, 0};
   lp.fetch(dz, n, ho_lo, wo_lo, d, Hout, Wout, C, cg0);
-  dw_stage_weights(wl, w, C, cg0, d.CGB);
+  dw_stage_weights(wl, w, C, cg0, d.CGB, d.m_cgb);
   lp.commit(patch, none, d, cg0);
   __syncthreads();
   const int QB = 2 * d.CGB, seg0 = dw_div(threadIdx.x, d.m_qb), cq = threadIdx.x - seg0 * QB;
