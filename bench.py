@@ -326,7 +326,7 @@ def main():
     SPINUP_S = args.spinup
     if args.gpus != 1:
         print("bench.py: this build runs one pipeline stage on ONE GPU; --gpus must be 1 "
-              "(no multi-GPU path exists, see DESIGN.md 'More than one GPU')", file=sys.stderr)
+              "(no multi-GPU path exists: a pipeline would put one stage on each GPU and exchange only the boundary tensors)", file=sys.stderr)
         sys.exit(2)
 
     import torch
