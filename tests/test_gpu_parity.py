@@ -66,6 +66,13 @@ SINGLE = [
     ("invres_t1", invres_unit(32, 16, 1, 1), (6, 6, 32), 4),
     ("invres_t1_res", invres_unit(16, 16, 1, 1), (6, 5, 16), 4),
     ("invres_wide", invres_unit(88, 136, 2, 6), (7, 7, 88), 3),
+    # more than 2048 rows (the tiled / streaming kernels), with nothing a multiple of a tile: rows not of 128 or 32,
+    # feature maps not of 8x16, channels of 8 only
+    ("invres_ragged_big_s1_res", invres_unit(40, 40, 1, 6), (37, 29, 40), 3),
+    ("invres_ragged_big_s2", invres_unit(24, 40, 2, 4), (75, 61, 24), 2),
+    ("invres_ragged_mixed_s2", invres_unit(40, 72, 2, 6), (37, 29, 40), 3),
+    ("pw_ragged_big", conv_unit(40, 72, 1, 1, 1, 0, 0, L.ACT_RELU6), (37, 61, 40), 2),
+    ("stem_ragged_big_s2", conv_unit(3, 24, 3, 3, 2, 1, 1, L.ACT_RELU6), (75, 61, 3), 3),
 ]
 
 
