@@ -418,6 +418,51 @@ def test_recomputation_along_the_one_f_one_b_schedule(dtype):
         pair.close()
 
 
+def test_recomputation_on_a_two_stream_stage_is_bit_identical():
+    """A stage large enough to run its weight gradients on the second stream (largest activation 58 MB), two
+    micro-batches in flight: the recomputing stage's second forward runs in front of each backward while nothing
+    of the previous backward is pending, so it must leave exactly the weights of the stage that keeps everything."""
+    import torch
+    import paper_2110_02781_amd as P
+    print("recomputation, 224x224 w1.4 batch 16 bf16, two slots", flush=True)
+    units = P.models.mobilenet_v2_units(1.4, 1000, 2)
+    model = P.model_create(units, 224, 224, 3, P.BF16)
+    L = P.model_num_units(model)
+    params = P.models.init_unit_params(units, 71)
+    stages = [P.stage_create(model, 0, L, 16, 2, f) for f in (0, P.STAGE_RECOMPUTE)]
+    try:
+        dev = torch.device("cuda:0")
+        for st in stages:
+            for i in range(L):
+                P.stage_import_weights(st, i, params[i])
+        xs = [torch.from_numpy(synth.normal(71, f"x{k}", (16, 224, 224, 3)).astype(np.float32)).to(dev).to(torch.bfloat16) for k in range(2)]
+        ls = [torch.from_numpy(synth.labels(71, f"l{k}", 16, 1000).astype(np.int32)).to(dev) for k in range(2)]
+        loss = torch.zeros(1, dtype=torch.float32, device=dev)
+        sp = torch.cuda.current_stream().cuda_stream
+        assert P.stage_device_bytes(stages[1]) < P.stage_device_bytes(stages[0])
+        for rep in range(2):
+            for st in stages:
+                for k in range(2):
+                    P.stage_forward(st, k, xs[k], None, sp)
+                    P.stage_loss(st, k, ls[k], loss, sp)
+                for k in range(2):
+                    P.stage_backward(st, k, None, None, sp)
+                P.stage_update(st, 0.005, 0.9, 4e-5, sp)
+            torch.cuda.synchronize()
+            for i in range(L):
+                n = P.model_unit_param_count(model, i)
+                if n:
+                    assert np.array_equal(P.stage_export_weights(stages[0], i, n), P.stage_export_weights(stages[1], i, n)), \
+                        f"mini-batch {rep}: unit {i} differs"
+                nb = P.model_unit_bn_channels(model, i)
+                if nb:
+                    assert np.array_equal(P.stage_export_bn_stats(stages[0], i, 2 * nb), P.stage_export_bn_stats(stages[1], i, 2 * nb))
+    finally:
+        for st in stages:
+            P.stage_destroy(st)
+        P.model_destroy(model)
+
+
 def test_recomputation_call_order_errors():
     """With recomputation the logits of a slot are gone once another slot has been forwarded."""
     import paper_2110_02781_amd as P
