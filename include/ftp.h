@@ -18,6 +18,11 @@
  *     addresses.  `stream` is a hipStream_t passed as void* (NULL = default
  *     stream).  Compute calls are asynchronous on that stream; import / export /
  *     profile / solve are synchronous.
+ *   - The compute calls of one stage share its workspace: issue them in program
+ *     order on one stream (or on streams the caller has ordered with events).
+ *     A large stage runs its weight gradients on a stream of its own inside
+ *     ftp_stage_backward; that work is ordered before anything enqueued on the
+ *     caller's stream after the call.  Different stages are independent.
  *   - Activations are NHWC (channels fastest): [batch, H, W, C]; a 1-D window of
  *     T steps is H = 1, W = T.  Their element type is the model's ftp_dtype
  *     (float, or bfloat16 with fp32 accumulation, statistics, gradients of
