@@ -333,6 +333,7 @@ struct DwPlan {
   unsigned m_cgb, m_qb, m_pw, m_segw;   // reciprocals for dw_div (divisors < 64, dividends < 1024)
 };
 enum { kDwFillNV = 6 };     // passes the patch staging is unrolled for
+enum { kDwSegs = 2 };       // 4-pixel runs of a tile a weight-gradient thread keeps the dz of
 
 // x / d for x < 1024, d < 64 with m = 65536 / d + 1: two full-rate instructions instead of the
 // ~25-instruction integer division sequence (thread-index decoding was a third of the kernel's VALU work)
@@ -490,10 +491,15 @@ __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ 
 
 static size_t dw_lds_bytes(const DwPlan& d) { return ((size_t)d.PH * d.PW + 9) * d.CGB * 8 * 4; }
 
-static void dw_check_plan(DwPlan& d) {
-  // staging is unrolled for kDwFillNV passes; dw_div needs small divisors
-  if (d.PH * d.PW > kDwFillNV * d.PPB || d.PW > 63 || d.CGB > 16 || d.segw > 32) abort();
+// staging is unrolled for kDwFillNV passes; dw_div needs small divisors.  The plans of every shape a model can
+// describe satisfy this; if one ever does not, the launch is skipped and the stage call reports it.
+static bool dw_check_plan(DwPlan& d) {
+  if (d.PH * d.PW > kDwFillNV * d.PPB || d.PW > 63 || d.CGB > 16 || d.segw > 32 || d.nseg > kDwSegs * d.spp) {
+    launch_plan_failed("depthwise tile plan outside the kernels' limits");
+    return false;
+  }
   d.m_pw = dw_magic(d.PW);
+  return true;
 }
 
 void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z) {
@@ -502,7 +508,7 @@ void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, 
   d.PH = (d.TH - 1) * s + 3;
   d.PW = (d.segw * 4 - 1) * s + 3;               // runs are whole: the patch covers the rounded-up tile width
   d.ntiles = g.N * d.tiles_h * d.tiles_w;
-  dw_check_plan(d);
+  if (!dw_check_plan(d)) return;
   View v{in.z, in.scale, in.shift, in.act};
   size_t total = (size_t)g.N * g.Hout * g.Wout;
   KScope ks(st, "dw_fwd", ((double)g.N * g.Hin * g.Win * g.Cout + (double)total * g.Cout) * es, 18.0 * total * g.Cout,
@@ -901,14 +907,14 @@ void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvG
     // the forward kernel on dz with the weights flipped
     d.PH = d.TH + 2;
     d.PW = d.segw * 4 + 2;
-    dw_check_plan(d);
+    if (!dw_check_plan(d)) return;
     View v{dz, nullptr, nullptr, 0};
     FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 1, true>), dim3(grid), dim3(256), dw_lds_bytes(d), st, v, (const T*)w, d,
                                         g.Hout, g.Wout, g.Hin, g.Win, g.Cout, (T*)dIn));
   } else {
     d.PH = d.TH / 2 + 2;
     d.PW = d.segw * 2 + 2;
-    dw_check_plan(d);
+    if (!dw_check_plan(d)) return;
     FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_dgrad_s2_k<T>, dim3(grid), dim3(256), dw_lds_bytes(d), st, (const T*)dz, (const T*)w,
                                         d, g.Hin, g.Win, g.Hout, g.Wout, g.Cout, (T*)dIn));
   }
@@ -931,7 +937,6 @@ __device__ __forceinline__ float4 raw4_unpack(const Raw4<bf16_t>& r) {
 
 // The dz values of a thread's (at most kDwSegs) 4-pixel runs of one tile, requested a whole tile ahead like the
 // input patch: a persistent block has few neighbours on its CU to hide a load behind.
-enum { kDwSegs = 2 };
 template <typename T>
 struct DwDzRuns {
   Raw4<T> r[kDwSegs][4];
@@ -1051,7 +1056,6 @@ static DwPlan dw_wgrad_plan(const ConvGeom& g, int es, size_t* lds) {
   d.ntiles = g.N * d.tiles_h * d.tiles_w;
   const int cap = 512 / d.nslab > 1 ? 512 / d.nslab : 1;   // about 512 persistent blocks over all slabs
   d.nblocks = d.ntiles < cap ? d.ntiles : cap;
-  if (d.nseg > kDwSegs * d.spp) abort();                   // a thread holds the dz of at most kDwSegs runs per tile
   size_t a = (size_t)d.PH * d.PW * d.CGB * 8 * 4;
   size_t b = (size_t)d.spp * 9 * 2 * d.CGB * 16;
   *lds = a > b ? a : b;
@@ -1069,7 +1073,7 @@ void dw_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& 
   const int es = dt == 0 ? 4 : 2;
   size_t lds;
   DwPlan d = dw_wgrad_plan(g, es, &lds);
-  dw_check_plan(d);
+  if (!dw_check_plan(d)) return;     // also: a thread holds the dz of at most kDwSegs runs per tile
   View v{in.z, in.scale, in.shift, in.act};
   {
     KScope ks(st, "dw_wgrad", ((double)g.N * g.Hin * g.Win * g.Cout + (double)g.N * g.Hout * g.Wout * g.Cout) * es + (double)d.nblocks * 9 * g.Cout * 4,

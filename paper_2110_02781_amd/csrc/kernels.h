@@ -20,6 +20,11 @@ struct KScope {
   hipStream_t st;
 };
 
+// A launcher that finds its own launch plan outside what its kernel was written for skips the launch and says so here;
+// the stage call that enqueued it returns an error (launch_plan_failure_take returns the text once, or nullptr).
+void launch_plan_failed(const char* what);
+const char* launch_plan_failure_take();
+
 struct HView {  // same layout as the device-side View
   const void* z;
   const float* scale;

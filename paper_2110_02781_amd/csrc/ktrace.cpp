@@ -24,6 +24,10 @@ struct Trace {
 }  // namespace
 
 namespace ftp {
+static const char* g_plan_failure = nullptr;
+void launch_plan_failed(const char* what) { g_plan_failure = what; }
+const char* launch_plan_failure_take() { const char* w = g_plan_failure; g_plan_failure = nullptr; return w; }
+
 KScope::KScope(hipStream_t s, const char* name, double alg_bytes, double flops, long d0, long d1, long d2) : slot(-1), st(s) {
   if (!g_trace.on) return;
   if (g_trace.used >= g_trace.recs.size()) { g_trace.overflow = true; return; }

@@ -450,6 +450,7 @@ extern "C" int ftp_stage_import_weights(ftp_stage* s, int unit, const float* hos
   if (s->w_lp) {
     f32_to_storage(FTP_BF16, nullptr, s->params + p.p_off, (char*)s->w_lp + p.p_off * 2, n);
     HIP_TRY(hipGetLastError());
+  if (const char* why = launch_plan_failure_take()) { ftp_set_error("%s", why); return FTP_ERR_UNSUPPORTED; }
     HIP_TRY(hipDeviceSynchronize());
   }
   return FTP_OK;
@@ -706,6 +707,7 @@ extern "C" int ftp_stage_forward(ftp_stage* s, int slot, const void* x_dev, void
   }
   if (s->timer && sl.timer_idx >= 0) HIP_TRY(hipEventRecord(s->timer->ev[sl.timer_idx][1], st));
   HIP_TRY(hipGetLastError());
+  if (const char* why = launch_plan_failure_take()) { ftp_set_error("%s", why); return FTP_ERR_UNSUPPORTED; }
   sl.busy = true; sl.has_snap = false; sl.has_loss = false;
   return FTP_OK;
 }
@@ -729,6 +731,7 @@ extern "C" int ftp_stage_loss(ftp_stage* s, int slot, const int32_t* labels_dev,
   softmax_ce(s->dt, st, v.unit_in[li].z, labels_dev, s->batch, s->classes, s->row_loss, sl.dlogits, loss_dev);
   if (s->prof) HIP_TRY(hipEventRecord(s->prof->f1[li], st));
   HIP_TRY(hipGetLastError());
+  if (const char* why = launch_plan_failure_take()) { ftp_set_error("%s", why); return FTP_ERR_UNSUPPORTED; }
   sl.has_loss = true;
   return FTP_OK;
 }
@@ -774,6 +777,7 @@ extern "C" int ftp_stage_copy_units(ftp_stage* dst, const ftp_stage* src, int un
     }
   }
   HIP_TRY(hipGetLastError());
+  if (const char* why = launch_plan_failure_take()) { ftp_set_error("%s", why); return FTP_ERR_UNSUPPORTED; }
   return FTP_OK;
 }
 
@@ -797,6 +801,7 @@ extern "C" int ftp_stage_aggregate_weights(ftp_stage* s, const int* slots, int n
   }
   if (s->n_param) aggregate_weights((hipStream_t)stream, s->params, s->w_lp, src, n, s->n_param);
   HIP_TRY(hipGetLastError());
+  if (const char* why = launch_plan_failure_take()) { ftp_set_error("%s", why); return FTP_ERR_UNSUPPORTED; }
   return FTP_OK;
 }
 
@@ -994,6 +999,7 @@ extern "C" int ftp_stage_backward(ftp_stage* s, int slot, const void* dy_dev, vo
     sl.timer_idx = -1;
   }
   HIP_TRY(hipGetLastError());
+  if (const char* why = launch_plan_failure_take()) { ftp_set_error("%s", why); return FTP_ERR_UNSUPPORTED; }
   sl.busy = false; sl.has_snap = false; sl.has_loss = false;
   return FTP_OK;
 }
@@ -1051,6 +1057,7 @@ extern "C" int ftp_stage_update(ftp_stage* s, const ftp_sgd* opt, void* stream) 
   }
   if (s->n_param) sgd_update((hipStream_t)stream, s->params, s->grads, s->mom, s->w_lp, s->n_param, opt->lr, opt->momentum, opt->weight_decay);
   HIP_TRY(hipGetLastError());
+  if (const char* why = launch_plan_failure_take()) { ftp_set_error("%s", why); return FTP_ERR_UNSUPPORTED; }
   return FTP_OK;
 }
 
