@@ -318,7 +318,7 @@ void conv_direct_dgrad_gemm(int dt, hipStream_t st, const void* dz, const void* 
 
 // ================================================================ depthwise 3x3
 // A block owns a slab of CGB*8 channels (128 bytes of every pixel) of one spatial tile.  The input
-// patch with its one-pixel halo is staged in LDS once as floats, already passed through the
+// patch with its one-pixel halo is staged in LDS once in the tensor's own type, already passed through the
 // producer's BatchNorm + activation and with zeros outside the image, so HBM sees every input
 // element once per tile.  A thread then owns 4 channels of a horizontal run of 4 pixels: per kernel
 // row it reads the 6 (stride 1) or 9 (stride 2) patch vectors under the run once and uses each for
@@ -388,7 +388,7 @@ struct DwPatch {
       if (pw >= d.PW) { pw -= d.PW; ++ph; }
     }
   }
-  __device__ __forceinline__ void commit(float* patch, const View& vw, const DwPlan& d, int cg0) const {
+  __device__ __forceinline__ void commit(T* patch, const View& vw, const DwPlan& d, int cg0) const {
     const int pl = dw_div(threadIdx.x, d.m_cgb), cg = threadIdx.x - pl * d.CGB;
     if (pl >= d.PPB) return;
     const int npix = d.PH * d.PW;
@@ -399,7 +399,7 @@ struct DwPatch {
       load8(vw.shift + (cg0 + cg) * 8, sh);
     }
     const float lo = act_lo(vw.act), hi = act_hi(vw.act);
-    float* dst = patch + (pl * d.CGB + cg) * 8;
+    T* dst = patch + (pl * d.CGB + cg) * 8;            // stored in the tensor's own type: the values are already rounded to it
     const int step = d.PPB * d.CGB * 8;
 #pragma unroll
     for (int q = 0; q < kDwFillNV; ++q) {
@@ -446,8 +446,8 @@ __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ 
                                                  int Wout, int C, T* __restrict__ out) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   if (FLIP) __builtin_amdgcn_s_setprio(3);   // data-gradient chain: ahead of the weight-gradient stream's waves
-  float* patch = reinterpret_cast<float*>(smem_raw);
-  float* wl = patch + (size_t)d.PH * d.PW * d.CGB * 8;
+  T* patch = reinterpret_cast<T*>(smem_raw);
+  float* wl = reinterpret_cast<float*>(smem_raw + (((size_t)d.PH * d.PW * d.CGB * 8 * sizeof(T) + 15) / 16 * 16));
   const int lb = xcd_logical_block();
   const int tile = lb % d.ntiles, slab = lb / d.ntiles;
   const int tw = tile % d.tiles_w, th = (tile / d.tiles_w) % d.tiles_h, n = tile / (d.tiles_w * d.tiles_h);
@@ -473,10 +473,10 @@ __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ 
     for (int o = 0; o < 4; ++o) acc[o] = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
     for (int ky = 0; ky < 3; ++ky) {
-      const float* row = patch + (size_t)((hl * S + ky) * d.PW + wl0 * S) * vs + c4;
+      const T* row = patch + (size_t)((hl * S + ky) * d.PW + wl0 * S) * vs + c4;
       float4 iv[3 * S + 3];
 #pragma unroll
-      for (int x = 0; x < 3 * S + 3; ++x) iv[x] = ld4(row + (size_t)x * vs);
+      for (int x = 0; x < 3 * S + 3; ++x) iv[x] = load4(row + (size_t)x * vs);
 #pragma unroll
       for (int kx = 0; kx < 3; ++kx)
 #pragma unroll
@@ -489,7 +489,9 @@ __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ 
   }
 }
 
-static size_t dw_lds_bytes(const DwPlan& d) { return ((size_t)d.PH * d.PW + 9) * d.CGB * 8 * 4; }
+// LDS layout: the patch as T [PH][PW][CGB][8], then (16-byte aligned) the weights as float [9][CGB][8]
+static size_t dw_patch_bytes(const DwPlan& d, int es) { return (((size_t)d.PH * d.PW * d.CGB * 8 * es) + 15) / 16 * 16; }
+static size_t dw_lds_bytes(const DwPlan& d, int es) { return dw_patch_bytes(d, es) + (size_t)9 * d.CGB * 8 * 4; }
 
 // staging is unrolled for kDwFillNV passes; dw_div needs small divisors.  The plans of every shape a model can
 // describe satisfy this; if one ever does not, the launch is skipped and the stage call reports it.
@@ -515,10 +517,10 @@ void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, 
             (long)total, g.Cout, g.stride);
   const unsigned grid = (unsigned)d.ntiles * d.nslab;
   if (s == 1) {
-    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 1, false>), dim3(grid), dim3(256), dw_lds_bytes(d), st, v, (const T*)w, d,
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 1, false>), dim3(grid), dim3(256), dw_lds_bytes(d, es), st, v, (const T*)w, d,
                                         g.Hin, g.Win, g.Hout, g.Wout, g.Cout, (T*)z));
   } else {
-    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 2, false>), dim3(grid), dim3(256), dw_lds_bytes(d), st, v, (const T*)w, d,
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 2, false>), dim3(grid), dim3(256), dw_lds_bytes(d, es), st, v, (const T*)w, d,
                                         g.Hin, g.Win, g.Hout, g.Wout, g.Cout, (T*)z));
   }
 }
@@ -845,8 +847,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void dw_dgrad_s2_k(const T* __restrict__ dz, const T* __restrict__ w, DwPlan d, int Hin,
                                                      int Win, int Hout, int Wout, int C, T* __restrict__ dIn) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  float* patch = reinterpret_cast<float*>(smem_raw);
-  float* wl = patch + (size_t)d.PH * d.PW * d.CGB * 8;
+  T* patch = reinterpret_cast<T*>(smem_raw);
+  float* wl = reinterpret_cast<float*>(smem_raw + (((size_t)d.PH * d.PW * d.CGB * 8 * sizeof(T) + 15) / 16 * 16));
   const int lb = xcd_logical_block();
   const int tile = lb % d.ntiles, slab = lb / d.ntiles;
   const int tw = tile % d.tiles_w, th = (tile / d.tiles_w) % d.tiles_h, n = tile / (d.tiles_w * d.tiles_h);
@@ -877,8 +879,8 @@ __global__ __launch_bounds__(256) void dw_dgrad_s2_k(const T* __restrict__ dz, c
     for (int i = 0; i < 3; ++i) {
       const int hn = h + 1 - i;
       if (hn & 1) continue;                        // also skips hn = -1
-      const float* row = patch + (size_t)((hn / 2 - ho_lo) * d.PW + wl0 / 2) * vs + c4;
-      const float4 d0 = ld4(row), d1 = ld4(row + vs), d2 = ld4(row + 2 * (size_t)vs);
+      const T* row = patch + (size_t)((hn / 2 - ho_lo) * d.PW + wl0 / 2) * vs + c4;
+      const float4 d0 = load4(row), d1 = load4(row + vs), d2 = load4(row + 2 * (size_t)vs);
       // pixel 0, 2 (even columns): tap j = 1; pixel 1, 3 (odd): taps j = 0 (next dz column) and j = 2
       acc[0] = fma4(d0, wr[i * 3 + 1], acc[0]);
       acc[1] = fma4(d1, wr[i * 3 + 0], acc[1]);
@@ -909,13 +911,13 @@ void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvG
     d.PW = d.segw * 4 + 2;
     if (!dw_check_plan(d)) return;
     View v{dz, nullptr, nullptr, 0};
-    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 1, true>), dim3(grid), dim3(256), dw_lds_bytes(d), st, v, (const T*)w, d,
+    FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 1, true>), dim3(grid), dim3(256), dw_lds_bytes(d, es), st, v, (const T*)w, d,
                                         g.Hout, g.Wout, g.Hin, g.Win, g.Cout, (T*)dIn));
   } else {
     d.PH = d.TH / 2 + 2;
     d.PW = d.segw * 2 + 2;
     if (!dw_check_plan(d)) return;
-    FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_dgrad_s2_k<T>, dim3(grid), dim3(256), dw_lds_bytes(d), st, (const T*)dz, (const T*)w,
+    FTP_DISPATCH(dt, hipLaunchKernelGGL(dw_dgrad_s2_k<T>, dim3(grid), dim3(256), dw_lds_bytes(d, es), st, (const T*)dz, (const T*)w,
                                         d, g.Hin, g.Win, g.Hout, g.Wout, g.Cout, (T*)dIn));
   }
 }
@@ -969,7 +971,7 @@ template <typename T, int S>
 __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View in, DwPlan d, int Hin, int Win, int Hout,
                                                   int Wout, int C, float* __restrict__ ws) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  float* patch = reinterpret_cast<float*>(smem_raw);
+  T* patch = reinterpret_cast<T*>(smem_raw);
   const int lb = xcd_logical_block();
   const int b = lb % d.nblocks, slab = lb / d.nblocks, cg0 = slab * d.CGB;
   const int QB = 2 * d.CGB, seg0 = dw_div(threadIdx.x, d.m_qb), cq = threadIdx.x - seg0 * QB;
@@ -1016,10 +1018,10 @@ __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View
           dv[o] = (cur.ok >> (4 * k + o)) & 1u ? raw4_unpack(cur.r[k][o]) : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
         for (int ky = 0; ky < 3; ++ky) {
-          const float* row = patch + (size_t)((hl * S + ky) * d.PW + wl0 * S) * vs + c4;
+          const T* row = patch + (size_t)((hl * S + ky) * d.PW + wl0 * S) * vs + c4;
           float4 iv[3 * S + 3];
 #pragma unroll
-          for (int x = 0; x < 3 * S + 3; ++x) iv[x] = ld4(row + (size_t)x * vs);
+          for (int x = 0; x < 3 * S + 3; ++x) iv[x] = load4(row + (size_t)x * vs);
 #pragma unroll
           for (int kx = 0; kx < 3; ++kx)
 #pragma unroll
@@ -1056,7 +1058,7 @@ static DwPlan dw_wgrad_plan(const ConvGeom& g, int es, size_t* lds) {
   d.ntiles = g.N * d.tiles_h * d.tiles_w;
   const int cap = 512 / d.nslab > 1 ? 512 / d.nslab : 1;   // about 512 persistent blocks over all slabs
   d.nblocks = d.ntiles < cap ? d.ntiles : cap;
-  size_t a = (size_t)d.PH * d.PW * d.CGB * 8 * 4;
+  size_t a = (size_t)d.PH * d.PW * d.CGB * 8 * es;          // the patch in the tensor's type
   size_t b = (size_t)d.spp * 9 * 2 * d.CGB * 16;
   *lds = a > b ? a : b;
   return d;
