@@ -409,7 +409,7 @@ struct DwPatch {
         raw_unpack(raw[q], val);
         if (view) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) val[e] = round_to<T>(clamp_act(fmaf(val[e], sc[e], sh[e]), lo, hi));
+          for (int e = 0; e < 8; ++e) val[e] = clamp_act(fmaf(val[e], sc[e], sh[e]), lo, hi);   // store8 rounds to T
         }
       }
       store8(dst + q * step, val);
