@@ -35,6 +35,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 enum { BJ = 64, CLD = BJ + 4 };
 enum { MODE_FWD = 0, MODE_DGRAD = 1, MODE_WGRAD = 2 };
+enum { kViewLds = 2048 };   // longest reduction whose view vectors (scale, shift) a forward GEMM block copies into LDS
 
 template <bool SMALL> struct Shape {
   enum { TI = SMALL ? 32 : 128, CH = SMALL ? 128 : 32 };
@@ -58,6 +59,12 @@ struct GemmArgs {
   int tiles_per_range;
   size_t mchunk;     // wgrad: pixels per split
 };
+
+// forward: copy the view vectors into LDS?  measured: pays from three reduction steps on; below that the copy costs
+// more than the loads it replaces
+__host__ __device__ static inline bool view_in_lds(const GemmArgs& a) {
+  return a.view.scale != nullptr && a.K <= (int)kViewLds && a.K >= 96;
+}
 
 // One operand tile: ROWS (i or j) x CH (r).  RC = source is r-contiguous (element (i,r) at
 // src[i*ld + r]); otherwise i-contiguous (element (i,r) at src[r*ld + i]) and transposed on the
@@ -291,6 +298,28 @@ struct VecTileLoader {   // r-contiguous source
       store8(lds + (PERM ? perm64(i) : i) * LD + r, val);
     }
   }
+
+  // The same with the view's scale / shift read from LDS copies indexed by the reduction index (lsc, lsh cover
+  // [0, nr)): fetched from global memory inside commit they cost a memory round trip per vector per step, after the
+  // tile had arrived and with nothing to hide it.
+  __device__ __forceinline__ void commit_lv(T* lds, size_t r0, const float* lsc, const float* lsh, int act) const {
+    const float lo = act_lo(act), hi = act_hi(act);
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int v = threadIdx.x + q * 256;
+      const int i = v / (CH / 8), r = (v % (CH / 8)) * 8;
+      const bool in = (ok >> q) & 1u;
+      float val[8];
+      raw_unpack(raw[q], val);
+      const size_t ch = in ? r0 + r : 0;
+      const float4 s0 = ld4(lsc + ch), s1 = ld4(lsc + ch + 4), h0 = ld4(lsh + ch), h1 = ld4(lsh + ch + 4);
+      const float sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+      const float sh[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) val[e] = in ? clamp_act(fmaf(val[e], sc[e], sh[e]), lo, hi) : 0.f;
+      store8(lds + (PERM ? perm64(i) : i) * LD + r, val);
+    }
+  }
 };
 
 template <typename T, int ROWS, int CH, bool USE_VIEW, bool PERM>
@@ -298,6 +327,23 @@ struct VecTransLoader {  // i-contiguous source, transposed into (r, r+1) pairs 
   enum { NITEM = (ROWS / 8) * (CH / 2), PER = (NITEM + 255) / 256, LD = CH + Pad<T>::V };
   Raw<T> raw[PER][2];
   unsigned ok;
+  // the view's scale / shift of this thread's columns: the same for every step of a block (the channel is the tile's
+  // i index), so they are loaded once (hold_view) instead of in every commit, where the load could not be hidden
+  float vsc[USE_VIEW ? PER : 1][8], vsh[USE_VIEW ? PER : 1][8];
+  bool held = false;
+
+  __device__ __forceinline__ void hold_view(const View& vw, size_t i0, size_t ni) {
+    if (!USE_VIEW || !vw.scale) return;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int item = threadIdx.x + q * 256;
+      const int i = (item / (CH / 2)) * 8;
+      const size_t ch = (item < NITEM && i0 + i < ni) ? i0 + i : 0;      // ni is a multiple of 8 here
+      load8(vw.scale + ch, vsc[q]);
+      load8(vw.shift + ch, vsh[q]);
+    }
+    held = true;
+  }
 
   __device__ __forceinline__ void fetch(const T* __restrict__ src, size_t ld, size_t i0, size_t ni, size_t r0,
                                         size_t nr) {
@@ -343,10 +389,15 @@ struct VecTransLoader {  // i-contiguous source, transposed into (r, r+1) pairs 
       raw_unpack(raw[q][0], val[0]);
       raw_unpack(raw[q][1], val[1]);
       if (view) {
-        const size_t ch = (in0 || in1) ? i0 + i : 0;     // same channels for both rows
         float sc[8], sh[8];
-        load8(vw.scale + ch, sc);
-        load8(vw.shift + ch, sh);
+        if (held) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) { sc[e] = vsc[USE_VIEW ? q : 0][e]; sh[e] = vsh[USE_VIEW ? q : 0][e]; }
+        } else {
+          const size_t ch = (in0 || in1) ? i0 + i : 0;     // same channels for both rows
+          load8(vw.scale + ch, sc);
+          load8(vw.shift + ch, sh);
+        }
         const float lo = act_lo(vw.act), hi = act_hi(vw.act);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -452,6 +503,8 @@ __global__ __launch_bounds__(256) void pw_gemm_k(GemmArgs p) {
   // wgrad  : X = dZ as (i=n, r=m),        Y = A' as (j=k, r=m) (both i-contiguous, view on Y)
   typename LoaderSel<T, TI, CH, MODE != MODE_WGRAD, MODE == MODE_FWD, false, VEC>::type lx;
   typename LoaderSel<T, BJ, CH, MODE == MODE_FWD, MODE == MODE_WGRAD, false, VEC>::type ly;
+  // weight gradient: the view vectors of this block's columns stay in registers (the same columns at every step)
+  if constexpr (MODE == MODE_WGRAD && VEC) ly.hold_view(p.view, j0, nj);
 
   f16v acc[2];
 #pragma unroll
@@ -646,6 +699,19 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
 
   typename LoaderSel<T, TI, CH, MODE != MODE_WGRAD, MODE == MODE_FWD, false, VEC>::type lx;
   typename LoaderSel<T, BJ, CH, MODE == MODE_FWD, MODE == MODE_WGRAD, true, VEC>::type ly;
+  // view vectors where a commit finds them without a trip to memory: forward in LDS (indexed by the reduction
+  // index), weight gradient in registers (the same columns at every step)
+  extern __shared__ __attribute__((aligned(16))) float vlds[];     // 2 * K floats when the launch asked for them
+  const int VL = p.K;                                              // K is a multiple of 8 here
+  bool lview = false;
+  if constexpr (MODE == MODE_FWD && VEC) {
+    lview = view_in_lds(p);
+    if (lview) {
+      for (int i = threadIdx.x; i < p.K; i += 256) { vlds[i] = p.view.scale[i]; vlds[VL + i] = p.view.shift[i]; }
+      __syncthreads();
+    }
+  }
+  if constexpr (MODE == MODE_WGRAD && VEC) ly.hold_view(p.view, j0, nj);
 
   f16v acc[2];
 #pragma unroll
@@ -672,7 +738,12 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
     const size_t i0 = (size_t)it * TI, r0 = rbeg + (size_t)kc * CH;
     T* xs = smem + (s & 1) * BUF;
     T* ys = xs + TI * LD;
-    lx.commit(xs, X, ldx, i0, ni, r0, rend, p.view);
+    if constexpr (MODE == MODE_FWD && VEC) {
+      if (lview) lx.commit_lv(xs, r0, vlds, vlds + VL, p.view.act);
+      else lx.commit(xs, X, ldx, i0, ni, r0, rend, p.view);
+    } else {
+      lx.commit(xs, X, ldx, i0, ni, r0, rend, p.view);
+    }
     if (!y_static || s < 2) ly.commit(ys, Y, ldy, j0, nj, r0, rend, p.view);
     __syncthreads();
     if (s + 1 < nsteps) {
@@ -988,9 +1059,10 @@ static void launch_t(hipStream_t st, const GemmArgs& a, bool small, unsigned gri
   const size_t red = MODE == MODE_FWD ? (size_t)a.K : MODE == MODE_DGRAD ? (size_t)a.N : a.mchunk;   // reduction extent of a block
   // measured: the weight gradient (both operands transposed on the way into LDS) gains 10-30 %, forward and data
   // gradient lose a little (fewer blocks fit a CU)
+  const size_t vbytes = (MODE == MODE_FWD && VEC && view_in_lds(a)) ? (size_t)2 * a.K * sizeof(float) : 0;
   if (MODE == MODE_WGRAD && sizeof(T) == 2 && red >= (size_t)kDeepReduction)
     hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, sizeof(T) == 2 ? 64 : 32>), dim3(grid), dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, 32>), dim3(grid), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, 32>), dim3(grid), dim3(256), vbytes, st, a);
 }
 
 template <int MODE>
