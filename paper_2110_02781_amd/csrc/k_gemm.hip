@@ -35,7 +35,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 enum { BJ = 64, CLD = BJ + 4 };
 enum { MODE_FWD = 0, MODE_DGRAD = 1, MODE_WGRAD = 2 };
-enum { kViewLds = 2048 };   // longest reduction whose view vectors (scale, shift) a forward GEMM block copies into LDS
 
 template <bool SMALL> struct Shape {
   enum { TI = SMALL ? 32 : 128, CH = SMALL ? 128 : 32 };
@@ -59,12 +58,6 @@ struct GemmArgs {
   int tiles_per_range;
   size_t mchunk;     // wgrad: pixels per split
 };
-
-// forward: copy the view vectors into LDS?  measured: pays from three reduction steps on; below that the copy costs
-// more than the loads it replaces
-__host__ __device__ static inline bool view_in_lds(const GemmArgs& a) {
-  return a.view.scale != nullptr && a.K <= (int)kViewLds && a.K >= 96;
-}
 
 // One operand tile: ROWS (i or j) x CH (r).  RC = source is r-contiguous (element (i,r) at
 // src[i*ld + r]); otherwise i-contiguous (element (i,r) at src[r*ld + i]) and transposed on the
@@ -260,6 +253,35 @@ struct VecTileLoader {   // r-contiguous source
   static_assert(NVEC % 256 == 0, "tile must divide over 256 threads");
   Raw<T> raw[PER];
   unsigned ok;
+  float psc[USE_VIEW ? PER : 1][8], psh[USE_VIEW ? PER : 1][8];   // view vectors requested together with the tile
+
+  // the scale / shift of the channels (= reduction indices) of the vectors that fetch() requests for the same step
+  __device__ __forceinline__ void fetch_view(const View& vw, size_t r0, size_t nr) {
+    if (!USE_VIEW || !vw.scale) return;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int v = threadIdx.x + q * 256;
+      const int r = (v % (CH / 8)) * 8;
+      const size_t ch = r0 + r < nr ? r0 + r : 0;
+      load8(vw.scale + ch, psc[q]);
+      load8(vw.shift + ch, psh[q]);
+    }
+  }
+  // commit with the view vectors that fetch_view requested
+  __device__ __forceinline__ void commit_pv(T* lds, int act) const {
+    const float lo = act_lo(act), hi = act_hi(act);
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int v = threadIdx.x + q * 256;
+      const int i = v / (CH / 8), r = (v % (CH / 8)) * 8;
+      const bool in = (ok >> q) & 1u;
+      float val[8];
+      raw_unpack(raw[q], val);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) val[e] = in ? clamp_act(fmaf(val[e], psc[USE_VIEW ? q : 0][e], psh[USE_VIEW ? q : 0][e]), lo, hi) : 0.f;
+      store8(lds + (PERM ? perm64(i) : i) * LD + r, val);
+    }
+  }
 
   __device__ __forceinline__ void fetch(const T* __restrict__ src, size_t ld, size_t i0, size_t ni, size_t r0,
                                         size_t nr) {
@@ -299,27 +321,6 @@ struct VecTileLoader {   // r-contiguous source
     }
   }
 
-  // The same with the view's scale / shift read from LDS copies indexed by the reduction index (lsc, lsh cover
-  // [0, nr)): fetched from global memory inside commit they cost a memory round trip per vector per step, after the
-  // tile had arrived and with nothing to hide it.
-  __device__ __forceinline__ void commit_lv(T* lds, size_t r0, const float* lsc, const float* lsh, int act) const {
-    const float lo = act_lo(act), hi = act_hi(act);
-#pragma unroll
-    for (int q = 0; q < PER; ++q) {
-      const int v = threadIdx.x + q * 256;
-      const int i = v / (CH / 8), r = (v % (CH / 8)) * 8;
-      const bool in = (ok >> q) & 1u;
-      float val[8];
-      raw_unpack(raw[q], val);
-      const size_t ch = in ? r0 + r : 0;
-      const float4 s0 = ld4(lsc + ch), s1 = ld4(lsc + ch + 4), h0 = ld4(lsh + ch), h1 = ld4(lsh + ch + 4);
-      const float sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
-      const float sh[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) val[e] = in ? clamp_act(fmaf(val[e], sc[e], sh[e]), lo, hi) : 0.f;
-      store8(lds + (PERM ? perm64(i) : i) * LD + r, val);
-    }
-  }
 };
 
 template <typename T, int ROWS, int CH, bool USE_VIEW, bool PERM>
@@ -518,18 +519,25 @@ __global__ __launch_bounds__(256) void pw_gemm_k(GemmArgs p) {
 
   if (nsteps > 0) {
     lx.fetch(X, ldx, (size_t)it_beg * TI, ni, rbeg, rend);
+    if constexpr (MODE == MODE_FWD && VEC) lx.fetch_view(p.view, rbeg, rend);
     ly.fetch(Y, ldy, j0, nj, rbeg, rend);
   }
   for (int s = 0; s < nsteps; ++s) {
     const int it = it_beg + s / nchunks, kc = s % nchunks;
     const size_t i0 = (size_t)it * TI, r0 = rbeg + (size_t)kc * CH;
     __syncthreads();                       // LDS free: previous multiply / output pass finished
-    lx.commit(xs, X, ldx, i0, ni, r0, rend, p.view);
+    if constexpr (MODE == MODE_FWD && VEC) {
+      if (p.view.scale) lx.commit_pv(xs, p.view.act);
+      else lx.commit(xs, X, ldx, i0, ni, r0, rend, p.view);
+    } else {
+      lx.commit(xs, X, ldx, i0, ni, r0, rend, p.view);
+    }
     ly.commit(ys, Y, ldy, j0, nj, r0, rend, p.view);
     __syncthreads();
     if (s + 1 < nsteps) {                  // next chunk travels while this one is multiplied
       const int it2 = it_beg + (s + 1) / nchunks, kc2 = (s + 1) % nchunks;
       lx.fetch(X, ldx, (size_t)it2 * TI, ni, rbeg + (size_t)kc2 * CH, rend);
+      if constexpr (MODE == MODE_FWD && VEC) lx.fetch_view(p.view, rbeg + (size_t)kc2 * CH, rend);
       ly.fetch(Y, ldy, j0, nj, rbeg + (size_t)kc2 * CH, rend);
     }
     if (SMALL) mma32(xs, ys, LD, lane & 31, lane, wave * 32, acc);
@@ -699,18 +707,8 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
 
   typename LoaderSel<T, TI, CH, MODE != MODE_WGRAD, MODE == MODE_FWD, false, VEC>::type lx;
   typename LoaderSel<T, BJ, CH, MODE == MODE_FWD, MODE == MODE_WGRAD, true, VEC>::type ly;
-  // view vectors where a commit finds them without a trip to memory: forward in LDS (indexed by the reduction
-  // index), weight gradient in registers (the same columns at every step)
-  extern __shared__ __attribute__((aligned(16))) float vlds[];     // 2 * K floats when the launch asked for them
-  const int VL = p.K;                                              // K is a multiple of 8 here
-  bool lview = false;
-  if constexpr (MODE == MODE_FWD && VEC) {
-    lview = view_in_lds(p);
-    if (lview) {
-      for (int i = threadIdx.x; i < p.K; i += 256) { vlds[i] = p.view.scale[i]; vlds[VL + i] = p.view.shift[i]; }
-      __syncthreads();
-    }
-  }
+  // weight gradient: the view vectors of this block's columns stay in registers (the same columns at every step);
+  // forward: they are requested together with the tile they belong to (fetch_view)
   if constexpr (MODE == MODE_WGRAD && VEC) ly.hold_view(p.view, j0, nj);
 
   f16v acc[2];
@@ -729,8 +727,10 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
     if (jc + 1 < nj) b1 = p.bias[jc + 1];
   }
 
+  const bool pview = MODE == MODE_FWD && VEC && p.view.scale != nullptr;   // view vectors travel with the tile
   if (nsteps > 0) {
     lx.fetch(X, ldx, (size_t)it_beg * TI, ni, rbeg, rend);
+    if constexpr (MODE == MODE_FWD && VEC) { if (pview) lx.fetch_view(p.view, rbeg, rend); }
     ly.fetch(Y, ldy, j0, nj, rbeg, rend);
   }
   for (int s = 0; s < nsteps; ++s) {
@@ -739,7 +739,7 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
     T* xs = smem + (s & 1) * BUF;
     T* ys = xs + TI * LD;
     if constexpr (MODE == MODE_FWD && VEC) {
-      if (lview) lx.commit_lv(xs, r0, vlds, vlds + VL, p.view.act);
+      if (pview) lx.commit_pv(xs, p.view.act);
       else lx.commit(xs, X, ldx, i0, ni, r0, rend, p.view);
     } else {
       lx.commit(xs, X, ldx, i0, ni, r0, rend, p.view);
@@ -749,6 +749,7 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
     if (s + 1 < nsteps) {
       const int it2 = it_beg + (s + 1) / nchunks, kc2 = (s + 1) % nchunks;
       lx.fetch(X, ldx, (size_t)it2 * TI, ni, rbeg + (size_t)kc2 * CH, rend);
+      if constexpr (MODE == MODE_FWD && VEC) { if (pview) lx.fetch_view(p.view, rbeg + (size_t)kc2 * CH, rend); }
       if (!y_static || s + 1 < 2) ly.fetch(Y, ldy, j0, nj, rbeg + (size_t)kc2 * CH, rend);
     }
 #pragma unroll
@@ -1059,10 +1060,9 @@ static void launch_t(hipStream_t st, const GemmArgs& a, bool small, unsigned gri
   const size_t red = MODE == MODE_FWD ? (size_t)a.K : MODE == MODE_DGRAD ? (size_t)a.N : a.mchunk;   // reduction extent of a block
   // measured: the weight gradient (both operands transposed on the way into LDS) gains 10-30 %, forward and data
   // gradient lose a little (fewer blocks fit a CU)
-  const size_t vbytes = (MODE == MODE_FWD && VEC && view_in_lds(a)) ? (size_t)2 * a.K * sizeof(float) : 0;
   if (MODE == MODE_WGRAD && sizeof(T) == 2 && red >= (size_t)kDeepReduction)
     hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, sizeof(T) == 2 ? 64 : 32>), dim3(grid), dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, 32>), dim3(grid), dim3(256), vbytes, st, a);
+  else hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, 32>), dim3(grid), dim3(256), 0, st, a);
 }
 
 template <int MODE>
