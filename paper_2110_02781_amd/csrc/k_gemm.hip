@@ -561,6 +561,16 @@ __global__ __launch_bounds__(256) void pw_gemm_k(GemmArgs p) {
     __syncthreads();
     const size_t jg = j0 + ocg * 8;
     const bool vec_out = (nj % 8) == 0;
+    // residual vectors of all rows of the pass first (see the row-streaming kernel)
+    float rpre[SMALL ? 1 : 4][8];
+    const bool res_pre = MODE == MODE_DGRAD && p.res != nullptr && vec_out && jg + 8 <= nj;
+    if (res_pre) {
+#pragma unroll
+      for (int q = 0; q < (SMALL ? 1 : 4); ++q) {
+        const size_t ig = i0 + orl + q * 32;
+        if (ig < ni) load8(reinterpret_cast<const T*>(p.res) + ig * p.K + jg, rpre[q]);
+      }
+    }
 #pragma unroll
     for (int q = 0; q < (SMALL ? 1 : 4); ++q) {
       const int row = orl + q * 32;
@@ -602,10 +612,8 @@ __global__ __launch_bounds__(256) void pw_gemm_k(GemmArgs p) {
         if (p.res) {
           const T* rs = reinterpret_cast<const T*>(p.res) + ig * p.K + jg;
           if (full) {
-            float rv[8];
-            load8(rs, rv);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] += rv[e];
+            for (int e = 0; e < 8; ++e) v[e] += rpre[q][e];      // full implies res_pre
           } else {
             for (int e = 0; e < 8 && jg + e < nj; ++e) v[e] += to_f32(rs[e]);
           }
@@ -666,7 +674,9 @@ __device__ __forceinline__ void load_pair(const bf16_t* p, float& a, float& b) {
 
 // CH = reduction elements staged per step: the bfloat16 weight gradient runs with 64, which halves the steps and
 // their barriers.
-template <typename T, int MODE, bool VEC, int CH>
+// RES: data gradient with a residual to add (a variant of its own: the sixteen prefetched residual pairs cost
+// registers that the plain data gradient should not pay for)
+template <typename T, int MODE, bool VEC, int CH, bool RES = false>
 __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
   constexpr int TI = 128;
   constexpr int LD = CH + Pad<T>::V;
@@ -763,6 +773,14 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
       // tests, one address computation per lane
       if (jc < nj) {
         const size_t obase = (MODE == MODE_WGRAD ? (size_t)split * p.N + irow : irow) * ldo + jc;
+        // all sixteen residual pairs are requested before the first store: res and out are not known to be
+        // distinct, so loads left between the stores are not moved up and each one waits for memory on its own
+        float ra[RES ? 16 : 1], rb[RES ? 16 : 1];
+        if (RES) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            load_pair(reinterpret_cast<const T*>(p.res) + obase + (size_t)(8 * (r / 4) + (r % 4)) * ldo, ra[RES ? r : 0], rb[RES ? r : 0]);
+        }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const size_t o = obase + (size_t)(8 * (r / 4) + (r % 4)) * ldo;
@@ -773,7 +791,7 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
             store_pair_rounded(reinterpret_cast<T*>(p.out) + o, v0, v1, a, b);
             if (p.stats) { s0 += a; q0 = fmaf(a, a, q0); s1 += b; q1 = fmaf(b, b, q1); }
           } else if (MODE == MODE_DGRAD) {
-            if (p.res) { float ra, rb; load_pair(reinterpret_cast<const T*>(p.res) + o, ra, rb); v0 += ra; v1 += rb; }
+            if (RES) { v0 += ra[RES ? r : 0]; v1 += rb[RES ? r : 0]; }
             store_pair(reinterpret_cast<T*>(p.out) + o, v0, v1);
           } else {
             store_pair(reinterpret_cast<float*>(p.out) + o, v0, v1);
@@ -801,7 +819,7 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
         }
       } else if (MODE == MODE_DGRAD) {
         T* dst = reinterpret_cast<T*>(p.out) + ig * ldo + jc;
-        if (p.res) {
+        if (RES) {
           const T* rs = reinterpret_cast<const T*>(p.res) + ig * ldo + jc;
           if (pair_ok) { float ra, rb; load_pair(rs, ra, rb); v0 += ra; v1 += rb; }
           else { v0 += to_f32(rs[0]); if (jc + 1 < nj) v1 += to_f32(rs[1]); }
@@ -1062,6 +1080,7 @@ static void launch_t(hipStream_t st, const GemmArgs& a, bool small, unsigned gri
   // gradient lose a little (fewer blocks fit a CU)
   if (MODE == MODE_WGRAD && sizeof(T) == 2 && red >= (size_t)kDeepReduction)
     hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, sizeof(T) == 2 ? 64 : 32>), dim3(grid), dim3(256), 0, st, a);
+  else if (MODE == MODE_DGRAD && a.res) hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, 32, MODE == MODE_DGRAD>), dim3(grid), dim3(256), 0, st, a);
   else hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, 32>), dim3(grid), dim3(256), 0, st, a);
 }
 
