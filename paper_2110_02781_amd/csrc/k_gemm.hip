@@ -865,6 +865,22 @@ __device__ __forceinline__ void load_frag(const float* p, float* v) {
   v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
 }
 __device__ __forceinline__ void load_frag(const bf16_t* p, float* v) { load8(p, v); }
+// A fragment as loaded: converted only after every load of a round has been issued.  A conversion next to its
+// (conditional) load makes the compiler wait for that one load before it issues the next.
+template <typename T> struct FragRaw;
+template <> struct FragRaw<float> { float4 v; };
+template <> struct FragRaw<bf16_t> { uint4 v; };
+__device__ __forceinline__ void frag_load(FragRaw<float>& r, const float* p) { r.v = *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ void frag_load(FragRaw<bf16_t>& r, const bf16_t* p) { r.v = *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ void frag_zero(FragRaw<float>& r) { r.v = make_float4(0.f, 0.f, 0.f, 0.f); }
+__device__ __forceinline__ void frag_zero(FragRaw<bf16_t>& r) { r.v = make_uint4(0u, 0u, 0u, 0u); }
+__device__ __forceinline__ void frag_unpack(const FragRaw<float>& r, float* v) { v[0] = r.v.x; v[1] = r.v.y; v[2] = r.v.z; v[3] = r.v.w; }
+__device__ __forceinline__ void frag_unpack(const FragRaw<bf16_t>& r, float* v) {
+  v[0] = __uint_as_float(r.v.x << 16); v[1] = __uint_as_float(r.v.x & 0xffff0000u);
+  v[2] = __uint_as_float(r.v.y << 16); v[3] = __uint_as_float(r.v.y & 0xffff0000u);
+  v[4] = __uint_as_float(r.v.z << 16); v[5] = __uint_as_float(r.v.z & 0xffff0000u);
+  v[6] = __uint_as_float(r.v.w << 16); v[7] = __uint_as_float(r.v.w & 0xffff0000u);
+}
 
 __device__ __forceinline__ f4v tiny_mma(const float* a, const float* b, f4v acc, float) {
 #pragma unroll
@@ -909,27 +925,41 @@ __device__ __forceinline__ void pw_gemm_tiny_body(const GemmArgs& p, const int b
   f4v acc = {0.f, 0.f, 0.f, 0.f};
   for (int s = sb; s < se; s += U) {
     float a[U][G], b[U][G], sc[U][G], sh[U][G];
+    FragRaw<T> ar[U], br[U];
+    T bs[U][G];                                // data gradient: single elements of W down a column
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int k = (s + u) * KS + kg;
       const bool ok = s + u < se && k < R;
+      frag_zero(ar[u]); frag_zero(br[u]);
 #pragma unroll
-      for (int e = 0; e < G; ++e) { a[u][e] = 0.f; b[u][e] = 0.f; sc[u][e] = 1.f; sh[u][e] = 0.f; }
+      for (int e = 0; e < G; ++e) { sc[u][e] = 1.f; sh[u][e] = 0.f; }
       if (ok && row_ok) {
-        load_frag(X + k, a[u]);
+        frag_load(ar[u], X + k);
         if (view) {
           load_frag(p.view.scale + k, sc[u]);
           load_frag(p.view.shift + k, sh[u]);
           if (G == 8) { load_frag(p.view.scale + k + 4, sc[u] + 4); load_frag(p.view.shift + k + 4, sh[u] + 4); }
         }
       }
-      if (ok && col_ok) {
-        if (MODE == MODE_FWD) {
-          load_frag(W + (size_t)col * p.K + k, b[u]);
-        } else {
+      if (MODE == MODE_FWD) {
+        if (ok && col_ok) frag_load(br[u], W + (size_t)col * p.K + k);
+      } else {
+        // unconditional, from rows / a column that exist (R is a multiple of G): zeroed below when out of range
+        const int kc = ok ? k : 0, cc = col_ok ? col : 0;
 #pragma unroll
-          for (int e = 0; e < G; ++e) b[u][e] = to_f32(W[(size_t)(k + e) * p.K + col]);
-        }
+        for (int e = 0; e < G; ++e) bs[u][e] = W[(size_t)(kc + e) * p.K + cc];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      frag_unpack(ar[u], a[u]);
+      if (MODE == MODE_FWD) {
+        frag_unpack(br[u], b[u]);
+      } else {
+        const bool okb = s + u < se && (s + u) * KS + kg < R && col_ok;
+#pragma unroll
+        for (int e = 0; e < G; ++e) b[u][e] = okb ? to_f32(bs[u][e]) : 0.f;
       }
     }
 #pragma unroll
@@ -1005,12 +1035,19 @@ __device__ __forceinline__ void pw_wgrad_tiny_body(const GemmArgs& p, const int 
   f4v acc = {0.f, 0.f, 0.f, 0.f};
   for (size_t m0 = mb; m0 < me; m0 += 4 * U) {
     float x[U], y[U];
+    T xr[U], yr[U];                            // converted after all loads of the round are out (see FragRaw)
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const size_t m = m0 + 4 * u + mg;
-      const bool ok = m < me;
-      x[u] = ok && n_ok ? to_f32(X[m * p.N]) : 0.f;
-      y[u] = ok && k_ok ? to_f32(Y[m * p.K]) : 0.f;
+      const size_t mc = m < me ? m : mb;       // unconditional loads from a valid row (X, Y point at valid columns)
+      xr[u] = X[mc * p.N];
+      yr[u] = Y[mc * p.K];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool ok = m0 + 4 * u + mg < me;
+      x[u] = ok && n_ok ? to_f32(xr[u]) : 0.f;
+      y[u] = ok && k_ok ? to_f32(yr[u]) : 0.f;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
