@@ -286,15 +286,20 @@ struct VecTileLoader {   // r-contiguous source
   __device__ __forceinline__ void fetch(const T* __restrict__ src, size_t ld, size_t i0, size_t ni, size_t r0,
                                         size_t nr) {
     ok = 0;
+    // every address first, then the loads back to back: an address computed between two loads can land in a
+    // register the compiler still counts as the target of an earlier load, and then each load waits for the one before
+    const T* ptr[PER];
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
       const int v = threadIdx.x + q * 256;
       const int i = v / (CH / 8), r = (v % (CH / 8)) * 8;
       const size_t gi = i0 + i, gr = r0 + r;
       const bool in = gi < ni && gr < nr;
-      raw_load(raw[q], in ? src + gi * ld + gr : src);
+      ptr[q] = in ? src + gi * ld + gr : src;
       ok |= (in ? 1u : 0u) << q;
     }
+#pragma unroll
+    for (int q = 0; q < PER; ++q) raw_load(raw[q], ptr[q]);
   }
 
   __device__ __forceinline__ void commit(T* lds, const T* __restrict__, size_t, size_t, size_t, size_t r0, size_t,
@@ -349,19 +354,24 @@ struct VecTransLoader {  // i-contiguous source, transposed into (r, r+1) pairs 
   __device__ __forceinline__ void fetch(const T* __restrict__ src, size_t ld, size_t i0, size_t ni, size_t r0,
                                         size_t nr) {
     ok = 0;
+    const T* ptr[PER][2];                    // every address first, then the loads back to back (see VecTileLoader)
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
       const int item = threadIdx.x + q * 256;
-      if (item >= NITEM) break;
       const int r = (item % (CH / 2)) * 2, i = (item / (CH / 2)) * 8;
       const size_t gi = i0 + i;
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const size_t gr = r0 + r + u;
-        const bool in = gr < nr && gi < ni;
-        raw_load(raw[q][u], in ? src + gr * ld + gi : src);
+        const bool in = item < NITEM && gr < nr && gi < ni;
+        ptr[q][u] = in ? src + gr * ld + gi : src;
         ok |= (in ? 1u : 0u) << (2 * q + u);
       }
+    }
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      raw_load(raw[q][0], ptr[q][0]);
+      raw_load(raw[q][1], ptr[q][1]);
     }
   }
 
@@ -736,6 +746,10 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
     if (jc < nj) b0 = p.bias[jc];
     if (jc + 1 < nj) b1 = p.bias[jc + 1];
   }
+  // Have the two values arrive here.  Their first use is in the tile epilogue inside the loop, where the compiler
+  // cannot tell how many younger loads are outstanding and waits for all of them: the prefetch of the next tile
+  // would be drained before every output pass.
+  asm volatile("" ::"v"(b0), "v"(b1));
 
   const bool pview = MODE == MODE_FWD && VEC && p.view.scale != nullptr;   // view vectors travel with the tile
   if (nsteps > 0) {
@@ -758,9 +772,11 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
     __syncthreads();
     if (s + 1 < nsteps) {
       const int it2 = it_beg + (s + 1) / nchunks, kc2 = (s + 1) % nchunks;
+      // the weight tile first: its registers may still be the target of a load the compiler has not seen consumed
+      // (its commit is conditional), and the wait for that must not come behind this step's other requests
+      if (!y_static || s + 1 < 2) ly.fetch(Y, ldy, j0, nj, rbeg + (size_t)kc2 * CH, rend);
       lx.fetch(X, ldx, (size_t)it2 * TI, ni, rbeg + (size_t)kc2 * CH, rend);
       if constexpr (MODE == MODE_FWD && VEC) { if (pview) lx.fetch_view(p.view, rbeg + (size_t)kc2 * CH, rend); }
-      if (!y_static || s + 1 < 2) ly.fetch(Y, ldy, j0, nj, rbeg + (size_t)kc2 * CH, rend);
     }
 #pragma unroll
     for (int c0 = 0; c0 < CH; c0 += 32) mma32(xs, ys, LD, wave * 32 + jl, lane, c0, acc);
