@@ -377,16 +377,21 @@ struct DwPatch {
     const T* img = src + (size_t)n * H * W * C + gcg * 8;
     const int npix = d.PH * d.PW, dph = dw_div(d.PPB, d.m_pw), dpw = d.PPB - dph * d.PW;
     int ph = dw_div(pl, d.m_pw), pw = pl - ph * d.PW;
+    // Offsets first, then the loads back to back and unconditional (a pixel outside the image or the patch reads the
+    // image's first pixel and is zeroed in commit): with a branch around each load, and its address computed next to
+    // it, every load waited for the one before.
+    unsigned off[kDwFillNV];
 #pragma unroll
     for (int q = 0; q < kDwFillNV; ++q) {
       const int h = h0 + ph, w = w0 + pw;
-      if (pl + q * d.PPB < npix && h >= 0 && h < H && w >= 0 && w < W) {
-        raw_load(raw[q], img + __umul24(__umul24(h, W) + w, C));
-        ok |= 1u << q;
-      }
+      const bool in = pl + q * d.PPB < npix && h >= 0 && h < H && w >= 0 && w < W;
+      off[q] = in ? __umul24(__umul24(h, W) + w, C) : 0u;
+      ok |= (in ? 1u : 0u) << q;
       ph += dph; pw += dpw;
       if (pw >= d.PW) { pw -= d.PW; ++ph; }
     }
+#pragma unroll
+    for (int q = 0; q < kDwFillNV; ++q) raw_load(raw[q], img + off[q]);
   }
   __device__ __forceinline__ void commit(T* patch, const View& vw, const DwPlan& d, int cg0) const {
     const int pl = dw_div(threadIdx.x, d.m_cgb), cg = threadIdx.x - pl * d.CGB;
@@ -424,18 +429,20 @@ template <typename T>
 __device__ __forceinline__ void dw_stage_weights(float* wl, const T* __restrict__ w, int C, int cg0, int CGB, unsigned m_cgb) {
   constexpr int NV = 5;
   const int n = 9 * CGB * 8;
-  float v[NV];
+  T v[NV];                 // as loaded: a conversion next to its load makes the compiler wait for that load alone
+  bool live[NV];
 #pragma unroll
   for (int q = 0; q < NV; ++q) {
     const int i = threadIdx.x + q * 256;
     const int e = i & 7, t = dw_div(i >> 3, m_cgb), c8 = (i >> 3) - t * CGB;      // i >> 3 < 160
     const int c = (cg0 + c8) * 8 + e;
-    v[q] = (i < n && c < C) ? to_f32(w[(size_t)c * 9 + t]) : 0.f;
+    live[q] = i < n && c < C;
+    v[q] = w[live[q] ? (size_t)c * 9 + t : 0];
   }
 #pragma unroll
   for (int q = 0; q < NV; ++q) {
     const int i = threadIdx.x + q * 256;
-    if (i < n) wl[i] = v[q];
+    if (i < n) wl[i] = live[q] ? to_f32(v[q]) : 0.f;
   }
 }
 
@@ -949,21 +956,26 @@ struct DwDzRuns {
     if (!worker) return;
     const int tw = tile % d.tiles_w, th = (tile / d.tiles_w) % d.tiles_h, n = tile / (d.tiles_w * d.tiles_h);
     const int ho0 = th * d.TH, wo0 = tw * d.TW;
+    // offsets first, then unconditional loads back to back (a pixel outside reads the image's first pixel and is
+    // not used): see DwPatch::fetch
+    const T* img = dz + (size_t)n * Hout * Wout * C + gc;
+    unsigned off[kDwSegs][4];
 #pragma unroll
     for (int k = 0; k < kDwSegs; ++k) {
       const int sg = seg0 + k * d.spp;
-      if (sg >= d.nseg) break;
-      const int hl = dw_div(sg, d.m_segw), wl0 = (sg - hl * d.segw) * 4;
+      const int hl = dw_div(sg < d.nseg ? sg : 0, d.m_segw), wl0 = ((sg < d.nseg ? sg : 0) - hl * d.segw) * 4;
       const int ho = ho0 + hl;
-      if (ho >= Hout) continue;
-      const T* dp = dz + (((size_t)n * Hout + ho) * Wout + wo0 + wl0) * C + gc;
 #pragma unroll
-      for (int o = 0; o < 4; ++o)
-        if (wo0 + wl0 + o < Wout) {
-          raw4_load(r[k][o], dp + (size_t)o * C);
-          ok |= 1u << (4 * k + o);
-        }
+      for (int o = 0; o < 4; ++o) {
+        const bool in = sg < d.nseg && ho < Hout && wo0 + wl0 + o < Wout;
+        off[k][o] = in ? __umul24(__umul24(ho, Wout) + wo0 + wl0 + o, C) : 0u;
+        ok |= (in ? 1u : 0u) << (4 * k + o);
+      }
     }
+#pragma unroll
+    for (int k = 0; k < kDwSegs; ++k)
+#pragma unroll
+      for (int o = 0; o < 4; ++o) raw4_load(r[k][o], img + off[k][o]);
   }
 };
 
@@ -1001,8 +1013,10 @@ __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View
       const int nt = tile + d.nblocks;
       if (nt < d.ntiles) {
         const int tw2 = nt % d.tiles_w, th2 = (nt / d.tiles_w) % d.tiles_h, n2 = nt / (d.tiles_w * d.tiles_h);
-        lp.fetch(src, n2, th2 * d.TH * S - 1, tw2 * d.TW * S - 1, d, Hin, Win, C, cg0);
+        // the dz runs first: a wait the compiler puts in front of them (their registers were read in the last
+        // round's taps) then finds nothing outstanding, instead of the six patch loads
         dq[par ^ 1].fetch(dz, nt, d, Hout, Wout, C, seg0, gc, worker);
+        lp.fetch(src, n2, th2 * d.TH * S - 1, tw2 * d.TW * S - 1, d, Hin, Win, C, cg0);
       }
       if (!worker) continue;
       const DwDzRuns<T>& cur = dq[par];
