@@ -456,7 +456,7 @@ __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ 
   T* patch = reinterpret_cast<T*>(smem_raw);
   float* wl = reinterpret_cast<float*>(smem_raw + (((size_t)d.PH * d.PW * d.CGB * 8 * sizeof(T) + 15) / 16 * 16));
   const int lb = xcd_logical_block();
-  const int tile = lb % d.ntiles, slab = lb / d.ntiles;
+  const int slab = lb % d.nslab, tile = lb / d.nslab;     // the slabs of a tile run together: they share cache lines when a slab is not 128 bytes
   const int tw = tile % d.tiles_w, th = (tile / d.tiles_w) % d.tiles_h, n = tile / (d.tiles_w * d.tiles_h);
   const int ho0 = th * d.TH, wo0 = tw * d.TW, cg0 = slab * d.CGB;
   DwPatch<T> lp;
@@ -857,7 +857,7 @@ __global__ __launch_bounds__(256) void dw_dgrad_s2_k(const T* __restrict__ dz, c
   T* patch = reinterpret_cast<T*>(smem_raw);
   float* wl = reinterpret_cast<float*>(smem_raw + (((size_t)d.PH * d.PW * d.CGB * 8 * sizeof(T) + 15) / 16 * 16));
   const int lb = xcd_logical_block();
-  const int tile = lb % d.ntiles, slab = lb / d.ntiles;
+  const int slab = lb % d.nslab, tile = lb / d.nslab;     // the slabs of a tile run together: they share cache lines when a slab is not 128 bytes
   const int tw = tile % d.tiles_w, th = (tile / d.tiles_w) % d.tiles_h, n = tile / (d.tiles_w * d.tiles_h);
   const int h0 = th * d.TH, w0 = tw * d.TW, cg0 = slab * d.CGB;       // tile origin, even
   __builtin_amdgcn_s_setprio(3);             // data-gradient chain: ahead of the weight-gradient stream's waves
@@ -985,7 +985,7 @@ __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   T* patch = reinterpret_cast<T*>(smem_raw);
   const int lb = xcd_logical_block();
-  const int b = lb % d.nblocks, slab = lb / d.nblocks, cg0 = slab * d.CGB;
+  const int slab = lb % d.nslab, b = lb / d.nslab, cg0 = slab * d.CGB;     // the slabs of a tile run together
   const int QB = 2 * d.CGB, seg0 = dw_div(threadIdx.x, d.m_qb), cq = threadIdx.x - seg0 * QB;
   const int c4 = cq * 4, gc = cg0 * 8 + c4;
   const bool worker = seg0 < d.spp && gc < C;
