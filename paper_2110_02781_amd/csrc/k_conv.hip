@@ -31,7 +31,7 @@ __global__ void reduce_partials_wide_k(const float* __restrict__ ws, int P, size
                                        size_t stride_c, int valid_c, float* __restrict__ g) {
   __shared__ double sm[16][17];
   const int jl = threadIdx.x & 15, lane = threadIdx.x >> 4;
-  const size_t j = (size_t)blockIdx.x * 16 + jl;
+  const size_t j = (size_t)xcd_logical_block() * 16 + jl;     // neighbours read the same lines of the partials: one L2
   double s = 0.0;
   if (j < QC) {
     int p = lane;
@@ -662,6 +662,7 @@ __global__ __launch_bounds__(512) void dw_bwd_small_k(const T* __restrict__ dz, 
   float4* tile = reinterpret_cast<float4*>(smem_raw);           // dz, [Mout]
   __shared__ float wl[9][4];
   __shared__ float red[8][44];    // [wave][value]
+  __builtin_amdgcn_s_setprio(3);             // data-gradient chain: ahead of the weight-gradient stream's waves
   __shared__ float coef[3][4];
   // adjacent channel groups share cache lines: keep them on one XCD
   const int C = g.Cout, c0 = xcd_logical_block() * 4, tid = threadIdx.x, nt = blockDim.x, s = g.stride;
@@ -1070,7 +1071,11 @@ static DwPlan dw_wgrad_plan(const ConvGeom& g, int es, size_t* lds) {
   d.PH = (d.TH - 1) * s + 3;
   d.PW = (d.segw * 4 - 1) * s + 3;
   d.ntiles = g.N * d.tiles_h * d.tiles_w;
-  const int cap = 512 / d.nslab > 1 ? 512 / d.nslab : 1;   // about 512 persistent blocks over all slabs
+  // About 384 persistent blocks over all slabs.  Measured: with 512 the stride-2 kernel no longer fits the GPU at once
+  // next to the BatchNorm backward of the other stream; blocks then wait for a place, and a 5 us finalize kernel of the
+  // data-gradient chain waited up to 200 us with them (a trace shows it ending when the first blocks end).  256 blocks
+  // leave the weight gradient itself too slow.
+  const int cap = 384 / d.nslab > 1 ? 384 / d.nslab : 1;
   d.nblocks = d.ntiles < cap ? d.ntiles : cap;
   size_t a = (size_t)d.PH * d.PW * d.CGB * 8 * es;          // the patch in the tensor's type
   size_t b = (size_t)d.spp * 9 * 2 * d.CGB * 16;

@@ -141,7 +141,7 @@ __global__ void bn_finalize_k(const float* __restrict__ partial, int P, size_t M
                               float* run_var, float eps, float momentum) {
   __shared__ double smem[2 * kFinLanes * kFinCh];
   int cl = threadIdx.x % kFinCh, lane = threadIdx.x / kFinCh;
-  int c = blockIdx.x * kFinCh + cl;
+  int c = xcd_logical_block() * kFinCh + cl;     // neighbours read the same lines of the partials: one L2
   double s[2];
   sum_partials<2>(partial, P, C, c, lane, s, smem);
   if (lane == 0 && c < C) {
@@ -246,8 +246,12 @@ __global__ void bn_bwd_finalize_k(const float* __restrict__ partial, int P, size
                                   const float* __restrict__ invstd, float* g_gamma, float* g_beta,
                                   float* coef) {
   __shared__ double smem[2 * kFinLanes * kFinCh];
+  // data-gradient chain.  Without this its few waves are the youngest on SIMDs that the weight-gradient stream's
+  // long-running waves keep busy, and issue goes to the oldest wave first: measured 190 us instead of 5 next to a
+  // persistent depthwise weight-gradient kernel
+  __builtin_amdgcn_s_setprio(3);
   int cl = threadIdx.x % kFinCh, lane = threadIdx.x / kFinCh;
-  int c = blockIdx.x * kFinCh + cl;
+  int c = xcd_logical_block() * kFinCh + cl;     // neighbours read the same lines of the partials: one L2
   double s[2];
   sum_partials<2>(partial, P, C, c, lane, s, smem);
   if (lane == 0 && c < C) {
@@ -336,6 +340,7 @@ __global__ __launch_bounds__(1024) void bn_bwd_small_k(const T* __restrict__ dA,
                                                        const float* __restrict__ gamma, const float* __restrict__ mean,
                                                        const float* __restrict__ invstd, float* g_gamma, float* g_beta,
                                                        T* __restrict__ dz) {
+  __builtin_amdgcn_s_setprio(3);     // data-gradient chain: ahead of the weight-gradient stream's waves on a shared SIMD
   __shared__ float red[16][8];    // [wave][value]
   __shared__ float coef[3][4];
   const int c0 = xcd_logical_block() * 4, tid = threadIdx.x, nt = blockDim.x;   // RPT * nt >= M; neighbours share an XCD

@@ -477,6 +477,7 @@ __global__ __launch_bounds__(256) void pw_gemm_k(GemmArgs p) {
   T* xs = reinterpret_cast<T*>(smem);
   T* ys = xs + TI * LD;
   float* ct = reinterpret_cast<float*>(smem);   // aliases the staging buffers between tiles
+  if (MODE == MODE_DGRAD) __builtin_amdgcn_s_setprio(3);   // data-gradient chain: ahead of the weight-gradient stream's waves
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int lb = xcd_logical_block();
@@ -919,6 +920,7 @@ __device__ __forceinline__ void pw_gemm_tiny_body(const GemmArgs& p, const int b
   constexpr int GROUPS = NW / 4;
   __shared__ float red[GROUPS][4][16][17];
   __shared__ float sred[GROUPS][2][16][17];
+  if (MODE == MODE_DGRAD) __builtin_amdgcn_s_setprio(3);   // data-gradient chain: ahead of the weight-gradient stream's waves
   const int grp = (threadIdx.x >> 8), wave = (threadIdx.x >> 6) & 3, lane = threadIdx.x & 63;
   const int tile = bid * GROUPS + grp;
   const bool tile_ok = tile < p.jtiles * p.itiles;
