@@ -256,6 +256,12 @@ struct ftp_stage {
   bool join_pending[2] = {false, false};
   unsigned n_sub_bwd = 0;
   float *bn_part = nullptr, *coef = nullptr, *ws = nullptr, *row_loss = nullptr;
+  // A second partial-sum workspace for the weight gradient of the stage's very first layer when the stage forks
+  // its weight gradients: that layer has no data gradient, so nothing follows it on the caller's stream and it
+  // runs there, next to whatever the side stream still has queued, instead of behind it.
+  float* ws_tail = nullptr;
+  size_t ws_tail_floats = 0;
+  int n_direct = 0;           // sublayers that use the patch-matrix buffer
   void* im2col = nullptr;     // patch matrix for the weight gradient of small dense convolutions
   size_t im2col_elems = 0;
   size_t ws_floats = 0;
@@ -286,7 +292,7 @@ static void stage_free(ftp_stage* s) {
     if (s->ev_fork[i]) (void)hipEventDestroy(s->ev_fork[i]);
     if (s->ev_join[i]) (void)hipEventDestroy(s->ev_join[i]);
   }
-  dfree(s->bn_part); dfree(s->coef); dfree(s->ws); dfree(s->row_loss); dfree(s->im2col);
+  dfree(s->bn_part); dfree(s->coef); dfree(s->ws); dfree(s->ws_tail); dfree(s->row_loss); dfree(s->im2col);
   if (s->timer) {
     if (s->timer->created)
       for (auto& q : s->timer->ev)
@@ -349,6 +355,8 @@ extern "C" int ftp_stage_create_ex(const ftp_model* m, int a, int b, int batch, 
       size_t M = (size_t)batch * g.Hout * g.Wout;
       size_t need = sb.type == SUB_DIRECT ? conv_direct_wgrad_ws(g) : sb.type == SUB_DW ? dw_wgrad_ws(g) : pw_wgrad_ws(M, g.Cin, g.Cout);
       if (need > ws_floats) ws_floats = need;
+      if (i == a && &sb == &u.subs[0]) s->ws_tail_floats = need;
+      if (sb.type == SUB_DIRECT) ++s->n_direct;
       if (sb.type == SUB_DIRECT && conv_direct_gemm_ok(g) && conv_direct_gemm_wpad_elems(g) > ws_floats)
         ws_floats = conv_direct_gemm_wpad_elems(g);      // padded weight copy of the GEMM forward (at most 4 bytes each)
       if (sb.type == SUB_DIRECT && conv_direct_im2col_elems(g) > s->im2col_elems) s->im2col_elems = conv_direct_im2col_elems(g);
@@ -407,6 +415,8 @@ extern "C" int ftp_stage_create_ex(const ftp_model* m, int a, int b, int batch, 
   if ((rc = dev_alloc(&s->bn_part, (size_t)kBnPartials * 2 * max_c * 4)) || (rc = dev_alloc(&s->coef, (size_t)3 * max_c * 4)) ||
       (rc = dev_alloc(&s->ws, ws_floats * 4)) || (rc = dev_alloc(&s->row_loss, (size_t)batch * 4))) { stage_free(s); return rc; }
   if (s->im2col_elems && (rc = dev_alloc(&s->im2col, s->im2col_elems * s->es))) { stage_free(s); return rc; }
+  if (s->max_act_bytes >= ((size_t)32 << 20) && s->ws_tail_floats && s->n_direct <= 1 &&
+      (rc = dev_alloc(&s->ws_tail, s->ws_tail_floats * 4))) { stage_free(s); return rc; }
 
   // initial state: zero weights / momentum / gradients, running mean 0, running variance 1
   std::vector<float> ones(nb, 1.0f);
@@ -854,7 +864,11 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
   // the memory-bound BatchNorm backward of the layer in front.
   const bool dgrad_first = overlap && sb.type == SUB_DW && dIn != nullptr;
   if (dgrad_first) dw_dgrad(s->dt, st, dz, conv_w(s, W, p.p_off + sb.w_off), g, dIn);
-  if (overlap) {
+  // the first layer of the stage, last in this pass and without a data gradient: its weight gradient is all that is
+  // left for this stream, so it runs here with a workspace of its own while the side stream works off its queue
+  const bool tail_here = overlap && dIn == nullptr && s->ws_tail != nullptr && &p == &s->plan[0] && k == 0;
+  float* wsp = tail_here ? s->ws_tail : s->ws;
+  if (overlap && !tail_here) {
     HIP_TRY(hipEventRecord(s->ev_fork[b], st));
     HIP_TRY(hipStreamWaitEvent(s->side, s->ev_fork[b], 0));
     ws = s->side;
@@ -868,10 +882,10 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
     pw_bwd(s->dt, st, dz, w, res, in, M, g.Cin, g.Cout, s->ws, gw, dIn);
     return FTP_OK;
   }
-  if (sb.type == SUB_DIRECT) conv_direct_wgrad(s->dt, ws, dz, in, g, s->im2col, s->ws, gw);
-  else if (sb.type == SUB_PW) pw_wgrad(s->dt, ws, dz, in, M, g.Cin, g.Cout, s->ws, gw);
-  else dw_wgrad(s->dt, ws, dz, in, g, s->ws, gw);
-  if (overlap) {
+  if (sb.type == SUB_DIRECT) conv_direct_wgrad(s->dt, ws, dz, in, g, s->im2col, wsp, gw);
+  else if (sb.type == SUB_PW) pw_wgrad(s->dt, ws, dz, in, M, g.Cin, g.Cout, wsp, gw);
+  else dw_wgrad(s->dt, ws, dz, in, g, wsp, gw);
+  if (overlap && !tail_here) {
     HIP_TRY(hipEventRecord(s->ev_join[b], s->side));
     s->join_pending[b] = true;
   }
