@@ -545,6 +545,18 @@ template <typename T> __device__ __forceinline__ float4 round4(float4 v) {
   return make_float4(round_to<T>(v.x), round_to<T>(v.y), round_to<T>(v.z), round_to<T>(v.w));
 }
 
+// four channels of one pixel as loaded, converted at the point of use (so the load can stay in flight)
+template <typename T> struct Raw4;
+template <> struct Raw4<float> { float4 v; };
+template <> struct Raw4<bf16_t> { uint2 v; };
+__device__ __forceinline__ void raw4_load(Raw4<float>& r, const float* p) { r.v = *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ void raw4_load(Raw4<bf16_t>& r, const bf16_t* p) { r.v = *reinterpret_cast<const uint2*>(p); }
+__device__ __forceinline__ float4 raw4_unpack(const Raw4<float>& r) { return r.v; }
+__device__ __forceinline__ float4 raw4_unpack(const Raw4<bf16_t>& r) {
+  return make_float4(__uint_as_float(r.v.x << 16), __uint_as_float(r.v.x & 0xffff0000u), __uint_as_float(r.v.y << 16),
+                     __uint_as_float(r.v.y & 0xffff0000u));
+}
+
 // Depthwise convolution + BatchNorm statistics + their finalisation (and, when the producer left them pending,
 // the finalisation of the input's BatchNorm too).
 template <typename T>
@@ -561,6 +573,18 @@ __global__ __launch_bounds__(1024) void dw_fwd_bn_small_k(View in, BnPending pen
   __shared__ float insc[2][4];
   // adjacent channel groups share cache lines: keep them on one XCD
   const int C = g.Cout, c0 = xcd_logical_block() * 4, tid = threadIdx.x, nt = blockDim.x, s = g.stride;
+  // Everything that depends on nothing is requested first: the input pixels of this block (at most three per thread,
+  // raw, from a clamped address), the BatchNorm parameters and running statistics.  They then travel while the pending
+  // BatchNorm of the input is finished; the kernel is a chain of memory round trips and little else.
+  const T* src = reinterpret_cast<const T*>(in.z);
+  Raw4<T> rv[3];
+#pragma unroll
+  for (int q = 0; q < 3; ++q) {
+    const size_t m = (size_t)tid + (size_t)q * nt;
+    raw4_load(rv[q], src + (m < Min ? m : 0) * C + c0);
+  }
+  float bn_g = 0.f, bn_b = 0.f, bn_rm = 0.f, bn_rv = 0.f;
+  if (tid < 4) { bn_g = gamma[c0 + tid]; bn_b = beta[c0 + tid]; bn_rm = run_mean[c0 + tid]; bn_rv = run_var[c0 + tid]; }
   if (tid < 36) wl[tid / 4][tid % 4] = to_f32(w[(size_t)(c0 + tid % 4) * 9 + tid / 4]);
   const bool view = in.scale != nullptr;
   if (pend.partial) finish_pending4(pend, C, c0, eps, momentum, pre, insc);
@@ -572,9 +596,11 @@ __global__ __launch_bounds__(1024) void dw_fwd_bn_small_k(View in, BnPending pen
     for (int e = 0; e < 4; ++e) { sc[e] = insc[0][e]; sh[e] = insc[1][e]; }
   }
   const float lo = view ? act_lo(in.act) : -INFINITY, hi = view ? act_hi(in.act) : INFINITY;
-  const T* src = reinterpret_cast<const T*>(in.z);
-  for (size_t m = tid; m < Min; m += nt) {
-    float4 v = load4(src + m * C + c0);
+#pragma unroll
+  for (int q = 0; q < 3; ++q) {
+    const size_t m = (size_t)tid + (size_t)q * nt;
+    if (m >= Min) break;
+    float4 v = raw4_unpack(rv[q]);
     if (view) v = round4<T>(view4(v, sc, sh, lo, hi));
     tile[m] = v;
   }
@@ -611,6 +637,8 @@ __global__ __launch_bounds__(1024) void dw_fwd_bn_small_k(View in, BnPending pen
     for (int e = 0; e < 8; ++e) red[wave][e] = acc[e];
   }
   __syncthreads();
+  // first use of the four values requested at the top: their conversions must not move up to the loads
+  asm volatile("" : "+v"(bn_g), "+v"(bn_b), "+v"(bn_rm), "+v"(bn_rv));
   if (tid < 4) {
     const int c = c0 + tid;
     double s0 = 0.0, s1 = 0.0;
@@ -619,14 +647,14 @@ __global__ __launch_bounds__(1024) void dw_fwd_bn_small_k(View in, BnPending pen
     double var = s1 / Md - mu * mu;
     if (var < 0.0) var = 0.0;
     const double is = 1.0 / sqrt(var + (double)eps);
-    const float scv = (float)((double)gamma[c] * is);
+    const float scv = (float)((double)bn_g * is);
     mean[c] = (float)mu;
     invstd[c] = (float)is;
     scale[c] = scv;
-    shift[c] = (float)((double)beta[c] - mu * (double)scv);
+    shift[c] = (float)((double)bn_b - mu * (double)scv);
     const double unb = M > 1 ? var * (Md / (Md - 1.0)) : var;
-    run_mean[c] = (float)((1.0 - momentum) * run_mean[c] + momentum * mu);
-    run_var[c] = (float)((1.0 - momentum) * run_var[c] + momentum * unb);
+    run_mean[c] = (float)((1.0 - momentum) * bn_rm + momentum * mu);
+    run_var[c] = (float)((1.0 - momentum) * bn_rv + momentum * unb);
   }
 }
 
@@ -933,18 +961,6 @@ void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvG
 // dW[c][ky][kx] += sum over output pixels dz[p][c] * in[p*S-1+(ky,kx)][c].  Blocks are persistent over
 // tiles; a thread reads the dz of its run straight from global memory (nobody else needs it), keeps
 // 9 x 4 sums over all its runs, and the block leaves one partial ws[block][9][C].
-// four channels of one pixel as loaded, converted at the point of use (so the load can stay in flight)
-template <typename T> struct Raw4;
-template <> struct Raw4<float> { float4 v; };
-template <> struct Raw4<bf16_t> { uint2 v; };
-__device__ __forceinline__ void raw4_load(Raw4<float>& r, const float* p) { r.v = *reinterpret_cast<const float4*>(p); }
-__device__ __forceinline__ void raw4_load(Raw4<bf16_t>& r, const bf16_t* p) { r.v = *reinterpret_cast<const uint2*>(p); }
-__device__ __forceinline__ float4 raw4_unpack(const Raw4<float>& r) { return r.v; }
-__device__ __forceinline__ float4 raw4_unpack(const Raw4<bf16_t>& r) {
-  return make_float4(__uint_as_float(r.v.x << 16), __uint_as_float(r.v.x & 0xffff0000u), __uint_as_float(r.v.y << 16),
-                     __uint_as_float(r.v.y & 0xffff0000u));
-}
-
 // The dz values of a thread's (at most kDwSegs) 4-pixel runs of one tile, requested a whole tile ahead like the
 // input patch: a persistent block has few neighbours on its CU to hide a load behind.
 template <typename T>

@@ -344,17 +344,15 @@ __global__ __launch_bounds__(1024) void bn_bwd_small_k(const T* __restrict__ dA,
   __shared__ float red[16][8];    // [wave][value]
   __shared__ float coef[3][4];
   const int c0 = xcd_logical_block() * 4, tid = threadIdx.x, nt = blockDim.x;   // RPT * nt >= M; neighbours share an XCD
+  // requested with the rows: what the four finishing threads need after the reduction
+  float f_mu = 0.f, f_is = 0.f, f_g = 0.f, f_gg = 0.f, f_gb = 0.f;
+  if (tid < 4) { f_mu = mean[c0 + tid]; f_is = invstd[c0 + tid]; f_g = gamma[c0 + tid]; f_gg = g_gamma[c0 + tid]; f_gb = g_beta[c0 + tid]; }
   float4 d[RPT], v[RPT];
 #pragma unroll
-  for (int q = 0; q < RPT; ++q) {
-    const size_t m = tid + (size_t)q * nt;
-    if (m < M) {
-      d[q] = load4(dA + m * C + c0);
-      v[q] = load4(z + m * C + c0);
-    } else {
-      d[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-      v[q] = d[q];
-    }
+  for (int q = 0; q < RPT; ++q) {       // unconditional, from a clamped row: rows past M are masked where they are used
+    const size_t m = tid + (size_t)q * nt, mc = m < M ? m : 0;
+    d[q] = load4(dA + mc * C + c0);
+    v[q] = load4(z + mc * C + c0);
   }
   float sc[4], sh[4];
 #pragma unroll
@@ -365,11 +363,12 @@ __global__ __launch_bounds__(1024) void bn_bwd_small_k(const T* __restrict__ dA,
   for (int q = 0; q < RPT; ++q) {
     const float y0 = fmaf(v[q].x, sc[0], sh[0]), y1 = fmaf(v[q].y, sc[1], sh[1]), y2 = fmaf(v[q].z, sc[2], sh[2]),
                 y3 = fmaf(v[q].w, sc[3], sh[3]);
-    float4 dy;                              // rows past M hold zeros
-    dy.x = (y0 > lo && y0 < hi) ? d[q].x : 0.f;
-    dy.y = (y1 > lo && y1 < hi) ? d[q].y : 0.f;
-    dy.z = (y2 > lo && y2 < hi) ? d[q].z : 0.f;
-    dy.w = (y3 > lo && y3 < hi) ? d[q].w : 0.f;
+    const bool live = tid + (size_t)q * nt < M;
+    float4 dy;                              // rows past M count as zeros
+    dy.x = (live && y0 > lo && y0 < hi) ? d[q].x : 0.f;
+    dy.y = (live && y1 > lo && y1 < hi) ? d[q].y : 0.f;
+    dy.z = (live && y2 > lo && y2 < hi) ? d[q].z : 0.f;
+    dy.w = (live && y3 > lo && y3 < hi) ? d[q].w : 0.f;
     d[q] = dy;
     acc[0] += dy.x; acc[1] += dy.y; acc[2] += dy.z; acc[3] += dy.w;
     acc[4] = fmaf(dy.x, v[q].x, acc[4]); acc[5] = fmaf(dy.y, v[q].y, acc[5]);
@@ -384,14 +383,16 @@ __global__ __launch_bounds__(1024) void bn_bwd_small_k(const T* __restrict__ dA,
     for (int e = 0; e < 8; ++e) red[wave][e] = acc[e];
   }
   __syncthreads();
+  // first use of the five values requested at the top: their conversions must not move up to the loads
+  asm volatile("" : "+v"(f_mu), "+v"(f_is), "+v"(f_g), "+v"(f_gg), "+v"(f_gb));
   if (tid < 4) {
     const int c = c0 + tid;
     double s0 = 0.0, s1 = 0.0;
     for (int w = 0; w < nw; ++w) { s0 += red[w][tid]; s1 += red[w][4 + tid]; }
-    const double mu = mean[c], is = invstd[c], g = gamma[c], Md = (double)M;
+    const double mu = f_mu, is = f_is, g = f_g, Md = (double)M;
     const double dbeta = s0, dgamma = is * (s1 - mu * s0);
-    g_gamma[c] += (float)dgamma;
-    g_beta[c] += (float)dbeta;
+    g_gamma[c] = f_gg + (float)dgamma;
+    g_beta[c] = f_gb + (float)dbeta;
     const double k1 = g * is, k2 = -k1 * is * dgamma / Md, k3 = -k1 * dbeta / Md - k2 * mu;
     coef[0][tid] = (float)k1; coef[1][tid] = (float)k2; coef[2][tid] = (float)k3;
   }
@@ -456,21 +457,30 @@ __global__ __launch_bounds__(1024) void bn_finalize_apply_small_k(BnPending pend
   __shared__ double pre[32][8];
   __shared__ float insc[2][4];
   const int c0 = xcd_logical_block() * 4, tid = threadIdx.x, nt = blockDim.x;
+  // the rows of this thread (at most two: M <= 2048 with 1024 threads, else one) and their residuals are requested
+  // before the statistics are finished, so the two round trips overlap
+  float4 zv[2], rv[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const size_t m = (size_t)tid + (size_t)q * nt, mc = m < M ? m : 0;
+    zv[q] = load4(z + mc * C + c0);
+    rv[q] = load4((res ? res : z) + mc * C + c0);      // unconditional: without a residual the row itself, not used
+  }
   finish_pending4(pend, C, c0, eps, momentum, pre, insc);
   float sc[4], sh[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) { sc[e] = insc[0][e]; sh[e] = insc[1][e]; }
   const float lo = act_lo(act), hi = act_hi(act);
-  for (size_t m = tid; m < M; m += nt) {
-    float4 v = load4(z + m * C + c0);
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const size_t m = (size_t)tid + (size_t)q * nt;
+    if (m >= M) break;
+    float4 v = zv[q];
     v.x = round_to<T>(clamp_act(fmaf(v.x, sc[0], sh[0]), lo, hi));
     v.y = round_to<T>(clamp_act(fmaf(v.y, sc[1], sh[1]), lo, hi));
     v.z = round_to<T>(clamp_act(fmaf(v.z, sc[2], sh[2]), lo, hi));
     v.w = round_to<T>(clamp_act(fmaf(v.w, sc[3], sh[3]), lo, hi));
-    if (res) {
-      const float4 r = load4(res + m * C + c0);
-      v.x += r.x; v.y += r.y; v.z += r.z; v.w += r.w;
-    }
+    if (res) { v.x += rv[q].x; v.y += rv[q].y; v.z += rv[q].z; v.w += rv[q].w; }
     store4(out + m * C + c0, v);
   }
 }
