@@ -694,12 +694,32 @@ __global__ __launch_bounds__(512) void dw_bwd_small_k(const T* __restrict__ dz, 
   __shared__ float coef[3][4];
   // adjacent channel groups share cache lines: keep them on one XCD
   const int C = g.Cout, c0 = xcd_logical_block() * 4, tid = threadIdx.x, nt = blockDim.x, s = g.stride;
+  const T* zin = reinterpret_cast<const T*>(in.z);
+  // Everything that depends on nothing is requested first, unconditionally and from clamped addresses: this thread's
+  // rows of the layer input, the old weight gradient, and what the finishing threads need after each reduction.
+  // The kernel is a chain of memory round trips; these then overlap with the first of them.
+  float4 zv[RPT];
+#pragma unroll
+  for (int q = 0; q < RPT; ++q) {
+    const size_t m = tid + (size_t)q * nt;
+    zv[q] = load4(zin + (m < M ? m : 0) * C + c0);
+  }
+  float gw_old = 0.f, f_mu = 0.f, f_is = 0.f, f_g = 0.f, f_gg = 0.f, f_gb = 0.f;
+  float f2_mu = 0.f, f2_is = 0.f, f2_g = 0.f, f2_gg = 0.f, f2_gb = 0.f;
+  if (tid < 36) gw_old = g_w[(size_t)(c0 + tid % 4) * 9 + tid / 4];
+  if (tid >= 64 && tid < 68) {
+    const int c = c0 + tid - 64;
+    f_mu = mean[c]; f_is = invstd[c]; f_g = gamma[c]; f_gg = g_gamma[c]; f_gb = g_beta[c];
+  }
+  if (bo.dA && tid < 4) {
+    const int c = c0 + tid;
+    f2_mu = bo.mean[c]; f2_is = bo.invstd[c]; f2_g = bo.gamma[c]; f2_gg = bo.g_gamma[c]; f2_gb = bo.g_beta[c];
+  }
   if (tid < 36) wl[tid / 4][tid % 4] = to_f32(w[(size_t)(c0 + tid % 4) * 9 + tid / 4]);
   float sc[4], sh[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) { sc[e] = in.scale[c0 + e]; sh[e] = in.shift[c0 + e]; }
   const float lo = act_lo(in.act), hi = act_hi(in.act);
-  const T* zin = reinterpret_cast<const T*>(in.z);
   if (bo.dA) {
     // dz is not formed yet: this layer's own BatchNorm backward first (same channels, all pixels: block-local),
     // its result goes straight into the LDS tile and never to memory
@@ -713,14 +733,20 @@ __global__ __launch_bounds__(512) void dw_bwd_small_k(const T* __restrict__ dz, 
     const float lo2 = act_lo(bo.out.act), hi2 = act_hi(bo.out.act);
     float4 dy2[RPT], z2v[RPT];
     float b2[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    float4 d2r[RPT];
+#pragma unroll
+    for (int q = 0; q < RPT; ++q) {
+      const size_t m = tid + (size_t)q * nt, mc = m < Mout ? m : 0;
+      d2r[q] = load4(dA2 + mc * C + c0);
+      z2v[q] = load4(z2 + mc * C + c0);
+    }
 #pragma unroll
     for (int q = 0; q < RPT; ++q) {
       const size_t m = tid + (size_t)q * nt;
       dy2[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-      z2v[q] = dy2[q];
-      if (m >= Mout) continue;
-      const float4 d = load4(dA2 + m * C + c0);
-      const float4 zz = load4(z2 + m * C + c0);
+      if (m >= Mout) { z2v[q] = dy2[q]; continue; }
+      const float4 d = d2r[q];
+      const float4 zz = z2v[q];
       const float y0 = fmaf(zz.x, sc2[0], sh2[0]), y1 = fmaf(zz.y, sc2[1], sh2[1]), y2 = fmaf(zz.z, sc2[2], sh2[2]),
                   y3 = fmaf(zz.w, sc2[3], sh2[3]);
       float4 v;
@@ -728,7 +754,7 @@ __global__ __launch_bounds__(512) void dw_bwd_small_k(const T* __restrict__ dz, 
       v.y = (y1 > lo2 && y1 < hi2) ? d.y : 0.f;
       v.z = (y2 > lo2 && y2 < hi2) ? d.z : 0.f;
       v.w = (y3 > lo2 && y3 < hi2) ? d.w : 0.f;
-      dy2[q] = v; z2v[q] = zz;
+      dy2[q] = v;
       b2[0] += v.x; b2[1] += v.y; b2[2] += v.z; b2[3] += v.w;
       b2[4] = fmaf(v.x, zz.x, b2[4]); b2[5] = fmaf(v.y, zz.y, b2[5]); b2[6] = fmaf(v.z, zz.z, b2[6]); b2[7] = fmaf(v.w, zz.w, b2[7]);
     }
@@ -738,14 +764,16 @@ __global__ __launch_bounds__(512) void dw_bwd_small_k(const T* __restrict__ dz, 
       if ((tid & 63) == 0) red2[tid >> 6][e] = r;
     }
     __syncthreads();
+    // first use of the values requested at the top: their conversions must not move up to the loads
+    asm volatile("" : "+v"(f2_mu), "+v"(f2_is), "+v"(f2_g), "+v"(f2_gg), "+v"(f2_gb));
     if (tid < 4) {
       const int c = c0 + tid;
       double s0 = 0.0, s1 = 0.0;
       for (int q = 0; q < (nt >> 6); ++q) { s0 += red2[q][tid]; s1 += red2[q][4 + tid]; }
-      const double mu = bo.mean[c], is = bo.invstd[c], gm = bo.gamma[c], Md = (double)Mout;
+      const double mu = f2_mu, is = f2_is, gm = f2_g, Md = (double)Mout;
       const double dbeta = s0, dgamma = is * (s1 - mu * s0);
-      bo.g_gamma[c] += (float)dgamma;
-      bo.g_beta[c] += (float)dbeta;
+      bo.g_gamma[c] = f2_gg + (float)dgamma;
+      bo.g_beta[c] = f2_gb + (float)dbeta;
       const double k1 = gm * is, k2 = -k1 * is * dgamma / Md, k3 = -k1 * dbeta / Md - k2 * mu;
       coef2[0][tid] = (float)k1; coef2[1][tid] = (float)k2; coef2[2][tid] = (float)k3;
     }
@@ -762,7 +790,7 @@ __global__ __launch_bounds__(512) void dw_bwd_small_k(const T* __restrict__ dz, 
     for (size_t m = tid; m < Mout; m += nt) tile[m] = load4(dz + m * C + c0);
   }
   __syncthreads();
-  float4 wr[9], accw[9], dy[RPT], zv[RPT];
+  float4 wr[9], accw[9], dy[RPT];
 #pragma unroll
   for (int t = 0; t < 9; ++t) {
     wr[t] = make_float4(wl[t][0], wl[t][1], wl[t][2], wl[t][3]);
@@ -773,10 +801,8 @@ __global__ __launch_bounds__(512) void dw_bwd_small_k(const T* __restrict__ dz, 
   for (int q = 0; q < RPT; ++q) {
     const size_t m = tid + (size_t)q * nt;
     dy[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-    zv[q] = dy[q];
-    if (m >= M) continue;
+    if (m >= M) { zv[q] = dy[q]; continue; }
     const int ww = (int)(m % g.Win), h = (int)((m / g.Win) % g.Hin), n = (int)(m / ((size_t)g.Win * g.Hin));
-    zv[q] = load4(zin + m * C + c0);
     const float4 y = make_float4(fmaf(zv[q].x, sc[0], sh[0]), fmaf(zv[q].y, sc[1], sh[1]), fmaf(zv[q].z, sc[2], sh[2]),
                                  fmaf(zv[q].w, sc[3], sh[3]));
     const float4 a = round4<T>(make_float4(clamp_act(y.x, lo, hi), clamp_act(y.y, lo, hi), clamp_act(y.z, lo, hi),
@@ -824,18 +850,19 @@ __global__ __launch_bounds__(512) void dw_bwd_small_k(const T* __restrict__ dz, 
     if (lead) red[wave][36 + e] = r;
   }
   __syncthreads();
+  asm volatile("" : "+v"(gw_old), "+v"(f_mu), "+v"(f_is), "+v"(f_g), "+v"(f_gg), "+v"(f_gb));
   if (tid < 36) {
     float tot = 0.f;
     for (int q = 0; q < nw; ++q) tot += red[q][tid];
-    g_w[(size_t)(c0 + tid % 4) * 9 + tid / 4] += tot;
+    g_w[(size_t)(c0 + tid % 4) * 9 + tid / 4] = gw_old + tot;
   } else if (tid >= 64 && tid < 68) {
     const int e = tid - 64, c = c0 + e;
     double s0 = 0.0, s1 = 0.0;
     for (int q = 0; q < nw; ++q) { s0 += red[q][36 + e]; s1 += red[q][40 + e]; }
-    const double mu = mean[c], is = invstd[c], gm = gamma[c], Md = (double)M;
+    const double mu = f_mu, is = f_is, gm = f_g, Md = (double)M;
     const double dbeta = s0, dgamma = is * (s1 - mu * s0);
-    g_gamma[c] += (float)dgamma;
-    g_beta[c] += (float)dbeta;
+    g_gamma[c] = f_gg + (float)dgamma;
+    g_beta[c] = f_gb + (float)dbeta;
     const double k1 = gm * is, k2 = -k1 * is * dgamma / Md, k3 = -k1 * dbeta / Md - k2 * mu;
     coef[0][e] = (float)k1; coef[1][e] = (float)k2; coef[2][e] = (float)k3;
   }
