@@ -939,6 +939,15 @@ __device__ __forceinline__ void pw_gemm_tiny_body(const GemmArgs& p, const int b
   const T* W = reinterpret_cast<const T*>(p.y);
   const bool view = MODE == MODE_FWD && p.view.scale != nullptr;
   const float lo = act_lo(p.view.act), hi = act_hi(p.view.act);
+  // the output element this thread writes after the reduction; what is added to it there (residual, bias) is
+  // requested now: a load at the end of the kernel would be one more round trip on the launch-latency path
+  const int orow = (threadIdx.x >> 4) & 15, ocol = threadIdx.x & 15;
+  const size_t ig = i0 + orow;
+  const int jg = j0 + ocol;
+  const bool in = tile_ok && ig < p.M && jg < nj;
+  float addend = 0.f;
+  if (MODE == MODE_FWD) { if (p.bias && tile_ok && jg < nj) addend = p.bias[jg]; }
+  else if (p.res && in) addend = to_f32(reinterpret_cast<const T*>(p.res)[ig * p.K + jg]);
 
   f4v acc = {0.f, 0.f, 0.f, 0.f};
   for (int s = sb; s < se; s += U) {
@@ -998,14 +1007,11 @@ __device__ __forceinline__ void pw_gemm_tiny_body(const GemmArgs& p, const int b
 #pragma unroll
   for (int r = 0; r < 4; ++r) red[grp][wave][4 * (lane >> 4) + r][l16] = acc[r];
   __syncthreads();
-  const int orow = (threadIdx.x >> 4) & 15, ocol = threadIdx.x & 15;
-  const size_t ig = i0 + orow;
-  const int jg = j0 + ocol;
-  const bool in = tile_ok && ig < p.M && jg < nj;
+  asm volatile("" : "+v"(addend));          // first use: its conversion stays here
   const float v0 = red[grp][0][orow][ocol] + red[grp][1][orow][ocol] + red[grp][2][orow][ocol] + red[grp][3][orow][ocol];
   float v = v0;
   if (MODE == MODE_FWD) {
-    if (p.bias && jg < nj) v += p.bias[jg];
+    v += addend;
     if (in) reinterpret_cast<T*>(p.out)[ig * p.N + jg] = from_f32<T>(v);
     if (p.stats) {
       const float sv = in ? round_to<T>(v) : 0.f;     // statistics of the values as stored
@@ -1021,10 +1027,7 @@ __device__ __forceinline__ void pw_gemm_tiny_body(const GemmArgs& p, const int b
       }
     }
   } else {
-    if (in) {
-      if (p.res) v += to_f32(reinterpret_cast<const T*>(p.res)[ig * p.K + jg]);
-      reinterpret_cast<T*>(p.out)[ig * p.K + jg] = from_f32<T>(v);
-    }
+    if (in) reinterpret_cast<T*>(p.out)[ig * p.K + jg] = from_f32<T>(v + addend);
   }
 }
 
@@ -1048,6 +1051,12 @@ __device__ __forceinline__ void pw_wgrad_tiny_body(const GemmArgs& p, const int 
   const float sc = view && k_ok ? p.view.scale[k] : 1.f, sh = view && k_ok ? p.view.shift[k] : 0.f;
   const float lo = act_lo(p.view.act), hi = act_hi(p.view.act);
   const size_t M = p.M;
+  // the gradient element this thread adds to after the reduction, requested now (see pw_gemm_tiny_body)
+  const int orow = (threadIdx.x >> 4) & 15, ocol = threadIdx.x & 15;
+  const int on = it * 16 + orow, ok_ = jt * 16 + ocol;
+  const bool writer = threadIdx.x < 256 && on < p.N && ok_ < K_out;
+  float* dst = reinterpret_cast<float*>(p.out) + (writer ? (size_t)on * K_out + ok_ : 0);
+  float g_old = writer ? *dst : 0.f;
   const size_t per = ((M + 4 * NW - 1) / (4 * NW)) * 4;    // pixels per wavefront, a multiple of 4
   const size_t mb = (size_t)wave * per, me = mb + per < M ? mb + per : M;
   f4v acc = {0.f, 0.f, 0.f, 0.f};
@@ -1081,14 +1090,12 @@ __device__ __forceinline__ void pw_wgrad_tiny_body(const GemmArgs& p, const int 
 #pragma unroll
   for (int r = 0; r < 4; ++r) red[wave][4 * mg + r][l16] = acc[r];
   __syncthreads();
-  const int orow = (threadIdx.x >> 4) & 15, ocol = threadIdx.x & 15;
-  const int on = it * 16 + orow, ok_ = jt * 16 + ocol;
-  if (threadIdx.x < 256 && on < p.N && ok_ < K_out) {
+  asm volatile("" : "+v"(g_old));
+  if (writer) {
     float v = 0.f;
 #pragma unroll
     for (int q = 0; q < NW; ++q) v += red[q][orow][ocol];
-    float* dst = reinterpret_cast<float*>(p.out) + (size_t)on * K_out + ok_;
-    *dst += v;
+    *dst = g_old + v;
   }
 }
 
