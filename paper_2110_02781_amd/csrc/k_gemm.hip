@@ -25,6 +25,7 @@
 // layer share one launch and the weight gradient needs no partial buffers.
 // bfloat16 uses v_mfma_f32_32x32x16_bf16 (16x16x32 in the short kernels), float uses
 // v_mfma_f32_32x32x2_f32 (16x16x4).
+#include <type_traits>
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -687,9 +688,18 @@ __device__ __forceinline__ void load_pair(const bf16_t* p, float& a, float& b) {
 // their barriers.
 // RES: data gradient with a residual to add (a variant of its own: the sixteen prefetched residual pairs cost
 // registers that the plain data gradient should not pay for)
-template <typename T, int MODE, bool VEC, int CH, bool RES = false>
+// DEEP: data gradient whose reduction spans at least two steps.  The loads of TWO steps are kept in flight (two
+// register sets and the two LDS buffers, addressed statically: the chunk loop is unrolled by two, and a tile with an
+// odd number of chunks hands over to a copy of the tile code that starts on the other set).  On this architecture
+// loads and stores share one counter and complete out of order with respect to each other, so a wait for "all but
+// the youngest n loads" exists only while no store is pending and only if n is the same on every path: the chunk
+// loop of a tile has no stores, it is entered after an explicit wait for everything, every step requests its
+// successor's successor unconditionally (past the end: a valid tile again, never used), and the tile's stores follow.
+template <typename T, int MODE, bool VEC, int CH, bool RES = false, bool DEEP = false>
 __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
   constexpr int TI = 128;
+  constexpr int PD = DEEP ? 2 : 1;
+  static_assert(!DEEP || MODE == MODE_DGRAD, "two steps in flight: data gradient only");
   constexpr int LD = CH + Pad<T>::V;
   constexpr int BUF = (TI + BJ) * LD;
   __shared__ __attribute__((aligned(16))) T smem[2 * BUF];
@@ -717,8 +727,6 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
     it_end = it_beg + p.tiles_per_range < p.itiles ? it_beg + p.tiles_per_range : p.itiles;
   }
   const int nchunks = (int)((rend - rbeg + CH - 1) / CH);
-  const int nsteps = (it_end - it_beg) * nchunks;
-  const bool y_static = nchunks == 1;      // the weight tile never changes: stage it once per buffer
 
   const size_t ldx = MODE == MODE_FWD ? p.K : p.N;
   const size_t ldy = p.K;
@@ -726,11 +734,11 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
   const size_t nj = MODE == MODE_FWD ? (size_t)p.N : (size_t)p.K;
   const size_t ldo = nj;                   // leading dimension of the output
 
-  typename LoaderSel<T, TI, CH, MODE != MODE_WGRAD, MODE == MODE_FWD, false, VEC>::type lx;
-  typename LoaderSel<T, BJ, CH, MODE == MODE_FWD, MODE == MODE_WGRAD, true, VEC>::type ly;
+  typename LoaderSel<T, TI, CH, MODE != MODE_WGRAD, MODE == MODE_FWD, false, VEC>::type lx[PD];
+  typename LoaderSel<T, BJ, CH, MODE == MODE_FWD, MODE == MODE_WGRAD, true, VEC>::type ly[PD];
   // weight gradient: the view vectors of this block's columns stay in registers (the same columns at every step);
   // forward: they are requested together with the tile they belong to (fetch_view)
-  if constexpr (MODE == MODE_WGRAD && VEC) ly.hold_view(p.view, j0, nj);
+  if constexpr (MODE == MODE_WGRAD && VEC) ly[0].hold_view(p.view, j0, nj);
 
   f16v acc[2];
 #pragma unroll
@@ -753,36 +761,9 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
   asm volatile("" ::"v"(b0), "v"(b1));
 
   const bool pview = MODE == MODE_FWD && VEC && p.view.scale != nullptr;   // view vectors travel with the tile
-  if (nsteps > 0) {
-    lx.fetch(X, ldx, (size_t)it_beg * TI, ni, rbeg, rend);
-    if constexpr (MODE == MODE_FWD && VEC) { if (pview) lx.fetch_view(p.view, rbeg, rend); }
-    ly.fetch(Y, ldy, j0, nj, rbeg, rend);
-  }
-  for (int s = 0; s < nsteps; ++s) {
-    const int it = it_beg + s / nchunks, kc = s % nchunks;
-    const size_t i0 = (size_t)it * TI, r0 = rbeg + (size_t)kc * CH;
-    T* xs = smem + (s & 1) * BUF;
-    T* ys = xs + TI * LD;
-    if constexpr (MODE == MODE_FWD && VEC) {
-      if (pview) lx.commit_pv(xs, p.view.act);
-      else lx.commit(xs, X, ldx, i0, ni, r0, rend, p.view);
-    } else {
-      lx.commit(xs, X, ldx, i0, ni, r0, rend, p.view);
-    }
-    if (!y_static || s < 2) ly.commit(ys, Y, ldy, j0, nj, r0, rend, p.view);
-    __syncthreads();
-    if (s + 1 < nsteps) {
-      const int it2 = it_beg + (s + 1) / nchunks, kc2 = (s + 1) % nchunks;
-      // the weight tile first: its registers may still be the target of a load the compiler has not seen consumed
-      // (its commit is conditional), and the wait for that must not come behind this step's other requests
-      if (!y_static || s + 1 < 2) ly.fetch(Y, ldy, j0, nj, rbeg + (size_t)kc2 * CH, rend);
-      lx.fetch(X, ldx, (size_t)it2 * TI, ni, rbeg + (size_t)kc2 * CH, rend);
-      if constexpr (MODE == MODE_FWD && VEC) { if (pview) lx.fetch_view(p.view, rbeg + (size_t)kc2 * CH, rend); }
-    }
-#pragma unroll
-    for (int c0 = 0; c0 < CH; c0 += 32) mma32(xs, ys, LD, wave * 32 + jl, lane, c0, acc);
-    if (kc + 1 < nchunks) continue;
 
+  // the finished tile with first row i0; the sums are cleared for the next tile
+  auto epilogue = [&](const size_t i0) __attribute__((always_inline)) {
     // tile finished: register r of this lane is row 8*(r/4) + 4*h + r%4, columns jc (acc[0]) and jc+1 (acc[1])
     const size_t irow = i0 + wave * 32 + 4 * h;
     if (VEC && i0 + TI <= ni) {
@@ -817,7 +798,7 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) { acc[0][r] = 0.f; acc[1][r] = 0.f; }
-      continue;
+      return;
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -848,6 +829,86 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
         if (pair_ok) store_pair(dst, v0, v1);
         else { dst[0] = v0; if (jc + 1 < nj) dst[1] = v1; }
       }
+    }
+  };
+
+  if constexpr (!DEEP) {
+    const int nsteps = (it_end - it_beg) * nchunks;
+    const bool y_static = nchunks == 1;      // the weight tile never changes: stage it once per buffer
+    if (nsteps > 0) {
+      lx[0].fetch(X, ldx, (size_t)it_beg * TI, ni, rbeg, rend);
+      if constexpr (MODE == MODE_FWD && VEC) { if (pview) lx[0].fetch_view(p.view, rbeg, rend); }
+      ly[0].fetch(Y, ldy, j0, nj, rbeg, rend);
+    }
+    for (int s = 0; s < nsteps; ++s) {
+      const int it = it_beg + s / nchunks, kc = s % nchunks;
+      const size_t i0 = (size_t)it * TI, r0 = rbeg + (size_t)kc * CH;
+      T* xs = smem + (s & 1) * BUF;
+      T* ys = xs + TI * LD;
+      if constexpr (MODE == MODE_FWD && VEC) {
+        if (pview) lx[0].commit_pv(xs, p.view.act);
+        else lx[0].commit(xs, X, ldx, i0, ni, r0, rend, p.view);
+      } else {
+        lx[0].commit(xs, X, ldx, i0, ni, r0, rend, p.view);
+      }
+      if (!y_static || s < 2) ly[0].commit(ys, Y, ldy, j0, nj, r0, rend, p.view);
+      __syncthreads();
+      if (s + 1 < nsteps) {
+        const int it2 = it_beg + (s + 1) / nchunks, kc2 = (s + 1) % nchunks;
+        // the weight tile first: its registers may still be the target of a load the compiler has not seen consumed
+        // (its commit is conditional), and the wait for that must not come behind this step's other requests
+        if (!y_static || s + 1 < 2) ly[0].fetch(Y, ldy, j0, nj, rbeg + (size_t)kc2 * CH, rend);
+        lx[0].fetch(X, ldx, (size_t)it2 * TI, ni, rbeg + (size_t)kc2 * CH, rend);
+        if constexpr (MODE == MODE_FWD && VEC) { if (pview) lx[0].fetch_view(p.view, rbeg + (size_t)kc2 * CH, rend); }
+      }
+  #pragma unroll
+      for (int c0 = 0; c0 < CH; c0 += 32) mma32(xs, ys, LD, wave * 32 + jl, lane, c0, acc);
+      if (kc + 1 == nchunks) epilogue(i0);
+    }
+  } else {
+    const int ntile = it_end - it_beg;
+    auto fetch_step = [&](auto& fx, auto& fy, const int t2, const int kc2) __attribute__((always_inline)) {
+      const size_t r2 = rbeg + (size_t)kc2 * CH;
+      fy.fetch(Y, ldy, j0, nj, r2, rend);
+      fx.fetch(X, ldx, (size_t)(it_beg + (t2 < ntile ? t2 : ntile - 1)) * TI, ni, r2, rend);
+    };
+    // chunk kc of tile t from register set / LDS buffer SET, then the request for the step two ahead into the same set
+    auto step = [&](auto SET, const int t, const int kc) __attribute__((always_inline)) {
+      constexpr int set = decltype(SET)::value;
+      const size_t i0 = (size_t)(it_beg + t) * TI, r0 = rbeg + (size_t)kc * CH;
+      T* xs = smem + set * BUF;
+      T* ys = xs + TI * LD;
+      lx[set].commit(xs, X, ldx, i0, ni, r0, rend, p.view);
+      ly[set].commit(ys, Y, ldy, j0, nj, r0, rend, p.view);
+      __syncthreads();
+      int kc2 = kc + 2, t2 = t;
+      if (kc2 >= nchunks) { kc2 -= nchunks; ++t2; }
+      fetch_step(lx[set], ly[set], t2, kc2);
+#pragma unroll
+      for (int c0 = 0; c0 < CH; c0 += 32) mma32(xs, ys, LD, wave * 32 + jl, lane, c0, acc);
+    };
+    // one tile whose chunk 0 sits in set P0
+    auto tile_body = [&](auto P0, const int t) __attribute__((always_inline)) {
+      constexpr int p0 = decltype(P0)::value;
+      // vmcnt(0): the last tile's stores and the two steps requested so far are complete; from here to the end of
+      // the chunk loop only loads are pending
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      int kc = 0;
+      for (; kc + 1 < nchunks; kc += 2) {
+        step(std::integral_constant<int, p0>(), t, kc);
+        step(std::integral_constant<int, p0 ^ 1>(), t, kc + 1);
+      }
+      if (kc < nchunks) step(std::integral_constant<int, p0>(), t, kc);
+      epilogue((size_t)(it_beg + t) * TI);
+    };
+    if (ntile > 0) {           // nchunks >= 2 (the host launches this variant only then)
+      fetch_step(lx[0], ly[0], 0, 0);
+      fetch_step(lx[PD - 1], ly[PD - 1], 0, 1);
+    }
+    const bool odd = nchunks & 1;
+    for (int t = 0; t < ntile;) {
+      tile_body(std::integral_constant<int, 0>(), t++);
+      if (odd && t < ntile) tile_body(std::integral_constant<int, 1>(), t++);
     }
   }
 
@@ -1142,6 +1203,11 @@ static void launch_t(hipStream_t st, const GemmArgs& a, bool small, unsigned gri
   // gradient lose a little (fewer blocks fit a CU)
   if (MODE == MODE_WGRAD && sizeof(T) == 2 && red >= (size_t)kDeepReduction)
     hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, sizeof(T) == 2 ? 64 : 32>), dim3(grid), dim3(256), 0, st, a);
+  else if (MODE == MODE_DGRAD && red > 32) {     // at least two steps per tile: two steps' loads in flight
+    constexpr bool D = MODE == MODE_DGRAD;
+    if (a.res) hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, 32, D, D>), dim3(grid), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, 32, false, D>), dim3(grid), dim3(256), 0, st, a);
+  }
   else if (MODE == MODE_DGRAD && a.res) hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, 32, MODE == MODE_DGRAD>), dim3(grid), dim3(256), 0, st, a);
   else hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, 32>), dim3(grid), dim3(256), 0, st, a);
 }
