@@ -699,7 +699,7 @@ template <typename T, int MODE, bool VEC, int CH, bool RES = false, bool DEEP = 
 __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
   constexpr int TI = 128;
   constexpr int PD = DEEP ? 2 : 1;
-  static_assert(!DEEP || MODE == MODE_DGRAD, "two steps in flight: data gradient only");
+  static_assert(!DEEP || MODE != MODE_FWD, "two steps in flight: data gradient and weight gradient");
   constexpr int LD = CH + Pad<T>::V;
   constexpr int BUF = (TI + BJ) * LD;
   __shared__ __attribute__((aligned(16))) T smem[2 * BUF];
@@ -738,7 +738,10 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
   typename LoaderSel<T, BJ, CH, MODE == MODE_FWD, MODE == MODE_WGRAD, true, VEC>::type ly[PD];
   // weight gradient: the view vectors of this block's columns stay in registers (the same columns at every step);
   // forward: they are requested together with the tile they belong to (fetch_view)
-  if constexpr (MODE == MODE_WGRAD && VEC) ly[0].hold_view(p.view, j0, nj);
+  if constexpr (MODE == MODE_WGRAD && VEC) {
+#pragma unroll
+    for (int d = 0; d < PD; ++d) ly[d].hold_view(p.view, j0, nj);
+  }
 
   f16v acc[2];
 #pragma unroll
@@ -1202,7 +1205,9 @@ static void launch_t(hipStream_t st, const GemmArgs& a, bool small, unsigned gri
   // measured: the weight gradient (both operands transposed on the way into LDS) gains 10-30 %, forward and data
   // gradient lose a little (fewer blocks fit a CU)
   if (MODE == MODE_WGRAD && sizeof(T) == 2 && red >= (size_t)kDeepReduction)
-    hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, sizeof(T) == 2 ? 64 : 32>), dim3(grid), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, sizeof(T) == 2 ? 64 : 32, false, MODE == MODE_WGRAD>), dim3(grid), dim3(256), 0, st, a);
+  else if (MODE == MODE_WGRAD && red > 32)
+    hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, 32, false, MODE == MODE_WGRAD>), dim3(grid), dim3(256), 0, st, a);
   else if (MODE == MODE_DGRAD && red > 32) {     // at least two steps per tile: two steps' loads in flight
     constexpr bool D = MODE == MODE_DGRAD;
     if (a.res) hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, 32, D, D>), dim3(grid), dim3(256), 0, st, a);
