@@ -871,9 +871,12 @@ __global__ __launch_bounds__(256) void pw_gemm_rows_k(GemmArgs p) {
   } else {
     const int ntile = it_end - it_beg;
     auto fetch_step = [&](auto& fx, auto& fy, const int t2, const int kc2) __attribute__((always_inline)) {
-      const size_t r2 = rbeg + (size_t)kc2 * CH;
+      // past the last tile the request is only there to keep the count of loads in flight the same on every path: it
+      // repeats one of the last tile's last two chunks, which the caches still hold
+      const bool past = t2 >= ntile;
+      const size_t r2 = rbeg + (size_t)(past ? nchunks - 2 + kc2 : kc2) * CH;
       fy.fetch(Y, ldy, j0, nj, r2, rend);
-      fx.fetch(X, ldx, (size_t)(it_beg + (t2 < ntile ? t2 : ntile - 1)) * TI, ni, r2, rend);
+      fx.fetch(X, ldx, (size_t)(it_beg + (past ? ntile - 1 : t2)) * TI, ni, r2, rend);
     };
     // chunk kc of tile t from register set / LDS buffer SET, then the request for the step two ahead into the same set
     auto step = [&](auto SET, const int t, const int kc) __attribute__((always_inline)) {
