@@ -448,7 +448,9 @@ __device__ __forceinline__ void dw_stage_weights(float* wl, const T* __restrict_
 
 // out[ho][wo] = sum_{ky,kx} src[ho*S-1+ky][wo*S-1+kx] * w[ky][kx]   (FLIP: w[2-ky][2-kx], which for
 // S = 1 is the data gradient with src = dz)
-template <typename T, int S, bool FLIP>
+// RL = pixels per run: four at stride 1; two at stride 2, where a run of four keeps 9 patch vectors and 4 sums live
+// (111 registers, four resident blocks per CU) and a 4 x 8 tile has work for only 96 of the 256 threads
+template <typename T, int S, bool FLIP, int RL = (S == 2 ? 2 : 4)>
 __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ w, DwPlan d, int Hin, int Win, int Hout,
                                                  int Wout, int C, T* __restrict__ out) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
@@ -472,26 +474,26 @@ __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ 
   for (int t = 0; t < 9; ++t) wr[t] = ld4(wl + (size_t)(FLIP ? 8 - t : t) * d.CGB * 8 + c4);
   const int vs = d.CGB * 8;                       // floats per patch pixel
   for (int sg = seg0; sg < d.nseg; sg += d.spp) {
-    const int hl = dw_div(sg, d.m_segw), wl0 = (sg - hl * d.segw) * 4;
+    const int hl = dw_div(sg, d.m_segw), wl0 = (sg - hl * d.segw) * RL;
     const int ho = ho0 + hl;
     if (ho >= Hout) continue;
-    float4 acc[4];
+    float4 acc[RL];
 #pragma unroll
-    for (int o = 0; o < 4; ++o) acc[o] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int o = 0; o < RL; ++o) acc[o] = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
     for (int ky = 0; ky < 3; ++ky) {
       const T* row = patch + (size_t)((hl * S + ky) * d.PW + wl0 * S) * vs + c4;
-      float4 iv[3 * S + 3];
+      float4 iv[(RL - 1) * S + 3];
 #pragma unroll
-      for (int x = 0; x < 3 * S + 3; ++x) iv[x] = load4(row + (size_t)x * vs);
+      for (int x = 0; x < (RL - 1) * S + 3; ++x) iv[x] = load4(row + (size_t)x * vs);
 #pragma unroll
       for (int kx = 0; kx < 3; ++kx)
 #pragma unroll
-        for (int o = 0; o < 4; ++o) acc[o] = fma4(iv[o * S + kx], wr[ky * 3 + kx], acc[o]);
+        for (int o = 0; o < RL; ++o) acc[o] = fma4(iv[o * S + kx], wr[ky * 3 + kx], acc[o]);
     }
     T* dst = out + (((size_t)n * Hout + ho) * Wout + wo0 + wl0) * C + gc;
 #pragma unroll
-    for (int o = 0; o < 4; ++o)
+    for (int o = 0; o < RL; ++o)
       if (wo0 + wl0 + o < Wout) store4(dst + (size_t)o * C, acc[o]);
   }
 }
@@ -514,8 +516,12 @@ static bool dw_check_plan(DwPlan& d) {
 void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z) {
   const int es = dt == 0 ? 4 : 2, s = g.stride;
   DwPlan d = dw_plan(g.Cout, es, s == 2, g.Hout, g.Wout);
+  const int run = s == 2 ? 2 : 4;                // pixels per run, as the kernel's RL
+  d.segw = (d.TW + run - 1) / run;
+  d.nseg = d.TH * d.segw;
+  d.m_segw = dw_magic(d.segw);
   d.PH = (d.TH - 1) * s + 3;
-  d.PW = (d.segw * 4 - 1) * s + 3;               // runs are whole: the patch covers the rounded-up tile width
+  d.PW = (d.segw * run - 1) * s + 3;             // runs are whole: the patch covers the rounded-up tile width
   d.ntiles = g.N * d.tiles_h * d.tiles_w;
   if (!dw_check_plan(d)) return;
   View v{in.z, in.scale, in.shift, in.act};
