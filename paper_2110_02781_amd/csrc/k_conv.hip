@@ -996,9 +996,9 @@ void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvG
 // 9 x 4 sums over all its runs, and the block leaves one partial ws[block][9][C].
 // The dz values of a thread's (at most kDwSegs) 4-pixel runs of one tile, requested a whole tile ahead like the
 // input patch: a persistent block has few neighbours on its CU to hide a load behind.
-template <typename T>
+template <typename T, int RL = 4>
 struct DwDzRuns {
-  Raw4<T> r[kDwSegs][4];
+  Raw4<T> r[kDwSegs][RL];
   unsigned ok;
   __device__ __forceinline__ void fetch(const T* __restrict__ dz, int tile, const DwPlan& d, int Hout, int Wout, int C,
                                         int seg0, int gc, bool worker) {
@@ -1009,27 +1009,28 @@ struct DwDzRuns {
     // offsets first, then unconditional loads back to back (a pixel outside reads the image's first pixel and is
     // not used): see DwPatch::fetch
     const T* img = dz + (size_t)n * Hout * Wout * C + gc;
-    unsigned off[kDwSegs][4];
+    unsigned off[kDwSegs][RL];
 #pragma unroll
     for (int k = 0; k < kDwSegs; ++k) {
       const int sg = seg0 + k * d.spp;
-      const int hl = dw_div(sg < d.nseg ? sg : 0, d.m_segw), wl0 = ((sg < d.nseg ? sg : 0) - hl * d.segw) * 4;
+      const int hl = dw_div(sg < d.nseg ? sg : 0, d.m_segw), wl0 = ((sg < d.nseg ? sg : 0) - hl * d.segw) * RL;
       const int ho = ho0 + hl;
 #pragma unroll
-      for (int o = 0; o < 4; ++o) {
+      for (int o = 0; o < RL; ++o) {
         const bool in = sg < d.nseg && ho < Hout && wo0 + wl0 + o < Wout;
         off[k][o] = in ? __umul24(__umul24(ho, Wout) + wo0 + wl0 + o, C) : 0u;
-        ok |= (in ? 1u : 0u) << (4 * k + o);
+        ok |= (in ? 1u : 0u) << (RL * k + o);
       }
     }
 #pragma unroll
     for (int k = 0; k < kDwSegs; ++k)
 #pragma unroll
-      for (int o = 0; o < 4; ++o) raw4_load(r[k][o], img + off[k][o]);
+      for (int o = 0; o < RL; ++o) raw4_load(r[k][o], img + off[k][o]);
   }
 };
 
-template <typename T, int S>
+// RL = pixels per run: four at stride 1, two at stride 2 (see dw_conv_k)
+template <typename T, int S, int RL = (S == 2 ? 2 : 4)>
 __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View in, DwPlan d, int Hin, int Win, int Hout,
                                                   int Wout, int C, float* __restrict__ ws) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
@@ -1045,7 +1046,7 @@ __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View
 #pragma unroll
   for (int t = 0; t < 9; ++t) acc[t] = make_float4(0.f, 0.f, 0.f, 0.f);
   DwPatch<T> lp;
-  DwDzRuns<T> dq[2];
+  DwDzRuns<T, RL> dq[2];
   if (b < d.ntiles) {
     const int tw = b % d.tiles_w, th = (b / d.tiles_w) % d.tiles_h, n = b / (d.tiles_w * d.tiles_h);
     lp.fetch(src, n, th * d.TH * S - 1, tw * d.TW * S - 1, d, Hin, Win, C, cg0);
@@ -1069,27 +1070,27 @@ __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View
         lp.fetch(src, n2, th2 * d.TH * S - 1, tw2 * d.TW * S - 1, d, Hin, Win, C, cg0);
       }
       if (!worker) continue;
-      const DwDzRuns<T>& cur = dq[par];
+      const DwDzRuns<T, RL>& cur = dq[par];
 #pragma unroll
       for (int k = 0; k < kDwSegs; ++k) {
         const int sg = seg0 + k * d.spp;
         if (sg >= d.nseg) break;
-        if (((cur.ok >> (4 * k)) & 15u) == 0u) continue;     // the run lies outside the image
-        const int hl = dw_div(sg, d.m_segw), wl0 = (sg - hl * d.segw) * 4;
-        float4 dv[4];
+        if (((cur.ok >> (RL * k)) & ((1u << RL) - 1u)) == 0u) continue;     // the run lies outside the image
+        const int hl = dw_div(sg, d.m_segw), wl0 = (sg - hl * d.segw) * RL;
+        float4 dv[RL];
 #pragma unroll
-        for (int o = 0; o < 4; ++o)
-          dv[o] = (cur.ok >> (4 * k + o)) & 1u ? raw4_unpack(cur.r[k][o]) : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int o = 0; o < RL; ++o)
+          dv[o] = (cur.ok >> (RL * k + o)) & 1u ? raw4_unpack(cur.r[k][o]) : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
         for (int ky = 0; ky < 3; ++ky) {
           const T* row = patch + (size_t)((hl * S + ky) * d.PW + wl0 * S) * vs + c4;
-          float4 iv[3 * S + 3];
+          float4 iv[(RL - 1) * S + 3];
 #pragma unroll
-          for (int x = 0; x < 3 * S + 3; ++x) iv[x] = load4(row + (size_t)x * vs);
+          for (int x = 0; x < (RL - 1) * S + 3; ++x) iv[x] = load4(row + (size_t)x * vs);
 #pragma unroll
           for (int kx = 0; kx < 3; ++kx)
 #pragma unroll
-            for (int o = 0; o < 4; ++o) acc[ky * 3 + kx] = fma4(dv[o], iv[o * S + kx], acc[ky * 3 + kx]);
+            for (int o = 0; o < RL; ++o) acc[ky * 3 + kx] = fma4(dv[o], iv[o * S + kx], acc[ky * 3 + kx]);
         }
       }
     }
@@ -1117,8 +1118,12 @@ __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View
 static DwPlan dw_wgrad_plan(const ConvGeom& g, int es, size_t* lds) {
   const int s = g.stride;
   DwPlan d = dw_plan(g.Cout, es, s == 2, g.Hout, g.Wout);
+  const int run = s == 2 ? 2 : 4;                // pixels per run, as the kernel's RL
+  d.segw = (d.TW + run - 1) / run;
+  d.nseg = d.TH * d.segw;
+  d.m_segw = dw_magic(d.segw);
   d.PH = (d.TH - 1) * s + 3;
-  d.PW = (d.segw * 4 - 1) * s + 3;
+  d.PW = (d.segw * run - 1) * s + 3;
   d.ntiles = g.N * d.tiles_h * d.tiles_w;
   // About 384 persistent blocks over all slabs.  Measured: with 512 the stride-2 kernel no longer fits the GPU at once
   // next to the BatchNorm backward of the other stream; blocks then wait for a place, and a 5 us finalize kernel of the
