@@ -504,8 +504,8 @@ static size_t dw_lds_bytes(const DwPlan& d, int es) { return dw_patch_bytes(d, e
 
 // staging is unrolled for kDwFillNV passes; dw_div needs small divisors.  The plans of every shape a model can
 // describe satisfy this; if one ever does not, the launch is skipped and the stage call reports it.
-static bool dw_check_plan(DwPlan& d) {
-  if (d.PH * d.PW > kDwFillNV * d.PPB || d.PW > 63 || d.CGB > 16 || d.segw > 32 || d.nseg > kDwSegs * d.spp) {
+static bool dw_check_plan(DwPlan& d, int segs = kDwSegs) {
+  if (d.PH * d.PW > kDwFillNV * d.PPB || d.PW > 63 || d.CGB > 16 || d.segw > 32 || d.nseg > segs * d.spp) {
     launch_plan_failed("depthwise tile plan outside the kernels' limits");
     return false;
   }
@@ -996,9 +996,9 @@ void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvG
 // 9 x 4 sums over all its runs, and the block leaves one partial ws[block][9][C].
 // The dz values of a thread's (at most kDwSegs) 4-pixel runs of one tile, requested a whole tile ahead like the
 // input patch: a persistent block has few neighbours on its CU to hide a load behind.
-template <typename T, int RL = 4>
+template <typename T, int RL = 4, int SEGS = kDwSegs>
 struct DwDzRuns {
-  Raw4<T> r[kDwSegs][RL];
+  Raw4<T> r[SEGS][RL];
   unsigned ok;
   __device__ __forceinline__ void fetch(const T* __restrict__ dz, int tile, const DwPlan& d, int Hout, int Wout, int C,
                                         int seg0, int gc, bool worker) {
@@ -1009,9 +1009,9 @@ struct DwDzRuns {
     // offsets first, then unconditional loads back to back (a pixel outside reads the image's first pixel and is
     // not used): see DwPatch::fetch
     const T* img = dz + (size_t)n * Hout * Wout * C + gc;
-    unsigned off[kDwSegs][RL];
+    unsigned off[SEGS][RL];
 #pragma unroll
-    for (int k = 0; k < kDwSegs; ++k) {
+    for (int k = 0; k < SEGS; ++k) {
       const int sg = seg0 + k * d.spp;
       const int hl = dw_div(sg < d.nseg ? sg : 0, d.m_segw), wl0 = ((sg < d.nseg ? sg : 0) - hl * d.segw) * RL;
       const int ho = ho0 + hl;
@@ -1023,14 +1023,15 @@ struct DwDzRuns {
       }
     }
 #pragma unroll
-    for (int k = 0; k < kDwSegs; ++k)
+    for (int k = 0; k < SEGS; ++k)
 #pragma unroll
       for (int o = 0; o < RL; ++o) raw4_load(r[k][o], img + off[k][o]);
   }
 };
 
-// RL = pixels per run: four at stride 1, two at stride 2 (see dw_conv_k)
-template <typename T, int S, int RL = (S == 2 ? 2 : 4)>
+// RL = pixels per run: four at stride 1, two at stride 2 (see dw_conv_k); SEGS = runs of a tile per thread: the 4 x 8
+// stride-2 tile has 16 runs, one per thread
+template <typename T, int S, int RL = (S == 2 ? 2 : 4), int SEGS = (S == 2 ? 1 : kDwSegs)>
 __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View in, DwPlan d, int Hin, int Win, int Hout,
                                                   int Wout, int C, float* __restrict__ ws) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
@@ -1046,7 +1047,7 @@ __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View
 #pragma unroll
   for (int t = 0; t < 9; ++t) acc[t] = make_float4(0.f, 0.f, 0.f, 0.f);
   DwPatch<T> lp;
-  DwDzRuns<T, RL> dq[2];
+  DwDzRuns<T, RL, SEGS> dq[2];
   if (b < d.ntiles) {
     const int tw = b % d.tiles_w, th = (b / d.tiles_w) % d.tiles_h, n = b / (d.tiles_w * d.tiles_h);
     lp.fetch(src, n, th * d.TH * S - 1, tw * d.TW * S - 1, d, Hin, Win, C, cg0);
@@ -1070,9 +1071,9 @@ __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View
         lp.fetch(src, n2, th2 * d.TH * S - 1, tw2 * d.TW * S - 1, d, Hin, Win, C, cg0);
       }
       if (!worker) continue;
-      const DwDzRuns<T, RL>& cur = dq[par];
+      const DwDzRuns<T, RL, SEGS>& cur = dq[par];
 #pragma unroll
-      for (int k = 0; k < kDwSegs; ++k) {
+      for (int k = 0; k < SEGS; ++k) {
         const int sg = seg0 + k * d.spp;
         if (sg >= d.nseg) break;
         if (((cur.ok >> (RL * k)) & ((1u << RL) - 1u)) == 0u) continue;     // the run lies outside the image
@@ -1125,11 +1126,13 @@ static DwPlan dw_wgrad_plan(const ConvGeom& g, int es, size_t* lds) {
   d.PH = (d.TH - 1) * s + 3;
   d.PW = (d.segw * run - 1) * s + 3;
   d.ntiles = g.N * d.tiles_h * d.tiles_w;
-  // About 384 persistent blocks over all slabs.  Measured: with 512 the stride-2 kernel no longer fits the GPU at once
-  // next to the BatchNorm backward of the other stream; blocks then wait for a place, and a 5 us finalize kernel of the
-  // data-gradient chain waited up to 200 us with them (a trace shows it ending when the first blocks end).  256 blocks
-  // leave the weight gradient itself too slow.
-  const int cap = 384 / d.nslab > 1 ? 384 / d.nslab : 1;
+  // Persistent blocks over all slabs: fewer than fit the GPU at once next to the other stream's kernels.  The stride-1
+  // kernel holds 207 registers (two blocks per CU): with 512 blocks some waited for a place, and a 5 us finalize kernel
+  // of the data-gradient chain was measured waiting up to 200 us with them (a trace shows it ending when the first
+  // blocks end); 256 leave the weight gradient itself too slow.  The stride-2 kernel holds 149 registers (three blocks
+  // per CU): 480 measured best of 384-768.
+  const int capn = s == 2 ? 480 : 384;
+  const int cap = capn / d.nslab > 1 ? capn / d.nslab : 1;
   d.nblocks = d.ntiles < cap ? d.ntiles : cap;
   size_t a = (size_t)d.PH * d.PW * d.CGB * 8 * es;          // the patch in the tensor's type
   size_t b = (size_t)d.spp * 9 * 2 * d.CGB * 16;
@@ -1148,7 +1151,7 @@ void dw_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& 
   const int es = dt == 0 ? 4 : 2;
   size_t lds;
   DwPlan d = dw_wgrad_plan(g, es, &lds);
-  if (!dw_check_plan(d)) return;     // also: a thread holds the dz of at most kDwSegs runs per tile
+  if (!dw_check_plan(d, g.stride == 2 ? 1 : kDwSegs)) return;     // also: the runs of a tile whose dz a thread holds
   View v{in.z, in.scale, in.shift, in.act};
   {
     KScope ks(st, "dw_wgrad", ((double)g.N * g.Hin * g.Win * g.Cout + (double)g.N * g.Hout * g.Wout * g.Cout) * es + (double)d.nblocks * 9 * g.Cout * 4,
