@@ -684,8 +684,7 @@ __device__ __forceinline__ void load_pair(const bf16_t* p, float& a, float& b) {
   a = __uint_as_float(v << 16); b = __uint_as_float(v & 0xffff0000u);
 }
 
-// CH = reduction elements staged per step: the bfloat16 weight gradient runs with 64, which halves the steps and
-// their barriers.
+// CH = reduction elements staged per step (32 everywhere, see launch_t).
 // RES: data gradient with a residual to add (a variant of its own: the sixteen prefetched residual pairs cost
 // registers that the plain data gradient should not pay for)
 // DEEP: data gradient whose reduction spans at least two steps.  The loads of TWO steps are kept in flight (two
@@ -1200,16 +1199,14 @@ static void launch_tiny(int dt, hipStream_t st, GemmArgs& a, int ncols) {
   else hipLaunchKernelGGL((pw_gemm_tiny_k<bf16_t, MODE>), dim3(grid), dim3(256), 0, st, a);
 }
 
-enum { kDeepReduction = 256 };   // bfloat16 reductions at least this long are staged 64 elements per step
 template <typename T, int MODE, bool VEC>
 static void launch_t(hipStream_t st, const GemmArgs& a, bool small, unsigned grid) {
   if (small) { hipLaunchKernelGGL((pw_gemm_k<T, MODE, true, VEC>), dim3(grid), dim3(256), 0, st, a); return; }
   const size_t red = MODE == MODE_FWD ? (size_t)a.K : MODE == MODE_DGRAD ? (size_t)a.N : a.mchunk;   // reduction extent of a block
-  // measured: the weight gradient (both operands transposed on the way into LDS) gains 10-30 %, forward and data
-  // gradient lose a little (fewer blocks fit a CU)
-  if (MODE == MODE_WGRAD && sizeof(T) == 2 && red >= (size_t)kDeepReduction)
-    hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, sizeof(T) == 2 ? 64 : 32, false, MODE == MODE_WGRAD>), dim3(grid), dim3(256), 0, st, a);
-  else if (MODE == MODE_WGRAD && red > 32)
+  // Every mode stages 32 reduction elements per step.  64 per step made the weight-gradient kernel itself 5 % faster
+  // (half the barriers) but costs 55 KB of LDS per block: next to the data-gradient chain on the other stream the
+  // step was 0.9 % slower with it.
+  if (MODE == MODE_WGRAD && red > 32)
     hipLaunchKernelGGL((pw_gemm_rows_k<T, MODE, VEC, 32, false, MODE == MODE_WGRAD>), dim3(grid), dim3(256), 0, st, a);
   else if (MODE == MODE_DGRAD && red > 32) {     // at least two steps per tile: two steps' loads in flight
     constexpr bool D = MODE == MODE_DGRAD;
