@@ -2,14 +2,15 @@
 """Stage-training throughput on one MI355X: forward + loss + backward + SGD update of one
 pipeline stage on seeded synthetic data, through the C-ABI library.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config {1,2,5}] [--also 5] [--graph]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config {1,2,5,6}] [--also 2 1] [--graph]
 
-Prints ONE JSON line: samples/s of the whole step (inputs resident in HBM), the roofline
-of the kernel family that takes the most time (measured with HIP events around every
-launch in a second pass of K steps) and the CPU oracle timed on this host as a baseline.
-The headline workload is config 2 (MobileNetV2 at 32x32, batch 32, fp32); because its tensors
-are a few MB and its step is launch-latency bound, the large bf16 workload (config 5) is
-measured in the same run and reported under "also" with its own roofline.
+Prints ONE JSON line: samples/s of the whole step (inputs resident in HBM; K steps between two
+device synchronisations, plus the median of the K per-step times from HIP events on the stream),
+the roofline of the kernel family that takes the most time (HIP events around every launch in a
+second pass, less the measured cost of the event pair) and the CPU oracle timed on this host as
+a baseline.  The headline workload is the largest single-GPU configuration, config 5 (MobileNetV2
+w1.4 at 224x224, batch 128, bf16); config 2 (32x32, batch 32, fp32, launch-latency bound) and
+config 1 (the 1-D CNN) are measured in the same run and reported under "also".
 """
 import argparse
 import json
@@ -45,17 +46,18 @@ def build_units(P, w):
     return P.models.mobilenet_v2_units(w["width"], w["classes"], w["stem_stride"])
 
 
-def oracle_baseline(w, seed, budget_s=30.0):
-    """One training step of the CPU oracle (float64, as it stands) on a bounded sample of the
-    same workload: the batch is cut so that the step should fit the time budget."""
+def oracle_baseline(w, seed, budget_s=10.0, one_thread=False):
+    """Training steps of the CPU oracle (float64, as it stands) on a bounded sample of the
+    same workload: the batch is cut so that a step takes seconds, and whole steps are repeated
+    for about budget_s.  one_thread: with the numerical library held to one thread."""
     import synth
     from oracle import models as OM
     from oracle.stage import Stage
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        threads = os.cpu_count() or 1
+    from threadpoolctl import threadpool_info, threadpool_limits
+    if one_thread:
+        with threadpool_limits(limits=1):
+            return oracle_baseline(w, seed, budget_s)
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     units = OM.cnn1d() if w["net"] == "cnn1d" else OM.mobilenet_v2(w["width"], w["classes"], w["stem_stride"])
     # rough cost model: config-2 batch 32 takes a few seconds; 224x224 images cost 49x more per sample
     per_sample = (w["in_shape"][0] * w["in_shape"][1]) / 1024.0 * (w.get("width", 1.0) ** 2)
@@ -76,7 +78,7 @@ def oracle_baseline(w, seed, budget_s=30.0):
         st.update(w["lr"], w["mu"], w["wd"])
         nsteps += 1
         dt = time.perf_counter() - t0
-        if dt >= 10.0 or nsteps >= 200:
+        if dt >= budget_s or nsteps >= 200:
             break
     return dict(value=batch * nsteps / dt, unit="samples/s", cores=int(threads), kind="oracle",
                 sample=f"{nsteps} full training steps (fwd+loss+bwd+update) of the same network at batch {batch} "
@@ -97,6 +99,53 @@ def load_traffic(config):
                 except ValueError:
                     pass
     return out
+
+
+def fused_rule_step_bytes(units, in_shape, batch, es):
+    """Bytes a training step must move under the best legal fusion (the accounting the roofline of the WHOLE step
+    uses): per convolution + BatchNorm (+ activation) with input `i` and output `z`, forward i + z, backward
+    2 i + 3 z; a residual block 2 |out| more each way; global average pool its input each way; FC its operands;
+    the update 20 bytes per parameter (+ 2 for the bfloat16 copy)."""
+    import paper_2110_02781_amd.binding as B
+    H, W, C = in_shape
+    fwd = bwd = 0.0
+    n_param = 0
+    for u in units:
+        k = u["kind"]
+        if k == B.UNIT_CONV:
+            Ho = (H + 2 * u.get("pad_h", 0) - u["kh"]) // u["stride"] + 1
+            Wo = (W + 2 * u.get("pad_w", 0) - u["kw"]) // u["stride"] + 1
+            i, z = batch * H * W * C * es, batch * Ho * Wo * u["cout"] * es
+            fwd += i + z; bwd += 2 * i + 3 * z
+            n_param += u["cout"] * u["kh"] * u["kw"] * C + 2 * u["cout"]
+            H, W, C = Ho, Wo, u["cout"]
+        elif k == B.UNIT_INVRES:
+            ce, s_ = C * u["expand"], u["stride"]
+            Ho, Wo = (H + 2 - 3) // s_ + 1, (W + 2 - 3) // s_ + 1
+            xin = batch * H * W * C * es
+            if u["expand"] != 1:
+                z = batch * H * W * ce * es
+                fwd += xin + z; bwd += 2 * xin + 3 * z
+                n_param += ce * C + 2 * ce
+            i, z = batch * H * W * ce * es, batch * Ho * Wo * ce * es
+            fwd += i + z; bwd += 2 * i + 3 * z
+            n_param += 9 * ce + 2 * ce
+            i, z = z, batch * Ho * Wo * u["cout"] * es
+            fwd += i + z; bwd += 2 * i + 3 * z
+            n_param += u["cout"] * ce + 2 * u["cout"]
+            if s_ == 1 and C == u["cout"]:
+                fwd += 2 * z; bwd += 2 * z
+            H, W, C = Ho, Wo, u["cout"]
+        elif k == B.UNIT_GAP:
+            fwd += batch * H * W * C * es; bwd += batch * H * W * C * es
+            H = W = 1
+        elif k == B.UNIT_FC:
+            fwd += (batch * C + batch * u["cout"] + C * u["cout"]) * es
+            bwd += 2 * (batch * C + batch * u["cout"] + C * u["cout"]) * es
+            n_param += u["cout"] * C + u["cout"]
+            C = u["cout"]
+    upd = n_param * (20.0 + (2.0 if es == 2 else 0.0))
+    return dict(forward=fwd, backward=bwd, update=upd, total=fwd + bwd + upd)
 
 
 SPINUP_S = 1.0
@@ -154,16 +203,31 @@ def run_workload(config, steps, warmup, use_graph, ktrace, calibrate, seed):
         torch.cuda.synchronize()
     for _ in range(warmup):
         run()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(steps):
-        run()
+    with torch.cuda.stream(stream):
+        for k in range(steps):
+            marks[k].record(stream)          # on the stream the kernels are launched on
+            run()
+        marks[steps].record(stream)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(steps))
+    median_ms = per_step[len(per_step) // 2] if steps % 2 else 0.5 * (per_step[steps // 2 - 1] + per_step[steps // 2])
     final_loss = float(loss.item())
+    es = 4 if w["dtype"] == "f32" else 2
+    rule = fused_rule_step_bytes(units, w["in_shape"], w["batch"], es)
     res = dict(workload=w["name"], batch=w["batch"], units=L, dtype=w["dtype"], hip_graph=bool(use_graph),
                value=round(w["batch"] * steps / dt, 2), ms_per_step=round(dt / steps * 1e3, 4),
-               final_loss=round(final_loss, 4), roofline=None, kernels=[])
+               median_ms_per_step=round(median_ms, 4), min_ms_per_step=round(per_step[0], 4),
+               final_loss=round(final_loss, 4), roofline=None, kernels=[],
+               whole_step=dict(alg_bytes=round(rule["total"]), alg_bytes_forward=round(rule["forward"]),
+                               alg_bytes_backward=round(rule["backward"]), alg_bytes_update=round(rule["update"]),
+                               achieved_GBps=round(rule["total"] / (median_ms * 1e-3) / 1e9, 1),
+                               frac_of_hbm_peak=round(rule["total"] / (median_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                               note="bytes under the best legal fusion (conv+BN: forward in+z, backward 2in+3z; residual 2 out each "
+                                    "way; update 20-22 B/param) / median step time / 8 TB/s"))
 
     # second pass: HIP events around every launch -> the dominant kernel family and its roofline
     if ktrace:
@@ -173,6 +237,11 @@ def run_workload(config, steps, warmup, use_graph, ktrace, calibrate, seed):
         for _ in range(nsteps):
             step()
         rows = P.ktrace_end()
+        pair_ms = sum(r["total_ms"] for r in rows if r["name"] == "__event_pair_overhead")
+        rows = [r for r in rows if r["name"] != "__event_pair_overhead"]
+        for r in rows:                       # take the cost of the event pair off every launch
+            r["raw_total_ms"] = r["total_ms"]
+            r["total_ms"] = max(r["total_ms"] - pair_ms * r["launches"], 0.05 * r["total_ms"])
         rows.sort(key=lambda r: -r["total_ms"])
         tot = sum(r["total_ms"] for r in rows) or 1.0
         for r in rows:
@@ -196,9 +265,13 @@ def run_workload(config, steps, warmup, use_graph, ktrace, calibrate, seed):
         roof.update(kernel=d["name"], avg_launch_us=round(d["total_ms"] / d["launches"] * 1e3, 2),
                     launches_per_step=d["launches"] / nsteps,
                     alg_bytes_per_launch=round(d["alg_bytes"] / d["launches"]),
+                    event_pair_overhead_us=round(pair_ms * 1e3, 2),
+                    avg_launch_us_with_event_pair=round(d["raw_total_ms"] / d["launches"] * 1e3, 2),
                     note="algorithmic bytes = every operand of a launch once; durations from HIP events around each "
-                         "launch on its stream, in a separate traced pass; traffic = measured HBM bytes per launch "
-                         "(rocprofv3 FETCH_SIZE + WRITE_SIZE, see profiles/) or null")
+                         "launch on its stream, in a separate traced pass, less the cost of the event pair itself "
+                         "(measured on empty kernels when the trace starts); traffic = HBM bytes per launch from "
+                         f"profiles/config{config}_pmc_traffic.txt (rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a plain "
+                         "copy; a committed measurement, not taken in this run) or null")
         res["roofline"] = roof
     P.stage_destroy(stage)
     P.model_destroy(model)
@@ -309,11 +382,11 @@ def bench_recompute(config, micro=4, reps=3, seed=2110):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, choices=sorted(WORKLOADS))
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=5, choices=sorted(WORKLOADS))
     ap.add_argument("--also", type=int, nargs="*", default=None,
-                    help="further configs reported under 'also' (default: 5 when --config is 2)")
+                    help="further configs reported under 'also' (default: 2 and 1 when --config is 5)")
     ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ktrace", action="store_true")
@@ -334,20 +407,24 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     main_res = run_workload(args.config, args.steps, args.warmup, args.graph, not args.no_ktrace, args.calibrate, args.seed)
-    also_cfgs = args.also if args.also is not None else ([5] if args.config == 2 else [])
+    also_cfgs = args.also if args.also is not None else ([2, 1] if args.config == 5 else [])
     also = []
     for c in also_cfgs:
         if c == args.config or c not in WORKLOADS:
             continue
-        r = run_workload(c, max(5, min(args.steps, 10)), 3, False, not args.no_ktrace, False, args.seed)
+        small = WORKLOADS[c]["batch"] * WORKLOADS[c]["in_shape"][0] * WORKLOADS[c]["in_shape"][1] <= (1 << 16)
+        r = run_workload(c, 200 if small else 20, 20 if small else 5, False, not args.no_ktrace, False, args.seed)
         r["kernels"] = r["kernels"][:12]
+        if not args.no_cpu_baseline and small:
+            r["cpu_baseline"] = oracle_baseline(WORKLOADS[c], args.seed, 3.0)
+            r["cpu_baseline_one_thread"] = oracle_baseline(WORKLOADS[c], args.seed, 3.0, one_thread=True)
         also.append(r)
 
-    # the widened row: weight aggregation over three stashed versions, on the larger parameter set
+    # the widened rows: weight aggregation over three stashed versions and recomputation, on the headline workload
     agg = rec = None
-    if also and not args.no_ktrace:
-        agg = bench_aggregate(also_cfgs[0] if also_cfgs[0] in WORKLOADS else args.config, 3, 50, args.seed)
-        rec = bench_recompute(also_cfgs[0] if also_cfgs[0] in WORKLOADS else args.config, 4, 3, args.seed)
+    if args.config == 5 and not args.no_ktrace:
+        agg = bench_aggregate(args.config, 3, 50, args.seed)
+        rec = bench_recompute(args.config, 4, 3, args.seed)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -356,11 +433,13 @@ def main():
     out = {
         "metric": "stage train samples/sec (fwd+bwd+update) at 1 MI355X; % HBM/MFMA roofline",
         "value": main_res["value"], "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": main_res["ms_per_step"], "median_ms_per_step": main_res["median_ms_per_step"],
+        "min_ms_per_step": main_res["min_ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": main_res["dtype"], "data": "synthetic (seeded N(0,1) inputs, uniform labels, He-normal weights)",
         "config": {"workload": main_res["workload"], "batch": main_res["batch"], "units": main_res["units"],
                    "hip_graph": main_res["hip_graph"], "final_loss": main_res["final_loss"]},
-        "roofline": main_res["roofline"], "cpu_baseline": cpu, "kernels": main_res["kernels"], "also": also,
+        "roofline": main_res["roofline"], "whole_step": main_res["whole_step"], "cpu_baseline": cpu,
+        "kernels": main_res["kernels"], "also": also,
         "aggregate": agg, "recompute": rec,
     }
     print(json.dumps(out))

@@ -161,6 +161,20 @@ int ftp_stage_forward(ftp_stage*, int slot, const void* x_dev, void* y_dev, void
  * float); also seeds the slot's backward so dy_dev may be NULL there. */
 int ftp_stage_loss(ftp_stage*, int slot, const int32_t* labels_dev, float* loss_dev, void* stream);
 
+/* The loss of ftp_stage_loss for callers that cannot allocate device memory and have no stage object at hand: code
+ * under HIP graph capture, tight serving or evaluation loops, harnesses that forbid hipMalloc.  Same kernels, same
+ * results bit for bit; the per-row losses that ftp_stage_loss keeps in memory the stage allocated live in a
+ * file-scope device array of FTP_STATIC_LOSS_MAX_BATCH floats (256 KiB per GPU, held until the process ends).
+ * logits_dev [batch, classes] and dlogits_dev (same shape, receives (softmax - onehot) / batch) are of `dtype`;
+ * labels_dev int32 [batch], 0 <= label < classes (a label outside gives a NaN loss); loss_dev one float.  The caller
+ * owns all four buffers.  batch > FTP_STATIC_LOSS_MAX_BATCH: FTP_ERR_ARG, nothing is launched.  Calls no hipMalloc,
+ * hipFree or other allocating routine (the first call on a device looks up that device's address of the array);
+ * nothing in the array has to be cleared between calls.  All calls on one GPU share the array: calls that may run
+ * concurrently there (different streams without an ordering) race on it.  Asynchronous on `stream`. */
+#define FTP_STATIC_LOSS_MAX_BATCH 65536
+int ftp_softmax_ce_static(const void* logits_dev, const int32_t* labels_dev, int batch, int classes, ftp_dtype dtype,
+                          void* dlogits_dev, float* loss_dev, void* stream);
+
 /* Copies the current weights into the slot (weight stashing): the slot's
  * backward then differentiates with respect to that version.  Call it between
  * the slot's forward and the next update.  Without it, backward uses the
@@ -192,11 +206,14 @@ int ftp_stage_update(ftp_stage*, const ftp_sgd* opt, void* stream);
 
 /* ---- profiling and partition ------------------------------------------------ */
 
-/* Model profiling: runs forward and backward of every unit of the whole model
- * on synthetic data `reps` times (the paper uses 10) after 2 discarded warm-up
- * runs, and returns per unit the mean forward+backward time in nanoseconds
- * rounded to an integer value (t_ns, host, [L]) and the output size in bytes
- * (out_bytes, host, [L]).  Synchronous. */
+/* Model profiling (section "Initialization", model profiling phase: the central node measures the running time
+ * of the forward and backward pass of each layer, averaged over ten executions, and the size of each layer's
+ * output).  Runs forward and backward of every unit of the whole model on synthetic data `reps` times (the paper
+ * uses 10) after 2 discarded warm-up runs, and returns per unit the mean forward+backward time in nanoseconds
+ * rounded to an integer value (t_ns, host, [L]) and the output size in bytes (out_bytes, host, [L]).  The
+ * per-unit times are measured unit after unit on one stream and then scaled by one common factor so that their
+ * sum is the mean forward+backward time of a whole batch under the execution plan training uses (`reps` more
+ * runs): ftp_estimate_capacity of this same device on the whole model is then 1.  Synchronous. */
 int ftp_profile_layers(const ftp_model*, int batch, int reps, double* t_ns, int64_t* out_bytes,
                        void* stream);
 
@@ -263,6 +280,17 @@ int ftp_stage_timing_read(ftp_stage*, double* mean_ns, int* n_batches);
 int ftp_redistribution_plan(const int32_t* bounds_new, int n_new, const int32_t* bounds_cur, int n_cur, int i_fail,
                             int i_cur, int i_new, int32_t* source);
 
+/* Worker list after failures (section "Fault Tolerance Mechanism": with one failed worker every index greater
+ * than its index decreases by one and the smaller ones stay; with several, each failed worker is replaced by the
+ * alive workers that follow it, one by one).  worker_ids[n]: the current list (device ids in training order,
+ * entry 0 the central node); failed[n_failed]: indices into it, each in 1..n-1 (the central node runs the fault
+ * handler and cannot be listed), no index twice.  new_ids (room for n entries) receives the alive entries in
+ * their old order and *n_new their number; new_index (n entries, may be NULL) receives for every old index its
+ * new index, or -1 for a failed worker.  The index a failed worker had is thereby carried by the alive worker
+ * that followed it, which is what ftp_redistribution_plan's `source` refers to.  Host pointers only. */
+int ftp_renumber_workers(const int32_t* worker_ids, int n, const int32_t* failed, int n_failed, int32_t* new_ids,
+                         int32_t* new_index, int* n_new);
+
 /* Device-side half of the redistribution: copies weights, momentum and BatchNorm
  * running statistics of units [unit_lo, unit_hi) from `src` to `dst` (both
  * stages must contain the range and be built from the same model and type),
@@ -280,6 +308,9 @@ int ftp_stage_copy_units(ftp_stage* dst, const ftp_stage* src, int unit_lo, int 
  * event pool; exceeding it makes end return FTP_ERR_ARG with partial rows.  A
  * negative max_launches (pool size = its magnitude) splits the rows further by
  * problem shape: the name then reads "family d0 d1 d2" (GEMMs: M K N).
+ * One more row, named "__event_pair_overhead" (launches = 1), gives in total_ms what a pair of events adds
+ * to the launch it brackets, measured at begin on empty kernels: take it off every launch's time to get kernel
+ * durations comparable with a profiler's.
  * Process-wide, not thread-safe, and the event records slow small steps down. */
 typedef struct {
   char name[48];
@@ -288,6 +319,12 @@ typedef struct {
 } ftp_ktrace_row;
 int ftp_ktrace_begin(int max_launches);
 int ftp_ktrace_end(ftp_ktrace_row* rows, int max_rows, int* n_rows);
+
+/* Test hook for the error path of the compute calls: marks, for the calling thread, a launch plan as failed, exactly
+ * as a kernel launcher does when a shape falls outside what its kernel was written for.  The next compute call of
+ * this thread (forward, loss, backward, update, aggregate, copy_units) then returns FTP_ERR_UNSUPPORTED with the
+ * reason in ftp_last_error() and clears the mark; other threads are not affected. */
+int ftp_diag_fail_next_launch_plan(void);
 
 /* Copies `bytes` (a multiple of 16) from src_dev to dst_dev with a plain kernel: a launch of
  * exactly known HBM traffic (bytes read + bytes written) against which hardware traffic counters

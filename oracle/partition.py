@@ -109,18 +109,26 @@ def redistribution_plan(bounds_new, bounds_cur, i_fail, i_cur, i_new):
     that follows it in the chain (chain replication puts its backup there: that
     worker's new index equals the failed index), or from worker 0 (the central
     node) when the failed stage was the last one."""
-    start_cur, end_cur = bounds_cur[i_cur], bounds_cur[i_cur + 1] - 1
-    start_new, end_new = bounds_new[i_new], bounds_new[i_new + 1] - 1
-    needed = [l for l in range(start_new, end_new + 1) if not (start_cur <= l <= end_cur)]
-    local = [l for l in range(start_new, end_new + 1) if l not in needed]
-    last_stage = len(bounds_cur) - 2
-    m_need = {}
-    for l in needed:
-        target = next(k for k in range(len(bounds_cur) - 1) if bounds_cur[k] <= l < bounds_cur[k + 1])
-        if i_fail is not None:
-            if target > i_fail:
-                target -= 1
-            elif target == i_fail and i_fail == last_stage:
-                target = 0
-        m_need.setdefault(target, []).append(l)
+    n_cur = len(bounds_cur) - 1
+    holder = {}                       # layer -> stage that holds it under the current partition
+    for k in range(n_cur):
+        for l in range(bounds_cur[k], bounds_cur[k + 1]):
+            holder[l] = k
+
+    def index_after_failure(k):
+        """Where the weights of current stage k are found once the failed worker has left the list."""
+        if i_fail is None or k < i_fail:
+            return k
+        if k > i_fail:
+            return k - 1              # every worker behind the failed one moved up by one
+        # the failed stage itself: its chain successor keeps the backup and has just taken over this index;
+        # the last stage has no successor, its backup sits on the central node
+        return 0 if i_fail == n_cur - 1 else k
+
+    m_need, local = {}, []
+    for l in range(bounds_new[i_new], bounds_new[i_new + 1]):
+        if holder[l] == i_cur:
+            local.append(l)
+        else:
+            m_need.setdefault(index_after_failure(holder[l]), []).append(l)
     return m_need, local

@@ -28,7 +28,7 @@ def _conv_bn_act_fwd(x, w, gamma, beta, stride, ph, pw, groups, act, q=_identity
     z = q(L.conv2d_fwd(x, q(w), stride, ph, pw, groups))
     y, mean, invstd, var = L.bn_fwd(z, gamma, beta)
     a = q(L.act_fwd(y, act))
-    return a, dict(x=x, z=z, y=y, mean=mean, invstd=invstd, var=var, beta=beta)
+    return a, dict(x=x, z=z, y=y, mean=mean, invstd=invstd, var=var, gamma=gamma, beta=beta)
 
 
 def _conv_bn_act_bwd(da, c, w, gamma, stride, ph, pw, groups, act, q=_identity, tie=None):

@@ -79,6 +79,7 @@ _SIGS = {
     "ftp_stage_export_bn_batch_stats": (_i, [_vp, _i, _i, _i, _fp, _sz]),
     "ftp_stage_forward": (_i, [_vp, _i, _vp, _vp, _vp]),
     "ftp_stage_loss": (_i, [_vp, _i, _vp, _vp, _vp]),
+    "ftp_softmax_ce_static": (_i, [_vp, _vp, _i, _i, _i, _vp, _vp, _vp]),
     "ftp_stage_snapshot_weights": (_i, [_vp, _i, _vp]),
     "ftp_stage_aggregate_weights": (_i, [_vp, C.POINTER(C.c_int), _i, _vp]),
     "ftp_stage_backward": (_i, [_vp, _i, _vp, _vp, _vp]),
@@ -89,10 +90,13 @@ _SIGS = {
     "ftp_repartition_due": (_i, [C.c_int64, C.POINTER(_i)]),
     "ftp_repartition_capacities": (_i, [_dp, _dp, _i, C.POINTER(C.c_int32), _i, _dp]),
     "ftp_redistribution_plan": (_i, [C.POINTER(C.c_int32), _i, C.POINTER(C.c_int32), _i, _i, _i, _i, C.POINTER(C.c_int32)]),
+    "ftp_renumber_workers": (_i, [C.POINTER(C.c_int32), _i, C.POINTER(C.c_int32), _i, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                  C.POINTER(_i)]),
     "ftp_stage_copy_units": (_i, [_vp, _vp, _i, _i, _vp]),
     "ftp_stage_timing": (_i, [_vp, _i]),
     "ftp_stage_timing_read": (_i, [_vp, _dp, C.POINTER(C.c_int)]),
     "ftp_calibration_copy": (_i, [_vp, _vp, _sz, _vp]),
+    "ftp_diag_fail_next_launch_plan": (_i, []),
     "ftp_ktrace_begin": (_i, [_i]),
     "ftp_ktrace_end": (_i, [C.POINTER(KtraceRow), _i, C.POINTER(_i)]),
 }
@@ -241,6 +245,14 @@ def stage_loss(stage, slot, labels_dev, loss_dev, stream=None):
     _chk(lib.ftp_stage_loss(stage, slot, _ptr(labels_dev), _ptr(loss_dev), _ptr(stream)))
 
 
+STATIC_LOSS_MAX_BATCH = 65536
+
+
+def softmax_ce_static(logits_dev, labels_dev, batch, classes, dtype, dlogits_dev, loss_dev, stream=None):
+    _chk(lib.ftp_softmax_ce_static(_ptr(logits_dev), _ptr(labels_dev), batch, classes, dtype, _ptr(dlogits_dev), _ptr(loss_dev),
+                                   _ptr(stream)))
+
+
 def stage_snapshot_weights(stage, slot, stream=None):
     _chk(lib.ftp_stage_snapshot_weights(stage, slot, _ptr(stream)))
 
@@ -304,6 +316,10 @@ def ktrace_end():
                  alg_bytes=rows[i].alg_bytes, flops=rows[i].flops) for i in range(n.value)]
 
 
+def diag_fail_next_launch_plan():
+    _chk(lib.ftp_diag_fail_next_launch_plan())
+
+
 def calibration_copy(dst_dev, src_dev, nbytes, stream=None):
     _chk(lib.ftp_calibration_copy(_ptr(dst_dev), _ptr(src_dev), nbytes, _ptr(stream)))
 
@@ -341,6 +357,19 @@ def redistribution_plan(bounds_new, bounds_cur, i_fail, i_cur, i_new):
         else:
             m_need.setdefault(int(src[j]), []).append(unit)
     return m_need, local
+
+
+def renumber_workers(worker_ids, failed):
+    """-> (new worker list, old index -> new index with -1 for the failed)."""
+    ids = np.ascontiguousarray(worker_ids, dtype=np.int32)
+    fl = np.ascontiguousarray(failed, dtype=np.int32)
+    out = np.zeros(max(len(ids), 1), dtype=np.int32)
+    idx = np.zeros(max(len(ids), 1), dtype=np.int32)
+    n_new = C.c_int(0)
+    i32p = C.POINTER(C.c_int32)
+    _chk(lib.ftp_renumber_workers(ids.ctypes.data_as(i32p), len(ids), fl.ctypes.data_as(i32p), len(fl),
+                                  out.ctypes.data_as(i32p), idx.ctypes.data_as(i32p), C.byref(n_new)))
+    return [int(v) for v in out[:n_new.value]], [int(v) for v in idx[:len(ids)]]
 
 
 def stage_copy_units(dst, src, unit_lo, unit_hi, stream=None):

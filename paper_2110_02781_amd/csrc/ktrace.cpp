@@ -1,6 +1,7 @@
 // Per-launch kernel timing behind ftp_ktrace_begin / ftp_ktrace_end.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 #include <map>
@@ -20,11 +21,46 @@ struct Trace {
   size_t used = 0;
   bool overflow = false;
   bool detail = false;   // one row per (kernel family, problem shape) instead of per family
+  double bracket_overhead_ms = 0.0;   // what a pair of events adds to the launch it brackets (measured at begin)
 } g_trace;
+
+__global__ void ktrace_noop_k() {}
+
+// The time between the two events around a launch is the kernel plus what the events themselves cost.  With e1 the
+// bracket around one empty kernel and e2 the bracket around two of them, the second kernel costs e2 - e1 and the
+// bracket alone 2*e1 - e2 (medians of 64 samples each on a stream of its own).
+double measure_bracket_overhead_ms() {
+  hipStream_t st = nullptr;
+  hipEvent_t a = nullptr, b = nullptr;
+  if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) return 0.0;
+  double out = 0.0;
+  if (hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess) {
+    std::vector<float> t[2];
+    for (int rep = 0; rep < 72; ++rep)
+      for (int n = 1; n <= 2; ++n) {
+        (void)hipEventRecord(a, st);
+        for (int k = 0; k < n; ++k) hipLaunchKernelGGL(ktrace_noop_k, dim3(1), dim3(64), 0, st);
+        (void)hipEventRecord(b, st);
+        (void)hipStreamSynchronize(st);
+        float ms = 0.f;
+        if (rep >= 8 && hipEventElapsedTime(&ms, a, b) == hipSuccess) t[n - 1].push_back(ms);
+      }
+    if (!t[0].empty() && !t[1].empty()) {
+      for (auto& v : t) std::nth_element(v.begin(), v.begin() + v.size() / 2, v.end());
+      out = 2.0 * t[0][t[0].size() / 2] - t[1][t[1].size() / 2];
+      if (out < 0.0) out = 0.0;
+    }
+  }
+  if (a) (void)hipEventDestroy(a);
+  if (b) (void)hipEventDestroy(b);
+  (void)hipStreamDestroy(st);
+  return out;
+}
 }  // namespace
 
 namespace ftp {
-static const char* g_plan_failure = nullptr;
+// per thread, like the error text: the launcher that fails and the stage call that reports it run on one thread
+static thread_local const char* g_plan_failure = nullptr;
 void launch_plan_failed(const char* what) { g_plan_failure = what; }
 const char* launch_plan_failure_take() { const char* w = g_plan_failure; g_plan_failure = nullptr; return w; }
 
@@ -40,6 +76,11 @@ KScope::~KScope() {
   if (slot >= 0) (void)hipEventRecord(g_trace.recs[slot].e1, st);
 }
 }  // namespace ftp
+
+extern "C" int ftp_diag_fail_next_launch_plan(void) {
+  ftp::launch_plan_failed("launch plan failure requested through ftp_diag_fail_next_launch_plan");
+  return FTP_OK;
+}
 
 static void trace_release() {
   for (auto& r : g_trace.recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
@@ -62,6 +103,7 @@ extern "C" int ftp_ktrace_begin(int max_launches) {
     }
   }
   g_trace.overflow = false;
+  g_trace.bracket_overhead_ms = measure_bracket_overhead_ms();
   g_trace.on = true;
   return FTP_OK;
 }
@@ -84,6 +126,13 @@ extern "C" int ftp_ktrace_end(ftp_ktrace_row* rows, int max_rows, int* n_rows) {
   }
   int n = 0;
   for (auto& kv : agg) { if (n < max_rows) rows[n++] = kv.second; }
+  if (n < max_rows) {      // what to take off every launch's time: the cost of the event pair itself
+    ftp_ktrace_row& row = rows[n++];
+    memset(&row, 0, sizeof(row));
+    strncpy(row.name, "__event_pair_overhead", sizeof(row.name) - 1);
+    row.launches = 1;
+    row.total_ms = g_trace.bracket_overhead_ms;
+  }
   *n_rows = n;
   bool ovf = g_trace.overflow;
   trace_release();

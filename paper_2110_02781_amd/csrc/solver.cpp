@@ -136,6 +136,35 @@ extern "C" int ftp_redistribution_plan(const int32_t* bounds_new, int n_new, con
   return FTP_OK;
 }
 
+// Worker list after failures (section "Fault Tolerance Mechanism"): the failed entries leave the list and the alive
+// ones keep their order.  With one failure that lowers every index behind it by one; with several, each failed
+// place is taken by the next alive worker behind it, one by one.  Worker 0 is the central node, which runs the
+// fault handler and therefore is never among the failed.
+extern "C" int ftp_renumber_workers(const int32_t* worker_ids, int n, const int32_t* failed, int n_failed, int32_t* new_ids,
+                                    int32_t* new_index, int* n_new) {
+  if (!worker_ids || !new_ids || !n_new || n < 1 || n_failed < 0 || (n_failed > 0 && !failed)) {
+    ftp_set_error("renumber_workers: NULL argument or empty worker list");
+    return FTP_ERR_ARG;
+  }
+  for (int f = 0; f < n_failed; ++f) {
+    if (failed[f] < 1 || failed[f] >= n) {
+      ftp_set_error("renumber_workers: failed index %d is not a worker index 1..%d (0 is the central node)", (int)failed[f], n - 1);
+      return FTP_ERR_ARG;
+    }
+    for (int q = 0; q < f; ++q)
+      if (failed[q] == failed[f]) { ftp_set_error("renumber_workers: index %d listed twice", (int)failed[f]); return FTP_ERR_ARG; }
+  }
+  int m = 0;
+  for (int i = 0; i < n; ++i) {
+    bool dead = false;
+    for (int f = 0; f < n_failed; ++f) dead = dead || failed[f] == i;
+    if (new_index) new_index[i] = dead ? -1 : m;
+    if (!dead) new_ids[m++] = worker_ids[i];
+  }
+  *n_new = m;
+  return FTP_OK;
+}
+
 // Re-partition schedule (section "Dynamic Model Partition"): first after 10 trained batches, then every 100.
 extern "C" int ftp_repartition_due(int64_t batches_done, int* due) {
   if (!due || batches_done < 0) { ftp_set_error("repartition_due: batches_done >= 0 and a non-NULL result required"); return FTP_ERR_ARG; }

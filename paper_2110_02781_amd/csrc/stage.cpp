@@ -15,6 +15,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -821,7 +822,10 @@ extern "C" int ftp_stage_aggregate_weights(ftp_stage* s, const int* slots, int n
 // gradient runs on the stage's side stream unless per-unit profiling is on.
 // mode: the whole layer, or from a dz that the caller formed (passed as dA)
 enum { BWD_FULL = 0, BWD_FROM_DZ = 1 };
-static bool stage_overlaps(const ftp_stage* s) { return s->prof == nullptr && s->max_act_bytes >= ((size_t)32 << 20); }
+// stage_forks: the stage is large enough to run weight gradients on its second stream (decides which kernels a
+// layer uses); stage_overlaps: it does so now (not while per-unit profiling needs everything on one stream)
+static bool stage_forks(const ftp_stage* s) { return s->max_act_bytes >= ((size_t)32 << 20); }
+static bool stage_overlaps(const ftp_stage* s) { return s->prof == nullptr && stage_forks(s); }
 
 static int join_side(ftp_stage* s, hipStream_t st);
 
@@ -893,7 +897,7 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
     if (sb.type == SUB_DIRECT) {
       // the scratch buffers are shared with the weight gradients: fine on one stream, but a stage that runs them on
       // the side stream keeps the direct kernel
-      if (conv_direct_dgrad_gemm_ok(g) && !stage_overlaps(s) && s->im2col) conv_direct_dgrad_gemm(s->dt, st, dz, w, g, s->im2col, s->ws, dIn);
+      if (conv_direct_dgrad_gemm_ok(g) && !stage_forks(s) && s->im2col) conv_direct_dgrad_gemm(s->dt, st, dz, w, g, s->im2col, s->ws, dIn);
       else conv_direct_dgrad(s->dt, st, dz, w, g, dIn);
     }
     else if (sb.type == SUB_PW) pw_dgrad(s->dt, st, dz, w, res, M, g.Cin, g.Cout, dIn);
@@ -973,7 +977,7 @@ extern "C" int ftp_stage_backward(ftp_stage* s, int slot, const void* dy_dev, vo
         if ((rc = sub_backward(s, sl, p, ns - 1, d, v.sub_out[i][ns - 2], v.sub_out[i][ns - 1], tmp, nullptr, W, st))) return rc;
         ConvGeom gd = ns == 3 ? u.subs[1].g : ConvGeom{};
         gd.N = s->batch;
-        if (ns == 3 && !stage_overlaps(s) && !s->prof && dw_bwd_small_ok(gd)) {
+        if (ns == 3 && !stage_forks(s) && dw_bwd_small_ok(gd)) {
           // short tensors: depthwise dgrad + wgrad and the expand layer's BatchNorm backward in one launch
           const Sub& s0 = u.subs[0];
           const Sub& s1 = u.subs[1];
@@ -1075,6 +1079,48 @@ extern "C" int ftp_stage_update(ftp_stage* s, const ftp_sgd* opt, void* stream) 
   return FTP_OK;
 }
 
+// ------------------------------------------------------------ loss without a stage, without allocation
+// Per-row losses of ftp_softmax_ce_static: partial results between its two kernels.  One copy per GPU, held until the
+// process ends; in host code the name is only a handle for hipGetSymbolAddress, the kernels get the address.
+enum { kStaticLossMaxBatch = FTP_STATIC_LOSS_MAX_BATCH, kStaticMaxDevices = 64 };
+static __device__ __align__(256) float scratch[kStaticLossMaxBatch];
+static float* g_scratch_ptr[kStaticMaxDevices];     // per device: the address of that GPU's copy
+static std::mutex g_scratch_mu;
+
+static int static_scratch(float** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kStaticMaxDevices) { ftp_set_error("softmax_ce_static: device ordinal %d not supported", dev); return FTP_ERR_UNSUPPORTED; }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    float* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));    // with `dev` current: this GPU's copy
+    if (!p) { ftp_set_error("softmax_ce_static: no device address for the scratch array"); return FTP_ERR_HIP; }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return FTP_OK;
+}
+
+extern "C" int ftp_softmax_ce_static(const void* logits_dev, const int32_t* labels_dev, int batch, int classes, ftp_dtype dtype,
+                                     void* dlogits_dev, float* loss_dev, void* stream) {
+  if (!logits_dev || !labels_dev || !dlogits_dev || !loss_dev) { ftp_set_error("softmax_ce_static: NULL argument"); return FTP_ERR_ARG; }
+  if (dtype != FTP_F32 && dtype != FTP_BF16) { ftp_set_error("softmax_ce_static: unknown dtype %d", (int)dtype); return FTP_ERR_ARG; }
+  if (batch < 1 || classes < 1) { ftp_set_error("softmax_ce_static: batch and classes must be positive"); return FTP_ERR_ARG; }
+  if (batch > kStaticLossMaxBatch) {
+    ftp_set_error("softmax_ce_static: batch %d is beyond the %d rows the static scratch array holds", batch, (int)kStaticLossMaxBatch);
+    return FTP_ERR_ARG;
+  }
+  float* rows = nullptr;
+  int rc = static_scratch(&rows);
+  if (rc) return rc;
+  // every row < batch is written before it is read and nothing beyond is read: nothing has to start at zero
+  softmax_ce((int)dtype, (hipStream_t)stream, logits_dev, labels_dev, batch, classes, rows, dlogits_dev, loss_dev);
+  HIP_TRY(hipGetLastError());
+  if (const char* why = launch_plan_failure_take()) { ftp_set_error("%s", why); return FTP_ERR_UNSUPPORTED; }
+  return FTP_OK;
+}
+
 // ------------------------------------------------------------ profile_layers
 __global__ void synth_fill_k(float* p, size_t n, uint32_t salt, float amp) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
@@ -1158,8 +1204,29 @@ extern "C" int ftp_profile_layers(const ftp_model* m, int batch, int reps, doubl
       acc[i] += ((double)f + (double)b) * 1e6;
     }
   }
+  // The per-unit events need every unit to begin and end on the caller's stream, so a stage that normally runs its
+  // weight gradients on a second stream was just timed without that overlap.  The per-unit times keep their
+  // proportions and are scaled so that they add up to what a batch costs under the plan training really runs
+  // (forward + loss + backward, timed like ftp_stage_timing does): the capacity equation divides a worker's
+  // measured batch time by this sum, and the same device then comes out at capacity 1.
+  double sum_units = 0.0, whole = 0.0;
+  for (int i = 0; i < L; ++i) sum_units += acc[i] / reps;
+  for (int r = 0; r < reps + 1; ++r) {
+    PROF_TRY(hipEventRecord(ev.f0[0], st));
+    rc = ftp_stage_forward(s, 0, x, nullptr, st);
+    if (!rc && has_loss) rc = ftp_stage_loss(s, 0, labels, loss, st);
+    if (!rc) rc = ftp_stage_backward(s, 0, has_loss ? nullptr : dy, nullptr, st);
+    if (rc) { cleanup(); return rc; }
+    PROF_TRY(hipEventRecord(ev.f1[0], st));
+    PROF_TRY(hipStreamSynchronize(st));
+    float ms = 0.f;
+    PROF_TRY(hipEventElapsedTime(&ms, ev.f0[0], ev.f1[0]));
+    if (r > 0) whole += (double)ms * 1e6;   // first run discarded: the other plan's kernels load their code
+  }
+  whole /= reps;
+  const double k_plan = sum_units > 0.0 && whole > 0.0 ? whole / sum_units : 1.0;
   for (int i = 0; i < L; ++i) {
-    double t = std::floor(acc[i] / reps + 0.5);
+    double t = std::floor(acc[i] / reps * k_plan + 0.5);
     t_ns[i] = t < 1.0 ? 1.0 : t;
     const UnitInfo& u = m->units[i];
     out_bytes[i] = (int64_t)((size_t)batch * u.outH * u.outW * u.outC * es);

@@ -131,6 +131,33 @@ def test_redistribution_plan_rejects_bad_arguments(P):
         P.redistribution_plan([0, 4, 8], [0, 4, 8], None, 2, 0)          # index out of range
 
 
+def test_renumber_workers_matches_oracle_and_the_plan(P):
+    """Section "Fault Tolerance Mechanism": the worker list after failures, through the C ABI, against the oracle's
+    table and random cases; and the index that ftp_redistribution_plan names for a unit of a failed stage is, in the
+    renumbered list, the worker that followed the failed one."""
+    from oracle.partition import renumber_workers as oracle_renumber
+    assert P.renumber_workers([10, 11, 12, 13], [2]) == ([10, 11, 13], [0, 1, -1, 2])
+    assert P.renumber_workers([10, 11, 12, 13, 14], [1, 3]) == ([10, 12, 14], [0, -1, 1, -1, 2])
+    assert P.renumber_workers([7, 8], []) == ([7, 8], [0, 1])
+    for t in range(200):
+        n = 2 + t % 9
+        ids = [int(v) for v in synth.integers(t, "ids", (n,), 100, 999)]
+        k = t % n
+        failed = sorted(set(1 + int(v) % (n - 1) for v in synth.integers(t, "failed", (k,), 0, 1000))) if k else []
+        new_ids, new_index = P.renumber_workers(ids, failed)
+        assert new_ids == oracle_renumber(ids, failed)
+        assert [i for i, v in enumerate(new_index) if v < 0] == failed
+        assert [new_ids[v] for v in new_index if v >= 0] == [w for i, w in enumerate(ids) if i not in failed]
+    # one failure in the middle of a 4-stage pipeline: worker 1 asks for a unit of failed stage 2 -> index 2, now worker 13
+    cur, new = [0, 3, 6, 9, 12], [0, 4, 8, 12]
+    m_need, _ = P.redistribution_plan(new, cur, 2, 1, 1)
+    ids, _ = P.renumber_workers([10, 11, 12, 13], [2])
+    assert m_need == {2: [6, 7]} and ids[2] == 13
+    for bad in ([0], [4], [1, 1], [-1]):
+        with pytest.raises(RuntimeError):
+            P.renumber_workers([10, 11, 12, 13], bad)
+
+
 def test_repartition_schedule_and_capacities_match_oracle(P):
     from oracle.partition import repartition_due, repartition_capacities
     assert [b for b in range(0, 450) if P.repartition_due(b)] == [b for b in range(0, 450) if repartition_due(b)] == [10, 110, 210, 310, 410]
