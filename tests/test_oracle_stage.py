@@ -259,6 +259,100 @@ def test_bf16_storage_mode_stays_close_to_exact_and_rounds_stored_tensors():
     assert np.abs(out[0][2] - out[1][2]).max() < 0.5 * np.abs(out[0][2]).max()
 
 
+class _StoreBF16(torch.autograd.Function):
+    """A tensor stored in bfloat16: the value is rounded on the way forward and its gradient on the way back
+    (the library's own conversion, round to nearest even, does both roundings)."""
+    @staticmethod
+    def forward(ctx, t):
+        return t.to(torch.bfloat16).to(t.dtype)
+
+    @staticmethod
+    def backward(ctx, g):
+        return g.to(torch.bfloat16).to(g.dtype)
+
+
+class _WorkingCopyBF16(torch.autograd.Function):
+    """The bfloat16 working copy of a weight: rounded forward; the weight gradient stays in full precision."""
+    @staticmethod
+    def forward(ctx, t):
+        return t.to(torch.bfloat16).to(t.dtype)
+
+    @staticmethod
+    def backward(ctx, g):
+        return g
+
+
+def torch_forward_bf16_storage(units, params, x, labels):
+    """The network of torch_forward with every tensor that mixed-precision training stores in bfloat16 passed
+    through _StoreBF16: the working copy of conv / FC weights, every convolution output, every BatchNorm +
+    activation output, block outputs, pooled features, logits; BatchNorm statistics, gamma, beta and the loss stay
+    in float64."""
+    R, Rw = _StoreBF16.apply, _WorkingCopyBF16.apply
+
+    def cba(h, w, g, b, stride, pad, groups, act):
+        z = R(F.conv2d(h, Rw(w).permute(0, 3, 1, 2), None, stride=stride, padding=pad, groups=groups))
+        y = F.batch_norm(z, None, None, g, b, True, 0.1, L.BN_EPS)
+        return R(F.relu6(y) if act == L.ACT_RELU6 else F.relu(y) if act == L.ACT_RELU else y)
+    h = x
+    for u, P in zip(units, params):
+        if u.kind == 'conv':
+            h = cba(h, P[0], P[1], P[2], u.stride, (u.pad_h, u.pad_w), 1, u.act)
+        elif u.kind == 'invres':
+            inp, k = h, 0
+            ce = u.cin * u.expand
+            if u.expand != 1:
+                h = cba(h, P[0], P[1], P[2], 1, 0, 1, L.ACT_RELU6); k = 3
+            h = cba(h, P[k], P[k + 1], P[k + 2], u.stride, 1, ce, L.ACT_RELU6)
+            h = cba(h, P[k + 3], P[k + 4], P[k + 5], 1, 0, 1, L.ACT_NONE)
+            if u.stride == 1 and u.cin == u.cout:
+                h = h + inp
+            h = R(h)
+        elif u.kind == 'gap':
+            h = R(h.mean(dim=(2, 3)))
+        elif u.kind == 'fc':
+            h = R(F.linear(h, Rw(P[0]), P[1]))
+        elif u.kind == 'loss':
+            return F.cross_entropy(h, labels), h
+    return h, h
+
+
+@pytest.mark.parametrize("name", ["cnn1d", "small_mbv2"])
+def test_bf16_storage_mode_rounds_exactly_at_the_stated_points(name):
+    """Pin of the storage='bf16' oracle: the same step from library operators and autograd in float64, with the
+    library's own bfloat16 conversion inserted at the storage points (forward value and backward gradient), must give
+    the same logits, loss, input gradient and weight gradients to float64 accuracy.  A rounding that the oracle
+    misses, adds or puts elsewhere shows up at the 1e-3 level."""
+    from oracle.stage import bf16_round
+    if name == "cnn1d":
+        units, in_shape, batch, classes = M.cnn1d(), (1, 128, 9), 8, 6
+    else:
+        units, in_shape, batch, classes = small_mbv2(), (9, 9, 3), 4, 10
+    seed = 23
+    x = bf16_round(synth.normal(seed, "x", (batch,) + in_shape))
+    labels = synth.labels(seed, "labels", batch, classes)
+    st = Stage(units, in_shape, 0, len(units), 1, storage='bf16')
+    P = M.init_params(units, seed)
+    for i in range(len(units)):
+        st.set_params(i, [p.astype(np.float32).astype(np.float64) for p in P[i]])
+    logits = st.forward(0, x)
+    loss = st.loss(0, labels)
+    dx = st.backward(0)
+    tparams = [[torch.from_numpy(p.copy()).requires_grad_() for p in st.params[i]] for i in range(len(units))]
+    xt = torch.from_numpy(x.transpose(0, 3, 1, 2).copy()).requires_grad_()
+    tl, tlogits = torch_forward_bf16_storage(units, tparams, xt, torch.from_numpy(labels).long())
+    tl.backward()
+    np.testing.assert_array_equal(logits.reshape(batch, -1), tlogits.detach().numpy())       # stored values: identical
+    assert abs(loss - tl.item()) < 1e-12 * max(1, abs(loss))
+    # the gradient that reaches the input is a stored tensor too: the oracle returns it rounded
+    want_dx = bf16_round(xt.grad.numpy().transpose(0, 2, 3, 1))
+    flips = (dx != want_dx).mean()
+    assert flips <= 1e-3 and np.abs(dx - want_dx).max() <= 2.0 ** -7 * np.abs(want_dx).max(), flips
+    for i in range(len(units)):
+        for k, p in enumerate(tparams[i]):
+            g, ref = st.grads[i][k], p.grad.numpy()
+            assert np.abs(g - ref).max() <= 1e-9 * max(np.abs(ref).max(), 1e-30) + 1e-14, (i, k, np.abs(g - ref).max(), np.abs(ref).max())
+
+
 def test_tie_breaks_only_act_inside_the_band():
     """Decisions handed to backward are adopted only within the rounding band around a
     kink; elsewhere the oracle keeps its own and counts the disagreement."""
