@@ -1116,6 +1116,232 @@ __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View
   }
 }
 
+// ---- depthwise weight gradient without LDS staging: a lane walks down the image ------------------------
+// g_w[c][ky][kx] = sum over output pixels of dz[ho][wo][c] * in[ho*S+ky-1][wo*S+kx-1][c].  A lane owns 4 channels and a
+// strip of R output columns of one image (R = 2 at stride 1, 1 at stride 2) and walks it from the top row down with
+// the input window under the current output pixels in registers ((R-1)*S+3 columns x 3 rows, already through the view,
+// as float): per step it brings in S new input rows and R new dz vectors from global memory (requested three steps
+// ahead) and does 9 * R four-wide FMAs.  Every input element is converted once per strip it lies under, there is no
+// barrier and no LDS traffic inside the walk, and the 36 sums stay in registers over all strips of the lane.
+// The lanes of a wavefront (and the wavefronts of a block) take neighbouring strips, so what they request in one
+// step is one contiguous stretch of an image row (walking ALONG the rows instead put every lane on a row of its own:
+// thousands of 256-byte streams, which the memory served at 2 TB/s).
+// The 4-channel groups of a layer are cut into slabs whose widths are powers of two (144 channels = 36 groups =
+// 32 + 4), so that gw groups x sw strips fill the 64 lanes of a wavefront exactly; a block's four wavefronts
+// take 4 * sw strips of one slab per pass, and the block leaves one partial ws[p][9][C] (its slab's channels).
+struct DwMarchSlab { int ch0, gw, sw; };
+enum { kDwMarchSlabs = 16, kDwMarchBlocks = 2048, kDwMarchCpl = 2 };   // slabs a layer may need, blocks in all, channels per lane
+struct DwMarchArgs {
+  const void* dz;
+  View in;
+  float* ws;
+  int Hin, Win, Hout, Wout, C;
+  int ncb, nseg, seglen;    // strips side by side, row segments per image (a strip is one segment high), rows per segment
+  int nstrips;              // N * nseg * ncb
+  int P, nslab;             // blocks (= partials) per slab
+  DwMarchSlab slab[kDwMarchSlabs];
+};
+
+template <int V> struct IntC { static constexpr int value = V; };
+
+// two channels of one pixel as loaded
+template <typename T> struct Raw2;
+template <> struct Raw2<float> { float2 v; };
+template <> struct Raw2<bf16_t> { uint32_t v; };
+__device__ __forceinline__ void raw2_load(Raw2<float>& r, const float* p) { r.v = *reinterpret_cast<const float2*>(p); }
+__device__ __forceinline__ void raw2_load(Raw2<bf16_t>& r, const bf16_t* p) { r.v = *reinterpret_cast<const uint32_t*>(p); }
+__device__ __forceinline__ float2 raw2_unpack(const Raw2<float>& r) { return r.v; }
+__device__ __forceinline__ float2 raw2_unpack(const Raw2<bf16_t>& r) {
+  return make_float2(__uint_as_float(r.v << 16), __uint_as_float(r.v & 0xffff0000u));
+}
+// the pair as it reads back after being stored in T (one conversion instruction for both halves)
+__device__ __forceinline__ float2 round2(float2 v, float) { return v; }
+__device__ __forceinline__ float2 round2(float2 v, bf16_t) {
+  const uint32_t u = f32x2_to_bf16x2(v.x, v.y);
+  return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xffff0000u));
+}
+
+template <typename T, int S, bool VIEW>
+__global__ __launch_bounds__(256) void dw_wgrad_march_k(DwMarchArgs a) {
+  constexpr int R = S == 1 ? 2 : 1;
+  constexpr int NCOL = (R - 1) * S + 3;
+  __shared__ float2 red[4][9][64];
+  const int lb = xcd_logical_block();
+  const int p = lb / a.nslab, si = lb - p * a.nslab;             // the slabs of a pass run side by side on one XCD
+  const DwMarchSlab sl = a.slab[si];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int g = lane & (sl.gw - 1), s_l = lane / sl.gw;
+  const int c = sl.ch0 + kDwMarchCpl * g;
+  const T* src = reinterpret_cast<const T*>(a.in.z);
+  const T* dzp = reinterpret_cast<const T*>(a.dz);
+  constexpr bool view = VIEW;
+  // The walk must be free of branches: only then does the compiler count the loads in flight and wait for the oldest
+  // register set alone (with a branch in the loop it waits for all of them).  The heights therefore live in vector
+  // registers (a comparison with them is a lane mask, never a jump), and every walk takes a multiple of three steps;
+  // the steps behind the last row see dz = 0.
+  int hinL = a.Hin, houtL = a.Hout;
+  asm volatile("" : "+v"(hinL), "+v"(houtL));
+  float2 sc = make_float2(1.f, 1.f), sh = make_float2(0.f, 0.f);
+  if (view) {
+    sc = *reinterpret_cast<const float2*>(a.in.scale + c);
+    sh = *reinterpret_cast<const float2*>(a.in.shift + c);
+  }
+  const float lo = act_lo(a.in.act), hi = act_hi(a.in.act);
+  const float2 zero2 = make_float2(0.f, 0.f);
+  float2 acc[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) acc[t] = zero2;
+  const unsigned in_row = __umul24(a.Win, a.C), dz_row = __umul24(a.Wout, a.C);
+
+  const int spb = 4 * sl.sw;
+  for (int sidx = p * spb + wave * sl.sw + s_l; sidx < a.nstrips; sidx += a.P * spb) {
+    const int ns = sidx / a.ncb, cb = sidx - ns * a.ncb;
+    const int n = ns / a.nseg, h_beg = (ns - n * a.nseg) * a.seglen;       // a multiple of three: the phases line up
+    const int wo0 = cb * R, wi0 = wo0 * S - 1;
+    int hendL = h_beg + a.seglen < a.Hout ? h_beg + a.seglen : a.Hout;
+    asm volatile("" : "+v"(hendL));
+    const T* img = src + (size_t)n * a.Hin * a.Win * a.C + c;
+    const T* dimg = dzp + (size_t)n * a.Hout * a.Wout * a.C + c;
+    unsigned coff[NCOL], doff[R];
+    bool cok[NCOL], dok[R];
+#pragma unroll
+    for (int r = 0; r < NCOL; ++r) {
+      cok[r] = wi0 + r >= 0 && wi0 + r < a.Win;
+      coff[r] = cok[r] ? __umul24(wi0 + r, a.C) : 0u;
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      dok[r] = wo0 + r < a.Wout;
+      doff[r] = dok[r] ? __umul24(wo0 + r, a.C) : 0u;
+    }
+    float2 win[NCOL][3];
+#pragma unroll
+    for (int r = 0; r < NCOL; ++r)
+#pragma unroll
+      for (int y = 0; y < 3; ++y) win[r][y] = zero2;
+    // Three steps' loads are in flight (one register set per phase): a lane has nothing else to hide a memory round
+    // trip behind, and one step's arithmetic is a fraction of it.
+    Raw2<T> rin[3][NCOL][S], rdz[3][R];
+    // what output row ho brings in: its S new input rows (y < Hin, else nothing is there) under every column of the
+    // strip, and its dz
+    auto request_row = [&](auto BUF, const int q, const int y) __attribute__((always_inline)) {
+      constexpr int buf = decltype(BUF)::value;
+      const unsigned ro = (unsigned)y < (unsigned)hinL ? (unsigned)y * in_row : 0u;
+#pragma unroll
+      for (int r = 0; r < NCOL; ++r) raw2_load(rin[buf][r][q], img + ro + coff[r]);
+    };
+    auto request = [&](auto BUF, const int ho) __attribute__((always_inline)) {
+      constexpr int buf = decltype(BUF)::value;
+      const int y0 = S == 1 ? ho + 1 : 2 * ho;
+#pragma unroll
+      for (int q = 0; q < S; ++q) request_row(BUF, q, y0 + q);
+      const unsigned hr = ho < houtL ? (unsigned)ho * dz_row : 0u;
+#pragma unroll
+      for (int r = 0; r < R; ++r) raw2_load(rdz[buf][r], dimg + hr + doff[r]);
+    };
+    auto bring = [&](auto BUF, auto SLOT, const int q, const int y) __attribute__((always_inline)) {
+      constexpr int buf = decltype(BUF)::value;
+      constexpr int slot = decltype(SLOT)::value;
+      const bool yok = (unsigned)y < (unsigned)hinL;
+#pragma unroll
+      for (int r = 0; r < NCOL; ++r) {
+        float2 v = raw2_unpack(rin[buf][r][q]);
+        if (view) v = round2(make_float2(clamp_act(fmaf(v.x, sc.x, sh.x), lo, hi), clamp_act(fmaf(v.y, sc.y, sh.y), lo, hi)), T());
+        win[r][slot] = (yok && cok[r]) ? v : zero2;       // padding is zero AFTER the view
+      }
+    };
+    // one output row: phase = ho % 3 fixes which window slot holds which input row (row y sits in slot y % 3)
+    auto step = [&](auto PH, const int ho) __attribute__((always_inline)) {
+      constexpr int ph = decltype(PH)::value;
+      constexpr int base = (S * ph + 2) % 3;              // slot of input row ho*S - 1
+      if (S == 1) {
+        bring(PH, IntC<(ph + 1) % 3>(), 0, ho + 1);
+      } else {
+        bring(PH, IntC<(2 * ph) % 3>(), 0, 2 * ho);
+        bring(PH, IntC<(2 * ph + 1) % 3>(), 1, 2 * ho + 1);
+      }
+      float2 dv[R];
+#pragma unroll
+      for (int r = 0; r < R; ++r) dv[r] = (dok[r] && ho < hendL) ? raw2_unpack(rdz[ph][r]) : zero2;
+      request(PH, ho + 3);                                 // this register set is free again: the step three ahead
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+          for (int kx = 0; kx < 3; ++kx) {
+            const float2 w2 = win[r * S + kx][(base + ky) % 3];
+            acc[ky * 3 + kx].x = fmaf(dv[r].x, w2.x, acc[ky * 3 + kx].x);
+            acc[ky * 3 + kx].y = fmaf(dv[r].y, w2.y, acc[ky * 3 + kx].y);
+          }
+    };
+    // the input rows above the segment's first output row that are under it already: row h_beg*S - 1 (slot 2), and
+    // at stride 1 row h_beg as well (slot 0)
+    request_row(IntC<0>(), 0, h_beg * S - 1);
+    if (S == 1) request_row(IntC<1>(), 0, h_beg);
+    bring(IntC<0>(), IntC<2>(), 0, h_beg * S - 1);
+    if (S == 1) bring(IntC<1>(), IntC<0>(), 0, h_beg);
+    request(IntC<0>(), h_beg);
+    request(IntC<1>(), h_beg + 1);
+    request(IntC<2>(), h_beg + 2);
+    for (int i = 0; i < a.seglen; i += 3) {
+      step(IntC<0>(), h_beg + i);
+      step(IntC<1>(), h_beg + i + 1);
+      step(IntC<2>(), h_beg + i + 2);
+    }
+  }
+
+  // the block's partial: lanes of one channel group over strips and wavefronts, in a fixed order
+#pragma unroll
+  for (int t = 0; t < 9; ++t) red[wave][t][lane] = acc[t];
+  __syncthreads();
+  for (int i = threadIdx.x; i < 9 * sl.gw; i += 256) {
+    const int t = i / sl.gw, gg = i - t * sl.gw;
+    float2 tot = zero2;
+    for (int w = 0; w < 4; ++w)
+      for (int q = 0; q < sl.sw; ++q) {
+        const float2 v = red[w][t][q * sl.gw + gg];
+        tot.x += v.x; tot.y += v.y;
+      }
+    *reinterpret_cast<float2*>(a.ws + ((size_t)p * 9 + t) * a.C + sl.ch0 + kDwMarchCpl * gg) = tot;
+  }
+}
+
+// slabs (powers of two, widest first) and the number of blocks; false if the layer needs more slabs than the kernel takes
+static bool dw_march_plan(const ConvGeom& g, DwMarchArgs* a) {
+  int G = g.Cout / kDwMarchCpl, ch = 0, n = 0;
+  while (G > 0) {
+    int gw = 64;
+    while (gw > G) gw >>= 1;
+    if (n == kDwMarchSlabs) return false;
+    a->slab[n++] = DwMarchSlab{ch, gw, 64 / gw};
+    ch += kDwMarchCpl * gw; G -= gw;
+  }
+  a->nslab = n;
+  const int R = g.stride == 1 ? 2 : 1;
+  a->ncb = (g.Wout + R - 1) / R;
+  // Row segments: a lane's walk is one long chain of dependent steps, so a layer with few strips is cut across its
+  // rows until about 2048 wavefronts' worth of lanes exist (cutting further only added partial sums: measured); a segment is a
+  // multiple of three rows (the window's phases) and at least 12 rows (its first rows are read twice).
+  {
+    const double waves = (double)g.N * a->ncb * (g.Cout / kDwMarchCpl) / 64.0;
+    int want = (int)(2048.0 / (waves > 1.0 ? waves : 1.0) + 0.999);
+    if (want < 1) want = 1;
+    int len = (g.Hout + want - 1) / want;
+    if (len < 12) len = 12;
+    len = (len + 2) / 3 * 3;
+    a->seglen = len;
+    a->nseg = (g.Hout + len - 1) / len;
+  }
+  a->nstrips = g.N * a->nseg * a->ncb;
+  const int per_pass = 4 * a->slab[0].sw;                 // the widest slab takes the fewest strips per pass
+  int P = (a->nstrips + per_pass - 1) / per_pass;
+  const int cap = kDwMarchBlocks / n > 1 ? kDwMarchBlocks / n : 1;
+  a->P = P < 1 ? 1 : P > cap ? cap : P;
+  a->Hin = g.Hin; a->Win = g.Win; a->Hout = g.Hout; a->Wout = g.Wout; a->C = g.Cout;
+  return g.Cout % 8 == 0 && (g.stride == 1 || g.stride == 2);
+}
+
 static DwPlan dw_wgrad_plan(const ConvGeom& g, int es, size_t* lds) {
   const int s = g.stride;
   DwPlan d = dw_plan(g.Cout, es, s == 2, g.Hout, g.Wout);
@@ -1144,11 +1370,33 @@ size_t dw_wgrad_ws(const ConvGeom& g) {
   size_t lds;
   DwPlan d = dw_wgrad_plan(g, 4, &lds);          // the float plan has at least as many slabs, the bound holds for both
   DwPlan e = dw_wgrad_plan(g, 2, &lds);
-  return (size_t)(d.nblocks > e.nblocks ? d.nblocks : e.nblocks) * 9 * g.Cout;
+  size_t n = (size_t)(d.nblocks > e.nblocks ? d.nblocks : e.nblocks);
+  DwMarchArgs m{};
+  if (dw_march_plan(g, &m) && (size_t)m.P > n) n = m.P;
+  return n * 9 * g.Cout;
 }
 
 void dw_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, float* ws, float* g_w) {
   const int es = dt == 0 ? 4 : 2;
+  DwMarchArgs m{};
+  if (dw_march_plan(g, &m)) {
+    m.dz = dz; m.in = View{in.z, in.scale, in.shift, in.act}; m.ws = ws;
+    {
+      KScope ks(st, "dw_wgrad", ((double)g.N * g.Hin * g.Win * g.Cout + (double)g.N * g.Hout * g.Wout * g.Cout) * es + (double)m.P * 9 * g.Cout * 4,
+                18.0 * g.N * g.Hout * g.Wout * g.Cout, (long)g.N * g.Hout * g.Wout, g.Cout, g.stride);
+      const unsigned grid = (unsigned)m.P * m.nslab;
+      const bool vw = in.scale != nullptr;
+      if (g.stride == 1) {
+        if (vw) { FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_wgrad_march_k<T, 1, true>), dim3(grid), dim3(256), 0, st, m)); }
+        else { FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_wgrad_march_k<T, 1, false>), dim3(grid), dim3(256), 0, st, m)); }
+      } else {
+        if (vw) { FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_wgrad_march_k<T, 2, true>), dim3(grid), dim3(256), 0, st, m)); }
+        else { FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_wgrad_march_k<T, 2, false>), dim3(grid), dim3(256), 0, st, m)); }
+      }
+    }
+    reduce_partials(st, ws, m.P, (size_t)9 * g.Cout, g.Cout, 1, 9, g_w);
+    return;
+  }
   size_t lds;
   DwPlan d = dw_wgrad_plan(g, es, &lds);
   if (!dw_check_plan(d, g.stride == 2 ? 1 : kDwSegs)) return;     // also: the runs of a tile whose dz a thread holds
