@@ -17,6 +17,7 @@ SOURCES = [
     ("k_elem.hip", ["-x", "hip"]),
     ("k_conv.hip", ["-x", "hip"]),
     ("k_gemm.hip", ["-x", "hip"]),
+    ("k_fused.hip", ["-x", "hip"]),
     ("stage.cpp", ["-x", "hip"]),
     ("ktrace.cpp", ["-x", "hip"]),
     ("solver.cpp", ["-x", "c++", "-ffp-contract=off"]),

@@ -175,6 +175,14 @@ size_t pw_wgrad_ws(size_t M, int K, int N);
 void pw_wgrad(int dt, hipStream_t st, const void* dz, HView a, size_t M, int K, int N, float* ws,
               float* g_w, int K_out = -1);
 
+// Narrow-to-wide pointwise layer (K inputs, N >= 2K outputs, bfloat16, input stored activated), whole backward behind
+// the BatchNorm reductions in one pass: dz = k1*dA*act'(out) + k2*z + k3 formed per row tile on chip,
+// dIn = dz * W (+ res), g_w += dz^T * A.  coef: [3][N] from bn_bwd_finalize.  ws: pw_bwd_fused_ws(M, K, N) floats.
+int pw_bwd_fused_ok(int dt, size_t M, int K, int N, HView a);
+size_t pw_bwd_fused_ws(size_t M, int K, int N);
+void pw_bwd_fused(hipStream_t st, const void* dA, HView out, const float* coef, const void* w, const void* a_in,
+                  const void* res, size_t M, int K, int N, float* ws, float* g_w, void* dIn);
+
 // wgrad (g_w +=) then dgrad (dA =) of one layer on one stream; one launch for short problems
 void pw_bwd(int dt, hipStream_t st, const void* dz, const void* w, const void* res, HView a, size_t M, int K, int N,
             float* ws, float* g_w, void* dA);

@@ -262,6 +262,10 @@ struct ftp_stage {
   // runs there, next to whatever the side stream still has queued, instead of behind it.
   float* ws_tail = nullptr;
   size_t ws_tail_floats = 0;
+  // partial sums of the one-pass backward of the expand layers: it runs on the caller's stream while the side stream
+  // may be using ws, so it has a workspace of its own
+  float* ws_fused = nullptr;
+  size_t ws_fused_floats = 0;
   int n_direct = 0;           // sublayers that use the patch-matrix buffer
   void* im2col = nullptr;     // patch matrix for the weight gradient of small dense convolutions
   size_t im2col_elems = 0;
@@ -293,7 +297,7 @@ static void stage_free(ftp_stage* s) {
     if (s->ev_fork[i]) (void)hipEventDestroy(s->ev_fork[i]);
     if (s->ev_join[i]) (void)hipEventDestroy(s->ev_join[i]);
   }
-  dfree(s->bn_part); dfree(s->coef); dfree(s->ws); dfree(s->ws_tail); dfree(s->row_loss); dfree(s->im2col);
+  dfree(s->bn_part); dfree(s->coef); dfree(s->ws); dfree(s->ws_tail); dfree(s->ws_fused); dfree(s->row_loss); dfree(s->im2col);
   if (s->timer) {
     if (s->timer->created)
       for (auto& q : s->timer->ev)
@@ -357,6 +361,8 @@ extern "C" int ftp_stage_create_ex(const ftp_model* m, int a, int b, int batch, 
       size_t need = sb.type == SUB_DIRECT ? conv_direct_wgrad_ws(g) : sb.type == SUB_DW ? dw_wgrad_ws(g) : pw_wgrad_ws(M, g.Cin, g.Cout);
       if (need > ws_floats) ws_floats = need;
       if (i == a && &sb == &u.subs[0]) s->ws_tail_floats = need;
+      if (sb.type == SUB_PW && m->dtype == FTP_BF16 && pw_bwd_fused_ws(M, g.Cin, g.Cout) > s->ws_fused_floats)
+        s->ws_fused_floats = pw_bwd_fused_ws(M, g.Cin, g.Cout);
       if (sb.type == SUB_DIRECT) ++s->n_direct;
       if (sb.type == SUB_DIRECT && conv_direct_gemm_ok(g) && conv_direct_gemm_wpad_elems(g) > ws_floats)
         ws_floats = conv_direct_gemm_wpad_elems(g);      // padded weight copy of the GEMM forward (at most 4 bytes each)
@@ -416,6 +422,7 @@ extern "C" int ftp_stage_create_ex(const ftp_model* m, int a, int b, int batch, 
   if ((rc = dev_alloc(&s->bn_part, (size_t)kBnPartials * 2 * max_c * 4)) || (rc = dev_alloc(&s->coef, (size_t)3 * max_c * 4)) ||
       (rc = dev_alloc(&s->ws, ws_floats * 4)) || (rc = dev_alloc(&s->row_loss, (size_t)batch * 4))) { stage_free(s); return rc; }
   if (s->im2col_elems && (rc = dev_alloc(&s->im2col, s->im2col_elems * s->es))) { stage_free(s); return rc; }
+  if (s->ws_fused_floats && (rc = dev_alloc(&s->ws_fused, s->ws_fused_floats * 4))) { stage_free(s); return rc; }
   if (s->max_act_bytes >= ((size_t)32 << 20) && s->ws_tail_floats && s->n_direct <= 1 &&
       (rc = dev_alloc(&s->ws_tail, s->ws_tail_floats * 4))) { stage_free(s); return rc; }
 
@@ -842,6 +849,18 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
   const bool overlap = mode == BWD_FULL && stage_overlaps(s) && M * (size_t)C >= ((size_t)1 << 20);
   int b = 0, rc_join = 0;
   void* dz = const_cast<void*>(dA);
+  // An expand layer in bfloat16: behind the BatchNorm reductions the rest of its backward (dz, data gradient,
+  // weight gradient) is one pass on this stream; dz never reaches memory.
+  if (mode == BWD_FULL && sb.type == SUB_PW && dIn && s->ws_fused && !bn_bwd_small_ok(M, C) &&
+      pw_bwd_fused_ok(s->dt, M, g.Cin, g.Cout, in) && pw_bwd_fused_ws(M, g.Cin, g.Cout) <= s->ws_fused_floats) {
+    int P = 0;
+    bn_bwd_reduce(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->bn_part, &P);
+    bn_bwd_finalize(st, s->bn_part, P, M, C, W.w32 + p.p_off + sb.gamma_off, stt, stt + C, s->grads + p.p_off + sb.gamma_off,
+                    s->grads + p.p_off + sb.beta_off, s->coef);
+    pw_bwd_fused(st, dA, out, s->coef, conv_w(s, W, p.p_off + sb.w_off), in.z, res, M, g.Cin, g.Cout, s->ws_fused,
+                 s->grads + p.p_off + sb.w_off, dIn);
+    return FTP_OK;
+  }
   if (mode != BWD_FROM_DZ) {
     b = (int)(s->n_sub_bwd++ & 1u);
     dz = s->gbuf[b ? 4 : 2];
