@@ -315,3 +315,172 @@ void pw_bwd_fused(hipStream_t st, const void* dA, HView out, const float* coef, 
 }
 
 }  // namespace ftp
+
+// ---- weight gradient of a pointwise layer, bfloat16, operands staged as they lie in memory --------------------
+// g_w[n][k] += sum_m dZ[m][n] * A'[m][k]: both MFMA operands need the rows m as the contiguous index of a lane's
+// fragment while dZ and A hold channels contiguously.  A block stages 64-row chunks of a 128-column strip of dZ and a
+// 64-column strip of A (through the view) into LDS with plain 16-byte copies and reads them back with the LDS
+// transpose read (lds_frag_tr): no repacking pass (the layer-by-layer kernel spends most of its instructions
+// interleaving row pairs).  The rows are split over blocks; every block leaves one fp32 partial of its
+// 128 x 64 tile, summed by reduce_partials in a fixed order.
+namespace ftp {
+
+enum { kWgN = 128, kWgK = 64, kWgRows = 64 };
+
+struct WgTrArgs {
+  const bf16_t* dz;     // [M][N]
+  const bf16_t* a;      // [M][K]
+  const float* scale;   // view of A (nullptr: stored activated)
+  const float* shift;
+  int act;
+  float* ws;            // [S][N][K]
+  size_t M, mchunk;     // rows per split (a multiple of 64)
+  int K, N, itiles, jtiles;
+};
+
+template <bool VIEW>
+__global__ __launch_bounds__(256) void pw_wgrad_tr_k(WgTrArgs p) {
+  constexpr int LDN = kWgN + 8, LDK = kWgK + 8;
+  __shared__ __attribute__((aligned(16))) bf16_t sZ[2][kWgRows * LDN];
+  __shared__ __attribute__((aligned(16))) bf16_t sA[2][kWgRows * LDK];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l16 = lane & 15, G = lane >> 4;
+  const int lb = xcd_logical_block();
+  const int jt = lb % p.jtiles, rest = lb / p.jtiles, it = rest % p.itiles, split = rest / p.itiles;
+  const int n0 = it * kWgN, k0 = jt * kWgK;
+  const size_t mb = (size_t)split * p.mchunk, me = mb + p.mchunk < p.M ? mb + p.mchunk : p.M;
+  const int N = p.N, K = p.K;
+
+  // staging map: dZ chunk = 64 rows x 16 vectors (4 per thread), A chunk = 64 rows x 8 vectors (2 per thread)
+  const int zc = (tid & 15) * 8, zr = tid >> 4;         // + 16 rows per pass
+  const int ac = (tid & 7) * 8, ar = tid >> 3;          // + 32 rows per pass
+  const bool zc_ok = n0 + zc < N, ac_ok = k0 + ac < K;
+  float sc[8], sh[8];
+  if (VIEW) { load8(p.scale + (ac_ok ? k0 + ac : 0), sc); load8(p.shift + (ac_ok ? k0 + ac : 0), sh); }
+  const float lo = act_lo(p.act), hi = act_hi(p.act);
+
+  Raw<bf16_t> rz[4], ra[2];
+  auto fetch = [&](const size_t m0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const size_t m = m0 + zr + 16 * q;
+      raw_load(rz[q], p.dz + ((zc_ok && m < me) ? m * N + n0 + zc : 0));
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const size_t m = m0 + ar + 32 * q;
+      raw_load(ra[q], p.a + ((ac_ok && m < me) ? m * K + k0 + ac : 0));
+    }
+  };
+  auto commit = [&](const int buf, const size_t m0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const size_t m = m0 + zr + 16 * q;
+      uint4 v = rz[q].a;
+      if (!(zc_ok && m < me)) v = make_uint4(0u, 0u, 0u, 0u);
+      *reinterpret_cast<uint4*>(&sZ[buf][(zr + 16 * q) * LDN + zc]) = v;
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const size_t m = m0 + ar + 32 * q;
+      const bool in = ac_ok && m < me;
+      if (VIEW) {
+        float v[8];
+        raw_unpack(ra[q], v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = in ? clamp_act(fmaf(v[e], sc[e], sh[e]), lo, hi) : 0.f;   // padding stays zero
+        store8(&sA[buf][(ar + 32 * q) * LDK + ac], v);
+      } else {
+        uint4 v = ra[q].a;
+        if (!in) v = make_uint4(0u, 0u, 0u, 0u);
+        *reinterpret_cast<uint4*>(&sA[buf][(ar + 32 * q) * LDK + ac]) = v;
+      }
+    }
+  };
+
+  // wavefront w: n-tiles 2w, 2w+1 of the strip (16 columns each), all four k-tiles
+  f4v_t acc[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f4v_t{0.f, 0.f, 0.f, 0.f};
+
+  const int nchunks = (int)((me - mb + kWgRows - 1) / kWgRows);
+  if (nchunks > 0) fetch(mb);
+  for (int ch = 0; ch < nchunks; ++ch) {
+    const int buf = ch & 1;
+    commit(buf, mb + (size_t)ch * kWgRows);
+    __syncthreads();                      // chunk ch is in LDS; the other buffer's readers finished before their next commit
+    if (ch + 1 < nchunks) fetch(mb + (size_t)(ch + 1) * kWgRows);
+#pragma unroll
+    for (int s = 0; s < kWgRows / 32; ++s) {
+      bf16x8_t bk[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) bk[j] = lds_frag_tr(sA[buf], LDK, s * 32 + G * 8, j * 16, l16);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const bf16x8_t an = lds_frag_tr(sZ[buf], LDN, s * 32 + G * 8, (2 * wave + i) * 16, l16);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(an, bk[j], acc[i][j], 0, 0, 0);
+      }
+    }
+  }
+  // register r of lane l: D[n = tile*16 + 4*G + r][k = j*16 + l16]
+  float* out = p.ws + (size_t)split * N * K;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int k = k0 + j * 16 + l16;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int n = n0 + (2 * wave + i) * 16 + 4 * G + r;
+        if (n < N && k < K) out[(size_t)n * K + k] = acc[i][j][r];
+      }
+    }
+}
+
+static bool wg_tr_plan(size_t M, int K, int N, WgTrArgs* a, int* S) {
+  if (K % 8 || N % 8 || M <= 2048 || N < 48) return false;     // a 128-column strip of a narrower dZ is mostly padding: measured slower
+  a->itiles = (N + kWgN - 1) / kWgN;
+  a->jtiles = (K + kWgK - 1) / kWgK;
+  const size_t tiles = (size_t)a->itiles * a->jtiles;
+  size_t s = (1024 + tiles - 1) / tiles;                 // about 1024 blocks
+  const size_t smax = (M + 2 * kWgRows - 1) / (2 * kWgRows);
+  if (s > smax) s = smax;
+  if (s > (size_t)kMaxPartials) s = kMaxPartials;
+  if (s < 1) s = 1;
+  size_t mc = (M + s - 1) / s;
+  mc = (mc + kWgRows - 1) / kWgRows * kWgRows;
+  a->mchunk = mc;
+  *S = (int)((M + mc - 1) / mc);
+  return true;
+}
+
+int pw_wgrad_tr_ok(int dt, size_t M, int K, int N) {
+  WgTrArgs a{};
+  int S;
+  return dt == 1 && wg_tr_plan(M, K, N, &a, &S);
+}
+size_t pw_wgrad_tr_ws(size_t M, int K, int N) {
+  WgTrArgs a{};
+  int S;
+  if (!wg_tr_plan(M, K, N, &a, &S)) return 0;
+  return (size_t)S * N * K;
+}
+void pw_wgrad_tr(hipStream_t st, const void* dz, HView av, size_t M, int K, int N, float* ws, float* g_w, int K_out) {
+  WgTrArgs a{};
+  int S = 1;
+  if (!wg_tr_plan(M, K, N, &a, &S)) { launch_plan_failed("transposing weight gradient called for a shape it does not take"); return; }
+  a.dz = (const bf16_t*)dz; a.a = (const bf16_t*)av.z; a.scale = av.scale; a.shift = av.shift; a.act = av.act;
+  a.ws = ws; a.M = M; a.K = K; a.N = N;
+  {
+    KScope ks(st, "pw_wgrad", ((double)M * K + (double)M * N) * 2.0 + (double)S * N * K * 4, 2.0 * M * K * N, (long)M, K, N);
+    const unsigned grid = (unsigned)(a.itiles * a.jtiles * S);
+    if (av.scale) hipLaunchKernelGGL(pw_wgrad_tr_k<true>, dim3(grid), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(pw_wgrad_tr_k<false>, dim3(grid), dim3(256), 0, st, a);
+  }
+  if (K_out < 0) K_out = K;
+  reduce_partials(st, ws, S, (size_t)N * K, K, (size_t)K_out, 1, g_w, K_out);
+}
+
+}  // namespace ftp

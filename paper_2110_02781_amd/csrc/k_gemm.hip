@@ -1300,7 +1300,8 @@ size_t pw_wgrad_ws(size_t M, int K, int N) {
   GemmArgs a{};
   bool small;
   plan_wgrad(M, K, N, &a, &small);
-  return (size_t)(a.nranges / a.itiles) * N * K;
+  const size_t own = (size_t)(a.nranges / a.itiles) * N * K, tr = pw_wgrad_tr_ws(M, K, N);   // either storage type may run
+  return own > tr ? own : tr;
 }
 
 void pw_wgrad(int dt, hipStream_t st, const void* dz, HView av, size_t M, int K, int N, float* ws,
@@ -1319,6 +1320,7 @@ void pw_wgrad(int dt, hipStream_t st, const void* dz, HView av, size_t M, int K,
     else hipLaunchKernelGGL(pw_wgrad_tiny_k<bf16_t>, dim3(grid), dim3(256), 0, st, a, K_out < 0 ? K : K_out);
     return;
   }
+  if (pw_wgrad_tr_ok(dt, M, K, N)) { pw_wgrad_tr(st, dz, av, M, K, N, ws, g_w, K_out); return; }
   bool small;
   plan_wgrad(M, K, N, &a, &small);
   int S = a.nranges / a.itiles;

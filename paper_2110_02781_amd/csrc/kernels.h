@@ -183,6 +183,12 @@ size_t pw_bwd_fused_ws(size_t M, int K, int N);
 void pw_bwd_fused(hipStream_t st, const void* dA, HView out, const float* coef, const void* w, const void* a_in,
                   const void* res, size_t M, int K, int N, float* ws, float* g_w, void* dIn);
 
+// the weight gradient for bfloat16 layers with more than 2048 rows: operands staged untransposed, transposed on the
+// way out of LDS (pw_wgrad dispatches to it; ws: pw_wgrad_tr_ws floats)
+int pw_wgrad_tr_ok(int dt, size_t M, int K, int N);
+size_t pw_wgrad_tr_ws(size_t M, int K, int N);
+void pw_wgrad_tr(hipStream_t st, const void* dz, HView a, size_t M, int K, int N, float* ws, float* g_w, int K_out);
+
 // wgrad (g_w +=) then dgrad (dA =) of one layer on one stream; one launch for short problems
 void pw_bwd(int dt, hipStream_t st, const void* dz, const void* w, const void* res, HView a, size_t M, int K, int N,
             float* ws, float* g_w, void* dA);
