@@ -89,8 +89,10 @@ const char* ftp_last_error(void);
 
 /* ---- model description ---------------------------------------------------- */
 
-/* Copies `units` (host, L entries).  in_h/in_w/in_c: shape of the network input.
- * Channel counts that feed a BatchNorm must be multiples of 8. */
+/* The network every worker partitions (section "Initialization": the central node sends the model and the initial
+ * partition points; a worker builds its sub-model from layer start_i to layer end_i).  Copies `units` (host, L
+ * entries).  in_h/in_w/in_c: shape of the network input.  Channel counts that feed a BatchNorm must be multiples
+ * of 8. */
 int ftp_model_create(const ftp_unit_desc* units, int L, int in_h, int in_w, int in_c,
                      ftp_dtype act_dtype, ftp_model** out);
 void ftp_model_destroy(ftp_model*);
@@ -110,7 +112,9 @@ int ftp_model_unit_bn_channels(const ftp_model*, int u, size_t* n);
 
 /* ---- stage ------------------------------------------------------------------ */
 
-/* Builds units [a,b) for `batch` samples with `n_slots` in-flight batches on the
+/* The sub-model of one worker (section "Initialization": layers start_i .. end_i of the partition points; section
+ * "Async Pipeline Training": stage i of n keeps n-i batches in flight, hence the slots).
+ * Builds units [a,b) for `batch` samples with `n_slots` in-flight batches on the
  * current HIP device; allocates all device memory it will ever need.  Weights
  * start at zero (import them), momentum and gradients at zero, BN running mean
  * 0 / variance 1. */
@@ -131,7 +135,9 @@ void ftp_stage_destroy(ftp_stage*);
 /* Device memory, in bytes, that the stage allocated at creation (host pointer out). */
 int ftp_stage_device_bytes(const ftp_stage*, size_t* bytes);
 
-/* Host <-> device copies of one unit's parameter vector (layout above), its
+/* Weights travel between workers and the central node as per-layer vectors (sections "Weight Replication" and
+ * "Fault Tolerance Mechanism": a worker fetches the layers it lacks; here the host side of that exchange).
+ * Host <-> device copies of one unit's parameter vector (layout above), its
  * accumulated gradient, its momentum buffer, and its BN running statistics
  * (running_mean then running_var of each BatchNorm in order; 2 * bn_channels). */
 int ftp_stage_import_weights(ftp_stage*, int unit, const float* host_w, size_t n);
@@ -149,14 +155,16 @@ int ftp_stage_export_bn_stats(const ftp_stage*, int unit, float* host_s, size_t 
 int ftp_stage_export_conv_output(const ftp_stage*, int slot, int unit, int conv, float* host_z, size_t n);
 int ftp_stage_export_bn_batch_stats(const ftp_stage*, int slot, int unit, int conv, float* host_s, size_t n);
 
-/* Forward of one batch through units [a,b) with the current weights.
+/* Section "Async Pipeline Training": a worker forwards a batch through its sub-model with its newest weights and
+ * passes the result on.  Forward of one batch through units [a,b) with the current weights.
  * x_dev: [batch, H, W, C] of unit a's input, read only, copied into the slot
  * (the stashed stage input).  y_dev: output of the last unit, or NULL; when the
  * stage ends with the LOSS unit, y receives the logits [batch, classes].
  * The slot must be free; it is busy until its backward. */
 int ftp_stage_forward(ftp_stage*, int slot, const void* x_dev, void* y_dev, void* stream);
 
-/* Stages that end with the LOSS unit: mean cross-entropy of the slot's logits
+/* Section "Async Pipeline Training": the last stage computes the loss of a batch and starts its backward pass.
+ * Stages that end with the LOSS unit: mean cross-entropy of the slot's logits
  * against labels_dev (int32 [batch], 0 <= label < classes) into loss_dev (one
  * float); also seeds the slot's backward so dy_dev may be NULL there. */
 int ftp_stage_loss(ftp_stage*, int slot, const int32_t* labels_dev, float* loss_dev, void* stream);
@@ -175,7 +183,8 @@ int ftp_stage_loss(ftp_stage*, int slot, const int32_t* labels_dev, float* loss_
 int ftp_softmax_ce_static(const void* logits_dev, const int32_t* labels_dev, int batch, int classes, ftp_dtype dtype,
                           void* dlogits_dev, float* loss_dev, void* stream);
 
-/* Copies the current weights into the slot (weight stashing): the slot's
+/* Section "Async Pipeline Training" (weight stashing: the backward of a batch uses the weight version its forward
+ * used).  Copies the current weights into the slot (weight stashing): the slot's
  * backward then differentiates with respect to that version.  Call it between
  * the slot's forward and the next update.  Without it, backward uses the
  * weights current at that time. */
@@ -194,14 +203,15 @@ int ftp_stage_snapshot_weights(ftp_stage*, int slot, void* stream);
  * every (n-i)-th backward. */
 int ftp_stage_aggregate_weights(ftp_stage*, const int* slots, int n, void* stream);
 
-/* Backward of the slot's batch.  dy_dev: gradient of the stage output (same
+/* Section "Async Pipeline Training": the backward pass of a batch through the sub-model, with the stashed weight
+ * version.  Backward of the slot's batch.  dy_dev: gradient of the stage output (same
  * shape and type as y), or NULL after ftp_stage_loss.  dx_dev: receives the
  * gradient of the stage input, or NULL (e.g. a == 0).  Weight gradients are
  * ACCUMULATED into the stage's gradient buffers.  Frees the slot. */
 int ftp_stage_backward(ftp_stage*, int slot, const void* dy_dev, void* dx_dev, void* stream);
 
-/* One SGD-momentum step on all parameters of the stage from the accumulated
- * gradients, which are then zeroed. */
+/* Section "Experiment Setup" (SGD, momentum 0.9, weight decay 4e-5): g += wd*w; v = momentum*v + g; w -= lr*v.
+ * One step on all parameters of the stage from the accumulated gradients, which are then zeroed. */
 int ftp_stage_update(ftp_stage*, const ftp_sgd* opt, void* stream);
 
 /* ---- profiling and partition ------------------------------------------------ */
@@ -217,7 +227,10 @@ int ftp_stage_update(ftp_stage*, const ftp_sgd* opt, void* stream);
 int ftp_profile_layers(const ftp_model*, int batch, int reps, double* t_ns, int64_t* out_bytes,
                        void* stream);
 
-/* Partition dynamic programme.  layer_costs[L] > 0: execution time of each unit
+/* Section "Dynamic Model Partition": the dynamic programme A(j, n) over contiguous splits that minimises the slowest
+ * stage (base case: the prefix on device 0; recurrence: the last cut, with the optional transfer term and the
+ * last-stage time), every layer's time on worker k being its profiled time times the capacity C_k.
+ * layer_costs[L] > 0: execution time of each unit
  * on the profiling device; device_capacities[N] > 0: TIME MULTIPLIERS (the
  * paper's computing capacity C_k = worker time / central-node time, so larger =
  * slower; stage k on device k costs C_k * sum of its costs).  Optional
@@ -231,7 +244,7 @@ int ftp_solve_partition(const double* layer_costs, int L, const double* device_c
                         const double* out_bytes, const double* bandwidth, int32_t* bounds,
                         double* bottleneck);
 
-/* Capacity estimate of a worker: its measured stage time divided by the
+/* Section "Dynamic Model Partition", capacity equation: a worker's measured stage time divided by the
  * profiling device's time for the same units [start, end] (inclusive). */
 int ftp_estimate_capacity(double stage_time, const double* layer_costs, int L, int start, int end,
                           double* capacity);
