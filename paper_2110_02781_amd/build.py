@@ -18,6 +18,7 @@ SOURCES = [
     ("k_conv.hip", ["-x", "hip"]),
     ("k_gemm.hip", ["-x", "hip"]),
     ("k_fused.hip", ["-x", "hip"]),
+    ("k_gemm_deep.hip", ["-x", "hip"]),
     ("stage.cpp", ["-x", "hip"]),
     ("ktrace.cpp", ["-x", "hip"]),
     ("solver.cpp", ["-x", "c++", "-ffp-contract=off"]),

@@ -16,12 +16,9 @@
 // with the largest tensors); the rest keep the layer-by-layer kernels.
 #include "dev_common.h"
 #include "kernels.h"
+#include "mfma_frag.h"
 
 namespace ftp {
-
-typedef float f4v_t __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef short s4v_t __attribute__((ext_vector_type(4)));
 
 enum { kFusedRows = 64, kFusedBlocks = 256 };   // rows per tile (32 or 64); blocks: one per CU (two where the partials allow)
 
@@ -40,21 +37,6 @@ struct FusedArgs {
   int K, N, NP, KP;      // NP, KP: N rounded up to 32, K rounded up to 16 (LDS tiles, zero padded)
   int ntiles;
 };
-
-__device__ __forceinline__ bf16x8_t lds_frag(const bf16_t* p) {
-  return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(p));
-}
-// rows r0 .. r0+7 of column c0 + (lane % 16) of a row-major LDS tile with leading dimension ld, for the lanes of one
-// 16-lane group: lane j hands in the address of row (j / 4) [+4 for the second read], columns c0 + 4 * (j % 4) ...
-// and receives column c0 + j of four consecutive rows
-__device__ __forceinline__ bf16x8_t lds_frag_tr(const bf16_t* tile, int ld, int r0, int c0, int l16) {
-  const bf16_t* p = tile + (r0 + (l16 >> 2)) * ld + c0 + 4 * (l16 & 3);
-  const s4v_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s4v_t __attribute__((address_space(3)))*)p);
-  const s4v_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s4v_t __attribute__((address_space(3)))*)(p + 4 * ld));
-  typedef short s8v_t __attribute__((ext_vector_type(8)));
-  const s8v_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8_t, v);
-}
 
 // NTW: 16-wide tiles of N per wavefront (4 * NTW * 16 >= N), KT: 16-wide tiles of K; IT: passes of the elementwise
 // stage (256 threads cover 256 / (N/8) rows per pass)

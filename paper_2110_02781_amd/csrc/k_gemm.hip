@@ -1256,6 +1256,7 @@ void pw_fwd(int dt, hipStream_t st, HView av, const void* w, const float* bias, 
     if (P_out) *P_out = a.nranges;
     return;
   }
+  if (!bias && pw_deep_ok(dt, M, K, N, false)) { pw_fwd_deep(st, av, w, M, K, N, z, stats, P_out); return; }
   bool small;
   plan_rows(M, N, K, &a, &small);
   if (P_out) *P_out = a.nranges;
@@ -1271,6 +1272,7 @@ void pw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const void*
     launch_tiny<MODE_DGRAD>(dt, st, a, K);
     return;
   }
+  if (pw_deep_ok(dt, M, N, K, true)) { pw_dgrad_deep(st, dz, w, res, M, K, N, dA); return; }
   bool small;
   plan_rows(M, K, N, &a, &small);
   launch<MODE_DGRAD>(dt, st, a, small);

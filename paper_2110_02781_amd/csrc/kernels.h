@@ -183,6 +183,13 @@ size_t pw_bwd_fused_ws(size_t M, int K, int N);
 void pw_bwd_fused(hipStream_t st, const void* dA, HView out, const float* coef, const void* w, const void* a_in,
                   const void* res, size_t M, int K, int N, float* ws, float* g_w, void* dIn);
 
+
+// bfloat16 pointwise layers with a long reduction (>= 192) and 2 K - 64 K rows: forward (A' * W^T, BatchNorm partial sums
+// as pw_fwd leaves them) and data gradient (dZ * W (+ res)) on 2 x 2 wavefront tiles of 16x16x32 MFMAs; pw_fwd and
+// pw_dgrad dispatch to them.  R = reduction extent, NC = output columns.
+int pw_deep_ok(int dt, size_t M, int R, int NC, bool dgrad);
+void pw_fwd_deep(hipStream_t st, HView a, const void* w, size_t M, int K, int N, void* z, float* stats, int* P_out);
+void pw_dgrad_deep(hipStream_t st, const void* dz, const void* w, const void* res, size_t M, int K, int N, void* dA);
 // the weight gradient for bfloat16 layers with more than 2048 rows: operands staged untransposed, transposed on the
 // way out of LDS (pw_wgrad dispatches to it; ws: pw_wgrad_tr_ws floats)
 int pw_wgrad_tr_ok(int dt, size_t M, int K, int N);

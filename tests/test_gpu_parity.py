@@ -73,6 +73,13 @@ SINGLE = [
     ("invres_ragged_mixed_s2", invres_unit(40, 72, 2, 6), (37, 29, 40), 3),
     ("pw_ragged_big", conv_unit(40, 72, 1, 1, 1, 0, 0, L.ACT_RELU6), (37, 61, 40), 2),
     ("stem_ragged_big_s2", conv_unit(3, 24, 3, 3, 2, 1, 1, L.ACT_RELU6), (75, 61, 3), 3),
+    # reductions of 256 channels or more over more than 2048 rows (bfloat16: the long-reduction GEMM), ragged in every
+    # extent: rows not a multiple of 64, reductions not of 64, output columns not of 32; with and without a view on
+    # the input, with and without a residual
+    ("invres_long_reduction_s1_res", invres_unit(48, 48, 1, 6), (27, 29, 48), 3),
+    ("invres_long_reduction_wide", invres_unit(88, 136, 1, 6), (19, 19, 88), 6),
+    ("pw_long_reduction_fwd", conv_unit(264, 72, 1, 1, 1, 0, 0, L.ACT_RELU6), (37, 61, 264), 1),
+    ("pw_long_reduction_dgrad", conv_unit(40, 264, 1, 1, 1, 0, 0, L.ACT_RELU6), (37, 61, 40), 1),
 ]
 
 
