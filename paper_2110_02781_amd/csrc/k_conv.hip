@@ -215,11 +215,11 @@ size_t conv_direct_wgrad_ws(const ConvGeom& g) {
 }
 
 void conv_direct_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, void* im2col, float* ws,
-                       float* g_w) {
+                       float* g_w, bool patches_ready) {
   const int Kpad = direct_kpad(g), K = g.kh * g.kw * g.Cin;
   const size_t M = (size_t)g.N * g.Hout * g.Wout;
   View v{in.z, in.scale, in.shift, in.act};
-  {
+  if (!patches_ready) {
     const double es = dt == 0 ? 4.0 : 2.0;
     KScope ks(st, "im2col", ((double)g.N * g.Hin * g.Win * g.Cin + (double)M * Kpad) * es, 0, (long)M, Kpad, g.Cout);
     size_t nvec = M * (Kpad / 8);

@@ -426,7 +426,9 @@ static bool wg_tr_plan(size_t M, int K, int N, WgTrArgs* a, int* S) {
   a->itiles = (N + kWgN - 1) / kWgN;
   a->jtiles = (K + kWgK - 1) / kWgK;
   const size_t tiles = (size_t)a->itiles * a->jtiles;
-  size_t s = (1024 + tiles - 1) / tiles;                 // about 1024 blocks
+  // about 512 blocks: with 1024 the kernel itself takes the same time, but twice the partial tiles are written and
+  // summed afterwards (more than the operands themselves for the layers with large weight matrices)
+  size_t s = (512 + tiles - 1) / tiles;
   const size_t smax = (M + 2 * kWgRows - 1) / (2 * kWgRows);
   if (s > smax) s = smax;
   if (s > (size_t)kMaxPartials) s = kMaxPartials;

@@ -134,8 +134,9 @@ void conv_direct_dgrad_gemm(int dt, hipStream_t st, const void* dz, const void* 
 // g_w[Cout][kh][kw][Cin] += dW; im2col: scratch of conv_direct_im2col_elems(g) activation elements
 size_t conv_direct_wgrad_ws(const ConvGeom& g);  // floats of workspace needed
 size_t conv_direct_im2col_elems(const ConvGeom& g);
+// patches_ready: im2col already holds this layer's patch matrix (left there by conv_direct_fwd_gemm on the same input)
 void conv_direct_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, void* im2col, float* ws,
-                       float* g_w);
+                       float* g_w, bool patches_ready = false);
 // g[(j % C) * stride_c + (j / C) * stride_q] += sum_p ws[p * QC + j]; columns j % C >= valid_c skipped (-1: none)
 void reduce_partials(hipStream_t st, const float* ws, int P, size_t QC, int C, size_t stride_q, size_t stride_c,
                      float* g, int valid_c = -1);

@@ -268,6 +268,10 @@ struct ftp_stage {
   size_t ws_fused_floats = 0;
   int n_direct = 0;           // sublayers that use the patch-matrix buffer
   void* im2col = nullptr;     // patch matrix for the weight gradient of small dense convolutions
+  // The conv output whose input patches the buffer holds right now (nullptr: none).  A forward that goes through the
+  // patch matrix leaves it behind; if nothing has used the buffer since, the weight gradient of the same layer and
+  // slot takes it as it is instead of writing the same matrix again.
+  const void* im2col_of = nullptr;
   size_t im2col_elems = 0;
   size_t ws_floats = 0;
   int max_c = 0;
@@ -602,6 +606,7 @@ static void sub_forward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, HVi
   int P = 0;
   float* stt = sl.stats + p.st_off[k];
   int C = g.Cout;
+  if (s->im2col_of == z) s->im2col_of = nullptr;     // this layer's input is a new one: patches kept from before are stale
   const float* gamma = W.w32 + p.p_off + sb.gamma_off;
   const float* beta = W.w32 + p.p_off + sb.beta_off;
   float* rm = s->run_mean + p.bn_off + sb.bn_off;
@@ -623,6 +628,7 @@ static void sub_forward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, HVi
              conv_direct_gemm_wpad_elems(g) * s->es <= s->ws_floats * sizeof(float)) {
     // the float workspace is free during a forward: the padded weight copy lives there
     conv_direct_fwd_gemm(s->dt, st, in, w, g, s->im2col, s->ws, z, s->bn_part, &P);
+    s->im2col_of = z;
   } else {
     if (sb.type == SUB_DW) dw_fwd(s->dt, st, in, w, g, z);
     else conv_direct_fwd(s->dt, st, in, w, g, z);
@@ -905,7 +911,10 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
     pw_bwd(s->dt, st, dz, w, res, in, M, g.Cin, g.Cout, s->ws, gw, dIn);
     return FTP_OK;
   }
-  if (sb.type == SUB_DIRECT) conv_direct_wgrad(s->dt, ws, dz, in, g, s->im2col, wsp, gw);
+  if (sb.type == SUB_DIRECT) {
+    conv_direct_wgrad(s->dt, ws, dz, in, g, s->im2col, wsp, gw, s->im2col_of == out.z);
+    s->im2col_of = nullptr;      // one weight gradient per forward: nobody else can want these patches
+  }
   else if (sb.type == SUB_PW) pw_wgrad(s->dt, ws, dz, in, M, g.Cin, g.Cout, wsp, gw);
   else dw_wgrad(s->dt, ws, dz, in, g, wsp, gw);
   if (overlap && !tail_here) {
@@ -916,7 +925,10 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
     if (sb.type == SUB_DIRECT) {
       // the scratch buffers are shared with the weight gradients: fine on one stream, but a stage that runs them on
       // the side stream keeps the direct kernel
-      if (conv_direct_dgrad_gemm_ok(g) && !stage_forks(s) && s->im2col) conv_direct_dgrad_gemm(s->dt, st, dz, w, g, s->im2col, s->ws, dIn);
+      if (conv_direct_dgrad_gemm_ok(g) && !stage_forks(s) && s->im2col) {
+        conv_direct_dgrad_gemm(s->dt, st, dz, w, g, s->im2col, s->ws, dIn);
+        s->im2col_of = nullptr;
+      }
       else conv_direct_dgrad(s->dt, st, dz, w, g, dIn);
     }
     else if (sb.type == SUB_PW) pw_dgrad(s->dt, st, dz, w, res, M, g.Cin, g.Cout, dIn);
