@@ -120,11 +120,11 @@ __device__ __forceinline__ void view_load8(const View& v, size_t idx, int c, flo
 // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Renumbering them so that
 // consecutive logical ids share an XCD keeps blocks that touch the same cache lines (column tiles of one row range,
 // neighbouring spatial tiles, adjacent channel groups of one pixel row) behind one L2.
-__device__ __forceinline__ int xcd_logical_block() {
-  const int nb = gridDim.x, b = blockIdx.x;
+__device__ __forceinline__ int xcd_logical(const int b, const int nb) {    // b in [0, nb), block 0 of the range on XCD 0
   const int x = b & 7, idx = b >> 3, q = nb >> 3, rem = nb & 7;
   return x * q + (x < rem ? x : rem) + idx;
 }
+__device__ __forceinline__ int xcd_logical_block() { return xcd_logical(blockIdx.x, gridDim.x); }
 
 // four consecutive channels as a float4
 __device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }

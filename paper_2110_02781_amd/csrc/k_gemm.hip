@@ -1166,7 +1166,7 @@ __device__ __forceinline__ void pw_wgrad_tiny_body(const GemmArgs& p, const int 
 }
 
 template <typename T, int MODE>
-__global__ __launch_bounds__(256) void pw_gemm_tiny_k(GemmArgs p) { pw_gemm_tiny_body<T, MODE, 4>(p, blockIdx.x); }
+__global__ __launch_bounds__(256) void pw_gemm_tiny_k(GemmArgs p) { pw_gemm_tiny_body<T, MODE, 4>(p, xcd_logical_block()); }   // the column tiles of a row panel share an L2
 template <typename T>
 __global__ __launch_bounds__(256) void pw_wgrad_tiny_k(GemmArgs p, int K_out) { pw_wgrad_tiny_body<T, 4>(p, K_out, blockIdx.x); }
 // data gradient and weight gradient of one short layer in one launch: both read the same dZ, their tiles are
@@ -1174,7 +1174,7 @@ __global__ __launch_bounds__(256) void pw_wgrad_tiny_k(GemmArgs p, int K_out) { 
 // pixels the weight-gradient tiles are few and each walks all pixels, so 16 wavefronts share that walk.
 template <typename T, int NW>
 __global__ __launch_bounds__(64 * NW) void pw_bwd_tiny_k(GemmArgs pd, GemmArgs pw, int K_out, int n_dgrad) {
-  if ((int)blockIdx.x < n_dgrad) pw_gemm_tiny_body<T, MODE_DGRAD, NW>(pd, blockIdx.x);
+  if ((int)blockIdx.x < n_dgrad) pw_gemm_tiny_body<T, MODE_DGRAD, NW>(pd, xcd_logical(blockIdx.x, n_dgrad));   // the range starts on XCD 0
   else pw_wgrad_tiny_body<T, NW>(pw, K_out, blockIdx.x - n_dgrad);
 }
 
