@@ -1174,7 +1174,7 @@ __global__ __launch_bounds__(256) void pw_wgrad_tiny_k(GemmArgs p, int K_out) { 
 // pixels the weight-gradient tiles are few and each walks all pixels, so 16 wavefronts share that walk.
 template <typename T, int NW>
 __global__ __launch_bounds__(64 * NW) void pw_bwd_tiny_k(GemmArgs pd, GemmArgs pw, int K_out, int n_dgrad) {
-  if ((int)blockIdx.x < n_dgrad) pw_gemm_tiny_body<T, MODE_DGRAD, NW>(pd, xcd_logical(blockIdx.x, n_dgrad));   // the range starts on XCD 0
+  if ((int)blockIdx.x < n_dgrad) pw_gemm_tiny_body<T, MODE_DGRAD, NW>(pd, blockIdx.x);
   else pw_wgrad_tiny_body<T, NW>(pw, K_out, blockIdx.x - n_dgrad);
 }
 
