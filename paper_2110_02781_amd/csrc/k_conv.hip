@@ -181,7 +181,19 @@ void conv_direct_dgrad(int dt, hipStream_t st, const void* dz, const void* w, co
 // activation applied), then dW = dZ^T * A runs on the MFMA weight-gradient kernel.
 template <typename T>
 __global__ void im2col_k(View in, ConvGeom g, int Kpad, T* __restrict__ out) {
+  // which tap and input channel column k of the matrix is: worked out once per block (two divisions per column)
+  // instead of once per element, packed as (row offset + 1) << 24 | column offset << 16 | channel; 0 = padding column
+  extern __shared__ uint32_t taps[];
   const int KG = Kpad / 8, K = g.kh * g.kw * g.Cin;
+  for (int k = threadIdx.x; k < Kpad; k += blockDim.x) {
+    uint32_t t = 0;
+    if (k < K) {
+      const int tap = k / g.Cin, ci = k - tap * g.Cin, i = tap / g.kw, j = tap - i * g.kw;
+      t = ((uint32_t)(i + 1) << 24) | ((uint32_t)j << 16) | (uint32_t)ci;
+    }
+    taps[k] = t;
+  }
+  __syncthreads();
   const size_t total = (size_t)g.N * g.Hout * g.Wout * KG;
   for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
     const int kg = (int)(idx % KG);
@@ -189,17 +201,16 @@ __global__ void im2col_k(View in, ConvGeom g, int Kpad, T* __restrict__ out) {
     const int wo = (int)(pix % g.Wout);
     const size_t r = pix / g.Wout;
     const int ho = (int)(r % g.Hout), n = (int)(r / g.Hout);
+    const int h0 = ho * g.stride - g.ph, w0 = wo * g.stride - g.pw;
+    const size_t img = (size_t)n * g.Hin;
     float v[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const int k = kg * 8 + e;
+      const uint32_t t = taps[kg * 8 + e];
+      const int hi = h0 + (int)(t >> 24) - 1, wi = w0 + (int)((t >> 16) & 0xffu), ci = (int)(t & 0xffffu);
       float x = 0.f;
-      if (k < K) {
-        const int tap = k / g.Cin, ci = k % g.Cin, i = tap / g.kw, j = tap % g.kw;
-        const int hi = ho * g.stride + i - g.ph, wi = wo * g.stride + j - g.pw;
-        if (hi >= 0 && hi < g.Hin && wi >= 0 && wi < g.Win)
-          x = view_at<T>(in, (((size_t)n * g.Hin + hi) * g.Win + wi) * g.Cin + ci, ci);
-      }
+      if (t != 0 && hi >= 0 && hi < g.Hin && wi >= 0 && wi < g.Win)
+        x = view_at<T>(in, ((img + hi) * g.Win + wi) * g.Cin + ci, ci);
       v[e] = x;
     }
     store8(out + idx * 8, v);
@@ -224,7 +235,7 @@ void conv_direct_wgrad(int dt, hipStream_t st, const void* dz, HView in, const C
     KScope ks(st, "im2col", ((double)g.N * g.Hin * g.Win * g.Cin + (double)M * Kpad) * es, 0, (long)M, Kpad, g.Cout);
     size_t nvec = M * (Kpad / 8);
     unsigned grid = (unsigned)((nvec + 255) / 256 > 65536 ? 65536 : (nvec + 255) / 256);
-    FTP_DISPATCH(dt, hipLaunchKernelGGL(im2col_k<T>, dim3(grid), dim3(256), 0, st, v, g, Kpad, (T*)im2col));
+    FTP_DISPATCH(dt, hipLaunchKernelGGL(im2col_k<T>, dim3(grid), dim3(256), (size_t)Kpad * sizeof(uint32_t), st, v, g, Kpad, (T*)im2col));
   }
   pw_wgrad(dt, st, dz, HView{im2col, nullptr, nullptr, 0}, M, Kpad, g.Cout, ws, g_w, K);
 }
@@ -257,7 +268,7 @@ void conv_direct_fwd_gemm(int dt, hipStream_t st, HView in, const void* w, const
     KScope ks(st, "im2col", ((double)g.N * g.Hin * g.Win * g.Cin + (double)M * Kpad) * es, 0, (long)M, Kpad, g.Cout);
     size_t nvec = M * (Kpad / 8);
     unsigned grid = (unsigned)((nvec + 255) / 256 > 65536 ? 65536 : (nvec + 255) / 256);
-    FTP_DISPATCH(dt, hipLaunchKernelGGL(im2col_k<T>, dim3(grid), dim3(256), 0, st, v, g, Kpad, (T*)im2col));
+    FTP_DISPATCH(dt, hipLaunchKernelGGL(im2col_k<T>, dim3(grid), dim3(256), (size_t)Kpad * sizeof(uint32_t), st, v, g, Kpad, (T*)im2col));
     FTP_DISPATCH(dt, hipLaunchKernelGGL(pad_rows_k<T>, dim3((g.Cout * Kpad + 255) / 256), dim3(256), 0, st, (const T*)w, g.Cout, K,
                                         Kpad, (T*)wpad));
   }
@@ -309,7 +320,7 @@ void conv_direct_dgrad_gemm(int dt, hipStream_t st, const void* dz, const void* 
     KScope ks(st, "im2col", ((double)g.N * g.Hout * g.Wout * g.Cout + (double)M * Kpad) * es, 0, (long)M, Kpad, g.Cin);
     size_t nvec = M * (Kpad / 8);
     unsigned grid = (unsigned)((nvec + 255) / 256 > 65536 ? 65536 : (nvec + 255) / 256);
-    FTP_DISPATCH(dt, hipLaunchKernelGGL(im2col_k<T>, dim3(grid), dim3(256), 0, st, v, d, Kpad, (T*)im2col));
+    FTP_DISPATCH(dt, hipLaunchKernelGGL(im2col_k<T>, dim3(grid), dim3(256), (size_t)Kpad * sizeof(uint32_t), st, v, d, Kpad, (T*)im2col));
     FTP_DISPATCH(dt, hipLaunchKernelGGL(dgrad_weights_k<T>, dim3((g.Cin * Kpad + 255) / 256), dim3(256), 0, st, (const T*)w, g.Cout,
                                         g.kh, g.kw, g.Cin, Kpad, (T*)wscratch));
   }
