@@ -279,7 +279,8 @@ static void fused_launch_shape(hipStream_t st, const FusedArgs& a, const FusedPl
 }
 
 void pw_bwd_fused(hipStream_t st, const void* dA, HView out, const float* coef, const void* w, const void* a_in,
-                  const void* res, size_t M, int K, int N, float* ws, float* g_w, void* dIn) {
+                  const void* res, size_t M, int K, int N, float* ws, float* g_w, void* dIn, hipStream_t st_sum,
+                  hipEvent_t ev_sum) {
   FusedPlan f;
   if (!fused_plan(M, K, N, &f)) { launch_plan_failed("fused pointwise backward called for a shape it does not take"); return; }
   FusedArgs a{};
@@ -293,7 +294,13 @@ void pw_bwd_fused(hipStream_t st, const void* dA, HView out, const float* coef, 
     else if (out.act == ACT_RELU) fused_launch_shape<ACT_RELU>(st, a, f);
     else fused_launch_shape<ACT_RELU6>(st, a, f);
   }
-  reduce_partials(st, ws, f.P, (size_t)N * K, K, (size_t)K, 1, g_w, K);
+  if (st_sum != st) {                 // the partial sums are summed on another stream, behind the kernel
+    if (hipEventRecord(ev_sum, st) != hipSuccess || hipStreamWaitEvent(st_sum, ev_sum, 0) != hipSuccess) {
+      launch_plan_failed("fused pointwise backward: could not order the partial sums behind the kernel");
+      return;
+    }
+  }
+  reduce_partials(st_sum, ws, f.P, (size_t)N * K, K, (size_t)K, 1, g_w, K);
 }
 
 }  // namespace ftp

@@ -179,10 +179,12 @@ void pw_wgrad(int dt, hipStream_t st, const void* dz, HView a, size_t M, int K, 
 // Narrow-to-wide pointwise layer (K inputs, N >= 2K outputs, bfloat16, input stored activated), whole backward behind
 // the BatchNorm reductions in one pass: dz = k1*dA*act'(out) + k2*z + k3 formed per row tile on chip,
 // dIn = dz * W (+ res), g_w += dz^T * A.  coef: [3][N] from bn_bwd_finalize.  ws: pw_bwd_fused_ws(M, K, N) floats.
+// The kernel's partial weight gradients are summed on st_sum; if that is not st, ev_sum orders the sum behind the kernel.
 int pw_bwd_fused_ok(int dt, size_t M, int K, int N, HView a);
 size_t pw_bwd_fused_ws(size_t M, int K, int N);
 void pw_bwd_fused(hipStream_t st, const void* dA, HView out, const float* coef, const void* w, const void* a_in,
-                  const void* res, size_t M, int K, int N, float* ws, float* g_w, void* dIn);
+                  const void* res, size_t M, int K, int N, float* ws, float* g_w, void* dIn, hipStream_t st_sum,
+                  hipEvent_t ev_sum);
 
 
 // bfloat16 pointwise layers with a long reduction (>= 192) and 2 K - 64 K rows: forward (A' * W^T, BatchNorm partial sums

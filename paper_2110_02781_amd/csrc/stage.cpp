@@ -253,8 +253,9 @@ struct ftp_stage {
   // Weight gradients depend on nothing downstream, so in backward they run on a second stream next to the
   // data-gradient chain: fork after dz is formed, join before that dz buffer is overwritten / at the end.
   hipStream_t side = nullptr;
-  hipEvent_t ev_fork[2] = {nullptr, nullptr}, ev_join[2] = {nullptr, nullptr};
-  bool join_pending[2] = {false, false};
+  // fork / join of the side stream: one pair per dz buffer, and a third for the partial sums of the one-pass expand backward
+  hipEvent_t ev_fork[3] = {nullptr, nullptr, nullptr}, ev_join[3] = {nullptr, nullptr, nullptr};
+  bool join_pending[3] = {false, false, false};
   unsigned n_sub_bwd = 0;
   float *bn_part = nullptr, *coef = nullptr, *ws = nullptr, *row_loss = nullptr;
   // A second partial-sum workspace for the weight gradient of the stage's very first layer when the stage forks
@@ -297,7 +298,7 @@ static void stage_free(ftp_stage* s) {
   dfree(s->shared_stash);
   for (int i = 0; i < 5; ++i) dfree(s->gbuf[i]);
   if (s->side) (void)hipStreamDestroy(s->side);
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < 3; ++i) {
     if (s->ev_fork[i]) (void)hipEventDestroy(s->ev_fork[i]);
     if (s->ev_join[i]) (void)hipEventDestroy(s->ev_join[i]);
   }
@@ -417,7 +418,7 @@ extern "C" int ftp_stage_create_ex(const ftp_model* m, int a, int b, int batch, 
     if ((rc = dev_alloc(&s->gbuf[i], max_act))) { stage_free(s); return rc; }
   {
     hipError_t e = hipStreamCreateWithFlags(&s->side, hipStreamNonBlocking);     // default priority
-    for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+    for (int i = 0; i < 3 && e == hipSuccess; ++i) {
       e = hipEventCreateWithFlags(&s->ev_fork[i], hipEventDisableTiming);
       if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_join[i], hipEventDisableTiming);
     }
@@ -863,8 +864,19 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
     bn_bwd_reduce(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->bn_part, &P);
     bn_bwd_finalize(st, s->bn_part, P, M, C, W.w32 + p.p_off + sb.gamma_off, stt, stt + C, s->grads + p.p_off + sb.gamma_off,
                     s->grads + p.p_off + sb.beta_off, s->coef);
+    // the sum of the kernel's partial weight gradients is off the data-gradient chain: it goes to the side stream,
+    // and the next user of the partial buffer waits for it
+    const bool aside = stage_overlaps(s);
+    if (s->join_pending[2]) {
+      HIP_TRY(hipStreamWaitEvent(st, s->ev_join[2], 0));
+      s->join_pending[2] = false;
+    }
     pw_bwd_fused(st, dA, out, s->coef, conv_w(s, W, p.p_off + sb.w_off), in.z, res, M, g.Cin, g.Cout, s->ws_fused,
-                 s->grads + p.p_off + sb.w_off, dIn);
+                 s->grads + p.p_off + sb.w_off, dIn, aside ? s->side : st, aside ? s->ev_fork[2] : nullptr);
+    if (aside) {
+      HIP_TRY(hipEventRecord(s->ev_join[2], s->side));
+      s->join_pending[2] = true;
+    }
     return FTP_OK;
   }
   if (mode != BWD_FROM_DZ) {
@@ -939,7 +951,7 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
 
 // all side-stream work of this backward is ordered before whatever the caller enqueues next
 static int join_side(ftp_stage* s, hipStream_t st) {
-  for (int b = 0; b < 2; ++b)
+  for (int b = 0; b < 3; ++b)
     if (s->join_pending[b]) {
       HIP_TRY(hipStreamWaitEvent(st, s->ev_join[b], 0));
       s->join_pending[b] = false;
