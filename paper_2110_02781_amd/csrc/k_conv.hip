@@ -461,9 +461,11 @@ __device__ __forceinline__ void dw_stage_weights(float* wl, const T* __restrict_
 // S = 1 is the data gradient with src = dz)
 // RL = pixels per run: four at stride 1; two at stride 2, where a run of four keeps 9 patch vectors and 4 sums live
 // (111 registers, four resident blocks per CU) and a 4 x 8 tile has work for only 96 of the 256 threads
-template <typename T, int S, bool FLIP, int RL = (S == 2 ? 2 : 4)>
+// STATS: the block also leaves the per-channel sums of its stored outputs and of their squares, one partial per tile
+// ([tile][2][C], what bn_stats would compute in a pass of its own); for layers with at most kMaxPartials tiles
+template <typename T, int S, bool FLIP, bool STATS = false, int RL = (S == 2 ? 2 : 4)>
 __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ w, DwPlan d, int Hin, int Win, int Hout,
-                                                 int Wout, int C, T* __restrict__ out) {
+                                                 int Wout, int C, T* __restrict__ out, float* __restrict__ stats = nullptr) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   if (FLIP) __builtin_amdgcn_s_setprio(3);   // data-gradient chain: ahead of the weight-gradient stream's waves
   T* patch = reinterpret_cast<T*>(smem_raw);
@@ -479,12 +481,14 @@ __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ 
   __syncthreads();
   const int QB = 2 * d.CGB, seg0 = dw_div(threadIdx.x, d.m_qb), cq = threadIdx.x - seg0 * QB;
   const int c4 = cq * 4, gc = cg0 * 8 + c4;
-  if (seg0 >= d.spp || gc >= C) return;
+  const bool worker = seg0 < d.spp && gc < C;
+  if (!STATS && !worker) return;
   float4 wr[9];
 #pragma unroll
-  for (int t = 0; t < 9; ++t) wr[t] = ld4(wl + (size_t)(FLIP ? 8 - t : t) * d.CGB * 8 + c4);
+  for (int t = 0; t < 9; ++t) wr[t] = worker ? ld4(wl + (size_t)(FLIP ? 8 - t : t) * d.CGB * 8 + c4) : make_float4(0.f, 0.f, 0.f, 0.f);
   const int vs = d.CGB * 8;                       // floats per patch pixel
-  for (int sg = seg0; sg < d.nseg; sg += d.spp) {
+  float4 s1 = make_float4(0.f, 0.f, 0.f, 0.f), s2 = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int sg = worker ? seg0 : d.nseg; sg < d.nseg; sg += d.spp) {
     const int hl = dw_div(sg, d.m_segw), wl0 = (sg - hl * d.segw) * RL;
     const int ho = ho0 + hl;
     if (ho >= Hout) continue;
@@ -505,7 +509,32 @@ __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ 
     T* dst = out + (((size_t)n * Hout + ho) * Wout + wo0 + wl0) * C + gc;
 #pragma unroll
     for (int o = 0; o < RL; ++o)
-      if (wo0 + wl0 + o < Wout) store4(dst + (size_t)o * C, acc[o]);
+      if (wo0 + wl0 + o < Wout) {
+        store4(dst + (size_t)o * C, acc[o]);
+        if (STATS) {                              // statistics of the values as stored
+          const float4 r = make_float4(round_to<T>(acc[o].x), round_to<T>(acc[o].y), round_to<T>(acc[o].z), round_to<T>(acc[o].w));
+          s1.x += r.x; s1.y += r.y; s1.z += r.z; s1.w += r.w;
+          s2 = fma4(r, r, s2);
+        }
+      }
+  }
+  if (STATS) {
+    // the runs of a channel quad are spread over spp threads: through LDS (the patch is no longer needed), summed in
+    // a fixed order by one thread per channel and value
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(smem_raw);            // [spp][QB][8]
+    if (worker) {
+      float* r = red + ((size_t)seg0 * QB + cq) * 8;
+      r[0] = s1.x; r[1] = s1.y; r[2] = s1.z; r[3] = s1.w; r[4] = s2.x; r[5] = s2.y; r[6] = s2.z; r[7] = s2.w;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < QB * 8; i += 256) {
+      const int q = i >> 3, e = i & 7, c = cg0 * 8 + q * 4 + (e & 3);
+      if (c >= C) continue;
+      float t = 0.f;
+      for (int sgi = 0; sgi < d.spp; ++sgi) t += red[((size_t)sgi * QB + q) * 8 + e];
+      stats[((size_t)tile * 2 + (e >> 2)) * C + c] = t;
+    }
   }
 }
 
@@ -524,7 +553,14 @@ static bool dw_check_plan(DwPlan& d, int segs = kDwSegs) {
   return true;
 }
 
-void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z) {
+// the depthwise forward can leave the BatchNorm partial sums itself when its tiles are few enough to be the partials
+int dw_fwd_stats_ok(int dt, const ConvGeom& g) {
+  const int es = dt == 0 ? 4 : 2;
+  const DwPlan d = dw_plan(g.Cout, es, g.stride == 2, g.Hout, g.Wout);
+  return (size_t)g.N * d.tiles_h * d.tiles_w <= (size_t)kMaxPartials;
+}
+
+void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z, float* stats, int* P_out) {
   const int es = dt == 0 ? 4 : 2, s = g.stride;
   DwPlan d = dw_plan(g.Cout, es, s == 2, g.Hout, g.Wout);
   const int run = s == 2 ? 2 : 4;                // pixels per run, as the kernel's RL
@@ -540,6 +576,22 @@ void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, 
   KScope ks(st, "dw_fwd", ((double)g.N * g.Hin * g.Win * g.Cout + (double)total * g.Cout) * es, 18.0 * total * g.Cout,
             (long)total, g.Cout, g.stride);
   const unsigned grid = (unsigned)d.ntiles * d.nslab;
+  if (stats) {
+    if (d.ntiles > kMaxPartials) { launch_plan_failed("depthwise forward with statistics: more tiles than partial sums"); return; }
+    // the reduction reuses the patch's LDS: [spp][2*CGB][8] floats
+    size_t lds = dw_lds_bytes(d, es);
+    const size_t red = (size_t)d.spp * 2 * d.CGB * 8 * sizeof(float);
+    if (lds < red) lds = red;
+    if (s == 1) {
+      FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 1, false, true>), dim3(grid), dim3(256), lds, st, v, (const T*)w, d,
+                                          g.Hin, g.Win, g.Hout, g.Wout, g.Cout, (T*)z, stats));
+    } else {
+      FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 2, false, true>), dim3(grid), dim3(256), lds, st, v, (const T*)w, d,
+                                          g.Hin, g.Win, g.Hout, g.Wout, g.Cout, (T*)z, stats));
+    }
+    *P_out = d.ntiles;
+    return;
+  }
   if (s == 1) {
     FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 1, false>), dim3(grid), dim3(256), dw_lds_bytes(d, es), st, v, (const T*)w, d,
                                         g.Hin, g.Win, g.Hout, g.Wout, g.Cout, (T*)z));

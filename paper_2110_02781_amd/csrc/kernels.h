@@ -142,7 +142,10 @@ void reduce_partials(hipStream_t st, const float* ws, int P, size_t QC, int C, s
                      float* g, int valid_c = -1);
 
 // ---- depthwise 3x3 ----------------------------------------------------------------
-void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z);
+// stats != nullptr (only if dw_fwd_stats_ok): the kernel also writes the BatchNorm partial sums [*P_out][2][C] of z
+int dw_fwd_stats_ok(int dt, const ConvGeom& g);
+void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, void* z, float* stats = nullptr,
+            int* P_out = nullptr);
 // convolution + BatchNorm statistics + finalize in one launch for short tensors (dw_fwd_bn_small_ok)
 int dw_fwd_bn_small_ok(const ConvGeom& g);
 // pend.partial != nullptr: the BatchNorm of the input is still partial sums (pw_fwd's epilogue); the kernel

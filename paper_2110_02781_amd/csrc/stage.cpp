@@ -631,9 +631,13 @@ static void sub_forward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, HVi
     conv_direct_fwd_gemm(s->dt, st, in, w, g, s->im2col, s->ws, z, s->bn_part, &P);
     s->im2col_of = z;
   } else {
-    if (sb.type == SUB_DW) dw_fwd(s->dt, st, in, w, g, z);
-    else conv_direct_fwd(s->dt, st, in, w, g, z);
-    bn_stats(s->dt, st, z, M, g.Cout, s->bn_part, &P);
+    if (sb.type == SUB_DW && dw_fwd_stats_ok(s->dt, g)) {
+      dw_fwd(s->dt, st, in, w, g, z, s->bn_part, &P);           // few tiles: their sums are the partials
+    } else {
+      if (sb.type == SUB_DW) dw_fwd(s->dt, st, in, w, g, z);
+      else conv_direct_fwd(s->dt, st, in, w, g, z);
+      bn_stats(s->dt, st, z, M, g.Cout, s->bn_part, &P);
+    }
   }
   bn_finalize(st, s->bn_part, P, M, C, gamma, beta, stt, stt + C, stt + 2 * C, stt + 3 * C, rm, rv, kBnEps, s->bn_mom);
 }
