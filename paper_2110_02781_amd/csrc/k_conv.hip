@@ -461,11 +461,16 @@ __device__ __forceinline__ void dw_stage_weights(float* wl, const T* __restrict_
 // S = 1 is the data gradient with src = dz)
 // RL = pixels per run: four at stride 1; two at stride 2, where a run of four keeps 9 patch vectors and 4 sums live
 // (111 registers, four resident blocks per CU) and a 4 x 8 tile has work for only 96 of the 256 threads
-// STATS: the block also leaves the per-channel sums of its stored outputs and of their squares, one partial per tile
-// ([tile][2][C], what bn_stats would compute in a pass of its own); for layers with at most kMaxPartials tiles
-template <typename T, int S, bool FLIP, bool STATS = false, int RL = (S == 2 ? 2 : 4)>
+// STATS (layers with at most kMaxPartials tiles): the block also leaves per-channel sums over its stored outputs, one
+// partial per tile ([tile][2][C]).  1: the sum and the sum of squares (what bn_stats would compute in a pass of its
+// own).  2, for the data gradient: the output is the gradient dA of the BatchNorm + activation in front of this layer,
+// whose conv output zp sits at the same positions; the sums are those of bn_bwd_reduce (dY = dA where the activation
+// passes, sum of dY and of dY * zp), so that BatchNorm's backward starts at its finalize.
+struct DwPrev { const void* z; const float* scale; const float* shift; int act; };
+template <typename T, int S, bool FLIP, int STATS = 0, int RL = (S == 2 ? 2 : 4)>
 __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ w, DwPlan d, int Hin, int Win, int Hout,
-                                                 int Wout, int C, T* __restrict__ out, float* __restrict__ stats = nullptr) {
+                                                 int Wout, int C, T* __restrict__ out, float* __restrict__ stats = nullptr,
+                                                 DwPrev prev = DwPrev{nullptr, nullptr, nullptr, 0}) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   if (FLIP) __builtin_amdgcn_s_setprio(3);   // data-gradient chain: ahead of the weight-gradient stream's waves
   T* patch = reinterpret_cast<T*>(smem_raw);
@@ -488,10 +493,22 @@ __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ 
   for (int t = 0; t < 9; ++t) wr[t] = worker ? ld4(wl + (size_t)(FLIP ? 8 - t : t) * d.CGB * 8 + c4) : make_float4(0.f, 0.f, 0.f, 0.f);
   const int vs = d.CGB * 8;                       // floats per patch pixel
   float4 s1 = make_float4(0.f, 0.f, 0.f, 0.f), s2 = make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 psc = make_float4(0.f, 0.f, 0.f, 0.f), psh = psc;
+  if (STATS == 2 && worker) { psc = ld4(prev.scale + gc); psh = ld4(prev.shift + gc); }
+  const float plo = act_lo(prev.act), phi = act_hi(prev.act);
   for (int sg = worker ? seg0 : d.nseg; sg < d.nseg; sg += d.spp) {
     const int hl = dw_div(sg, d.m_segw), wl0 = (sg - hl * d.segw) * RL;
     const int ho = ho0 + hl;
     if (ho >= Hout) continue;
+    float4 zp[RL];
+    if (STATS == 2) {                             // requested before the taps are worked off, used after the stores
+      const T* zrow = reinterpret_cast<const T*>(prev.z) + ((size_t)n * Hout + ho) * Wout * C + gc;
+#pragma unroll
+      for (int o = 0; o < RL; ++o) {              // a pixel past the row's end reads the row's first pixel and is not used
+        const int wq = wo0 + wl0 + o;
+        zp[o] = load4(zrow + (size_t)(wq < Wout ? wq : 0) * C);
+      }
+    }
     float4 acc[RL];
 #pragma unroll
     for (int o = 0; o < RL; ++o) acc[o] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -511,10 +528,17 @@ __global__ __launch_bounds__(256) void dw_conv_k(View in, const T* __restrict__ 
     for (int o = 0; o < RL; ++o)
       if (wo0 + wl0 + o < Wout) {
         store4(dst + (size_t)o * C, acc[o]);
-        if (STATS) {                              // statistics of the values as stored
-          const float4 r = make_float4(round_to<T>(acc[o].x), round_to<T>(acc[o].y), round_to<T>(acc[o].z), round_to<T>(acc[o].w));
+        if (STATS) {                              // sums over the values as stored
+          float4 r = make_float4(round_to<T>(acc[o].x), round_to<T>(acc[o].y), round_to<T>(acc[o].z), round_to<T>(acc[o].w));
+          float4 f = r;
+          if (STATS == 2) {
+            const float4 y = fma4(zp[o], psc, psh);
+            r.x = (y.x > plo && y.x < phi) ? r.x : 0.f; r.y = (y.y > plo && y.y < phi) ? r.y : 0.f;
+            r.z = (y.z > plo && y.z < phi) ? r.z : 0.f; r.w = (y.w > plo && y.w < phi) ? r.w : 0.f;
+            f = zp[o];
+          }
           s1.x += r.x; s1.y += r.y; s1.z += r.z; s1.w += r.w;
-          s2 = fma4(r, r, s2);
+          s2 = fma4(r, f, s2);
         }
       }
   }
@@ -583,10 +607,10 @@ void dw_fwd(int dt, hipStream_t st, HView in, const void* w, const ConvGeom& g, 
     const size_t red = (size_t)d.spp * 2 * d.CGB * 8 * sizeof(float);
     if (lds < red) lds = red;
     if (s == 1) {
-      FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 1, false, true>), dim3(grid), dim3(256), lds, st, v, (const T*)w, d,
+      FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 1, false, 1>), dim3(grid), dim3(256), lds, st, v, (const T*)w, d,
                                           g.Hin, g.Win, g.Hout, g.Wout, g.Cout, (T*)z, stats));
     } else {
-      FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 2, false, true>), dim3(grid), dim3(256), lds, st, v, (const T*)w, d,
+      FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 2, false, 1>), dim3(grid), dim3(256), lds, st, v, (const T*)w, d,
                                           g.Hin, g.Win, g.Hout, g.Wout, g.Cout, (T*)z, stats));
     }
     *P_out = d.ntiles;
@@ -1028,7 +1052,16 @@ __global__ __launch_bounds__(256) void dw_dgrad_s2_k(const T* __restrict__ dz, c
   }
 }
 
-void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvGeom& g, void* dIn) {
+// the stride-1 data gradient can leave the backward sums of the BatchNorm in front (dw_conv_k, STATS = 2) when its
+// tiles are few enough to be the partials
+int dw_dgrad_sums_ok(int dt, const ConvGeom& g) {
+  if (g.stride != 1) return 0;
+  const DwPlan d = dw_plan(g.Cout, dt == 0 ? 4 : 2, false, g.Hin, g.Win);
+  return (size_t)g.N * d.tiles_h * d.tiles_w <= (size_t)kMaxPartials;
+}
+
+void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvGeom& g, void* dIn, HView prev, float* sums,
+              int* P_out) {
   const int es = dt == 0 ? 4 : 2;
   size_t total = (size_t)g.N * g.Hin * g.Win;
   KScope ks(st, "dw_dgrad", ((double)total * g.Cout + (double)g.N * g.Hout * g.Wout * g.Cout) * es, 18.0 * g.N * g.Hout * g.Wout * g.Cout,
@@ -1043,6 +1076,17 @@ void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvG
     d.PW = d.segw * 4 + 2;
     if (!dw_check_plan(d)) return;
     View v{dz, nullptr, nullptr, 0};
+    if (sums) {
+      if (d.ntiles > kMaxPartials || !prev.scale) { launch_plan_failed("depthwise data gradient with BatchNorm sums: not for this layer"); return; }
+      size_t lds = dw_lds_bytes(d, es);
+      const size_t red = (size_t)d.spp * 2 * d.CGB * 8 * sizeof(float);
+      if (lds < red) lds = red;
+      const DwPrev pv{prev.z, prev.scale, prev.shift, prev.act};
+      FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 1, true, 2>), dim3(grid), dim3(256), lds, st, v, (const T*)w, d,
+                                          g.Hout, g.Wout, g.Hin, g.Win, g.Cout, (T*)dIn, sums, pv));
+      *P_out = d.ntiles;
+      return;
+    }
     FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_conv_k<T, 1, true>), dim3(grid), dim3(256), dw_lds_bytes(d, es), st, v, (const T*)w, d,
                                         g.Hout, g.Wout, g.Hin, g.Win, g.Cout, (T*)dIn));
   } else {

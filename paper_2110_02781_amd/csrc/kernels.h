@@ -161,7 +161,11 @@ int dw_bwd_small_ok(const ConvGeom& g);
 void dw_bwd_small(int dt, hipStream_t st, const void* dz, const BnBwdIn& bo, const void* w, HView in, const ConvGeom& g,
                   const float* gamma, const float* mean, const float* invstd, float* g_w, float* g_gamma, float* g_beta,
                   void* dz_prev);
-void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvGeom& g, void* dIn);
+// sums != nullptr (only if dw_dgrad_sums_ok and prev is a view): the kernel also leaves the partial sums
+// [*P_out][2][C] that bn_bwd_reduce would compute for the BatchNorm + activation `prev` in front of this layer
+int dw_dgrad_sums_ok(int dt, const ConvGeom& g);
+void dw_dgrad(int dt, hipStream_t st, const void* dz, const void* w, const ConvGeom& g, void* dIn, HView prev = HView{},
+              float* sums = nullptr, int* P_out = nullptr);
 size_t dw_wgrad_ws(const ConvGeom& g);
 void dw_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, float* ws, float* g_w);
 

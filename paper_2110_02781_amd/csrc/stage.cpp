@@ -273,6 +273,10 @@ struct ftp_stage {
   // patch matrix leaves it behind; if nothing has used the buffer since, the weight gradient of the same layer and
   // slot takes it as it is instead of writing the same matrix again.
   const void* im2col_of = nullptr;
+  // The gradient tensor whose BatchNorm-backward partial sums bn_part holds already (left there by the depthwise data
+  // gradient that produced it), and how many partials; nullptr: none.
+  const void* bwd_sums_of = nullptr;
+  int bwd_sums_P = 0;
   size_t im2col_elems = 0;
   size_t ws_floats = 0;
   int max_c = 0;
@@ -865,7 +869,9 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
   if (mode == BWD_FULL && sb.type == SUB_PW && dIn && s->ws_fused && !bn_bwd_small_ok(M, C) &&
       pw_bwd_fused_ok(s->dt, M, g.Cin, g.Cout, in) && pw_bwd_fused_ws(M, g.Cin, g.Cout) <= s->ws_fused_floats) {
     int P = 0;
-    bn_bwd_reduce(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->bn_part, &P);
+    if (s->bwd_sums_of == dA) P = s->bwd_sums_P;
+    else bn_bwd_reduce(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->bn_part, &P);
+    s->bwd_sums_of = nullptr;
     bn_bwd_finalize(st, s->bn_part, P, M, C, W.w32 + p.p_off + sb.gamma_off, stt, stt + C, s->grads + p.p_off + sb.gamma_off,
                     s->grads + p.p_off + sb.beta_off, s->coef);
     // the sum of the kernel's partial weight gradients is off the data-gradient chain: it goes to the side stream,
@@ -889,7 +895,8 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
     const bool small = bn_bwd_small_ok(M, C) != 0;
     if (!small) {
       int P = 0;
-      bn_bwd_reduce(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->bn_part, &P);
+      if (s->bwd_sums_of == dA) P = s->bwd_sums_P;          // the producer of dA has left the sums
+      else bn_bwd_reduce(s->dt, st, dA, out.z, M, C, out.scale, out.shift, sb.act, s->bn_part, &P);
       bn_bwd_finalize(st, s->bn_part, P, M, C, W.w32 + p.p_off + sb.gamma_off, stt, stt + C, s->grads + p.p_off + sb.gamma_off,
                       s->grads + p.p_off + sb.beta_off, s->coef);
     }
@@ -908,7 +915,20 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
   // takes nearly twice as long.  The data gradient goes first, alone; the weight gradient then shares the GPU with
   // the memory-bound BatchNorm backward of the layer in front.
   const bool dgrad_first = overlap && sb.type == SUB_DW && dIn != nullptr;
-  if (dgrad_first) dw_dgrad(s->dt, st, dz, conv_w(s, W, p.p_off + sb.w_off), g, dIn);
+  s->bwd_sums_of = nullptr;
+  // a depthwise layer behind a BatchNorm + activation of the same unit (the expand layer's): its data gradient is that
+  // BatchNorm's dA and can leave the backward sums on the way
+  const bool with_sums = sb.type == SUB_DW && dIn != nullptr && mode == BWD_FULL && k > 0 && in.scale != nullptr &&
+                         !bn_bwd_small_ok((size_t)s->batch * g.Hin * g.Win, g.Cout) && dw_dgrad_sums_ok(s->dt, g);
+  auto run_dw_dgrad = [&]() {
+    if (with_sums) {
+      dw_dgrad(s->dt, st, dz, conv_w(s, W, p.p_off + sb.w_off), g, dIn, in, s->bn_part, &s->bwd_sums_P);
+      s->bwd_sums_of = dIn;
+    } else {
+      dw_dgrad(s->dt, st, dz, conv_w(s, W, p.p_off + sb.w_off), g, dIn);
+    }
+  };
+  if (dgrad_first) run_dw_dgrad();
   // the first layer of the stage, last in this pass and without a data gradient: its weight gradient is all that is
   // left for this stream, so it runs here with a workspace of its own while the side stream works off its queue
   const bool tail_here = overlap && dIn == nullptr && s->ws_tail != nullptr && &p == &s->plan[0] && k == 0;
@@ -948,7 +968,7 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
       else conv_direct_dgrad(s->dt, st, dz, w, g, dIn);
     }
     else if (sb.type == SUB_PW) pw_dgrad(s->dt, st, dz, w, res, M, g.Cin, g.Cout, dIn);
-    else if (!dgrad_first) dw_dgrad(s->dt, st, dz, w, g, dIn);
+    else if (!dgrad_first) run_dw_dgrad();
   }
   return FTP_OK;
 }
