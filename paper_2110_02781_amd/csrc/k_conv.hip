@@ -1473,6 +1473,250 @@ static DwPlan dw_wgrad_plan(const ConvGeom& g, int es, size_t* lds) {
   return d;
 }
 
+// ---- depthwise weight gradient, bfloat16: rows staged through LDS ---------------------------------------------
+// The marching kernel above reads memory with one 4-byte access per lane.  With a power-of-two channel count a
+// wavefront's access is exactly one aligned pixel and it streams at 4.4 - 4.7 TB/s; with 48, 144, 192 ... channels
+// (every layer of a width-1.4 MobileNetV2) pixels straddle cache lines and a narrow tail slab needs accesses of its
+// own: 2.1 - 3.4 TB/s, although the arithmetic alone would take a quarter of the time (measured with all rows
+// redirected to one cached row).  Here the memory side is decoupled from the channel count: a block owns a band of
+// WB output columns of one image (all channels of a slab of at most 256) and walks down a segment of its rows; the
+// S new input rows of a step and the dz row are contiguous runs of several KB in memory, fetched with 16-byte
+// vectors a step ahead, put through the view once, and kept in an LDS ring of rows; a thread owns one channel QUAD
+// and every NCG-th column of the band and reads its nine taps from the ring (8-byte LDS reads, no bounds logic: the
+// ring holds zeros where the image ends).  One barrier per step; one fp32 partial [9][C] per block at the end.
+enum { kDwRowsNV = 4, kDwRowsDzNV = 2, kDwRowsMaxCpt = 4 };
+struct DwRowsArgs {
+  const bf16_t* dz;
+  const bf16_t* in;
+  const float* scale;
+  const float* shift;
+  int act;
+  float* ws;
+  int Hin, Win, Hout, Wout, C;
+  int CS, nslab;            // channels per slab (a multiple of 8), slabs
+  int Q, NCG, CPT, WB;      // channel quads of a slab, column groups, columns per thread and step, columns per band
+  int WIN;                  // input columns under a band
+  int bands, nseg, seglen;  // bands across, row segments per image, output rows per segment
+  int P;                    // blocks (= partials) per slab: N * bands * nseg
+};
+
+template <int S, bool VIEW>
+__global__ __launch_bounds__(256) void dw_wgrad_rows_k(DwRowsArgs a) {
+  constexpr int RING = S == 1 ? 4 : 5;
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  const int tid = threadIdx.x;
+  const int lb = xcd_logical_block();
+  const int si = lb % a.nslab, pb = lb / a.nslab;             // the slabs of a band run side by side
+  const int band = pb % a.bands, rest = pb / a.bands, seg = rest % a.nseg, n = rest / a.nseg;
+  const int c0 = si * a.CS, cs = a.C - c0 < a.CS ? a.C - c0 : a.CS;      // this slab's channels
+  const int CS = a.CS, WIN = a.WIN, WB = a.WB;
+  const int wb0 = band * WB, wi0 = wb0 * S - 1;
+  const int h0 = seg * a.seglen, h1 = h0 + a.seglen < a.Hout ? h0 + a.seglen : a.Hout;
+  const int rowElems = WIN * CS;                               // one ring slot
+  bf16_t* ring = reinterpret_cast<bf16_t*>(smem_raw);          // [RING][WIN][CS]
+  bf16_t* dzs = ring + RING * rowElems;                        // [2][WB][CS]
+  const bf16_t* img = a.in + (size_t)n * a.Hin * a.Win * a.C + c0;
+  const bf16_t* dimg = a.dz + (size_t)n * a.Hout * a.Wout * a.C + c0;
+  const int VR = CS / 8;                                       // vectors per pixel of the slab
+  const int nin = WIN * VR, ndz = WB * VR;                     // vectors per input row, per dz row
+
+  // ---- staging: vector v of a row is (column v / VR, channels 8 * (v % VR) ..); a thread's vectors are the same
+  // in every row, so their offsets are worked out once ----
+  float* vsc = reinterpret_cast<float*>(dzs + 2 * WB * CS);    // [CS] scale, [CS] shift of the view
+  if (VIEW) {
+    for (int i = tid; i < CS; i += 256) {
+      vsc[i] = i < cs ? a.scale[c0 + i] : 0.f;
+      vsc[CS + i] = i < cs ? a.shift[c0 + i] : 0.f;
+    }
+  }
+  int goff[kDwRowsNV], loff[kDwRowsNV];                        // offset inside an image row (-1: nothing there), inside a ring slot
+#pragma unroll
+  for (int q = 0; q < kDwRowsNV; ++q) {
+    const int v = tid + q * 256;
+    const int col = v / VR, ch = (v - col * VR) * 8, wi = wi0 + col;
+    loff[q] = col * CS + ch;
+    goff[q] = (v < nin && wi >= 0 && wi < a.Win && ch < cs) ? wi * a.C + ch : -1;
+  }
+  int dgoff[kDwRowsDzNV], dloff[kDwRowsDzNV];
+#pragma unroll
+  for (int q = 0; q < kDwRowsDzNV; ++q) {
+    const int v = tid + q * 256;
+    const int col = v / VR, ch = (v - col * VR) * 8;
+    dloff[q] = col * CS + ch;
+    dgoff[q] = (v < ndz && wb0 + col < a.Wout && ch < cs) ? (wb0 + col) * a.C + ch : -1;
+  }
+  const int nq = (nin + 255) / 256;                            // passes a row takes (uniform)
+  uint4 rin[S][kDwRowsNV], rdz[kDwRowsDzNV];
+  unsigned okin[S], okdz;
+  // an input row y of the image; the ring holds zeros outside the image and past the slab's channels
+  auto fetch_row = [&](uint4* r, unsigned& ok, const int y) __attribute__((always_inline)) {
+    ok = 0;
+    const bool yin = y >= 0 && y < a.Hin;
+    const bf16_t* rowp = img + (size_t)(yin ? y : 0) * a.Win * a.C;
+#pragma unroll
+    for (int q = 0; q < kDwRowsNV; ++q) {
+      if (q >= nq) break;
+      const bool in = yin && goff[q] >= 0;
+      r[q] = *reinterpret_cast<const uint4*>(rowp + (in ? goff[q] : 0));
+      ok |= (in ? 1u : 0u) << q;
+    }
+  };
+  auto commit_row = [&](const uint4* r, const unsigned ok, const int y) __attribute__((always_inline)) {
+    bf16_t* dst = ring + ((y + RING) % RING) * rowElems;
+    const float lo = act_lo(a.act), hi = act_hi(a.act);
+#pragma unroll
+    for (int q = 0; q < kDwRowsNV; ++q) {
+      if (q >= nq) break;
+      if (tid + q * 256 >= nin) break;
+      uint4 o = make_uint4(0u, 0u, 0u, 0u);
+      if (ok & (1u << q)) {
+        o = r[q];
+        if (VIEW) {
+          Raw<bf16_t> raw; raw.a = o;
+          float f[8], sc[8], sh[8];
+          raw_unpack(raw, f);
+          const int ch = loff[q] % CS;
+          load8(vsc + ch, sc);
+          load8(vsc + CS + ch, sh);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) f[e] = clamp_act(fmaf(f[e], sc[e], sh[e]), lo, hi);
+          o.x = f32x2_to_bf16x2(f[0], f[1]); o.y = f32x2_to_bf16x2(f[2], f[3]);
+          o.z = f32x2_to_bf16x2(f[4], f[5]); o.w = f32x2_to_bf16x2(f[6], f[7]);
+        }
+      }
+      *reinterpret_cast<uint4*>(dst + loff[q]) = o;
+    }
+  };
+  auto fetch_dz = [&](const int ho) __attribute__((always_inline)) {
+    okdz = 0;
+    const bf16_t* rowp = dimg + (size_t)(ho < h1 ? ho : h0) * a.Wout * a.C;
+#pragma unroll
+    for (int q = 0; q < kDwRowsDzNV; ++q) {
+      if (q * 256 >= ndz) break;
+      const bool in = dgoff[q] >= 0 && ho < h1;
+      rdz[q] = *reinterpret_cast<const uint4*>(rowp + (in ? dgoff[q] : 0));
+      okdz |= (in ? 1u : 0u) << q;
+    }
+  };
+  auto commit_dz = [&](const int ho) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < kDwRowsDzNV; ++q) {
+      if (tid + q * 256 >= ndz) break;
+      *reinterpret_cast<uint4*>(dzs + (ho & 1) * WB * CS + dloff[q]) = (okdz & (1u << q)) ? rdz[q] : make_uint4(0u, 0u, 0u, 0u);
+    }
+  };
+
+  // ---- this thread's work: channel quad q4 of the slab, columns cgi + j * NCG of the band ----
+  const int q4 = tid % a.Q, cgi = tid / a.Q;
+  const bool worker = cgi < a.NCG && q4 * 4 < cs;
+  float4 acc[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) acc[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+
+  if (VIEW) __syncthreads();                                   // the view vectors are in LDS
+  // rows above the first step's new ones
+  if (S == 1) {
+    fetch_row(rin[0], okin[0], h0 - 1);
+    commit_row(rin[0], okin[0], h0 - 1);
+    fetch_row(rin[0], okin[0], h0);
+    commit_row(rin[0], okin[0], h0);
+  } else {
+    fetch_row(rin[0], okin[0], 2 * h0 - 1);
+    commit_row(rin[0], okin[0], 2 * h0 - 1);
+  }
+  // the new rows of step ho: S == 1: row ho + 1; S == 2: rows 2 ho and 2 ho + 1
+  auto fetch_step = [&](const int ho) __attribute__((always_inline)) {
+#pragma unroll
+    for (int r = 0; r < S; ++r) fetch_row(rin[r], okin[r], S == 1 ? ho + 1 : 2 * ho + r);
+    fetch_dz(ho);
+  };
+  fetch_step(h0);
+  for (int ho = h0; ho < h1; ++ho) {
+#pragma unroll
+    for (int r = 0; r < S; ++r) commit_row(rin[r], okin[r], S == 1 ? ho + 1 : 2 * ho + r);
+    commit_dz(ho);
+    __syncthreads();          // also: every thread is done with the step before last, whose ring slots are written next
+    fetch_step(ho + 1);       // past the segment: rows of the image that are simply not used (dz past h1 is zero)
+    if (worker) {
+      const bf16_t* dzr = dzs + (ho & 1) * WB * CS + q4 * 4;
+      const bf16_t* rows[3];
+#pragma unroll
+      for (int ky = 0; ky < 3; ++ky) rows[ky] = ring + ((ho * S - 1 + ky + RING) % RING) * rowElems + q4 * 4;
+#pragma unroll
+      for (int j = 0; j < kDwRowsMaxCpt; ++j) {
+        if (j >= a.CPT) break;
+        const int lc = cgi + j * a.NCG;                        // column of the band
+        const float4 d = load4(dzr + lc * CS);
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky) {
+          const bf16_t* row = rows[ky] + (lc * S) * CS;
+#pragma unroll
+          for (int kx = 0; kx < 3; ++kx) acc[ky * 3 + kx] = fma4(d, load4(row + kx * CS), acc[ky * 3 + kx]);
+        }
+      }
+    }
+  }
+  // ---- the block's partial: the column groups of a channel quad in a fixed order ----
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(smem_raw);             // [NCG][9][CS]
+  if (worker) {
+#pragma unroll
+    for (int t = 0; t < 9; ++t) *reinterpret_cast<float4*>(red + ((size_t)cgi * 9 + t) * CS + q4 * 4) = acc[t];
+  }
+  __syncthreads();
+  for (int i = tid; i < 9 * cs; i += 256) {
+    const int t = i / cs, c = i - t * cs;
+    float tot = 0.f;
+    for (int g = 0; g < a.NCG; ++g) tot += red[((size_t)g * 9 + t) * CS + c];
+    a.ws[((size_t)pb * 9 + t) * a.C + c0 + c] = tot;
+  }
+}
+
+static bool dw_rows_plan(const ConvGeom& g, DwRowsArgs* a, size_t* lds) {
+  const int S = g.stride, C = g.Cout;
+  if (C % 8 || (S != 1 && S != 2) || g.kh != 3 || g.kw != 3) return false;
+  a->nslab = (C + 255) / 256;
+  a->CS = ((C + a->nslab - 1) / a->nslab + 7) / 8 * 8;
+  a->Q = a->CS / 4;
+  a->NCG = 256 / a->Q;
+  if (a->NCG < 1) return false;
+  if (a->NCG > g.Wout) a->NCG = g.Wout;
+  // columns per thread and step
+  // ring rows of about 8 KB at stride 2, 4 KB at stride 1, and about 1024 / 2048 blocks: measured on the 112 x 112 layers
+  const double row_bytes = S == 2 ? 8192.0 : 4096.0, want_blocks = S == 2 ? 1024.0 : 2048.0;
+  int cpt = (int)(row_bytes / ((double)a->NCG * S * a->CS * 2) + 0.5);
+  if (cpt < 1) cpt = 1;
+  if (cpt > kDwRowsMaxCpt) cpt = kDwRowsMaxCpt;
+  while (cpt > 1 && a->NCG * (cpt - 1) >= g.Wout) --cpt;
+  a->CPT = cpt;
+  a->WB = a->NCG * cpt;
+  a->WIN = (a->WB - 1) * S + 3;
+  a->bands = (g.Wout + a->WB - 1) / a->WB;
+  while (a->CPT > 1 && ((size_t)a->WIN * (a->CS / 8) > (size_t)kDwRowsNV * 256 || (size_t)a->WB * (a->CS / 8) > (size_t)kDwRowsDzNV * 256)) {
+    --a->CPT;
+    a->WB = a->NCG * a->CPT;
+    a->WIN = (a->WB - 1) * S + 3;
+    a->bands = (g.Wout + a->WB - 1) / a->WB;
+  }
+  if ((size_t)a->WIN * (a->CS / 8) > (size_t)kDwRowsNV * 256 || (size_t)a->WB * (a->CS / 8) > (size_t)kDwRowsDzNV * 256) return false;
+  // row segments, at least 8 rows each
+  const double blocks = (double)g.N * a->bands * a->nslab;
+  int want = (int)(want_blocks / (blocks > 1.0 ? blocks : 1.0) + 0.999);
+  if (want < 1) want = 1;
+  int len = (g.Hout + want - 1) / want;
+  if (len < 8) len = 8;
+  if (len > g.Hout) len = g.Hout;
+  a->seglen = len;
+  a->nseg = (g.Hout + len - 1) / len;
+  a->P = g.N * a->bands * a->nseg;
+  a->Hin = g.Hin; a->Win = g.Win; a->Hout = g.Hout; a->Wout = g.Wout; a->C = C;
+  const int RING = S == 1 ? 4 : 5;
+  const size_t stage = ((size_t)RING * a->WIN + 2 * (size_t)a->WB) * a->CS * sizeof(bf16_t) + 2 * (size_t)a->CS * sizeof(float);
+  const size_t red = (size_t)a->NCG * 9 * a->CS * sizeof(float);
+  *lds = stage > red ? stage : red;
+  return *lds <= 64 * 1024 && a->P <= 65535;
+}
+
 size_t dw_wgrad_ws(const ConvGeom& g) {
   size_t lds;
   DwPlan d = dw_wgrad_plan(g, 4, &lds);          // the float plan has at least as many slabs, the bound holds for both
@@ -1480,11 +1724,40 @@ size_t dw_wgrad_ws(const ConvGeom& g) {
   size_t n = (size_t)(d.nblocks > e.nblocks ? d.nblocks : e.nblocks);
   DwMarchArgs m{};
   if (dw_march_plan(g, &m) && (size_t)m.P > n) n = m.P;
+  DwRowsArgs r{};
+  size_t rl;
+  if (dw_rows_plan(g, &r, &rl) && (size_t)r.P > n) n = r.P;
   return n * 9 * g.Cout;
 }
 
 void dw_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& g, float* ws, float* g_w) {
   const int es = dt == 0 ? 4 : 2;
+  {
+    DwRowsArgs r{};
+    size_t lds;
+    // Where it pays (measured, all layer shapes of the two MobileNetV2 widths): images of 112 x 112 and more whose channel
+    // count the marching kernel has to cut into a wide slab and a narrow tail.  Power-of-two channel counts, and the
+    // smaller images (too few rows per block to hide the step's barrier behind), stay with the marching kernel.
+    DwMarchArgs mm{};
+    const bool tail = dw_march_plan(g, &mm) && mm.nslab > 1;
+    if (dt == 1 && tail && (size_t)g.Hin * g.Win >= (size_t)112 * 112 && dw_rows_plan(g, &r, &lds)) {
+      r.dz = (const bf16_t*)dz; r.in = (const bf16_t*)in.z; r.scale = in.scale; r.shift = in.shift; r.act = in.act; r.ws = ws;
+      {
+        KScope ks(st, "dw_wgrad", ((double)g.N * g.Hin * g.Win * g.Cout + (double)g.N * g.Hout * g.Wout * g.Cout) * es + (double)r.P * 9 * g.Cout * 4,
+                  18.0 * g.N * g.Hout * g.Wout * g.Cout, (long)g.N * g.Hout * g.Wout, g.Cout, g.stride);
+        const dim3 grid((unsigned)r.P * r.nslab), block(256);
+        if (g.stride == 1) {
+          if (in.scale) hipLaunchKernelGGL((dw_wgrad_rows_k<1, true>), grid, block, lds, st, r);
+          else hipLaunchKernelGGL((dw_wgrad_rows_k<1, false>), grid, block, lds, st, r);
+        } else {
+          if (in.scale) hipLaunchKernelGGL((dw_wgrad_rows_k<2, true>), grid, block, lds, st, r);
+          else hipLaunchKernelGGL((dw_wgrad_rows_k<2, false>), grid, block, lds, st, r);
+        }
+      }
+      reduce_partials(st, ws, r.P, (size_t)9 * g.Cout, g.Cout, 1, 9, g_w);
+      return;
+    }
+  }
   DwMarchArgs m{};
   if (dw_march_plan(g, &m)) {
     m.dz = dz; m.in = View{in.z, in.scale, in.shift, in.act}; m.ws = ws;
