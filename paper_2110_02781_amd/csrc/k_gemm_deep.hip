@@ -4,8 +4,8 @@
 // MFMA / HBM balance, so what they need is a GEMM that keeps the matrix cores fed, not a streaming kernel:
 //   * a block owns a (32*S) x (32*T) output tile (S = 2 or 4, T = 2 .. 5) and walks the whole reduction in steps of 64,
 //     its four wavefronts in a 2 x 2 arrangement of (16*S) x (16*T) sub-tiles of v_mfma_f32_16x16x32_bf16;
-//   * both operands go through double-buffered LDS (one barrier per step); the 16-byte vectors of the next two or
-//     three steps are on their way from memory into registers while the current step is multiplied (a layer has about one
+//   * both operands go through double-buffered LDS (one barrier per step); the 16-byte vectors of the next two
+//     steps are on their way from memory into registers while the current step is multiplied (a layer has about one
 //     block per CU and a round trip to memory takes several steps: what hides it is bytes in flight per block);
 //   * the weights of the data gradient are stored [reduction][column]: they are staged as they lie in memory and
 //     read back through the LDS transpose read, so neither mode repacks anything;
@@ -62,8 +62,8 @@ __global__ __launch_bounds__(256) void pw_gemm_deep_k(DeepArgs p) {
   // front of each step.  Through the view a zero row becomes act(shift): such rows (past M) are never stored and are
   // masked out of the statistics; past R the weights are zero, so the products vanish.
   const int xkv = (tid & 7) * 8, xrow = tid >> 3;           // x: 8 threads cover the 64 reduction elements of a row
-  // steps in flight: three where the registers leave room for two blocks per CU (two resident blocks hide each other's
-  // barrier and LDS phases, which is worth more than the third step), two otherwise
+  // steps in flight: two.  A third costs about a hundred registers here, and two resident blocks per CU, which hide each
+  // other's barrier and LDS phases, measured worth more than the third step.
   constexpr int D = 2;
   constexpr uint32_t kPast = 0x80000000u;                   // beyond any operand here (they are smaller than 2 GiB), also after adding a step
   struct Set { uint4 x[S]; uint4 y[T]; };
