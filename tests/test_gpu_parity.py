@@ -80,6 +80,10 @@ SINGLE = [
     ("invres_long_reduction_wide", invres_unit(88, 136, 1, 6), (19, 19, 88), 6),
     ("pw_long_reduction_fwd", conv_unit(264, 72, 1, 1, 1, 0, 0, L.ACT_RELU6), (37, 61, 264), 1),
     ("pw_long_reduction_dgrad", conv_unit(40, 264, 1, 1, 1, 0, 0, L.ACT_RELU6), (37, 61, 40), 1),
+    # images of more than 112 x 112 pixels with 144 / 48 depthwise channels (bfloat16: the depthwise weight gradient that
+    # stages rows through an LDS ring), widths and heights that are no multiple of its column bands or row segments
+    ("invres_row_ring_s2", invres_unit(24, 32, 2, 6), (113, 117, 24), 1),
+    ("invres_row_ring_s1_res", invres_unit(8, 8, 1, 6), (115, 113, 8), 1),
 ]
 
 
