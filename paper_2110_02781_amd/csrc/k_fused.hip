@@ -20,7 +20,7 @@
 
 namespace ftp {
 
-enum { kFusedRows = 64, kFusedBlocks = 256 };   // rows per tile (32 or 64); blocks: one per CU (two where the partials allow)
+enum { kFusedBlocks = 256 };   // blocks: one per CU (two where the partials allow, or where 32-row tiles leave the registers for it)
 
 struct FusedArgs {
   const bf16_t* dA;      // [M][N] gradient of the activated output
@@ -40,8 +40,11 @@ struct FusedArgs {
 
 // NTW: 16-wide tiles of N per wavefront (4 * NTW * 16 >= N), KT: 16-wide tiles of K; IT: passes of the elementwise
 // stage (256 threads cover 256 / (N/8) rows per pass)
-template <int ACT, int NTW, int KT, int IT, bool RES>
+// ROWS: rows per tile, 64 or 32 (the wide layers: ten 16-byte vectors each of dA and z in flight per thread for a 64-row
+// tile put the kernel above 256 registers, one block per CU; with 32 rows two blocks fit and hide each other's phases)
+template <int ACT, int NTW, int KT, int IT, bool RES, int ROWS>
 __global__ __launch_bounds__(256) void pw_bwd_fused_k(FusedArgs p) {
+  constexpr int kFusedRows = ROWS;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   __builtin_amdgcn_s_setprio(3);              // data-gradient chain
   const int LDN = p.NP + 8, LDK = p.KP + 8;
@@ -223,7 +226,7 @@ __global__ __launch_bounds__(256) void pw_bwd_fused_k(FusedArgs p) {
 }
 
 // ---- host side ---------------------------------------------------------------------------------------------
-struct FusedPlan { int NTW, KT, IT, NP, KP, ntiles, P; size_t lds; };
+struct FusedPlan { int NTW, KT, IT, NP, KP, ntiles, P, rows; size_t lds; };
 
 static bool fused_plan(size_t M, int K, int N, FusedPlan* f) {
   if (N % 16 || K % 8 || N < 64 || N > 320 || K > 48 || M <= 2048 || N < 2 * K) return false;
@@ -233,15 +236,19 @@ static bool fused_plan(size_t M, int K, int N, FusedPlan* f) {
   f->NP = (N + 31) / 32 * 32;
   f->KP = f->KT * 16;
   const int RP = 256 / CG;
+  // 64-row tiles unless their elementwise stage needs more than six passes per thread (above that the kernel holds
+  // more than 256 registers)
+  const int kFusedRows = (64 + RP - 1) / RP > 6 ? 32 : 64;
+  f->rows = kFusedRows;
   f->IT = (kFusedRows + RP - 1) / RP;
   f->ntiles = (int)((M + kFusedRows - 1) / kFusedRows);
   // one block per CU, two where the partials stay below ~4 % of what the layer moves
   const double layer_bytes = (double)M * (2.0 * N + 3.0 * K) * 2.0;
-  const int cap = 2.0 * kFusedBlocks * N * K * 8.0 <= 0.25 * layer_bytes ? 2 * kFusedBlocks : kFusedBlocks;
+  const int cap = (kFusedRows == 32 || 2.0 * kFusedBlocks * N * K * 8.0 <= 0.25 * layer_bytes) ? 2 * kFusedBlocks : kFusedBlocks;
   f->P = f->ntiles < cap ? f->ntiles : cap;
   f->lds = ((size_t)kFusedRows * (f->NP + 8) + (size_t)kFusedRows * (f->KP + 8) + (size_t)f->KP * (f->NP + 8)) * 2;
   if (kFusedRows * (K / 8) > 512) return false;
-  return f->NTW <= 5 && f->KT <= 3 && f->IT <= 12;
+  return f->NTW <= 5 && f->KT <= 3 && f->IT <= 6;
 }
 
 int pw_bwd_fused_ok(int dt, size_t M, int K, int N, HView a) {
@@ -255,20 +262,18 @@ size_t pw_bwd_fused_ws(size_t M, int K, int N) {
   return (size_t)f.P * N * K;
 }
 
-template <int ACT, int NTW, int KT, int IT>
+template <int ACT, int NTW, int KT, int IT, int ROWS>
 static void fused_launch(hipStream_t st, const FusedArgs& a, const FusedPlan& f) {
-  if (a.res) hipLaunchKernelGGL((pw_bwd_fused_k<ACT, NTW, KT, IT, true>), dim3(f.P), dim3(256), f.lds, st, a);
-  else hipLaunchKernelGGL((pw_bwd_fused_k<ACT, NTW, KT, IT, false>), dim3(f.P), dim3(256), f.lds, st, a);
+  if (a.res) hipLaunchKernelGGL((pw_bwd_fused_k<ACT, NTW, KT, IT, true, ROWS>), dim3(f.P), dim3(256), f.lds, st, a);
+  else hipLaunchKernelGGL((pw_bwd_fused_k<ACT, NTW, KT, IT, false, ROWS>), dim3(f.P), dim3(256), f.lds, st, a);
 }
 
 template <int ACT, int NTW, int KT>
 static void fused_launch_it(hipStream_t st, const FusedArgs& a, const FusedPlan& f) {
-  // passes of the elementwise stage: 64 rows over 256 / (N/8) rows per pass
-  if (f.IT <= 4) fused_launch<ACT, NTW, KT, 4>(st, a, f);
-  else if (f.IT <= 6) fused_launch<ACT, NTW, KT, 6>(st, a, f);
-  else if (f.IT <= 8) fused_launch<ACT, NTW, KT, 8>(st, a, f);
-  else if (f.IT <= 10) fused_launch<ACT, NTW, KT, 10>(st, a, f);
-  else fused_launch<ACT, NTW, KT, 12>(st, a, f);
+  // passes of the elementwise stage: the tile's rows over 256 / (N/8) rows per pass (at most 6, see fused_plan)
+  if (f.rows == 32) fused_launch<ACT, NTW, KT, 6, 32>(st, a, f);
+  else if (f.IT <= 4) fused_launch<ACT, NTW, KT, 4, 64>(st, a, f);
+  else fused_launch<ACT, NTW, KT, 6, 64>(st, a, f);
 }
 
 template <int ACT>
