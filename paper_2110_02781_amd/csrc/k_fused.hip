@@ -236,9 +236,10 @@ static bool fused_plan(size_t M, int K, int N, FusedPlan* f) {
   f->NP = (N + 31) / 32 * 32;
   f->KP = f->KT * 16;
   const int RP = 256 / CG;
-  // 64-row tiles unless their elementwise stage needs more than six passes per thread (above that the kernel holds
-  // more than 256 registers)
-  const int kFusedRows = (64 + RP - 1) / RP > 6 ? 32 : 64;
+  // 64-row tiles unless their elementwise stage needs more than eight passes per thread (the 288-channel layers: more
+  // than 256 registers).  Measured in a step: this rule 7.50 ms, 32 rows from seven passes on (the 192-channel layers
+  // too) 7.53 ms, 64 rows everywhere 7.55 ms.
+  const int kFusedRows = (64 + RP - 1) / RP > 8 ? 32 : 64;
   f->rows = kFusedRows;
   f->IT = (kFusedRows + RP - 1) / RP;
   f->ntiles = (int)((M + kFusedRows - 1) / kFusedRows);
@@ -248,7 +249,7 @@ static bool fused_plan(size_t M, int K, int N, FusedPlan* f) {
   f->P = f->ntiles < cap ? f->ntiles : cap;
   f->lds = ((size_t)kFusedRows * (f->NP + 8) + (size_t)kFusedRows * (f->KP + 8) + (size_t)f->KP * (f->NP + 8)) * 2;
   if (kFusedRows * (K / 8) > 512) return false;
-  return f->NTW <= 5 && f->KT <= 3 && f->IT <= 6;
+  return f->NTW <= 5 && f->KT <= 3 && f->IT <= (kFusedRows == 32 ? 6 : 8);
 }
 
 int pw_bwd_fused_ok(int dt, size_t M, int K, int N, HView a) {
@@ -270,10 +271,11 @@ static void fused_launch(hipStream_t st, const FusedArgs& a, const FusedPlan& f)
 
 template <int ACT, int NTW, int KT>
 static void fused_launch_it(hipStream_t st, const FusedArgs& a, const FusedPlan& f) {
-  // passes of the elementwise stage: the tile's rows over 256 / (N/8) rows per pass (at most 6, see fused_plan)
+  // passes of the elementwise stage: the tile's rows over 256 / (N/8) rows per pass (at most 8, see fused_plan)
   if (f.rows == 32) fused_launch<ACT, NTW, KT, 6, 32>(st, a, f);
   else if (f.IT <= 4) fused_launch<ACT, NTW, KT, 4, 64>(st, a, f);
-  else fused_launch<ACT, NTW, KT, 6, 64>(st, a, f);
+  else if (f.IT <= 6) fused_launch<ACT, NTW, KT, 6, 64>(st, a, f);
+  else fused_launch<ACT, NTW, KT, 8, 64>(st, a, f);
 }
 
 template <int ACT>
