@@ -1236,7 +1236,7 @@ __global__ __launch_bounds__(256) void dw_wgrad_k(const T* __restrict__ dz, View
 // The 4-channel groups of a layer are cut into slabs whose widths are powers of two (144 channels = 36 groups =
 // 32 + 4), so that gw groups x sw strips fill the 64 lanes of a wavefront exactly; a block's four wavefronts
 // take 4 * sw strips of one slab per pass, and the block leaves one partial ws[p][9][C] (its slab's channels).
-struct DwMarchSlab { int ch0, gw, sw; };
+struct DwMarchSlab { int ch0, gw, sw; int blk0, nblk; };   // first channel, lanes per strip, strips per wavefront; first block, blocks
 enum { kDwMarchSlabs = 16, kDwMarchBlocks = 2048, kDwMarchCpl = 2 };   // slabs a layer may need, blocks in all, channels per lane
 struct DwMarchArgs {
   const void* dz;
@@ -1245,7 +1245,8 @@ struct DwMarchArgs {
   int Hin, Win, Hout, Wout, C;
   int ncb, nseg, seglen;    // strips side by side, row segments per image (a strip is one segment high), rows per segment
   int nstrips;              // N * nseg * ncb
-  int P, nslab;             // blocks (= partials) per slab
+  int P, nslab;             // partial rows (the most blocks any slab has), slabs
+  int nblocks;              // all blocks: the slabs' block ranges one after the other
   DwMarchSlab slab[kDwMarchSlabs];
 };
 
@@ -1273,9 +1274,14 @@ __global__ __launch_bounds__(256) void dw_wgrad_march_k(DwMarchArgs a) {
   constexpr int R = S == 1 ? 2 : 1;
   constexpr int NCOL = (R - 1) * S + 3;
   __shared__ float2 red[4][9][64];
+  // Every slab has blocks in proportion to its work (a narrow tail slab takes many strips per wavefront and needs
+  // few): with the same number for all, half the resident blocks of a layer with a tail slab had nothing to do and the
+  // wide slabs' blocks took a second round.
   const int lb = xcd_logical_block();
-  const int p = lb / a.nslab, si = lb - p * a.nslab;             // the slabs of a pass run side by side on one XCD
+  int si = 0;
+  while (si + 1 < a.nslab && lb >= a.slab[si + 1].blk0) ++si;
   const DwMarchSlab sl = a.slab[si];
+  const int p = lb - sl.blk0;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int g = lane & (sl.gw - 1), s_l = lane / sl.gw;
   const int c = sl.ch0 + kDwMarchCpl * g;
@@ -1301,7 +1307,7 @@ __global__ __launch_bounds__(256) void dw_wgrad_march_k(DwMarchArgs a) {
   const unsigned in_row = __umul24(a.Win, a.C), dz_row = __umul24(a.Wout, a.C);
 
   const int spb = 4 * sl.sw;
-  for (int sidx = p * spb + wave * sl.sw + s_l; sidx < a.nstrips; sidx += a.P * spb) {
+  for (int sidx = p * spb + wave * sl.sw + s_l; sidx < a.nstrips; sidx += sl.nblk * spb) {
     const int ns = sidx / a.ncb, cb = sidx - ns * a.ncb;
     const int n = ns / a.nseg, h_beg = (ns - n * a.nseg) * a.seglen;       // a multiple of three: the phases line up
     const int wo0 = cb * R, wi0 = wo0 * S - 1;
@@ -1411,6 +1417,9 @@ __global__ __launch_bounds__(256) void dw_wgrad_march_k(DwMarchArgs a) {
         tot.x += v.x; tot.y += v.y;
       }
     *reinterpret_cast<float2*>(a.ws + ((size_t)p * 9 + t) * a.C + sl.ch0 + kDwMarchCpl * gg) = tot;
+    // the partial rows this slab has no block for (the sum runs over a.P rows for every channel)
+    for (int pz = sl.nblk + p; pz < a.P; pz += sl.nblk)
+      *reinterpret_cast<float2*>(a.ws + ((size_t)pz * 9 + t) * a.C + sl.ch0 + kDwMarchCpl * gg) = zero2;
   }
 }
 
@@ -1441,10 +1450,25 @@ static bool dw_march_plan(const ConvGeom& g, DwMarchArgs* a) {
     a->nseg = (g.Hout + len - 1) / len;
   }
   a->nstrips = g.N * a->nseg * a->ncb;
-  const int per_pass = 4 * a->slab[0].sw;                 // the widest slab takes the fewest strips per pass
-  int P = (a->nstrips + per_pass - 1) / per_pass;
-  const int cap = kDwMarchBlocks / n > 1 ? kDwMarchBlocks / n : 1;
-  a->P = P < 1 ? 1 : P > cap ? cap : P;
+  // blocks per slab: one per pass while all of them fit kDwMarchBlocks, else in proportion to the passes
+  long passes[kDwMarchSlabs], total = 0;
+  for (int i = 0; i < n; ++i) {
+    const int per_pass = 4 * a->slab[i].sw;
+    passes[i] = (a->nstrips + per_pass - 1) / per_pass;
+    total += passes[i];
+  }
+  int blk = 0, pmax = 1;
+  for (int i = 0; i < n; ++i) {
+    long b = total <= kDwMarchBlocks ? passes[i] : (passes[i] * kDwMarchBlocks + total - 1) / total;
+    if (b < 1) b = 1;
+    if (b > passes[i]) b = passes[i];
+    a->slab[i].blk0 = blk;
+    a->slab[i].nblk = (int)b;
+    blk += (int)b;
+    if ((int)b > pmax) pmax = (int)b;
+  }
+  a->nblocks = blk;
+  a->P = pmax;
   a->Hin = g.Hin; a->Win = g.Win; a->Hout = g.Hout; a->Wout = g.Wout; a->C = g.Cout;
   return g.Cout % 8 == 0 && (g.stride == 1 || g.stride == 2);
 }
@@ -1764,7 +1788,7 @@ void dw_wgrad(int dt, hipStream_t st, const void* dz, HView in, const ConvGeom& 
     {
       KScope ks(st, "dw_wgrad", ((double)g.N * g.Hin * g.Win * g.Cout + (double)g.N * g.Hout * g.Wout * g.Cout) * es + (double)m.P * 9 * g.Cout * 4,
                 18.0 * g.N * g.Hout * g.Wout * g.Cout, (long)g.N * g.Hout * g.Wout, g.Cout, g.stride);
-      const unsigned grid = (unsigned)m.P * m.nslab;
+      const unsigned grid = (unsigned)m.nblocks;
       const bool vw = in.scale != nullptr;
       if (g.stride == 1) {
         if (vw) { FTP_DISPATCH(dt, hipLaunchKernelGGL((dw_wgrad_march_k<T, 1, true>), dim3(grid), dim3(256), 0, st, m)); }
