@@ -17,10 +17,9 @@ namespace ftp {
     else { typedef bf16_t T; __VA_ARGS__; }     \
   } while (0)
 
-RowTile make_rowtile(size_t M, int C, int max_partials) {
+static RowTile rowtile_with(size_t M, int CG, int nslab, int max_partials) {
   RowTile t;
-  int CG = C / 8;
-  t.nslab = (CG + 255) / 256;
+  t.nslab = nslab;
   t.W = (CG + t.nslab - 1) / t.nslab;
   t.R = 256 / t.W;
   if (t.R < 1) t.R = 1;
@@ -32,6 +31,17 @@ RowTile make_rowtile(size_t M, int C, int max_partials) {
   t.rows_per_block = rpb;
   t.P = (int)((M + rpb - 1) / rpb);
   if (t.P < 1) t.P = 1;
+  return t;
+}
+
+RowTile make_rowtile(size_t M, int C, int max_partials) {
+  const int CG = C / 8;
+  RowTile t = rowtile_with(M, CG, (CG + 255) / 256, max_partials);
+  // Few rows and many channels (6 K x 1344): the rows alone give too few blocks for 256 CUs, so the channels are cut
+  // into slabs as well, down to 8 column groups (one 128-byte line per row and slab), until there are about 1024 blocks.
+  // Only where the ROWS are what limits the blocks (P stopped by the minimum rows per block, not by max_partials).
+  while (t.P < 256 && t.P < max_partials / 2 && (size_t)t.P * t.nslab < 1024 && (CG + t.nslab) / (t.nslab + 1) >= 8)
+    t = rowtile_with(M, CG, t.nslab + 1, max_partials);
   return t;
 }
 
