@@ -35,6 +35,15 @@ __global__ void reduce_partials_wide_k(const float* __restrict__ ws, int P, size
   double s = 0.0;
   if (j < QC) {
     int p = lane;
+    // many partials: sixteen independent loads per round (a round is one trip to memory, and this kernel is nothing but
+    // such trips); the sums keep their order
+    for (; p + 240 < P; p += 256) {
+      float v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) v[u] = ws[(size_t)(p + 16 * u) * QC + j];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) s += (double)v[u];
+    }
     for (; p + 48 < P; p += 64) {        // four independent loads per round
       float a = ws[(size_t)p * QC + j], b = ws[(size_t)(p + 16) * QC + j];
       float c2 = ws[(size_t)(p + 32) * QC + j], d = ws[(size_t)(p + 48) * QC + j];

@@ -116,22 +116,26 @@ __device__ __forceinline__ void sum_partials(const float* __restrict__ partial, 
 #pragma unroll
   for (int q = 0; q < Q; ++q) s[q] = 0.0;
   if (c < C) {
-    // four partials per round: the loads are independent, the sums keep a fixed order
-    int p = lane;
-    for (; p + 3 * kFinLanes < P; p += 4 * kFinLanes) {
-      float v[4][Q];
+    // sixteen partials per round (all of them, for up to 512 partials): the loads are independent and unconditional
+    // (past the end: the round's first partial again, not added), the sums keep their order; a round costs one trip to
+    // memory, and this kernel is nothing but such trips
+    constexpr int U = 16;
+    for (int p = lane; p < P; p += U * kFinLanes) {
+      float v[U][Q];
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < U; ++u) {
+        const int pp = p + kFinLanes * u < P ? p + kFinLanes * u : p;
 #pragma unroll
-        for (int q = 0; q < Q; ++q) v[u][q] = partial[((size_t)(p + kFinLanes * u) * Q + q) * C + c];
+        for (int q = 0; q < Q; ++q) v[u][q] = partial[((size_t)pp * Q + q) * C + c];
+      }
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < U; ++u) {
+        if (p + kFinLanes * u < P) {
 #pragma unroll
-        for (int q = 0; q < Q; ++q) s[q] += (double)v[u][q];
+          for (int q = 0; q < Q; ++q) s[q] += (double)v[u][q];
+        }
+      }
     }
-    for (; p < P; p += kFinLanes)
-#pragma unroll
-      for (int q = 0; q < Q; ++q) s[q] += (double)partial[((size_t)p * Q + q) * C + c];
   }
   int cl = threadIdx.x % kFinCh;
 #pragma unroll
@@ -139,9 +143,11 @@ __device__ __forceinline__ void sum_partials(const float* __restrict__ partial, 
   __syncthreads();
 #pragma unroll
   for (int q = 0; q < Q; ++q) {
-    double t = 0.0;
-    for (int l = 0; l < kFinLanes; ++l) t += smem[(q * kFinLanes + l) * kFinCh + cl];
-    out[q] = t;
+    // four chains of eight in a fixed order instead of one of thirty-two dependent float64 additions
+    double t[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int l = 0; l < kFinLanes; ++l) t[l & 3] += smem[(q * kFinLanes + l) * kFinCh + cl];
+    out[q] = (t[0] + t[1]) + (t[2] + t[3]);
   }
 }
 
