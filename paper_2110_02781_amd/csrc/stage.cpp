@@ -256,6 +256,20 @@ struct ftp_stage {
   // fork / join of the side stream: one pair per dz buffer, and a third for the partial sums of the one-pass expand backward
   hipEvent_t ev_fork[3] = {nullptr, nullptr, nullptr}, ev_join[3] = {nullptr, nullptr, nullptr};
   bool join_pending[3] = {false, false, false};
+  // Weight gradients of an inverted-residual unit whose tensors are small (kernels of 10 - 40 us): an event record
+  // between two kernels of a stream costs about 3 us and a wait for a recent event of the other stream about 2 (both
+  // measured), per layer as much as a finalize kernel.  Such a unit forks ONCE, behind its last layer: its layers write
+  // their dz into a set of three buffers of their own (two sets, alternating from unit to unit), the weight gradients
+  // are noted and all enqueued on the side stream at the end of the unit.
+  struct PendingWgrad { int type; const void* dz; HView in; ConvGeom g; size_t M; float* gw; };
+  PendingWgrad pend[3];
+  int n_pend = 0;
+  char* dzring[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  size_t dzring_bytes = 0;
+  hipEvent_t ev_bfork[2] = {nullptr, nullptr}, ev_bjoin[2] = {nullptr, nullptr};
+  bool bjoin_pending[2] = {false, false};
+  int bset = 0;
+  bool bset_open = false;      // a layer of the current unit has written into the set
   unsigned n_sub_bwd = 0;
   float *bn_part = nullptr, *coef = nullptr, *ws = nullptr, *row_loss = nullptr;
   // A second partial-sum workspace for the weight gradient of the stage's very first layer when the stage forks
@@ -306,6 +320,11 @@ static void stage_free(ftp_stage* s) {
     if (s->ev_fork[i]) (void)hipEventDestroy(s->ev_fork[i]);
     if (s->ev_join[i]) (void)hipEventDestroy(s->ev_join[i]);
   }
+  for (int i = 0; i < 2; ++i) {
+    if (s->ev_bfork[i]) (void)hipEventDestroy(s->ev_bfork[i]);
+    if (s->ev_bjoin[i]) (void)hipEventDestroy(s->ev_bjoin[i]);
+  }
+  for (int i = 0; i < 6; ++i) dfree(s->dzring[i]);
   dfree(s->bn_part); dfree(s->coef); dfree(s->ws); dfree(s->ws_tail); dfree(s->ws_fused); dfree(s->row_loss); dfree(s->im2col);
   if (s->timer) {
     if (s->timer->created)
@@ -426,7 +445,16 @@ extern "C" int ftp_stage_create_ex(const ftp_model* m, int a, int b, int batch, 
       e = hipEventCreateWithFlags(&s->ev_fork[i], hipEventDisableTiming);
       if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_join[i], hipEventDisableTiming);
     }
+    for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+      e = hipEventCreateWithFlags(&s->ev_bfork[i], hipEventDisableTiming);
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_bjoin[i], hipEventDisableTiming);
+    }
     if (e != hipSuccess) { ftp_set_error("stage_create: stream/event creation failed: %s", hipGetErrorString(e)); stage_free(s); return FTP_ERR_HIP; }
+  }
+  if (s->max_act_bytes >= ((size_t)32 << 20)) {        // a stage that forks (stage_forks)
+    s->dzring_bytes = max_act < ((size_t)64 << 20) ? max_act : ((size_t)64 << 20);
+    for (int i = 0; i < 6; ++i)
+      if ((rc = dev_alloc(&s->dzring[i], s->dzring_bytes))) { stage_free(s); return rc; }
   }
   if ((rc = dev_alloc(&s->bn_part, (size_t)kBnPartials * 2 * max_c * 4)) || (rc = dev_alloc(&s->coef, (size_t)3 * max_c * 4)) ||
       (rc = dev_alloc(&s->ws, ws_floats * 4)) || (rc = dev_alloc(&s->row_loss, (size_t)batch * 4))) { stage_free(s); return rc; }
@@ -850,9 +878,11 @@ static bool stage_forks(const ftp_stage* s) { return s->max_act_bytes >= ((size_
 static bool stage_overlaps(const ftp_stage* s) { return s->prof == nullptr && stage_forks(s); }
 
 static int join_side(ftp_stage* s, hipStream_t st);
+static int flush_unit_fork(ftp_stage* s, hipStream_t st);
 
 static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, const void* dA, HView in, HView out,
-                        void* dIn, const void* res, const WeightSet& W, hipStream_t st, int mode = BWD_FULL) {
+                        void* dIn, const void* res, const WeightSet& W, hipStream_t st, int mode = BWD_FULL,
+                        bool unit_fork = false) {
   const Sub& sb = p.info->subs[k];
   ConvGeom g = sb.g; g.N = s->batch;
   int C = g.Cout;
@@ -864,6 +894,9 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
   const bool overlap = mode == BWD_FULL && stage_overlaps(s) && M * (size_t)C >= ((size_t)1 << 20);
   int b = 0, rc_join = 0;
   void* dz = const_cast<void*>(dA);
+  // one fork for the whole unit (see PendingWgrad): this layer's dz goes into the unit's buffer set
+  const bool batched = unit_fork && overlap && k < 3 && sb.type != SUB_DIRECT && dIn != nullptr && s->dzring[0] != nullptr &&
+                       M * (size_t)C * s->es <= s->dzring_bytes;
   // An expand layer in bfloat16: behind the BatchNorm reductions the rest of its backward (dz, data gradient,
   // weight gradient) is one pass on this stream; dz never reaches memory.
   if (mode == BWD_FULL && sb.type == SUB_PW && dIn && s->ws_fused && !bn_bwd_small_ok(M, C) &&
@@ -890,8 +923,11 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
     return FTP_OK;
   }
   if (mode != BWD_FROM_DZ) {
-    b = (int)(s->n_sub_bwd++ & 1u);
-    dz = s->gbuf[b ? 4 : 2];
+    if (batched) dz = s->dzring[s->bset * 3 + (int)k];
+    else {
+      b = (int)(s->n_sub_bwd++ & 1u);
+      dz = s->gbuf[b ? 4 : 2];
+    }
     const bool small = bn_bwd_small_ok(M, C) != 0;
     if (!small) {
       int P = 0;
@@ -900,7 +936,15 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
       bn_bwd_finalize(st, s->bn_part, P, M, C, W.w32 + p.p_off + sb.gamma_off, stt, stt + C, s->grads + p.p_off + sb.gamma_off,
                       s->grads + p.p_off + sb.beta_off, s->coef);
     }
-    if (s->join_pending[b]) {             // the weight gradient that last read this dz buffer must be done
+    if (batched) {
+      if (!s->bset_open) {                // the unit's first write into this set: the weight gradients that last read it must be done
+        if (s->bjoin_pending[s->bset]) {
+          HIP_TRY(hipStreamWaitEvent(st, s->ev_bjoin[s->bset], 0));
+          s->bjoin_pending[s->bset] = false;
+        }
+        s->bset_open = true;
+      }
+    } else if (s->join_pending[b]) {      // the weight gradient that last read this dz buffer must be done
       HIP_TRY(hipStreamWaitEvent(st, s->ev_join[b], 0));
       s->join_pending[b] = false;
     }
@@ -929,6 +973,14 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
     }
   };
   if (dgrad_first) run_dw_dgrad();
+  if (batched && mode == BWD_FULL) {
+    // noted for the unit's fork; the data gradient goes on as it would behind a forked weight gradient
+    if (s->n_pend >= 3) { ftp_set_error("stage_backward: more weight gradients noted for a unit than it has layers"); return FTP_ERR_UNSUPPORTED; }
+    s->pend[s->n_pend++] = ftp_stage::PendingWgrad{sb.type, dz, in, g, M, s->grads + p.p_off + sb.w_off};
+    if (sb.type == SUB_PW) pw_dgrad(s->dt, st, dz, conv_w(s, W, p.p_off + sb.w_off), res, M, g.Cin, g.Cout, dIn);
+    else if (!dgrad_first) run_dw_dgrad();
+    return FTP_OK;
+  }
   // the first layer of the stage, last in this pass and without a data gradient: its weight gradient is all that is
   // left for this stream, so it runs here with a workspace of its own while the side stream works off its queue
   const bool tail_here = overlap && dIn == nullptr && s->ws_tail != nullptr && &p == &s->plan[0] && k == 0;
@@ -973,12 +1025,36 @@ static int sub_backward(ftp_stage* s, Slot& sl, const UnitPlan& p, size_t k, con
   return FTP_OK;
 }
 
+// the weight gradients a unit has noted: one fork behind everything the unit has enqueued, all of them on the side
+// stream, one join event for the unit's buffer set
+static int flush_unit_fork(ftp_stage* s, hipStream_t st) {
+  if (s->n_pend == 0) { s->bset_open = false; return FTP_OK; }
+  HIP_TRY(hipEventRecord(s->ev_bfork[s->bset], st));
+  HIP_TRY(hipStreamWaitEvent(s->side, s->ev_bfork[s->bset], 0));
+  for (int i = 0; i < s->n_pend; ++i) {
+    const ftp_stage::PendingWgrad& w = s->pend[i];
+    if (w.type == SUB_PW) pw_wgrad(s->dt, s->side, w.dz, w.in, w.M, w.g.Cin, w.g.Cout, s->ws, w.gw);
+    else dw_wgrad(s->dt, s->side, w.dz, w.in, w.g, s->ws, w.gw);
+  }
+  HIP_TRY(hipEventRecord(s->ev_bjoin[s->bset], s->side));
+  s->bjoin_pending[s->bset] = true;
+  s->n_pend = 0;
+  s->bset ^= 1;
+  s->bset_open = false;
+  return FTP_OK;
+}
+
 // all side-stream work of this backward is ordered before whatever the caller enqueues next
 static int join_side(ftp_stage* s, hipStream_t st) {
   for (int b = 0; b < 3; ++b)
     if (s->join_pending[b]) {
       HIP_TRY(hipStreamWaitEvent(st, s->ev_join[b], 0));
       s->join_pending[b] = false;
+    }
+  for (int b = 0; b < 2; ++b)
+    if (s->bjoin_pending[b]) {
+      HIP_TRY(hipStreamWaitEvent(st, s->ev_bjoin[b], 0));
+      s->bjoin_pending[b] = false;
     }
   return FTP_OK;
 }
@@ -1009,6 +1085,7 @@ extern "C" int ftp_stage_backward(ftp_stage* s, int slot, const void* dy_dev, vo
     if (rc) return rc;
     s->stash_owner = slot;
   }
+  s->n_pend = 0; s->bset_open = false;              // nothing is left noted by a call that ended in an error
   const void* d = dy_dev ? dy_dev : sl.dlogits;     // gradient of the current unit's output (read only)
   int flip = 0;
   for (int i = (int)s->plan.size() - 1; i >= 0; --i) {
@@ -1041,7 +1118,11 @@ extern "C" int ftp_stage_backward(ftp_stage* s, int slot, const void* dy_dev, vo
         size_t ns = u.subs.size();
         void* tmp = s->gbuf[3];
         // project: gradient of the activated depthwise output
-        if ((rc = sub_backward(s, sl, p, ns - 1, d, v.sub_out[i][ns - 2], v.sub_out[i][ns - 1], tmp, nullptr, W, st))) return rc;
+        // one fork for the unit when every layer's dz fits the small buffer sets
+        bool uf = ns == 3 && s->dzring[0] != nullptr;
+        for (const Sub& sb : u.subs)
+          if ((size_t)s->batch * sb.g.Hout * sb.g.Wout * sb.g.Cout * s->es > s->dzring_bytes) uf = false;
+        if ((rc = sub_backward(s, sl, p, ns - 1, d, v.sub_out[i][ns - 2], v.sub_out[i][ns - 1], tmp, nullptr, W, st, BWD_FULL, uf))) return rc;
         ConvGeom gd = ns == 3 ? u.subs[1].g : ConvGeom{};
         gd.N = s->batch;
         if (ns == 3 && !stage_forks(s) && dw_bwd_small_ok(gd)) {
@@ -1059,8 +1140,9 @@ extern "C" int ftp_stage_backward(ftp_stage* s, int slot, const void* dy_dev, vo
                        s->grads + p.p_off + s0.beta_off, dz1);
           if ((rc = sub_backward(s, sl, p, 0, dz1, in, v.sub_out[i][0], next, u.residual ? d : nullptr, W, st, BWD_FROM_DZ))) return rc;
         } else if (ns == 3) {
-          if ((rc = sub_backward(s, sl, p, 1, tmp, v.sub_out[i][0], v.sub_out[i][1], tmp, nullptr, W, st))) return rc;
-          if ((rc = sub_backward(s, sl, p, 0, tmp, in, v.sub_out[i][0], next, u.residual ? d : nullptr, W, st))) return rc;
+          if ((rc = sub_backward(s, sl, p, 1, tmp, v.sub_out[i][0], v.sub_out[i][1], tmp, nullptr, W, st, BWD_FULL, uf))) return rc;
+          if ((rc = sub_backward(s, sl, p, 0, tmp, in, v.sub_out[i][0], next, u.residual ? d : nullptr, W, st, BWD_FULL, uf))) return rc;
+          if ((rc = flush_unit_fork(s, st))) return rc;
         } else {
           if (next && u.residual) {
             if ((rc = sub_backward(s, sl, p, 0, tmp, in, v.sub_out[i][0], tmp, nullptr, W, st))) return rc;
